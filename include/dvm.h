@@ -1,0 +1,203 @@
+/*
+ * dvm.h -- C ABI of libdvm: a bytecode virtual machine for fused dynamic-shape tensor programs
+ *          on AMD MI355X (gfx950).
+ *
+ * The split follows the paper's operator compiler (Section 3 "Operator Compiler", Section 4):
+ * an operator program is *encoded* into tile-level bytecode on the host CPU in microseconds --
+ * no machine code is generated, nothing is cached -- and the bytecode is *decoded and executed*
+ * on the device by a pre-compiled interpreter kernel (Section 4.3, Algorithm 2).
+ *
+ *   dvm_prog_*   build a shape-free operator program (a DAG of basic and compound ops; compound
+ *                ops are decomposed into basic ops, Section 3).
+ *   dvm_encode   program + concrete input shapes -> bytecode: broadcast/shape inference and
+ *                dominant shape (Section 4.2), pattern fusion of the op chain into one
+ *                meta-kernel (Section 5.1), liveness and tile-register allocation (Algorithm 1's
+ *                n_max / T_max), tile plan with the cost model ceil(#tiles/N)*(tile+c)
+ *                (Section 4.2), and the header + body byte layout (Section 4.2 "Bytecode encoding").
+ *   dvm_stack    temporal stacking-based fusion: several meta-kernels in one launch (Section 5.1).
+ *   dvm_run      launch the interpreter on a HIP stream (Section 4.3).
+ *
+ * Conventions
+ *   - All pointers are HOST pointers except the entries of `tensors[]` in dvm_run, which are
+ *     DEVICE pointers.  `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *   - The caller owns every buffer.  The library allocates no device memory and keeps no
+ *     reference to any argument after a call returns.  dvm_encode / dvm_stack / dvm_validate /
+ *     dvm_disasm / dvm_plan make no HIP call and no heap allocation.
+ *   - Bytecode is position independent and holds tensor *indices*, never addresses: it can be
+ *     reused with other tensors of the same shapes, stored, or compared byte for byte.  Encoding
+ *     the same program with the same shapes always yields identical bytes.
+ *   - Every function returns 0 (DVM_OK) or a negative dvm_status; nothing aborts or throws.
+ *   - dvm_encode and dvm_run are re-entrant for distinct output buffers.
+ */
+#ifndef DVM_H
+#define DVM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DVM_MAX_RANK     6     /* rank of a tensor as given by the caller                         */
+#define DVM_MAX_TENSORS  32    /* inputs + outputs of one launch (all stacked segments together)  */
+#define DVM_MAX_OPS      96    /* ops (after decomposition) of one program                        */
+#define DVM_CODE_MAX_BYTES 3584 /* one launch's bytecode travels in the kernel-argument segment   */
+
+typedef enum dvm_status {
+    DVM_OK            =  0,
+    DVM_E_ARGS        = -1,   /* null pointer, bad index, bad count                               */
+    DVM_E_SHAPE       = -2,   /* shapes do not broadcast together                                 */
+    DVM_E_RANK        = -3,   /* rank above DVM_MAX_RANK, or iteration space not reducible to 4-D */
+    DVM_E_DTYPE       = -4,   /* unknown storage dtype                                            */
+    DVM_E_UNSUPPORTED = -5,   /* valid program the VM cannot run (see message of dvm_strerror)    */
+    DVM_E_BUFSZ       = -6,   /* output buffer too small; the needed size is written to *len      */
+    DVM_E_BADCODE     = -7,   /* bytecode fails structural validation                             */
+    DVM_E_HIP         = -8,   /* a HIP call failed; see dvm_last_hip_error                        */
+    DVM_E_ALIGN       = -9,   /* a device pointer is less aligned than the bytecode assumes       */
+    DVM_E_LIMIT       = -10,  /* too many ops / tensors / bytes for one launch                    */
+    DVM_E_STATE       = -11   /* program not finished, or already finished                        */
+} dvm_status;
+
+typedef enum dvm_dtype { DVM_F32 = 0, DVM_BF16 = 1 } dvm_dtype;
+
+/* Operator vocabulary of the program builder.  Names follow Table 1 of the paper; reductions act
+ * on the last axis and keep it with extent 1 (Table 1's Sum/Max/Min with N = 1). */
+typedef enum dvm_opcode {
+    /* unary */
+    DVM_OP_COPY = 1, DVM_OP_SQRT, DVM_OP_ABS, DVM_OP_LOG, DVM_OP_EXP, DVM_OP_ROUND, DVM_OP_FLOOR,
+    DVM_OP_ISFINITE, DVM_OP_NEG, DVM_OP_RSQRT, DVM_OP_RCP, DVM_OP_TANH, DVM_OP_ERF, DVM_OP_SIGMOID,
+    DVM_OP_SQUARE, DVM_OP_GELU_TANH, DVM_OP_GELU_ERF, DVM_OP_SILU,
+    DVM_OP_CAST,            /* imm[0] = target dvm_dtype: round to that dtype, keep computing in fp32 */
+    /* tile (op) scalar immediate: imm[0] */
+    DVM_OP_ADDS = 32, DVM_OP_MULS,
+    /* binary, NumPy broadcasting */
+    DVM_OP_ADD = 40, DVM_OP_SUB, DVM_OP_MUL, DVM_OP_DIV, DVM_OP_MIN, DVM_OP_MAX, DVM_OP_POW,
+    DVM_OP_CMP_EQ, DVM_OP_CMP_NE, DVM_OP_CMP_LT, DVM_OP_CMP_LE, DVM_OP_CMP_GT, DVM_OP_CMP_GE,
+    /* ternary: args = (cond, a, b) -> cond != 0 ? a : b */
+    DVM_OP_SELECT = 60,
+    /* reductions over the last axis (kept, extent 1) */
+    DVM_OP_SUM = 64, DVM_OP_RMAX, DVM_OP_RMIN, DVM_OP_MEAN, DVM_OP_MEANSQ,
+    /* compound ops, decomposed by dvm_prog_finish */
+    DVM_OP_SOFTMAX = 80,    /* args = (z)                                    */
+    DVM_OP_RMSNORM,         /* args = (x, w),           imm[0] = eps         */
+    DVM_OP_LAYERNORM        /* args = (x, gamma, beta), imm[0] = eps         */
+} dvm_opcode;
+
+/* Shape of one tensor as the caller holds it: dims and strides in ELEMENTS, outermost first.
+ * A dimension of extent 1, or of stride 0, broadcasts.  `align_bytes` is the guaranteed alignment
+ * of the device pointer that will be passed for this tensor (0 means 16). */
+typedef struct dvm_shape {
+    int32_t rank;
+    int32_t align_bytes;
+    int64_t dim[DVM_MAX_RANK];
+    int64_t stride[DVM_MAX_RANK];
+} dvm_shape;
+
+/* Fill `s` with a contiguous row-major shape. */
+int dvm_shape_contiguous(dvm_shape *s, int rank, const int64_t *dims);
+
+/* ---- context: a snapshot of device properties used by the tile planner; owns no device memory --- */
+typedef struct dvm_ctx dvm_ctx;
+
+/* hip_device >= 0: query that device (HIP calls).  hip_device == -1: no device is touched and the
+ * MI355X defaults are used (256 compute units), so that encoding works on a machine without GPU. */
+int  dvm_ctx_create(int hip_device, dvm_ctx **out);
+void dvm_ctx_destroy(dvm_ctx *ctx);
+/* Override planner inputs (tests, tuning): number of compute units and the per-tile overhead term
+ * of the cost model, in elements.  Values <= 0 leave the setting unchanged. */
+int  dvm_ctx_set_planner(dvm_ctx *ctx, int n_compute_units, int tile_overhead_elems);
+
+/* ---- program builder (shape free) --------------------------------------------------------------- */
+typedef struct dvm_prog dvm_prog;
+
+int  dvm_prog_create(dvm_prog **out);
+/* Declare the next input; *value_id receives its SSA id.  Inputs are numbered in declaration order
+ * and that is their order in `in_shapes[]` and at the front of `tensors[]`. */
+int  dvm_prog_input(dvm_prog *p, int dtype, int *value_id);
+/* Append an op.  `arg_ids` are SSA ids of earlier values, `imm` the immediates the opcode takes. */
+int  dvm_prog_op(dvm_prog *p, int opcode, const int *arg_ids, int n_args,
+                 const double *imm, int n_imm, int *value_id);
+/* Mark a value as the next output with storage dtype `dtype`.  Outputs follow the inputs in
+ * `tensors[]`, in the order of these calls. */
+int  dvm_prog_output(dvm_prog *p, int value_id, int dtype);
+/* Decompose compound ops into basic ops and freeze the program. */
+int  dvm_prog_finish(dvm_prog *p);
+int  dvm_prog_num_inputs(const dvm_prog *p);
+int  dvm_prog_num_outputs(const dvm_prog *p);
+void dvm_prog_destroy(dvm_prog *p);
+
+/* ---- host encoder ------------------------------------------------------------------------------- */
+/*
+ * Encode `prog` for the given input shapes.
+ *   in_shapes[n_in]   one per program input, in declaration order.
+ *   out_layout        NULL: outputs are contiguous row-major.  Otherwise out_layout[i].stride (and
+ *                     align_bytes) give the strides of output i (a view store); its rank and dims
+ *                     must equal the inferred ones.
+ *   bytecode, cap     caller buffer.  On DVM_E_BUFSZ *len holds the size needed.
+ *   out_shapes        optional (may be NULL): receives the inferred shape of every output.
+ * Runs entirely on the host: no HIP call, no heap allocation, no cache lookup.
+ */
+int  dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog,
+                const dvm_shape *in_shapes, int n_in, const dvm_shape *out_layout,
+                void *bytecode, size_t cap, size_t *len, dvm_shape *out_shapes);
+
+/* Temporal stacking (Section 5.1): concatenate n encoded programs into one launch.  The stacked
+ * program's tensor list is the concatenation of the parts' tensor lists, in order.  The parts
+ * must be independent of each other (no part reads what another writes). */
+int  dvm_stack(const void *const *codes, const size_t *lens, int n,
+               void *out, size_t cap, size_t *len);
+
+/* Structural check of a bytecode blob: header fields, segment and instruction lengths, register
+ * and tensor indices, launch geometry.  dvm_run calls it on every launch. */
+int  dvm_validate(const void *bytecode, size_t len);
+
+/* Readable dump (Section 4.2, the printed example program: tile number, tiles per core, kernel
+ * type, one line per instruction).  Always NUL-terminates within `cap`. */
+int  dvm_disasm(const void *bytecode, size_t len, char *txt, size_t cap);
+
+/* Introspection of an encoded program. */
+typedef struct dvm_code_info {
+    int32_t  kernel_type;      /* 0 = meta-kernel on the vector path, 1 = temporally stacked      */
+    int32_t  n_segments;
+    int32_t  n_tensors;
+    int32_t  grid;             /* workgroups launched (the N of Algorithm 2)                      */
+    int32_t  block;            /* threads per workgroup                                           */
+    int32_t  variant_k;        /* elements per lane per tile register of the interpreter variant  */
+    int32_t  variant_nr;       /* tile registers of the interpreter variant                       */
+    int32_t  n_instructions;   /* over all segments                                               */
+    int64_t  n_tiles;          /* over all segments (the M of Algorithm 2, summed)                */
+    int64_t  code_bytes;       /* over all segments (CodeSize, summed)                            */
+} dvm_code_info;
+int  dvm_code_info_get(const void *bytecode, size_t len, dvm_code_info *info);
+/* Minimum size in bytes of the buffer behind tensors[index], and whether it is written. */
+int  dvm_code_tensor(const void *bytecode, size_t len, int index,
+                     int64_t *min_bytes, int *is_output, int *dtype, int *align_bytes);
+
+/* The tile-size rule on a one-dimensional space (Section 4.2, hardware_align_div): among tile
+ * sizes 1..t_max the one minimising ceil(ceil(total/t)/n_cores) * (t + overhead), ties to the
+ * larger tile, then rounded up to a multiple of `align` without exceeding t_max.
+ * Writes the minimum-cost size, the aligned size and the resulting number of tiles. */
+int  dvm_plan(int64_t total, int n_cores, int64_t t_max, int align, int overhead,
+              int64_t *t_min_cost, int64_t *t_aligned, int64_t *n_tiles);
+
+/* ---- device execution ---------------------------------------------------------------------------- */
+/*
+ * Launch the interpreter for `bytecode` on `hip_stream` and return without waiting.
+ *   tensors[n_tensors]  DEVICE pointers: the program's inputs in declaration order, then its
+ *                       outputs (for a stacked program: part after part).
+ * The bytecode is copied into the launch's kernel arguments before the call returns; the caller
+ * may reuse its buffer at once.  ctx must have been created for a real device.
+ */
+int  dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len,
+             void *const *tensors, int n_tensors, void *hip_stream);
+
+const char *dvm_strerror(int status);
+/* Detail text of the last error raised on the calling thread ("" if none). */
+const char *dvm_last_error_detail(void);
+int  dvm_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DVM_H */

@@ -1,0 +1,145 @@
+// Bytecode layout shared by the host encoder and the device interpreter.
+//
+// A program is a header followed by one code body per meta-kernel (Section 4.2, "Bytecode
+// encoding": the header carries the kernel type, the code size and the total number of tiles;
+// the body holds one record per operation with its instruction id, its length, the destination
+// and source tile registers, and extras).  The paper's format figure is not reproduced in its
+// text, so the field widths below are this implementation's own: little-endian 32-bit words,
+// every record a whole number of words, unused bits zero (which makes equal inputs give equal
+// bytes).
+//
+//   program  := PH_WORDS header words | n_tensors * TT_WORDS tensor-table words | segment*
+//   segment  := SH_WORDS header words | body (S_CODESIZE words of instruction records)
+//   record   := word0 = op | len<<8 | a<<16 | b<<24, then len-1 operand words
+//
+// The tile registers are the interpreter's local memory: an accumulator ACC and NR tile
+// registers R0.. of K fp32 elements per lane each, and NS row-scalar registers S0.. (one value
+// per row, replicated on the lanes that hold the row).
+#ifndef DVM_BYTECODE_H
+#define DVM_BYTECODE_H
+
+#include <stdint.h>
+
+namespace dvmbc {
+
+constexpr uint32_t MAGIC   = 0x314D5644u;   // "DVM1"
+constexpr uint32_t VERSION = 1;
+
+// kernel types (Section 4.2: a meta-kernel on the vector path, or a stacking-based kernel)
+constexpr uint32_t KT_META  = 0;            // printed as "vmain.v"
+constexpr uint32_t KT_STACK = 1;            // temporally stacked meta-kernels, "vstack.t"
+
+// ---- program header -------------------------------------------------------------------------
+enum : int {
+    PH_MAGIC = 0,
+    PH_TYPE,        // kernel type | VERSION << 16
+    PH_WORDS,       // length of the whole program in words
+    PH_NSEG,        // number of segments (meta-kernels)
+    PH_BLOCK,       // threads per workgroup of the launch
+    PH_GRID,        // workgroups of the launch: the N of Algorithm 2
+    PH_VARIANT,     // interpreter variant: K | NR << 8
+    PH_NTENS,       // tensors of the launch
+    PH_WORDS_COUNT
+};
+constexpr int PH_WORDS_N = PH_WORDS_COUNT;
+
+// tensor table entry
+enum : int {
+    TT_INFO = 0,    // dtype | is_output << 8 | log2(assumed pointer alignment in bytes) << 16
+    TT_BYTES_LO,    // minimum size of the buffer in bytes
+    TT_BYTES_HI,
+    TT_WORDS
+};
+
+// ---- segment header -------------------------------------------------------------------------
+enum : int {
+    S_WORDS = 0,    // header + body, in words
+    S_CODESIZE,     // body size in words (the paper's CodeSize)
+    S_NTILES,       // total number of tiles M of this meta-kernel
+    S_GEOM,         // G (lanes per row, u16) | V (elements per chunk, u8) << 16 | nvec << 24
+    S_RP,           // rows per tile (u16) | active threads (u16) << 16
+    S_NCT,          // column tiles per row
+    S_TC,           // tile width in elements
+    S_D0LO, S_D0HI, // row length in elements
+    S_NROWS,        // number of rows (product of the outer iteration dims)
+    S_D1, S_M1, S_SH1,   // outer dim 1 and the multiply-shift constants that divide by it
+    S_D2, S_M2, S_SH2,   // outer dim 2
+    S_NCTM, S_NCTSH,     // multiply-shift constants that divide by S_NCT
+    S_TBASE,        // index of this segment's first tensor in the launch's tensor list
+    S_NTENS,        // tensors of this segment
+    S_FLAGS,        // SF_*
+    S_IMASK,        // bit op -> the instruction id occurs in the body (for the disassembler)
+    SH_WORDS
+};
+constexpr uint32_t SF_WGSYNC  = 1u;     // rows span several waves: reductions use the barrier
+constexpr uint32_t SF_RAGGED  = 2u;     // some tile has invalid rows or columns: mask reductions
+
+// ---- instruction ids --------------------------------------------------------------------------
+enum : uint32_t {
+    I_NOP = 0,
+    I_LOAD,      // contiguous rows, one row stride     a = dst, b = combine op (B_NONE: plain move)
+    I_VLOAD,     // view load: three outer strides      (Table 1: ViewLoad)
+    I_LOADS,     // one value per row -> S[a]
+    I_STORE,     // a = src register                    (Table 1: Store)
+    I_VSTORE,    //                                     (Table 1: ViewStore)
+    I_STORES,    // S[a] -> one value per row
+    I_MOVRA,     // R[a] = ACC                          (Table 1: Copy)
+    I_MOVAR,     // ACC = R[a]
+    I_UN,        // ACC = U_b(ACC)
+    I_BIN,       // ACC = B_b(ACC, src a)               src: R, S (Table 1: Broadcast of a row value), ACC, IMM
+    I_SEL,       // ACC = ACC != 0 ? R[a] : R[b]        (Table 1: Select)
+    I_RED,       // S[a] = R_b over the row of ACC, part inside a wave
+    I_SYNC,      // workgroup barrier (inserted by the encoder between I_RED and I_REDX)
+    I_REDX,      // S[a] = R_b over the per-wave partials
+    I_SOP,       // S[a] = op(S[b], S[c] | imm)
+    I_COUNT
+};
+
+// memory record: word1 = tensor | dtype << 8 | flags << 16 ; then strides as int64 (lo, hi)
+constexpr int LEN_LOAD  = 4;            // word0, word1, s1
+constexpr int LEN_VLOAD = 8;            // word0, word1, s1, s2, s3
+constexpr uint32_t MF_ALIGNED16 = 1u;   // every chunk of this tensor starts on a 16-byte boundary
+
+// source / destination selectors
+constexpr uint32_t SRC_R0  = 0;         // 0 .. NR-1
+constexpr uint32_t SRC_S0  = 16;        // 16 .. 16+NS-1
+constexpr uint32_t SRC_ACC = 32;
+constexpr uint32_t SRC_IMM = 33;
+constexpr int NS = 4;                   // row-scalar registers
+
+// binary ops B_*
+enum : uint32_t {
+    B_NONE = 0, B_ADD, B_SUB, B_RSUB, B_MUL, B_DIV, B_RDIV, B_MIN, B_MAX, B_POW, B_RPOW,
+    B_EQ, B_NE, B_LT, B_LE, B_GT, B_GE, B_COUNT
+};
+// unary ops U_*
+enum : uint32_t {
+    U_NONE = 0, U_SQRT, U_ABS, U_LOG, U_EXP, U_ROUND, U_FLOOR, U_ISFINITE, U_NEG, U_RSQRT, U_RCP,
+    U_TANH, U_ERF, U_SIGMOID, U_SQUARE, U_GELU_TANH, U_GELU_ERF, U_SILU, U_CAST_BF16, U_COUNT
+};
+// reductions R_*
+enum : uint32_t { R_SUM = 0, R_MAX, R_MIN, R_SUMSQ, R_COUNT };
+
+// I_SOP: word1 = kind | srckind << 8 | c << 16 ; word2 = immediate.  kind < 64: B_kind(S[b], x);
+// kind >= 64: U_(kind-64)(S[b]).  srckind 0: x = S[c]; 1: x = immediate.
+constexpr int LEN_SOP = 3;
+constexpr uint32_t SOP_UNARY = 64;
+
+inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
+    return op | (len << 8) | (a << 16) | (b << 24);
+}
+
+// interpreter variants compiled into the library: elements per lane per tile register (K),
+// number of tile registers (NR), largest workgroup, and resident waves per SIMD (from the
+// compiled kernels' register use; 4 SIMDs per compute unit).
+struct Variant { int K, NR, max_threads, waves_per_simd; };
+constexpr Variant VARIANTS[] = {
+    { 4, 2, 1024, 8}, { 4, 6, 1024, 5},
+    { 8, 2, 1024, 5}, { 8, 6,  512, 3},
+    {16, 2,  512, 3}, {16, 6,  256, 1},
+    {32, 2,  256, 1},
+};
+constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
+
+}  // namespace dvmbc
+#endif

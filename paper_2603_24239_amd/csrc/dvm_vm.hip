@@ -1,0 +1,823 @@
+// The device side of libdvm: the bytecode interpreter kernel for gfx950 and dvm_run.
+//
+// One workgroup plays the role of one "AI Core" of Algorithm 2 (Section 4.3): it takes a
+// contiguous range of tiles, and for every tile walks the code body from its first record to
+// CodeSize, dispatching each record on its instruction id.  Decoding is wave-uniform: the
+// bytecode sits in the kernel-argument segment and is read with scalar loads into SGPRs, the
+// dispatch is a scalar branch tree, so no vector lane ever spends an issue slot on decoding
+// (the GPU analogue of decoding on the NPU's Scalar unit, Section 4.3).
+//
+// Local memory of the paper's AI Core = the vector register file here.  A tile register is K
+// fp32 values per lane; the accumulator ACC and the registers R0..R(NR-1) hold fused
+// intermediates, which therefore never touch HBM (Section 5.1, vector-vector fusion).  Every
+// register reference in a handler is a compile-time constant: handlers are selected by scalar
+// switches on the register ids, because a GPU cannot index vector registers dynamically.
+//
+// Layout of a tile: RP rows x up to G*nvec*V columns.  Row r of the tile is held by the G
+// lanes [r*G, (r+1)*G); lane l of the group owns the chunks of V consecutive elements number
+// l, l+G, l+2G, ... so that each load instruction of a wave covers whole contiguous runs of
+// 16 bytes per lane.  Loads/stores do all address arithmetic (strides, broadcast, views), so
+// compute instructions see one canonical layout (Section 4.1, last paragraph).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+#include <utility>
+
+#include "../../include/dvm.h"
+#include "dvm_bytecode.h"
+#include "dvm_internal.h"
+
+using namespace dvmbc;
+
+namespace {
+
+constexpr int CODE_WORDS = DVM_CODE_MAX_BYTES / 4;
+
+struct KArgs {
+    uint32_t code[CODE_WORDS];          // the segments of the program (headers + bodies)
+    uint64_t tensors[DVM_MAX_TENSORS];  // device addresses
+    uint32_t nseg;
+    uint32_t pad;
+};
+
+#define DI __device__ __forceinline__
+#define LI __attribute__((always_inline))
+
+// Compile-time loop: f.operator()<I>() for I = 0..N-1.  Every register-array index in this file
+// is a template constant, so that the arrays are split into scalar registers before any other
+// optimisation can merge the handlers of different registers into one body with a run-time index.
+template <class F, int... I> DI void sfor_impl(F &f, std::integer_sequence<int, I...>) {
+    (f.template operator()<I>(), ...);
+}
+template <int N, class F> DI void sfor(F &&f) { sfor_impl(f, std::make_integer_sequence<int, N>{}); }
+
+// ------------------------------------------------------------------------------------------
+// scalar math on fp32 lanes
+// ------------------------------------------------------------------------------------------
+DI float f_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+DI float f_log2(float x) { return __builtin_amdgcn_logf(x); }
+DI float f_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+DI float f_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
+DI float f_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
+DI float f_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+
+constexpr float LOG2E    = 1.44269504088896340736f;
+constexpr float LOG2E_LO = 1.92596303e-8f;      // log2(e) - (float)log2(e)
+constexpr float LN2      = 0.69314718055994530942f;
+
+// exp(x) = 2^(x*log2e); the rounding error of the product is carried as a first-order correction
+// so that the relative error stays near 1 ulp for |x| up to the overflow threshold.
+DI float f_exp(float x) {
+    float t = x * LOG2E;
+    float e = f_fma(x, LOG2E, -t);
+    e = f_fma(x, LOG2E_LO, e);
+    e = (__builtin_fabsf(x) < __builtin_inff()) ? e : 0.0f;
+    float r = f_exp2(t);
+    return f_fma(r, e * LN2, r);
+}
+DI float f_sigmoid(float x) { return f_rcp(1.0f + f_exp2(-LOG2E * x)); }
+DI float f_silu(float x) { return x * f_sigmoid(x); }
+// 0.5 u (1 + tanh(c (u + 0.044715 u^3)))  ==  u * sigmoid(2 c (u + 0.044715 u^3))
+DI float f_gelu_tanh(float u) {
+    constexpr float C0 = -2.0f * LOG2E * 0.7978845608028654f;
+    constexpr float C1 = -2.0f * LOG2E * 0.7978845608028654f * 0.044715f;
+    float p = u * f_fma(u * u, C1, C0);
+    return u * f_rcp(1.0f + f_exp2(p));
+}
+DI float f_tanh(float x) {
+    float a = __builtin_fabsf(x);
+    float t = f_exp2(-2.0f * LOG2E * a);
+    float big = (1.0f - t) * f_rcp(1.0f + t);
+    float s = a * a;                               // odd Taylor series below 0.04
+    float small = a * f_fma(s, f_fma(s, 0.13333333f, -0.33333333f), 1.0f);
+    float r = a < 0.04f ? small : big;
+    return __builtin_copysignf(r, x);
+}
+// erf: odd polynomial in x on |x| <= 1, 1 - exp(q(|x| - 2.5)) on 1 < |x| <= 4, 1 beyond.
+// Coefficients: least-squares Chebyshev fits of erf(x)/x in x^2 on [0,1] (degree 6) and of
+// log(erfc(a)) in a-2.5 on [1,4] (degree 8), converted to the monomial basis.
+DI float f_erf(float x) {
+    float a = __builtin_fabsf(x);
+    float s = a * a;
+    float p = 7.882497448008507e-05f;
+    p = f_fma(p, s, -0.0008018855005502701f);
+    p = f_fma(p, s, 0.005189312156289816f);
+    p = f_fma(p, s, -0.02685432881116867f);
+    p = f_fma(p, s, 0.11283597350120544f);
+    p = f_fma(p, s, -0.3761262595653534f);
+    p = f_fma(p, s, 1.1283791065216064f);
+    float lo = a * p;
+    float u = __builtin_fminf(a, 4.0f) - 2.5f;
+    float q = 1.6140616025950294e-06f;
+    q = f_fma(q, u, -1.3309389942151029e-05f);
+    q = f_fma(q, u, 7.739442662568763e-05f);
+    q = f_fma(q, u, -0.0004201445553917438f);
+    q = f_fma(q, u, 0.0021651603747159243f);
+    q = f_fma(q, u, -0.01085851714015007f);
+    q = f_fma(q, u, -0.9438936114311218f);
+    q = f_fma(q, u, -5.352680683135986f);
+    q = f_fma(q, u, -7.806815147399902f);
+    float hi = 1.0f - f_exp2(q * LOG2E);
+    float r = a <= 1.0f ? lo : hi;
+    r = (a != a) ? a : r;
+    return __builtin_copysignf(r, x);
+}
+DI float f_gelu_erf(float u) { return 0.5f * u * (1.0f + f_erf(u * 0.70710678118654752f)); }
+DI float f_pow(float a, float b) { return f_exp2(b * f_log2(a)); }
+DI float f_bf16_round(float x) {
+    __bf16 h = (__bf16)x;
+    return (float)h;
+}
+
+template <uint32_t U> DI float un_op(float x) {
+    if constexpr (U == U_SQRT) return f_sqrt(x);
+    else if constexpr (U == U_ABS) return __builtin_fabsf(x);
+    else if constexpr (U == U_LOG) return f_log2(x) * LN2;
+    else if constexpr (U == U_EXP) return f_exp(x);
+    else if constexpr (U == U_ROUND) return __builtin_rintf(x);
+    else if constexpr (U == U_FLOOR) return __builtin_floorf(x);
+    else if constexpr (U == U_ISFINITE) return (__builtin_fabsf(x) < __builtin_inff()) ? 1.0f : 0.0f;
+    else if constexpr (U == U_NEG) return -x;
+    else if constexpr (U == U_RSQRT) return f_rsq(x);
+    else if constexpr (U == U_RCP) return f_rcp(x);
+    else if constexpr (U == U_TANH) return f_tanh(x);
+    else if constexpr (U == U_ERF) return f_erf(x);
+    else if constexpr (U == U_SIGMOID) return f_sigmoid(x);
+    else if constexpr (U == U_SQUARE) return x * x;
+    else if constexpr (U == U_GELU_TANH) return f_gelu_tanh(x);
+    else if constexpr (U == U_GELU_ERF) return f_gelu_erf(x);
+    else if constexpr (U == U_SILU) return f_silu(x);
+    else if constexpr (U == U_CAST_BF16) return f_bf16_round(x);
+    else return x;
+}
+
+template <uint32_t B> DI float bin_op(float a, float b) {
+    if constexpr (B == B_NONE) return b;
+    else if constexpr (B == B_ADD) return a + b;
+    else if constexpr (B == B_SUB) return a - b;
+    else if constexpr (B == B_RSUB) return b - a;
+    else if constexpr (B == B_MUL) return a * b;
+    else if constexpr (B == B_DIV) return a * f_rcp(b);
+    else if constexpr (B == B_RDIV) return b * f_rcp(a);
+    else if constexpr (B == B_MIN) return __builtin_fminf(a, b);
+    else if constexpr (B == B_MAX) return __builtin_fmaxf(a, b);
+    else if constexpr (B == B_POW) return f_pow(a, b);
+    else if constexpr (B == B_RPOW) return f_pow(b, a);
+    else if constexpr (B == B_EQ) return a == b ? 1.0f : 0.0f;
+    else if constexpr (B == B_NE) return a != b ? 1.0f : 0.0f;
+    else if constexpr (B == B_LT) return a < b ? 1.0f : 0.0f;
+    else if constexpr (B == B_LE) return a <= b ? 1.0f : 0.0f;
+    else if constexpr (B == B_GT) return a > b ? 1.0f : 0.0f;
+    else if constexpr (B == B_GE) return a >= b ? 1.0f : 0.0f;
+    else return a;
+}
+
+// scalar (one value) versions selected at run time; used for the row-scalar registers
+DI float un_dyn(uint32_t u, float x) {
+    switch (u) {
+#define C(U) case U: return un_op<U>(x);
+        C(U_SQRT) C(U_ABS) C(U_LOG) C(U_EXP) C(U_ROUND) C(U_FLOOR) C(U_ISFINITE) C(U_NEG) C(U_RSQRT)
+        C(U_RCP) C(U_TANH) C(U_ERF) C(U_SIGMOID) C(U_SQUARE) C(U_GELU_TANH) C(U_GELU_ERF) C(U_SILU)
+        C(U_CAST_BF16)
+#undef C
+        default: return x;
+    }
+}
+DI float bin_dyn(uint32_t b, float x, float y) {
+    switch (b) {
+#define C(B) case B: return bin_op<B>(x, y);
+        C(B_NONE) C(B_ADD) C(B_SUB) C(B_RSUB) C(B_MUL) C(B_DIV) C(B_RDIV) C(B_MIN) C(B_MAX) C(B_POW)
+        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE)
+#undef C
+        default: return x;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// A tile register is a struct of K fp32 per lane.  Helpers below touch it only through constant
+// element indices and never choose between two registers at run time (the interpreter's switch
+// does that, in the kernel body), so every register is split into K independent scalar VGPRs and
+// an instruction updates its destination in place.
+// ------------------------------------------------------------------------------------------
+template <int K> struct Tile { float v[K]; };
+template <int K> DI void tile_zero(Tile<K> &t) { sfor<K>([&]<int I>() LI { t.v[I] = 0.0f; }); }
+
+template <int K, uint32_t U> DI void tile_un(Tile<K> &a) {
+    sfor<K>([&]<int I>() LI { a.v[I] = un_op<U>(a.v[I]); });
+}
+template <int K, uint32_t B> DI void tile_bin(Tile<K> &a, const Tile<K> &b) {
+    sfor<K>([&]<int I>() LI { a.v[I] = bin_op<B>(a.v[I], b.v[I]); });
+}
+template <int K, uint32_t B> DI void tile_bins(Tile<K> &a, float s) {
+    sfor<K>([&]<int I>() LI { a.v[I] = bin_op<B>(a.v[I], s); });
+}
+
+template <int K> DI void tile_un_dispatch(Tile<K> &a, uint32_t u) {
+    switch (u) {
+#define C(U) case U: tile_un<K, U>(a); break;
+        C(U_SQRT) C(U_ABS) C(U_LOG) C(U_EXP) C(U_ROUND) C(U_FLOOR) C(U_ISFINITE) C(U_NEG) C(U_RSQRT)
+        C(U_RCP) C(U_TANH) C(U_ERF) C(U_SIGMOID) C(U_SQUARE) C(U_GELU_TANH) C(U_GELU_ERF) C(U_SILU)
+        C(U_CAST_BF16)
+#undef C
+        default: break;
+    }
+}
+template <int K> DI void tile_bin_dispatch(Tile<K> &a, const Tile<K> &b, uint32_t op) {
+    switch (op) {
+#define C(B) case B: tile_bin<K, B>(a, b); break;
+        C(B_NONE) C(B_ADD) C(B_SUB) C(B_RSUB) C(B_MUL) C(B_DIV) C(B_RDIV) C(B_MIN) C(B_MAX) C(B_POW)
+        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE)
+#undef C
+        default: break;
+    }
+}
+template <int K> DI void tile_bins_dispatch(Tile<K> &a, float s, uint32_t op) {
+    switch (op) {
+#define C(B) case B: tile_bins<K, B>(a, s); break;
+        C(B_NONE) C(B_ADD) C(B_SUB) C(B_RSUB) C(B_MUL) C(B_DIV) C(B_RDIV) C(B_MIN) C(B_MAX) C(B_POW)
+        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE)
+#undef C
+        default: break;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// cross-lane reduction inside a wave with DPP / ds_swizzle / readlane; `width` (lanes per
+// row, a power of two up to 64) is wave-uniform.  The combination order is fixed, so results
+// are bitwise reproducible.
+// ------------------------------------------------------------------------------------------
+template <uint32_t R> DI float red_comb(float a, float b) {
+    if constexpr (R == R_MAX) return __builtin_fmaxf(a, b);
+    else if constexpr (R == R_MIN) return __builtin_fminf(a, b);
+    else return a + b;
+}
+template <uint32_t R> DI float red_ident() {
+    if constexpr (R == R_MAX) return -__builtin_inff();
+    else if constexpr (R == R_MIN) return __builtin_inff();
+    else return 0.0f;
+}
+template <int CTRL> DI float dpp_mov(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+template <uint32_t R> DI float wave_allreduce(float v, uint32_t width) {
+    if (width >= 2) v = red_comb<R>(v, dpp_mov<0xB1>(v));                 // quad_perm [1,0,3,2]
+    if (width >= 4) v = red_comb<R>(v, dpp_mov<0x4E>(v));                 // quad_perm [2,3,0,1]
+    if (width >= 8) v = red_comb<R>(v, dpp_mov<0x141>(v));                // row_half_mirror
+    if (width >= 16) v = red_comb<R>(v, dpp_mov<0x140>(v));               // row_mirror
+    if (width >= 32)                                                      // swap with lane ^ 16
+        v = red_comb<R>(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));
+    if (width >= 64) {
+        float lo = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+        float hi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+        v = red_comb<R>(lo, hi);
+    }
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// per-tile geometry
+// ------------------------------------------------------------------------------------------
+struct Geo {
+    // wave-uniform
+    uint64_t colbase;     // first column of the tile
+    uint32_t ncols;       // valid columns of the tile
+    uint32_t GV;          // G * V: column distance between two chunks of one lane
+    uint32_t nvec;        // chunks per lane
+    uint32_t nact;        // nvec * V
+    uint32_t part_slot;   // chunk slot that holds the ragged last chunk, or ~0u
+    uint32_t part_lane;   // lane (within the row group) that owns it
+    uint32_t part_col;    // its first column (relative to colbase)
+    uint32_t part_n;      // its number of valid elements
+    uint32_t ragged;      // some lane has invalid columns inside live chunks: reductions must mask
+    // per lane
+    uint32_t i1, i2, i3;  // decomposition of the lane's row index over the outer dims
+    uint32_t lanecol;     // first column of the lane's chunk 0, relative to colbase
+    uint32_t lr;          // lane index within the row group
+    bool rowok;
+};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+#define GLOBAL_AS __attribute__((address_space(1)))
+typedef const GLOBAL_AS char *gcptr;   // global memory, read
+typedef GLOBAL_AS char *gptr;          // global memory, write
+
+DI float bf16_lo(uint32_t w) { return __builtin_bit_cast(float, w << 16); }
+DI float bf16_hi(uint32_t w) { return __builtin_bit_cast(float, w & 0xFFFF0000u); }
+DI uint32_t pack_bf16x2(float a, float b) {
+    typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+    typedef float f2 __attribute__((ext_vector_type(2)));
+    f2 v = {a, b};
+    bf2 h = __builtin_convertvector(v, bf2);
+    return __builtin_bit_cast(uint32_t, h);
+}
+DI uint16_t pack_bf16(float a) {
+    __bf16 h = (__bf16)a;
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+// element offset of the lane's row for a tensor with outer strides s1..s3
+DI int64_t row_offset(const Geo &g, int64_t s1, int64_t s2, int64_t s3) {
+    return (int64_t)g.i1 * s1 + (int64_t)g.i2 * s2 + (int64_t)g.i3 * s3;
+}
+
+// Load the lane's part of a tile as fp32.  DT: 0 = fp32, 1 = bf16.  V = chunk width.
+// `rowp` points at column `colbase` of the lane's row in this tensor.
+template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const Geo &g) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    static_assert(DT == 0 || V == 8, "bf16 tiles use 8-element chunks");
+    tile_zero<K>(t);
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        gcptr p = rowp + (uint64_t)g.lanecol * ES;
+        sfor<NJ>([&]<int J>() LI {
+            if (J == 0 || (uint32_t)J < g.nvec) {
+                const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                if (g.rowok && c0 + V <= g.ncols) {
+                    gcptr q = p + (uint64_t)J * g.GV * ES;
+                    if constexpr (DT == 0) {
+                        sfor<V / 4>([&]<int H>() LI {
+                            const u32x4 r = *(const GLOBAL_AS u32x4_a4 *)(q + 16 * H);
+                            sfor<4>([&]<int E>() LI { t.v[J * V + 4 * H + E] = __builtin_bit_cast(float, r[E]); });
+                        });
+                    } else {
+                        const u32x4 r = *(const GLOBAL_AS u32x4_a2 *)q;
+                        sfor<4>([&]<int E>() LI {
+                            t.v[J * V + 2 * E] = bf16_lo(r[E]);
+                            t.v[J * V + 2 * E + 1] = bf16_hi(r[E]);
+                        });
+                    }
+                }
+            }
+        });
+        if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
+            const bool own = g.rowok && g.lr == g.part_lane;
+            sfor<NJ>([&]<int J>() LI {
+                if ((uint32_t)J == g.part_slot) {
+                    sfor<V>([&]<int E>() LI {
+                        if ((uint32_t)E < g.part_n && own) {
+                            gcptr q = rowp + (uint64_t)(g.part_col + E) * ES;
+                            if constexpr (DT == 0) t.v[J * V + E] = *(const GLOBAL_AS float *)q;
+                            else t.v[J * V + E] = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
+                        }
+                    });
+                }
+            });
+        }
+    }
+}
+
+template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, const Geo &g) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        gptr p = rowp + (uint64_t)g.lanecol * ES;
+        sfor<NJ>([&]<int J>() LI {
+            if (J == 0 || (uint32_t)J < g.nvec) {
+                const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                if (g.rowok && c0 + V <= g.ncols) {
+                    gptr q = p + (uint64_t)J * g.GV * ES;
+                    if constexpr (DT == 0) {
+                        sfor<V / 4>([&]<int H>() LI {
+                            const u32x4 r = {__builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 0]),
+                                             __builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 1]),
+                                             __builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 2]),
+                                             __builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 3])};
+                            *(GLOBAL_AS u32x4_a4 *)(q + 16 * H) = r;
+                        });
+                    } else {
+                        const u32x4 r = {pack_bf16x2(t.v[J * V + 0], t.v[J * V + 1]), pack_bf16x2(t.v[J * V + 2], t.v[J * V + 3]),
+                                         pack_bf16x2(t.v[J * V + 4], t.v[J * V + 5]), pack_bf16x2(t.v[J * V + 6], t.v[J * V + 7])};
+                        *(GLOBAL_AS u32x4_a2 *)q = r;
+                    }
+                }
+            }
+        });
+        if (g.part_slot != ~0u) {
+            const bool own = g.rowok && g.lr == g.part_lane;
+            sfor<NJ>([&]<int J>() LI {
+                if ((uint32_t)J == g.part_slot) {
+                    sfor<V>([&]<int E>() LI {
+                        if ((uint32_t)E < g.part_n && own) {
+                            gptr q = rowp + (uint64_t)(g.part_col + E) * ES;
+                            if constexpr (DT == 0) *(GLOBAL_AS float *)q = t.v[J * V + E];
+                            else *(GLOBAL_AS uint16_t *)q = pack_bf16(t.v[J * V + E]);
+                        }
+                    });
+                }
+            });
+        }
+    }
+}
+
+template <int K> DI void load_dispatch(Tile<K> &t, uint32_t dt, uint32_t V, gcptr rowp, const Geo &g) {
+    if (dt == 0) {
+        if (V == 4) load_tile<K, 0, 4>(t, rowp, g);
+        else load_tile<K, 0, 8>(t, rowp, g);
+    } else {
+        load_tile<K, 1, 8>(t, rowp, g);
+    }
+}
+template <int K> DI void store_dispatch(const Tile<K> &t, uint32_t dt, uint32_t V, gptr rowp, const Geo &g) {
+    if (dt == 0) {
+        if (V == 4) store_tile<K, 0, 4>(t, rowp, g);
+        else store_tile<K, 0, 8>(t, rowp, g);
+    } else {
+        store_tile<K, 1, 8>(t, rowp, g);
+    }
+}
+
+// in-lane part of a row reduction over the accumulator, masking invalid columns when ragged
+template <int K, uint32_t R> DI float lane_reduce(const Tile<K> &a, const Geo &g, uint32_t V) {
+    float v = red_ident<R>();
+    if (!g.ragged) {
+        sfor<K / 4>([&]<int Q>() LI {
+            if (Q == 0 || (uint32_t)(Q * 4) < g.nact) {
+                sfor<4>([&]<int E>() LI {
+                    if constexpr (R == R_SUMSQ) v = f_fma(a.v[Q * 4 + E], a.v[Q * 4 + E], v);
+                    else v = red_comb<R>(v, a.v[Q * 4 + E]);
+                });
+            }
+        });
+    } else {
+        sfor<K / 4>([&]<int Q>() LI {
+            if (Q == 0 || (uint32_t)(Q * 4) < g.nact) {
+                // element k of the lane sits in chunk k / V at offset k % V
+                constexpr uint32_t k = Q * 4;
+                const uint32_t j = V == 8 ? k >> 3 : k >> 2;
+                const uint32_t c0 = g.lanecol + j * g.GV + (k & (V - 1));
+                sfor<4>([&]<int E>() LI {
+                    const bool ok = (c0 + E) < g.ncols;
+                    if constexpr (R == R_SUMSQ) {
+                        const float x = ok ? a.v[k + E] : 0.0f;
+                        v = f_fma(x, x, v);
+                    } else {
+                        v = red_comb<R>(v, ok ? a.v[k + E] : red_ident<R>());
+                    }
+                });
+            }
+        });
+    }
+    return v;
+}
+template <int K> DI float reduce_dispatch(const Tile<K> &a, const Geo &g, uint32_t V, uint32_t kind, uint32_t width) {
+    switch (kind) {
+        case R_MAX: return wave_allreduce<R_MAX>(lane_reduce<K, R_MAX>(a, g, V), width);
+        case R_MIN: return wave_allreduce<R_MIN>(lane_reduce<K, R_MIN>(a, g, V), width);
+        case R_SUMSQ: return wave_allreduce<R_SUM>(lane_reduce<K, R_SUMSQ>(a, g, V), width);
+        default: return wave_allreduce<R_SUM>(lane_reduce<K, R_SUM>(a, g, V), width);
+    }
+}
+
+DI float pick_s(float s0, float s1, float s2, float s3, uint32_t i) {
+    float v = s0;
+    v = i == 1 ? s1 : v;
+    v = i == 2 ? s2 : v;
+    v = i == 3 ? s3 : v;
+    return v;
+}
+
+// unsigned division by an invariant divisor with a precomputed multiplier and two shifts
+// (Granlund & Montgomery, "Division by invariant integers using multiplication", 32-bit case)
+DI uint32_t magic_div(uint32_t n, uint32_t m, uint32_t sh) {
+    uint32_t t = __umulhi(m, n);
+    return (t + ((n - t) >> (sh & 0xFF))) >> (sh >> 8);
+}
+DI uint32_t sdiv_u(uint32_t n, uint32_t m, uint32_t sh) {   // the same on wave-uniform values
+    uint32_t t = (uint32_t)(((uint64_t)m * n) >> 32);
+    return (t + ((n - t) >> (sh & 0xFF))) >> (sh >> 8);
+}
+
+// ------------------------------------------------------------------------------------------
+// the interpreter
+// ------------------------------------------------------------------------------------------
+// Run STMT with `RR` naming tile register number IDX (a wave-uniform value): one switch case per
+// register, so that every case references its register statically.
+#define DVM_WITH_R(IDX, RR, STMT)                                        \
+    switch (IDX) {                                                       \
+        case 0: { Tile<K> &RR = r0; STMT; } break;                         \
+        case 1: if constexpr (NR > 1) { Tile<K> &RR = r1; STMT; } break;   \
+        case 2: if constexpr (NR > 2) { Tile<K> &RR = r2; STMT; } break;   \
+        case 3: if constexpr (NR > 3) { Tile<K> &RR = r3; STMT; } break;   \
+        case 4: if constexpr (NR > 4) { Tile<K> &RR = r4; STMT; } break;   \
+        case 5: if constexpr (NR > 5) { Tile<K> &RR = r5; STMT; } break;   \
+        default: break;                                                  \
+    }
+#define DVM_GET_S(I) pick_s(s0, s1, s2, s3, (I))
+#define DVM_SET_S(I, VAL)                   \
+    do {                                    \
+        const uint32_t si_ = (I);           \
+        const float sv_ = (VAL);            \
+        s0 = si_ == 0 ? sv_ : s0;           \
+        s1 = si_ == 1 ? sv_ : s1;           \
+        s2 = si_ == 2 ? sv_ : s2;           \
+        s3 = si_ == 3 ? sv_ : s3;           \
+    } while (0)
+#define DVM_I64(AT) ((int64_t)((uint64_t)code[(AT)] | ((uint64_t)code[(AT) + 1] << 32)))
+
+template <int K, int NR, int MAXT>
+__global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
+    __shared__ float red_lds[2][16];
+
+    // the register file of one lane: accumulator, tile registers, row-scalar registers
+    Tile<K> acc, r0, r1, r2, r3, r4, r5;
+    tile_zero<K>(acc); tile_zero<K>(r0); tile_zero<K>(r1); tile_zero<K>(r2);
+    tile_zero<K>(r3); tile_zero<K>(r4); tile_zero<K>(r5);
+    float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+
+    const uint32_t tid = threadIdx.x;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid) >> 6;
+    const uint32_t bid = blockIdx.x;
+    const uint32_t ngrid = gridDim.x;
+    uint32_t red_par = 0;
+    const uint32_t *code = args.code;
+
+    uint32_t seg = 0;                       // word offset of the current segment
+    for (uint32_t si = 0; si < args.nseg; ++si) {
+        const uint32_t *sh = &code[seg];
+        const uint32_t seg_words = sh[S_WORDS];
+        const uint32_t code_size = sh[S_CODESIZE];
+        const uint32_t M = sh[S_NTILES];
+        const uint32_t geom = sh[S_GEOM];
+        const uint32_t G = geom & 0xFFFF, V = (geom >> 16) & 0xFF, nvec = geom >> 24;
+        const uint32_t RP = sh[S_RP] & 0xFFFF, seg_threads = sh[S_RP] >> 16;
+        const uint32_t tbase = sh[S_TBASE];
+        const uint32_t body = seg + SH_WORDS;
+        const uint32_t body_end = body + code_size;
+
+        Geo g;
+        g.GV = G * V;
+        g.nvec = nvec;
+        g.nact = nvec * V;
+        const uint32_t rp = tid / G;            // row of the tile held by this lane
+        g.lr = tid - rp * G;
+        g.lanecol = g.lr * V;
+        const uint32_t gw = G >> 6;             // waves per row when a row spans waves
+        const uint32_t width = G < 64 ? G : 64;
+        const uint32_t w0i = gw > 1 ? (wave / gw) * gw : wave;   // first wave of this lane's row
+
+        // Algorithm 2: m = ceil(M / N); this workgroup runs tiles [m*id, min(M, m*(id+1)))
+        const uint32_t m = (M + ngrid - 1) / ngrid;
+        const uint64_t t_lo64 = (uint64_t)m * bid;
+        const uint32_t t_lo = t_lo64 < M ? (uint32_t)t_lo64 : M;
+        const uint32_t t_hi = (M - t_lo) < m ? M : t_lo + m;
+
+        for (uint32_t tile = t_lo; tile < t_hi; ++tile) {
+            {   // tile prologue: where this tile sits, which of its lanes and chunks are valid
+                const uint32_t nct = sh[S_NCT], TC = sh[S_TC];
+                const uint64_t D0 = (uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32);
+                const uint32_t nrows = sh[S_NROWS];
+                uint32_t tile_r = tile, tile_c = 0;
+                if (nct > 1) {
+                    tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
+                    tile_c = tile - tile_r * nct;
+                }
+                g.colbase = (uint64_t)tile_c * TC;
+                const uint64_t rem = D0 - g.colbase;
+                g.ncols = rem < TC ? (uint32_t)rem : TC;
+                const uint32_t row = tile_r * RP + rp;
+                g.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
+                const uint32_t rowc = g.rowok ? row : 0;
+                g.i1 = rowc; g.i2 = 0; g.i3 = 0;
+                const uint32_t D1 = sh[S_D1];
+                if (D1 != 0) {
+                    const uint32_t q = magic_div(rowc, sh[S_M1], sh[S_SH1]);
+                    g.i1 = rowc - q * D1;
+                    g.i2 = q;
+                    const uint32_t D2 = sh[S_D2];
+                    if (D2 != 0) {
+                        const uint32_t q2 = magic_div(q, sh[S_M2], sh[S_SH2]);
+                        g.i2 = q - q2 * D2;
+                        g.i3 = q2;
+                    }
+                }
+                const uint32_t full_chunks = g.ncols / V;      // V is 4 or 8
+                g.part_n = g.ncols - full_chunks * V;
+                g.part_slot = ~0u;
+                g.part_lane = 0;
+                g.part_col = full_chunks * V;
+                if (g.part_n != 0) {
+                    g.part_slot = full_chunks / G;
+                    g.part_lane = full_chunks - g.part_slot * G;
+                }
+                // rows never mix in a reduction, so only invalid columns inside live chunks need a mask
+                g.ragged = g.ncols != g.nact * G;
+            }
+
+            for (uint32_t pc = body; pc < body_end;) {
+                const uint32_t w = code[pc];
+                const uint32_t op = w & 0xFF, len = (w >> 8) & 0xFF, a = (w >> 16) & 0xFF, b = w >> 24;
+                switch (op) {
+                    case I_LOAD:
+                    case I_VLOAD: {
+                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                        const int64_t st1 = DVM_I64(pc + 2);
+                        int64_t st2 = 0, st3 = 0;
+                        if (op == I_VLOAD) {
+                            st2 = DVM_I64(pc + 4);
+                            st3 = DVM_I64(pc + 6);
+                        }
+                        const uint32_t es = dt == 0 ? 4 : 2;
+                        gcptr base = (gcptr)args.tensors[tbase + ti];
+                        gcptr rowp = base + (row_offset(g, st1, st2, st3) + (int64_t)g.colbase) * es;
+                        Tile<K> t;
+                        load_dispatch<K>(t, dt, V, rowp, g);
+                        if (a == SRC_ACC) {
+                            tile_bin_dispatch<K>(acc, t, b);
+                        } else {
+                            DVM_WITH_R(a, rr, rr = t)
+                        }
+                        break;
+                    }
+                    case I_STORE:
+                    case I_VSTORE: {
+                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                        const int64_t st1 = DVM_I64(pc + 2);
+                        int64_t st2 = 0, st3 = 0;
+                        if (op == I_VSTORE) {
+                            st2 = DVM_I64(pc + 4);
+                            st3 = DVM_I64(pc + 6);
+                        }
+                        const uint32_t es = dt == 0 ? 4 : 2;
+                        gptr base = (gptr)args.tensors[tbase + ti];
+                        gptr rowp = base + (row_offset(g, st1, st2, st3) + (int64_t)g.colbase) * es;
+                        Tile<K> t = acc;
+                        if (a != SRC_ACC) {
+                            DVM_WITH_R(a, rr, t = rr)
+                        }
+                        store_dispatch<K>(t, dt, V, rowp, g);
+                        break;
+                    }
+                    case I_LOADS: {
+                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                        const int64_t off = row_offset(g, DVM_I64(pc + 2), DVM_I64(pc + 4), DVM_I64(pc + 6));
+                        gcptr base = (gcptr)args.tensors[tbase + ti];
+                        float v = 0.0f;
+                        if (g.rowok) {
+                            if (dt == 0) v = *(const GLOBAL_AS float *)(base + off * 4);
+                            else v = bf16_lo(*(const GLOBAL_AS uint16_t *)(base + off * 2));
+                        }
+                        DVM_SET_S(a, v);
+                        break;
+                    }
+                    case I_STORES: {
+                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                        const int64_t off = row_offset(g, DVM_I64(pc + 2), DVM_I64(pc + 4), DVM_I64(pc + 6));
+                        gptr base = (gptr)args.tensors[tbase + ti];
+                        const float v = DVM_GET_S(a);
+                        if (g.rowok && g.lr == 0 && g.colbase == 0) {
+                            if (dt == 0) *(GLOBAL_AS float *)(base + off * 4) = v;
+                            else *(GLOBAL_AS uint16_t *)(base + off * 2) = pack_bf16(v);
+                        }
+                        break;
+                    }
+                    case I_MOVRA:
+                        DVM_WITH_R(a, rr, rr = acc)
+                        break;
+                    case I_MOVAR:
+                        DVM_WITH_R(a, rr, acc = rr)
+                        break;
+                    case I_UN:
+                        tile_un_dispatch<K>(acc, b);
+                        break;
+                    case I_BIN:
+                        if (a < SRC_S0) {
+                            DVM_WITH_R(a, rr, tile_bin_dispatch<K>(acc, rr, b))
+                        } else if (a == SRC_ACC) {
+                            const Tile<K> t = acc;
+                            tile_bin_dispatch<K>(acc, t, b);
+                        } else {
+                            const float s = a == SRC_IMM ? __builtin_bit_cast(float, code[pc + 1]) : DVM_GET_S(a - SRC_S0);
+                            tile_bins_dispatch<K>(acc, s, b);
+                        }
+                        break;
+                    case I_SEL: {
+                        Tile<K> xa = acc, xb = acc;
+                        DVM_WITH_R(a, rr, xa = rr)
+                        DVM_WITH_R(b, rr, xb = rr)
+                        sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; });
+                        break;
+                    }
+                    case I_RED: {
+                        const float v = reduce_dispatch<K>(acc, g, V, b, width);
+                        if (gw > 1) {
+                            if ((tid & 63) == 0) red_lds[red_par][wave & 15] = v;
+                        } else {
+                            DVM_SET_S(a, v);
+                        }
+                        break;
+                    }
+                    case I_SYNC:
+                        __syncthreads();
+                        break;
+                    case I_REDX: {
+                        float v = red_lds[red_par][w0i & 15];
+                        for (uint32_t i = 1; i < gw; ++i) {
+                            const float o = red_lds[red_par][(w0i + i) & 15];
+                            v = b == R_MAX ? __builtin_fmaxf(v, o) : (b == R_MIN ? __builtin_fminf(v, o) : v + o);
+                        }
+                        DVM_SET_S(a, v);
+                        red_par ^= 1;
+                        break;
+                    }
+                    case I_SOP: {
+                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t kind = w1 & 0xFF, srck = (w1 >> 8) & 0xFF, c = (w1 >> 16) & 0xFF;
+                        const float x = DVM_GET_S(b);
+                        float r;
+                        if (kind >= SOP_UNARY) {
+                            r = un_dyn(kind - SOP_UNARY, x);
+                        } else {
+                            const float y = srck == 1 ? __builtin_bit_cast(float, code[pc + 2]) : DVM_GET_S(c);
+                            r = bin_dyn(kind, x, y);
+                        }
+                        DVM_SET_S(a, r);
+                        break;
+                    }
+                    default:
+                        break;
+                }
+                pc += len ? len : 1;
+            }
+        }
+        seg += seg_words;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side: dvm_run
+// ------------------------------------------------------------------------------------------
+typedef void (*vm_kernel_t)(const KArgs);
+
+struct VariantEntry { int K, NR; vm_kernel_t fn; };
+
+const VariantEntry g_variants[] = {
+    { 4, 2, dvm_vm_kernel< 4, 2, 1024>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024>},
+    { 8, 2, dvm_vm_kernel< 8, 2, 1024>}, { 8, 6, dvm_vm_kernel< 8, 6,  512>},
+    {16, 2, dvm_vm_kernel<16, 2,  512>}, {16, 6, dvm_vm_kernel<16, 6,  256>},
+    {32, 2, dvm_vm_kernel<32, 2,  256>},
+};
+
+thread_local int t_last_hip_error = 0;
+
+}  // namespace
+
+extern "C" int dvm_last_hip_error(void) { return t_last_hip_error; }
+
+extern "C" int dvm_ctx_query_device(int hip_device, int *n_cu) {
+    hipDeviceProp_t prop;
+    hipError_t e = hipGetDeviceProperties(&prop, hip_device);
+    if (e != hipSuccess) {
+        t_last_hip_error = (int)e;
+        return DVM_E_HIP;
+    }
+    *n_cu = prop.multiProcessorCount;
+    return DVM_OK;
+}
+
+extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors, int n_tensors,
+                       void *hip_stream) {
+    if (!ctx || !bytecode || (!tensors && n_tensors > 0)) return dvm_set_error(DVM_E_ARGS, "dvm_run: null argument");
+    if (dvm_ctx_device(ctx) < 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: context was created without a device");
+    int st = dvm_validate(bytecode, len);
+    if (st != DVM_OK) return st;
+    const uint32_t *w = (const uint32_t *)bytecode;
+    const uint32_t ntens = w[PH_NTENS];
+    if ((uint32_t)n_tensors != ntens) return dvm_set_error(DVM_E_ARGS, "dvm_run: tensor count does not match the bytecode");
+    const uint32_t segs_off = PH_WORDS_N + ntens * TT_WORDS;
+    const uint32_t seg_words = w[PH_WORDS] - segs_off;
+    if (seg_words > (uint32_t)CODE_WORDS) return dvm_set_error(DVM_E_LIMIT, "dvm_run: bytecode exceeds the kernel-argument budget");
+
+    KArgs ka;
+    memcpy(ka.code, w + segs_off, (size_t)seg_words * 4);
+    for (uint32_t i = 0; i < ntens; ++i) {
+        const uint32_t info = w[PH_WORDS_N + i * TT_WORDS + TT_INFO];
+        const uint64_t align = 1ull << ((info >> 16) & 0xFF);
+        const uint64_t addr = (uint64_t)(uintptr_t)tensors[i];
+        if (addr == 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: null tensor pointer");
+        if (addr & (align - 1)) return dvm_set_error(DVM_E_ALIGN, "dvm_run: tensor pointer below the alignment the bytecode was encoded for");
+        ka.tensors[i] = addr;
+    }
+    ka.nseg = w[PH_NSEG];
+    ka.pad = 0;
+
+    const int K = (int)(w[PH_VARIANT] & 0xFF), NR = (int)((w[PH_VARIANT] >> 8) & 0xFF);
+    vm_kernel_t fn = nullptr;
+    for (const VariantEntry &v : g_variants)
+        if (v.K == K && v.NR == NR) fn = v.fn;
+    if (!fn) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
+    const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
+    if (grid == 0) return DVM_OK;   // an empty iteration space: nothing to launch
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), 0, (hipStream_t)hip_stream, ka);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        t_last_hip_error = (int)e;
+        return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
+    }
+    return DVM_OK;
+}
