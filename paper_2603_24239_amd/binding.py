@@ -1,0 +1,305 @@
+"""Thin ctypes binding over libdvm.so (see include/dvm.h).  Argument marshalling only: every step
+of the path (decomposition, fusion, tile planning, encoding, execution) runs in the library.
+
+PyTorch is used by callers for device memory and streams; this module only reads
+``tensor.data_ptr()``, ``tensor.shape``, ``tensor.stride()`` and the current stream handle.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libdvm.so")
+
+DVM_MAX_RANK = 6
+DVM_F32, DVM_BF16 = 0, 1
+DTYPES = {"f32": DVM_F32, "bf16": DVM_BF16}
+
+# opcode values of include/dvm.h
+OPCODES: Dict[str, int] = {}
+for _i, _n in enumerate(["copy", "sqrt", "abs", "log", "exp", "round", "floor", "isfinite", "neg", "rsqrt", "rcp",
+                         "tanh", "erf", "sigmoid", "square", "gelu_tanh", "gelu_erf", "silu", "cast"], start=1):
+    OPCODES[_n] = _i
+OPCODES.update({"adds": 32, "muls": 33})
+for _i, _n in enumerate(["add", "sub", "mul", "div", "min", "max", "pow", "cmp_eq", "cmp_ne", "cmp_lt", "cmp_le",
+                         "cmp_gt", "cmp_ge"], start=40):
+    OPCODES[_n] = _i
+OPCODES["select"] = 60
+for _i, _n in enumerate(["sum", "rmax", "rmin", "mean", "meansq"], start=64):
+    OPCODES[_n] = _i
+for _i, _n in enumerate(["softmax", "rmsnorm", "layernorm"], start=80):
+    OPCODES[_n] = _i
+
+
+class dvm_shape(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("align_bytes", C.c_int32),
+                ("dim", C.c_int64 * DVM_MAX_RANK), ("stride", C.c_int64 * DVM_MAX_RANK)]
+
+
+class dvm_code_info(C.Structure):
+    _fields_ = [("kernel_type", C.c_int32), ("n_segments", C.c_int32), ("n_tensors", C.c_int32),
+                ("grid", C.c_int32), ("block", C.c_int32), ("variant_k", C.c_int32), ("variant_nr", C.c_int32),
+                ("n_instructions", C.c_int32), ("n_tiles", C.c_int64), ("code_bytes", C.c_int64)]
+
+
+class DvmError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        lib = load()
+        msg = lib.dvm_strerror(status).decode()
+        detail = lib.dvm_last_error_detail().decode()
+        super().__init__(f"{where}: {msg} ({status})" + (f": {detail}" if detail else ""))
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libdvm.so from the package directory.  There is no fallback: without the built
+    library nothing in this package can run."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2603_24239_amd.build`")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i, sz = C.c_void_p, C.c_int, C.c_size_t
+    P = C.POINTER
+    sig = {
+        "dvm_shape_contiguous": (i, [P(dvm_shape), i, P(C.c_int64)]),
+        "dvm_ctx_create": (i, [i, P(vp)]),
+        "dvm_ctx_destroy": (None, [vp]),
+        "dvm_ctx_set_planner": (i, [vp, i, i]),
+        "dvm_prog_create": (i, [P(vp)]),
+        "dvm_prog_input": (i, [vp, i, P(i)]),
+        "dvm_prog_op": (i, [vp, i, P(i), i, P(C.c_double), i, P(i)]),
+        "dvm_prog_output": (i, [vp, i, i]),
+        "dvm_prog_finish": (i, [vp]),
+        "dvm_prog_num_inputs": (i, [vp]),
+        "dvm_prog_num_outputs": (i, [vp]),
+        "dvm_prog_destroy": (None, [vp]),
+        "dvm_encode": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), P(dvm_shape)]),
+        "dvm_stack": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
+        "dvm_validate": (i, [vp, sz]),
+        "dvm_disasm": (i, [vp, sz, C.c_char_p, sz]),
+        "dvm_code_info_get": (i, [vp, sz, P(dvm_code_info)]),
+        "dvm_code_tensor": (i, [vp, sz, i, P(C.c_int64), P(i), P(i), P(i)]),
+        "dvm_plan": (i, [C.c_int64, i, C.c_int64, i, i, P(C.c_int64), P(C.c_int64), P(C.c_int64)]),
+        "dvm_run": (i, [vp, vp, sz, P(vp), i, vp]),
+        "dvm_strerror": (C.c_char_p, [i]),
+        "dvm_last_error_detail": (C.c_char_p, []),
+        "dvm_last_hip_error": (i, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_prog_create",
+            "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
+            "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_validate", "dvm_disasm",
+            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_strerror", "dvm_last_error_detail",
+            "dvm_last_hip_error"]
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise DvmError(status, where)
+
+
+def make_shape(dims: Sequence[int], strides: Optional[Sequence[int]] = None, align_bytes: int = 0) -> dvm_shape:
+    s = dvm_shape()
+    r = len(dims)
+    if r > DVM_MAX_RANK:
+        raise DvmError(-3, "make_shape")
+    s.rank = r
+    s.align_bytes = align_bytes
+    if strides is None:
+        arr = (C.c_int64 * max(r, 1))(*dims)
+        _check(load().dvm_shape_contiguous(C.byref(s), r, arr), "dvm_shape_contiguous")
+        s.align_bytes = align_bytes
+    else:
+        for k in range(r):
+            s.dim[k] = int(dims[k])
+            s.stride[k] = int(strides[k])
+    return s
+
+
+def _ptr_align(ptr: int) -> int:
+    a = 1
+    while a < 16 and ptr % (a * 2) == 0:
+        a *= 2
+    return a
+
+
+def shape_of_tensor(t) -> dvm_shape:
+    return make_shape(tuple(t.shape), tuple(t.stride()), _ptr_align(t.data_ptr()))
+
+
+class Context:
+    """dvm_ctx: device properties for the planner.  device=-1 builds an encode-only context."""
+
+    def __init__(self, device: int = -1):
+        self._h = C.c_void_p()
+        _check(load().dvm_ctx_create(device, C.byref(self._h)), "dvm_ctx_create")
+        self.device = device
+
+    def set_planner(self, n_compute_units: int = 0, tile_overhead_elems: int = 0) -> None:
+        _check(load().dvm_ctx_set_planner(self._h, n_compute_units, tile_overhead_elems), "dvm_ctx_set_planner")
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.dvm_ctx_destroy(self._h)
+            self._h = None
+
+
+class Program:
+    """dvm_prog built from a neutral program description (workloads.programs.Program)."""
+
+    def __init__(self, desc):
+        lib = load()
+        self.desc = desc
+        self._h = C.c_void_p()
+        _check(lib.dvm_prog_create(C.byref(self._h)), "dvm_prog_create")
+        ids: Dict[str, int] = {}
+        vid = C.c_int()
+        for name, dt in desc.inputs:
+            _check(lib.dvm_prog_input(self._h, DTYPES[dt], C.byref(vid)), "dvm_prog_input")
+            ids[name] = vid.value
+        for op in desc.ops:
+            name = op.name
+            imm: List[float] = []
+            if name == "cmp":
+                name = "cmp_" + str(op.attrs["cmp"])
+            elif name in ("adds", "muls"):
+                imm = [float(op.attrs["imm"])]
+            elif name in ("rmsnorm", "layernorm"):
+                imm = [float(op.attrs["eps"])]
+            elif name == "cast":
+                imm = [float(DTYPES[str(op.attrs["to"])])]
+            args = (C.c_int * max(len(op.args), 1))(*[ids[a] for a in op.args])
+            immarr = (C.c_double * max(len(imm), 1))(*imm)
+            _check(lib.dvm_prog_op(self._h, OPCODES[name], args, len(op.args), immarr, len(imm), C.byref(vid)),
+                   f"dvm_prog_op({op.name})")
+            ids[op.out] = vid.value
+        for name, dt in desc.outputs:
+            _check(lib.dvm_prog_output(self._h, ids[name], DTYPES[dt]), "dvm_prog_output")
+        _check(lib.dvm_prog_finish(self._h), "dvm_prog_finish")
+        self.n_in = lib.dvm_prog_num_inputs(self._h)
+        self.n_out = lib.dvm_prog_num_outputs(self._h)
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.dvm_prog_destroy(self._h)
+            self._h = None
+
+
+class Bytecode:
+    def __init__(self, raw: bytes, out_shapes: List[Tuple[int, ...]]):
+        self.raw = raw
+        self._buf = C.create_string_buffer(raw, len(raw))
+        self.out_shapes = out_shapes
+
+    def __len__(self):
+        return len(self.raw)
+
+    @property
+    def ptr(self):
+        return C.cast(self._buf, C.c_void_p)
+
+    def info(self) -> dvm_code_info:
+        inf = dvm_code_info()
+        _check(load().dvm_code_info_get(self.ptr, len(self.raw), C.byref(inf)), "dvm_code_info_get")
+        return inf
+
+    def tensor(self, index: int) -> Tuple[int, bool, int, int]:
+        mb, io, dt, al = C.c_int64(), C.c_int(), C.c_int(), C.c_int()
+        _check(load().dvm_code_tensor(self.ptr, len(self.raw), index, C.byref(mb), C.byref(io), C.byref(dt),
+                                      C.byref(al)), "dvm_code_tensor")
+        return mb.value, bool(io.value), dt.value, al.value
+
+    def disasm(self) -> str:
+        buf = C.create_string_buffer(1 << 16)
+        _check(load().dvm_disasm(self.ptr, len(self.raw), buf, len(buf)), "dvm_disasm")
+        return buf.value.decode()
+
+    def validate(self) -> None:
+        _check(load().dvm_validate(self.ptr, len(self.raw)), "dvm_validate")
+
+
+_ENC_CAP = 8192
+
+
+def dvm_encode(ctx: Context, prog: Program, in_shapes: Sequence[dvm_shape],
+               out_layout: Optional[Sequence[dvm_shape]] = None) -> Bytecode:
+    lib = load()
+    n = len(in_shapes)
+    arr = (dvm_shape * max(n, 1))(*in_shapes)
+    outl = None
+    if out_layout is not None:
+        outl = (dvm_shape * max(len(out_layout), 1))(*out_layout)
+    buf = C.create_string_buffer(_ENC_CAP)
+    ln = C.c_size_t()
+    outs = (dvm_shape * max(prog.n_out, 1))()
+    _check(lib.dvm_encode(ctx._h, prog._h, arr, n, outl, buf, _ENC_CAP, C.byref(ln), outs), "dvm_encode")
+    shapes = [tuple(outs[i].dim[k] for k in range(outs[i].rank)) for i in range(prog.n_out)]
+    return Bytecode(buf.raw[: ln.value], shapes)
+
+
+def dvm_stack(codes: Sequence[Bytecode]) -> Bytecode:
+    lib = load()
+    n = len(codes)
+    ptrs = (C.c_void_p * n)(*[c.ptr for c in codes])
+    lens = (C.c_size_t * n)(*[len(c) for c in codes])
+    buf = C.create_string_buffer(_ENC_CAP)
+    ln = C.c_size_t()
+    _check(lib.dvm_stack(ptrs, lens, n, buf, _ENC_CAP, C.byref(ln)), "dvm_stack")
+    shapes: List[Tuple[int, ...]] = []
+    for c in codes:
+        shapes.extend(c.out_shapes)
+    return Bytecode(buf.raw[: ln.value], shapes)
+
+
+def dvm_run(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: int = 0) -> None:
+    n = len(tensor_ptrs)
+    arr = (C.c_void_p * max(n, 1))(*tensor_ptrs)
+    _check(load().dvm_run(ctx._h, code.ptr, len(code), arr, n, C.c_void_p(stream)), "dvm_run")
+
+
+def dvm_plan(total: int, n_cores: int, t_max: int, align: int, overhead: int = 2) -> Tuple[int, int, int]:
+    a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
+    _check(load().dvm_plan(total, n_cores, t_max, align, overhead, C.byref(a), C.byref(b), C.byref(c)), "dvm_plan")
+    return a.value, b.value, c.value
+
+
+# ------------------------------------------------------------------------------------------------
+# convenience for torch callers: marshal tensors, allocate outputs (torch owns device memory)
+# ------------------------------------------------------------------------------------------------
+
+def encode_for(ctx: Context, prog: Program, inputs: Sequence, outputs: Optional[Sequence] = None) -> Bytecode:
+    """Encode `prog` for the shapes/strides of the given torch tensors (and output views, if any)."""
+    in_shapes = [shape_of_tensor(t) for t in inputs]
+    out_layout = [shape_of_tensor(t) for t in outputs] if outputs is not None else None
+    return dvm_encode(ctx, prog, in_shapes, out_layout)
+
+
+def check_buffers(code: Bytecode, tensors: Sequence) -> None:
+    """Host-side guard: every tensor's storage must cover what the bytecode will touch."""
+    for i, t in enumerate(tensors):
+        need, _is_out, _dt, _al = code.tensor(i)
+        have = (t.untyped_storage().nbytes() - t.storage_offset() * t.element_size()) if t.numel() else 0
+        if need > have:
+            raise DvmError(-1, f"tensor {i}: bytecode touches {need} bytes, storage holds {have}")
+
+
+def run_on(ctx: Context, code: Bytecode, tensors: Sequence, stream: Optional[int] = None) -> None:
+    import torch
+    check_buffers(code, tensors)
+    if stream is None:
+        stream = torch.cuda.current_stream().cuda_stream
+    dvm_run(ctx, code, [t.data_ptr() for t in tensors], stream)

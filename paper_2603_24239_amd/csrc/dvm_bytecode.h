@@ -136,7 +136,7 @@ struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
     { 4, 2, 1024, 8}, { 4, 6, 1024, 5},
     { 8, 2, 1024, 5}, { 8, 6,  512, 3},
-    {16, 2,  512, 3}, {16, 6,  256, 1},
+    {16, 2,  512, 3},
     {32, 2,  256, 1},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);

@@ -1,0 +1,1612 @@
+// The host side of libdvm: program builder, bytecode encoder, stacker, validator, disassembler.
+//
+// Everything in this file runs on the CPU and makes no HIP call.  dvm_encode does, in order
+// (Section 4.2 of the paper unless noted):
+//   1. shape inference with broadcasting, dominant shape S_d ("Shape tiling", first step);
+//   2. pattern fusion check: all ops must share one iteration space so that they become one
+//      meta-kernel whose intermediates stay in registers (Section 5.1);
+//   3. collapsing of the iteration space to rows x columns and per-tensor strides (the worked
+//      example tiles the flattened 32768 elements of a [32,1024] tensor);
+//   4. linearisation of the op DAG into accumulator-machine code with liveness-driven tile
+//      register allocation (Algorithm 1's n_max: the peak number of live tiles);
+//   5. the tile plan: interpreter variant K (T_max = register budget / n_max), lanes per row,
+//      rows or columns per tile chosen by the cost model ceil(#tiles/N) * (tile + c);
+//   6. emission of header + body, every unused bit zero.
+// No heap allocation happens in dvm_encode: all scratch lives on the stack.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/dvm.h"
+#include "dvm_bytecode.h"
+#include "dvm_internal.h"
+
+using namespace dvmbc;
+
+// ------------------------------------------------------------------------------------------------
+// errors
+// ------------------------------------------------------------------------------------------------
+namespace {
+thread_local char t_detail[256] = "";
+}
+
+extern "C" int dvm_set_error(int status, const char *detail) {
+    if (detail) {
+        strncpy(t_detail, detail, sizeof(t_detail) - 1);
+        t_detail[sizeof(t_detail) - 1] = 0;
+    } else {
+        t_detail[0] = 0;
+    }
+    return status;
+}
+extern "C" const char *dvm_last_error_detail(void) { return t_detail; }
+
+extern "C" const char *dvm_strerror(int status) {
+    switch (status) {
+        case DVM_OK: return "ok";
+        case DVM_E_ARGS: return "bad argument";
+        case DVM_E_SHAPE: return "shapes do not broadcast";
+        case DVM_E_RANK: return "rank not supported";
+        case DVM_E_DTYPE: return "unknown dtype";
+        case DVM_E_UNSUPPORTED: return "program not supported by the VM";
+        case DVM_E_BUFSZ: return "buffer too small";
+        case DVM_E_BADCODE: return "malformed bytecode";
+        case DVM_E_HIP: return "HIP error";
+        case DVM_E_ALIGN: return "tensor pointer misaligned";
+        case DVM_E_LIMIT: return "program exceeds a size limit";
+        case DVM_E_STATE: return "wrong program state";
+        default: return "unknown status";
+    }
+}
+
+extern "C" int dvm_shape_contiguous(dvm_shape *s, int rank, const int64_t *dims) {
+    if (!s || rank < 0 || rank > DVM_MAX_RANK || (rank > 0 && !dims)) return dvm_set_error(DVM_E_ARGS, "dvm_shape_contiguous");
+    memset(s, 0, sizeof(*s));
+    s->rank = rank;
+    int64_t st = 1;
+    for (int i = rank - 1; i >= 0; --i) {
+        if (dims[i] < 0) return dvm_set_error(DVM_E_SHAPE, "negative dimension");
+        s->dim[i] = dims[i];
+        s->stride[i] = st;
+        st *= dims[i] > 0 ? dims[i] : 1;
+    }
+    return DVM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// context
+// ------------------------------------------------------------------------------------------------
+struct dvm_ctx {
+    int device;
+    int n_cu;
+    int overhead;   // per-tile overhead of the cost model, in elements
+};
+
+extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
+    if (!out) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_create: null out");
+    dvm_ctx *c = new (std::nothrow) dvm_ctx;
+    if (!c) return dvm_set_error(DVM_E_LIMIT, "out of memory");
+    c->device = hip_device;
+    c->n_cu = 256;          // MI355X
+    c->overhead = 512;
+    if (hip_device >= 0) {
+        int n = 0;
+        int st = dvm_ctx_query_device(hip_device, &n);
+        if (st != DVM_OK) {
+            delete c;
+            return dvm_set_error(st, "dvm_ctx_create: device query failed");
+        }
+        if (n > 0) c->n_cu = n;
+    } else if (hip_device != -1) {
+        delete c;
+        return dvm_set_error(DVM_E_ARGS, "dvm_ctx_create: device must be >= 0 or -1");
+    }
+    *out = c;
+    return DVM_OK;
+}
+extern "C" void dvm_ctx_destroy(dvm_ctx *c) { delete c; }
+extern "C" int dvm_ctx_device(const dvm_ctx *c) { return c ? c->device : -1; }
+extern "C" int dvm_ctx_set_planner(dvm_ctx *c, int n_cu, int overhead) {
+    if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
+    if (n_cu > 0) c->n_cu = n_cu;
+    if (overhead > 0) c->overhead = overhead;
+    return DVM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// program builder and front end (decomposition into basic ops)
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+enum NodeKind : uint8_t { N_IN = 0, N_UN, N_BIN, N_BINI, N_SEL, N_RED, N_DEAD };
+enum ImmKind : uint8_t { IMM_LIT = 0, IMM_INV_H = 1 };   // literal, or 1 / (row length of operand a)
+
+constexpr int MAX_NODES = 160;
+constexpr int MAX_VALUES = DVM_MAX_OPS + DVM_MAX_TENSORS;
+
+struct Node {
+    uint8_t kind, op, immkind, pad;
+    int16_t a, b, c;
+    int16_t input;       // for N_IN: input index
+    float imm;
+};
+
+struct UserOp { int opcode; int args[3]; int n_args; double imm[2]; int n_imm; };
+
+}  // namespace
+
+struct dvm_prog {
+    bool finished;
+    int n_in, n_out, n_values, n_nodes;
+    int in_dtype[DVM_MAX_TENSORS];
+    int out_value[DVM_MAX_TENSORS], out_dtype[DVM_MAX_TENSORS];
+    int out_node[DVM_MAX_TENSORS];
+    // values in declaration order: inputs and user ops
+    bool value_is_input[MAX_VALUES];
+    int value_input_index[MAX_VALUES];
+    UserOp value_op[MAX_VALUES];
+    int value_node[MAX_VALUES];
+    Node nodes[MAX_NODES];
+};
+
+extern "C" int dvm_prog_create(dvm_prog **out) {
+    if (!out) return dvm_set_error(DVM_E_ARGS, "dvm_prog_create: null out");
+    dvm_prog *p = new (std::nothrow) dvm_prog;
+    if (!p) return dvm_set_error(DVM_E_LIMIT, "out of memory");
+    memset(p, 0, sizeof(*p));
+    *out = p;
+    return DVM_OK;
+}
+extern "C" void dvm_prog_destroy(dvm_prog *p) { delete p; }
+extern "C" int dvm_prog_num_inputs(const dvm_prog *p) { return p ? p->n_in : 0; }
+extern "C" int dvm_prog_num_outputs(const dvm_prog *p) { return p ? p->n_out : 0; }
+
+extern "C" int dvm_prog_input(dvm_prog *p, int dtype, int *value_id) {
+    if (!p || !value_id) return dvm_set_error(DVM_E_ARGS, "dvm_prog_input: null argument");
+    if (p->finished) return dvm_set_error(DVM_E_STATE, "program already finished");
+    if (dtype != DVM_F32 && dtype != DVM_BF16) return dvm_set_error(DVM_E_DTYPE, "dvm_prog_input: dtype");
+    if (p->n_in >= DVM_MAX_TENSORS - 1 || p->n_values >= MAX_VALUES) return dvm_set_error(DVM_E_LIMIT, "too many inputs");
+    const int v = p->n_values++;
+    p->value_is_input[v] = true;
+    p->value_input_index[v] = p->n_in;
+    p->in_dtype[p->n_in++] = dtype;
+    *value_id = v;
+    return DVM_OK;
+}
+
+static int op_arity(int opcode, int *n_imm) {
+    *n_imm = 0;
+    if (opcode >= DVM_OP_COPY && opcode <= DVM_OP_SILU) return 1;
+    if (opcode == DVM_OP_CAST) { *n_imm = 1; return 1; }
+    if (opcode == DVM_OP_ADDS || opcode == DVM_OP_MULS) { *n_imm = 1; return 1; }
+    if (opcode >= DVM_OP_ADD && opcode <= DVM_OP_CMP_GE) return 2;
+    if (opcode == DVM_OP_SELECT) return 3;
+    if (opcode >= DVM_OP_SUM && opcode <= DVM_OP_MEANSQ) return 1;
+    if (opcode == DVM_OP_SOFTMAX) return 1;
+    if (opcode == DVM_OP_RMSNORM) { *n_imm = 1; return 2; }
+    if (opcode == DVM_OP_LAYERNORM) { *n_imm = 1; return 3; }
+    return -1;
+}
+
+extern "C" int dvm_prog_op(dvm_prog *p, int opcode, const int *arg_ids, int n_args, const double *imm, int n_imm,
+                           int *value_id) {
+    if (!p || !value_id || (n_args > 0 && !arg_ids)) return dvm_set_error(DVM_E_ARGS, "dvm_prog_op: null argument");
+    if (p->finished) return dvm_set_error(DVM_E_STATE, "program already finished");
+    int want_imm = 0;
+    const int ar = op_arity(opcode, &want_imm);
+    if (ar < 0) return dvm_set_error(DVM_E_ARGS, "dvm_prog_op: unknown opcode");
+    if (n_args != ar) return dvm_set_error(DVM_E_ARGS, "dvm_prog_op: wrong number of arguments");
+    if (n_imm < want_imm || (want_imm > 0 && !imm)) return dvm_set_error(DVM_E_ARGS, "dvm_prog_op: missing immediate");
+    if (p->n_values >= MAX_VALUES) return dvm_set_error(DVM_E_LIMIT, "too many ops");
+    const int v = p->n_values;
+    UserOp &u = p->value_op[v];
+    memset(&u, 0, sizeof(u));
+    u.opcode = opcode;
+    u.n_args = n_args;
+    for (int i = 0; i < n_args; ++i) {
+        if (arg_ids[i] < 0 || arg_ids[i] >= v) return dvm_set_error(DVM_E_ARGS, "dvm_prog_op: argument is not an earlier value");
+        u.args[i] = arg_ids[i];
+    }
+    u.n_imm = want_imm;
+    for (int i = 0; i < want_imm; ++i) u.imm[i] = imm[i];
+    p->value_is_input[v] = false;
+    p->n_values++;
+    *value_id = v;
+    return DVM_OK;
+}
+
+extern "C" int dvm_prog_output(dvm_prog *p, int value_id, int dtype) {
+    if (!p) return dvm_set_error(DVM_E_ARGS, "dvm_prog_output: null program");
+    if (p->finished) return dvm_set_error(DVM_E_STATE, "program already finished");
+    if (dtype != DVM_F32 && dtype != DVM_BF16) return dvm_set_error(DVM_E_DTYPE, "dvm_prog_output: dtype");
+    if (value_id < 0 || value_id >= p->n_values) return dvm_set_error(DVM_E_ARGS, "dvm_prog_output: bad value id");
+    if (p->n_in + p->n_out >= DVM_MAX_TENSORS) return dvm_set_error(DVM_E_LIMIT, "too many tensors");
+    p->out_value[p->n_out] = value_id;
+    p->out_dtype[p->n_out] = dtype;
+    p->n_out++;
+    return DVM_OK;
+}
+
+namespace {
+
+struct Lower {
+    dvm_prog *p;
+    bool overflow;
+    int add(uint8_t kind, uint8_t op, int a, int b = -1, int c = -1, float imm = 0.0f, uint8_t immkind = IMM_LIT) {
+        if (p->n_nodes >= MAX_NODES) { overflow = true; return 0; }
+        Node &n = p->nodes[p->n_nodes];
+        memset(&n, 0, sizeof(n));
+        n.kind = kind; n.op = op; n.immkind = immkind;
+        n.a = (int16_t)a; n.b = (int16_t)b; n.c = (int16_t)c; n.input = -1; n.imm = imm;
+        return p->n_nodes++;
+    }
+    int un(uint32_t u, int a) { return add(N_UN, (uint8_t)u, a); }
+    int bin(uint32_t b, int x, int y) { return add(N_BIN, (uint8_t)b, x, y); }
+    int bini(uint32_t b, int x, float imm) { return add(N_BINI, (uint8_t)b, x, -1, -1, imm); }
+    int inv_h(int x) { return add(N_BINI, (uint8_t)B_MUL, x, -1, -1, 0.0f, IMM_INV_H); }   // x * (1/H)
+    int red(uint32_t r, int a) { return add(N_RED, (uint8_t)r, a); }
+};
+
+}  // namespace
+
+extern "C" int dvm_prog_finish(dvm_prog *p) {
+    if (!p) return dvm_set_error(DVM_E_ARGS, "dvm_prog_finish: null program");
+    if (p->finished) return dvm_set_error(DVM_E_STATE, "program already finished");
+    if (p->n_out == 0) return dvm_set_error(DVM_E_ARGS, "program has no output");
+    Lower L{p, false};
+    p->n_nodes = 0;
+    for (int v = 0; v < p->n_values; ++v) {
+        if (p->value_is_input[v]) {
+            int n = L.add(N_IN, 0, -1);
+            p->nodes[n].input = (int16_t)p->value_input_index[v];
+            p->value_node[v] = n;
+            continue;
+        }
+        const UserOp &u = p->value_op[v];
+        const int a = p->value_node[u.args[0]];
+        const int b = u.n_args > 1 ? p->value_node[u.args[1]] : -1;
+        const int c = u.n_args > 2 ? p->value_node[u.args[2]] : -1;
+        int r = -1;
+        switch (u.opcode) {
+            case DVM_OP_COPY: r = a; break;
+            case DVM_OP_SQRT: r = L.un(U_SQRT, a); break;
+            case DVM_OP_ABS: r = L.un(U_ABS, a); break;
+            case DVM_OP_LOG: r = L.un(U_LOG, a); break;
+            case DVM_OP_EXP: r = L.un(U_EXP, a); break;
+            case DVM_OP_ROUND: r = L.un(U_ROUND, a); break;
+            case DVM_OP_FLOOR: r = L.un(U_FLOOR, a); break;
+            case DVM_OP_ISFINITE: r = L.un(U_ISFINITE, a); break;
+            case DVM_OP_NEG: r = L.un(U_NEG, a); break;
+            case DVM_OP_RSQRT: r = L.un(U_RSQRT, a); break;
+            case DVM_OP_RCP: r = L.un(U_RCP, a); break;
+            case DVM_OP_TANH: r = L.un(U_TANH, a); break;
+            case DVM_OP_ERF: r = L.un(U_ERF, a); break;
+            case DVM_OP_SIGMOID: r = L.un(U_SIGMOID, a); break;
+            case DVM_OP_SQUARE: r = L.un(U_SQUARE, a); break;
+            case DVM_OP_GELU_TANH: r = L.un(U_GELU_TANH, a); break;
+            case DVM_OP_GELU_ERF: r = L.un(U_GELU_ERF, a); break;
+            case DVM_OP_SILU: r = L.un(U_SILU, a); break;
+            case DVM_OP_CAST:
+                if ((int)u.imm[0] == DVM_BF16) r = L.un(U_CAST_BF16, a);
+                else if ((int)u.imm[0] == DVM_F32) r = a;
+                else return dvm_set_error(DVM_E_DTYPE, "cast: unknown target dtype");
+                break;
+            case DVM_OP_ADDS: r = L.bini(B_ADD, a, (float)u.imm[0]); break;
+            case DVM_OP_MULS: r = L.bini(B_MUL, a, (float)u.imm[0]); break;
+            case DVM_OP_ADD: r = L.bin(B_ADD, a, b); break;
+            case DVM_OP_SUB: r = L.bin(B_SUB, a, b); break;
+            case DVM_OP_MUL: r = L.bin(B_MUL, a, b); break;
+            case DVM_OP_DIV: r = L.bin(B_DIV, a, b); break;
+            case DVM_OP_MIN: r = L.bin(B_MIN, a, b); break;
+            case DVM_OP_MAX: r = L.bin(B_MAX, a, b); break;
+            case DVM_OP_POW: r = L.bin(B_POW, a, b); break;
+            case DVM_OP_CMP_EQ: r = L.bin(B_EQ, a, b); break;
+            case DVM_OP_CMP_NE: r = L.bin(B_NE, a, b); break;
+            case DVM_OP_CMP_LT: r = L.bin(B_LT, a, b); break;
+            case DVM_OP_CMP_LE: r = L.bin(B_LE, a, b); break;
+            case DVM_OP_CMP_GT: r = L.bin(B_GT, a, b); break;
+            case DVM_OP_CMP_GE: r = L.bin(B_GE, a, b); break;
+            case DVM_OP_SELECT: r = L.add(N_SEL, 0, a, b, c); break;
+            case DVM_OP_SUM: r = L.red(R_SUM, a); break;
+            case DVM_OP_RMAX: r = L.red(R_MAX, a); break;
+            case DVM_OP_RMIN: r = L.red(R_MIN, a); break;
+            case DVM_OP_MEAN: r = L.inv_h(L.red(R_SUM, a)); p->nodes[r].b = (int16_t)a; break;
+            case DVM_OP_MEANSQ: r = L.inv_h(L.red(R_SUMSQ, a)); p->nodes[r].b = (int16_t)a; break;
+            case DVM_OP_SOFTMAX: {       // exp(z - max z) / sum exp(z - max z)
+                int m = L.red(R_MAX, a);
+                int d = L.bin(B_SUB, a, m);
+                int e = L.un(U_EXP, d);
+                int s = L.red(R_SUM, e);
+                r = L.bin(B_DIV, e, s);
+                break;
+            }
+            case DVM_OP_RMSNORM: {       // x * rsqrt(mean(x^2) + eps) * w
+                int ms = L.inv_h(L.red(R_SUMSQ, a));
+                p->nodes[ms].b = (int16_t)a;
+                int rs = L.un(U_RSQRT, L.bini(B_ADD, ms, (float)u.imm[0]));
+                r = L.bin(B_MUL, L.bin(B_MUL, a, rs), b);
+                break;
+            }
+            case DVM_OP_LAYERNORM: {     // (h - mu) * rsqrt(mean((h - mu)^2) + eps) * gamma + beta
+                int mu = L.inv_h(L.red(R_SUM, a));
+                p->nodes[mu].b = (int16_t)a;
+                int d = L.bin(B_SUB, a, mu);
+                int var = L.inv_h(L.red(R_SUMSQ, d));
+                p->nodes[var].b = (int16_t)d;
+                int rs = L.un(U_RSQRT, L.bini(B_ADD, var, (float)u.imm[0]));
+                r = L.bin(B_ADD, L.bin(B_MUL, L.bin(B_MUL, d, rs), b), c);
+                break;
+            }
+            default: return dvm_set_error(DVM_E_ARGS, "dvm_prog_finish: unknown opcode");
+        }
+        if (L.overflow) return dvm_set_error(DVM_E_LIMIT, "program too long after decomposition");
+        p->value_node[v] = r;
+    }
+    for (int i = 0; i < p->n_out; ++i) p->out_node[i] = p->value_node[p->out_value[i]];
+
+    // peephole: sum(square(x)) or sum(x * x), the square used nowhere else -> one sum-of-squares
+    int uses[MAX_NODES];
+    memset(uses, 0, sizeof(uses));
+    for (int n = 0; n < p->n_nodes; ++n) {
+        const Node &nd = p->nodes[n];
+        if (nd.kind == N_IN) continue;
+        if (nd.a >= 0) uses[nd.a]++;
+        if ((nd.kind == N_BIN || nd.kind == N_SEL) && nd.b >= 0) uses[nd.b]++;
+        if (nd.kind == N_SEL && nd.c >= 0) uses[nd.c]++;
+    }
+    for (int i = 0; i < p->n_out; ++i) uses[p->out_node[i]]++;
+    for (int n = 0; n < p->n_nodes; ++n) {
+        Node &nd = p->nodes[n];
+        if (nd.kind != N_RED || nd.op != R_SUM) continue;
+        Node &sq = p->nodes[nd.a];
+        const bool is_sq = (sq.kind == N_UN && sq.op == U_SQUARE) || (sq.kind == N_BIN && sq.op == B_MUL && sq.a == sq.b);
+        if (is_sq && uses[nd.a] == 1) {
+            nd.op = R_SUMSQ;
+            nd.a = sq.a;
+            sq.kind = N_DEAD;
+        }
+    }
+    p->finished = true;
+    return DVM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// small integer helpers
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline uint32_t pow2ceil(uint32_t x) {
+    uint32_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+// multiplier and shifts that divide any 32-bit unsigned number by d (1 <= d < 2^31):
+// l = ceil(log2 d), m = floor(2^32 (2^l - d) / d) + 1, q = (t + ((n - t) >> sh1)) >> sh2 with
+// t = mulhi(m, n), sh1 = min(l, 1), sh2 = max(l - 1, 0).
+void magic_u32(uint32_t d, uint32_t *m, uint32_t *sh) {
+    uint32_t l = 0;
+    while ((1ull << l) < d) ++l;
+    const uint64_t mm = ((((uint64_t)1 << l) - d) << 32) / d + 1;
+    *m = (uint32_t)mm;
+    const uint32_t sh1 = l < 1 ? l : 1, sh2 = l > 0 ? l - 1 : 0;
+    *sh = sh1 | (sh2 << 8);
+}
+
+// The tile-size rule on a one-dimensional space of `total` elements (Section 4.2): minimise
+// ceil(ceil(total/t)/n) * (t + c) over t in 1..min(t_max,total); ties go to the larger tile.
+// For a given number of rounds w the cheapest tile is the smallest one that needs no more than
+// w rounds, t_w = ceil(total / (w n)); rounds are tried upwards until total/n + w c, a lower bound
+// of any cost with w rounds, reaches the best cost found.
+int64_t min_cost_tile(int64_t total, int64_t n, int64_t t_max, int64_t c) {
+    const int64_t t0 = t_max < total ? t_max : total;
+    int64_t w = cdiv(cdiv(total, t0), n);
+    int64_t best_t = t0, best_c = w * (t0 + c);
+    for (;; ++w) {
+        const int64_t t = cdiv(total, w * n);
+        const int64_t wa = cdiv(cdiv(total, t), n);
+        const int64_t cost = wa * (t + c);
+        if (cost < best_c || (cost == best_c && t > best_t)) { best_c = cost; best_t = t; }
+        if (t == 1) break;
+        if (total / n + (w + 1) * c >= best_c && c > 0) break;
+    }
+    return best_t;
+}
+
+int64_t align_up_capped(int64_t t, int64_t align, int64_t t_max) {
+    const int64_t up = cdiv(t, align) * align;
+    if (up <= t_max) return up;
+    const int64_t down = (t_max / align) * align;
+    return down >= align ? down : t;
+}
+
+}  // namespace
+
+extern "C" int dvm_plan(int64_t total, int n_cores, int64_t t_max, int align, int overhead, int64_t *t_min_cost,
+                        int64_t *t_aligned, int64_t *n_tiles) {
+    if (total < 1 || n_cores < 1 || t_max < 1 || align < 1 || overhead < 0) return dvm_set_error(DVM_E_ARGS, "dvm_plan");
+    const int64_t t = min_cost_tile(total, n_cores, t_max, overhead);
+    const int64_t ta = align_up_capped(t, align, t_max);
+    if (t_min_cost) *t_min_cost = t;
+    if (t_aligned) *t_aligned = ta;
+    if (n_tiles) *n_tiles = cdiv(total, ta);
+    return DVM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// the encoder
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int NR_MAX = 6;
+constexpr int MAX_AI = 4 * MAX_NODES;
+
+struct Access {             // one tensor of the launch as the kernel addresses it
+    int dtype;
+    bool is_output;
+    bool rows;              // one value per row (last-axis extent 1)
+    int align_log2;
+    int64_t min_bytes;
+    int64_t ostride[DVM_MAX_RANK];   // per original axis, right aligned, 0 where broadcast
+    int64_t s[4];           // collapsed: s[0] inner (0 or 1), s[1..3] outer groups
+};
+
+struct AI {                 // abstract instruction before emission
+    uint8_t op, a, b, c;
+    uint8_t kind, srck;
+    int16_t tensor;
+    float imm;
+};
+
+struct Enc {
+    const dvm_prog *p;
+    int R;                              // rank of the dominant shape
+    int64_t shape[MAX_NODES][DVM_MAX_RANK];
+    int64_t dom[DVM_MAX_RANK];
+    bool rows_class[MAX_NODES];
+    bool row_axis;                      // the dominant shape's last axis has extent > 1
+    Access acc[DVM_MAX_TENSORS];
+    int n_acc;
+    // collapsed space
+    int64_t D0, nrows, Dg[4];
+    int n_groups;
+    bool has_red;
+    // linearisation
+    AI ai[MAX_AI];
+    int n_ai;
+    int uses[MAX_NODES];
+    int reg_of[MAX_NODES], sreg_of[MAX_NODES];
+    int regs[NR_MAX], sregs[NS];
+    int in_acc;
+    int nr_used, ns_used;
+    const char *err;
+    int err_code;
+
+    bool fail(int code, const char *msg) { if (!err) { err = msg; err_code = code; } return false; }
+
+    void emit(uint8_t op, uint8_t a = 0, uint8_t b = 0, int tensor = -1, float imm = 0.0f, uint8_t kind = 0,
+              uint8_t srck = 0, uint8_t c = 0) {
+        if (n_ai >= MAX_AI) { fail(DVM_E_LIMIT, "too many instructions"); return; }
+        AI &x = ai[n_ai++];
+        x.op = op; x.a = a; x.b = b; x.c = c; x.kind = kind; x.srck = srck; x.tensor = (int16_t)tensor; x.imm = imm;
+    }
+    int alloc_reg(int node) {
+        for (int i = 0; i < NR_MAX; ++i)
+            if (regs[i] < 0) {
+                regs[i] = node;
+                reg_of[node] = i;
+                if (i + 1 > nr_used) nr_used = i + 1;
+                return i;
+            }
+        fail(DVM_E_UNSUPPORTED, "program needs more than 6 live tile registers");
+        return 0;
+    }
+    int alloc_sreg(int node) {
+        for (int i = 0; i < NS; ++i)
+            if (sregs[i] < 0) {
+                sregs[i] = node;
+                if (node >= 0) sreg_of[node] = i;
+                if (i + 1 > ns_used) ns_used = i + 1;
+                return i;
+            }
+        fail(DVM_E_UNSUPPORTED, "program needs more than 4 live row-scalar registers");
+        return 0;
+    }
+    void release(int node) {            // called when the last use of `node` is gone
+        if (reg_of[node] >= 0) { regs[reg_of[node]] = -1; reg_of[node] = -1; }
+        if (sreg_of[node] >= 0) { sregs[sreg_of[node]] = -1; sreg_of[node] = -1; }
+        if (in_acc == node) in_acc = -1;
+    }
+    void use(int node) {
+        if (--uses[node] <= 0) release(node);
+    }
+    bool is_input(int n) const { return p->nodes[n].kind == N_IN; }
+    int tensor_of_input(int n) const { return p->nodes[n].input; }
+
+    // keep the accumulator's value alive if something still needs it
+    void save_acc_if_live() {
+        const int v = in_acc;
+        if (v < 0 || uses[v] <= 0 || reg_of[v] >= 0) return;
+        if (is_input(v)) return;        // an input tile can be loaded again
+        const int r = alloc_reg(v);
+        emit(I_MOVRA, (uint8_t)r);
+    }
+    void load_rows_input(int n) {       // a [.., 1] input: one value per row into an S register
+        if (sreg_of[n] >= 0) return;
+        const int s = alloc_sreg(n);
+        emit(I_LOADS, (uint8_t)s, 0, tensor_of_input(n));
+    }
+    bool to_acc(int n) {
+        if (in_acc == n) return true;
+        save_acc_if_live();
+        if (reg_of[n] >= 0) emit(I_MOVAR, (uint8_t)reg_of[n]);
+        else if (is_input(n)) emit(I_LOAD, (uint8_t)SRC_ACC, (uint8_t)B_NONE, tensor_of_input(n));
+        else return fail(DVM_E_UNSUPPORTED, "internal: value lost during linearisation");
+        in_acc = n;
+        return true;
+    }
+    // the accumulator holds `n` and is about to be overwritten: keep a copy if n is needed later
+    void preserve(int n, int pending_uses) {
+        if (uses[n] - pending_uses <= 0 || reg_of[n] >= 0) return;
+        if (is_input(n)) {
+            int free_regs = 0;
+            for (int i = 0; i < NR_MAX; ++i) free_regs += regs[i] < 0;
+            if (free_regs == 0) return;   // reload it later instead
+        }
+        const int r = alloc_reg(n);
+        emit(I_MOVRA, (uint8_t)r);
+    }
+    int to_reg(int n) {                 // make sure a tile value sits in some R register
+        if (reg_of[n] >= 0) return reg_of[n];
+        if (in_acc == n) {
+            const int r = alloc_reg(n);
+            emit(I_MOVRA, (uint8_t)r);
+            return r;
+        }
+        if (is_input(n)) {
+            const int r = alloc_reg(n);
+            emit(I_LOAD, (uint8_t)r, (uint8_t)B_NONE, tensor_of_input(n));
+            return r;
+        }
+        fail(DVM_E_UNSUPPORTED, "internal: value lost during linearisation");
+        return 0;
+    }
+    int sreg(int n) {
+        if (sreg_of[n] < 0 && is_input(n)) load_rows_input(n);
+        if (sreg_of[n] < 0) { fail(DVM_E_UNSUPPORTED, "internal: row value lost"); return 0; }
+        return sreg_of[n];
+    }
+};
+
+uint32_t reversed(uint32_t b) {
+    switch (b) {
+        case B_SUB: return B_RSUB;
+        case B_DIV: return B_RDIV;
+        case B_POW: return B_RPOW;
+        case B_LT: return B_GT;
+        case B_LE: return B_GE;
+        case B_GT: return B_LT;
+        case B_GE: return B_LE;
+        default: return b;      // commutative
+    }
+}
+
+float f32_bits(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+uint32_t bits_f32(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+
+}  // namespace
+
+extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_shape *in_shapes, int n_in,
+                          const dvm_shape *out_layout, void *bytecode, size_t cap, size_t *len, dvm_shape *out_shapes) {
+    if (!ctx || !prog || !len || (n_in > 0 && !in_shapes)) return dvm_set_error(DVM_E_ARGS, "dvm_encode: null argument");
+    if (!prog->finished) return dvm_set_error(DVM_E_STATE, "dvm_encode: program not finished");
+    if (n_in != prog->n_in) return dvm_set_error(DVM_E_ARGS, "dvm_encode: number of input shapes");
+    Enc E;
+    E.p = prog;
+    E.err = nullptr;
+    E.err_code = 0;
+    const int NN = prog->n_nodes;
+
+    // ---- 1. shapes ---------------------------------------------------------------------------
+    int R = 1;
+    for (int i = 0; i < n_in; ++i) {
+        if (in_shapes[i].rank < 0 || in_shapes[i].rank > DVM_MAX_RANK) return dvm_set_error(DVM_E_RANK, "input rank");
+        if (in_shapes[i].rank > R) R = in_shapes[i].rank;
+    }
+    E.R = R;
+    for (int n = 0; n < NN; ++n) {
+        const Node &nd = prog->nodes[n];
+        int64_t *sh = E.shape[n];
+        if (nd.kind == N_DEAD) continue;
+        if (nd.kind == N_IN) {
+            const dvm_shape &s = in_shapes[nd.input];
+            for (int k = 0; k < R; ++k) sh[k] = 1;
+            for (int k = 0; k < s.rank; ++k) {
+                if (s.dim[k] < 0) return dvm_set_error(DVM_E_SHAPE, "negative dimension");
+                sh[R - s.rank + k] = s.dim[k];
+            }
+            continue;
+        }
+        const int args[3] = {nd.a, (nd.kind == N_BIN || nd.kind == N_SEL) ? nd.b : -1, nd.kind == N_SEL ? nd.c : -1};
+        for (int k = 0; k < R; ++k) sh[k] = 1;
+        for (int j = 0; j < 3; ++j) {
+            if (args[j] < 0) continue;
+            const int64_t *as = E.shape[args[j]];
+            for (int k = 0; k < R; ++k) {
+                if (as[k] == sh[k] || as[k] == 1) continue;
+                if (sh[k] == 1) sh[k] = as[k];
+                else return dvm_set_error(DVM_E_SHAPE, "operands do not broadcast together");
+            }
+        }
+        if (nd.kind == N_RED) sh[R - 1] = 1;
+    }
+    for (int k = 0; k < R; ++k) E.dom[k] = 1;
+    for (int n = 0; n < NN; ++n) {
+        if (prog->nodes[n].kind == N_DEAD) continue;
+        for (int k = 0; k < R; ++k) {
+            const int64_t d = E.shape[n][k];
+            if (d == E.dom[k] || d == 1) continue;
+            if (E.dom[k] == 1) E.dom[k] = d;
+            else return dvm_set_error(DVM_E_UNSUPPORTED, "ops have different iteration spaces: cannot fuse into one meta-kernel");
+        }
+    }
+    if (out_shapes) {
+        for (int i = 0; i < prog->n_out; ++i) {
+            dvm_shape_contiguous(&out_shapes[i], R, E.shape[prog->out_node[i]]);
+        }
+    }
+    int64_t total = 1;
+    for (int k = 0; k < R; ++k) total *= E.dom[k];
+
+    // ---- 2. classes ---------------------------------------------------------------------------
+    E.row_axis = E.dom[R - 1] > 1;
+    E.has_red = false;
+    for (int n = 0; n < NN; ++n) {
+        const Node &nd = prog->nodes[n];
+        if (nd.kind == N_DEAD) continue;
+        E.rows_class[n] = E.row_axis && E.shape[n][R - 1] == 1;
+        if (nd.kind == N_RED && !E.rows_class[nd.a] && E.row_axis) E.has_red = true;
+    }
+
+    // ---- 3. tensor accesses, collapse -------------------------------------------------------------
+    E.n_acc = prog->n_in + prog->n_out;
+    for (int t = 0; t < E.n_acc; ++t) {
+        Access &A = E.acc[t];
+        memset(&A, 0, sizeof(A));
+        const bool is_out = t >= prog->n_in;
+        const dvm_shape *s = nullptr;
+        dvm_shape tmp;
+        int node;
+        if (!is_out) {
+            s = &in_shapes[t];
+            A.dtype = prog->in_dtype[t];
+            node = -1;
+            for (int n = 0; n < NN; ++n)
+                if (prog->nodes[n].kind == N_IN && prog->nodes[n].input == t) node = n;
+        } else {
+            const int o = t - prog->n_in;
+            node = prog->out_node[o];
+            A.dtype = prog->out_dtype[o];
+            dvm_shape_contiguous(&tmp, R, E.shape[node]);
+            if (out_layout) {
+                if (out_layout[o].rank != R) return dvm_set_error(DVM_E_SHAPE, "output layout rank differs from the inferred rank");
+                for (int k = 0; k < R; ++k) {
+                    if (out_layout[o].dim[k] != tmp.dim[k]) return dvm_set_error(DVM_E_SHAPE, "output layout dims differ from the inferred shape");
+                    tmp.stride[k] = out_layout[o].stride[k];
+                }
+                tmp.align_bytes = out_layout[o].align_bytes;
+            }
+            s = &tmp;
+            // an output must cover the whole iteration space (except the row axis for row values)
+            for (int k = 0; k < R; ++k) {
+                const bool row_value = (k == R - 1) && E.rows_class[node];
+                if (E.shape[node][k] != E.dom[k] && !row_value)
+                    return dvm_set_error(DVM_E_UNSUPPORTED, "an output is smaller than the fused iteration space");
+            }
+        }
+        A.is_output = is_out;
+        const int es = A.dtype == DVM_F32 ? 4 : 2;
+        int al = s->align_bytes > 0 ? s->align_bytes : 16;
+        int lg = 0;
+        while ((2 << lg) <= al && lg < 8) ++lg;
+        if (lg > 4) lg = 4;
+        if ((1 << lg) < es) return dvm_set_error(DVM_E_ALIGN, "tensor alignment below its element size");
+        A.align_log2 = lg;
+        int64_t maxoff = 0;
+        bool empty = false;
+        for (int k = 0; k < R; ++k) A.ostride[k] = 0;
+        for (int k = 0; k < s->rank; ++k) {
+            const int ax = R - s->rank + k;
+            const int64_t d = s->dim[k], st = s->stride[k];
+            if (d == 0) empty = true;
+            if (d > 1) {
+                if (st < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "negative strides are not supported");
+                A.ostride[ax] = st;
+                maxoff += (d - 1) * st;
+            }
+        }
+        A.min_bytes = empty ? 0 : (maxoff + 1) * es;
+        A.rows = E.row_axis && (node >= 0 ? E.rows_class[node] : false);
+        if (E.row_axis && !A.rows && A.ostride[R - 1] == 0 && E.dom[R - 1] > 1) {
+            // the tensor has the full row extent in its shape; a zero stride there is an expanded view
+            if (E.shape[node][R - 1] > 1) return dvm_set_error(DVM_E_UNSUPPORTED, "zero stride on the last axis of a full tensor");
+        }
+    }
+
+    // group the axes of the dominant shape from the innermost outwards
+    int ax_list[DVM_MAX_RANK], n_ax = 0;
+    for (int k = R - 1; k >= 0; --k)
+        if (E.dom[k] > 1) ax_list[n_ax++] = k;
+    int grp_first[4], grp_last[4];      // innermost and outermost axis of each group
+    int64_t grp_ext[4];
+    int ng = 0;
+    for (int i = 0; i < n_ax; ++i) {
+        const int ax = ax_list[i];
+        bool merge = ng > 0;
+        if (merge && ng == 1 && E.row_axis && E.has_red) merge = false;     // rows stay whole under a reduction
+        if (merge) {
+            const int inner = grp_last[ng - 1];
+            for (int t = 0; t < E.n_acc && merge; ++t) {
+                const Access &A = E.acc[t];
+                if (A.ostride[ax] != A.ostride[inner] * E.dom[inner]) merge = false;
+            }
+        }
+        if (merge) {
+            grp_last[ng - 1] = ax;
+            grp_ext[ng - 1] *= E.dom[ax];
+        } else {
+            if (ng == 4) return dvm_set_error(DVM_E_RANK, "iteration space does not reduce to four dimensions");
+            grp_first[ng] = ax;
+            grp_last[ng] = ax;
+            grp_ext[ng] = E.dom[ax];
+            ++ng;
+        }
+    }
+    // if the row axis exists it must be group 0; otherwise group 0 is whatever is innermost
+    E.n_groups = ng;
+    const bool g0_is_row = ng > 0 && E.row_axis && grp_first[0] == R - 1;
+    E.D0 = ng > 0 ? grp_ext[0] : 1;
+    E.nrows = 1;
+    for (int g = 1; g < ng; ++g) E.nrows *= grp_ext[g];
+    for (int g = 0; g < 4; ++g) E.Dg[g] = g < ng ? grp_ext[g] : 1;
+    if (total == 0) { E.D0 = 0; E.nrows = 0; }
+    if (E.nrows >= (1ll << 31)) return dvm_set_error(DVM_E_LIMIT, "more than 2^31 rows");
+    bool any_bf16_full = false;
+    for (int t = 0; t < E.n_acc; ++t) {
+        Access &A = E.acc[t];
+        for (int g = 0; g < 4; ++g) A.s[g] = g < ng ? A.ostride[grp_first[g]] : 0;
+        if (ng > 0 && !A.rows && A.s[0] != 1 && A.s[0] != 0)
+            return dvm_set_error(DVM_E_UNSUPPORTED, "innermost stride of a tensor must be 1 (or 0 for a broadcast)");
+        if (ng > 0 && A.s[0] == 0 && !(A.rows && g0_is_row)) {
+            // broadcast along the innermost group without being a row value: only legal when the
+            // tensor is constant along that group, which the row-value path handles
+            A.rows = true;
+        }
+        if (!A.rows && A.dtype == DVM_BF16) any_bf16_full = true;
+    }
+    (void)g0_is_row;
+
+    // ---- 4. linearise ---------------------------------------------------------------------------
+    memset(E.uses, 0, sizeof(E.uses));
+    for (int n = 0; n < NN; ++n) {
+        const Node &nd = prog->nodes[n];
+        if (nd.kind == N_IN || nd.kind == N_DEAD) continue;
+        if (nd.a >= 0) E.uses[nd.a]++;
+        if ((nd.kind == N_BIN || nd.kind == N_SEL) && nd.b >= 0) E.uses[nd.b]++;
+        if (nd.kind == N_SEL && nd.c >= 0) E.uses[nd.c]++;
+    }
+    for (int i = 0; i < prog->n_out; ++i) E.uses[prog->out_node[i]]++;
+    for (int n = 0; n < NN; ++n) { E.reg_of[n] = -1; E.sreg_of[n] = -1; }
+    for (int i = 0; i < NR_MAX; ++i) E.regs[i] = -1;
+    for (int i = 0; i < NS; ++i) E.sregs[i] = -1;
+    E.in_acc = -1;
+    E.n_ai = 0;
+    E.nr_used = 0;
+    E.ns_used = 0;
+    // input tensors that are row values by layout (see above) make their nodes row values too
+    for (int n = 0; n < NN; ++n)
+        if (prog->nodes[n].kind == N_IN && E.acc[prog->nodes[n].input].rows) E.rows_class[n] = true;
+
+    auto store_outputs = [&](int n) {
+        for (int o = 0; o < prog->n_out; ++o) {
+            if (prog->out_node[o] != n) continue;
+            const int t = prog->n_in + o;
+            if (E.rows_class[n]) {
+                E.emit(I_STORES, (uint8_t)E.sreg(n), 0, t);
+            } else if (E.in_acc == n) {
+                E.emit(I_STORE, (uint8_t)SRC_ACC, 0, t);
+            } else if (E.reg_of[n] >= 0) {
+                E.emit(I_STORE, (uint8_t)E.reg_of[n], 0, t);
+            } else {
+                E.to_acc(n);
+                E.emit(I_STORE, (uint8_t)SRC_ACC, 0, t);
+            }
+            E.use(n);
+        }
+    };
+
+    for (int n = 0; n < NN && !E.err; ++n) {
+        const Node &nd = prog->nodes[n];
+        if (nd.kind == N_DEAD) continue;
+        if (nd.kind == N_IN) {
+            store_outputs(n);       // an input that is also an output: a plain copy
+            continue;
+        }
+        if (E.uses[n] == 0) {       // dead code: still consume the operands
+            if (nd.a >= 0) E.use(nd.a);
+            if ((nd.kind == N_BIN || nd.kind == N_SEL) && nd.b >= 0) E.use(nd.b);
+            if (nd.kind == N_SEL && nd.c >= 0) E.use(nd.c);
+            continue;
+        }
+        const bool rows = E.rows_class[n];
+        float imm = nd.imm;
+        if (nd.kind == N_BINI && nd.immkind == IMM_INV_H) {
+            const int64_t H = E.shape[nd.b][R - 1];
+            imm = (float)(1.0 / (double)(H > 0 ? H : 1));
+        }
+        switch (nd.kind) {
+            case N_UN:
+                if (rows) {
+                    const int sa = E.sreg(nd.a);
+                    E.use(nd.a);
+                    const int sd = E.alloc_sreg(n);
+                    E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, 0.0f, (uint8_t)(SOP_UNARY + nd.op), 0, 0);
+                } else {
+                    E.to_acc(nd.a);
+                    E.preserve(nd.a, 1);
+                    E.use(nd.a);
+                    E.emit(I_UN, 0, nd.op);
+                    E.in_acc = n;
+                }
+                break;
+            case N_BINI:
+                if (rows) {
+                    const int sa = E.sreg(nd.a);
+                    E.use(nd.a);
+                    const int sd = E.alloc_sreg(n);
+                    E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, imm, nd.op, 1, 0);
+                } else {
+                    E.to_acc(nd.a);
+                    E.preserve(nd.a, 1);
+                    E.use(nd.a);
+                    E.emit(I_BIN, (uint8_t)SRC_IMM, nd.op, -1, imm);
+                    E.in_acc = n;
+                }
+                break;
+            case N_BIN: {
+                int a = nd.a, b = nd.b;
+                uint32_t op = nd.op;
+                const bool ra = E.rows_class[a], rb = E.rows_class[b];
+                if (rows) {                         // both operands are row values
+                    const int sa = E.sreg(a), sb = E.sreg(b);
+                    E.use(a);
+                    E.use(b);
+                    const int sd = E.alloc_sreg(n);
+                    E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, 0.0f, (uint8_t)op, 0, (uint8_t)sb);
+                    break;
+                }
+                if (ra && !rb) {                    // row value on the left: swap and reverse
+                    int t = a; a = b; b = t;
+                    op = reversed(op);
+                } else if (!ra && !rb && E.in_acc == b && a != b) {
+                    int t = a; a = b; b = t;
+                    op = reversed(op);
+                }
+                // now `a` is a tile and goes through the accumulator
+                if (E.rows_class[b]) {
+                    int sb = E.sreg(b);
+                    E.to_acc(a);
+                    E.preserve(a, 1);
+                    E.use(a);
+                    if (op == B_DIV) {              // tile / row value = tile * (1 / row value)
+                        const int st = E.alloc_sreg(-1);
+                        E.emit(I_SOP, (uint8_t)st, (uint8_t)sb, -1, 0.0f, (uint8_t)(SOP_UNARY + U_RCP), 0, 0);
+                        E.emit(I_BIN, (uint8_t)(SRC_S0 + st), (uint8_t)B_MUL);
+                        E.sregs[st] = -1;
+                    } else {
+                        E.emit(I_BIN, (uint8_t)(SRC_S0 + sb), (uint8_t)op);
+                    }
+                    E.use(b);
+                } else if (a == b) {
+                    E.to_acc(a);
+                    E.preserve(a, 2);
+                    E.use(a);
+                    E.use(a);
+                    E.emit(I_BIN, (uint8_t)SRC_ACC, (uint8_t)op);
+                } else {
+                    E.to_acc(a);
+                    E.preserve(a, 1);
+                    E.use(a);
+                    if (E.reg_of[b] >= 0) {
+                        E.emit(I_BIN, (uint8_t)E.reg_of[b], (uint8_t)op);
+                    } else if (E.is_input(b)) {
+                        if (E.uses[b] == 1) {
+                            E.emit(I_LOAD, (uint8_t)SRC_ACC, (uint8_t)op, E.tensor_of_input(b));
+                        } else {
+                            const int r = E.to_reg(b);
+                            E.emit(I_BIN, (uint8_t)r, (uint8_t)op);
+                        }
+                    } else {
+                        E.fail(DVM_E_UNSUPPORTED, "internal: operand lost during linearisation");
+                    }
+                    E.use(b);
+                }
+                E.in_acc = n;
+                break;
+            }
+            case N_SEL: {
+                if (rows || E.rows_class[nd.a] || E.rows_class[nd.b] || E.rows_class[nd.c]) {
+                    E.fail(DVM_E_UNSUPPORTED, "select with row-value operands");
+                    break;
+                }
+                const int rb = E.to_reg(nd.b);
+                const int rc = E.to_reg(nd.c);
+                E.to_acc(nd.a);
+                E.preserve(nd.a, 1);
+                E.use(nd.a);
+                E.emit(I_SEL, (uint8_t)rb, (uint8_t)rc);
+                E.use(nd.b);
+                E.use(nd.c);
+                E.in_acc = n;
+                break;
+            }
+            case N_RED: {
+                if (E.rows_class[nd.a] || !E.row_axis) {
+                    // a row of one element: sum, max and min are the element, sum of squares its square
+                    if (E.row_axis) {
+                        const int sa = E.sreg(nd.a);
+                        E.use(nd.a);
+                        const int sd = E.alloc_sreg(n);
+                        if (nd.op == R_SUMSQ) E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, 0.0f, (uint8_t)(SOP_UNARY + U_SQUARE), 0, 0);
+                        else E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, 0.0f, (uint8_t)B_ADD, 1, 0);
+                    } else {
+                        E.to_acc(nd.a);
+                        E.preserve(nd.a, 1);
+                        E.use(nd.a);
+                        if (nd.op == R_SUMSQ) E.emit(I_UN, 0, (uint8_t)U_SQUARE);
+                        E.in_acc = n;
+                    }
+                    break;
+                }
+                E.to_acc(nd.a);
+                const int sd = E.alloc_sreg(n);
+                E.emit(I_RED, (uint8_t)sd, nd.op);
+                E.use(nd.a);
+                break;
+            }
+            default: E.fail(DVM_E_BADCODE, "internal: bad node"); break;
+        }
+        if (!E.err) store_outputs(n);
+    }
+    if (E.err) return dvm_set_error(E.err_code, E.err);
+
+    // ---- 5. tile plan ---------------------------------------------------------------------------
+    const uint32_t V = any_bf16_full ? 8 : 4;
+    const int need_nr = E.nr_used;
+    const int64_t Cr = cdiv(E.D0 > 0 ? E.D0 : 1, V);
+    int vi = -1;                    // chosen variant
+    uint32_t G = 1, RP = 1, nvec = 1, nct = 1, TC = 0;
+    auto find_variant = [&](int K) {
+        int best = -1;
+        for (int i = 0; i < N_VARIANTS; ++i)
+            if (VARIANTS[i].K == K && VARIANTS[i].NR >= need_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
+        return best;
+    };
+    auto slots_per_cu = [&](const Variant &v, uint32_t threads) {
+        const int waves_wg = (int)((threads + 63) / 64);
+        int s = v.waves_per_simd * 4 / waves_wg;
+        return s < 1 ? 1 : s;
+    };
+    const int64_t ovh = ctx->overhead;
+    bool column_mode = !E.has_red && E.D0 > 4096;
+    bool has_rows_output = false;
+    for (int t = prog->n_in; t < E.n_acc; ++t) has_rows_output |= E.acc[t].rows;
+    if (has_rows_output) column_mode = false;
+    if (!column_mode) {
+        const int ks[4] = {4, 8, 16, 32};
+        int pick = -1;
+        for (int i = 0; i < 4; ++i) {           // the largest K up to 16 that still spreads a row over >= 16 lanes
+            const int K = ks[i];
+            if ((uint32_t)K < V || K > 16) continue;
+            const int v = find_variant(K);
+            if (v < 0) continue;
+            const int64_t gneed = cdiv(Cr, K / V);
+            if (gneed > VARIANTS[v].max_threads) continue;
+            if (pick < 0 || gneed >= 16) pick = v;
+        }
+        if (pick < 0) {                         // long rows: more elements per lane
+            for (int i = 0; i < 4 && pick < 0; ++i) {
+                const int K = ks[i];
+                if ((uint32_t)K < V) continue;
+                const int v = find_variant(K);
+                if (v >= 0 && cdiv(Cr, K / V) <= VARIANTS[v].max_threads) pick = v;
+            }
+        }
+        if (pick < 0) {
+            if (E.has_red || has_rows_output) return dvm_set_error(DVM_E_UNSUPPORTED, "row too long for a register-resident reduction");
+            column_mode = true;
+        } else {
+            vi = pick;
+            const Variant &vr = VARIANTS[vi];
+            const int64_t gneed = cdiv(Cr, vr.K / V);
+            G = gneed <= 64 ? pow2ceil((uint32_t)gneed) : (uint32_t)(cdiv(gneed, 64) * 64);
+            nvec = (uint32_t)cdiv(Cr, G);
+            TC = G * nvec * V;
+            nct = 1;
+            // rows per tile by the cost model (Section 4.2): candidates keep the workgroup a
+            // whole number of waves and at most 256 threads (or one row if a row needs more)
+            const uint32_t step = G < 64 ? 64 / G : 1;
+            const uint32_t rp_max = G >= 256 ? 1 : 256 / G;
+            int64_t best_cost = -1;
+            RP = step;
+            for (uint32_t rp = step; rp <= (rp_max > step ? rp_max : step); rp += step) {
+                const uint32_t threads = rp * G;
+                if (threads > (uint32_t)vr.max_threads) break;
+                const int64_t N = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
+                const int64_t tiles = cdiv(E.nrows > 0 ? E.nrows : 1, rp);
+                const int64_t cost = cdiv(tiles, N) * ((int64_t)rp * (E.D0 > 0 ? E.D0 : 1) + ovh);
+                if (best_cost < 0 || cost <= best_cost) { best_cost = cost; RP = rp; }
+            }
+        }
+    }
+    if (column_mode) {
+        int v = find_variant(16);
+        if (v < 0) v = find_variant(8);
+        if (v < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
+        vi = v;
+        const Variant &vr = VARIANTS[vi];
+        G = 256;
+        RP = 1;
+        const int64_t t_max = (int64_t)G * vr.K;
+        const int64_t N = (int64_t)ctx->n_cu * slots_per_cu(vr, G);
+        // columns per tile by the cost model: try numbers of column tiles around whole rounds of N
+        const int64_t nct_min = cdiv(E.D0, t_max);
+        int64_t best_cost = -1, best_nct = nct_min;
+        auto consider = [&](int64_t k) {
+            if (k < nct_min) k = nct_min;
+            int64_t tc = cdiv(cdiv(E.D0, k), V) * V;
+            const int64_t tc_min = (int64_t)G * V;      // at least one chunk for every lane
+            if (tc < tc_min) tc = tc_min;
+            if (tc > t_max) return;
+            const int64_t kk = cdiv(E.D0, tc);
+            const int64_t cost = cdiv(E.nrows * kk, N) * (tc + ovh);
+            if (best_cost < 0 || cost < best_cost || (cost == best_cost && kk < best_nct)) { best_cost = cost; best_nct = kk; }
+        };
+        consider(nct_min);
+        const int64_t w0 = cdiv(E.nrows * nct_min, N);
+        for (int64_t w = w0; w < w0 + 8; ++w) consider((w * N) / E.nrows);
+        int64_t tc = cdiv(cdiv(E.D0, best_nct), V) * V;
+        if (tc < (int64_t)G * V) tc = (int64_t)G * V;
+        TC = (uint32_t)tc;
+        nct = (uint32_t)cdiv(E.D0, tc);
+        nvec = (uint32_t)cdiv(cdiv(tc, V), G);
+    }
+    const Variant &vr = VARIANTS[vi];
+    const uint32_t threads = G * RP;
+    const int64_t M64 = total == 0 ? 0 : cdiv(E.nrows, RP) * nct;
+    if (M64 >= (1ll << 31)) return dvm_set_error(DVM_E_LIMIT, "more than 2^31 tiles");
+    const int64_t Nslots = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
+    const uint32_t grid = (uint32_t)(M64 < Nslots ? M64 : Nslots);
+    const bool wgsync = G > 64;
+
+    // ---- 6. emit ---------------------------------------------------------------------------
+    // size first
+    size_t body_words = 0;
+    const bool view = ng > 2;       // more than one outer group: rows need the multi-stride form
+    for (int i = 0; i < E.n_ai; ++i) {
+        const AI &x = E.ai[i];
+        switch (x.op) {
+            case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
+            case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
+            case I_BIN: body_words += x.a == SRC_IMM ? 2 : 1; break;
+            case I_SOP: body_words += LEN_SOP; break;
+            case I_RED: body_words += wgsync ? 3 : 1; break;
+            default: body_words += 1; break;
+        }
+    }
+    const size_t words = PH_WORDS_N + (size_t)E.n_acc * TT_WORDS + SH_WORDS + body_words;
+    *len = words * 4;
+    if ((SH_WORDS + body_words) * 4 > DVM_CODE_MAX_BYTES) return dvm_set_error(DVM_E_LIMIT, "bytecode exceeds the per-launch limit");
+    if (!bytecode || cap < words * 4) return dvm_set_error(DVM_E_BUFSZ, "bytecode buffer too small");
+    uint32_t *w = (uint32_t *)bytecode;
+    memset(w, 0, words * 4);
+    w[PH_MAGIC] = MAGIC;
+    w[PH_TYPE] = KT_META | (VERSION << 16);
+    w[PH_WORDS] = (uint32_t)words;
+    w[PH_NSEG] = 1;
+    w[PH_BLOCK] = threads;
+    w[PH_GRID] = grid;
+    w[PH_VARIANT] = (uint32_t)vr.K | ((uint32_t)vr.NR << 8);
+    w[PH_NTENS] = (uint32_t)E.n_acc;
+    for (int t = 0; t < E.n_acc; ++t) {
+        uint32_t *tt = w + PH_WORDS_N + t * TT_WORDS;
+        const Access &A = E.acc[t];
+        // a full tensor is read in chunks of V elements at element alignment; only the element
+        // alignment is required of the pointer
+        const int es_log2 = A.dtype == DVM_F32 ? 2 : 1;
+        tt[TT_INFO] = (uint32_t)A.dtype | ((uint32_t)A.is_output << 8) | ((uint32_t)es_log2 << 16);
+        tt[TT_BYTES_LO] = (uint32_t)((uint64_t)A.min_bytes & 0xFFFFFFFFu);
+        tt[TT_BYTES_HI] = (uint32_t)((uint64_t)A.min_bytes >> 32);
+    }
+    uint32_t *sh = w + PH_WORDS_N + E.n_acc * TT_WORDS;
+    sh[S_WORDS] = (uint32_t)(SH_WORDS + body_words);
+    sh[S_CODESIZE] = (uint32_t)body_words;
+    sh[S_NTILES] = (uint32_t)M64;
+    sh[S_GEOM] = G | (V << 16) | (nvec << 24);
+    sh[S_RP] = RP | (threads << 16);
+    sh[S_NCT] = nct;
+    sh[S_TC] = TC;
+    sh[S_D0LO] = (uint32_t)((uint64_t)E.D0 & 0xFFFFFFFFu);
+    sh[S_D0HI] = (uint32_t)((uint64_t)E.D0 >> 32);
+    sh[S_NROWS] = (uint32_t)E.nrows;
+    if (ng > 2) {
+        sh[S_D1] = (uint32_t)E.Dg[1];
+        magic_u32((uint32_t)E.Dg[1], &sh[S_M1], &sh[S_SH1]);
+        if (ng > 3) {
+            sh[S_D2] = (uint32_t)E.Dg[2];
+            magic_u32((uint32_t)E.Dg[2], &sh[S_M2], &sh[S_SH2]);
+        }
+    }
+    if (nct > 1) magic_u32(nct, &sh[S_NCTM], &sh[S_NCTSH]);
+    sh[S_TBASE] = 0;
+    sh[S_NTENS] = (uint32_t)E.n_acc;
+    sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
+    uint32_t imask = 0;
+    uint32_t *b = sh + SH_WORDS;
+    auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
+    for (int i = 0; i < E.n_ai; ++i) {
+        const AI &x = E.ai[i];
+        switch (x.op) {
+            case I_LOAD: case I_STORE: {
+                const Access &A = E.acc[x.tensor];
+                const uint32_t op = view ? (x.op == I_LOAD ? I_VLOAD : I_VSTORE) : x.op;
+                imask |= 1u << op;
+                *b++ = w0(op, view ? LEN_VLOAD : LEN_LOAD, x.a, x.b);
+                *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8);
+                put_i64(A.s[1]);
+                if (view) { put_i64(A.s[2]); put_i64(A.s[3]); }
+                break;
+            }
+            case I_LOADS: case I_STORES: {
+                const Access &A = E.acc[x.tensor];
+                imask |= 1u << x.op;
+                *b++ = w0(x.op, LEN_VLOAD, x.a, 0);
+                *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8);
+                put_i64(A.s[1]); put_i64(A.s[2]); put_i64(A.s[3]);
+                break;
+            }
+            case I_BIN:
+                imask |= 1u << I_BIN;
+                if (x.a == SRC_IMM) { *b++ = w0(I_BIN, 2, x.a, x.b); *b++ = bits_f32(x.imm); }
+                else *b++ = w0(I_BIN, 1, x.a, x.b);
+                break;
+            case I_SOP:
+                imask |= 1u << I_SOP;
+                *b++ = w0(I_SOP, LEN_SOP, x.a, x.b);
+                *b++ = (uint32_t)x.kind | ((uint32_t)x.srck << 8) | ((uint32_t)x.c << 16);
+                *b++ = x.srck == 1 ? bits_f32(x.imm) : 0u;
+                break;
+            case I_RED:
+                imask |= 1u << I_RED;
+                *b++ = w0(I_RED, 1, x.a, x.b);
+                if (wgsync) {           // rows span several waves: synchronise, then combine the partials
+                    imask |= (1u << I_SYNC) | (1u << I_REDX);
+                    *b++ = w0(I_SYNC, 1, 0, 0);
+                    *b++ = w0(I_REDX, 1, x.a, x.b == R_SUMSQ ? (uint32_t)R_SUM : x.b);
+                }
+                break;
+            default:
+                imask |= 1u << x.op;
+                *b++ = w0(x.op, 1, x.a, x.b);
+                break;
+        }
+    }
+    sh[S_IMASK] = imask;
+    t_detail[0] = 0;
+    return DVM_OK;
+}
+
+// ------------------------------------------------------------------------------------------------
+// validation, introspection, disassembly
+// ------------------------------------------------------------------------------------------------
+namespace {
+
+int bad(const char *msg) { return dvm_set_error(DVM_E_BADCODE, msg); }
+
+const Variant *variant_of(uint32_t word) {
+    for (int i = 0; i < N_VARIANTS; ++i)
+        if ((uint32_t)VARIANTS[i].K == (word & 0xFF) && (uint32_t)VARIANTS[i].NR == ((word >> 8) & 0xFF)) return &VARIANTS[i];
+    return nullptr;
+}
+
+bool reg_ok(uint32_t r, const Variant *v) { return r < (uint32_t)v->NR; }
+bool sreg_ok(uint32_t s) { return s < (uint32_t)NS; }
+
+}  // namespace
+
+extern "C" int dvm_validate(const void *bytecode, size_t len) {
+    if (!bytecode) return dvm_set_error(DVM_E_ARGS, "dvm_validate: null bytecode");
+    if (len < PH_WORDS_N * 4 || (len & 3)) return bad("bytecode shorter than its header");
+    const uint32_t *w = (const uint32_t *)bytecode;
+    if (w[PH_MAGIC] != MAGIC) return bad("bad magic");
+    if ((w[PH_TYPE] >> 16) != VERSION) return bad("unknown version");
+    const uint32_t kt = w[PH_TYPE] & 0xFFFF;
+    if (kt != KT_META && kt != KT_STACK) return bad("unknown kernel type");
+    const uint32_t words = w[PH_WORDS];
+    if ((size_t)words * 4 != len) return bad("length field does not match the buffer");
+    const uint32_t nseg = w[PH_NSEG], ntens = w[PH_NTENS];
+    if (nseg == 0 || nseg > 64) return bad("bad segment count");
+    if (kt == KT_META && nseg != 1) return bad("a meta-kernel has one segment");
+    if (ntens > DVM_MAX_TENSORS) return bad("too many tensors");
+    const Variant *vr = variant_of(w[PH_VARIANT]);
+    if (!vr) return bad("unknown interpreter variant");
+    const uint32_t block = w[PH_BLOCK];
+    if (block == 0 || (block & 63) || block > (uint32_t)vr->max_threads) return bad("bad workgroup size");
+    size_t at = PH_WORDS_N + (size_t)ntens * TT_WORDS;
+    if (at > words) return bad("tensor table runs past the end");
+    for (uint32_t t = 0; t < ntens; ++t) {
+        const uint32_t info = w[PH_WORDS_N + t * TT_WORDS + TT_INFO];
+        if ((info & 0xFF) > 1) return bad("tensor dtype");
+        if (((info >> 16) & 0xFF) > 8) return bad("tensor alignment");
+    }
+    if ((words - at) * 4 > DVM_CODE_MAX_BYTES) return bad("segments exceed the per-launch limit");
+    uint64_t tiles_total = 0;
+    for (uint32_t s = 0; s < nseg; ++s) {
+        if (at + SH_WORDS > words) return bad("segment header runs past the end");
+        const uint32_t *sh = w + at;
+        const uint32_t sw = sh[S_WORDS], cs = sh[S_CODESIZE];
+        if (sw != SH_WORDS + cs || at + sw > words) return bad("segment length");
+        const uint32_t G = sh[S_GEOM] & 0xFFFF, V = (sh[S_GEOM] >> 16) & 0xFF, nvec = sh[S_GEOM] >> 24;
+        const uint32_t RP = sh[S_RP] & 0xFFFF, thr = sh[S_RP] >> 16;
+        if (V != 4 && V != 8) return bad("chunk width");
+        if (G == 0 || RP == 0 || nvec == 0) return bad("zero geometry field");
+        if (G > 64 ? (G & 63) != 0 : (G & (G - 1)) != 0) return bad("lanes per row");
+        if (nvec * V > (uint32_t)vr->K) return bad("chunks per lane exceed the variant");
+        if (thr != G * RP || thr > block || (thr & 63)) return bad("segment threads");
+        if (G > 1024) return bad("row group larger than a workgroup");
+        const uint32_t nct = sh[S_NCT], TC = sh[S_TC];
+        if (nct == 0) return bad("column tiles");
+        if (TC > G * nvec * V) return bad("tile wider than the lanes can hold");
+        const uint64_t D0 = (uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32);
+        const uint64_t nrows = sh[S_NROWS];
+        const uint64_t M = sh[S_NTILES];
+        if (M != 0) {
+            if ((uint64_t)nct * TC < D0) return bad("column tiles do not cover the row");
+            if (nct > 1 && (uint64_t)(nct - 1) * TC >= D0) return bad("an empty column tile");
+            if (M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
+        }
+        if (sh[S_D1] == 0 && sh[S_D2] != 0) return bad("outer dims");
+        if (sh[S_D1] != 0) {
+            uint32_t m, sft;
+            magic_u32(sh[S_D1], &m, &sft);
+            if (m != sh[S_M1] || sft != sh[S_SH1]) return bad("division constants of outer dim 1");
+        }
+        if (sh[S_D2] != 0) {
+            uint32_t m, sft;
+            magic_u32(sh[S_D2], &m, &sft);
+            if (m != sh[S_M2] || sft != sh[S_SH2]) return bad("division constants of outer dim 2");
+        }
+        if (nct > 1) {
+            uint32_t m, sft;
+            magic_u32(nct, &m, &sft);
+            if (m != sh[S_NCTM] || sft != sh[S_NCTSH]) return bad("division constants of the column tiles");
+        }
+        const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
+        if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
+        tiles_total += M;
+        // body
+        size_t pc = at + SH_WORDS;
+        const size_t end = pc + cs;
+        bool pending_red = false;
+        while (pc < end) {
+            const uint32_t x = w[pc];
+            const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, bb = x >> 24;
+            if (l == 0 || pc + l > end) return bad("instruction length");
+            uint32_t want = 1;
+            switch (op) {
+                case I_LOAD: case I_VLOAD: case I_STORE: case I_VSTORE: {
+                    want = (op == I_LOAD || op == I_STORE) ? LEN_LOAD : LEN_VLOAD;
+                    if (l != want) return bad("memory instruction length");
+                    if (a != SRC_ACC && !reg_ok(a, vr)) return bad("tile register index");
+                    if ((op == I_LOAD || op == I_VLOAD) ? (bb >= B_COUNT || (a != SRC_ACC && bb != B_NONE)) : bb != 0) return bad("combine op");
+                    const uint32_t w1 = w[pc + 1];
+                    if ((w1 & 0xFF) >= nt) return bad("tensor index");
+                    const uint32_t info = w[PH_WORDS_N + (tbase + (w1 & 0xFF)) * TT_WORDS + TT_INFO];
+                    if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
+                    if ((op == I_STORE || op == I_VSTORE) && !((info >> 8) & 1)) return bad("store to an input tensor");
+                    if (((w1 >> 8) & 0xFF) == DVM_BF16 && V != 8) return bad("bf16 tile with 4-element chunks");
+                    break;
+                }
+                case I_LOADS: case I_STORES: {
+                    want = LEN_VLOAD;
+                    if (l != want) return bad("memory instruction length");
+                    if (!sreg_ok(a)) return bad("row register index");
+                    const uint32_t w1 = w[pc + 1];
+                    if ((w1 & 0xFF) >= nt) return bad("tensor index");
+                    const uint32_t info = w[PH_WORDS_N + (tbase + (w1 & 0xFF)) * TT_WORDS + TT_INFO];
+                    if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
+                    if (op == I_STORES && !((info >> 8) & 1)) return bad("store to an input tensor");
+                    break;
+                }
+                case I_MOVRA: case I_MOVAR:
+                    if (l != 1 || !reg_ok(a, vr)) return bad("move");
+                    break;
+                case I_UN:
+                    if (l != 1 || bb == 0 || bb >= U_COUNT) return bad("unary op");
+                    break;
+                case I_BIN:
+                    if (bb == 0 || bb >= B_COUNT) return bad("binary op");
+                    if (a == SRC_IMM) { if (l != 2) return bad("binary op length"); }
+                    else {
+                        if (l != 1) return bad("binary op length");
+                        if (!(a == SRC_ACC || reg_ok(a, vr) || (a >= SRC_S0 && sreg_ok(a - SRC_S0)))) return bad("binary source");
+                    }
+                    break;
+                case I_SEL:
+                    if (l != 1 || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("select");
+                    break;
+                case I_RED:
+                    if (l != 1 || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
+                    if (G > 64) pending_red = true;
+                    break;
+                case I_SYNC:
+                    if (l != 1) return bad("sync");
+                    break;
+                case I_REDX:
+                    if (l != 1 || !sreg_ok(a) || bb >= R_SUMSQ) return bad("reduction combine");
+                    if (G <= 64 || !pending_red) return bad("reduction combine without partials");
+                    if (pc < at + SH_WORDS + 1 || (w[pc - 1] & 0xFF) != I_SYNC) return bad("reduction combine without barrier");
+                    pending_red = false;
+                    break;
+                case I_SOP: {
+                    if (l != LEN_SOP || !sreg_ok(a) || !sreg_ok(bb)) return bad("row-scalar op");
+                    const uint32_t w1 = w[pc + 1];
+                    const uint32_t kind = w1 & 0xFF, srck = (w1 >> 8) & 0xFF, c = (w1 >> 16) & 0xFF;
+                    if (kind >= SOP_UNARY ? (kind - SOP_UNARY == 0 || kind - SOP_UNARY >= U_COUNT) : (kind == 0 || kind >= B_COUNT)) return bad("row-scalar op kind");
+                    if (srck > 1 || (srck == 0 && !sreg_ok(c))) return bad("row-scalar source");
+                    break;
+                }
+                case I_NOP:
+                    if (l != 1) return bad("nop");
+                    break;
+                default: return bad("unknown instruction id");
+            }
+            pc += l;
+        }
+        if (pending_red) return bad("reduction partials never combined");
+        at += sw;
+    }
+    if (at != words) return bad("trailing words after the last segment");
+    if (tiles_total != 0 && w[PH_GRID] == 0) return bad("zero grid for a non-empty program");
+    if (w[PH_GRID] > 65535u * 16) return bad("grid too large");
+    return DVM_OK;
+}
+
+extern "C" int dvm_code_info_get(const void *bytecode, size_t len, dvm_code_info *info) {
+    if (!info) return dvm_set_error(DVM_E_ARGS, "dvm_code_info_get: null info");
+    int st = dvm_validate(bytecode, len);
+    if (st != DVM_OK) return st;
+    const uint32_t *w = (const uint32_t *)bytecode;
+    memset(info, 0, sizeof(*info));
+    info->kernel_type = (int32_t)(w[PH_TYPE] & 0xFFFF);
+    info->n_segments = (int32_t)w[PH_NSEG];
+    info->n_tensors = (int32_t)w[PH_NTENS];
+    info->grid = (int32_t)w[PH_GRID];
+    info->block = (int32_t)w[PH_BLOCK];
+    info->variant_k = (int32_t)(w[PH_VARIANT] & 0xFF);
+    info->variant_nr = (int32_t)((w[PH_VARIANT] >> 8) & 0xFF);
+    size_t at = PH_WORDS_N + (size_t)w[PH_NTENS] * TT_WORDS;
+    for (uint32_t s = 0; s < w[PH_NSEG]; ++s) {
+        const uint32_t *sh = w + at;
+        info->n_tiles += sh[S_NTILES];
+        info->code_bytes += (int64_t)sh[S_CODESIZE] * 4;
+        size_t pc = at + SH_WORDS;
+        const size_t end = pc + sh[S_CODESIZE];
+        while (pc < end) { info->n_instructions++; pc += (w[pc] >> 8) & 0xFF; }
+        at += sh[S_WORDS];
+    }
+    return DVM_OK;
+}
+
+extern "C" int dvm_code_tensor(const void *bytecode, size_t len, int index, int64_t *min_bytes, int *is_output,
+                               int *dtype, int *align_bytes) {
+    int st = dvm_validate(bytecode, len);
+    if (st != DVM_OK) return st;
+    const uint32_t *w = (const uint32_t *)bytecode;
+    if (index < 0 || (uint32_t)index >= w[PH_NTENS]) return dvm_set_error(DVM_E_ARGS, "dvm_code_tensor: index");
+    const uint32_t *tt = w + PH_WORDS_N + index * TT_WORDS;
+    if (min_bytes) *min_bytes = (int64_t)((uint64_t)tt[TT_BYTES_LO] | ((uint64_t)tt[TT_BYTES_HI] << 32));
+    if (is_output) *is_output = (int)((tt[TT_INFO] >> 8) & 1);
+    if (dtype) *dtype = (int)(tt[TT_INFO] & 0xFF);
+    if (align_bytes) *align_bytes = 1 << ((tt[TT_INFO] >> 16) & 0xFF);
+    return DVM_OK;
+}
+
+extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {
+    if (!codes || !lens || !len || n < 1) return dvm_set_error(DVM_E_ARGS, "dvm_stack: bad argument");
+    size_t seg_words = 0;
+    uint32_t ntens = 0, nseg = 0, block = 0, K = 0, NR = 0;
+    uint64_t grid = 0;
+    for (int i = 0; i < n; ++i) {
+        int st = dvm_validate(codes[i], lens[i]);
+        if (st != DVM_OK) return st;
+        const uint32_t *w = (const uint32_t *)codes[i];
+        const uint32_t off = PH_WORDS_N + w[PH_NTENS] * TT_WORDS;
+        seg_words += w[PH_WORDS] - off;
+        ntens += w[PH_NTENS];
+        nseg += w[PH_NSEG];
+        if (w[PH_BLOCK] > block) block = w[PH_BLOCK];
+        if ((w[PH_VARIANT] & 0xFF) > K) K = w[PH_VARIANT] & 0xFF;
+        if (((w[PH_VARIANT] >> 8) & 0xFF) > NR) NR = (w[PH_VARIANT] >> 8) & 0xFF;
+        if (w[PH_GRID] > grid) grid = w[PH_GRID];
+    }
+    if (ntens > DVM_MAX_TENSORS) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: too many tensors for one launch");
+    if (nseg > 64) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: too many segments");
+    if (seg_words * 4 > DVM_CODE_MAX_BYTES) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: bytecode exceeds the per-launch limit");
+    // the stacked launch runs one interpreter variant: the smallest one that holds every part
+    const Variant *vr = nullptr;
+    for (int i = 0; i < N_VARIANTS; ++i) {
+        const Variant &v = VARIANTS[i];
+        if ((uint32_t)v.K >= K && (uint32_t)v.NR >= NR && (uint32_t)v.max_threads >= block) {
+            if (!vr || v.K < vr->K || (v.K == vr->K && v.NR < vr->NR)) vr = &v;
+        }
+    }
+    if (!vr) return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_stack: no interpreter variant fits all parts");
+    const size_t words = PH_WORDS_N + (size_t)ntens * TT_WORDS + seg_words;
+    *len = words * 4;
+    if (!out || cap < words * 4) return dvm_set_error(DVM_E_BUFSZ, "dvm_stack: buffer too small");
+    uint32_t *w = (uint32_t *)out;
+    memset(w, 0, words * 4);
+    w[PH_MAGIC] = MAGIC;
+    w[PH_TYPE] = KT_STACK | (VERSION << 16);
+    w[PH_WORDS] = (uint32_t)words;
+    w[PH_NSEG] = nseg;
+    w[PH_BLOCK] = block;
+    w[PH_GRID] = (uint32_t)grid;
+    w[PH_VARIANT] = (uint32_t)vr->K | ((uint32_t)vr->NR << 8);
+    w[PH_NTENS] = ntens;
+    uint32_t *tt = w + PH_WORDS_N;
+    uint32_t *sg = w + PH_WORDS_N + ntens * TT_WORDS;
+    uint32_t tbase = 0;
+    for (int i = 0; i < n; ++i) {
+        const uint32_t *c = (const uint32_t *)codes[i];
+        const uint32_t nt = c[PH_NTENS];
+        memcpy(tt, c + PH_WORDS_N, (size_t)nt * TT_WORDS * 4);
+        tt += nt * TT_WORDS;
+        const uint32_t off = PH_WORDS_N + nt * TT_WORDS;
+        const uint32_t sw = c[PH_WORDS] - off;
+        memcpy(sg, c + off, (size_t)sw * 4);
+        // rebase the tensor indices of the copied segments
+        uint32_t at = 0;
+        for (uint32_t s = 0; s < c[PH_NSEG]; ++s) {
+            sg[at + S_TBASE] += tbase;
+            at += sg[at + S_WORDS];
+        }
+        sg += sw;
+        tbase += nt;
+    }
+    return dvm_validate(out, words * 4);
+}
+
+namespace {
+
+const char *const UN_NAMES[] = {"none", "sqrt", "abs", "log", "exp", "round", "floor", "isfinite", "neg", "rsqrt", "rcp",
+                                "tanh", "erf", "sigmoid", "square", "gelu_tanh", "gelu_erf", "silu", "cast_bf16"};
+const char *const BIN_NAMES[] = {"mov", "add", "sub", "rsub", "mul", "div", "rdiv", "min", "max", "pow", "rpow",
+                                 "cmp_eq", "cmp_ne", "cmp_lt", "cmp_le", "cmp_gt", "cmp_ge"};
+const char *const RED_NAMES[] = {"sum", "max", "min", "sumsq"};
+
+struct Out {
+    char *p;
+    size_t cap, n;
+    void put(const char *fmt, ...) __attribute__((format(printf, 2, 3))) {
+        va_list ap;
+        va_start(ap, fmt);
+        if (n < cap) {
+            int k = vsnprintf(p + n, cap - n, fmt, ap);
+            if (k > 0) n += (size_t)k;
+            if (n >= cap) n = cap - 1;
+        }
+        va_end(ap);
+    }
+};
+
+void reg_name(char *buf, uint32_t r) {
+    if (r == SRC_ACC) snprintf(buf, 8, "acc");
+    else if (r == SRC_IMM) snprintf(buf, 8, "imm");
+    else if (r >= SRC_S0) snprintf(buf, 8, "s%u", r - SRC_S0);
+    else snprintf(buf, 8, "r%u", r);
+}
+
+}  // namespace
+
+extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t cap) {
+    if (!txt || cap == 0) return dvm_set_error(DVM_E_ARGS, "dvm_disasm: null text buffer");
+    txt[0] = 0;
+    int st = dvm_validate(bytecode, len);
+    if (st != DVM_OK) return st;
+    const uint32_t *w = (const uint32_t *)bytecode;
+    Out o{txt, cap, 0};
+    const uint32_t kt = w[PH_TYPE] & 0xFFFF;
+    o.put("dvm program: kernel_type=%s block_dim=%u threads=%u variant=K%u/R%u segments=%u tensors=%u words=%u\n",
+          kt == KT_META ? "vmain.v" : "vstack.t", w[PH_GRID], w[PH_BLOCK], w[PH_VARIANT] & 0xFF, (w[PH_VARIANT] >> 8) & 0xFF,
+          w[PH_NSEG], w[PH_NTENS], w[PH_WORDS]);
+    for (uint32_t t = 0; t < w[PH_NTENS]; ++t) {
+        const uint32_t *tt = w + PH_WORDS_N + t * TT_WORDS;
+        o.put("  tensor %u: %s %s min_bytes=%llu\n", t, (tt[TT_INFO] & 0xFF) ? "bf16" : "f32", ((tt[TT_INFO] >> 8) & 1) ? "out" : "in",
+              (unsigned long long)((uint64_t)tt[TT_BYTES_LO] | ((uint64_t)tt[TT_BYTES_HI] << 32)));
+    }
+    size_t at = PH_WORDS_N + (size_t)w[PH_NTENS] * TT_WORDS;
+    for (uint32_t s = 0; s < w[PH_NSEG]; ++s) {
+        const uint32_t *sh = w + at;
+        const uint32_t M = sh[S_NTILES], N = w[PH_GRID];
+        const uint32_t body_tile = N ? (M + N - 1) / N : 0;
+        o.put("segment %u: tiles=%u body_tile=%u code_size=%u rows=%u row_len=%llu lanes_per_row=%u chunk=%u chunks_per_lane=%u "
+              "rows_per_tile=%u col_tiles=%u tile_cols=%u outer=[%u,%u] tensor_base=%u\n",
+              s, M, body_tile, sh[S_CODESIZE] * 4, sh[S_NROWS],
+              (unsigned long long)((uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32)), sh[S_GEOM] & 0xFFFF,
+              (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE]);
+        size_t pc = at + SH_WORDS;
+        const size_t end = pc + sh[S_CODESIZE];
+        while (pc < end) {
+            const uint32_t x = w[pc];
+            const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, b = x >> 24;
+            char ra[8], rb[8];
+            reg_name(ra, a);
+            reg_name(rb, b);
+            auto i64 = [&](size_t i) { return (long long)((uint64_t)w[i] | ((uint64_t)w[i + 1] << 32)); };
+            switch (op) {
+                case I_LOAD:
+                    o.put("  %04zu load    %s %s= t%u stride=%lld\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "", w[pc + 1] & 0xFF, i64(pc + 2));
+                    break;
+                case I_VLOAD:
+                    o.put("  %04zu viewload %s %s= t%u strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "",
+                          w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6));
+                    break;
+                case I_STORE:
+                    o.put("  %04zu store   t%u = %s stride=%lld\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2));
+                    break;
+                case I_VSTORE:
+                    o.put("  %04zu viewstore t%u = %s strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2),
+                          i64(pc + 4), i64(pc + 6));
+                    break;
+                case I_LOADS:
+                    o.put("  %04zu loads   s%u = t%u strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, a, w[pc + 1] & 0xFF, i64(pc + 2),
+                          i64(pc + 4), i64(pc + 6));
+                    break;
+                case I_STORES:
+                    o.put("  %04zu stores  t%u = s%u strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, a, i64(pc + 2),
+                          i64(pc + 4), i64(pc + 6));
+                    break;
+                case I_MOVRA: o.put("  %04zu copy    r%u = acc\n", pc - at - SH_WORDS, a); break;
+                case I_MOVAR: o.put("  %04zu copy    acc = r%u\n", pc - at - SH_WORDS, a); break;
+                case I_UN: o.put("  %04zu %-7s acc\n", pc - at - SH_WORDS, UN_NAMES[b]); break;
+                case I_BIN:
+                    if (a == SRC_IMM) o.put("  %04zu %-7s acc, %.9g\n", pc - at - SH_WORDS, BIN_NAMES[b], (double)f32_bits(w[pc + 1]));
+                    else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
+                    break;
+                case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
+                case I_RED: o.put("  %04zu red.%-5s s%u = acc\n", pc - at - SH_WORDS, RED_NAMES[b], a); break;
+                case I_SYNC: o.put("  %04zu sync\n", pc - at - SH_WORDS); break;
+                case I_REDX: o.put("  %04zu redx.%-4s s%u\n", pc - at - SH_WORDS, RED_NAMES[b], a); break;
+                case I_SOP: {
+                    const uint32_t w1 = w[pc + 1];
+                    const uint32_t kind = w1 & 0xFF, srck = (w1 >> 8) & 0xFF, c = (w1 >> 16) & 0xFF;
+                    if (kind >= SOP_UNARY) o.put("  %04zu s.%-6s s%u = s%u\n", pc - at - SH_WORDS, UN_NAMES[kind - SOP_UNARY], a, b);
+                    else if (srck == 1) o.put("  %04zu s.%-6s s%u = s%u, %.9g\n", pc - at - SH_WORDS, BIN_NAMES[kind], a, b, (double)f32_bits(w[pc + 2]));
+                    else o.put("  %04zu s.%-6s s%u = s%u, s%u\n", pc - at - SH_WORDS, BIN_NAMES[kind], a, b, c);
+                    break;
+                }
+                default: o.put("  %04zu nop\n", pc - at - SH_WORDS); break;
+            }
+            pc += l;
+        }
+        at += sh[S_WORDS];
+    }
+    return DVM_OK;
+}

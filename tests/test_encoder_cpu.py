@@ -1,0 +1,207 @@
+"""Host-side tests (no GPU): the library loads and exports its C ABI, the tile-size rule equals
+the oracle's brute force bit for bit, encoding is deterministic, emitted bytecode validates,
+malformed bytecode and bad programs are rejected with error codes."""
+import ctypes
+import os
+import re
+import subprocess
+import sys
+import time
+
+import numpy as np
+import pytest
+
+from oracle import tiling
+from paper_2603_24239_amd import binding as B
+from workloads import gen
+from workloads import programs as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    return B.Context(-1)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    header = open(os.path.join(ROOT, "include", "dvm.h")).read()
+    declared = set(re.findall(r"\b(dvm_[a-z_0-9]+)\s*\(", header))
+    declared -= {"dvm_status", "dvm_dtype", "dvm_opcode"}
+    assert declared, "no declarations found"
+    for name in sorted(declared):
+        assert hasattr(lib, name), f"libdvm.so does not export {name}"
+    assert set(B.EXPORTED) == declared
+
+
+def test_plan_matches_paper_example_and_oracle_bruteforce():
+    assert B.dvm_plan(32 * 1024, 40, 1 << 20, 16, 2) == (820, 832, 40)
+    rng = np.random.default_rng(7)
+    for _ in range(400):
+        total = int(rng.integers(1, 6000))
+        n = int(rng.integers(1, 80))
+        tmax = int(rng.integers(1, 4000))
+        align = int(rng.choice([1, 2, 4, 8, 16, 64]))
+        extra = int(rng.choice([0, 1, 2, 7, 100]))
+        t, ta = tiling.hardware_align_div(total, n, tmax, align, extra)
+        got = B.dvm_plan(total, n, tmax, align, extra)
+        assert got[:2] == (t, ta), (total, n, tmax, align, extra)
+        assert got[2] == tiling.ceil_div(total, ta)
+
+
+CASES = [
+    ("c1_gelu_erf", [(4, 1000), (1000,), (1000,)]),
+    ("c2_rmsnorm", [(3, 77, 4096), (4096,)]),
+    ("c3_masked_softmax", [(2, 32, 333, 333), (333, 333)]),
+    ("c4_chain", [(1000, 8192), (1000, 8192), (8192,), (8192,), (8192,), (1000, 8192)]),
+    ("c5_silu_gate", [(100, 14336), (100, 14336)]),
+    ("c5_softmax", [(32, 100, 13)]),
+    ("if_else_add", [(7, 9, 100)] * 4),
+    ("layernorm_f32", [(5, 8192, 1024), (1024,), (1024,)]),
+]
+
+
+@pytest.mark.parametrize("name,shapes", CASES)
+def test_encode_is_deterministic_and_validates(ctx, name, shapes):
+    prog = B.Program(W.get_program(name))
+    shs = [B.make_shape(s) for s in shapes]
+    a = B.dvm_encode(ctx, prog, shs)
+    other = B.Program(W.get_program("c2_rmsnorm"))
+    B.dvm_encode(ctx, other, [B.make_shape((5, 4096)), B.make_shape((4096,))])   # interleaved encode
+    b = B.dvm_encode(ctx, B.Program(W.get_program(name)), shs)
+    assert a.raw == b.raw
+    a.validate()
+    inf = a.info()
+    txt = a.disasm()
+    assert inf.n_segments == 1 and inf.n_tensors == len(shapes) + len(W.get_program(name).outputs)
+    assert f"tiles={inf.n_tiles}" in txt and f"code_size={inf.code_bytes}" in txt
+    assert "vmain.v" in txt
+    n_lines = sum(1 for l in txt.splitlines() if re.match(r"\s+\d{4} ", l))
+    assert n_lines == inf.n_instructions
+    # tiles partition the rows: tiles * rows_per_tile covers nrows without an empty tile
+    m = re.search(r"rows=(\d+) .*rows_per_tile=(\d+) col_tiles=(\d+)", txt)
+    rows, rp, nct = int(m.group(1)), int(m.group(2)), int(m.group(3))
+    assert inf.n_tiles == -(-rows // rp) * nct
+    assert 0 < inf.grid <= inf.n_tiles
+
+
+def test_encode_fresh_process_gives_same_bytes(ctx):
+    prog = B.Program(W.get_program("c4_chain"))
+    shapes = [(77, 8192), (77, 8192), (8192,), (8192,), (8192,), (77, 8192)]
+    mine = B.dvm_encode(ctx, prog, [B.make_shape(s) for s in shapes]).raw.hex()
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2603_24239_amd import binding as B\nfrom workloads import programs as W\n"
+            "p = B.Program(W.get_program('c4_chain'))\n"
+            "print(B.dvm_encode(B.Context(-1), p, [B.make_shape(s) for s in %r]).raw.hex())\n") % (ROOT, shapes)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, check=True).stdout.strip()
+    assert out == mine
+
+
+def test_fusion_keeps_intermediates_out_of_memory(ctx):
+    """The 12-op chain is one meta-kernel: the only memory instructions are the loads of the six
+    inputs and one store (Section 5.1: fused intermediates stay in local memory)."""
+    prog = B.Program(W.get_program("c4_chain"))
+    shapes = [(100, 8192), (100, 8192), (8192,), (8192,), (8192,), (100, 8192)]
+    txt = B.dvm_encode(ctx, prog, [B.make_shape(s) for s in shapes]).disasm()
+    assert len(re.findall(r"\bload\b", txt)) == 6
+    assert len(re.findall(r"\bstore\b", txt)) == 1
+    assert "sync" in txt and "redx" in txt      # rows of 8192 span several waves: barrier inserted
+
+
+def test_row_offsets_stay_inside_declared_extents(ctx):
+    prog = B.Program(W.get_program("c5_rope"))
+    T = 50
+    shs = [B.make_shape((T, 32, 64), (4096, 128, 1)), B.make_shape((T, 32, 64), (4096, 128, 1)),
+           B.make_shape((T, 1, 64)), B.make_shape((T, 1, 64))]
+    outl = [B.make_shape((T, 32, 64), (4096, 128, 1))] * 2
+    code = B.dvm_encode(ctx, prog, shs, outl)
+    need = [code.tensor(i)[0] for i in range(6)]
+    assert need[0] == ((T - 1) * 4096 + 31 * 128 + 63 + 1) * 2
+    assert need[2] == T * 64 * 4
+    assert need[4] == need[0] and code.tensor(4)[1] and not code.tensor(0)[1]
+    assert "viewload" in code.disasm() and "viewstore" in code.disasm()
+
+
+def test_errors_are_codes_not_crashes(ctx):
+    prog = B.Program(W.get_program("c1_gelu_erf"))
+    with pytest.raises(B.DvmError) as e:
+        B.dvm_encode(ctx, prog, [B.make_shape((4, 1000)), B.make_shape((999,)), B.make_shape((1000,))])
+    assert e.value.status == -2
+    with pytest.raises(B.DvmError) as e:
+        B.dvm_encode(ctx, prog, [B.make_shape((4, 1000))])
+    assert e.value.status == -1
+    good = B.dvm_encode(ctx, prog, [B.make_shape((4, 1000)), B.make_shape((1000,)), B.make_shape((1000,))])
+    lib = B.load()
+    raw = bytearray(good.raw)
+    assert lib.dvm_validate(bytes(raw), len(raw)) == 0
+    assert lib.dvm_validate(bytes(raw), len(raw) - 4) == -7          # truncated
+    bad = bytearray(raw); bad[0] ^= 0xFF
+    assert lib.dvm_validate(bytes(bad), len(bad)) == -7               # magic
+    # corrupt every word in turn: validation must never crash, and a changed register / tensor /
+    # length field must be caught
+    words = np.frombuffer(bytes(raw), dtype=np.uint32).copy()
+    caught = 0
+    for i in range(len(words)):
+        w = words.copy()
+        w[i] ^= 0x00FF0000
+        caught += lib.dvm_validate(w.tobytes(), w.nbytes) != 0
+    assert caught > 10
+    # too-small output buffer reports the needed size
+    buf = ctypes.create_string_buffer(16)
+    ln = ctypes.c_size_t()
+    shs = (B.dvm_shape * 3)(B.make_shape((4, 1000)), B.make_shape((1000,)), B.make_shape((1000,)))
+    st = lib.dvm_encode(ctx._h, prog._h, shs, 3, None, buf, 16, ctypes.byref(ln), None)
+    assert st == -6 and ln.value == len(good.raw)
+    # dvm_run without a device context is refused before anything touches a GPU
+    with pytest.raises(B.DvmError) as e:
+        B.dvm_run(ctx, good, [1, 2, 3, 4])
+    assert e.value.status == -1
+    # different iteration spaces cannot be one meta-kernel
+    from workloads.programs import _p
+    two = _p("two_spaces", [("a", "f32"), ("b", "f32")],
+             [("s", "sum", ["a"], {}), ("t", "add", ["s", "b"], {})], [("t", "f32")])
+    with pytest.raises(B.DvmError) as e:
+        B.dvm_encode(ctx, B.Program(two), [B.make_shape((4, 100)), B.make_shape((4, 7))])
+    assert e.value.status in (-2, -5)
+
+
+def test_stack_concatenates_segments(ctx):
+    T = 64
+    descs = ["c5_rmsnorm", "c5_residual", "c5_silu_gate", "c5_softmax"]
+    shapes = [[(T, 4096), (4096,)], [(T, 4096)] * 2, [(T, 14336)] * 2, [(32, T, T // 8 + 1)]]
+    codes = [B.dvm_encode(ctx, B.Program(W.get_program(d)), [B.make_shape(s) for s in sh])
+             for d, sh in zip(descs, shapes)]
+    st = B.dvm_stack(codes)
+    st.validate()
+    inf = st.info()
+    assert inf.kernel_type == 1 and inf.n_segments == 4
+    assert inf.n_tensors == sum(c.info().n_tensors for c in codes)
+    assert inf.n_tiles == sum(c.info().n_tiles for c in codes)
+    assert inf.block == max(c.info().block for c in codes)
+    assert "vstack.t" in st.disasm()
+    assert B.dvm_stack(codes).raw == st.raw
+
+
+def test_encode_latency_budget(ctx):
+    """dvm_encode stays far below the 20 us per-instance budget even through ctypes-free timing
+    of the C call loop (measured here through ctypes, which only adds overhead)."""
+    lib = B.load()
+    prog = B.Program(W.get_program("c4_chain"))
+    shs = (B.dvm_shape * 6)(*[B.make_shape(s) for s in
+                              [(1000, 8192), (1000, 8192), (8192,), (8192,), (8192,), (1000, 8192)]])
+    buf = ctypes.create_string_buffer(8192)
+    ln = ctypes.c_size_t()
+    n = 2000
+    t0 = time.perf_counter()
+    for _ in range(n):
+        lib.dvm_encode(ctx._h, prog._h, shs, 6, None, buf, 8192, ctypes.byref(ln), None)
+    us = (time.perf_counter() - t0) / n * 1e6
+    assert us < 20.0, us
+
+
+def test_shapes_stream_is_seeded_and_distinct():
+    s = gen.c2_shapes()
+    assert len(s) == 200 and len(set(s)) == 200 and s == gen.c2_shapes()
+    assert all(1 <= b <= 32 and 1 <= q <= 2048 for b, q in s)
+    assert all(1 <= t <= 8192 for t in gen.c5_steps()) and len(gen.c5_steps()) == 64
