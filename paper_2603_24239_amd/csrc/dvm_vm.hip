@@ -299,6 +299,8 @@ struct Geo {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
 #define GLOBAL_AS __attribute__((address_space(1)))
 typedef const GLOBAL_AS char *gcptr;   // global memory, read
 typedef GLOBAL_AS char *gptr;          // global memory, write
@@ -338,15 +340,19 @@ template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const 
                     gcptr q = p + (uint64_t)J * g.GV * ES;
                     if constexpr (DT == 0) {
                         sfor<V / 4>([&]<int H>() LI {
-                            const u32x4 r = *(const GLOBAL_AS u32x4_a4 *)(q + 16 * H);
-                            sfor<4>([&]<int E>() LI { t.v[J * V + 4 * H + E] = __builtin_bit_cast(float, r[E]); });
+                            const f32x4 r = *(const GLOBAL_AS f32x4_a4 *)(q + 16 * H);
+                            t.v[J * V + 4 * H + 0] = r.x;
+                            t.v[J * V + 4 * H + 1] = r.y;
+                            t.v[J * V + 4 * H + 2] = r.z;
+                            t.v[J * V + 4 * H + 3] = r.w;
                         });
                     } else {
                         const u32x4 r = *(const GLOBAL_AS u32x4_a2 *)q;
-                        sfor<4>([&]<int E>() LI {
-                            t.v[J * V + 2 * E] = bf16_lo(r[E]);
-                            t.v[J * V + 2 * E + 1] = bf16_hi(r[E]);
-                        });
+                        const uint32_t w0 = r.x, w1 = r.y, w2 = r.z, w3 = r.w;
+                        t.v[J * V + 0] = bf16_lo(w0); t.v[J * V + 1] = bf16_hi(w0);
+                        t.v[J * V + 2] = bf16_lo(w1); t.v[J * V + 3] = bf16_hi(w1);
+                        t.v[J * V + 4] = bf16_lo(w2); t.v[J * V + 5] = bf16_hi(w2);
+                        t.v[J * V + 6] = bf16_lo(w3); t.v[J * V + 7] = bf16_hi(w3);
                     }
                 }
             }
@@ -380,11 +386,9 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
                     gptr q = p + (uint64_t)J * g.GV * ES;
                     if constexpr (DT == 0) {
                         sfor<V / 4>([&]<int H>() LI {
-                            const u32x4 r = {__builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 0]),
-                                             __builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 1]),
-                                             __builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 2]),
-                                             __builtin_bit_cast(uint32_t, t.v[J * V + 4 * H + 3])};
-                            *(GLOBAL_AS u32x4_a4 *)(q + 16 * H) = r;
+                            const f32x4 r = {t.v[J * V + 4 * H + 0], t.v[J * V + 4 * H + 1], t.v[J * V + 4 * H + 2],
+                                             t.v[J * V + 4 * H + 3]};
+                            *(GLOBAL_AS f32x4_a4 *)(q + 16 * H) = r;
                         });
                     } else {
                         const u32x4 r = {pack_bf16x2(t.v[J * V + 0], t.v[J * V + 1]), pack_bf16x2(t.v[J * V + 2], t.v[J * V + 3]),

@@ -41,7 +41,7 @@ def gpu_ctx() -> B.Context:
 
 
 def program(desc) -> B.Program:
-    key = desc.name + repr(desc.ops)
+    key = repr((desc.name, desc.inputs, desc.ops, desc.outputs))
     if key not in _prog_cache:
         _prog_cache[key] = B.Program(desc)
     return _prog_cache[key]
