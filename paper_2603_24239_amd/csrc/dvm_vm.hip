@@ -797,6 +797,8 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     const uint32_t seg_words = w[PH_WORDS] - segs_off;
     if (seg_words > (uint32_t)CODE_WORDS) return dvm_set_error(DVM_E_LIMIT, "dvm_run: bytecode exceeds the kernel-argument budget");
 
+    if (w[PH_GRID] == 0) return DVM_OK;   // an empty iteration space: nothing to launch, pointers may be null
+
     KArgs ka;
     memcpy(ka.code, w + segs_off, (size_t)seg_words * 4);
     for (uint32_t i = 0; i < ntens; ++i) {
@@ -816,7 +818,6 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
         if (v.K == K && v.NR == NR) fn = v.fn;
     if (!fn) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
-    if (grid == 0) return DVM_OK;   // an empty iteration space: nothing to launch
     hipLaunchKernelGGL(fn, dim3(grid), dim3(block), 0, (hipStream_t)hip_stream, ka);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
