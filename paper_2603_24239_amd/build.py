@@ -4,7 +4,9 @@
 
 Flags: the interpreter is written for gfx950 only; packed-fp32 instructions are disabled
 (-packed-fp32-ops); the vector-combine pass is disabled because it splits the 128-bit global
-loads of the tile load handler into dword loads.
+loads of the tile load handler into dword loads; control flow that is uniform across a wave is
+left unstructured (the interpreter loop has no lane-divergent branch), which keeps the dispatch
+as plain scalar jumps and lets every instruction update its destination registers in place.
 """
 from __future__ import annotations
 
@@ -18,7 +20,7 @@ LIB = os.path.join(HERE, "libdvm.so")
 
 COMMON = ["-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-mllvm", "-disable-vector-combine"]
+          "-mllvm", "-disable-vector-combine", "-mllvm", "-structurizecfg-skip-uniform-regions=1"]
 
 
 def build(verbose: bool = True) -> str:

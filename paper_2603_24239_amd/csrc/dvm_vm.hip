@@ -324,20 +324,46 @@ DI int64_t row_offset(const Geo &g, int64_t s1, int64_t s2, int64_t s3) {
     return (int64_t)g.i1 * s1 + (int64_t)g.i2 * s2 + (int64_t)g.i3 * s3;
 }
 
+// Predicated stores.  The interpreter loop must not contain a branch that differs between the
+// lanes of a wave: with only wave-uniform branches the compiler keeps the dispatch as plain scalar
+// jumps and updates registers in place.  Loads therefore clamp the address of an invalid lane to
+// a valid one (its data is never used), and stores switch the invalid lanes off in EXEC inside
+// one assembly statement.
+DI void st_b128(gptr p, f32x4 v, bool ok) {
+    const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
+    uint64_t sv;
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dwordx4 %2, %3, off\n\ts_mov_b64 exec, %0"
+                 : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
+}
+DI void st_b32(gptr p, float v, bool ok) {
+    const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
+    uint64_t sv;
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dword %2, %3, off\n\ts_mov_b64 exec, %0"
+                 : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
+}
+DI void st_b16(gptr p, uint32_t v, bool ok) {
+    const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
+    uint64_t sv;
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_short %2, %3, off\n\ts_mov_b64 exec, %0"
+                 : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
+}
+
 // Load the lane's part of a tile as fp32.  DT: 0 = fp32, 1 = bf16.  V = chunk width.
-// `rowp` points at column `colbase` of the lane's row in this tensor.
+// `rowp` points at column `colbase` of the lane's row in this tensor (row 0 for a lane whose row
+// is outside the tensor).  A chunk that lies beyond the tile's columns reads the tile's chunk 0
+// instead: the value is never stored and reductions mask it.
 template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const Geo &g) {
     constexpr int ES = DT == 0 ? 4 : 2;
     static_assert(DT == 0 || V == 8, "bf16 tiles use 8-element chunks");
     tile_zero<K>(t);
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        gcptr p = rowp + (uint64_t)g.lanecol * ES;
-        sfor<NJ>([&]<int J>() LI {
-            if (J == 0 || (uint32_t)J < g.nvec) {
-                const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
-                if (g.rowok && c0 + V <= g.ncols) {
-                    gcptr q = p + (uint64_t)J * g.GV * ES;
+        if (g.ncols >= (uint32_t)V) {       // wave-uniform: the tile has at least one whole chunk
+            sfor<NJ>([&]<int J>() LI {
+                if (J == 0 || (uint32_t)J < g.nvec) {
+                    const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                    const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
+                    gcptr q = rowp + (uint64_t)cc * ES;
                     if constexpr (DT == 0) {
                         sfor<V / 4>([&]<int H>() LI {
                             const f32x4 r = *(const GLOBAL_AS f32x4_a4 *)(q + 16 * H);
@@ -355,17 +381,19 @@ template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const 
                         t.v[J * V + 6] = bf16_lo(w3); t.v[J * V + 7] = bf16_hi(w3);
                     }
                 }
-            }
-        });
+            });
+        }
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
-            const bool own = g.rowok && g.lr == g.part_lane;
+            const bool own = g.lr == g.part_lane;
             sfor<NJ>([&]<int J>() LI {
                 if ((uint32_t)J == g.part_slot) {
                     sfor<V>([&]<int E>() LI {
-                        if ((uint32_t)E < g.part_n && own) {
+                        if ((uint32_t)E < g.part_n) {       // wave-uniform
                             gcptr q = rowp + (uint64_t)(g.part_col + E) * ES;
-                            if constexpr (DT == 0) t.v[J * V + E] = *(const GLOBAL_AS float *)q;
-                            else t.v[J * V + E] = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
+                            float x;
+                            if constexpr (DT == 0) x = *(const GLOBAL_AS float *)q;
+                            else x = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
+                            t.v[J * V + E] = own ? x : t.v[J * V + E];
                         }
                     });
                 }
@@ -378,35 +406,35 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
     constexpr int ES = DT == 0 ? 4 : 2;
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        gptr p = rowp + (uint64_t)g.lanecol * ES;
-        sfor<NJ>([&]<int J>() LI {
-            if (J == 0 || (uint32_t)J < g.nvec) {
-                const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
-                if (g.rowok && c0 + V <= g.ncols) {
-                    gptr q = p + (uint64_t)J * g.GV * ES;
+        if (g.ncols >= (uint32_t)V) {
+            sfor<NJ>([&]<int J>() LI {
+                if (J == 0 || (uint32_t)J < g.nvec) {
+                    const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                    const bool ok = g.rowok && c0 + V <= g.ncols;
+                    gptr q = rowp + (uint64_t)c0 * ES;
                     if constexpr (DT == 0) {
                         sfor<V / 4>([&]<int H>() LI {
                             const f32x4 r = {t.v[J * V + 4 * H + 0], t.v[J * V + 4 * H + 1], t.v[J * V + 4 * H + 2],
                                              t.v[J * V + 4 * H + 3]};
-                            *(GLOBAL_AS f32x4_a4 *)(q + 16 * H) = r;
+                            st_b128(q + 16 * H, r, ok);
                         });
                     } else {
                         const u32x4 r = {pack_bf16x2(t.v[J * V + 0], t.v[J * V + 1]), pack_bf16x2(t.v[J * V + 2], t.v[J * V + 3]),
                                          pack_bf16x2(t.v[J * V + 4], t.v[J * V + 5]), pack_bf16x2(t.v[J * V + 6], t.v[J * V + 7])};
-                        *(GLOBAL_AS u32x4_a2 *)q = r;
+                        st_b128(q, __builtin_bit_cast(f32x4, r), ok);
                     }
                 }
-            }
-        });
+            });
+        }
         if (g.part_slot != ~0u) {
             const bool own = g.rowok && g.lr == g.part_lane;
             sfor<NJ>([&]<int J>() LI {
                 if ((uint32_t)J == g.part_slot) {
                     sfor<V>([&]<int E>() LI {
-                        if ((uint32_t)E < g.part_n && own) {
+                        if ((uint32_t)E < g.part_n) {       // wave-uniform
                             gptr q = rowp + (uint64_t)(g.part_col + E) * ES;
-                            if constexpr (DT == 0) *(GLOBAL_AS float *)q = t.v[J * V + E];
-                            else *(GLOBAL_AS uint16_t *)q = pack_bf16(t.v[J * V + E]);
+                            if constexpr (DT == 0) st_b32(q, t.v[J * V + E], own);
+                            else st_b16(q, (uint32_t)pack_bf16(t.v[J * V + E]), own);
                         }
                     });
                 }
@@ -660,11 +688,9 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
                         const int64_t off = row_offset(g, DVM_I64(pc + 2), DVM_I64(pc + 4), DVM_I64(pc + 6));
                         gcptr base = (gcptr)args.tensors[tbase + ti];
-                        float v = 0.0f;
-                        if (g.rowok) {
-                            if (dt == 0) v = *(const GLOBAL_AS float *)(base + off * 4);
-                            else v = bf16_lo(*(const GLOBAL_AS uint16_t *)(base + off * 2));
-                        }
+                        float v;       // a lane outside the tensor reads row 0: valid memory, value unused
+                        if (dt == 0) v = *(const GLOBAL_AS float *)(base + off * 4);
+                        else v = bf16_lo(*(const GLOBAL_AS uint16_t *)(base + off * 2));
                         DVM_SET_S(a, v);
                         break;
                     }
@@ -674,10 +700,9 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         const int64_t off = row_offset(g, DVM_I64(pc + 2), DVM_I64(pc + 4), DVM_I64(pc + 6));
                         gptr base = (gptr)args.tensors[tbase + ti];
                         const float v = DVM_GET_S(a);
-                        if (g.rowok && g.lr == 0 && g.colbase == 0) {
-                            if (dt == 0) *(GLOBAL_AS float *)(base + off * 4) = v;
-                            else *(GLOBAL_AS uint16_t *)(base + off * 2) = pack_bf16(v);
-                        }
+                        const bool ok = g.rowok && g.lr == 0 && g.colbase == 0;
+                        if (dt == 0) st_b32(base + off * 4, v, ok);
+                        else st_b16(base + off * 2, (uint32_t)pack_bf16(v), ok);
                         break;
                     }
                     case I_MOVRA:
@@ -710,7 +735,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                     case I_RED: {
                         const float v = reduce_dispatch<K>(acc, g, V, b, width);
                         if (gw > 1) {
-                            if ((tid & 63) == 0) red_lds[red_par][wave & 15] = v;
+                            red_lds[red_par][wave & 15] = v;     // every lane of the wave holds the same value
                         } else {
                             DVM_SET_S(a, v);
                         }
