@@ -10,7 +10,8 @@
 //
 //   program  := PH_WORDS header words | n_tensors * TT_WORDS tensor-table words | segment*
 //   segment  := SH_WORDS header words | body (S_CODESIZE words of instruction records)
-//   record   := word0 = op | len<<8 | a<<16 | b<<24, then len-1 operand words
+//   record   := word0 = op | len<<8 | a<<16 | b<<24, then len-1 operand words; len is 4 or 8: every
+//               record starts on a 16-byte boundary so that one scalar load fetches it whole
 //
 // The tile registers are the interpreter's local memory: an accumulator ACC and NR tile
 // registers R0.. of K fp32 elements per lane each, and NS row-scalar registers S0.. (one value
@@ -69,8 +70,11 @@ enum : int {
     S_NTENS,        // tensors of this segment
     S_FLAGS,        // SF_*
     S_IMASK,        // bit op -> the instruction id occurs in the body (for the disassembler)
+    S_PAD0, S_PAD1, // keep the body 16-byte aligned
     SH_WORDS
 };
+static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");
+constexpr int LEN_REC = 4;              // length of every record except the view forms
 constexpr uint32_t SF_WGSYNC  = 1u;     // rows span several waves: reductions use the barrier
 constexpr uint32_t SF_RAGGED  = 2u;     // some tile has invalid rows or columns: mask reductions
 
@@ -122,7 +126,7 @@ enum : uint32_t { R_SUM = 0, R_MAX, R_MIN, R_SUMSQ, R_COUNT };
 
 // I_SOP: word1 = kind | srckind << 8 | c << 16 ; word2 = immediate.  kind < 64: B_kind(S[b], x);
 // kind >= 64: U_(kind-64)(S[b]).  srckind 0: x = S[c]; 1: x = immediate.
-constexpr int LEN_SOP = 3;
+constexpr int LEN_SOP = 4;
 constexpr uint32_t SOP_UNARY = 64;
 
 inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
@@ -134,10 +138,10 @@ inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
 // compiled kernels' register use; 4 SIMDs per compute unit).
 struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
-    { 4, 2, 1024, 8}, { 4, 6, 1024, 5},
-    { 8, 2, 1024, 5}, { 8, 6,  512, 3},
-    {16, 2,  512, 3},
-    {32, 2,  256, 1},
+    { 4, 2, 1024, 8}, { 4, 6, 1024, 8},
+    { 8, 2, 1024, 7}, { 8, 6,  512, 4},
+    {16, 2,  512, 4},
+    {32, 2,  256, 2},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 

@@ -1103,10 +1103,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         switch (x.op) {
             case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
             case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
-            case I_BIN: body_words += x.a == SRC_IMM ? 2 : 1; break;
-            case I_SOP: body_words += LEN_SOP; break;
-            case I_RED: body_words += wgsync ? 3 : 1; break;
-            default: body_words += 1; break;
+            case I_RED: body_words += wgsync ? 3 * LEN_REC : LEN_REC; break;
+            default: body_words += LEN_REC; break;
         }
     }
     const size_t words = PH_WORDS_N + (size_t)E.n_acc * TT_WORDS + SH_WORDS + body_words;
@@ -1182,27 +1180,33 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             }
             case I_BIN:
                 imask |= 1u << I_BIN;
-                if (x.a == SRC_IMM) { *b++ = w0(I_BIN, 2, x.a, x.b); *b++ = bits_f32(x.imm); }
-                else *b++ = w0(I_BIN, 1, x.a, x.b);
+                b[0] = w0(I_BIN, LEN_REC, x.a, x.b);
+                b[1] = x.a == SRC_IMM ? bits_f32(x.imm) : 0u;
+                b += LEN_REC;
                 break;
             case I_SOP:
                 imask |= 1u << I_SOP;
-                *b++ = w0(I_SOP, LEN_SOP, x.a, x.b);
-                *b++ = (uint32_t)x.kind | ((uint32_t)x.srck << 8) | ((uint32_t)x.c << 16);
-                *b++ = x.srck == 1 ? bits_f32(x.imm) : 0u;
+                b[0] = w0(I_SOP, LEN_SOP, x.a, x.b);
+                b[1] = (uint32_t)x.kind | ((uint32_t)x.srck << 8) | ((uint32_t)x.c << 16);
+                b[2] = x.srck == 1 ? bits_f32(x.imm) : 0u;
+                b += LEN_SOP;
                 break;
             case I_RED:
                 imask |= 1u << I_RED;
-                *b++ = w0(I_RED, 1, x.a, x.b);
+                b[0] = w0(I_RED, LEN_REC, x.a, x.b);
+                b += LEN_REC;
                 if (wgsync) {           // rows span several waves: synchronise, then combine the partials
                     imask |= (1u << I_SYNC) | (1u << I_REDX);
-                    *b++ = w0(I_SYNC, 1, 0, 0);
-                    *b++ = w0(I_REDX, 1, x.a, x.b == R_SUMSQ ? (uint32_t)R_SUM : x.b);
+                    b[0] = w0(I_SYNC, LEN_REC, 0, 0);
+                    b += LEN_REC;
+                    b[0] = w0(I_REDX, LEN_REC, x.a, x.b == R_SUMSQ ? (uint32_t)R_SUM : x.b);
+                    b += LEN_REC;
                 }
                 break;
             default:
                 imask |= 1u << x.op;
-                *b++ = w0(x.op, 1, x.a, x.b);
+                b[0] = w0(x.op, LEN_REC, x.a, x.b);
+                b += LEN_REC;
                 break;
         }
     }
@@ -1306,8 +1310,8 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         while (pc < end) {
             const uint32_t x = w[pc];
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, bb = x >> 24;
-            if (l == 0 || pc + l > end) return bad("instruction length");
-            uint32_t want = 1;
+            if ((l != LEN_REC && l != LEN_VLOAD) || pc + l > end) return bad("instruction length");
+            uint32_t want = LEN_REC;
             switch (op) {
                 case I_LOAD: case I_VLOAD: case I_STORE: case I_VSTORE: {
                     want = (op == I_LOAD || op == I_STORE) ? LEN_LOAD : LEN_VLOAD;
@@ -1334,33 +1338,30 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     break;
                 }
                 case I_MOVRA: case I_MOVAR:
-                    if (l != 1 || !reg_ok(a, vr)) return bad("move");
+                    if (l != LEN_REC || !reg_ok(a, vr)) return bad("move");
                     break;
                 case I_UN:
-                    if (l != 1 || bb == 0 || bb >= U_COUNT) return bad("unary op");
+                    if (l != LEN_REC || bb == 0 || bb >= U_COUNT) return bad("unary op");
                     break;
                 case I_BIN:
                     if (bb == 0 || bb >= B_COUNT) return bad("binary op");
-                    if (a == SRC_IMM) { if (l != 2) return bad("binary op length"); }
-                    else {
-                        if (l != 1) return bad("binary op length");
-                        if (!(a == SRC_ACC || reg_ok(a, vr) || (a >= SRC_S0 && sreg_ok(a - SRC_S0)))) return bad("binary source");
-                    }
+                    if (l != LEN_REC) return bad("binary op length");
+                    if (!(a == SRC_IMM || a == SRC_ACC || reg_ok(a, vr) || (a >= SRC_S0 && sreg_ok(a - SRC_S0)))) return bad("binary source");
                     break;
                 case I_SEL:
-                    if (l != 1 || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("select");
+                    if (l != LEN_REC || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("select");
                     break;
                 case I_RED:
-                    if (l != 1 || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
+                    if (l != LEN_REC || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
                     if (G > 64) pending_red = true;
                     break;
                 case I_SYNC:
-                    if (l != 1) return bad("sync");
+                    if (l != LEN_REC) return bad("sync");
                     break;
                 case I_REDX:
-                    if (l != 1 || !sreg_ok(a) || bb >= R_SUMSQ) return bad("reduction combine");
+                    if (l != LEN_REC || !sreg_ok(a) || bb >= R_SUMSQ) return bad("reduction combine");
                     if (G <= 64 || !pending_red) return bad("reduction combine without partials");
-                    if (pc < at + SH_WORDS + 1 || (w[pc - 1] & 0xFF) != I_SYNC) return bad("reduction combine without barrier");
+                    if (pc < at + SH_WORDS + LEN_REC || (w[pc - LEN_REC] & 0xFF) != I_SYNC) return bad("reduction combine without barrier");
                     pending_red = false;
                     break;
                 case I_SOP: {
@@ -1372,7 +1373,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     break;
                 }
                 case I_NOP:
-                    if (l != 1) return bad("nop");
+                    if (l != LEN_REC) return bad("nop");
                     break;
                 default: return bad("unknown instruction id");
             }

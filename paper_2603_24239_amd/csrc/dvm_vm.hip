@@ -358,30 +358,38 @@ template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const 
     tile_zero<K>(t);
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
+        uint32_t lanecol = g.lanecol;
+        asm volatile("" : "+v"(lanecol));   // recompute the lane masks here instead of keeping them all live
         if (g.ncols >= (uint32_t)V) {       // wave-uniform: the tile has at least one whole chunk
-            sfor<NJ>([&]<int J>() LI {
-                if (J == 0 || (uint32_t)J < g.nvec) {
-                    const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+            // phase 1: request every chunk (all loads in flight together); phase 2: widen to fp32
+            if constexpr (DT == 0) {
+                f32x4 raw[NJ * (V / 4)];
+                sfor<NJ>([&]<int J>() LI {
+                    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
                     const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
                     gcptr q = rowp + (uint64_t)cc * ES;
-                    if constexpr (DT == 0) {
-                        sfor<V / 4>([&]<int H>() LI {
-                            const f32x4 r = *(const GLOBAL_AS f32x4_a4 *)(q + 16 * H);
-                            t.v[J * V + 4 * H + 0] = r.x;
-                            t.v[J * V + 4 * H + 1] = r.y;
-                            t.v[J * V + 4 * H + 2] = r.z;
-                            t.v[J * V + 4 * H + 3] = r.w;
-                        });
-                    } else {
-                        const u32x4 r = *(const GLOBAL_AS u32x4_a2 *)q;
-                        const uint32_t w0 = r.x, w1 = r.y, w2 = r.z, w3 = r.w;
-                        t.v[J * V + 0] = bf16_lo(w0); t.v[J * V + 1] = bf16_hi(w0);
-                        t.v[J * V + 2] = bf16_lo(w1); t.v[J * V + 3] = bf16_hi(w1);
-                        t.v[J * V + 4] = bf16_lo(w2); t.v[J * V + 5] = bf16_hi(w2);
-                        t.v[J * V + 6] = bf16_lo(w3); t.v[J * V + 7] = bf16_hi(w3);
-                    }
-                }
-            });
+                    sfor<V / 4>([&]<int H>() LI { raw[J * (V / 4) + H] = *(const GLOBAL_AS f32x4_a4 *)(q + 16 * H); });
+                });
+                sfor<NJ *(V / 4)>([&]<int Q>() LI {
+                    const f32x4 r = raw[Q];
+                    t.v[4 * Q + 0] = r.x; t.v[4 * Q + 1] = r.y; t.v[4 * Q + 2] = r.z; t.v[4 * Q + 3] = r.w;
+                });
+            } else {
+                u32x4 raw[NJ];
+                sfor<NJ>([&]<int J>() LI {
+                    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
+                    const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
+                    raw[J] = *(const GLOBAL_AS u32x4_a2 *)(rowp + (uint64_t)cc * ES);
+                });
+                sfor<NJ>([&]<int J>() LI {
+                    const u32x4 r = raw[J];
+                    const uint32_t w0 = r.x, w1 = r.y, w2 = r.z, w3 = r.w;
+                    t.v[J * V + 0] = bf16_lo(w0); t.v[J * V + 1] = bf16_hi(w0);
+                    t.v[J * V + 2] = bf16_lo(w1); t.v[J * V + 3] = bf16_hi(w1);
+                    t.v[J * V + 4] = bf16_lo(w2); t.v[J * V + 5] = bf16_hi(w2);
+                    t.v[J * V + 6] = bf16_lo(w3); t.v[J * V + 7] = bf16_hi(w3);
+                });
+            }
         }
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
             const bool own = g.lr == g.part_lane;
@@ -406,10 +414,12 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
     constexpr int ES = DT == 0 ? 4 : 2;
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
+        uint32_t lanecol = g.lanecol;
+        asm volatile("" : "+v"(lanecol));
         if (g.ncols >= (uint32_t)V) {
             sfor<NJ>([&]<int J>() LI {
-                if (J == 0 || (uint32_t)J < g.nvec) {
-                    const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                {
+                    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
                     const bool ok = g.rowok && c0 + V <= g.ncols;
                     gptr q = rowp + (uint64_t)c0 * ES;
                     if constexpr (DT == 0) {
@@ -502,6 +512,16 @@ template <int K> DI float reduce_dispatch(const Tile<K> &a, const Geo &g, uint32
     }
 }
 
+// Every record starts on a 16-byte boundary and is 4 or 8 words long, so one scalar 128-bit load
+// fetches a whole record (the view forms take a second one).  The record after the current one is
+// requested before the current handler runs, so that the scalar-cache latency of decoding overlaps
+// the vector work (the pipelining of decode and execute of Section 4.3).  The prefetch may reach
+// past the code body: it stays inside the kernel-argument struct.
+typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
+DI u32x4s fetch4(const uint32_t *code, uint32_t pc) {
+    return *(const u32x4s *)__builtin_assume_aligned(code + pc, 16);
+}
+
 DI float pick_s(float s0, float s1, float s2, float s3, uint32_t i) {
     float v = s0;
     v = i == 1 ? s1 : v;
@@ -546,7 +566,7 @@ DI uint32_t sdiv_u(uint32_t n, uint32_t m, uint32_t sh) {   // the same on wave-
         s2 = si_ == 2 ? sv_ : s2;           \
         s3 = si_ == 3 ? sv_ : s3;           \
     } while (0)
-#define DVM_I64(AT) ((int64_t)((uint64_t)code[(AT)] | ((uint64_t)code[(AT) + 1] << 32)))
+#define DVM_I64(LO, HI) ((int64_t)((uint64_t)(LO) | ((uint64_t)(HI) << 32)))
 
 template <int K, int NR, int MAXT>
 __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
@@ -637,23 +657,29 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                 g.ragged = g.ncols != g.nact * G;
             }
 
+            u32x4s nw = fetch4(code, body);
             for (uint32_t pc = body; pc < body_end;) {
-                const uint32_t w = code[pc];
+                const u32x4s cw = nw;
+                // (elements are copied to scalars first: bit-casting a vector element directly is miscompiled)
+                const uint32_t w = cw.x, cw1 = cw.y, cw2 = cw.z, cw3 = cw.w;
                 const uint32_t op = w & 0xFF, len = (w >> 8) & 0xFF, a = (w >> 16) & 0xFF, b = w >> 24;
+                const uint32_t cur = pc;
+                pc += len == LEN_VLOAD ? LEN_VLOAD : LEN_REC;
+                nw = fetch4(code, pc);
                 switch (op) {
                     case I_LOAD:
                     case I_VLOAD: {
-                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
-                        const int64_t st1 = DVM_I64(pc + 2);
-                        int64_t st2 = 0, st3 = 0;
+                        int64_t off = (int64_t)g.i1 * DVM_I64(cw2, cw3) + (int64_t)g.colbase;
                         if (op == I_VLOAD) {
-                            st2 = DVM_I64(pc + 4);
-                            st3 = DVM_I64(pc + 6);
+                            const u32x4s hw = fetch4(code, cur + 4);
+                            const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                            off += (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3);
                         }
                         const uint32_t es = dt == 0 ? 4 : 2;
                         gcptr base = (gcptr)args.tensors[tbase + ti];
-                        gcptr rowp = base + (row_offset(g, st1, st2, st3) + (int64_t)g.colbase) * es;
+                        gcptr rowp = base + off * es;
                         Tile<K> t;
                         load_dispatch<K>(t, dt, V, rowp, g);
                         if (a == SRC_ACC) {
@@ -665,17 +691,17 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                     }
                     case I_STORE:
                     case I_VSTORE: {
-                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
-                        const int64_t st1 = DVM_I64(pc + 2);
-                        int64_t st2 = 0, st3 = 0;
+                        int64_t off = (int64_t)g.i1 * DVM_I64(cw2, cw3) + (int64_t)g.colbase;
                         if (op == I_VSTORE) {
-                            st2 = DVM_I64(pc + 4);
-                            st3 = DVM_I64(pc + 6);
+                            const u32x4s hw = fetch4(code, cur + 4);
+                            const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                            off += (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3);
                         }
                         const uint32_t es = dt == 0 ? 4 : 2;
                         gptr base = (gptr)args.tensors[tbase + ti];
-                        gptr rowp = base + (row_offset(g, st1, st2, st3) + (int64_t)g.colbase) * es;
+                        gptr rowp = base + off * es;
                         Tile<K> t = acc;
                         if (a != SRC_ACC) {
                             DVM_WITH_R(a, rr, t = rr)
@@ -684,9 +710,11 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         break;
                     }
                     case I_LOADS: {
-                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
-                        const int64_t off = row_offset(g, DVM_I64(pc + 2), DVM_I64(pc + 4), DVM_I64(pc + 6));
+                        const u32x4s hw = fetch4(code, cur + 4);
+                        const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                        const int64_t off = row_offset(g, DVM_I64(cw2, cw3), DVM_I64(h0, h1), DVM_I64(h2, h3));
                         gcptr base = (gcptr)args.tensors[tbase + ti];
                         float v;       // a lane outside the tensor reads row 0: valid memory, value unused
                         if (dt == 0) v = *(const GLOBAL_AS float *)(base + off * 4);
@@ -695,9 +723,11 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         break;
                     }
                     case I_STORES: {
-                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
-                        const int64_t off = row_offset(g, DVM_I64(pc + 2), DVM_I64(pc + 4), DVM_I64(pc + 6));
+                        const u32x4s hw = fetch4(code, cur + 4);
+                        const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                        const int64_t off = row_offset(g, DVM_I64(cw2, cw3), DVM_I64(h0, h1), DVM_I64(h2, h3));
                         gptr base = (gptr)args.tensors[tbase + ti];
                         const float v = DVM_GET_S(a);
                         const bool ok = g.rowok && g.lr == 0 && g.colbase == 0;
@@ -721,7 +751,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                             const Tile<K> t = acc;
                             tile_bin_dispatch<K>(acc, t, b);
                         } else {
-                            const float s = a == SRC_IMM ? __builtin_bit_cast(float, code[pc + 1]) : DVM_GET_S(a - SRC_S0);
+                            const float s = a == SRC_IMM ? __builtin_bit_cast(float, cw1) : DVM_GET_S(a - SRC_S0);
                             tile_bins_dispatch<K>(acc, s, b);
                         }
                         break;
@@ -755,14 +785,14 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         break;
                     }
                     case I_SOP: {
-                        const uint32_t w1 = code[pc + 1];
+                        const uint32_t w1 = cw1;
                         const uint32_t kind = w1 & 0xFF, srck = (w1 >> 8) & 0xFF, c = (w1 >> 16) & 0xFF;
                         const float x = DVM_GET_S(b);
                         float r;
                         if (kind >= SOP_UNARY) {
                             r = un_dyn(kind - SOP_UNARY, x);
                         } else {
-                            const float y = srck == 1 ? __builtin_bit_cast(float, code[pc + 2]) : DVM_GET_S(c);
+                            const float y = srck == 1 ? __builtin_bit_cast(float, cw2) : DVM_GET_S(c);
                             r = bin_dyn(kind, x, y);
                         }
                         DVM_SET_S(a, r);
@@ -771,7 +801,6 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                     default:
                         break;
                 }
-                pc += len ? len : 1;
             }
         }
         seg += seg_words;
