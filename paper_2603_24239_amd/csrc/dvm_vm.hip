@@ -293,7 +293,7 @@ struct Geo {
     uint32_t i1, i2, i3;  // decomposition of the lane's row index over the outer dims
     uint32_t lanecol;     // first column of the lane's chunk 0, relative to colbase
     uint32_t lr;          // lane index within the row group
-    bool rowok;
+    uint32_t rowok;       // 1 when the lane's row lies inside the tensor
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -358,8 +358,7 @@ template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const 
     tile_zero<K>(t);
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        uint32_t lanecol = g.lanecol;
-        asm volatile("" : "+v"(lanecol));   // recompute the lane masks here instead of keeping them all live
+        const uint32_t lanecol = g.lanecol;
         if (g.ncols >= (uint32_t)V) {       // wave-uniform: the tile has at least one whole chunk
             // phase 1: request every chunk (all loads in flight together); phase 2: widen to fp32
             if constexpr (DT == 0) {
@@ -414,8 +413,7 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
     constexpr int ES = DT == 0 ? 4 : 2;
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        uint32_t lanecol = g.lanecol;
-        asm volatile("" : "+v"(lanecol));
+        const uint32_t lanecol = g.lanecol;
         if (g.ncols >= (uint32_t)V) {
             sfor<NJ>([&]<int J>() LI {
                 {
@@ -598,13 +596,13 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
         const uint32_t body = seg + SH_WORDS;
         const uint32_t body_end = body + code_size;
 
-        Geo g;
-        g.GV = G * V;
-        g.nvec = nvec;
-        g.nact = nvec * V;
+        Geo gt;
+        gt.GV = G * V;
+        gt.nvec = nvec;
+        gt.nact = nvec * V;
         const uint32_t rp = tid / G;            // row of the tile held by this lane
-        g.lr = tid - rp * G;
-        g.lanecol = g.lr * V;
+        gt.lr = tid - rp * G;
+        gt.lanecol = gt.lr * V;
         const uint32_t gw = G >> 6;             // waves per row when a row spans waves
         const uint32_t width = G < 64 ? G : 64;
         const uint32_t w0i = gw > 1 ? (wave / gw) * gw : wave;   // first wave of this lane's row
@@ -625,36 +623,36 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                     tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
                     tile_c = tile - tile_r * nct;
                 }
-                g.colbase = (uint64_t)tile_c * TC;
-                const uint64_t rem = D0 - g.colbase;
-                g.ncols = rem < TC ? (uint32_t)rem : TC;
+                gt.colbase = (uint64_t)tile_c * TC;
+                const uint64_t rem = D0 - gt.colbase;
+                gt.ncols = rem < TC ? (uint32_t)rem : TC;
                 const uint32_t row = tile_r * RP + rp;
-                g.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
-                const uint32_t rowc = g.rowok ? row : 0;
-                g.i1 = rowc; g.i2 = 0; g.i3 = 0;
+                gt.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
+                const uint32_t rowc = gt.rowok ? row : 0;
+                gt.i1 = rowc; gt.i2 = 0; gt.i3 = 0;
                 const uint32_t D1 = sh[S_D1];
                 if (D1 != 0) {
                     const uint32_t q = magic_div(rowc, sh[S_M1], sh[S_SH1]);
-                    g.i1 = rowc - q * D1;
-                    g.i2 = q;
+                    gt.i1 = rowc - q * D1;
+                    gt.i2 = q;
                     const uint32_t D2 = sh[S_D2];
                     if (D2 != 0) {
                         const uint32_t q2 = magic_div(q, sh[S_M2], sh[S_SH2]);
-                        g.i2 = q - q2 * D2;
-                        g.i3 = q2;
+                        gt.i2 = q - q2 * D2;
+                        gt.i3 = q2;
                     }
                 }
-                const uint32_t full_chunks = g.ncols / V;      // V is 4 or 8
-                g.part_n = g.ncols - full_chunks * V;
-                g.part_slot = ~0u;
-                g.part_lane = 0;
-                g.part_col = full_chunks * V;
-                if (g.part_n != 0) {
-                    g.part_slot = full_chunks / G;
-                    g.part_lane = full_chunks - g.part_slot * G;
+                const uint32_t full_chunks = V == 8 ? gt.ncols >> 3 : gt.ncols >> 2;      // V is 4 or 8
+                gt.part_n = gt.ncols - full_chunks * V;
+                gt.part_slot = ~0u;
+                gt.part_lane = 0;
+                gt.part_col = full_chunks * V;
+                if (gt.part_n != 0) {
+                    gt.part_slot = __builtin_amdgcn_readfirstlane(full_chunks / G);
+                    gt.part_lane = full_chunks - gt.part_slot * G;
                 }
                 // rows never mix in a reduction, so only invalid columns inside live chunks need a mask
-                g.ragged = g.ncols != g.nact * G;
+                gt.ragged = gt.ncols != gt.nact * G;
             }
 
             u32x4s nw = fetch4(code, body);
@@ -666,6 +664,27 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                 const uint32_t cur = pc;
                 pc += len == LEN_VLOAD ? LEN_VLOAD : LEN_REC;
                 nw = fetch4(code, pc);
+                // The handlers see the tile geometry through values the optimiser cannot trace back
+                // across iterations; otherwise it hoists every handler's address arithmetic and lane
+                // masks into the tile prologue and executes them for every tile, used or not.
+                Geo g = gt;
+                {
+                    uint32_t cb_lo = __builtin_amdgcn_readfirstlane((uint32_t)gt.colbase);
+                    uint32_t cb_hi = __builtin_amdgcn_readfirstlane((uint32_t)(gt.colbase >> 32));
+                    g.ncols = __builtin_amdgcn_readfirstlane(gt.ncols);
+                    g.GV = __builtin_amdgcn_readfirstlane(gt.GV);
+                    g.nvec = __builtin_amdgcn_readfirstlane(gt.nvec);
+                    g.nact = __builtin_amdgcn_readfirstlane(gt.nact);
+                    g.part_slot = __builtin_amdgcn_readfirstlane(gt.part_slot);
+                    g.part_lane = __builtin_amdgcn_readfirstlane(gt.part_lane);
+                    g.part_col = __builtin_amdgcn_readfirstlane(gt.part_col);
+                    g.part_n = __builtin_amdgcn_readfirstlane(gt.part_n);
+                    g.ragged = __builtin_amdgcn_readfirstlane(gt.ragged);
+                    asm volatile("" : "+s"(cb_lo), "+s"(cb_hi), "+s"(g.ncols), "+s"(g.GV), "+s"(g.nvec), "+s"(g.nact));
+                    asm volatile("" : "+s"(g.part_slot), "+s"(g.part_lane), "+s"(g.part_col), "+s"(g.part_n), "+s"(g.ragged));
+                    g.colbase = (uint64_t)cb_lo | ((uint64_t)cb_hi << 32);
+                }
+                asm volatile("" : "+v"(g.i1), "+v"(g.i2), "+v"(g.i3), "+v"(g.lanecol), "+v"(g.lr), "+v"(g.rowok));
                 switch (op) {
                     case I_LOAD:
                     case I_VLOAD: {
