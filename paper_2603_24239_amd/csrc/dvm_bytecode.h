@@ -92,9 +92,10 @@ enum : uint32_t {
     I_UN,        // ACC = U_b(ACC)
     I_BIN,       // ACC = B_b(ACC, src a)               src: R, S (Table 1: Broadcast of a row value), ACC, IMM
     I_SEL,       // ACC = ACC != 0 ? R[a] : R[b]        (Table 1: Select)
-    I_RED,       // S[a] = R_b over the row of ACC, part inside a wave
-    I_SYNC,      // workgroup barrier (inserted by the encoder between I_RED and I_REDX)
-    I_REDX,      // S[a] = R_b over the per-wave partials
+    I_RED,       // S[a] = post(R_b over the row of ACC); word1 = U_post, word2 = scale, word3 = shift:
+                 // post(x) = U_post(x * scale + shift), the row-scalar ops that directly follow a
+                 // reduction folded into its record.  When a row spans several waves the handler
+                 // synchronises the workgroup between the per-wave part and the combination.
     I_SOP,       // S[a] = op(S[b], S[c] | imm)
     I_COUNT
 };

@@ -460,7 +460,7 @@ struct AI {                 // abstract instruction before emission
     uint8_t op, a, b, c;
     uint8_t kind, srck;
     int16_t tensor;
-    float imm;
+    float imm, imm2;
 };
 
 struct Enc {
@@ -494,6 +494,28 @@ struct Enc {
         if (n_ai >= MAX_AI) { fail(DVM_E_LIMIT, "too many instructions"); return; }
         AI &x = ai[n_ai++];
         x.op = op; x.a = a; x.b = b; x.c = c; x.kind = kind; x.srck = srck; x.tensor = (int16_t)tensor; x.imm = imm;
+        x.imm2 = 0.0f;
+    }
+    // Row-scalar op on the value a reduction has just produced, that value being used nowhere
+    // else: fold it into the reduction's record as post(x) = U(x * scale + shift).
+    // what: 0 = multiply by imm, 1 = add imm, 2 = unary uop.  srck of the RED record tracks the
+    // stage reached (0 nothing, 1 scaled, 2 shifted, 3 unary applied).
+    bool fold_into_red(int src_sreg, int what, float v, uint8_t uop) {
+        if (n_ai == 0) return false;
+        AI &r = ai[n_ai - 1];
+        if (r.op != I_RED || r.a != src_sreg) return false;
+        if (what == 0 && r.srck <= 1) { r.imm *= v; r.srck = 1; return true; }
+        if (what == 0 && r.srck == 2) { r.imm *= v; r.imm2 *= v; return true; }
+        if (what == 1 && r.srck <= 2) { r.imm2 += v; r.srck = 2; return true; }
+        if (what == 2 && r.srck <= 2) { r.kind = uop; r.srck = 3; return true; }
+        return false;
+    }
+    // the folded result takes over the source's S register
+    void take_over_sreg(int src_node, int dst_node) {
+        const int sr = sreg_of[src_node];
+        sreg_of[src_node] = -1;
+        sregs[sr] = dst_node;
+        sreg_of[dst_node] = sr;
     }
     int alloc_reg(int node) {
         for (int i = 0; i < NR_MAX; ++i)
@@ -853,6 +875,11 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             case N_UN:
                 if (rows) {
                     const int sa = E.sreg(nd.a);
+                    if (E.uses[nd.a] == 1 && E.fold_into_red(sa, 2, 0.0f, nd.op)) {
+                        E.take_over_sreg(nd.a, n);
+                        E.use(nd.a);
+                        break;
+                    }
                     E.use(nd.a);
                     const int sd = E.alloc_sreg(n);
                     E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, 0.0f, (uint8_t)(SOP_UNARY + nd.op), 0, 0);
@@ -867,6 +894,12 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             case N_BINI:
                 if (rows) {
                     const int sa = E.sreg(nd.a);
+                    if (E.uses[nd.a] == 1 && (nd.op == B_MUL || nd.op == B_ADD) &&
+                        E.fold_into_red(sa, nd.op == B_MUL ? 0 : 1, imm, 0)) {
+                        E.take_over_sreg(nd.a, n);
+                        E.use(nd.a);
+                        break;
+                    }
                     E.use(nd.a);
                     const int sd = E.alloc_sreg(n);
                     E.emit(I_SOP, (uint8_t)sd, (uint8_t)sa, -1, imm, nd.op, 1, 0);
@@ -904,10 +937,14 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                     E.preserve(a, 1);
                     E.use(a);
                     if (op == B_DIV) {              // tile / row value = tile * (1 / row value)
-                        const int st = E.alloc_sreg(-1);
-                        E.emit(I_SOP, (uint8_t)st, (uint8_t)sb, -1, 0.0f, (uint8_t)(SOP_UNARY + U_RCP), 0, 0);
-                        E.emit(I_BIN, (uint8_t)(SRC_S0 + st), (uint8_t)B_MUL);
-                        E.sregs[st] = -1;
+                        if (E.uses[b] == 1 && E.fold_into_red(sb, 2, 0.0f, U_RCP)) {
+                            E.emit(I_BIN, (uint8_t)(SRC_S0 + sb), (uint8_t)B_MUL);
+                        } else {
+                            const int st = E.alloc_sreg(-1);
+                            E.emit(I_SOP, (uint8_t)st, (uint8_t)sb, -1, 0.0f, (uint8_t)(SOP_UNARY + U_RCP), 0, 0);
+                            E.emit(I_BIN, (uint8_t)(SRC_S0 + st), (uint8_t)B_MUL);
+                            E.sregs[st] = -1;
+                        }
                     } else {
                         E.emit(I_BIN, (uint8_t)(SRC_S0 + sb), (uint8_t)op);
                     }
@@ -975,7 +1012,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 }
                 E.to_acc(nd.a);
                 const int sd = E.alloc_sreg(n);
-                E.emit(I_RED, (uint8_t)sd, nd.op);
+                E.emit(I_RED, (uint8_t)sd, nd.op, -1, 1.0f, (uint8_t)U_NONE, 0, 0);
                 E.use(nd.a);
                 break;
             }
@@ -1103,7 +1140,6 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         switch (x.op) {
             case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
             case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
-            case I_RED: body_words += wgsync ? 3 * LEN_REC : LEN_REC; break;
             default: body_words += LEN_REC; break;
         }
     }
@@ -1194,14 +1230,10 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             case I_RED:
                 imask |= 1u << I_RED;
                 b[0] = w0(I_RED, LEN_REC, x.a, x.b);
+                b[1] = x.kind;                  // post unary op (U_NONE: none)
+                b[2] = bits_f32(x.imm);         // scale
+                b[3] = bits_f32(x.imm2);        // shift
                 b += LEN_REC;
-                if (wgsync) {           // rows span several waves: synchronise, then combine the partials
-                    imask |= (1u << I_SYNC) | (1u << I_REDX);
-                    b[0] = w0(I_SYNC, LEN_REC, 0, 0);
-                    b += LEN_REC;
-                    b[0] = w0(I_REDX, LEN_REC, x.a, x.b == R_SUMSQ ? (uint32_t)R_SUM : x.b);
-                    b += LEN_REC;
-                }
                 break;
             default:
                 imask |= 1u << x.op;
@@ -1306,7 +1338,6 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         // body
         size_t pc = at + SH_WORDS;
         const size_t end = pc + cs;
-        bool pending_red = false;
         while (pc < end) {
             const uint32_t x = w[pc];
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, bb = x >> 24;
@@ -1353,16 +1384,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     break;
                 case I_RED:
                     if (l != LEN_REC || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
-                    if (G > 64) pending_red = true;
-                    break;
-                case I_SYNC:
-                    if (l != LEN_REC) return bad("sync");
-                    break;
-                case I_REDX:
-                    if (l != LEN_REC || !sreg_ok(a) || bb >= R_SUMSQ) return bad("reduction combine");
-                    if (G <= 64 || !pending_red) return bad("reduction combine without partials");
-                    if (pc < at + SH_WORDS + LEN_REC || (w[pc - LEN_REC] & 0xFF) != I_SYNC) return bad("reduction combine without barrier");
-                    pending_red = false;
+                    if (w[pc + 1] >= U_COUNT) return bad("reduction post op");
                     break;
                 case I_SOP: {
                     if (l != LEN_SOP || !sreg_ok(a) || !sreg_ok(bb)) return bad("row-scalar op");
@@ -1379,7 +1401,6 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             }
             pc += l;
         }
-        if (pending_red) return bad("reduction partials never combined");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");
@@ -1592,9 +1613,11 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
                     break;
                 case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
-                case I_RED: o.put("  %04zu red.%-5s s%u = acc\n", pc - at - SH_WORDS, RED_NAMES[b], a); break;
-                case I_SYNC: o.put("  %04zu sync\n", pc - at - SH_WORDS); break;
-                case I_REDX: o.put("  %04zu redx.%-4s s%u\n", pc - at - SH_WORDS, RED_NAMES[b], a); break;
+                case I_RED:
+                    o.put("  %04zu red.%-5s s%u = %s(acc * %.9g + %.9g)%s\n", pc - at - SH_WORDS, RED_NAMES[b], a,
+                          w[pc + 1] ? UN_NAMES[w[pc + 1]] : "", (double)f32_bits(w[pc + 2]), (double)f32_bits(w[pc + 3]),
+                          (sh[S_GEOM] & 0xFFFF) > 64 ? "  [workgroup sync]" : "");
+                    break;
                 case I_SOP: {
                     const uint32_t w1 = w[pc + 1];
                     const uint32_t kind = w1 & 0xFF, srck = (w1 >> 8) & 0xFF, c = (w1 >> 16) & 0xFF;

@@ -664,9 +664,11 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                 const uint32_t cur = pc;
                 pc += len == LEN_VLOAD ? LEN_VLOAD : LEN_REC;
                 nw = fetch4(code, pc);
-                // The handlers see the tile geometry through values the optimiser cannot trace back
-                // across iterations; otherwise it hoists every handler's address arithmetic and lane
-                // masks into the tile prologue and executes them for every tile, used or not.
+                // The handlers must see the tile geometry through values the optimiser cannot trace
+                // back across iterations; otherwise it hoists every handler's address arithmetic
+                // and lane masks into the tile prologue and executes them for every tile, used or
+                // not.  The empty statements below pin each value to its register at no cost.
+                asm volatile("" : "+v"(gt.i1), "+v"(gt.i2), "+v"(gt.i3), "+v"(gt.lanecol), "+v"(gt.lr), "+v"(gt.rowok));
                 Geo g = gt;
                 {
                     uint32_t cb_lo = __builtin_amdgcn_readfirstlane((uint32_t)gt.colbase);
@@ -684,7 +686,6 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                     asm volatile("" : "+s"(g.part_slot), "+s"(g.part_lane), "+s"(g.part_col), "+s"(g.part_n), "+s"(g.ragged));
                     g.colbase = (uint64_t)cb_lo | ((uint64_t)cb_hi << 32);
                 }
-                asm volatile("" : "+v"(g.i1), "+v"(g.i2), "+v"(g.i3), "+v"(g.lanecol), "+v"(g.lr), "+v"(g.rowok));
                 switch (op) {
                     case I_LOAD:
                     case I_VLOAD: {
@@ -782,25 +783,23 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         break;
                     }
                     case I_RED: {
-                        const float v = reduce_dispatch<K>(acc, g, V, b, width);
+                        float v = reduce_dispatch<K>(acc, g, V, b, width);
                         if (gw > 1) {
+                            // a row spans gw waves: exchange the per-wave results through LDS.  Two
+                            // buffers alternate, so one barrier per reduction is enough.
                             red_lds[red_par][wave & 15] = v;     // every lane of the wave holds the same value
-                        } else {
-                            DVM_SET_S(a, v);
+                            __syncthreads();
+                            v = red_lds[red_par][w0i & 15];
+                            for (uint32_t i = 1; i < gw; ++i) {
+                                const float o = red_lds[red_par][(w0i + i) & 15];
+                                v = b == R_MAX ? __builtin_fmaxf(v, o) : (b == R_MIN ? __builtin_fminf(v, o) : v + o);
+                            }
+                            red_par ^= 1;
                         }
-                        break;
-                    }
-                    case I_SYNC:
-                        __syncthreads();
-                        break;
-                    case I_REDX: {
-                        float v = red_lds[red_par][w0i & 15];
-                        for (uint32_t i = 1; i < gw; ++i) {
-                            const float o = red_lds[red_par][(w0i + i) & 15];
-                            v = b == R_MAX ? __builtin_fmaxf(v, o) : (b == R_MIN ? __builtin_fminf(v, o) : v + o);
-                        }
+                        // the row-scalar ops folded into this record: U(v * scale + shift)
+                        v = f_fma(v, __builtin_bit_cast(float, cw2), __builtin_bit_cast(float, cw3));
+                        if (cw1 != U_NONE) v = un_dyn(cw1, v);
                         DVM_SET_S(a, v);
-                        red_par ^= 1;
                         break;
                     }
                     case I_SOP: {
