@@ -70,7 +70,8 @@ enum : int {
     S_NTENS,        // tensors of this segment
     S_FLAGS,        // SF_*
     S_IMASK,        // bit op -> the instruction id occurs in the body (for the disassembler)
-    S_PAD0, S_PAD1, // keep the body 16-byte aligned
+    S_PROLOG,       // words at the start of the body that run once per workgroup, before its first tile
+    S_PAD1,         // keeps the body 16-byte aligned
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");
@@ -141,7 +142,7 @@ struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
     { 4, 2, 1024, 8}, { 4, 6, 1024, 8},
     { 8, 2, 1024, 7}, { 8, 6,  512, 4},
-    {16, 2,  512, 4},
+    {16, 2,  512, 4}, {16, 4, 1024, 4},
     {32, 2,  256, 2},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);

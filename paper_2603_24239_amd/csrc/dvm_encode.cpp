@@ -478,7 +478,7 @@ struct Enc {
     bool has_red;
     // linearisation
     AI ai[MAX_AI];
-    int n_ai;
+    int n_ai, n_prolog;
     int uses[MAX_NODES];
     int reg_of[MAX_NODES], sreg_of[MAX_NODES];
     int regs[NR_MAX], sregs[NS];
@@ -814,6 +814,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     (void)g0_is_row;
 
     // ---- 4. linearise ---------------------------------------------------------------------------
+    auto linearize = [&](int hoist_budget) {
     memset(E.uses, 0, sizeof(E.uses));
     for (int n = 0; n < NN; ++n) {
         const Node &nd = prog->nodes[n];
@@ -833,6 +834,25 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     // input tensors that are row values by layout (see above) make their nodes row values too
     for (int n = 0; n < NN; ++n)
         if (prog->nodes[n].kind == N_IN && E.acc[prog->nodes[n].input].rows) E.rows_class[n] = true;
+
+    // Tile-invariant operands (every outer stride zero: a weight vector broadcast over the rows) are
+    // loaded once per workgroup into a pinned tile register by a prologue that runs before the
+    // first tile, instead of once per tile.
+    E.n_prolog = 0;
+    for (int n = 0, left = hoist_budget; n < NN && left > 0; ++n) {
+        const Node &nd = prog->nodes[n];
+        if (nd.kind != N_IN || E.rows_class[n] || E.uses[n] == 0) continue;
+        const Access &A = E.acc[nd.input];
+        if (A.s[1] != 0 || A.s[2] != 0 || A.s[3] != 0) continue;
+        bool is_out = false;
+        for (int o = 0; o < prog->n_out; ++o) is_out |= prog->out_node[o] == n;
+        if (is_out) continue;
+        const int r = E.alloc_reg(n);
+        E.emit(I_LOAD, (uint8_t)r, (uint8_t)B_NONE, nd.input);
+        E.uses[n] += 1 << 20;           // pinned: never released
+        --left;
+    }
+    E.n_prolog = E.n_ai;
 
     auto store_outputs = [&](int n) {
         for (int o = 0; o < prog->n_out; ++o) {
@@ -1020,6 +1040,15 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         }
         if (!E.err) store_outputs(n);
     }
+    };
+    // first without hoisting, to learn how many tile registers the body needs; then, in row mode,
+    // again with as many pinned operands as keep the program within four tile registers
+    linearize(0);
+    if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < 4) {
+        const int body_regs = E.nr_used;
+        linearize(4 - body_regs);
+        if (E.err || E.nr_used > 4) { E.err = nullptr; linearize(0); }
+    }
     if (E.err) return dvm_set_error(E.err_code, E.err);
 
     // ---- 5. tile plan ---------------------------------------------------------------------------
@@ -1133,10 +1162,11 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
 
     // ---- 6. emit ---------------------------------------------------------------------------
     // size first
-    size_t body_words = 0;
+    size_t body_words = 0, prolog_words = 0;
     const bool view = ng > 2;       // more than one outer group: rows need the multi-stride form
     for (int i = 0; i < E.n_ai; ++i) {
         const AI &x = E.ai[i];
+        if (i == E.n_prolog) prolog_words = body_words;
         switch (x.op) {
             case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
             case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
@@ -1190,6 +1220,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_TBASE] = 0;
     sh[S_NTENS] = (uint32_t)E.n_acc;
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
+    sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     uint32_t imask = 0;
     uint32_t *b = sh + SH_WORDS;
     auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
@@ -1332,6 +1363,8 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             magic_u32(nct, &m, &sft);
             if (m != sh[S_NCTM] || sft != sh[S_NCTSH]) return bad("division constants of the column tiles");
         }
+        if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
+        bool prolog_ends_on_record = sh[S_PROLOG] == 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
         if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
         tiles_total += M;
@@ -1342,6 +1375,8 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             const uint32_t x = w[pc];
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, bb = x >> 24;
             if ((l != LEN_REC && l != LEN_VLOAD) || pc + l > end) return bad("instruction length");
+            if (pc + l == at + SH_WORDS + sh[S_PROLOG]) prolog_ends_on_record = true;
+            if (pc < at + SH_WORDS + sh[S_PROLOG] && op != I_LOAD && op != I_VLOAD) return bad("prologue holds loads only");
             uint32_t want = LEN_REC;
             switch (op) {
                 case I_LOAD: case I_VLOAD: case I_STORE: case I_VSTORE: {
@@ -1401,6 +1436,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             }
             pc += l;
         }
+        if (!prolog_ends_on_record) return bad("prologue does not end on a record boundary");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");
@@ -1575,7 +1611,9 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
               (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE]);
         size_t pc = at + SH_WORDS;
         const size_t end = pc + sh[S_CODESIZE];
+        if (sh[S_PROLOG]) o.put("  ; prologue (once per workgroup)\n");
         while (pc < end) {
+            if (sh[S_PROLOG] && pc == at + SH_WORDS + sh[S_PROLOG]) o.put("  ; body (once per tile)\n");
             const uint32_t x = w[pc];
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, b = x >> 24;
             char ra[8], rb[8];

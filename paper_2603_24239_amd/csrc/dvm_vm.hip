@@ -655,8 +655,10 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                 gt.ragged = gt.ncols != gt.nact * G;
             }
 
-            u32x4s nw = fetch4(code, body);
-            for (uint32_t pc = body; pc < body_end;) {
+            // the first tile of this workgroup also runs the prologue records (pinned operands)
+            const uint32_t first = tile == t_lo ? body : body + sh[S_PROLOG];
+            u32x4s nw = fetch4(code, first);
+            for (uint32_t pc = first; pc < body_end;) {
                 const u32x4s cw = nw;
                 // (elements are copied to scalars first: bit-casting a vector element directly is miscompiled)
                 const uint32_t w = cw.x, cw1 = cw.y, cw2 = cw.z, cw3 = cw.w;
@@ -835,7 +837,7 @@ struct VariantEntry { int K, NR; vm_kernel_t fn; };
 const VariantEntry g_variants[] = {
     { 4, 2, dvm_vm_kernel< 4, 2, 1024>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024>},
     { 8, 2, dvm_vm_kernel< 8, 2, 1024>}, { 8, 6, dvm_vm_kernel< 8, 6,  512>},
-    {16, 2, dvm_vm_kernel<16, 2,  512>},
+    {16, 2, dvm_vm_kernel<16, 2,  512>}, {16, 4, dvm_vm_kernel<16, 4, 1024>},
     {32, 2, dvm_vm_kernel<32, 2,  256>},
 };
 
