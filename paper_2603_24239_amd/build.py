@@ -20,7 +20,8 @@ LIB = os.path.join(HERE, "libdvm.so")
 
 COMMON = ["-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
 DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-          "-mllvm", "-disable-vector-combine", "-mllvm", "-structurizecfg-skip-uniform-regions=1"]
+          "-mllvm", "-disable-vector-combine", "-mllvm", "-structurizecfg-skip-uniform-regions=1",
+          "-mllvm", "-simplifycfg-sink-common=false"]
 
 
 def build(verbose: bool = True) -> str:

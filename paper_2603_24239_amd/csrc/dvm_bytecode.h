@@ -71,7 +71,7 @@ enum : int {
     S_FLAGS,        // SF_*
     S_IMASK,        // bit op -> the instruction id occurs in the body (for the disassembler)
     S_PROLOG,       // words at the start of the body that run once per workgroup, before its first tile
-    S_PAD1,         // keeps the body 16-byte aligned
+    S_PIPEBYTES,    // bytes of workgroup memory per thread that the pipelined load stages its data in (0: none)
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");
@@ -105,6 +105,9 @@ enum : uint32_t {
 constexpr int LEN_LOAD  = 4;            // word0, word1, s1
 constexpr int LEN_VLOAD = 8;            // word0, word1, s1, s2, s3
 constexpr uint32_t MF_ALIGNED16 = 1u;   // every chunk of this tensor starts on a 16-byte boundary
+constexpr uint32_t MF_PIPELINED = 2u;   // load only: the record consumes what it requested one tile earlier and
+                                        // requests the next tile's data (at most one such record per segment);
+                                        // the data waits in workgroup memory, S_PIPEBYTES per thread
 
 // source / destination selectors
 constexpr uint32_t SRC_R0  = 0;         // 0 .. NR-1
@@ -140,9 +143,9 @@ inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
 // compiled kernels' register use; 4 SIMDs per compute unit).
 struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
-    { 4, 2, 1024, 8}, { 4, 6, 1024, 8},
-    { 8, 2, 1024, 7}, { 8, 6,  512, 4},
-    {16, 2,  512, 4}, {16, 4, 1024, 4},
+    { 4, 2, 1024, 8}, { 4, 6, 1024, 7},
+    { 8, 2, 1024, 5}, { 8, 6,  512, 4},
+    {16, 2, 1024, 4}, {16, 4, 1024, 4},
     {32, 2,  256, 2},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);

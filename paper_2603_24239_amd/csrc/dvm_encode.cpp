@@ -84,6 +84,11 @@ struct dvm_ctx {
     int device;
     int n_cu;
     int overhead;   // per-tile overhead of the cost model, in elements
+    // tuning aids, settable through environment variables read once at dvm_ctx_create
+    int pipeline;   // DVM_DEBUG_PIPELINE=0 switches the one-tile-ahead load off
+    int dbg_k;      // DVM_DEBUG_K: preferred elements per lane (0 = planner's choice)
+    int dbg_grid_x; // DVM_DEBUG_GRIDX: workgroups launched per resident slot (default 1)
+    int dbg_rp;     // DVM_DEBUG_RP: rows per tile (0 = cost model)
 };
 
 extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
@@ -93,6 +98,12 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->device = hip_device;
     c->n_cu = 256;          // MI355X
     c->overhead = 512;
+    const char *e;
+    c->pipeline = (e = getenv("DVM_DEBUG_PIPELINE")) ? atoi(e) : 0;
+    c->dbg_k = (e = getenv("DVM_DEBUG_K")) ? atoi(e) : 0;
+    c->dbg_grid_x = (e = getenv("DVM_DEBUG_GRIDX")) ? atoi(e) : 1;
+    c->dbg_rp = (e = getenv("DVM_DEBUG_RP")) ? atoi(e) : 0;
+    if (c->dbg_grid_x < 1) c->dbg_grid_x = 1;
     if (hip_device >= 0) {
         int n = 0;
         int st = dvm_ctx_query_device(hip_device, &n);
@@ -1043,11 +1054,17 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     };
     // first without hoisting, to learn how many tile registers the body needs; then, in row mode,
     // again with as many pinned operands as keep the program within four tile registers
+    // (rows long enough for 32 elements per lane keep to the two tile registers of that variant:
+    // fewer interpreted records per element outweigh reloading a row vector from cache)
     linearize(0);
-    if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < 4) {
-        const int body_regs = E.nr_used;
-        linearize(4 - body_regs);
-        if (E.err || E.nr_used > 4) { E.err = nullptr; linearize(0); }
+    {
+        const int64_t lanes32 = cdiv(cdiv(E.D0 > 0 ? E.D0 : 1, any_bf16_full ? 8 : 4), any_bf16_full ? 4 : 8);
+        const int reg_cap = (lanes32 >= 128 && E.nr_used <= 2 && ctx->dbg_k != 16) ? 2 : 4;
+        if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap) {
+            const int body_regs = E.nr_used;
+            linearize(reg_cap - body_regs);
+            if (E.err || E.nr_used > reg_cap) { E.err = nullptr; linearize(0); }
+        }
     }
     if (E.err) return dvm_set_error(E.err_code, E.err);
 
@@ -1076,14 +1093,21 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (!column_mode) {
         const int ks[4] = {4, 8, 16, 32};
         int pick = -1;
-        for (int i = 0; i < 4; ++i) {           // the largest K up to 16 that still spreads a row over >= 16 lanes
+        // the largest K that still spreads a row over >= 16 lanes (K = 32: over two whole waves, since
+        // that variant keeps only two waves per SIMD resident); fewer lanes per row mean fewer
+        // interpreted records per element
+        for (int i = 0; i < 4; ++i) {
             const int K = ks[i];
-            if ((uint32_t)K < V || K > 16) continue;
+            if ((uint32_t)K < V) continue;
             const int v = find_variant(K);
             if (v < 0) continue;
             const int64_t gneed = cdiv(Cr, K / V);
             if (gneed > VARIANTS[v].max_threads) continue;
-            if (pick < 0 || gneed >= 16) pick = v;
+            if (pick < 0 || gneed >= (K == 32 ? 128 : 16)) pick = v;
+        }
+        if (ctx->dbg_k >= (int)V) {
+            const int v = find_variant(ctx->dbg_k);
+            if (v >= 0 && cdiv(Cr, ctx->dbg_k / V) <= VARIANTS[v].max_threads) pick = v;
         }
         if (pick < 0) {                         // long rows: more elements per lane
             for (int i = 0; i < 4 && pick < 0; ++i) {
@@ -1118,6 +1142,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 const int64_t cost = cdiv(tiles, N) * ((int64_t)rp * (E.D0 > 0 ? E.D0 : 1) + ovh);
                 if (best_cost < 0 || cost <= best_cost) { best_cost = cost; RP = rp; }
             }
+            if (ctx->dbg_rp > 0 && (uint32_t)ctx->dbg_rp % step == 0 && (uint32_t)ctx->dbg_rp * G <= (uint32_t)vr.max_threads)
+                RP = (uint32_t)ctx->dbg_rp;
         }
     }
     if (column_mode) {
@@ -1157,7 +1183,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     const int64_t M64 = total == 0 ? 0 : cdiv(E.nrows, RP) * nct;
     if (M64 >= (1ll << 31)) return dvm_set_error(DVM_E_LIMIT, "more than 2^31 tiles");
     const int64_t Nslots = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
-    const uint32_t grid = (uint32_t)(M64 < Nslots ? M64 : Nslots);
+    const int64_t Ngrid = Nslots * ctx->dbg_grid_x;
+    const uint32_t grid = (uint32_t)(M64 < Ngrid ? M64 : Ngrid);
     const bool wgsync = G > 64;
 
     // ---- 6. emit ---------------------------------------------------------------------------
@@ -1222,6 +1249,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     uint32_t imask = 0;
+    bool pipelined = false;
     uint32_t *b = sh + SH_WORDS;
     auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
     for (int i = 0; i < E.n_ai; ++i) {
@@ -1232,7 +1260,14 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 const uint32_t op = view ? (x.op == I_LOAD ? I_VLOAD : I_VSTORE) : x.op;
                 imask |= 1u << op;
                 *b++ = w0(op, view ? LEN_VLOAD : LEN_LOAD, x.a, x.b);
-                *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8);
+                // the first load of the body runs one tile ahead when some workgroup has several tiles
+                uint32_t mflags = 0;
+                if (x.op == I_LOAD && i >= E.n_prolog && !pipelined && ctx->pipeline && M64 > (int64_t)grid) {
+                    mflags |= MF_PIPELINED;
+                    pipelined = true;
+                    sh[S_PIPEBYTES] = (uint32_t)vr.K * (A.dtype == DVM_BF16 ? 2u : 4u);
+                }
+                *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8) | (mflags << 16);
                 put_i64(A.s[1]);
                 if (view) { put_i64(A.s[2]); put_i64(A.s[3]); }
                 break;
@@ -1365,6 +1400,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         }
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
         bool prolog_ends_on_record = sh[S_PROLOG] == 0;
+        int n_pipelined = 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
         if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
         tiles_total += M;
@@ -1390,6 +1426,11 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
                     if ((op == I_STORE || op == I_VSTORE) && !((info >> 8) & 1)) return bad("store to an input tensor");
                     if (((w1 >> 8) & 0xFF) == DVM_BF16 && V != 8) return bad("bf16 tile with 4-element chunks");
+                    if ((w1 >> 16) & ~MF_PIPELINED) return bad("memory flags");
+                    if ((w1 >> 16) & MF_PIPELINED) {
+                        if ((op != I_LOAD && op != I_VLOAD) || pc < at + SH_WORDS + sh[S_PROLOG] || n_pipelined++) return bad("pipelined load");
+                        if (sh[S_PIPEBYTES] != (uint32_t)vr->K * (((w1 >> 8) & 0xFF) == DVM_BF16 ? 2u : 4u)) return bad("pipelined load staging size");
+                    }
                     break;
                 }
                 case I_LOADS: case I_STORES: {
@@ -1437,6 +1478,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             pc += l;
         }
         if (!prolog_ends_on_record) return bad("prologue does not end on a record boundary");
+        if (n_pipelined == 0 && sh[S_PIPEBYTES] != 0) return bad("staging memory without a pipelined load");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");
@@ -1622,11 +1664,12 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
             auto i64 = [&](size_t i) { return (long long)((uint64_t)w[i] | ((uint64_t)w[i + 1] << 32)); };
             switch (op) {
                 case I_LOAD:
-                    o.put("  %04zu load    %s %s= t%u stride=%lld\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "", w[pc + 1] & 0xFF, i64(pc + 2));
+                    o.put("  %04zu load    %s %s= t%u stride=%lld%s\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "", w[pc + 1] & 0xFF, i64(pc + 2),
+                          ((w[pc + 1] >> 16) & MF_PIPELINED) ? "  [one tile ahead]" : "");
                     break;
                 case I_VLOAD:
-                    o.put("  %04zu viewload %s %s= t%u strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "",
-                          w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6));
+                    o.put("  %04zu viewload %s %s= t%u strides=[%lld,%lld,%lld]%s\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "",
+                          w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6), ((w[pc + 1] >> 16) & MF_PIPELINED) ? "  [one tile ahead]" : "");
                     break;
                 case I_STORE:
                     o.put("  %04zu store   t%u = %s stride=%lld\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2));

@@ -348,40 +348,58 @@ DI void st_b16(gptr p, uint32_t v, bool ok) {
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 
-// Load the lane's part of a tile as fp32.  DT: 0 = fp32, 1 = bf16.  V = chunk width.
-// `rowp` points at column `colbase` of the lane's row in this tensor (row 0 for a lane whose row
-// is outside the tensor).  A chunk that lies beyond the tile's columns reads the tile's chunk 0
-// instead: the value is never stored and reductions mask it.
-template <int K, int DT, int V> DI void load_tile(Tile<K> &t, gcptr rowp, const Geo &g) {
+// Loading the lane's part of a tile has two halves: request_tile puts every whole chunk in flight
+// (raw bits, 16 bytes per chunk half), and widen_tile turns the raw bits into fp32 once they are
+// needed.  A plain load runs them back to back; a pipelined load runs the request one tile early.
+// DT: 0 = fp32, 1 = bf16.  V = chunk width.  `rowp` points at column `colbase` of the lane's row in
+// this tensor (row 0 for a lane whose row is outside the tensor).  A chunk that lies beyond the
+// tile's columns reads the tile's chunk 0 instead: the value is never stored and reductions mask it.
+template <int K> struct Raw { f32x4 q[K / 4]; };
+typedef f32x4 f32x4_a2 __attribute__((aligned(2)));
+
+// One code path for every dtype and chunk width (wave-uniform `dt` and `V` only enter the address
+// arithmetic): 16-byte piece Q of the lane belongs to chunk Q (bf16, and fp32 with 4-element
+// chunks) or to half Q&1 of chunk Q>>1 (fp32 with 8-element chunks).  `sink.operator()<Q>(address)`
+// starts the transfer of piece Q.
+template <int K, class Sink> DI void request_tile(uint32_t dt, uint32_t V, gcptr rowp, const Geo &g, Sink &&sink) {
+    const uint32_t halves = (dt == 0 && V == 8) ? 1u : 0u;
+    const uint32_t npieces = dt == 0 ? (uint32_t)(K / 4) : (uint32_t)(K / 8);
+    const uint32_t esh = dt == 0 ? 2u : 1u;
+    if ((uint32_t)K >= V && g.ncols >= V) {     // wave-uniform: the tile has at least one whole chunk
+        sfor<K / 4>([&]<int Q>() LI {
+            if ((uint32_t)Q < npieces) {        // wave-uniform
+                const uint32_t j = (uint32_t)Q >> halves, h = (uint32_t)Q & halves;
+                const uint32_t c0 = g.lanecol + j * g.GV;
+                const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
+                sink.template operator()<Q>(rowp + (((uint64_t)cc << esh) + 16u * h));
+            }
+        });
+    }
+}
+
+// Global memory -> workgroup memory without passing through registers: lane l of the wave puts its
+// 16 bytes at byte address m0 + 16 * l.  The transfer is counted by vmcnt like any other load; the
+// compiler does not know of it, so the reader waits explicitly (lds_transfers_wait).
+DI void lds_transfer_b128(gcptr p, uint32_t lds_byte_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte_addr), "v"(p) : "memory");
+}
+DI void lds_transfers_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
+
+template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw, gcptr rowp, const Geo &g) {
     constexpr int ES = DT == 0 ? 4 : 2;
-    static_assert(DT == 0 || V == 8, "bf16 tiles use 8-element chunks");
-    tile_zero<K>(t);
+    if constexpr (K < V) tile_zero<K>(t);
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        const uint32_t lanecol = g.lanecol;
-        if (g.ncols >= (uint32_t)V) {       // wave-uniform: the tile has at least one whole chunk
-            // phase 1: request every chunk (all loads in flight together); phase 2: widen to fp32
+        if (g.ncols < (uint32_t)V) tile_zero<K>(t);     // narrower than one chunk: only the ragged part below
+        if (g.ncols >= (uint32_t)V) {
             if constexpr (DT == 0) {
-                f32x4 raw[NJ * (V / 4)];
-                sfor<NJ>([&]<int J>() LI {
-                    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
-                    const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
-                    gcptr q = rowp + (uint64_t)cc * ES;
-                    sfor<V / 4>([&]<int H>() LI { raw[J * (V / 4) + H] = *(const GLOBAL_AS f32x4_a4 *)(q + 16 * H); });
-                });
                 sfor<NJ *(V / 4)>([&]<int Q>() LI {
-                    const f32x4 r = raw[Q];
+                    const f32x4 r = raw.q[Q];
                     t.v[4 * Q + 0] = r.x; t.v[4 * Q + 1] = r.y; t.v[4 * Q + 2] = r.z; t.v[4 * Q + 3] = r.w;
                 });
             } else {
-                u32x4 raw[NJ];
                 sfor<NJ>([&]<int J>() LI {
-                    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
-                    const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
-                    raw[J] = *(const GLOBAL_AS u32x4_a2 *)(rowp + (uint64_t)cc * ES);
-                });
-                sfor<NJ>([&]<int J>() LI {
-                    const u32x4 r = raw[J];
+                    const u32x4 r = __builtin_bit_cast(u32x4, raw.q[J]);
                     const uint32_t w0 = r.x, w1 = r.y, w2 = r.z, w3 = r.w;
                     t.v[J * V + 0] = bf16_lo(w0); t.v[J * V + 1] = bf16_hi(w0);
                     t.v[J * V + 2] = bf16_lo(w1); t.v[J * V + 3] = bf16_hi(w1);
@@ -451,12 +469,12 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
     }
 }
 
-template <int K> DI void load_dispatch(Tile<K> &t, uint32_t dt, uint32_t V, gcptr rowp, const Geo &g) {
+template <int K> DI void widen_dispatch(Tile<K> &t, const Raw<K> &raw, uint32_t dt, uint32_t V, gcptr rowp, const Geo &g) {
     if (dt == 0) {
-        if (V == 4) load_tile<K, 0, 4>(t, rowp, g);
-        else load_tile<K, 0, 8>(t, rowp, g);
+        if (V == 4) widen_tile<K, 0, 4>(t, raw, rowp, g);
+        else widen_tile<K, 0, 8>(t, raw, rowp, g);
     } else {
-        load_tile<K, 1, 8>(t, rowp, g);
+        widen_tile<K, 1, 8>(t, raw, rowp, g);
     }
 }
 template <int K> DI void store_dispatch(const Tile<K> &t, uint32_t dt, uint32_t V, gptr rowp, const Geo &g) {
@@ -539,6 +557,38 @@ DI uint32_t sdiv_u(uint32_t n, uint32_t m, uint32_t sh) {   // the same on wave-
     return (t + ((n - t) >> (sh & 0xFF))) >> (sh >> 8);
 }
 
+// Where tile number `tile` of a segment sits: its first column and width (wave-uniform), and the
+// lane's row decomposed over the outer iteration dims.  `rp` is the row of the tile this lane holds.
+DI void tile_place(Geo &gt, const uint32_t *sh, uint32_t tile, uint32_t rp, uint32_t tid, uint32_t RP, uint32_t seg_threads) {
+    const uint32_t nct = sh[S_NCT], TC = sh[S_TC];
+    const uint64_t D0 = (uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32);
+    const uint32_t nrows = sh[S_NROWS];
+    uint32_t tile_r = tile, tile_c = 0;
+    if (nct > 1) {
+        tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
+        tile_c = tile - tile_r * nct;
+    }
+    gt.colbase = (uint64_t)tile_c * TC;
+    const uint64_t rem = D0 - gt.colbase;
+    gt.ncols = rem < TC ? (uint32_t)rem : TC;
+    const uint32_t row = tile_r * RP + rp;
+    gt.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
+    const uint32_t rowc = gt.rowok ? row : 0;
+    gt.i1 = rowc; gt.i2 = 0; gt.i3 = 0;
+    const uint32_t D1 = sh[S_D1];
+    if (D1 != 0) {
+        const uint32_t q = magic_div(rowc, sh[S_M1], sh[S_SH1]);
+        gt.i1 = rowc - q * D1;
+        gt.i2 = q;
+        const uint32_t D2 = sh[S_D2];
+        if (D2 != 0) {
+            const uint32_t q2 = magic_div(q, sh[S_M2], sh[S_SH2]);
+            gt.i2 = q - q2 * D2;
+            gt.i3 = q2;
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // the interpreter
 // ------------------------------------------------------------------------------------------
@@ -566,6 +616,30 @@ DI uint32_t sdiv_u(uint32_t n, uint32_t m, uint32_t sh) {   // the same on wave-
     } while (0)
 #define DVM_I64(LO, HI) ((int64_t)((uint64_t)(LO) | ((uint64_t)(HI) << 32)))
 
+// The handlers that use the tile geometry must see it through values the optimiser cannot trace
+// back across iterations; otherwise it hoists their address arithmetic and lane masks into the
+// tile prologue and executes them for every tile, used or not.  The empty assembly statements pin
+// each value to its register at no cost.  Handlers that work on registers only skip all of this.
+#define DVM_GEO()                                                                                             \
+    asm volatile("" : "+v"(gt.i1), "+v"(gt.i2), "+v"(gt.i3), "+v"(gt.lanecol), "+v"(gt.lr), "+v"(gt.rowok));   \
+    Geo g = gt;                                                                                               \
+    {                                                                                                         \
+        uint32_t cb_lo = __builtin_amdgcn_readfirstlane((uint32_t)gt.colbase);                                \
+        uint32_t cb_hi = __builtin_amdgcn_readfirstlane((uint32_t)(gt.colbase >> 32));                        \
+        g.ncols = __builtin_amdgcn_readfirstlane(gt.ncols);                                                   \
+        g.GV = __builtin_amdgcn_readfirstlane(gt.GV);                                                         \
+        g.nvec = __builtin_amdgcn_readfirstlane(gt.nvec);                                                     \
+        g.nact = __builtin_amdgcn_readfirstlane(gt.nact);                                                     \
+        g.part_slot = __builtin_amdgcn_readfirstlane(gt.part_slot);                                           \
+        g.part_lane = __builtin_amdgcn_readfirstlane(gt.part_lane);                                           \
+        g.part_col = __builtin_amdgcn_readfirstlane(gt.part_col);                                             \
+        g.part_n = __builtin_amdgcn_readfirstlane(gt.part_n);                                                 \
+        g.ragged = __builtin_amdgcn_readfirstlane(gt.ragged);                                                 \
+        asm volatile("" : "+s"(cb_lo), "+s"(cb_hi), "+s"(g.ncols), "+s"(g.GV), "+s"(g.nvec), "+s"(g.nact));   \
+        asm volatile("" : "+s"(g.part_slot), "+s"(g.part_lane), "+s"(g.part_col), "+s"(g.part_n), "+s"(g.ragged)); \
+        g.colbase = (uint64_t)cb_lo | ((uint64_t)cb_hi << 32);                                                \
+    }
+
 template <int K, int NR, int MAXT>
 __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
     __shared__ float red_lds[2][16];
@@ -575,9 +649,14 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
     tile_zero<K>(acc); tile_zero<K>(r0); tile_zero<K>(r1); tile_zero<K>(r2);
     tile_zero<K>(r3); tile_zero<K>(r4); tile_zero<K>(r5);
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
+    // raw bits of the tile that the pipelined load record requested one tile ahead: piece Q of wave
+    // w occupies 1 KiB at pf_lds[(Q * waves + w) * 64], one 16-byte slot per lane
+    extern __shared__ f32x4 pf_lds[];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid) >> 6;
+    const uint32_t nwaves = (blockDim.x + 63) >> 6;
+    const uint32_t pf_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)pf_lds);
     const uint32_t bid = blockIdx.x;
     const uint32_t ngrid = gridDim.x;
     uint32_t red_par = 0;
@@ -615,33 +694,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
 
         for (uint32_t tile = t_lo; tile < t_hi; ++tile) {
             {   // tile prologue: where this tile sits, which of its lanes and chunks are valid
-                const uint32_t nct = sh[S_NCT], TC = sh[S_TC];
-                const uint64_t D0 = (uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32);
-                const uint32_t nrows = sh[S_NROWS];
-                uint32_t tile_r = tile, tile_c = 0;
-                if (nct > 1) {
-                    tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
-                    tile_c = tile - tile_r * nct;
-                }
-                gt.colbase = (uint64_t)tile_c * TC;
-                const uint64_t rem = D0 - gt.colbase;
-                gt.ncols = rem < TC ? (uint32_t)rem : TC;
-                const uint32_t row = tile_r * RP + rp;
-                gt.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
-                const uint32_t rowc = gt.rowok ? row : 0;
-                gt.i1 = rowc; gt.i2 = 0; gt.i3 = 0;
-                const uint32_t D1 = sh[S_D1];
-                if (D1 != 0) {
-                    const uint32_t q = magic_div(rowc, sh[S_M1], sh[S_SH1]);
-                    gt.i1 = rowc - q * D1;
-                    gt.i2 = q;
-                    const uint32_t D2 = sh[S_D2];
-                    if (D2 != 0) {
-                        const uint32_t q2 = magic_div(q, sh[S_M2], sh[S_SH2]);
-                        gt.i2 = q - q2 * D2;
-                        gt.i3 = q2;
-                    }
-                }
+                tile_place(gt, sh, tile, rp, tid, RP, seg_threads);
                 const uint32_t full_chunks = V == 8 ? gt.ncols >> 3 : gt.ncols >> 2;      // V is 4 or 8
                 gt.part_n = gt.ncols - full_chunks * V;
                 gt.part_slot = ~0u;
@@ -666,53 +719,65 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                 const uint32_t cur = pc;
                 pc += len == LEN_VLOAD ? LEN_VLOAD : LEN_REC;
                 nw = fetch4(code, pc);
-                // The handlers must see the tile geometry through values the optimiser cannot trace
-                // back across iterations; otherwise it hoists every handler's address arithmetic
-                // and lane masks into the tile prologue and executes them for every tile, used or
-                // not.  The empty statements below pin each value to its register at no cost.
-                asm volatile("" : "+v"(gt.i1), "+v"(gt.i2), "+v"(gt.i3), "+v"(gt.lanecol), "+v"(gt.lr), "+v"(gt.rowok));
-                Geo g = gt;
-                {
-                    uint32_t cb_lo = __builtin_amdgcn_readfirstlane((uint32_t)gt.colbase);
-                    uint32_t cb_hi = __builtin_amdgcn_readfirstlane((uint32_t)(gt.colbase >> 32));
-                    g.ncols = __builtin_amdgcn_readfirstlane(gt.ncols);
-                    g.GV = __builtin_amdgcn_readfirstlane(gt.GV);
-                    g.nvec = __builtin_amdgcn_readfirstlane(gt.nvec);
-                    g.nact = __builtin_amdgcn_readfirstlane(gt.nact);
-                    g.part_slot = __builtin_amdgcn_readfirstlane(gt.part_slot);
-                    g.part_lane = __builtin_amdgcn_readfirstlane(gt.part_lane);
-                    g.part_col = __builtin_amdgcn_readfirstlane(gt.part_col);
-                    g.part_n = __builtin_amdgcn_readfirstlane(gt.part_n);
-                    g.ragged = __builtin_amdgcn_readfirstlane(gt.ragged);
-                    asm volatile("" : "+s"(cb_lo), "+s"(cb_hi), "+s"(g.ncols), "+s"(g.GV), "+s"(g.nvec), "+s"(g.nact));
-                    asm volatile("" : "+s"(g.part_slot), "+s"(g.part_lane), "+s"(g.part_col), "+s"(g.part_n), "+s"(g.ragged));
-                    g.colbase = (uint64_t)cb_lo | ((uint64_t)cb_hi << 32);
-                }
                 switch (op) {
                     case I_LOAD:
                     case I_VLOAD: {
+                        DVM_GEO()
                         const uint32_t w1 = cw1;
-                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
-                        int64_t off = (int64_t)g.i1 * DVM_I64(cw2, cw3) + (int64_t)g.colbase;
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF, pipe = (w1 >> 16) & MF_PIPELINED;
+                        const int64_t st1 = DVM_I64(cw2, cw3);
+                        int64_t st2 = 0, st3 = 0;
                         if (op == I_VLOAD) {
                             const u32x4s hw = fetch4(code, cur + 4);
                             const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
-                            off += (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3);
+                            st2 = DVM_I64(h0, h1);
+                            st3 = DVM_I64(h2, h3);
                         }
+                        int64_t off = (int64_t)g.i1 * st1 + (int64_t)g.colbase;
+                        if (op == I_VLOAD) off += (int64_t)g.i2 * st2 + (int64_t)g.i3 * st3;
                         const uint32_t es = dt == 0 ? 4 : 2;
                         gcptr base = (gcptr)args.tensors[tbase + ti];
                         gcptr rowp = base + off * es;
-                        Tile<K> t;
-                        load_dispatch<K>(t, dt, V, rowp, g);
-                        if (a == SRC_ACC) {
-                            tile_bin_dispatch<K>(acc, t, b);
+                        Raw<K> raw;
+                        uint32_t tl = tile;
+                        asm volatile("" : "+s"(tl));     // keeps the next tile's arithmetic inside this handler
+                        const auto to_lds = [&]<int Q>(gcptr p) LI { lds_transfer_b128(p, pf_base + ((Q * nwaves + wave) << 10)); };
+                        if (pipe) {
+                            // this tile's data was requested while the previous tile was being
+                            // computed (by this record); only a workgroup's first tile asks now
+                            if (tl == t_lo) request_tile<K>(dt, V, rowp, g, to_lds);
+                            lds_transfers_wait();
+                            const uint32_t npieces = dt == 0 ? (uint32_t)(K / 4) : (uint32_t)(K / 8);
+                            sfor<K / 4>([&]<int Q>() LI {
+                                if ((uint32_t)Q < npieces) raw.q[Q] = pf_lds[(Q * nwaves + wave) * 64 + (tid & 63)];
+                            });
                         } else {
-                            DVM_WITH_R(a, rr, rr = t)
+                            request_tile<K>(dt, V, rowp, g, [&]<int Q>(gcptr p) LI { raw.q[Q] = *(const GLOBAL_AS f32x4_a2 *)p; });
+                        }
+                        // widen straight into the destination register
+                        if (a == SRC_ACC) {
+                            if (b == B_NONE) {
+                                widen_dispatch<K>(acc, raw, dt, V, rowp, g);
+                            } else {
+                                Tile<K> t;
+                                widen_dispatch<K>(t, raw, dt, V, rowp, g);
+                                tile_bin_dispatch<K>(acc, t, b);
+                            }
+                        } else {
+                            DVM_WITH_R(a, rr, widen_dispatch<K>(rr, raw, dt, V, rowp, g))
+                        }
+                        if (pipe && tl + 1 < t_hi) {
+                            Geo gn = g;
+                            tile_place(gn, sh, tl + 1, rp, tid, RP, seg_threads);
+                            int64_t offn = (int64_t)gn.i1 * st1 + (int64_t)gn.colbase;
+                            if (op == I_VLOAD) offn += (int64_t)gn.i2 * st2 + (int64_t)gn.i3 * st3;
+                            request_tile<K>(dt, V, base + offn * es, gn, to_lds);
                         }
                         break;
                     }
                     case I_STORE:
                     case I_VSTORE: {
+                        DVM_GEO()
                         const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
                         int64_t off = (int64_t)g.i1 * DVM_I64(cw2, cw3) + (int64_t)g.colbase;
@@ -724,14 +789,15 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         const uint32_t es = dt == 0 ? 4 : 2;
                         gptr base = (gptr)args.tensors[tbase + ti];
                         gptr rowp = base + off * es;
-                        Tile<K> t = acc;
-                        if (a != SRC_ACC) {
-                            DVM_WITH_R(a, rr, t = rr)
+                        if (a == SRC_ACC) {
+                            store_dispatch<K>(acc, dt, V, rowp, g);
+                        } else {
+                            DVM_WITH_R(a, rr, store_dispatch<K>(rr, dt, V, rowp, g))
                         }
-                        store_dispatch<K>(t, dt, V, rowp, g);
                         break;
                     }
                     case I_LOADS: {
+                        DVM_GEO()
                         const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
                         const u32x4s hw = fetch4(code, cur + 4);
@@ -745,6 +811,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         break;
                     }
                     case I_STORES: {
+                        DVM_GEO()
                         const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
                         const u32x4s hw = fetch4(code, cur + 4);
@@ -785,6 +852,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         break;
                     }
                     case I_RED: {
+                        DVM_GEO()
                         float v = reduce_dispatch<K>(acc, g, V, b, width);
                         if (gw > 1) {
                             // a row spans gw waves: exchange the per-wave results through LDS.  Two
@@ -837,7 +905,7 @@ struct VariantEntry { int K, NR; vm_kernel_t fn; };
 const VariantEntry g_variants[] = {
     { 4, 2, dvm_vm_kernel< 4, 2, 1024>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024>},
     { 8, 2, dvm_vm_kernel< 8, 2, 1024>}, { 8, 6, dvm_vm_kernel< 8, 6,  512>},
-    {16, 2, dvm_vm_kernel<16, 2,  512>}, {16, 4, dvm_vm_kernel<16, 4, 1024>},
+    {16, 2, dvm_vm_kernel<16, 2, 1024>}, {16, 4, dvm_vm_kernel<16, 4, 1024>},
     {32, 2, dvm_vm_kernel<32, 2,  256>},
 };
 
@@ -892,7 +960,12 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
         if (v.K == K && v.NR == NR) fn = v.fn;
     if (!fn) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), 0, (hipStream_t)hip_stream, ka);
+    // workgroup memory for the pipelined loads: every thread stages S_PIPEBYTES of the next tile
+    uint32_t pipe_bytes = 0;
+    for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s, at += w[at + S_WORDS])
+        if (w[at + S_PIPEBYTES] > pipe_bytes) pipe_bytes = w[at + S_PIPEBYTES];
+    const uint32_t waves = (block + 63) / 64;
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), (size_t)waves * 64 * pipe_bytes, (hipStream_t)hip_stream, ka);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;
