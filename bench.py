@@ -29,6 +29,23 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 
+# rocprofv3 summaries of this command (kernel trace and the two HBM byte counters) per workload
+PROFILE_SUMMARY = {"c2_rmsnorm": "profiles/dvm_vm_kernel_c2_rmsnorm.md", "c4_chain": "profiles/dvm_vm_kernel_c4_chain.md"}
+
+
+def measured_traffic(workload: str):
+    """HBM bytes per interpreter launch from the committed counter summary (FETCH_SIZE + WRITE_SIZE, each scaled
+    by what the same counter reads for a plain copy of known size), or None if there is no such summary."""
+    path = os.path.join(ROOT, PROFILE_SUMMARY.get(workload, ""))
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(line.split(":", 1)[1])
+    except (OSError, ValueError):
+        pass
+    return None
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -38,6 +55,9 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_rmsnorm", choices=["c2_rmsnorm", "c4_chain"])
     ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region run a plain 256 MiB device copy (a known-size kernel that scales "
+                         "the HBM byte counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (the path needs no exchange between devices); "
@@ -129,6 +149,13 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = perf() - t_begin
 
+    if args.calibrate_copy:
+        src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     ms_per_step = elapsed / args.steps * 1e3
     value = total_bytes * args.steps / elapsed / 1e9
     kern_ms = [a.elapsed_time(b) for evs in all_events for (a, b) in evs]
@@ -156,7 +183,8 @@ def main() -> int:
         "roofline": {"bound": "hbm", "kernel": "dvm_vm_kernel (bytecode interpreter)", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(avg_launch_ms, 5),
-                     "launches": len(kern_ms), "traffic": None},
+                     "launches": len(kern_ms),
+                     "traffic": measured_traffic(args.workload) if not args.instances else None},
     }
 
     # ---- the CPU oracle on a bounded sample of the same workload (a baseline, not the target) -----

@@ -1,0 +1,160 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py times.
+
+The oracle cannot evaluate multi-gigabyte instances in seconds, but every program on the path is
+independent per row of the reduced (last) axis, so the oracle evaluates a seeded sample of rows
+(the first and last rows always among them) and the HIP result is compared on exactly those rows,
+element by element, to the same tolerance as the small cases.
+"""
+from __future__ import annotations
+
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from workloads import gen
+from workloads import programs as W
+
+from . import harness as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def sample_rows(n_rows: int, k: int, seed: int) -> torch.Tensor:
+    rng = np.random.default_rng(seed)
+    pick = set(rng.integers(0, n_rows, size=min(k, n_rows)).tolist()) | {0, n_rows - 1}
+    return torch.tensor(sorted(pick), dtype=torch.long)
+
+
+def check_rows(desc, ins_rows, outs_rows, what):
+    rounded, exact = H.run_oracle(desc, ins_rows)
+    red = H.has_reduction(desc)
+    worst = 0.0
+    for n, dt in desc.outputs:
+        worst = max(worst, H.compare(outs_rows[n], rounded[n], exact[n], dt, red, f"{what}:{n}"))
+    return worst
+
+
+def test_c2_rmsnorm_largest_instance():
+    shapes = gen.c2_shapes()
+    B, S = max(shapes, key=lambda bs: bs[0] * bs[1])
+    say(f"c2 rmsnorm full size B={B} S={S}")
+    d = gen.c2_inputs(B, S, gen.BASE_SEED + 2999, DEV)
+    desc = W.get_program("c2_rmsnorm")
+    outs, code = H.run_vm(desc, d)
+    y = outs["y"].reshape(B * S, 4096)
+    x = d["x"].reshape(B * S, 4096)
+    rows = sample_rows(B * S, 192, 1).to(DEV)
+    check_rows(desc, {"x": x[rows], "w": d["w"]}, {"y": y[rows]}, "c2 full")
+
+
+def test_c4_chain_largest_instance():
+    T = max(gen.c4_shapes())
+    say(f"c4 chain full size T={T}")
+    d = gen.c4_inputs(T, gen.BASE_SEED + 4999, DEV)
+    desc = W.get_program("c4_chain")
+    outs, code = H.run_vm(desc, d)
+    rows = sample_rows(T, 96, 2).to(DEV)
+    ins = {k: (v[rows] if v.dim() == 2 else v) for k, v in d.items()}
+    check_rows(desc, ins, {"y": outs["y"][rows]}, "c4 full")
+
+
+def test_c3_masked_softmax_large_instance():
+    # the largest S of the stream with B = 1: 32 * S rows of S fp32 scores (about 2 GiB in, 2 GiB out)
+    S = max(s for _, s in gen.c3_shapes())
+    say(f"c3 masked softmax full size B=1 S={S}")
+    d = gen.c3_inputs(1, S, gen.BASE_SEED + 3999, DEV)
+    desc = W.get_program("c3_masked_softmax")
+    outs, code = H.run_vm(desc, d)
+    out_name = desc.outputs[0][0]
+    p = outs[out_name].reshape(32 * S, S)
+    z = d["z"].reshape(32 * S, S)
+    rows = sample_rows(32 * S, 128, 3).to(DEV)
+    mrows = d["mask"][rows % S]
+    check_rows(desc, {"z": z[rows], "mask": mrows}, {out_name: p[rows]}, "c3 full")
+    # masked positions are exactly zero, every row sums to one
+    assert torch.all(p[rows][mrows == float("-inf")] == 0)
+    assert torch.allclose(p[rows].sum(-1), torch.ones(len(rows), device=DEV), atol=1e-5)
+    del outs, d, p, z
+    torch.cuda.empty_cache()
+
+
+def test_c5_layer_at_max_tokens():
+    T = 8192
+    say(f"c5 programs full size T={T}")
+    d = gen.c5_inputs(T, gen.BASE_SEED + 5999, DEV)
+    rows = sample_rows(T, 48, 4).to(DEV)
+    for name, key in [("c5_rmsnorm", "c5_rmsnorm"), ("c5_residual", "c5_residual_a"), ("c5_silu_gate", "c5_silu_gate")]:
+        desc = W.get_program(name)
+        outs, _ = H.run_vm(desc, d[key])
+        ins = {k: (v[rows] if v.dim() == 2 else v) for k, v in d[key].items()}
+        check_rows(desc, ins, {n: outs[n][rows] for n, _ in desc.outputs}, f"c5 full {name}")
+        del outs
+    say("c5 rope full size (views)")
+    desc = W.get_program("c5_rope")
+    out = torch.full((T, 32, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    views = {"y1": out[..., :64], "y2": out[..., 64:]}
+    H.run_vm(desc, d["c5_rope"], views)
+    assert not torch.isnan(out.float()).any()
+    ins = {k: v[rows] for k, v in d["c5_rope"].items()}
+    check_rows(desc, ins, {"y1": out[rows][..., :64], "y2": out[rows][..., 64:]}, "c5 full rope")
+    del out
+    say("c5 softmax full size [32, T, T//8+1]")
+    desc = W.get_program("c5_softmax")
+    z = d["c5_softmax"]["z"]
+    outs, _ = H.run_vm(desc, {"z": z})
+    L = T // 8 + 1
+    out_name = desc.outputs[0][0]
+    r2 = sample_rows(32 * T, 96, 5).to(DEV)
+    check_rows(desc, {"z": z.reshape(32 * T, L)[r2]}, {out_name: outs[out_name].reshape(32 * T, L)[r2]}, "c5 full softmax")
+    del outs, d
+    torch.cuda.empty_cache()
+
+
+def test_one_tile_ahead_loads_match(monkeypatch):
+    """The optional pipelined load (the record asks for the next tile's data while the current tile
+    is computed) gives the same results as the plain load."""
+    from paper_2603_24239_amd import binding as B
+    monkeypatch.setenv("DVM_DEBUG_PIPELINE", "1")
+    ctx = B.Context(torch.cuda.current_device())
+    monkeypatch.delenv("DVM_DEBUG_PIPELINE")
+    plain = H.gpu_ctx()
+
+    def both(desc, ins, outs_views=None, what=""):
+        o1, c1 = H.run_vm(desc, ins, outs_views() if outs_views else None, ctx=ctx)
+        assert "one tile ahead" in c1.disasm(), what
+        o1 = {k: v.clone() for k, v in o1.items()}
+        o2, c2 = H.run_vm(desc, ins, outs_views() if outs_views else None, ctx=plain)
+        assert "one tile ahead" not in c2.disasm(), what
+        for k in o1:
+            assert torch.equal(o1[k].view(torch.int16) if o1[k].dtype == torch.bfloat16 else o1[k].view(torch.int32),
+                               o2[k].view(torch.int16) if o2[k].dtype == torch.bfloat16 else o2[k].view(torch.int32)), (what, k)
+        rounded, exact = H.run_oracle(desc, ins)
+        for n, dt in desc.outputs:
+            H.compare(o1[n], rounded[n], exact[n], dt, H.has_reduction(desc), f"pipelined {what}:{n}")
+
+    say("pipelined rmsnorm bf16 [4100,4096] (several tiles per workgroup, ragged tail)")
+    both(W.get_program("c2_rmsnorm"), gen.c2_inputs(2, 2050, 71, DEV), what="rmsnorm")
+    say("pipelined softmax fp32 [60000,1000] + mask")
+    z = gen.randn((60, 1000, 1000), 72, DEV, "f32", std=3.0)
+    both(W.get_program("c3_masked_softmax"), {"z": z, "mask": gen.causal_mask(1000, DEV)}, what="softmax")
+    say("pipelined unaligned rows bf16 [9000, 1025]")
+    both(W.get_program("softmax_bf16"), {"z": gen.randn((9000, 1025), 73, DEV, "bf16")}, what="odd rows")
+    say("pipelined c4 chain [3000,8192]")
+    both(W.get_program("c4_chain"), gen.c4_inputs(3000, 74, DEV), what="c4")
+    say("pipelined rope views T=4096")
+    d = gen.c5_inputs(4096, 75, DEV)["c5_rope"]
+
+    def views():
+        out = torch.zeros((4096, 32, 128), dtype=torch.bfloat16, device=DEV)
+        return {"y1": out[..., :64], "y2": out[..., 64:]}
+    both(W.get_program("c5_rope"), d, views, what="rope")
+    say("pipelined elementwise column tiles fp32 [700, 20000]")
+    both(W.get_program("c1_gelu_erf"), {"x": gen.randn((700, 20000), 76, DEV), "a": gen.rand_uniform((20000,), 77, -1, 1, DEV),
+                                        "b": gen.rand_uniform((20000,), 78, -1, 1, DEV)}, what="columns")
