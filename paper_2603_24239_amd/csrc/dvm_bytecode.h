@@ -108,6 +108,11 @@ constexpr uint32_t MF_ALIGNED16 = 1u;   // every chunk of this tensor starts on 
 constexpr uint32_t MF_PIPELINED = 2u;   // load only: the record consumes what it requested one tile earlier and
                                         // requests the next tile's data (at most one such record per segment);
                                         // the data waits in workgroup memory, S_PIPEBYTES per thread
+constexpr uint32_t MF_STREAM    = 8u;   // load only: every element of the tensor is read exactly once by the
+                                        // launch (no broadcast over an iterated dim): bypass-style cache hint
+constexpr uint32_t MF_PIPEWAIT  = 4u;   // store only: first store after the pipelined load; it waits for the
+                                        // transfers requested by that load before it issues its own writes, so
+                                        // that the next tile never has to wait for these writes to be acknowledged
 
 // source / destination selectors
 constexpr uint32_t SRC_R0  = 0;         // 0 .. NR-1

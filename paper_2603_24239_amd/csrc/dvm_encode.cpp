@@ -1249,7 +1249,9 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     uint32_t imask = 0;
-    bool pipelined = false;
+    bool pipelined = false, pipewait = false;
+    bool has_tile_store = false;        // the pipelined load needs a tile store after it (see MF_PIPEWAIT)
+    for (int i = E.n_prolog; i < E.n_ai; ++i) has_tile_store |= E.ai[i].op == I_STORE;
     uint32_t *b = sh + SH_WORDS;
     auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
     for (int i = 0; i < E.n_ai; ++i) {
@@ -1262,10 +1264,19 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 *b++ = w0(op, view ? LEN_VLOAD : LEN_LOAD, x.a, x.b);
                 // the first load of the body runs one tile ahead when some workgroup has several tiles
                 uint32_t mflags = 0;
-                if (x.op == I_LOAD && i >= E.n_prolog && !pipelined && ctx->pipeline && M64 > (int64_t)grid) {
+                if (x.op == I_LOAD && i >= E.n_prolog && !pipelined && has_tile_store && ctx->pipeline && M64 > (int64_t)grid) {
                     mflags |= MF_PIPELINED;
                     pipelined = true;
                     sh[S_PIPEBYTES] = (uint32_t)vr.K * (A.dtype == DVM_BF16 ? 2u : 4u);
+                }
+                if (x.op == I_STORE && pipelined && !pipewait) {
+                    mflags |= MF_PIPEWAIT;
+                    pipewait = true;
+                }
+                if (x.op == I_LOAD) {
+                    bool once = !A.rows;        // read exactly once: no outer dim is broadcast
+                    for (int g = 1; g < ng; ++g) once &= !(E.Dg[g] > 1 && A.s[g] == 0);
+                    if (once) mflags |= MF_STREAM;
                 }
                 *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8) | (mflags << 16);
                 put_i64(A.s[1]);
@@ -1400,7 +1411,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         }
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
         bool prolog_ends_on_record = sh[S_PROLOG] == 0;
-        int n_pipelined = 0;
+        int n_pipelined = 0, n_pipewait = 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
         if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
         tiles_total += M;
@@ -1426,7 +1437,11 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
                     if ((op == I_STORE || op == I_VSTORE) && !((info >> 8) & 1)) return bad("store to an input tensor");
                     if (((w1 >> 8) & 0xFF) == DVM_BF16 && V != 8) return bad("bf16 tile with 4-element chunks");
-                    if ((w1 >> 16) & ~MF_PIPELINED) return bad("memory flags");
+                    if ((w1 >> 16) & ~(MF_PIPELINED | MF_PIPEWAIT | MF_STREAM)) return bad("memory flags");
+                    if (((w1 >> 16) & MF_STREAM) && op != I_LOAD && op != I_VLOAD) return bad("stream hint on a store");
+                    if ((w1 >> 16) & MF_PIPEWAIT) {
+                        if ((op != I_STORE && op != I_VSTORE) || n_pipelined != 1 || n_pipewait++) return bad("pipelined load wait");
+                    }
                     if ((w1 >> 16) & MF_PIPELINED) {
                         if ((op != I_LOAD && op != I_VLOAD) || pc < at + SH_WORDS + sh[S_PROLOG] || n_pipelined++) return bad("pipelined load");
                         if (sh[S_PIPEBYTES] != (uint32_t)vr->K * (((w1 >> 8) & 0xFF) == DVM_BF16 ? 2u : 4u)) return bad("pipelined load staging size");
@@ -1479,6 +1494,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         }
         if (!prolog_ends_on_record) return bad("prologue does not end on a record boundary");
         if (n_pipelined == 0 && sh[S_PIPEBYTES] != 0) return bad("staging memory without a pipelined load");
+        if (n_pipelined != n_pipewait) return bad("pipelined load without a store that waits for it");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");

@@ -332,19 +332,19 @@ DI int64_t row_offset(const Geo &g, int64_t s1, int64_t s2, int64_t s3) {
 DI void st_b128(gptr p, f32x4 v, bool ok) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
     uint64_t sv;
-    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dwordx4 %2, %3, off\n\ts_mov_b64 exec, %0"
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dwordx4 %2, %3, off nt\n\ts_mov_b64 exec, %0"
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 DI void st_b32(gptr p, float v, bool ok) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
     uint64_t sv;
-    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dword %2, %3, off\n\ts_mov_b64 exec, %0"
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dword %2, %3, off nt\n\ts_mov_b64 exec, %0"
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 DI void st_b16(gptr p, uint32_t v, bool ok) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
     uint64_t sv;
-    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_short %2, %3, off\n\ts_mov_b64 exec, %0"
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_short %2, %3, off nt\n\ts_mov_b64 exec, %0"
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 
@@ -374,6 +374,45 @@ template <int K, class Sink> DI void request_tile(uint32_t dt, uint32_t V, gcptr
                 sink.template operator()<Q>(rowp + (((uint64_t)cc << esh) + 16u * h));
             }
         });
+    }
+}
+
+// The same with dtype, chunk width and cache hint fixed at compile time (the plain load path):
+// no per-piece scalar arithmetic at all.  NT: the data is read once, hint the caches accordingly.
+template <int K, int DT, int V, bool NT> DI void request_tile_static(Raw<K> &raw, gcptr rowp, const Geo &g) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        if (g.ncols >= (uint32_t)V) {       // wave-uniform: the tile has at least one whole chunk
+            sfor<NJ>([&]<int J>() LI {
+                const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
+                gcptr q = rowp + (uint64_t)cc * ES;
+                constexpr int PIECES = DT == 0 ? V / 4 : 1;
+                sfor<PIECES>([&]<int H>() LI {
+                    const GLOBAL_AS f32x4_a2 *src = (const GLOBAL_AS f32x4_a2 *)(q + 16 * H);
+                    if constexpr (NT) raw.q[J * PIECES + H] = __builtin_nontemporal_load(src);
+                    else raw.q[J * PIECES + H] = *src;
+                });
+            });
+        }
+    }
+}
+template <int K> DI void request_dispatch(Raw<K> &raw, uint32_t dt, uint32_t V, bool nt, gcptr rowp, const Geo &g) {
+    if (nt) {
+        if (dt == 0) {
+            if (V == 4) request_tile_static<K, 0, 4, true>(raw, rowp, g);
+            else request_tile_static<K, 0, 8, true>(raw, rowp, g);
+        } else {
+            request_tile_static<K, 1, 8, true>(raw, rowp, g);
+        }
+    } else {
+        if (dt == 0) {
+            if (V == 4) request_tile_static<K, 0, 4, false>(raw, rowp, g);
+            else request_tile_static<K, 0, 8, false>(raw, rowp, g);
+        } else {
+            request_tile_static<K, 1, 8, false>(raw, rowp, g);
+        }
     }
 }
 
@@ -745,14 +784,17 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         if (pipe) {
                             // this tile's data was requested while the previous tile was being
                             // computed (by this record); only a workgroup's first tile asks now
-                            if (tl == t_lo) request_tile<K>(dt, V, rowp, g, to_lds);
-                            lds_transfers_wait();
+                            // (later tiles need no wait here: the previous tile's first store waited)
+                            if (tl == t_lo) {
+                                request_tile<K>(dt, V, rowp, g, to_lds);
+                                lds_transfers_wait();
+                            }
                             const uint32_t npieces = dt == 0 ? (uint32_t)(K / 4) : (uint32_t)(K / 8);
                             sfor<K / 4>([&]<int Q>() LI {
                                 if ((uint32_t)Q < npieces) raw.q[Q] = pf_lds[(Q * nwaves + wave) * 64 + (tid & 63)];
                             });
                         } else {
-                            request_tile<K>(dt, V, rowp, g, [&]<int Q>(gcptr p) LI { raw.q[Q] = *(const GLOBAL_AS f32x4_a2 *)p; });
+                            request_dispatch<K>(raw, dt, V, ((w1 >> 16) & MF_STREAM) != 0, rowp, g);
                         }
                         // widen straight into the destination register
                         if (a == SRC_ACC) {
@@ -789,6 +831,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         const uint32_t es = dt == 0 ? 4 : 2;
                         gptr base = (gptr)args.tensors[tbase + ti];
                         gptr rowp = base + off * es;
+                        if ((w1 >> 16) & MF_PIPEWAIT) lds_transfers_wait();
                         if (a == SRC_ACC) {
                             store_dispatch<K>(acc, dt, V, rowp, g);
                         } else {
