@@ -107,6 +107,12 @@ void dvm_ctx_destroy(dvm_ctx *ctx);
 /* Override planner inputs (tests, tuning): number of compute units and the per-tile overhead term
  * of the cost model, in elements.  Values <= 0 leave the setting unchanged. */
 int  dvm_ctx_set_planner(dvm_ctx *ctx, int n_compute_units, int tile_overhead_elems);
+/* Bound the interpreter variant dvm_encode may plan for: at most `max_elems_per_lane` elements of a
+ * tile per lane (4, 8, 16 or 32) and at most `max_tile_regs` tile registers (2, 4 or 6).  Parts that
+ * are to share one launch (dvm_stack; Section 5, stacking) must all fit one variant, so a caller that
+ * stacks encodes every part under common limits, e.g. (16, 4).  Values <= 0 leave a limit unchanged;
+ * a program that needs more tile registers than allowed makes dvm_encode return DVM_E_UNSUPPORTED. */
+int  dvm_ctx_set_limits(dvm_ctx *ctx, int max_elems_per_lane, int max_tile_regs);
 
 /* ---- program builder (shape free) --------------------------------------------------------------- */
 typedef struct dvm_prog dvm_prog;

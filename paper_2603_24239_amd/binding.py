@@ -72,6 +72,7 @@ def load() -> C.CDLL:
         "dvm_ctx_create": (i, [i, P(vp)]),
         "dvm_ctx_destroy": (None, [vp]),
         "dvm_ctx_set_planner": (i, [vp, i, i]),
+        "dvm_ctx_set_limits": (i, [vp, i, i]),
         "dvm_prog_create": (i, [P(vp)]),
         "dvm_prog_input": (i, [vp, i, P(i)]),
         "dvm_prog_op": (i, [vp, i, P(i), i, P(C.c_double), i, P(i)]),
@@ -100,7 +101,7 @@ def load() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_prog_create",
+EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_ctx_set_limits", "dvm_prog_create",
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
             "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_validate", "dvm_disasm",
             "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_strerror", "dvm_last_error_detail",
@@ -152,6 +153,9 @@ class Context:
     def set_planner(self, n_compute_units: int = 0, tile_overhead_elems: int = 0) -> None:
         _check(load().dvm_ctx_set_planner(self._h, n_compute_units, tile_overhead_elems), "dvm_ctx_set_planner")
 
+    def set_limits(self, max_elems_per_lane: int = 0, max_tile_regs: int = 0) -> None:
+        _check(load().dvm_ctx_set_limits(self._h, max_elems_per_lane, max_tile_regs), "dvm_ctx_set_limits")
+
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:
             _lib.dvm_ctx_destroy(self._h)
@@ -192,6 +196,9 @@ class Program:
         _check(lib.dvm_prog_finish(self._h), "dvm_prog_finish")
         self.n_in = lib.dvm_prog_num_inputs(self._h)
         self.n_out = lib.dvm_prog_num_outputs(self._h)
+
+    def set_limits(self, max_elems_per_lane: int = 0, max_tile_regs: int = 0) -> None:
+        _check(load().dvm_ctx_set_limits(self._h, max_elems_per_lane, max_tile_regs), "dvm_ctx_set_limits")
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

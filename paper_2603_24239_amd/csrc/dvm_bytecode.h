@@ -150,7 +150,7 @@ struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
     { 4, 2, 1024, 8}, { 4, 6, 1024, 7},
     { 8, 2, 1024, 5}, { 8, 6,  512, 4},
-    {16, 2, 1024, 4}, {16, 4, 1024, 4},
+    {16, 2, 1024, 4}, {16, 4,  512, 2}, {16, 6,  512, 2},
     {32, 2,  256, 2},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);

@@ -80,10 +80,14 @@ extern "C" int dvm_shape_contiguous(dvm_shape *s, int rank, const int64_t *dims)
 // ------------------------------------------------------------------------------------------------
 // context
 // ------------------------------------------------------------------------------------------------
+constexpr int NR_LIMIT = 6;      // tile registers of the largest interpreter variant
+
 struct dvm_ctx {
     int device;
     int n_cu;
     int overhead;   // per-tile overhead of the cost model, in elements
+    int max_k;      // largest elements-per-lane the planner may choose
+    int max_nr;     // most tile registers a program may use
     // tuning aids, settable through environment variables read once at dvm_ctx_create
     int pipeline;   // DVM_DEBUG_PIPELINE=0 switches the one-tile-ahead load off
     int dbg_k;      // DVM_DEBUG_K: preferred elements per lane (0 = planner's choice)
@@ -98,6 +102,8 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->device = hip_device;
     c->n_cu = 256;          // MI355X
     c->overhead = 512;
+    c->max_k = 32;
+    c->max_nr = NR_LIMIT;
     const char *e;
     c->pipeline = (e = getenv("DVM_DEBUG_PIPELINE")) ? atoi(e) : 0;
     c->dbg_k = (e = getenv("DVM_DEBUG_K")) ? atoi(e) : 0;
@@ -121,6 +127,19 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
 }
 extern "C" void dvm_ctx_destroy(dvm_ctx *c) { delete c; }
 extern "C" int dvm_ctx_device(const dvm_ctx *c) { return c ? c->device : -1; }
+extern "C" int dvm_ctx_set_limits(dvm_ctx *c, int max_k, int max_nr) {
+    if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
+    if (max_k > 0) {
+        if (max_k != 4 && max_k != 8 && max_k != 16 && max_k != 32) return dvm_set_error(DVM_E_ARGS, "elements per lane must be 4, 8, 16 or 32");
+        c->max_k = max_k;
+    }
+    if (max_nr > 0) {
+        if (max_nr != 2 && max_nr != 4 && max_nr != 6) return dvm_set_error(DVM_E_ARGS, "tile registers must be 2, 4 or 6");
+        c->max_nr = max_nr;
+    }
+    return DVM_OK;
+}
+
 extern "C" int dvm_ctx_set_planner(dvm_ctx *c, int n_cu, int overhead) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
     if (n_cu > 0) c->n_cu = n_cu;
@@ -493,6 +512,8 @@ struct Enc {
     int uses[MAX_NODES];
     int reg_of[MAX_NODES], sreg_of[MAX_NODES];
     int regs[NR_MAX], sregs[NS];
+    int nr_limit;           // tile registers the program may use
+    bool reload_inputs;     // never keep an input tile in a register: load it again at every use
     int in_acc;
     int nr_used, ns_used;
     const char *err;
@@ -529,14 +550,14 @@ struct Enc {
         sreg_of[dst_node] = sr;
     }
     int alloc_reg(int node) {
-        for (int i = 0; i < NR_MAX; ++i)
+        for (int i = 0; i < nr_limit; ++i)
             if (regs[i] < 0) {
                 regs[i] = node;
                 reg_of[node] = i;
                 if (i + 1 > nr_used) nr_used = i + 1;
                 return i;
             }
-        fail(DVM_E_UNSUPPORTED, "program needs more than 6 live tile registers");
+        fail(DVM_E_UNSUPPORTED, "program needs more live tile registers than available");
         return 0;
     }
     int alloc_sreg(int node) {
@@ -588,8 +609,8 @@ struct Enc {
         if (uses[n] - pending_uses <= 0 || reg_of[n] >= 0) return;
         if (is_input(n)) {
             int free_regs = 0;
-            for (int i = 0; i < NR_MAX; ++i) free_regs += regs[i] < 0;
-            if (free_regs == 0) return;   // reload it later instead
+            for (int i = 0; i < nr_limit; ++i) free_regs += regs[i] < 0;
+            if (free_regs == 0 || reload_inputs) return;   // reload it later instead
         }
         const int r = alloc_reg(n);
         emit(I_MOVRA, (uint8_t)r);
@@ -993,7 +1014,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                     if (E.reg_of[b] >= 0) {
                         E.emit(I_BIN, (uint8_t)E.reg_of[b], (uint8_t)op);
                     } else if (E.is_input(b)) {
-                        if (E.uses[b] == 1) {
+                        if (E.uses[b] == 1 || E.reload_inputs) {
                             E.emit(I_LOAD, (uint8_t)SRC_ACC, (uint8_t)op, E.tensor_of_input(b));
                         } else {
                             const int r = E.to_reg(b);
@@ -1056,10 +1077,18 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     // again with as many pinned operands as keep the program within four tile registers
     // (rows long enough for 32 elements per lane keep to the two tile registers of that variant:
     // fewer interpreted records per element outweigh reloading a row vector from cache)
+    E.nr_limit = ctx->max_nr < NR_MAX ? ctx->max_nr : NR_MAX;
+    E.reload_inputs = false;
     linearize(0);
+    if (E.err) {                // too many live tiles: trade registers for repeated (cached) loads
+        E.err = nullptr;
+        E.reload_inputs = true;
+        linearize(0);
+    }
     {
         const int64_t lanes32 = cdiv(cdiv(E.D0 > 0 ? E.D0 : 1, any_bf16_full ? 8 : 4), any_bf16_full ? 4 : 8);
-        const int reg_cap = (lanes32 >= 128 && E.nr_used <= 2 && ctx->dbg_k != 16) ? 2 : 4;
+        int reg_cap = (lanes32 >= 128 && E.nr_used <= 2 && ctx->dbg_k != 16 && ctx->max_k >= 32) ? 2 : 4;
+        if (reg_cap > ctx->max_nr) reg_cap = ctx->max_nr;
         if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap) {
             const int body_regs = E.nr_used;
             linearize(reg_cap - body_regs);
@@ -1067,6 +1096,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         }
     }
     if (E.err) return dvm_set_error(E.err_code, E.err);
+    if (E.nr_used > ctx->max_nr) return dvm_set_error(DVM_E_UNSUPPORTED, "program needs more tile registers than the context allows");
 
     // ---- 5. tile plan ---------------------------------------------------------------------------
     const uint32_t V = any_bf16_full ? 8 : 4;
@@ -1077,7 +1107,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     auto find_variant = [&](int K) {
         int best = -1;
         for (int i = 0; i < N_VARIANTS; ++i)
-            if (VARIANTS[i].K == K && VARIANTS[i].NR >= need_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
+            if (VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
         return best;
     };
     auto slots_per_cu = [&](const Variant &v, uint32_t threads) {
@@ -1149,6 +1179,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (column_mode) {
         int v = find_variant(16);
         if (v < 0) v = find_variant(8);
+        if (v < 0) v = find_variant(4);
         if (v < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
         vi = v;
         const Variant &vr = VARIANTS[vi];

@@ -948,7 +948,7 @@ struct VariantEntry { int K, NR; vm_kernel_t fn; };
 const VariantEntry g_variants[] = {
     { 4, 2, dvm_vm_kernel< 4, 2, 1024>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024>},
     { 8, 2, dvm_vm_kernel< 8, 2, 1024>}, { 8, 6, dvm_vm_kernel< 8, 6,  512>},
-    {16, 2, dvm_vm_kernel<16, 2, 1024>}, {16, 4, dvm_vm_kernel<16, 4, 1024>},
+    {16, 2, dvm_vm_kernel<16, 2, 1024>}, {16, 4, dvm_vm_kernel<16, 4,  512>}, {16, 6, dvm_vm_kernel<16, 6,  512>},
     {32, 2, dvm_vm_kernel<32, 2,  256>},
 };
 

@@ -205,3 +205,68 @@ def test_shapes_stream_is_seeded_and_distinct():
     assert len(s) == 200 and len(set(s)) == 200 and s == gen.c2_shapes()
     assert all(1 <= b <= 32 and 1 <= q <= 2048 for b, q in s)
     assert all(1 <= t <= 8192 for t in gen.c5_steps()) and len(gen.c5_steps()) == 64
+
+
+def _encode(ctx, name, dims, views=None):
+    desc = W.get_program(name)
+    prog = B.Program(desc)
+    return B.dvm_encode(ctx, prog, [B.make_shape(d) for d in dims], views)
+
+
+def test_limits_bound_the_variant_and_trade_registers_for_reloads():
+    free = B.Context(-1)
+    lim = B.Context(-1)
+    lim.set_limits(16, 4)
+    # long rows: 32 elements per lane unless the context forbids it
+    assert _encode(free, "c2_rmsnorm", [(64, 4096), (4096,)]).info().variant_k == 32
+    assert _encode(lim, "c2_rmsnorm", [(64, 4096), (4096,)]).info().variant_k == 16
+    # rotate-half RoPE keeps four inputs live; under four tile registers the inputs are loaded again instead
+    T = 700
+    half = [(T, 32, 64), (T, 32, 64), (T, 1, 64), (T, 1, 64)]
+    a = _encode(free, "c5_rope", half)
+    b = _encode(lim, "c5_rope", half)
+    assert a.info().variant_nr == 6 and b.info().variant_nr <= 4
+    loads = lambda code: len(re.findall(r"^\s+\d+ (?:view)?load ", code.disasm(), flags=re.M))
+    assert loads(b) > loads(a)
+    b.validate()
+    for bad in [(5, 0), (0, 3), (64, 0)]:
+        with pytest.raises(B.DvmError):
+            lim.set_limits(*bad)
+    two = B.Context(-1)
+    two.set_limits(0, 2)
+    with pytest.raises(B.DvmError):         # select needs both alternatives in tile registers plus temporaries
+        _encode(two, "if_else_add", [(8, 128)] * 4)
+
+
+def test_stream_hint_marks_tensors_read_once(ctx):
+    code = _encode(ctx, "c3_masked_softmax", [(2, 32, 256, 256), (256, 256)])
+    words = np.frombuffer(code.raw, dtype=np.uint32)
+    text = code.disasm()
+    assert "load" in text
+    # find the load records: the scores are streamed, the broadcast mask is not
+    from_hdr = 8 + 3 * code.info().n_tensors + 24
+    flags = {}
+    pc = from_hdr
+    while pc < len(words):
+        op, ln = words[pc] & 0xFF, (words[pc] >> 8) & 0xFF
+        if op in (1, 2):
+            flags[int(words[pc + 1] & 0xFF)] = int(words[pc + 1] >> 16)
+        pc += ln
+    assert flags[0] & 8, "the score tensor is read exactly once"
+    assert not (flags[1] & 8), "the mask is re-read for every batch and head"
+
+
+def test_pipelined_load_flags_are_consistent():
+    env = dict(os.environ, DVM_DEBUG_PIPELINE="1", PYTHONPATH=ROOT)
+    script = ("from paper_2603_24239_amd import binding as B\n"
+              "from workloads import programs as W\n"
+              "ctx = B.Context(-1)\n"
+              "for name, dims in [('c2_rmsnorm', [(70000, 4096), (4096,)]), ('softmax_f32', [(90000, 1000)]), ('c2_rmsnorm', [(8, 4096), (4096,)])]:\n"
+              "    code = B.dvm_encode(ctx, B.Program(W.get_program(name)), [B.make_shape(d) for d in dims], None)\n"
+              "    code.validate()\n"
+              "    print(name, dims[0][0], 'one tile ahead' in code.disasm())\n")
+    out = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, cwd=ROOT)
+    assert out.returncode == 0, out.stderr
+    lines = out.stdout.strip().splitlines()
+    assert lines[0].endswith("True") and lines[1].endswith("True")
+    assert lines[2].endswith("False")       # fewer tiles than workgroups: nothing to run ahead of
