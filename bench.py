@@ -1,10 +1,12 @@
 #!/usr/bin/env python3
 """Benchmark of the DVM hot path on one MI355X.
 
-A step is one pass of the whole hot path over the configured workload: for every instance of the
-dynamic-shape stream, dvm_encode (host: shape inference, fusion, register allocation, tile plan,
-bytecode) followed by dvm_run (device: the bytecode interpreter), all instances back to back on
-one stream.  Inputs and outputs of all instances are resident in HBM before the timed region.
+A step is one pass of the whole hot path over the configured workload: every instance of the
+dynamic-shape stream is encoded by dvm_encode (host: shape inference, fusion, register allocation,
+tile plan, bytecode), consecutive instances are merged eight at a time into one launch by dvm_stack
+(temporal stacking), and dvm_run executes each launch (device: the bytecode interpreter), all on one
+stream.  Inputs and outputs of all instances are resident in HBM before the timed region.  The same
+stream is also run with every instance as its own launch; that figure is reported beside the main one.
 
 Workload (default): fused RMSNorm with learned scale, bf16 in/out with fp32 accumulation,
 x = [B, S, 4096] ~ N(0,1), weight ~ N(1, 0.1), eps 1e-6, 200 instances with B uniform in 1..32 and
@@ -54,7 +56,14 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c2_rmsnorm", choices=["c2_rmsnorm", "c4_chain"])
     ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = all)")
+    ap.add_argument("--stack", type=int, default=0,
+                    help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
+                         "launch's tensor table; 1 = every instance its own launch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--skip-unstacked", action="store_true",
+                    help="leave out the second pass that launches every instance on its own (profiler runs use this so "
+                         "that the kernel statistics cover the stacked launches only)")
+    ap.add_argument("--dump-launches", default="", help="write per-instance bytes and mean launch time to this CSV file")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 256 MiB device copy (a known-size kernel that scales "
                          "the HBM byte counters of a profiler run)")
@@ -107,47 +116,78 @@ def main() -> int:
 
     # ---- marshalling prepared once: shapes as C structs, pointers as C arrays -------------------
     enc_cap = 8192
-    prepared = []
-    for ins, outs, nbytes, shp in insts:
-        shs = (B.dvm_shape * len(ins))(*[B.shape_of_tensor(t) for t in ins])
-        ptrs = (C.c_void_p * (len(ins) + len(outs)))(*[t.data_ptr() for t in ins + outs])
-        prepared.append((shs, len(ins), ptrs, len(ins) + len(outs)))
-    buf = C.create_string_buffer(enc_cap)
+    n_t_inst = len(insts[0][0]) + len(insts[0][1])
+    max_group = max(1, min(32 // n_t_inst, 10))
+    group = max(1, min(args.stack if args.stack > 0 else 8, max_group))
+    inst_shapes = [(B.dvm_shape * len(ins))(*[B.shape_of_tensor(t) for t in ins]) for ins, _, _, _ in insts]
+    n_in = len(insts[0][0])
+
+    def make_groups(g):
+        out = []
+        for lo in range(0, len(insts), g):
+            idx = list(range(lo, min(lo + g, len(insts))))
+            tens = [t for i in idx for t in insts[i][0] + insts[i][1]]
+            out.append((idx, (C.c_void_p * len(tens))(*[t.data_ptr() for t in tens]), len(tens)))
+        return out
+
+    part_bufs = [C.create_string_buffer(enc_cap) for _ in range(max_group)]
+    part_ptrs = (C.c_void_p * max_group)(*[C.cast(b, C.c_void_p) for b in part_bufs])
+    part_lens = (C.c_size_t * max_group)()
+    stacked = C.create_string_buffer(enc_cap)
     ln = C.c_size_t()
     stream = torch.cuda.current_stream()
     stream_h = C.c_void_p(stream.cuda_stream)
-    enc_us = []
     perf = time.perf_counter
 
-    def one_step(events=None, record_enc=False):
-        for k, (shs, n_in, ptrs, n_t) in enumerate(prepared):
-            t0 = perf()
-            st = lib.dvm_encode(ctx._h, prog._h, shs, n_in, None, buf, enc_cap, C.byref(ln), None)
-            t1 = perf()
-            if st != 0:
-                raise B.DvmError(st, "dvm_encode")
-            if record_enc:
-                enc_us.append((t1 - t0) * 1e6)
+    def one_step(groups, events=None, enc_us=None):
+        """Encode every instance, stack each group of consecutive instances into one launch (temporal
+        stacking; a group of one is launched as it is), run."""
+        for k, (idx, ptrs, n_t) in enumerate(groups):
+            for j, i in enumerate(idx):
+                t0 = perf()
+                st = lib.dvm_encode(ctx._h, prog._h, inst_shapes[i], n_in, None, part_bufs[j], enc_cap, C.byref(ln), None)
+                t1 = perf()
+                if st != 0:
+                    raise B.DvmError(st, "dvm_encode")
+                part_lens[j] = ln.value
+                if enc_us is not None:
+                    enc_us.append((t1 - t0) * 1e6)
+            if len(idx) == 1:
+                code, code_len = part_bufs[0], part_lens[0]
+            else:
+                st = lib.dvm_stack(part_ptrs, part_lens, len(idx), stacked, enc_cap, C.byref(ln))
+                if st != 0:
+                    raise B.DvmError(st, "dvm_stack")
+                code, code_len = stacked, ln.value
             if events is not None:
                 events[k][0].record(stream)
-            st = lib.dvm_run(ctx._h, buf, ln.value, ptrs, n_t, stream_h)
+            st = lib.dvm_run(ctx._h, code, code_len, ptrs, n_t, stream_h)
             if st != 0:
                 raise B.DvmError(st, "dvm_run")
             if events is not None:
                 events[k][1].record(stream)
 
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
+    def timed(groups, steps, warmup, enc_us=None):
+        for _ in range(warmup):
+            one_step(groups)
+        evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in groups]
+               for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = perf()
+        for s in range(steps):
+            one_step(groups, evs[s], enc_us)
+        torch.cuda.synchronize()
+        return perf() - t0, evs
 
-    all_events = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                   for _ in prepared] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t_begin = perf()
-    for s in range(args.steps):
-        one_step(all_events[s], record_enc=True)
-    torch.cuda.synchronize()
-    elapsed = perf() - t_begin
+    groups = make_groups(group)
+    enc_us = []
+    elapsed, all_events = timed(groups, args.steps, args.warmup, enc_us)
+
+    # the same stream with one launch per instance (no stacking): per-instance launch times
+    singles = make_groups(1)
+    unstacked = not args.skip_unstacked
+    if unstacked:
+        elapsed1, events1 = timed(singles, args.steps, 1) if group > 1 else (elapsed, all_events)
 
     if args.calibrate_copy:
         src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -160,17 +200,29 @@ def main() -> int:
     value = total_bytes * args.steps / elapsed / 1e9
     kern_ms = [a.elapsed_time(b) for evs in all_events for (a, b) in evs]
     avg_launch_ms = float(np.mean(kern_ms))
-    bytes_per_launch = total_bytes / len(prepared)
+    bytes_per_launch = total_bytes / len(groups)
     achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
-    # the same restricted to the large instances (beyond the 256 MB Infinity Cache)
-    big = [(b, i) for i, (_, _, b, _) in enumerate(insts) if b >= 256e6]
-    large = None
-    if big:
-        bb = sum(b for b, _ in big)
-        tt = sum(a.elapsed_time(bq) for evs in all_events for i, (a, bq) in enumerate(evs) if insts[i][2] >= 256e6)
-        large = {"instances": len(big), "GBps": bb * args.steps / (tt * 1e-3) / 1e9}
+    large = single = None
+    if unstacked:
+        inst_ms = [float(np.mean([events1[s][i][0].elapsed_time(events1[s][i][1]) for s in range(args.steps)]))
+                   for i in range(len(insts))]
+        if args.dump_launches:
+            with open(args.dump_launches, "w") as f:
+                f.write("instance,shape,bytes,mean_launch_us,GBps\n")
+                for i, (_, _, nbytes, shp) in enumerate(insts):
+                    f.write(f"{i},{'x'.join(map(str, shp))},{nbytes},{inst_ms[i] * 1e3:.2f},{nbytes / inst_ms[i] / 1e6:.1f}\n")
+        # the large instances (beyond the 256 MB Infinity Cache), launched one by one
+        big = [i for i, (_, _, b, _) in enumerate(insts) if b >= 256e6]
+        if big:
+            large = {"instances": len(big),
+                     "GBps": round(sum(insts[i][2] for i in big) / sum(inst_ms[i] for i in big) / 1e6, 1)}
+        single = {"value": round(total_bytes * args.steps / elapsed1 / 1e9, 2), "unit": "GB/s",
+                  "avg_launch_ms": round(float(np.mean(inst_ms)), 5),
+                  "achieved": round(total_bytes / len(insts) / float(np.mean(inst_ms)) / 1e6, 2),
+                  "note": "same stream, every instance its own launch, HIP events around every launch"}
     enc = np.array(enc_us)
 
+    wl["instances_per_launch"] = group
     result = {
         "metric": "achieved HBM GB/s of VM-run fused ops (algorithmic bytes / wall time, encode included)",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -179,12 +231,12 @@ def main() -> int:
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
         "encode_us_per_instance": {"median": round(float(np.median(enc)), 2), "p99": round(float(np.percentile(enc, 99)), 2),
                                    "max": round(float(enc.max()), 2), "note": "dvm_encode timed through ctypes"},
-        "large_instances": large,
+        "large_instances": large, "one_launch_per_instance": single,
         "roofline": {"bound": "hbm", "kernel": "dvm_vm_kernel (bytecode interpreter)", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(avg_launch_ms, 5),
-                     "launches": len(kern_ms),
-                     "traffic": measured_traffic(args.workload) if not args.instances else None},
+                     "launches": len(kern_ms), "instances_per_launch": group,
+                     "traffic": measured_traffic(args.workload) if not args.instances and not args.stack else None},
     }
 
     # ---- the CPU oracle on a bounded sample of the same workload (a baseline, not the target) -----
