@@ -1087,7 +1087,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     }
     {
         const int64_t lanes32 = cdiv(cdiv(E.D0 > 0 ? E.D0 : 1, any_bf16_full ? 8 : 4), any_bf16_full ? 4 : 8);
-        int reg_cap = (lanes32 >= 128 && E.nr_used <= 2 && ctx->dbg_k != 16 && ctx->max_k >= 32) ? 2 : 4;
+        int reg_cap = (lanes32 >= 32 && E.nr_used <= 2 && ctx->dbg_k != 16 && ctx->max_k >= 32) ? 2 : 4;
         if (reg_cap > ctx->max_nr) reg_cap = ctx->max_nr;
         if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap) {
             const int body_regs = E.nr_used;
@@ -1123,9 +1123,9 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (!column_mode) {
         const int ks[4] = {4, 8, 16, 32};
         int pick = -1;
-        // the largest K that still spreads a row over >= 16 lanes (K = 32: over two whole waves, since
-        // that variant keeps only two waves per SIMD resident); fewer lanes per row mean fewer
-        // interpreted records per element
+        // the largest K that still spreads a row over >= 16 lanes (K = 32: over >= 32 lanes, since that
+        // variant keeps only two waves per SIMD resident); fewer lanes per row mean fewer interpreted
+        // records per element, which measured faster than the higher occupancy of the smaller variants
         for (int i = 0; i < 4; ++i) {
             const int K = ks[i];
             if ((uint32_t)K < V) continue;
@@ -1133,7 +1133,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (v < 0) continue;
             const int64_t gneed = cdiv(Cr, K / V);
             if (gneed > VARIANTS[v].max_threads) continue;
-            if (pick < 0 || gneed >= (K == 32 ? 128 : 16)) pick = v;
+            if (pick < 0 || gneed >= (K == 32 ? 32 : 16)) pick = v;
         }
         if (ctx->dbg_k >= (int)V) {
             const int v = find_variant(ctx->dbg_k);

@@ -448,17 +448,26 @@ template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw
             }
         }
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
+            // its elements are read one by one by every lane of the row (one of them keeps them); all
+            // reads are requested before any is used, and an element beyond the row reads element 0 again
             const bool own = g.lr == g.part_lane;
+            float pv[V];
+            sfor<V>([&]<int E>() LI {
+                const uint32_t e = (uint32_t)E < g.part_n ? (uint32_t)E : 0u;       // wave-uniform
+                gcptr q = rowp + (uint64_t)(g.part_col + e) * ES;
+                if constexpr (DT == 0) pv[E] = *(const GLOBAL_AS float *)q;
+                else pv[E] = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
+            });
             sfor<NJ>([&]<int J>() LI {
-                if ((uint32_t)J == g.part_slot) {
+                if ((uint32_t)J == g.part_slot) {       // wave-uniform
                     sfor<V>([&]<int E>() LI {
-                        if ((uint32_t)E < g.part_n) {       // wave-uniform
-                            gcptr q = rowp + (uint64_t)(g.part_col + E) * ES;
-                            float x;
-                            if constexpr (DT == 0) x = *(const GLOBAL_AS float *)q;
-                            else x = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
-                            t.v[J * V + E] = own ? x : t.v[J * V + E];
-                        }
+                        const bool ok = own && (uint32_t)E < g.part_n;
+                        // (the empty statement keeps this a select between two values: a select between
+                        // two register-array elements would be turned into a select of their addresses,
+                        // which forces both arrays into memory)
+                        float x = pv[E];
+                        asm volatile("" : "+v"(x));
+                        t.v[J * V + E] = ok ? x : t.v[J * V + E];
                     });
                 }
             });
@@ -525,7 +534,44 @@ template <int K> DI void store_dispatch(const Tile<K> &t, uint32_t dt, uint32_t 
     }
 }
 
-// in-lane part of a row reduction over the accumulator, masking invalid columns when ragged
+// in-lane part of a row reduction over the accumulator.  When the tile is ragged, a chunk of a lane
+// is either wholly inside the row, wholly outside, or the one chunk the row ends in: whole chunks
+// are reduced unmasked and selected per chunk, only the last chunk is masked element by element.
+template <int K, uint32_t R, int V> DI float lane_reduce_ragged(const Tile<K> &a, const Geo &g) {
+    float v = red_ident<R>();
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        constexpr uint32_t RC = R == R_SUMSQ ? R_SUM : R;      // how partial results combine
+        sfor<NJ>([&]<int J>() LI {
+            if (J == 0 || (uint32_t)(J * V) < g.nact) {        // wave-uniform
+                float c = red_ident<R>();
+                sfor<V>([&]<int E>() LI {
+                    if constexpr (R == R_SUMSQ) c = f_fma(a.v[J * V + E], a.v[J * V + E], c);
+                    else c = red_comb<R>(c, a.v[J * V + E]);
+                });
+                const bool whole = g.lanecol + (uint32_t)J * g.GV + V <= g.ncols;
+                v = red_comb<RC>(v, whole ? c : red_ident<R>());
+            }
+        });
+        if (g.part_slot != ~0u) {
+            const bool own = g.lr == g.part_lane;
+            sfor<NJ>([&]<int J>() LI {
+                if ((uint32_t)J == g.part_slot) {              // wave-uniform
+                    sfor<V>([&]<int E>() LI {
+                        const bool ok = own && (uint32_t)E < g.part_n;
+                        if constexpr (R == R_SUMSQ) {
+                            const float x = ok ? a.v[J * V + E] : 0.0f;
+                            v = f_fma(x, x, v);
+                        } else {
+                            v = red_comb<R>(v, ok ? a.v[J * V + E] : red_ident<R>());
+                        }
+                    });
+                }
+            });
+        }
+    }
+    return v;
+}
 template <int K, uint32_t R> DI float lane_reduce(const Tile<K> &a, const Geo &g, uint32_t V) {
     float v = red_ident<R>();
     if (!g.ragged) {
@@ -537,27 +583,14 @@ template <int K, uint32_t R> DI float lane_reduce(const Tile<K> &a, const Geo &g
                 });
             }
         });
+    } else if (V == 8) {
+        v = lane_reduce_ragged<K, R, 8>(a, g);
     } else {
-        sfor<K / 4>([&]<int Q>() LI {
-            if (Q == 0 || (uint32_t)(Q * 4) < g.nact) {
-                // element k of the lane sits in chunk k / V at offset k % V
-                constexpr uint32_t k = Q * 4;
-                const uint32_t j = V == 8 ? k >> 3 : k >> 2;
-                const uint32_t c0 = g.lanecol + j * g.GV + (k & (V - 1));
-                sfor<4>([&]<int E>() LI {
-                    const bool ok = (c0 + E) < g.ncols;
-                    if constexpr (R == R_SUMSQ) {
-                        const float x = ok ? a.v[k + E] : 0.0f;
-                        v = f_fma(x, x, v);
-                    } else {
-                        v = red_comb<R>(v, ok ? a.v[k + E] : red_ident<R>());
-                    }
-                });
-            }
-        });
+        v = lane_reduce_ragged<K, R, 4>(a, g);
     }
     return v;
 }
+
 template <int K> DI float reduce_dispatch(const Tile<K> &a, const Geo &g, uint32_t V, uint32_t kind, uint32_t width) {
     switch (kind) {
         case R_MAX: return wave_allreduce<R_MAX>(lane_reduce<K, R_MAX>(a, g, V), width);
