@@ -71,7 +71,7 @@ enum : int {
     S_FLAGS,        // SF_*
     S_IMASK,        // bit op -> the instruction id occurs in the body (for the disassembler)
     S_PROLOG,       // words at the start of the body that run once per workgroup, before its first tile
-    S_PIPEBYTES,    // bytes of workgroup memory per thread that the pipelined load stages its data in (0: none)
+    S_PAD1,         // keeps the body 16-byte aligned
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");
@@ -105,14 +105,8 @@ enum : uint32_t {
 constexpr int LEN_LOAD  = 4;            // word0, word1, s1
 constexpr int LEN_VLOAD = 8;            // word0, word1, s1, s2, s3
 constexpr uint32_t MF_ALIGNED16 = 1u;   // every chunk of this tensor starts on a 16-byte boundary
-constexpr uint32_t MF_PIPELINED = 2u;   // load only: the record consumes what it requested one tile earlier and
-                                        // requests the next tile's data (at most one such record per segment);
-                                        // the data waits in workgroup memory, S_PIPEBYTES per thread
 constexpr uint32_t MF_STREAM    = 8u;   // load only: every element of the tensor is read exactly once by the
                                         // launch (no broadcast over an iterated dim): bypass-style cache hint
-constexpr uint32_t MF_PIPEWAIT  = 4u;   // store only: first store after the pipelined load; it waits for the
-                                        // transfers requested by that load before it issues its own writes, so
-                                        // that the next tile never has to wait for these writes to be acknowledged
 
 // source / destination selectors
 constexpr uint32_t SRC_R0  = 0;         // 0 .. NR-1
@@ -150,7 +144,7 @@ struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
     { 4, 2, 1024, 8}, { 4, 6, 1024, 7},
     { 8, 2, 1024, 5}, { 8, 6,  512, 4},
-    {16, 2, 1024, 4}, {16, 4,  512, 2}, {16, 6,  512, 2},
+    {16, 2, 1024, 4}, {16, 4,  512, 3}, {16, 6,  512, 2},
     {32, 2,  256, 2},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);

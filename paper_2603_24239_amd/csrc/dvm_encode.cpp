@@ -89,7 +89,6 @@ struct dvm_ctx {
     int max_k;      // largest elements-per-lane the planner may choose
     int max_nr;     // most tile registers a program may use
     // tuning aids, settable through environment variables read once at dvm_ctx_create
-    int pipeline;   // DVM_DEBUG_PIPELINE=0 switches the one-tile-ahead load off
     int dbg_k;      // DVM_DEBUG_K: preferred elements per lane (0 = planner's choice)
     int dbg_grid_x; // DVM_DEBUG_GRIDX: workgroups launched per resident slot (default 1)
     int dbg_rp;     // DVM_DEBUG_RP: rows per tile (0 = cost model)
@@ -105,7 +104,6 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->max_k = 32;
     c->max_nr = NR_LIMIT;
     const char *e;
-    c->pipeline = (e = getenv("DVM_DEBUG_PIPELINE")) ? atoi(e) : 0;
     c->dbg_k = (e = getenv("DVM_DEBUG_K")) ? atoi(e) : 0;
     c->dbg_grid_x = (e = getenv("DVM_DEBUG_GRIDX")) ? atoi(e) : 1;
     c->dbg_rp = (e = getenv("DVM_DEBUG_RP")) ? atoi(e) : 0;
@@ -1280,9 +1278,6 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     uint32_t imask = 0;
-    bool pipelined = false, pipewait = false;
-    bool has_tile_store = false;        // the pipelined load needs a tile store after it (see MF_PIPEWAIT)
-    for (int i = E.n_prolog; i < E.n_ai; ++i) has_tile_store |= E.ai[i].op == I_STORE;
     uint32_t *b = sh + SH_WORDS;
     auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
     for (int i = 0; i < E.n_ai; ++i) {
@@ -1293,17 +1288,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 const uint32_t op = view ? (x.op == I_LOAD ? I_VLOAD : I_VSTORE) : x.op;
                 imask |= 1u << op;
                 *b++ = w0(op, view ? LEN_VLOAD : LEN_LOAD, x.a, x.b);
-                // the first load of the body runs one tile ahead when some workgroup has several tiles
                 uint32_t mflags = 0;
-                if (x.op == I_LOAD && i >= E.n_prolog && !pipelined && has_tile_store && ctx->pipeline && M64 > (int64_t)grid) {
-                    mflags |= MF_PIPELINED;
-                    pipelined = true;
-                    sh[S_PIPEBYTES] = (uint32_t)vr.K * (A.dtype == DVM_BF16 ? 2u : 4u);
-                }
-                if (x.op == I_STORE && pipelined && !pipewait) {
-                    mflags |= MF_PIPEWAIT;
-                    pipewait = true;
-                }
                 if (x.op == I_LOAD) {
                     bool once = !A.rows;        // read exactly once: no outer dim is broadcast
                     for (int g = 1; g < ng; ++g) once &= !(E.Dg[g] > 1 && A.s[g] == 0);
@@ -1442,7 +1427,6 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         }
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
         bool prolog_ends_on_record = sh[S_PROLOG] == 0;
-        int n_pipelined = 0, n_pipewait = 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
         if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
         tiles_total += M;
@@ -1468,15 +1452,8 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
                     if ((op == I_STORE || op == I_VSTORE) && !((info >> 8) & 1)) return bad("store to an input tensor");
                     if (((w1 >> 8) & 0xFF) == DVM_BF16 && V != 8) return bad("bf16 tile with 4-element chunks");
-                    if ((w1 >> 16) & ~(MF_PIPELINED | MF_PIPEWAIT | MF_STREAM)) return bad("memory flags");
+                    if ((w1 >> 16) & ~MF_STREAM) return bad("memory flags");
                     if (((w1 >> 16) & MF_STREAM) && op != I_LOAD && op != I_VLOAD) return bad("stream hint on a store");
-                    if ((w1 >> 16) & MF_PIPEWAIT) {
-                        if ((op != I_STORE && op != I_VSTORE) || n_pipelined != 1 || n_pipewait++) return bad("pipelined load wait");
-                    }
-                    if ((w1 >> 16) & MF_PIPELINED) {
-                        if ((op != I_LOAD && op != I_VLOAD) || pc < at + SH_WORDS + sh[S_PROLOG] || n_pipelined++) return bad("pipelined load");
-                        if (sh[S_PIPEBYTES] != (uint32_t)vr->K * (((w1 >> 8) & 0xFF) == DVM_BF16 ? 2u : 4u)) return bad("pipelined load staging size");
-                    }
                     break;
                 }
                 case I_LOADS: case I_STORES: {
@@ -1524,8 +1501,6 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             pc += l;
         }
         if (!prolog_ends_on_record) return bad("prologue does not end on a record boundary");
-        if (n_pipelined == 0 && sh[S_PIPEBYTES] != 0) return bad("staging memory without a pipelined load");
-        if (n_pipelined != n_pipewait) return bad("pipelined load without a store that waits for it");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");
@@ -1712,11 +1687,11 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
             switch (op) {
                 case I_LOAD:
                     o.put("  %04zu load    %s %s= t%u stride=%lld%s\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "", w[pc + 1] & 0xFF, i64(pc + 2),
-                          ((w[pc + 1] >> 16) & MF_PIPELINED) ? "  [one tile ahead]" : "");
+                          ((w[pc + 1] >> 16) & MF_STREAM) ? "  [read once]" : "");
                     break;
                 case I_VLOAD:
                     o.put("  %04zu viewload %s %s= t%u strides=[%lld,%lld,%lld]%s\n", pc - at - SH_WORDS, ra, b ? BIN_NAMES[b] : "",
-                          w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6), ((w[pc + 1] >> 16) & MF_PIPELINED) ? "  [one tile ahead]" : "");
+                          w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6), ((w[pc + 1] >> 16) & MF_STREAM) ? "  [read once]" : "");
                     break;
                 case I_STORE:
                     o.put("  %04zu store   t%u = %s stride=%lld\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2));

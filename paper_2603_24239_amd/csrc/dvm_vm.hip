@@ -60,6 +60,10 @@ DI float f_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 DI float f_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
 DI float f_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
 DI float f_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
+// IEEE maxNum / minNum (a NaN operand yields the other one) as the single hardware instruction; the
+// compiler's own lowering of fmaxf first canonicalises both operands, three instructions per use
+DI float f_max(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+DI float f_min(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
 
 constexpr float LOG2E    = 1.44269504088896340736f;
 constexpr float LOG2E_LO = 1.92596303e-8f;      // log2(e) - (float)log2(e)
@@ -159,8 +163,8 @@ template <uint32_t B> DI float bin_op(float a, float b) {
     else if constexpr (B == B_MUL) return a * b;
     else if constexpr (B == B_DIV) return a * f_rcp(b);
     else if constexpr (B == B_RDIV) return b * f_rcp(a);
-    else if constexpr (B == B_MIN) return __builtin_fminf(a, b);
-    else if constexpr (B == B_MAX) return __builtin_fmaxf(a, b);
+    else if constexpr (B == B_MIN) return f_min(a, b);
+    else if constexpr (B == B_MAX) return f_max(a, b);
     else if constexpr (B == B_POW) return f_pow(a, b);
     else if constexpr (B == B_RPOW) return f_pow(b, a);
     else if constexpr (B == B_EQ) return a == b ? 1.0f : 0.0f;
@@ -247,8 +251,8 @@ template <int K> DI void tile_bins_dispatch(Tile<K> &a, float s, uint32_t op) {
 // are bitwise reproducible.
 // ------------------------------------------------------------------------------------------
 template <uint32_t R> DI float red_comb(float a, float b) {
-    if constexpr (R == R_MAX) return __builtin_fmaxf(a, b);
-    else if constexpr (R == R_MIN) return __builtin_fminf(a, b);
+    if constexpr (R == R_MAX) return f_max(a, b);
+    else if constexpr (R == R_MIN) return f_min(a, b);
     else return a + b;
 }
 template <uint32_t R> DI float red_ident() {
@@ -259,18 +263,25 @@ template <uint32_t R> DI float red_ident() {
 template <int CTRL> DI float dpp_mov(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
+template <uint32_t R> DI float swap16(float v) {   // combine with lane ^ 16
+    return red_comb<R>(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));
+}
 template <uint32_t R> DI float wave_allreduce(float v, uint32_t width) {
-    if (width >= 2) v = red_comb<R>(v, dpp_mov<0xB1>(v));                 // quad_perm [1,0,3,2]
-    if (width >= 4) v = red_comb<R>(v, dpp_mov<0x4E>(v));                 // quad_perm [2,3,0,1]
-    if (width >= 8) v = red_comb<R>(v, dpp_mov<0x141>(v));                // row_half_mirror
-    if (width >= 16) v = red_comb<R>(v, dpp_mov<0x140>(v));               // row_mirror
-    if (width >= 32)                                                      // swap with lane ^ 16
-        v = red_comb<R>(v, __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F)));
-    if (width >= 64) {
+    if (width == 64) {          // the common case, free of branches: the row spans the whole wave
+        v = red_comb<R>(v, dpp_mov<0xB1>(v));                             // quad_perm [1,0,3,2]
+        v = red_comb<R>(v, dpp_mov<0x4E>(v));                             // quad_perm [2,3,0,1]
+        v = red_comb<R>(v, dpp_mov<0x141>(v));                            // row_half_mirror
+        v = red_comb<R>(v, dpp_mov<0x140>(v));                            // row_mirror
+        v = swap16<R>(v);
         float lo = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
         float hi = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-        v = red_comb<R>(lo, hi);
+        return red_comb<R>(lo, hi);
     }
+    if (width >= 2) v = red_comb<R>(v, dpp_mov<0xB1>(v));
+    if (width >= 4) v = red_comb<R>(v, dpp_mov<0x4E>(v));
+    if (width >= 8) v = red_comb<R>(v, dpp_mov<0x141>(v));
+    if (width >= 16) v = red_comb<R>(v, dpp_mov<0x140>(v));
+    if (width >= 32) v = swap16<R>(v);
     return v;
 }
 
@@ -350,35 +361,15 @@ DI void st_b16(gptr p, uint32_t v, bool ok) {
 
 // Loading the lane's part of a tile has two halves: request_tile puts every whole chunk in flight
 // (raw bits, 16 bytes per chunk half), and widen_tile turns the raw bits into fp32 once they are
-// needed.  A plain load runs them back to back; a pipelined load runs the request one tile early.
+// needed (all chunk requests of a tile are in flight together).
 // DT: 0 = fp32, 1 = bf16.  V = chunk width.  `rowp` points at column `colbase` of the lane's row in
 // this tensor (row 0 for a lane whose row is outside the tensor).  A chunk that lies beyond the
 // tile's columns reads the tile's chunk 0 instead: the value is never stored and reductions mask it.
 template <int K> struct Raw { f32x4 q[K / 4]; };
 typedef f32x4 f32x4_a2 __attribute__((aligned(2)));
 
-// One code path for every dtype and chunk width (wave-uniform `dt` and `V` only enter the address
-// arithmetic): 16-byte piece Q of the lane belongs to chunk Q (bf16, and fp32 with 4-element
-// chunks) or to half Q&1 of chunk Q>>1 (fp32 with 8-element chunks).  `sink.operator()<Q>(address)`
-// starts the transfer of piece Q.
-template <int K, class Sink> DI void request_tile(uint32_t dt, uint32_t V, gcptr rowp, const Geo &g, Sink &&sink) {
-    const uint32_t halves = (dt == 0 && V == 8) ? 1u : 0u;
-    const uint32_t npieces = dt == 0 ? (uint32_t)(K / 4) : (uint32_t)(K / 8);
-    const uint32_t esh = dt == 0 ? 2u : 1u;
-    if ((uint32_t)K >= V && g.ncols >= V) {     // wave-uniform: the tile has at least one whole chunk
-        sfor<K / 4>([&]<int Q>() LI {
-            if ((uint32_t)Q < npieces) {        // wave-uniform
-                const uint32_t j = (uint32_t)Q >> halves, h = (uint32_t)Q & halves;
-                const uint32_t c0 = g.lanecol + j * g.GV;
-                const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
-                sink.template operator()<Q>(rowp + (((uint64_t)cc << esh) + 16u * h));
-            }
-        });
-    }
-}
-
-// The same with dtype, chunk width and cache hint fixed at compile time (the plain load path):
-// no per-piece scalar arithmetic at all.  NT: the data is read once, hint the caches accordingly.
+// Dtype, chunk width and cache hint are fixed at compile time, so the request needs no per-piece
+// scalar arithmetic.  NT: the data is read once, hint the caches accordingly.
 template <int K, int DT, int V, bool NT> DI void request_tile_static(Raw<K> &raw, gcptr rowp, const Geo &g) {
     constexpr int ES = DT == 0 ? 4 : 2;
     if constexpr (K >= V) {
@@ -415,14 +406,6 @@ template <int K> DI void request_dispatch(Raw<K> &raw, uint32_t dt, uint32_t V, 
         }
     }
 }
-
-// Global memory -> workgroup memory without passing through registers: lane l of the wave puts its
-// 16 bytes at byte address m0 + 16 * l.  The transfer is counted by vmcnt like any other load; the
-// compiler does not know of it, so the reader waits explicitly (lds_transfers_wait).
-DI void lds_transfer_b128(gcptr p, uint32_t lds_byte_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_byte_addr), "v"(p) : "memory");
-}
-DI void lds_transfers_wait() { asm volatile("s_waitcnt vmcnt(0)" : : : "memory"); }
 
 template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw, gcptr rowp, const Geo &g) {
     constexpr int ES = DT == 0 ? 4 : 2;
@@ -712,8 +695,8 @@ DI void tile_place(Geo &gt, const uint32_t *sh, uint32_t tile, uint32_t rp, uint
         g.colbase = (uint64_t)cb_lo | ((uint64_t)cb_hi << 32);                                                \
     }
 
-template <int K, int NR, int MAXT>
-__global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
+template <int K, int NR, int MAXT, int WAVES>
+__global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES))) dvm_vm_kernel(const KArgs args) {
     __shared__ float red_lds[2][16];
 
     // the register file of one lane: accumulator, tile registers, row-scalar registers
@@ -721,14 +704,9 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
     tile_zero<K>(acc); tile_zero<K>(r0); tile_zero<K>(r1); tile_zero<K>(r2);
     tile_zero<K>(r3); tile_zero<K>(r4); tile_zero<K>(r5);
     float s0 = 0.0f, s1 = 0.0f, s2 = 0.0f, s3 = 0.0f;
-    // raw bits of the tile that the pipelined load record requested one tile ahead: piece Q of wave
-    // w occupies 1 KiB at pf_lds[(Q * waves + w) * 64], one 16-byte slot per lane
-    extern __shared__ f32x4 pf_lds[];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(tid) >> 6;
-    const uint32_t nwaves = (blockDim.x + 63) >> 6;
-    const uint32_t pf_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)pf_lds);
     const uint32_t bid = blockIdx.x;
     const uint32_t ngrid = gridDim.x;
     uint32_t red_par = 0;
@@ -796,7 +774,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                     case I_VLOAD: {
                         DVM_GEO()
                         const uint32_t w1 = cw1;
-                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF, pipe = (w1 >> 16) & MF_PIPELINED;
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
                         const int64_t st1 = DVM_I64(cw2, cw3);
                         int64_t st2 = 0, st3 = 0;
                         if (op == I_VLOAD) {
@@ -811,24 +789,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         gcptr base = (gcptr)args.tensors[tbase + ti];
                         gcptr rowp = base + off * es;
                         Raw<K> raw;
-                        uint32_t tl = tile;
-                        asm volatile("" : "+s"(tl));     // keeps the next tile's arithmetic inside this handler
-                        const auto to_lds = [&]<int Q>(gcptr p) LI { lds_transfer_b128(p, pf_base + ((Q * nwaves + wave) << 10)); };
-                        if (pipe) {
-                            // this tile's data was requested while the previous tile was being
-                            // computed (by this record); only a workgroup's first tile asks now
-                            // (later tiles need no wait here: the previous tile's first store waited)
-                            if (tl == t_lo) {
-                                request_tile<K>(dt, V, rowp, g, to_lds);
-                                lds_transfers_wait();
-                            }
-                            const uint32_t npieces = dt == 0 ? (uint32_t)(K / 4) : (uint32_t)(K / 8);
-                            sfor<K / 4>([&]<int Q>() LI {
-                                if ((uint32_t)Q < npieces) raw.q[Q] = pf_lds[(Q * nwaves + wave) * 64 + (tid & 63)];
-                            });
-                        } else {
-                            request_dispatch<K>(raw, dt, V, ((w1 >> 16) & MF_STREAM) != 0, rowp, g);
-                        }
+                        request_dispatch<K>(raw, dt, V, ((w1 >> 16) & MF_STREAM) != 0, rowp, g);
                         // widen straight into the destination register
                         if (a == SRC_ACC) {
                             if (b == B_NONE) {
@@ -840,13 +801,6 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                             }
                         } else {
                             DVM_WITH_R(a, rr, widen_dispatch<K>(rr, raw, dt, V, rowp, g))
-                        }
-                        if (pipe && tl + 1 < t_hi) {
-                            Geo gn = g;
-                            tile_place(gn, sh, tl + 1, rp, tid, RP, seg_threads);
-                            int64_t offn = (int64_t)gn.i1 * st1 + (int64_t)gn.colbase;
-                            if (op == I_VLOAD) offn += (int64_t)gn.i2 * st2 + (int64_t)gn.i3 * st3;
-                            request_tile<K>(dt, V, base + offn * es, gn, to_lds);
                         }
                         break;
                     }
@@ -864,7 +818,6 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                         const uint32_t es = dt == 0 ? 4 : 2;
                         gptr base = (gptr)args.tensors[tbase + ti];
                         gptr rowp = base + off * es;
-                        if ((w1 >> 16) & MF_PIPEWAIT) lds_transfers_wait();
                         if (a == SRC_ACC) {
                             store_dispatch<K>(acc, dt, V, rowp, g);
                         } else {
@@ -938,7 +891,7 @@ __global__ void __launch_bounds__(MAXT) dvm_vm_kernel(const KArgs args) {
                             v = red_lds[red_par][w0i & 15];
                             for (uint32_t i = 1; i < gw; ++i) {
                                 const float o = red_lds[red_par][(w0i + i) & 15];
-                                v = b == R_MAX ? __builtin_fmaxf(v, o) : (b == R_MIN ? __builtin_fminf(v, o) : v + o);
+                                v = b == R_MAX ? f_max(v, o) : (b == R_MIN ? f_min(v, o) : v + o);
                             }
                             red_par ^= 1;
                         }
@@ -978,11 +931,12 @@ typedef void (*vm_kernel_t)(const KArgs);
 
 struct VariantEntry { int K, NR; vm_kernel_t fn; };
 
+// (the last template argument is the number of resident waves per SIMD the register allocation aims for)
 const VariantEntry g_variants[] = {
-    { 4, 2, dvm_vm_kernel< 4, 2, 1024>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024>},
-    { 8, 2, dvm_vm_kernel< 8, 2, 1024>}, { 8, 6, dvm_vm_kernel< 8, 6,  512>},
-    {16, 2, dvm_vm_kernel<16, 2, 1024>}, {16, 4, dvm_vm_kernel<16, 4,  512>}, {16, 6, dvm_vm_kernel<16, 6,  512>},
-    {32, 2, dvm_vm_kernel<32, 2,  256>},
+    { 4, 2, dvm_vm_kernel< 4, 2, 1024, 4>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024, 4>},
+    { 8, 2, dvm_vm_kernel< 8, 2, 1024, 4>}, { 8, 6, dvm_vm_kernel< 8, 6,  512, 4>},
+    {16, 2, dvm_vm_kernel<16, 2, 1024, 4>}, {16, 4, dvm_vm_kernel<16, 4,  512, 3>}, {16, 6, dvm_vm_kernel<16, 6,  512, 2>},
+    {32, 2, dvm_vm_kernel<32, 2,  256, 2>},
 };
 
 thread_local int t_last_hip_error = 0;
@@ -1036,12 +990,7 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
         if (v.K == K && v.NR == NR) fn = v.fn;
     if (!fn) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
-    // workgroup memory for the pipelined loads: every thread stages S_PIPEBYTES of the next tile
-    uint32_t pipe_bytes = 0;
-    for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s, at += w[at + S_WORDS])
-        if (w[at + S_PIPEBYTES] > pipe_bytes) pipe_bytes = w[at + S_PIPEBYTES];
-    const uint32_t waves = (block + 63) / 64;
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), (size_t)waves * 64 * pipe_bytes, (hipStream_t)hip_stream, ka);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), 0, (hipStream_t)hip_stream, ka);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;

@@ -254,19 +254,3 @@ def test_stream_hint_marks_tensors_read_once(ctx):
         pc += ln
     assert flags[0] & 8, "the score tensor is read exactly once"
     assert not (flags[1] & 8), "the mask is re-read for every batch and head"
-
-
-def test_pipelined_load_flags_are_consistent():
-    env = dict(os.environ, DVM_DEBUG_PIPELINE="1", PYTHONPATH=ROOT)
-    script = ("from paper_2603_24239_amd import binding as B\n"
-              "from workloads import programs as W\n"
-              "ctx = B.Context(-1)\n"
-              "for name, dims in [('c2_rmsnorm', [(70000, 4096), (4096,)]), ('softmax_f32', [(90000, 1000)]), ('c2_rmsnorm', [(8, 4096), (4096,)])]:\n"
-              "    code = B.dvm_encode(ctx, B.Program(W.get_program(name)), [B.make_shape(d) for d in dims], None)\n"
-              "    code.validate()\n"
-              "    print(name, dims[0][0], 'one tile ahead' in code.disasm())\n")
-    out = subprocess.run([sys.executable, "-c", script], env=env, capture_output=True, text=True, cwd=ROOT)
-    assert out.returncode == 0, out.stderr
-    lines = out.stdout.strip().splitlines()
-    assert lines[0].endswith("True") and lines[1].endswith("True")
-    assert lines[2].endswith("False")       # fewer tiles than workgroups: nothing to run ahead of

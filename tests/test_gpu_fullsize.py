@@ -7,8 +7,6 @@ element by element, to the same tolerance as the small cases.
 """
 from __future__ import annotations
 
-import os
-
 import numpy as np
 import pytest
 import torch
@@ -115,46 +113,3 @@ def test_c5_layer_at_max_tokens():
     check_rows(desc, {"z": z.reshape(32 * T, L)[r2]}, {out_name: outs[out_name].reshape(32 * T, L)[r2]}, "c5 full softmax")
     del outs, d
     torch.cuda.empty_cache()
-
-
-def test_one_tile_ahead_loads_match(monkeypatch):
-    """The optional pipelined load (the record asks for the next tile's data while the current tile
-    is computed) gives the same results as the plain load."""
-    from paper_2603_24239_amd import binding as B
-    monkeypatch.setenv("DVM_DEBUG_PIPELINE", "1")
-    ctx = B.Context(torch.cuda.current_device())
-    monkeypatch.delenv("DVM_DEBUG_PIPELINE")
-    plain = H.gpu_ctx()
-
-    def both(desc, ins, outs_views=None, what=""):
-        o1, c1 = H.run_vm(desc, ins, outs_views() if outs_views else None, ctx=ctx)
-        assert "one tile ahead" in c1.disasm(), what
-        o1 = {k: v.clone() for k, v in o1.items()}
-        o2, c2 = H.run_vm(desc, ins, outs_views() if outs_views else None, ctx=plain)
-        assert "one tile ahead" not in c2.disasm(), what
-        for k in o1:
-            assert torch.equal(o1[k].view(torch.int16) if o1[k].dtype == torch.bfloat16 else o1[k].view(torch.int32),
-                               o2[k].view(torch.int16) if o2[k].dtype == torch.bfloat16 else o2[k].view(torch.int32)), (what, k)
-        rounded, exact = H.run_oracle(desc, ins)
-        for n, dt in desc.outputs:
-            H.compare(o1[n], rounded[n], exact[n], dt, H.has_reduction(desc), f"pipelined {what}:{n}")
-
-    say("pipelined rmsnorm bf16 [4100,4096] (several tiles per workgroup, ragged tail)")
-    both(W.get_program("c2_rmsnorm"), gen.c2_inputs(2, 2050, 71, DEV), what="rmsnorm")
-    say("pipelined softmax fp32 [60000,1000] + mask")
-    z = gen.randn((60, 1000, 1000), 72, DEV, "f32", std=3.0)
-    both(W.get_program("c3_masked_softmax"), {"z": z, "mask": gen.causal_mask(1000, DEV)}, what="softmax")
-    say("pipelined unaligned rows bf16 [9000, 1025]")
-    both(W.get_program("softmax_bf16"), {"z": gen.randn((9000, 1025), 73, DEV, "bf16")}, what="odd rows")
-    say("pipelined c4 chain [3000,8192]")
-    both(W.get_program("c4_chain"), gen.c4_inputs(3000, 74, DEV), what="c4")
-    say("pipelined rope views T=4096")
-    d = gen.c5_inputs(4096, 75, DEV)["c5_rope"]
-
-    def views():
-        out = torch.zeros((4096, 32, 128), dtype=torch.bfloat16, device=DEV)
-        return {"y1": out[..., :64], "y2": out[..., 64:]}
-    both(W.get_program("c5_rope"), d, views, what="rope")
-    say("pipelined elementwise column tiles fp32 [700, 20000]")
-    both(W.get_program("c1_gelu_erf"), {"x": gen.randn((700, 20000), 76, DEV), "a": gen.rand_uniform((20000,), 77, -1, 1, DEV),
-                                        "b": gen.rand_uniform((20000,), 78, -1, 1, DEV)}, what="columns")
