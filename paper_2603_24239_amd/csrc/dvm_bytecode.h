@@ -118,7 +118,9 @@ constexpr int NS = 4;                   // row-scalar registers
 // binary ops B_*
 enum : uint32_t {
     B_NONE = 0, B_ADD, B_SUB, B_RSUB, B_MUL, B_DIV, B_RDIV, B_MIN, B_MAX, B_POW, B_RPOW,
-    B_EQ, B_NE, B_LT, B_LE, B_GT, B_GE, B_COUNT
+    B_EQ, B_NE, B_LT, B_LE, B_GT, B_GE,
+    B_EXPSUB, B_REXPSUB,    // exp(a - b), exp(b - a): the encoder's fusion of a subtraction feeding an exponential
+    B_COUNT
 };
 // unary ops U_*
 enum : uint32_t {

@@ -398,6 +398,20 @@ extern "C" int dvm_prog_finish(dvm_prog *p) {
             sq.kind = N_DEAD;
         }
     }
+    // peephole: exp(a - b), the difference used nowhere else -> one fused op (the softmax core)
+    for (int n = 0; n < p->n_nodes; ++n) {
+        Node &nd = p->nodes[n];
+        if (nd.kind != N_UN || nd.op != U_EXP) continue;
+        Node &d = p->nodes[nd.a];
+        if (d.kind == N_BIN && d.op == B_SUB && uses[nd.a] == 1) {
+            const int16_t da = d.a, db = d.b;
+            d.kind = N_DEAD;
+            nd.kind = N_BIN;
+            nd.op = B_EXPSUB;
+            nd.a = da;
+            nd.b = db;
+        }
+    }
     p->finished = true;
     return DVM_OK;
 }
@@ -640,6 +654,7 @@ uint32_t reversed(uint32_t b) {
         case B_SUB: return B_RSUB;
         case B_DIV: return B_RDIV;
         case B_POW: return B_RPOW;
+        case B_EXPSUB: return B_REXPSUB;
         case B_LT: return B_GT;
         case B_LE: return B_GE;
         case B_GT: return B_LT;
@@ -1620,7 +1635,7 @@ namespace {
 const char *const UN_NAMES[] = {"none", "sqrt", "abs", "log", "exp", "round", "floor", "isfinite", "neg", "rsqrt", "rcp",
                                 "tanh", "erf", "sigmoid", "square", "gelu_tanh", "gelu_erf", "silu", "cast_bf16"};
 const char *const BIN_NAMES[] = {"mov", "add", "sub", "rsub", "mul", "div", "rdiv", "min", "max", "pow", "rpow",
-                                 "cmp_eq", "cmp_ne", "cmp_lt", "cmp_le", "cmp_gt", "cmp_ge"};
+                                 "cmp_eq", "cmp_ne", "cmp_lt", "cmp_le", "cmp_gt", "cmp_ge", "expsub", "rexpsub"};
 const char *const RED_NAMES[] = {"sum", "max", "min", "sumsq"};
 
 struct Out {

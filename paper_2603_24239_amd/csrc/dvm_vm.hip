@@ -173,6 +173,10 @@ template <uint32_t B> DI float bin_op(float a, float b) {
     else if constexpr (B == B_LE) return a <= b ? 1.0f : 0.0f;
     else if constexpr (B == B_GT) return a > b ? 1.0f : 0.0f;
     else if constexpr (B == B_GE) return a >= b ? 1.0f : 0.0f;
+    // exp of a difference: the difference is exact to one rounding, so the plain product with
+    // log2(e) keeps the relative error below |a - b| * 2^-24 (5e-6 at the overflow threshold)
+    else if constexpr (B == B_EXPSUB) return f_exp2((a - b) * LOG2E);
+    else if constexpr (B == B_REXPSUB) return f_exp2((b - a) * LOG2E);
     else return a;
 }
 
@@ -191,7 +195,7 @@ DI float bin_dyn(uint32_t b, float x, float y) {
     switch (b) {
 #define C(B) case B: return bin_op<B>(x, y);
         C(B_NONE) C(B_ADD) C(B_SUB) C(B_RSUB) C(B_MUL) C(B_DIV) C(B_RDIV) C(B_MIN) C(B_MAX) C(B_POW)
-        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE)
+        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE) C(B_EXPSUB) C(B_REXPSUB)
 #undef C
         default: return x;
     }
@@ -230,7 +234,7 @@ template <int K> DI void tile_bin_dispatch(Tile<K> &a, const Tile<K> &b, uint32_
     switch (op) {
 #define C(B) case B: tile_bin<K, B>(a, b); break;
         C(B_NONE) C(B_ADD) C(B_SUB) C(B_RSUB) C(B_MUL) C(B_DIV) C(B_RDIV) C(B_MIN) C(B_MAX) C(B_POW)
-        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE)
+        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE) C(B_EXPSUB) C(B_REXPSUB)
 #undef C
         default: break;
     }
@@ -239,7 +243,7 @@ template <int K> DI void tile_bins_dispatch(Tile<K> &a, float s, uint32_t op) {
     switch (op) {
 #define C(B) case B: tile_bins<K, B>(a, s); break;
         C(B_NONE) C(B_ADD) C(B_SUB) C(B_RSUB) C(B_MUL) C(B_DIV) C(B_RDIV) C(B_MIN) C(B_MAX) C(B_POW)
-        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE)
+        C(B_RPOW) C(B_EQ) C(B_NE) C(B_LT) C(B_LE) C(B_GT) C(B_GE) C(B_EXPSUB) C(B_REXPSUB)
 #undef C
         default: break;
     }
@@ -592,6 +596,10 @@ typedef uint32_t u32x4s __attribute__((ext_vector_type(4)));
 DI u32x4s fetch4(const uint32_t *code, uint32_t pc) {
     return *(const u32x4s *)__builtin_assume_aligned(code + pc, 16);
 }
+// the same with a byte offset: one scalar load with a register offset, no 64-bit address arithmetic
+DI u32x4s fetch4b(const uint32_t *code, uint32_t byte_off) {
+    return *(const u32x4s *)__builtin_assume_aligned((const char *)code + (uint64_t)byte_off, 16);
+}
 
 DI float pick_s(float s0, float s1, float s2, float s3, uint32_t i) {
     float v = s0;
@@ -760,15 +768,16 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
             const uint32_t first = tile == t_lo ? body : body + sh[S_PROLOG];
-            u32x4s nw = fetch4(code, first);
-            for (uint32_t pc = first; pc < body_end;) {
+            // (the program counter is a byte offset into the code)
+            u32x4s nw = fetch4b(code, first * 4);
+            for (uint32_t pcb = first * 4; pcb < body_end * 4;) {
                 const u32x4s cw = nw;
                 // (elements are copied to scalars first: bit-casting a vector element directly is miscompiled)
                 const uint32_t w = cw.x, cw1 = cw.y, cw2 = cw.z, cw3 = cw.w;
-                const uint32_t op = w & 0xFF, len = (w >> 8) & 0xFF, a = (w >> 16) & 0xFF, b = w >> 24;
-                const uint32_t cur = pc;
-                pc += len == LEN_VLOAD ? LEN_VLOAD : LEN_REC;
-                nw = fetch4(code, pc);
+                const uint32_t op = w & 0xFF, a = (w >> 16) & 0xFF, b = w >> 24;
+                const uint32_t cur = pcb >> 2;
+                pcb += (w >> 6) & 0x3FCu;       // record length in words, times four
+                nw = fetch4b(code, pcb);
                 switch (op) {
                     case I_LOAD:
                     case I_VLOAD: {
