@@ -1120,7 +1120,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     auto find_variant = [&](int K) {
         int best = -1;
         for (int i = 0; i < N_VARIANTS; ++i)
-            if (VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
+            if (VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && VARIANTS[i].NR <= ctx->max_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
         return best;
     };
     auto slots_per_cu = [&](const Variant &v, uint32_t threads) {
