@@ -611,6 +611,7 @@ struct Enc {
         if (in_acc == n) return true;
         save_acc_if_live();
         if (reg_of[n] >= 0) emit(I_MOVAR, (uint8_t)reg_of[n]);
+        else if (rows_class[n]) emit(I_BIN, (uint8_t)(SRC_S0 + sreg(n)), (uint8_t)B_NONE);   // Table 1 Broadcast: row value -> tile
         else if (is_input(n)) emit(I_LOAD, (uint8_t)SRC_ACC, (uint8_t)B_NONE, tensor_of_input(n));
         else return fail(DVM_E_UNSUPPORTED, "internal: value lost during linearisation");
         in_acc = n;
@@ -619,6 +620,7 @@ struct Enc {
     // the accumulator holds `n` and is about to be overwritten: keep a copy if n is needed later
     void preserve(int n, int pending_uses) {
         if (uses[n] - pending_uses <= 0 || reg_of[n] >= 0) return;
+        if (rows_class[n]) return;          // a row value lives on in its row-scalar register
         if (is_input(n)) {
             int free_regs = 0;
             for (int i = 0; i < nr_limit; ++i) free_regs += regs[i] < 0;
@@ -629,6 +631,9 @@ struct Enc {
     }
     int to_reg(int n) {                 // make sure a tile value sits in some R register
         if (reg_of[n] >= 0) return reg_of[n];
+        if (rows_class[n] && in_acc != n) {     // a row value needed as a tile: broadcast it through the accumulator
+            to_acc(n);
+        }
         if (in_acc == n) {
             const int r = alloc_reg(n);
             emit(I_MOVRA, (uint8_t)r);
@@ -1042,8 +1047,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 break;
             }
             case N_SEL: {
-                if (rows || E.rows_class[nd.a] || E.rows_class[nd.b] || E.rows_class[nd.c]) {
-                    E.fail(DVM_E_UNSUPPORTED, "select with row-value operands");
+                if (rows) {
+                    E.fail(DVM_E_UNSUPPORTED, "select among row values only");
                     break;
                 }
                 const int rb = E.to_reg(nd.b);
@@ -1489,7 +1494,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (l != LEN_REC || bb == 0 || bb >= U_COUNT) return bad("unary op");
                     break;
                 case I_BIN:
-                    if (bb == 0 || bb >= B_COUNT) return bad("binary op");
+                    if (bb >= B_COUNT || (bb == B_NONE && a < SRC_S0)) return bad("binary op");
                     if (l != LEN_REC) return bad("binary op length");
                     if (!(a == SRC_IMM || a == SRC_ACC || reg_ok(a, vr) || (a >= SRC_S0 && sreg_ok(a - SRC_S0)))) return bad("binary source");
                     break;
