@@ -32,7 +32,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 # rocprofv3 summaries of this command (kernel trace and the two HBM byte counters) per workload
-PROFILE_SUMMARY = {"c2_rmsnorm": "profiles/dvm_vm_kernel_c2_rmsnorm.md", "c4_chain": "profiles/dvm_vm_kernel_c4_chain.md"}
+PROFILE_SUMMARY = {"c2_rmsnorm": "profiles/dvm_vm_kernel_c2_rmsnorm.md", "c4_chain": "profiles/dvm_vm_kernel_c4_chain.md",
+                   "layernorm_bf16": "profiles/dvm_vm_kernel_layernorm_bf16.md"}
 
 
 def measured_traffic(workload: str):
@@ -54,7 +55,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c2_rmsnorm", choices=["c2_rmsnorm", "c4_chain"])
+    ap.add_argument("--workload", default="c2_rmsnorm", choices=["c2_rmsnorm", "c4_chain", "layernorm_bf16"])
     ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = all)")
     ap.add_argument("--stack", type=int, default=0,
                     help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
@@ -100,6 +101,15 @@ def main() -> int:
             insts.append(([d["x"], d["w"]], [torch.empty_like(d["x"])], gen.c2_bytes(b, s), (b, s)))
         wl = {"workload": "config 2: fused RMSNorm bf16, x[B,S,4096], 200 dynamic instances (B 1..32, S 1..2048)",
               "instances": len(insts), "hidden": 4096, "eps": 1e-6}
+    elif args.workload == "layernorm_bf16":
+        # the LayerNorm subgraph range of the paper's Table 2 ([b, 8192, h]); the first 24 of the seeded stream
+        shapes = gen.layernorm_paper_shapes()[: args.instances or 24]
+        insts = []
+        for i, (b, s_, h) in enumerate(shapes):
+            d = gen.layernorm_inputs(b, s_, h, gen.BASE_SEED + 6000 + 3 * i, dev)
+            insts.append(([d["x"], d["gamma"], d["beta"]], [torch.empty_like(d["x"])], gen.layernorm_bytes(b, s_, h), (b, s_, h)))
+        wl = {"workload": "LayerNorm bf16 over [b, 8192, h], b 1..60, h in {1024, 2048, 3072, 4096} (the paper's Table 2 range), eps 1e-5",
+              "instances": len(insts)}
     else:
         shapes = gen.c4_shapes()
         if args.instances:
@@ -242,36 +252,46 @@ def main() -> int:
     # ---- the CPU oracle on a bounded sample of the same workload (a baseline, not the target) -----
     if not args.no_cpu_baseline:
         from oracle import interp
-        budget_rows = 100000 if args.workload == "c2_rmsnorm" else 25000
+        budget_rows = 25000 if args.workload == "c4_chain" else 100000
+        # whole instances while they fit the budget, else the leading rows of one (rows are independent)
         rows, sample = 0, []
         for i, (ins, outs, nbytes, shp) in enumerate(insts):
             r = int(np.prod(ins[0].shape[:-1]))
-            if rows + r > budget_rows and sample:
-                continue
-            if r > budget_rows:
-                continue
-            sample.append(i)
-            rows += r
-            if len(sample) >= 40:
+            if r <= budget_rows - rows:
+                sample.append((i, r))
+                rows += r
+            if len(sample) >= 40 or rows >= budget_rows:
                 break
+        if not sample:
+            r0 = int(np.prod(insts[0][0][0].shape[:-1]))
+            sample.append((0, min(r0, budget_rows)))
+            rows = sample[0][1]
+
+        def head_rows(t, n):
+            """The first n rows of a tensor with the full leading shape; broadcast vectors stay whole."""
+            if t.dim() >= 2 and t.numel() // t.shape[-1] >= n and t.shape[:-1] == insts_lead:
+                return t.reshape(-1, t.shape[-1])[:n]
+            return t
         host_inputs = []
-        for i in sample:
-            ins = insts[i][0]
-            host_inputs.append({n: t.detach().cpu().to(torch.float64).numpy() for (n, _), t in zip(desc.inputs, ins)})
+        for i, n in sample:
+            insts_lead = insts[i][0][0].shape[:-1]
+            host_inputs.append({nm: head_rows(t, n).detach().cpu().to(torch.float64).numpy()
+                                for (nm, _), t in zip(desc.inputs, insts[i][0])})
         t0 = perf()
         refs = [interp.run(desc, hi) for hi in host_inputs]
         cpu_s = perf() - t0
-        cpu_bytes = sum(insts[i][2] for i in sample)
+        cpu_bytes = sum(insts[i][2] * n / int(np.prod(insts[i][0][0].shape[:-1])) for i, n in sample)
         # the same sample doubles as an end-to-end check of the benchmarked path
         worst = 0.0
-        for i, (rounded, exact) in zip(sample, refs):
-            got = insts[i][1][0].detach().cpu().to(torch.float64).numpy()
-            ref = rounded[desc.outputs[0][0]]
-            scale = interp.row_scale(exact[desc.outputs[0][0]])
+        for (i, n), (rounded, exact) in zip(sample, refs):
+            H_last = insts[i][0][0].shape[-1]
+            got = insts[i][1][0].reshape(-1, H_last)[:n].detach().cpu().to(torch.float64).numpy()
+            ref = rounded[desc.outputs[0][0]].reshape(-1, H_last)
+            scale = interp.row_scale(exact[desc.outputs[0][0]]).reshape(-1, 1)
             tol = 2e-2 * np.abs(ref) + 2e-2 * scale
             worst = max(worst, float(np.max(np.abs(got - ref) / np.maximum(tol, 1e-300))))
         result["cpu_baseline"] = {"value": round(cpu_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-                                  "sample": f"{len(sample)} instances of the same stream ({rows} rows of the hidden size), "
+                                  "sample": f"{len(sample)} instances (or their leading rows) of the same stream, {rows} rows in all, "
                                             f"{cpu_s:.1f} s of NumPy float64 per-op evaluation",
                                   "max_err_over_tol_vs_gpu": round(worst, 4)}
         if worst > 1.0:

@@ -1585,8 +1585,13 @@ extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, vo
         if (w[PH_BLOCK] > block) block = w[PH_BLOCK];
         if ((w[PH_VARIANT] & 0xFF) > K) K = w[PH_VARIANT] & 0xFF;
         if (((w[PH_VARIANT] >> 8) & 0xFF) > NR) NR = (w[PH_VARIANT] >> 8) & 0xFF;
-        if (w[PH_GRID] > grid) grid = w[PH_GRID];
+        // every part was planned to fill the machine with workgroups of its own size: what carries
+        // over to the common workgroup size is the number of resident waves, not of workgroups
+        const uint64_t part_waves = (uint64_t)w[PH_GRID] * ((w[PH_BLOCK] + 63) / 64);
+        if (part_waves > grid) grid = part_waves;
     }
+    grid = grid / ((block + 63) / 64);
+    if (grid == 0 && nseg > 0) grid = 1;
     if (ntens > DVM_MAX_TENSORS) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: too many tensors for one launch");
     if (nseg > 64) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: too many segments");
     if (seg_words * 4 > DVM_CODE_MAX_BYTES) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: bytecode exceeds the per-launch limit");
@@ -1623,11 +1628,22 @@ extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, vo
         const uint32_t off = PH_WORDS_N + nt * TT_WORDS;
         const uint32_t sw = c[PH_WORDS] - off;
         memcpy(sg, c + off, (size_t)sw * 4);
-        // rebase the tensor indices of the copied segments
+        // rebase the tensor indices of the copied segments, and re-tile row-mode segments to the
+        // launch's workgroup size: a part planned for fewer threads takes more rows per tile
+        // instead of leaving the other threads of the common workgroup idle
         uint32_t at = 0;
         for (uint32_t s = 0; s < c[PH_NSEG]; ++s) {
-            sg[at + S_TBASE] += tbase;
-            at += sg[at + S_WORDS];
+            uint32_t *sh = sg + at;
+            sh[S_TBASE] += tbase;
+            const uint32_t G = sh[S_GEOM] & 0xFFFF, RP = sh[S_RP] & 0xFFFF;
+            if (sh[S_NCT] == 1 && G <= block && sh[S_NROWS] > 0) {
+                const uint32_t rp_new = block / G;
+                if (rp_new > RP && rp_new <= 0xFFFF) {
+                    sh[S_RP] = rp_new | ((rp_new * G) << 16);
+                    sh[S_NTILES] = (sh[S_NROWS] + rp_new - 1) / rp_new;
+                }
+            }
+            at += sh[S_WORDS];
         }
         sg += sw;
         tbase += nt;

@@ -178,6 +178,18 @@ def c2_bytes(B: int, S: int, H: int = 4096) -> int:
     return 2 * B * S * H * 2 + H * 2
 
 
+def layernorm_inputs(b: int, s: int, h: int, seed: int, device="cpu") -> Dict[str, torch.Tensor]:
+    return {
+        "x": randn((b, s, h), seed, device, "bf16"),
+        "gamma": randn((h,), seed + 1, device, "bf16", mean=1.0, std=0.1),
+        "beta": randn((h,), seed + 2, device, "bf16", std=0.1),
+    }
+
+
+def layernorm_bytes(b: int, s: int, h: int) -> int:
+    return 2 * b * s * h * 2 + 2 * h * 2
+
+
 def c3_bytes(B: int, S: int, heads: int = 32) -> int:
     return 2 * B * heads * S * S * 4 + S * S * 4
 
