@@ -32,8 +32,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 # rocprofv3 summaries of this command (kernel trace and the two HBM byte counters) per workload
-PROFILE_SUMMARY = {"c2_rmsnorm": "profiles/dvm_vm_kernel_c2_rmsnorm.md", "c4_chain": "profiles/dvm_vm_kernel_c4_chain.md",
-                   "layernorm_bf16": "profiles/dvm_vm_kernel_layernorm_bf16.md"}
+PROFILE_SUMMARY = {w: f"profiles/dvm_vm_kernel_{w}.md"
+                   for w in ("c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16")}
 
 
 def measured_traffic(workload: str):
@@ -55,16 +55,17 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c2_rmsnorm", choices=["c2_rmsnorm", "c4_chain", "layernorm_bf16"])
-    ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = all)")
+    ap.add_argument("--workload", default="c2_rmsnorm",
+                    choices=["c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16"])
+    ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = the workload's default)")
     ap.add_argument("--stack", type=int, default=0,
                     help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
-                         "launch's tensor table; 1 = every instance its own launch)")
+                         "launch's tensor table; 1 = every instance its own launch; config 5 always stacks a layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-unstacked", action="store_true",
-                    help="leave out the second pass that launches every instance on its own (profiler runs use this so "
+                    help="leave out the second pass that launches every program on its own (profiler runs use this so "
                          "that the kernel statistics cover the stacked launches only)")
-    ap.add_argument("--dump-launches", default="", help="write per-instance bytes and mean launch time to this CSV file")
+    ap.add_argument("--dump-launches", default="", help="write per-program bytes and mean launch time to this CSV file")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 256 MiB device copy (a known-size kernel that scales "
                          "the HBM byte counters of a profiler run)")
@@ -87,62 +88,121 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ctx = B.Context(0)
-    desc = W.get_program(args.workload)
-    prog = B.Program(desc)
+    progs = {}
+
+    def program(name):
+        if name not in progs:
+            progs[name] = (W.get_program(name), B.Program(W.get_program(name)))
+        return progs[name]
 
     # ---- synthetic inputs, resident in HBM -----------------------------------------------------
+    # a part is one program applied to one set of tensors; `groups` lists the parts of each launch
+    parts = []
+
+    def add_part(name, ins_d, nbytes, shape, outs=None):
+        desc, prog = program(name)
+        ins = [ins_d[n] for n, _ in desc.inputs]
+        if outs is None:
+            shapes = [tuple(t.shape) for t in ins]
+            full = max(shapes, key=lambda sh: (len(sh), int(np.prod(sh))))
+            out_shape = tuple(np.broadcast_shapes(*shapes)) if len(shapes) > 1 else full
+            outs_l = [torch.empty(out_shape, dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device=dev)
+                      for _, dt in desc.outputs]
+            layout = None
+        else:
+            outs_l = [outs[n] for n, _ in desc.outputs]
+            layout = (B.dvm_shape * len(outs_l))(*[B.shape_of_tensor(t) for t in outs_l])
+        parts.append({"name": name, "desc": desc, "prog": prog, "ins": ins, "outs": outs_l, "bytes": nbytes, "shape": shape,
+                      "shapes": (B.dvm_shape * len(ins))(*[B.shape_of_tensor(t) for t in ins]), "layout": layout})
+
+    fixed_groups = None
+    default_budget = 4e8        # elements of the first input the CPU oracle is given (about 10-30 s)
     if args.workload == "c2_rmsnorm":
-        shapes = gen.c2_shapes()
-        if args.instances:
-            shapes = shapes[: args.instances]
-        insts = []
+        shapes = gen.c2_shapes()[: args.instances or None]
         for i, (b, s) in enumerate(shapes):
-            d = gen.c2_inputs(b, s, gen.BASE_SEED + 2000 + i, dev)
-            insts.append(([d["x"], d["w"]], [torch.empty_like(d["x"])], gen.c2_bytes(b, s), (b, s)))
+            add_part("c2_rmsnorm", gen.c2_inputs(b, s, gen.BASE_SEED + 2000 + i, dev), gen.c2_bytes(b, s), (b, s))
         wl = {"workload": "config 2: fused RMSNorm bf16, x[B,S,4096], 200 dynamic instances (B 1..32, S 1..2048)",
-              "instances": len(insts), "hidden": 4096, "eps": 1e-6}
+              "instances": len(parts), "hidden": 4096, "eps": 1e-6}
     elif args.workload == "layernorm_bf16":
         # the LayerNorm subgraph range of the paper's Table 2 ([b, 8192, h]); the first 24 of the seeded stream
         shapes = gen.layernorm_paper_shapes()[: args.instances or 24]
-        insts = []
         for i, (b, s_, h) in enumerate(shapes):
-            d = gen.layernorm_inputs(b, s_, h, gen.BASE_SEED + 6000 + 3 * i, dev)
-            insts.append(([d["x"], d["gamma"], d["beta"]], [torch.empty_like(d["x"])], gen.layernorm_bytes(b, s_, h), (b, s_, h)))
+            add_part("layernorm_bf16", gen.layernorm_inputs(b, s_, h, gen.BASE_SEED + 6000 + 3 * i, dev),
+                     gen.layernorm_bytes(b, s_, h), (b, s_, h))
         wl = {"workload": "LayerNorm bf16 over [b, 8192, h], b 1..60, h in {1024, 2048, 3072, 4096} (the paper's Table 2 range), eps 1e-5",
-              "instances": len(insts)}
-    else:
-        shapes = gen.c4_shapes()
-        if args.instances:
-            shapes = shapes[: args.instances]
-        insts = []
+              "instances": len(parts)}
+    elif args.workload == "c4_chain":
+        shapes = gen.c4_shapes()[: args.instances or None]
         for i, t in enumerate(shapes):
-            d = gen.c4_inputs(t, gen.BASE_SEED + 4000 + i, dev)
-            ins = [d[n] for n, _ in desc.inputs]
-            insts.append((ins, [torch.empty_like(d["x"])], gen.c4_bytes(t), (t,)))
+            add_part("c4_chain", gen.c4_inputs(t, gen.BASE_SEED + 4000 + i, dev), gen.c4_bytes(t), (t,))
         wl = {"workload": "config 4: 12-op transformer non-GEMM chain bf16 over [T,8192], 100 dynamic instances",
-              "instances": len(insts), "hidden": 8192}
+              "instances": len(parts), "hidden": 8192}
+        default_budget = 2e8
+    elif args.workload == "c1_gelu":
+        add_part("c1_gelu_erf", gen.c1_inputs(gen.BASE_SEED + 1, dev), 4 * 1000 * 4 * 2 + 2 * 1000 * 4, (4, 1000))
+        wl = {"workload": "config 1: gelu(x*a+b) fp32 on [4,1000] (latency-bound)", "instances": 1}
+    elif args.workload == "c3_masked_softmax":
+        # the first 16 instances of the seeded stream (the whole stream is 185 GB of traffic)
+        shapes = gen.c3_shapes()[: args.instances or 16]
+        for i, (b, s) in enumerate(shapes):
+            add_part("c3_masked_softmax", gen.c3_inputs(b, s, gen.BASE_SEED + 3000 + i, dev), gen.c3_bytes(b, s), (b, s))
+        wl = {"workload": "config 3: causal-masked softmax fp32 over [B,32,S,S] (B 1..4, S 128..4096), mask [S,S] broadcast",
+              "instances": len(parts)}
+        default_budget = 1.5e8
+    else:
+        # config 5: 64 steps of a 32-layer stack, six programs per layer, T log-normal; one buffer set per
+        # step shared by its 32 layers; every layer is one launch (its six programs stacked)
+        ctx.set_limits(16, 6)       # parts that share a launch must fit one interpreter variant
+        steps_T = gen.c5_steps()[: args.instances or None]
+        fixed_groups = []
+        for si, T in enumerate(steps_T):
+            d = gen.c5_inputs(T, gen.BASE_SEED + 5000 + 100 * si, dev)
+            rope_out = torch.empty((T, 32, 128), dtype=torch.bfloat16, device=dev)
+            L = T // 8 + 1
+            first = len(parts)
+            add_part("c5_rmsnorm", d["c5_rmsnorm"], (2 * T * 4096 + 4096) * 2, (T,))
+            add_part("c5_rope", d["c5_rope"], 2 * T * 32 * 128 * 2 + 2 * T * 64 * 4, (T,),
+                     {"y1": rope_out[..., :64], "y2": rope_out[..., 64:]})
+            add_part("c5_softmax", d["c5_softmax"], 2 * 32 * T * L * 2, (T,))
+            add_part("c5_residual", d["c5_residual_a"], 3 * T * 4096 * 2, (T,))
+            add_part("c5_silu_gate", d["c5_silu_gate"], 3 * T * 14336 * 2, (T,))
+            add_part("c5_residual", d["c5_residual_b"], 3 * T * 4096 * 2, (T,))
+            layer = list(range(first, first + 6))
+            fixed_groups += [layer] * 32
+        wl = {"workload": "config 5: 64 steps x 32 layers x {rmsnorm, rope, softmax, residual, silu-gate, residual} bf16, "
+                          "T log-normal (median 512, 1..8192); one launch per layer",
+              "instances": len(fixed_groups), "steps_of_the_stream": len(steps_T)}
+        default_budget = 1.5e8
     torch.cuda.synchronize()
-    total_bytes = sum(x[2] for x in insts)
 
-    # ---- marshalling prepared once: shapes as C structs, pointers as C arrays -------------------
+    # ---- launches: lists of part indices -------------------------------------------------------
     enc_cap = 8192
-    n_t_inst = len(insts[0][0]) + len(insts[0][1])
-    max_group = max(1, min(32 // n_t_inst, 10))
-    group = max(1, min(args.stack if args.stack > 0 else 8, max_group))
-    inst_shapes = [(B.dvm_shape * len(ins))(*[B.shape_of_tensor(t) for t in ins]) for ins, _, _, _ in insts]
-    n_in = len(insts[0][0])
+    if fixed_groups is not None:
+        groups_idx = fixed_groups
+        group = 6
+        singles_idx = [[i] for g in fixed_groups for i in g]
+    else:
+        n_t_part = len(parts[0]["ins"]) + len(parts[0]["outs"])
+        max_group = max(1, min(32 // n_t_part, 10))
+        # default: eight per launch; config 3's instances are gigabytes each and differ in row length (a stacked
+        # launch runs all its parts with the largest tile register size among them), so they stay apart
+        default_stack = 1 if args.workload == "c3_masked_softmax" else 8
+        group = max(1, min(args.stack if args.stack > 0 else default_stack, max_group))
+        groups_idx = [list(range(lo, min(lo + group, len(parts)))) for lo in range(0, len(parts), group)]
+        singles_idx = [[i] for i in range(len(parts))]
+    total_bytes = sum(parts[i]["bytes"] for g in groups_idx for i in g)
 
-    def make_groups(g):
+    def marshal(groups):
         out = []
-        for lo in range(0, len(insts), g):
-            idx = list(range(lo, min(lo + g, len(insts))))
-            tens = [t for i in idx for t in insts[i][0] + insts[i][1]]
+        for idx in groups:
+            tens = [t for i in idx for t in parts[i]["ins"] + parts[i]["outs"]]
             out.append((idx, (C.c_void_p * len(tens))(*[t.data_ptr() for t in tens]), len(tens)))
         return out
 
-    part_bufs = [C.create_string_buffer(enc_cap) for _ in range(max_group)]
-    part_ptrs = (C.c_void_p * max_group)(*[C.cast(b, C.c_void_p) for b in part_bufs])
-    part_lens = (C.c_size_t * max_group)()
+    max_parts = max(len(g) for g in groups_idx)
+    part_bufs = [C.create_string_buffer(enc_cap) for _ in range(max_parts)]
+    part_ptrs = (C.c_void_p * max_parts)(*[C.cast(b, C.c_void_p) for b in part_bufs])
+    part_lens = (C.c_size_t * max_parts)()
     stacked = C.create_string_buffer(enc_cap)
     ln = C.c_size_t()
     stream = torch.cuda.current_stream()
@@ -150,12 +210,14 @@ def main() -> int:
     perf = time.perf_counter
 
     def one_step(groups, events=None, enc_us=None):
-        """Encode every instance, stack each group of consecutive instances into one launch (temporal
-        stacking; a group of one is launched as it is), run."""
+        """Encode every part, stack the parts of each launch (temporal stacking; a single part is launched
+        as it is), run."""
         for k, (idx, ptrs, n_t) in enumerate(groups):
             for j, i in enumerate(idx):
+                pt = parts[i]
                 t0 = perf()
-                st = lib.dvm_encode(ctx._h, prog._h, inst_shapes[i], n_in, None, part_bufs[j], enc_cap, C.byref(ln), None)
+                st = lib.dvm_encode(ctx._h, pt["prog"]._h, pt["shapes"], len(pt["ins"]), pt["layout"], part_bufs[j], enc_cap,
+                                    C.byref(ln), None)
                 t1 = perf()
                 if st != 0:
                     raise B.DvmError(st, "dvm_encode")
@@ -189,14 +251,14 @@ def main() -> int:
         torch.cuda.synchronize()
         return perf() - t0, evs
 
-    groups = make_groups(group)
+    groups = marshal(groups_idx)
     enc_us = []
     elapsed, all_events = timed(groups, args.steps, args.warmup, enc_us)
 
-    # the same stream with one launch per instance (no stacking): per-instance launch times
-    singles = make_groups(1)
+    # the same stream with every program as its own launch (no stacking): per-program launch times
     unstacked = not args.skip_unstacked
     if unstacked:
+        singles = marshal(singles_idx)
         elapsed1, events1 = timed(singles, args.steps, 1) if group > 1 else (elapsed, all_events)
 
     if args.calibrate_copy:
@@ -214,22 +276,26 @@ def main() -> int:
     achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
     large = single = None
     if unstacked:
-        inst_ms = [float(np.mean([events1[s][i][0].elapsed_time(events1[s][i][1]) for s in range(args.steps)]))
-                   for i in range(len(insts))]
+        one_ms = [float(np.mean([events1[s][k][0].elapsed_time(events1[s][k][1]) for s in range(args.steps)]))
+                  for k in range(len(singles_idx))]
+        one_bytes = [parts[g[0]]["bytes"] for g in singles_idx]
         if args.dump_launches:
             with open(args.dump_launches, "w") as f:
-                f.write("instance,shape,bytes,mean_launch_us,GBps\n")
-                for i, (_, _, nbytes, shp) in enumerate(insts):
-                    f.write(f"{i},{'x'.join(map(str, shp))},{nbytes},{inst_ms[i] * 1e3:.2f},{nbytes / inst_ms[i] / 1e6:.1f}\n")
-        # the large instances (beyond the 256 MB Infinity Cache), launched one by one
-        big = [i for i, (_, _, b, _) in enumerate(insts) if b >= 256e6]
+                f.write("launch,program,shape,bytes,mean_launch_us,GBps\n")
+                for k, g in enumerate(singles_idx):
+                    pt = parts[g[0]]
+                    f.write(f"{k},{pt['name']},{'x'.join(map(str, pt['shape']))},{pt['bytes']},{one_ms[k] * 1e3:.2f},"
+                            f"{pt['bytes'] / one_ms[k] / 1e6:.1f}\n")
+        # the large launches (beyond the 256 MB Infinity Cache), each program on its own
+        big = [k for k, b in enumerate(one_bytes) if b >= 256e6]
         if big:
-            large = {"instances": len(big),
-                     "GBps": round(sum(insts[i][2] for i in big) / sum(inst_ms[i] for i in big) / 1e6, 1)}
+            large = {"launches": len(big),
+                     "GBps": round(sum(one_bytes[k] for k in big) / sum(one_ms[k] for k in big) / 1e6, 1)}
         single = {"value": round(total_bytes * args.steps / elapsed1 / 1e9, 2), "unit": "GB/s",
-                  "avg_launch_ms": round(float(np.mean(inst_ms)), 5),
-                  "achieved": round(total_bytes / len(insts) / float(np.mean(inst_ms)) / 1e6, 2),
-                  "note": "same stream, every instance its own launch, HIP events around every launch"}
+                  "ms_per_step": round(elapsed1 / args.steps * 1e3, 4),
+                  "avg_launch_ms": round(float(np.mean(one_ms)), 5),
+                  "achieved": round(sum(one_bytes) / sum(one_ms) / 1e6, 2),
+                  "note": "same stream, every program its own launch, HIP events around every launch"}
     enc = np.array(enc_us)
 
     wl["instances_per_launch"] = group
@@ -252,46 +318,59 @@ def main() -> int:
     # ---- the CPU oracle on a bounded sample of the same workload (a baseline, not the target) -----
     if not args.no_cpu_baseline:
         from oracle import interp
-        budget_rows = 25000 if args.workload == "c4_chain" else 100000
-        # whole instances while they fit the budget, else the leading rows of one (rows are independent)
-        rows, sample = 0, []
-        for i, (ins, outs, nbytes, shp) in enumerate(insts):
-            r = int(np.prod(ins[0].shape[:-1]))
-            if r <= budget_rows - rows:
-                sample.append((i, r))
-                rows += r
-            if len(sample) >= 40 or rows >= budget_rows:
+        budget = default_budget
+        # distinct parts in stream order while they fit the budget (elements of the first input); if none
+        # fits, the leading rows of the first part (its rows are independent and its other inputs are vectors)
+        used, sample, seen = 0.0, [], set()
+        for g in groups_idx:
+            for i in g:
+                n_el = parts[i]["ins"][0].numel()
+                if i in seen or n_el > budget - used:
+                    continue
+                seen.add(i)
+                sample.append((i, None))
+                used += n_el
+            if len(sample) >= 40 or used >= 0.9 * budget:
                 break
         if not sample:
-            r0 = int(np.prod(insts[0][0][0].shape[:-1]))
-            sample.append((0, min(r0, budget_rows)))
-            rows = sample[0][1]
+            x = parts[0]["ins"][0]
+            sample.append((0, max(1, int(budget // x.shape[-1]))))
+            used = sample[0][1] * x.shape[-1]
 
-        def head_rows(t, n):
+        def head_rows(t, lead, n):
             """The first n rows of a tensor with the full leading shape; broadcast vectors stay whole."""
-            if t.dim() >= 2 and t.numel() // t.shape[-1] >= n and t.shape[:-1] == insts_lead:
-                return t.reshape(-1, t.shape[-1])[:n]
-            return t
+            if n is None or t.dim() < 2 or tuple(t.shape[:-1]) != lead:
+                return t
+            return t.reshape(-1, t.shape[-1])[:n]
         host_inputs = []
         for i, n in sample:
-            insts_lead = insts[i][0][0].shape[:-1]
-            host_inputs.append({nm: head_rows(t, n).detach().cpu().to(torch.float64).numpy()
-                                for (nm, _), t in zip(desc.inputs, insts[i][0])})
+            pt = parts[i]
+            lead = tuple(pt["ins"][0].shape[:-1])
+            host_inputs.append({nm: head_rows(t, lead, n).detach().cpu().to(torch.float64).numpy()
+                                for (nm, _), t in zip(pt["desc"].inputs, pt["ins"])})
         t0 = perf()
-        refs = [interp.run(desc, hi) for hi in host_inputs]
+        refs = [interp.run(parts[i]["desc"], hi) for (i, _), hi in zip(sample, host_inputs)]
         cpu_s = perf() - t0
-        cpu_bytes = sum(insts[i][2] * n / int(np.prod(insts[i][0][0].shape[:-1])) for i, n in sample)
+        cpu_bytes = sum(parts[i]["bytes"] * (1.0 if n is None else n / (parts[i]["ins"][0].numel() // parts[i]["ins"][0].shape[-1]))
+                        for i, n in sample)
         # the same sample doubles as an end-to-end check of the benchmarked path
         worst = 0.0
         for (i, n), (rounded, exact) in zip(sample, refs):
-            H_last = insts[i][0][0].shape[-1]
-            got = insts[i][1][0].reshape(-1, H_last)[:n].detach().cpu().to(torch.float64).numpy()
-            ref = rounded[desc.outputs[0][0]].reshape(-1, H_last)
-            scale = interp.row_scale(exact[desc.outputs[0][0]]).reshape(-1, 1)
-            tol = 2e-2 * np.abs(ref) + 2e-2 * scale
-            worst = max(worst, float(np.max(np.abs(got - ref) / np.maximum(tol, 1e-300))))
+            pt = parts[i]
+            for (nm, dt), out_t in zip(pt["desc"].outputs, pt["outs"]):
+                got = out_t.detach().cpu().to(torch.float64).numpy()
+                ref = rounded[nm]
+                if n is not None:
+                    got = got.reshape(-1, got.shape[-1])[:n]
+                    ref = ref.reshape(-1, ref.shape[-1])
+                rtol = 2e-2 if dt == "bf16" else 1e-4
+                scale = np.broadcast_to(interp.row_scale(exact[nm]).reshape(ref.shape[:-1] + (1,)), ref.shape)
+                tol = rtol * np.abs(ref) + rtol * scale
+                fin = np.isfinite(ref)
+                worst = max(worst, float(np.max(np.where(fin, np.abs(got - ref) / np.maximum(tol, 1e-300), 0.0))))
         result["cpu_baseline"] = {"value": round(cpu_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-                                  "sample": f"{len(sample)} instances (or their leading rows) of the same stream, {rows} rows in all, "
+                                  "sample": f"{len(sample)} programs (or their leading rows) of the same stream, "
+                                            f"{int(used)} elements of their first inputs, "
                                             f"{cpu_s:.1f} s of NumPy float64 per-op evaluation",
                                   "max_err_over_tol_vs_gpu": round(worst, 4)}
         if worst > 1.0:
