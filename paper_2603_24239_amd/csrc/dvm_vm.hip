@@ -369,7 +369,10 @@ DI void st_b16(gptr p, uint32_t v, bool ok) {
 // DT: 0 = fp32, 1 = bf16.  V = chunk width.  `rowp` points at column `colbase` of the lane's row in
 // this tensor (row 0 for a lane whose row is outside the tensor).  A chunk that lies beyond the
 // tile's columns reads the tile's chunk 0 instead: the value is never stored and reductions mask it.
-template <int K> struct Raw { f32x4 q[K / 4]; };
+template <int K> struct Raw {
+    f32x4 q[K / 4];     // the whole chunks, 16 bytes per piece
+    uint32_t pv[8];     // the elements of the chunk the row ends in (raw bits), requested alongside
+};
 typedef f32x4 f32x4_a2 __attribute__((aligned(2)));
 
 // Dtype, chunk width and cache hint are fixed at compile time, so the request needs no per-piece
@@ -389,6 +392,16 @@ template <int K, int DT, int V, bool NT> DI void request_tile_static(Raw<K> &raw
                     if constexpr (NT) raw.q[J * PIECES + H] = __builtin_nontemporal_load(src);
                     else raw.q[J * PIECES + H] = *src;
                 });
+            });
+        }
+        if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
+            // its elements are read one by one by every lane of the row (one of them keeps them), in
+            // flight together with the whole chunks; an element beyond the row reads element 0 again
+            sfor<V>([&]<int E>() LI {
+                const uint32_t e = (uint32_t)E < g.part_n ? (uint32_t)E : 0u;       // wave-uniform
+                gcptr q = rowp + (uint64_t)(g.part_col + e) * ES;
+                if constexpr (DT == 0) raw.pv[E] = *(const GLOBAL_AS uint32_t *)q;
+                else raw.pv[E] = *(const GLOBAL_AS uint16_t *)q;
             });
         }
     }
@@ -435,15 +448,12 @@ template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw
             }
         }
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
-            // its elements are read one by one by every lane of the row (one of them keeps them); all
-            // reads are requested before any is used, and an element beyond the row reads element 0 again
             const bool own = g.lr == g.part_lane;
             float pv[V];
             sfor<V>([&]<int E>() LI {
-                const uint32_t e = (uint32_t)E < g.part_n ? (uint32_t)E : 0u;       // wave-uniform
-                gcptr q = rowp + (uint64_t)(g.part_col + e) * ES;
-                if constexpr (DT == 0) pv[E] = *(const GLOBAL_AS float *)q;
-                else pv[E] = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
+                const uint32_t bits = raw.pv[E];
+                if constexpr (DT == 0) pv[E] = __builtin_bit_cast(float, bits);
+                else pv[E] = bf16_lo(bits);
             });
             sfor<NJ>([&]<int J>() LI {
                 if ((uint32_t)J == g.part_slot) {       // wave-uniform
