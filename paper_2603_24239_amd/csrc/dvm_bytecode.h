@@ -70,8 +70,9 @@ enum : int {
     S_NTENS,        // tensors of this segment
     S_FLAGS,        // SF_*
     S_IMASK,        // bit op -> the instruction id occurs in the body (for the disassembler)
-    S_PROLOG,       // words at the start of the body that run once per workgroup, before its first tile
-    S_PAD1,         // keeps the body 16-byte aligned
+    S_PROLOG,       // words at the start of the body that do not run for every tile: the prologue (pinned operands)
+    S_PROLOGA,      // the first S_PROLOGA words of the prologue run once per workgroup only; the rest of it runs
+                    // again whenever the index of the second outer dim (row / S_D1) differs from the previous tile's
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");

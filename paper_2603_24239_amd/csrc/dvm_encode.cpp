@@ -520,7 +520,7 @@ struct Enc {
     bool has_red;
     // linearisation
     AI ai[MAX_AI];
-    int n_ai, n_prolog;
+    int n_ai, n_prolog, n_prolog_a;
     int uses[MAX_NODES];
     int reg_of[MAX_NODES], sreg_of[MAX_NODES];
     int regs[NR_MAX], sregs[NS];
@@ -839,6 +839,34 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             ++ng;
         }
     }
+    // Order of the outer groups = order in which rows are visited (group 1 varies fastest).  A group
+    // along which some input is broadcast goes first: consecutive rows, and so the tiles one workgroup
+    // runs back to back, then read the same part of that input again and find it in cache, instead of
+    // every workgroup streaming the whole broadcast tensor once per repetition (a causal mask [S,S]
+    // under scores [B,H,S,S] would otherwise be fetched from memory B*H times).
+    if (ng > 2) {
+        auto carries_broadcast = [&](int g) {
+            for (int t = 0; t < prog->n_in; ++t) {
+                const Access &A = E.acc[t];
+                bool varies_elsewhere = false;
+                for (int h = 1; h < ng; ++h) varies_elsewhere |= (h != g && A.ostride[grp_first[h]] != 0 && grp_ext[h] > 1);
+                if (A.ostride[grp_first[g]] == 0 && grp_ext[g] > 1 && varies_elsewhere) return true;
+            }
+            return false;
+        };
+        int order[4] = {0, 1, 2, 3};
+        int n_first = 1;
+        for (int g = 1; g < ng; ++g)
+            if (carries_broadcast(g)) {     // move group g to position n_first, keeping the others in order
+                const int moved = order[g];
+                for (int h = g; h > n_first; --h) order[h] = order[h - 1];
+                order[n_first++] = moved;
+            }
+        int gf[4], gl[4];
+        int64_t ge[4];
+        for (int g = 0; g < ng; ++g) { gf[g] = grp_first[order[g]]; gl[g] = grp_last[order[g]]; ge[g] = grp_ext[order[g]]; }
+        for (int g = 0; g < ng; ++g) { grp_first[g] = gf[g]; grp_last[g] = gl[g]; grp_ext[g] = ge[g]; }
+    }
     // if the row axis exists it must be group 0; otherwise group 0 is whatever is innermost
     E.n_groups = ng;
     const bool g0_is_row = ng > 0 && E.row_axis && grp_first[0] == R - 1;
@@ -889,6 +917,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     // loaded once per workgroup into a pinned tile register by a prologue that runs before the
     // first tile, instead of once per tile.
     E.n_prolog = 0;
+    int hoisted = 0;
     for (int n = 0, left = hoist_budget; n < NN && left > 0; ++n) {
         const Node &nd = prog->nodes[n];
         if (nd.kind != N_IN || E.rows_class[n] || E.uses[n] == 0) continue;
@@ -900,6 +929,23 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         const int r = E.alloc_reg(n);
         E.emit(I_LOAD, (uint8_t)r, (uint8_t)B_NONE, nd.input);
         E.uses[n] += 1 << 20;           // pinned: never released
+        --left;
+        ++hoisted;
+    }
+    E.n_prolog_a = E.n_ai;
+    // Operands that are invariant along the fastest outer dim only (a mask [S,S] under [B*H,S,S] once that
+    // dim is the fastest) are pinned too; their loads run again when the slower index changes.
+    for (int n = 0, left = hoist_budget - hoisted; n < NN && left > 0 && ng >= 3 && E.Dg[1] >= 16; ++n) {
+        const Node &nd = prog->nodes[n];
+        if (nd.kind != N_IN || E.rows_class[n] || E.uses[n] == 0) continue;
+        const Access &A = E.acc[nd.input];
+        if (A.s[1] != 0 || (A.s[2] == 0 && A.s[3] == 0)) continue;
+        bool is_out = false;
+        for (int o = 0; o < prog->n_out; ++o) is_out |= prog->out_node[o] == n;
+        if (is_out) continue;
+        const int r = E.alloc_reg(n);
+        E.emit(I_LOAD, (uint8_t)r, (uint8_t)B_NONE, nd.input);
+        E.uses[n] += 1 << 20;
         --left;
     }
     E.n_prolog = E.n_ai;
@@ -1238,11 +1284,12 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
 
     // ---- 6. emit ---------------------------------------------------------------------------
     // size first
-    size_t body_words = 0, prolog_words = 0;
+    size_t body_words = 0, prolog_words = 0, prolog_a_words = 0;
     const bool view = ng > 2;       // more than one outer group: rows need the multi-stride form
     for (int i = 0; i < E.n_ai; ++i) {
         const AI &x = E.ai[i];
         if (i == E.n_prolog) prolog_words = body_words;
+        if (i == E.n_prolog_a) prolog_a_words = body_words;
         switch (x.op) {
             case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
             case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
@@ -1297,6 +1344,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_NTENS] = (uint32_t)E.n_acc;
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
+    sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
     uint32_t imask = 0;
     uint32_t *b = sh + SH_WORDS;
     auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
@@ -1446,7 +1494,10 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if (m != sh[S_NCTM] || sft != sh[S_NCTSH]) return bad("division constants of the column tiles");
         }
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
+        if (sh[S_PROLOGA] > sh[S_PROLOG] || (sh[S_PROLOGA] & 3)) return bad("prologue split");
+        if (sh[S_PROLOGA] != sh[S_PROLOG] && sh[S_D1] == 0) return bad("reloading prologue without a second outer dim");
         bool prolog_ends_on_record = sh[S_PROLOG] == 0;
+        bool prolog_a_ends_on_record = sh[S_PROLOGA] == 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
         if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
         tiles_total += M;
@@ -1458,6 +1509,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, bb = x >> 24;
             if ((l != LEN_REC && l != LEN_VLOAD) || pc + l > end) return bad("instruction length");
             if (pc + l == at + SH_WORDS + sh[S_PROLOG]) prolog_ends_on_record = true;
+            if (pc + l == at + SH_WORDS + sh[S_PROLOGA]) prolog_a_ends_on_record = true;
             if (pc < at + SH_WORDS + sh[S_PROLOG] && op != I_LOAD && op != I_VLOAD) return bad("prologue holds loads only");
             uint32_t want = LEN_REC;
             switch (op) {
@@ -1520,7 +1572,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             }
             pc += l;
         }
-        if (!prolog_ends_on_record) return bad("prologue does not end on a record boundary");
+        if (!prolog_ends_on_record || !prolog_a_ends_on_record) return bad("prologue does not end on a record boundary");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");
@@ -1711,9 +1763,11 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
               (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE]);
         size_t pc = at + SH_WORDS;
         const size_t end = pc + sh[S_CODESIZE];
-        if (sh[S_PROLOG]) o.put("  ; prologue (once per workgroup)\n");
+        if (sh[S_PROLOGA]) o.put("  ; prologue (once per workgroup)\n");
         while (pc < end) {
             if (sh[S_PROLOG] && pc == at + SH_WORDS + sh[S_PROLOG]) o.put("  ; body (once per tile)\n");
+            else if (sh[S_PROLOGA] != sh[S_PROLOG] && pc == at + SH_WORDS + sh[S_PROLOGA])
+                o.put("  ; prologue (again whenever the second outer index changes)\n");
             const uint32_t x = w[pc];
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, b = x >> 24;
             char ra[8], rb[8];

@@ -777,7 +777,19 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             }
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
-            const uint32_t first = tile == t_lo ? body : body + sh[S_PROLOG];
+            // (its second part runs again when the second outer index of the tile's first or last row
+            // differs from that of the previous tile: an operand pinned there varies with that index only)
+            uint32_t first = body;
+            if (tile != t_lo) {
+                first = body + sh[S_PROLOG];
+                if (sh[S_PROLOGA] != sh[S_PROLOG]) {
+                    const uint32_t m1 = sh[S_M1], sh1 = sh[S_SH1];
+                    const uint32_t ra = tile * RP;          // prologues exist in row mode only: tile = row tile
+                    const bool crossed = sdiv_u(ra, m1, sh1) != sdiv_u(ra - RP, m1, sh1) ||
+                                         sdiv_u(ra + RP - 1, m1, sh1) != sdiv_u(ra - 1, m1, sh1);
+                    if (crossed) first = body + sh[S_PROLOGA];
+                }
+            }
             // (the program counter is a byte offset into the code)
             u32x4s nw = fetch4b(code, first * 4);
             for (uint32_t pcb = first * 4; pcb < body_end * 4;) {
