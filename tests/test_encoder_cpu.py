@@ -257,3 +257,15 @@ def test_stream_hint_marks_tensors_read_once(ctx):
         pc += ln
     assert flags[0] & 8, "the score tensor is read exactly once"
     assert not (flags[1] & 8), "the mask is re-read for every batch and head"
+
+
+def test_broadcast_dim_is_visited_fastest_and_its_operand_pinned(ctx):
+    code = _encode(ctx, "c3_masked_softmax", [(2, 32, 256, 256), (256, 256)])
+    txt = code.disasm()
+    assert "outer=[64,0]" in txt                                    # batch*heads first, then the query index
+    assert "again whenever the second outer index changes" in txt   # the mask row is reloaded per query index only
+    body = txt.split("; body (once per tile)")[1]
+    assert len(re.findall(r"load", body)) == 1                      # only the scores are loaded per tile
+    # too few repetitions to be worth a register: the mask is loaded per tile
+    small = _encode(ctx, "c3_masked_softmax", [(1, 8, 256, 256), (256, 256)]).disasm()
+    assert "again whenever" not in small
