@@ -154,6 +154,15 @@ int  dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog,
 int  dvm_stack(const void *const *codes, const size_t *lens, int n,
                void *out, size_t cap, size_t *len);
 
+/* Spatial stacking (Section 5.1): like dvm_stack, but the parts run side by side in the one launch,
+ * each on its own share of the workgroups (in proportion to the bytes the part moves), instead of one
+ * after the other on all of them.  It pays when the parts are small: their ramp-up and tail overlap.
+ * Every part must be a single meta-kernel as dvm_encode produces it; more non-empty parts than the
+ * launch has workgroups gives DVM_E_UNSUPPORTED (use dvm_stack then).  Same arguments, ownership and
+ * error behaviour as dvm_stack. */
+int  dvm_stack_spatial(const void *const *codes, const size_t *lens, int n,
+                       void *out, size_t cap, size_t *len);
+
 /* Structural check of a bytecode blob: header fields, segment and instruction lengths, register
  * and tensor indices, launch geometry.  dvm_run calls it on every launch. */
 int  dvm_validate(const void *bytecode, size_t len);

@@ -83,6 +83,7 @@ def load() -> C.CDLL:
         "dvm_prog_destroy": (None, [vp]),
         "dvm_encode": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), P(dvm_shape)]),
         "dvm_stack": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
+        "dvm_stack_spatial": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
         "dvm_validate": (i, [vp, sz]),
         "dvm_disasm": (i, [vp, sz, C.c_char_p, sz]),
         "dvm_code_info_get": (i, [vp, sz, P(dvm_code_info)]),
@@ -103,7 +104,7 @@ def load() -> C.CDLL:
 
 EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_ctx_set_limits", "dvm_prog_create",
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
-            "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_validate", "dvm_disasm",
+            "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_validate", "dvm_disasm",
             "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_strerror", "dvm_last_error_detail",
             "dvm_last_hip_error"]
 
@@ -258,18 +259,23 @@ def dvm_encode(ctx: Context, prog: Program, in_shapes: Sequence[dvm_shape],
     return Bytecode(buf.raw[: ln.value], shapes)
 
 
-def dvm_stack(codes: Sequence[Bytecode]) -> Bytecode:
+def dvm_stack(codes: Sequence[Bytecode], spatial: bool = False) -> Bytecode:
     lib = load()
     n = len(codes)
     ptrs = (C.c_void_p * n)(*[c.ptr for c in codes])
     lens = (C.c_size_t * n)(*[len(c) for c in codes])
     buf = C.create_string_buffer(_ENC_CAP)
     ln = C.c_size_t()
-    _check(lib.dvm_stack(ptrs, lens, n, buf, _ENC_CAP, C.byref(ln)), "dvm_stack")
+    fn = lib.dvm_stack_spatial if spatial else lib.dvm_stack
+    _check(fn(ptrs, lens, n, buf, _ENC_CAP, C.byref(ln)), "dvm_stack_spatial" if spatial else "dvm_stack")
     shapes: List[Tuple[int, ...]] = []
     for c in codes:
         shapes.extend(c.out_shapes)
     return Bytecode(buf.raw[: ln.value], shapes)
+
+
+def dvm_stack_spatial(codes: Sequence[Bytecode]) -> Bytecode:
+    return dvm_stack(codes, spatial=True)
 
 
 def dvm_run(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: int = 0) -> None:

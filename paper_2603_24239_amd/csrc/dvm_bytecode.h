@@ -29,6 +29,7 @@ constexpr uint32_t VERSION = 1;
 // kernel types (Section 4.2: a meta-kernel on the vector path, or a stacking-based kernel)
 constexpr uint32_t KT_META  = 0;            // printed as "vmain.v"
 constexpr uint32_t KT_STACK = 1;            // temporally stacked meta-kernels, "vstack.t"
+constexpr uint32_t KT_STACK_SPATIAL = 2;    // spatially stacked: every segment runs on its own share of the workgroups, "vstack.s"
 
 // ---- program header -------------------------------------------------------------------------
 enum : int {
@@ -73,6 +74,8 @@ enum : int {
     S_PROLOG,       // words at the start of the body that do not run for every tile: the prologue (pinned operands)
     S_PROLOGA,      // the first S_PROLOGA words of the prologue run once per workgroup only; the rest of it runs
                     // again whenever the index of the second outer dim (row / S_D1) differs from the previous tile's
+    S_WG0, S_NWG,   // spatial stacking: this segment runs on workgroups [S_WG0, S_WG0 + S_NWG) only (S_NWG 0: on all)
+    S_PAD2, S_PAD3, // keep the body 16-byte aligned
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");

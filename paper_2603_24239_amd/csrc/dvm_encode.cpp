@@ -1433,7 +1433,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
     if (w[PH_MAGIC] != MAGIC) return bad("bad magic");
     if ((w[PH_TYPE] >> 16) != VERSION) return bad("unknown version");
     const uint32_t kt = w[PH_TYPE] & 0xFFFF;
-    if (kt != KT_META && kt != KT_STACK) return bad("unknown kernel type");
+    if (kt != KT_META && kt != KT_STACK && kt != KT_STACK_SPATIAL) return bad("unknown kernel type");
     const uint32_t words = w[PH_WORDS];
     if ((size_t)words * 4 != len) return bad("length field does not match the buffer");
     const uint32_t nseg = w[PH_NSEG], ntens = w[PH_NTENS];
@@ -1453,6 +1453,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
     }
     if ((words - at) * 4 > DVM_CODE_MAX_BYTES) return bad("segments exceed the per-launch limit");
     uint64_t tiles_total = 0;
+    uint32_t wg_next = 0;       // spatial stacking: first workgroup of the next segment's share
     for (uint32_t s = 0; s < nseg; ++s) {
         if (at + SH_WORDS > words) return bad("segment header runs past the end");
         const uint32_t *sh = w + at;
@@ -1494,6 +1495,18 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if (m != sh[S_NCTM] || sft != sh[S_NCTSH]) return bad("division constants of the column tiles");
         }
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
+        if (sh[S_PAD2] != 0 || sh[S_PAD3] != 0) return bad("padding words");
+        if (kt == KT_STACK_SPATIAL) {
+            if (sh[S_NWG] == 0 || sh[S_WG0] != wg_next) return bad("workgroup share of a spatially stacked segment");
+            if (sh[S_NTILES] != 0) {
+                if ((uint64_t)wg_next + sh[S_NWG] > w[PH_GRID]) return bad("workgroup shares exceed the grid");
+                wg_next += sh[S_NWG];
+            } else if (sh[S_NWG] != 1) {
+                return bad("workgroup share of an empty segment");
+            }
+        } else if (sh[S_NWG] != 0 || sh[S_WG0] != 0) {
+            return bad("workgroup share outside a spatially stacked program");
+        }
         if (sh[S_PROLOGA] > sh[S_PROLOG] || (sh[S_PROLOGA] & 3)) return bad("prologue split");
         if (sh[S_PROLOGA] != sh[S_PROLOG] && sh[S_D1] == 0) return bad("reloading prologue without a second outer dim");
         bool prolog_ends_on_record = sh[S_PROLOG] == 0;
@@ -1621,7 +1634,7 @@ extern "C" int dvm_code_tensor(const void *bytecode, size_t len, int index, int6
     return DVM_OK;
 }
 
-extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {
+static int stack_impl(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len, bool spatial) {
     if (!codes || !lens || !len || n < 1) return dvm_set_error(DVM_E_ARGS, "dvm_stack: bad argument");
     size_t seg_words = 0;
     uint32_t ntens = 0, nseg = 0, block = 0, K = 0, NR = 0;
@@ -1662,7 +1675,7 @@ extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, vo
     uint32_t *w = (uint32_t *)out;
     memset(w, 0, words * 4);
     w[PH_MAGIC] = MAGIC;
-    w[PH_TYPE] = KT_STACK | (VERSION << 16);
+    w[PH_TYPE] = (spatial ? KT_STACK_SPATIAL : KT_STACK) | (VERSION << 16);
     w[PH_WORDS] = (uint32_t)words;
     w[PH_NSEG] = nseg;
     w[PH_BLOCK] = block;
@@ -1700,7 +1713,75 @@ extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, vo
         sg += sw;
         tbase += nt;
     }
+    if (spatial) {
+        // Spatial stacking (Section 5.1): the segments run side by side, each on a share of the workgroups
+        // in proportion to the bytes it moves, at least one and at most one per tile.
+        uint32_t *seg[64];
+        double cost[64];
+        uint32_t share[64];
+        uint32_t ns = 0, at = PH_WORDS_N + ntens * TT_WORDS;
+        double total = 0;
+        for (uint32_t k = 0; k < nseg; ++k) {
+            uint32_t *sh = w + at;
+            seg[ns] = sh;
+            double c = 0;
+            for (uint32_t t = 0; t < sh[S_NTENS]; ++t) {
+                const uint32_t *te = w + PH_WORDS_N + (sh[S_TBASE] + t) * TT_WORDS;
+                c += (double)((uint64_t)te[TT_BYTES_LO] | ((uint64_t)te[TT_BYTES_HI] << 32));
+            }
+            if (sh[S_NTILES] == 0) c = 0;
+            cost[ns] = c;
+            total += c;
+            ++ns;
+            at += sh[S_WORDS];
+        }
+        uint32_t live = 0;
+        for (uint32_t k = 0; k < ns; ++k) live += seg[k][S_NTILES] != 0;
+        if (live > grid) return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_stack_spatial: more non-empty parts than resident workgroups");
+        uint32_t used = 0;
+        for (uint32_t k = 0; k < ns; ++k) {
+            uint32_t sh_k = 0;
+            if (seg[k][S_NTILES] != 0) {
+                sh_k = total > 0 ? (uint32_t)((double)grid * cost[k] / total) : 1;
+                if (sh_k < 1) sh_k = 1;
+                if (sh_k > seg[k][S_NTILES]) sh_k = seg[k][S_NTILES];
+            }
+            share[k] = sh_k;
+            used += sh_k;
+        }
+        // rounding may overshoot (minimum of one each) or leave workgroups over: trim from / add to the largest shares
+        while (used > grid) {
+            uint32_t best = 0;
+            for (uint32_t k = 1; k < ns; ++k) if (share[k] > share[best]) best = k;
+            --share[best];
+            --used;
+        }
+        for (bool grew = true; used < grid && grew;) {
+            grew = false;
+            for (uint32_t k = 0; k < ns && used < grid; ++k)
+                if (share[k] != 0 && share[k] < seg[k][S_NTILES] && cost[k] * grid >= total * share[k]) { ++share[k]; ++used; grew = true; }
+        }
+        uint32_t wg0 = 0;
+        for (uint32_t k = 0; k < ns; ++k) {
+            seg[k][S_WG0] = wg0;
+            seg[k][S_NWG] = share[k] ? share[k] : 1;       // an empty segment is skipped by its (zero) tile count anyway
+            wg0 += share[k];
+        }
+        w[PH_GRID] = wg0 ? wg0 : 1;
+    }
     return dvm_validate(out, words * 4);
+}
+
+extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {
+    return stack_impl(codes, lens, n, out, cap, len, false);
+}
+
+extern "C" int dvm_stack_spatial(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {
+    for (int i = 0; codes && lens && i < n; ++i) {
+        if (dvm_validate(codes[i], lens[i]) == DVM_OK && (((const uint32_t *)codes[i])[PH_TYPE] & 0xFFFF) != KT_META)
+            return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_stack_spatial: parts must be single meta-kernels");
+    }
+    return stack_impl(codes, lens, n, out, cap, len, true);
 }
 
 namespace {
@@ -1744,7 +1825,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
     Out o{txt, cap, 0};
     const uint32_t kt = w[PH_TYPE] & 0xFFFF;
     o.put("dvm program: kernel_type=%s block_dim=%u threads=%u variant=K%u/R%u segments=%u tensors=%u words=%u\n",
-          kt == KT_META ? "vmain.v" : "vstack.t", w[PH_GRID], w[PH_BLOCK], w[PH_VARIANT] & 0xFF, (w[PH_VARIANT] >> 8) & 0xFF,
+          kt == KT_META ? "vmain.v" : (kt == KT_STACK ? "vstack.t" : "vstack.s"), w[PH_GRID], w[PH_BLOCK], w[PH_VARIANT] & 0xFF, (w[PH_VARIANT] >> 8) & 0xFF,
           w[PH_NSEG], w[PH_NTENS], w[PH_WORDS]);
     for (uint32_t t = 0; t < w[PH_NTENS]; ++t) {
         const uint32_t *tt = w + PH_WORDS_N + t * TT_WORDS;

@@ -754,9 +754,19 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         const uint32_t width = G < 64 ? G : 64;
         const uint32_t w0i = gw > 1 ? (wave / gw) * gw : wave;   // first wave of this lane's row
 
-        // Algorithm 2: m = ceil(M / N); this workgroup runs tiles [m*id, min(M, m*(id+1)))
-        const uint32_t m = (M + ngrid - 1) / ngrid;
-        const uint64_t t_lo64 = (uint64_t)m * bid;
+        // Algorithm 2: m = ceil(M / N); this workgroup runs tiles [m*id, min(M, m*(id+1))).  In a
+        // spatially stacked launch N and id count the workgroups of this segment's share only.
+        uint32_t sbid = bid, sgrid = ngrid;
+        if (sh[S_NWG] != 0) {
+            sbid = bid - sh[S_WG0];
+            sgrid = sh[S_NWG];
+            if (sbid >= sgrid) {        // (unsigned: also true for workgroups below the share)
+                seg += seg_words;
+                continue;
+            }
+        }
+        const uint32_t m = (M + sgrid - 1) / sgrid;
+        const uint64_t t_lo64 = (uint64_t)m * sbid;
         const uint32_t t_lo = t_lo64 < M ? (uint32_t)t_lo64 : M;
         const uint32_t t_hi = (M - t_lo) < m ? M : t_lo + m;
 

@@ -247,7 +247,7 @@ def test_stream_hint_marks_tensors_read_once(ctx):
     text = code.disasm()
     assert "load" in text
     # find the load records: the scores are streamed, the broadcast mask is not
-    from_hdr = 8 + 3 * code.info().n_tensors + 24
+    from_hdr = 8 + 3 * code.info().n_tensors + 28
     flags = {}
     pc = from_hdr
     while pc < len(words):
@@ -269,3 +269,29 @@ def test_broadcast_dim_is_visited_fastest_and_its_operand_pinned(ctx):
     # too few repetitions to be worth a register: the mask is loaded per tile
     small = _encode(ctx, "c3_masked_softmax", [(1, 8, 256, 256), (256, 256)]).disasm()
     assert "again whenever" not in small
+
+
+def test_spatial_stack_gives_every_part_its_share_of_workgroups(ctx):
+    T = 700
+    lim = B.Context(-1)
+    lim.set_limits(16, 6)
+    descs = ["c5_rmsnorm", "c5_residual", "c5_silu_gate", "c5_softmax"]
+    shapes = [[(T, 4096), (4096,)], [(T, 4096)] * 2, [(T, 14336)] * 2, [(32, T, T // 8 + 1)]]
+    codes = [B.dvm_encode(lim, B.Program(W.get_program(d)), [B.make_shape(s) for s in sh]) for d, sh in zip(descs, shapes)]
+    st = B.dvm_stack(codes, spatial=True)
+    st.validate()
+    assert st.info().kernel_type == 2 and "vstack.s" in st.disasm()
+    words = np.frombuffer(st.raw, dtype=np.uint32)
+    at = 8 + 3 * st.info().n_tensors
+    shares, nxt = [], 0
+    for _ in range(4):
+        wg0, nwg = int(words[at + 24]), int(words[at + 25])
+        assert wg0 == nxt and nwg >= 1
+        nxt += nwg
+        shares.append(nwg)
+        at += int(words[at])
+    assert nxt == st.info().grid
+    assert shares[2] == max(shares)             # the widest program (silu gate over 14336 columns) moves the most bytes
+    # a stacked program cannot be a part of a spatial stack; a temporal stack of it is fine
+    with pytest.raises(B.DvmError):
+        B.dvm_stack([st, codes[0]], spatial=True)

@@ -38,7 +38,7 @@ def stack_ctx():
     return _stack_ctx
 
 
-def run_stacked(parts):
+def run_stacked(parts, spatial=False):
     """parts: list of (desc, inputs dict, optional output views dict).  Returns per-part output dicts."""
     ctx = stack_ctx()
     codes, tensors, outs_all = [], [], []
@@ -54,7 +54,7 @@ def run_stacked(parts):
         codes.append(code)
         tensors += in_list + outs
         outs_all.append({n: t for (n, _), t in zip(desc.outputs, outs)})
-    stacked = B.dvm_stack(codes)
+    stacked = B.dvm_stack(codes, spatial=spatial)
     stacked.validate()
     inf = stacked.info()
     assert inf.n_segments == len(parts)
@@ -63,8 +63,8 @@ def run_stacked(parts):
     return outs_all, stacked
 
 
-def check_parts(parts, what):
-    stacked_outs, code = run_stacked(parts)
+def check_parts(parts, what, spatial=False):
+    stacked_outs, code = run_stacked(parts, spatial)
     for (desc, ins, views), got in zip(parts, stacked_outs):
         got = {k: v.clone() for k, v in got.items()}
         alone, _ = H.run_vm(desc, ins, views, ctx=stack_ctx())
@@ -90,6 +90,13 @@ def test_c5_layer_in_one_launch(T):
     ]
     code = check_parts(parts, f"c5 T={T}")
     assert "vstack.t" in code.disasm()
+    # the same layer with its six programs side by side on shares of the workgroups (spatial stacking)
+    for _, _, views in parts:
+        if views:
+            for v in views.values():
+                v.zero_()
+    code = check_parts(parts, f"c5 spatial T={T}", spatial=True)
+    assert "vstack.s" in code.disasm()
 
 
 def test_stack_of_different_shapes_and_variants():
@@ -101,6 +108,7 @@ def test_stack_of_different_shapes_and_variants():
     z = gen.randn((4, 33, 100), 961, DEV, "f32", std=3.0)
     parts.append((W.get_program("softmax_f32"), {"z": z}, None))
     check_parts(parts, "mixed stack")
+    check_parts(parts, "mixed stack, spatial", spatial=True)
 
 
 def test_stack_limits():
