@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--stack", type=int, default=0,
                     help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
                          "launch's tensor table; 1 = every instance its own launch; config 5 always stacks a layer)")
+    ap.add_argument("--stacking", default="", choices=["", "temporal", "spatial"],
+                    help="how the parts of a launch share it: one after the other on all workgroups (temporal) or side by "
+                         "side on shares of the workgroups (spatial); default temporal (it measured faster on every workload here)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-unstacked", action="store_true",
                     help="leave out the second pass that launches every program on its own (profiler runs use this so "
@@ -209,6 +212,9 @@ def main() -> int:
     stream_h = C.c_void_p(stream.cuda_stream)
     perf = time.perf_counter
 
+    stacking = args.stacking or "temporal"
+    stack_fn = lib.dvm_stack_spatial if stacking == "spatial" else lib.dvm_stack
+
     def one_step(groups, events=None, enc_us=None):
         """Encode every part, stack the parts of each launch (temporal stacking; a single part is launched
         as it is), run."""
@@ -227,7 +233,7 @@ def main() -> int:
             if len(idx) == 1:
                 code, code_len = part_bufs[0], part_lens[0]
             else:
-                st = lib.dvm_stack(part_ptrs, part_lens, len(idx), stacked, enc_cap, C.byref(ln))
+                st = stack_fn(part_ptrs, part_lens, len(idx), stacked, enc_cap, C.byref(ln))
                 if st != 0:
                     raise B.DvmError(st, "dvm_stack")
                 code, code_len = stacked, ln.value
@@ -299,6 +305,7 @@ def main() -> int:
     enc = np.array(enc_us)
 
     wl["instances_per_launch"] = group
+    wl["stacking"] = stacking if group > 1 else "none"
     result = {
         "metric": "achieved HBM GB/s of VM-run fused ops (algorithmic bytes / wall time, encode included)",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -312,7 +319,7 @@ def main() -> int:
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                      "bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(avg_launch_ms, 5),
                      "launches": len(kern_ms), "instances_per_launch": group,
-                     "traffic": measured_traffic(args.workload) if not args.instances and not args.stack else None},
+                     "traffic": measured_traffic(args.workload) if not args.instances and not args.stack and not args.stacking else None},
     }
 
     # ---- the CPU oracle on a bounded sample of the same workload (a baseline, not the target) -----

@@ -155,8 +155,8 @@ int  dvm_stack(const void *const *codes, const size_t *lens, int n,
                void *out, size_t cap, size_t *len);
 
 /* Spatial stacking (Section 5.1): like dvm_stack, but the parts run side by side in the one launch,
- * each on its own share of the workgroups (in proportion to the bytes the part moves), instead of one
- * after the other on all of them.  It pays when the parts are small: their ramp-up and tail overlap.
+ * each on its own share of the workgroups (in proportion to an estimate of the part's run time: tiles
+ * times interpreted records, plus bytes moved), instead of one after the other on all of them.
  * Every part must be a single meta-kernel as dvm_encode produces it; more non-empty parts than the
  * launch has workgroups gives DVM_E_UNSUPPORTED (use dvm_stack then).  Same arguments, ownership and
  * error behaviour as dvm_stack. */

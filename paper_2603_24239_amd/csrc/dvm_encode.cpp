@@ -1715,7 +1715,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
     }
     if (spatial) {
         // Spatial stacking (Section 5.1): the segments run side by side, each on a share of the workgroups
-        // in proportion to the bytes it moves, at least one and at most one per tile.
+        // in proportion to its estimated run time, at least one and at most one per tile.
         uint32_t *seg[64];
         double cost[64];
         uint32_t share[64];
@@ -1729,6 +1729,11 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
                 const uint32_t *te = w + PH_WORDS_N + (sh[S_TBASE] + t) * TT_WORDS;
                 c += (double)((uint64_t)te[TT_BYTES_LO] | ((uint64_t)te[TT_BYTES_HI] << 32));
             }
+            // time of a part ~ tiles * (interpreted records + bytes per tile / 2 KiB): short tiles are bound by
+            // the per-record work of the interpreter, long ones by memory
+            uint32_t n_rec = 0;
+            for (uint32_t pc = SH_WORDS + sh[S_PROLOG]; pc < sh[S_WORDS]; pc += (sh[pc] >> 8) & 0xFF) ++n_rec;
+            c = (double)sh[S_NTILES] * n_rec + c / 2048.0;
             if (sh[S_NTILES] == 0) c = 0;
             cost[ns] = c;
             total += c;
