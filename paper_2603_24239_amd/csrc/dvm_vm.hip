@@ -630,20 +630,29 @@ DI uint32_t sdiv_u(uint32_t n, uint32_t m, uint32_t sh) {   // the same on wave-
     return (t + ((n - t) >> (sh & 0xFF))) >> (sh >> 8);
 }
 
-// Where tile number `tile` of a segment sits: its first column and width (wave-uniform), and the
-// lane's row decomposed over the outer iteration dims.  `rp` is the row of the tile this lane holds.
-DI void tile_place(Geo &gt, const uint32_t *sh, uint32_t tile, uint32_t rp, uint32_t tid, uint32_t RP, uint32_t seg_threads) {
-    const uint32_t nct = sh[S_NCT], TC = sh[S_TC];
+// Where a tile of a segment sits.  Columns (wave-uniform): first column and width of column tile
+// `tile_c`, and which chunk the row ends in.  Rows: the lane's row decomposed over the outer
+// iteration dims; `rp` is the row of the tile this lane holds.
+DI void tile_cols(Geo &gt, const uint32_t *sh, uint32_t tile_c, uint32_t G, uint32_t V) {
+    const uint32_t TC = sh[S_TC];
     const uint64_t D0 = (uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32);
-    const uint32_t nrows = sh[S_NROWS];
-    uint32_t tile_r = tile, tile_c = 0;
-    if (nct > 1) {
-        tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
-        tile_c = tile - tile_r * nct;
-    }
     gt.colbase = (uint64_t)tile_c * TC;
     const uint64_t rem = D0 - gt.colbase;
     gt.ncols = rem < TC ? (uint32_t)rem : TC;
+    const uint32_t full_chunks = V == 8 ? gt.ncols >> 3 : gt.ncols >> 2;      // V is 4 or 8
+    gt.part_n = gt.ncols - full_chunks * V;
+    gt.part_slot = ~0u;
+    gt.part_lane = 0;
+    gt.part_col = full_chunks * V;
+    if (gt.part_n != 0) {
+        gt.part_slot = __builtin_amdgcn_readfirstlane(full_chunks / G);
+        gt.part_lane = full_chunks - gt.part_slot * G;
+    }
+    // rows never mix in a reduction, so only invalid columns inside live chunks need a mask
+    gt.ragged = gt.ncols != gt.nact * G;
+}
+DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uint32_t tid, uint32_t RP, uint32_t seg_threads) {
+    const uint32_t nrows = sh[S_NROWS];
     const uint32_t row = tile_r * RP + rp;
     gt.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
     const uint32_t rowc = gt.rowok ? row : 0;
@@ -770,20 +779,16 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         const uint32_t t_lo = t_lo64 < M ? (uint32_t)t_lo64 : M;
         const uint32_t t_hi = (M - t_lo) < m ? M : t_lo + m;
 
+        const uint32_t nct = sh[S_NCT];
+        if (nct <= 1) tile_cols(gt, sh, 0, G, V);
         for (uint32_t tile = t_lo; tile < t_hi; ++tile) {
             {   // tile prologue: where this tile sits, which of its lanes and chunks are valid
-                tile_place(gt, sh, tile, rp, tid, RP, seg_threads);
-                const uint32_t full_chunks = V == 8 ? gt.ncols >> 3 : gt.ncols >> 2;      // V is 4 or 8
-                gt.part_n = gt.ncols - full_chunks * V;
-                gt.part_slot = ~0u;
-                gt.part_lane = 0;
-                gt.part_col = full_chunks * V;
-                if (gt.part_n != 0) {
-                    gt.part_slot = __builtin_amdgcn_readfirstlane(full_chunks / G);
-                    gt.part_lane = full_chunks - gt.part_slot * G;
+                uint32_t tile_r = tile;
+                if (nct > 1) {          // (a single column tile was placed once, before the loop)
+                    tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
+                    tile_cols(gt, sh, tile - tile_r * nct, G, V);
                 }
-                // rows never mix in a reduction, so only invalid columns inside live chunks need a mask
-                gt.ragged = gt.ncols != gt.nact * G;
+                tile_rows(gt, sh, tile_r, rp, tid, RP, seg_threads);
             }
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
