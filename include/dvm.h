@@ -163,6 +163,37 @@ int  dvm_stack(const void *const *codes, const size_t *lens, int n,
 int  dvm_stack_spatial(const void *const *codes, const size_t *lens, int n,
                        void *out, size_t cap, size_t *len);
 
+/* ---- streaming fuser for dynamic graphs (Section 5.2, dynamic graph fuser) -----------------------
+ * Operators arrive one at a time, as an eager framework issues them.  They are buffered lazily and
+ * fused on arrival while their iteration spaces merge; the buffer runs as ONE launch when an
+ * operator arrives that does not fuse, when the buffer is full, or on dvm_fuser_flush (a host read,
+ * a stream synchronisation).  A result the caller released before the buffer ran is a pure
+ * intermediate and is never written to memory.
+ *
+ * All calls are host calls.  The fuser owns no device memory: every tensor and every result buffer
+ * is the caller's (device pointers), and must stay valid until the buffer that uses it has run.
+ * A fuser is not thread-safe; use one per stream.  With a context created for device -1 a flush
+ * encodes the buffered operators but launches nothing (host-side measurement and tests). */
+typedef struct dvm_fuser dvm_fuser;
+
+int  dvm_fuser_create(dvm_ctx *ctx, void *hip_stream, dvm_fuser **out);
+void dvm_fuser_destroy(dvm_fuser *f);
+/* Register a tensor that already holds data; *value receives its id. */
+int  dvm_fuser_tensor(dvm_fuser *f, void *device_ptr, int dtype, const dvm_shape *shape, int *value);
+/* Issue an operator on earlier values (same opcodes and immediates as dvm_prog_op).  `out_ptr` is the
+ * buffer the framework allocated for the result (contiguous, inferred shape, storage `out_dtype`);
+ * it is written when the buffer runs, unless the result was released before.  *value: the result's id. */
+int  dvm_fuser_op(dvm_fuser *f, int opcode, const int *args, int n_args, const double *imm, int n_imm,
+                  int out_dtype, void *out_ptr, int *value);
+/* The caller no longer references `value`. */
+int  dvm_fuser_release(dvm_fuser *f, int value);
+/* Run everything that is buffered. */
+int  dvm_fuser_flush(dvm_fuser *f);
+/* Counters since creation: operators issued, launches, flushes, results never written. */
+int  dvm_fuser_stats(const dvm_fuser *f, int64_t *n_ops, int64_t *n_launches, int64_t *n_flushes, int64_t *n_elided);
+/* Copy out the bytecode of the most recent launch (DVM_E_BUFSZ with *len set if `cap` is too small). */
+int  dvm_fuser_last_code(const dvm_fuser *f, void *bytecode, size_t cap, size_t *len);
+
 /* Structural check of a bytecode blob: header fields, segment and instruction lengths, register
  * and tensor indices, launch geometry.  dvm_run calls it on every launch. */
 int  dvm_validate(const void *bytecode, size_t len);

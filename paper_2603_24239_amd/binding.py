@@ -93,6 +93,14 @@ def load() -> C.CDLL:
         "dvm_strerror": (C.c_char_p, [i]),
         "dvm_last_error_detail": (C.c_char_p, []),
         "dvm_last_hip_error": (i, []),
+        "dvm_fuser_create": (i, [vp, vp, P(vp)]),
+        "dvm_fuser_destroy": (None, [vp]),
+        "dvm_fuser_tensor": (i, [vp, vp, i, P(dvm_shape), P(i)]),
+        "dvm_fuser_op": (i, [vp, i, P(i), i, P(C.c_double), i, i, vp, P(i)]),
+        "dvm_fuser_release": (i, [vp, i]),
+        "dvm_fuser_flush": (i, [vp]),
+        "dvm_fuser_stats": (i, [vp, P(C.c_int64), P(C.c_int64), P(C.c_int64), P(C.c_int64)]),
+        "dvm_fuser_last_code": (i, [vp, vp, sz, P(sz)]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -106,7 +114,8 @@ EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ct
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
             "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_validate", "dvm_disasm",
             "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_strerror", "dvm_last_error_detail",
-            "dvm_last_hip_error"]
+            "dvm_last_hip_error", "dvm_fuser_create", "dvm_fuser_destroy", "dvm_fuser_tensor", "dvm_fuser_op",
+            "dvm_fuser_release", "dvm_fuser_flush", "dvm_fuser_stats", "dvm_fuser_last_code"]
 
 
 def _check(status: int, where: str) -> None:
@@ -163,6 +172,20 @@ class Context:
             self._h = None
 
 
+def _opcode(name: str, attrs) -> int:
+    return OPCODES["cmp_" + str(attrs["cmp"])] if name == "cmp" else OPCODES[name]
+
+
+def _immediates(name: str, attrs) -> List[float]:
+    if name in ("adds", "muls"):
+        return [float(attrs["imm"])]
+    if name in ("rmsnorm", "layernorm"):
+        return [float(attrs["eps"])]
+    if name == "cast":
+        return [float(DTYPES[str(attrs["to"])])]
+    return []
+
+
 class Program:
     """dvm_prog built from a neutral program description (workloads.programs.Program)."""
 
@@ -177,19 +200,10 @@ class Program:
             _check(lib.dvm_prog_input(self._h, DTYPES[dt], C.byref(vid)), "dvm_prog_input")
             ids[name] = vid.value
         for op in desc.ops:
-            name = op.name
-            imm: List[float] = []
-            if name == "cmp":
-                name = "cmp_" + str(op.attrs["cmp"])
-            elif name in ("adds", "muls"):
-                imm = [float(op.attrs["imm"])]
-            elif name in ("rmsnorm", "layernorm"):
-                imm = [float(op.attrs["eps"])]
-            elif name == "cast":
-                imm = [float(DTYPES[str(op.attrs["to"])])]
+            imm = _immediates(op.name, op.attrs)
             args = (C.c_int * max(len(op.args), 1))(*[ids[a] for a in op.args])
             immarr = (C.c_double * max(len(imm), 1))(*imm)
-            _check(lib.dvm_prog_op(self._h, OPCODES[name], args, len(op.args), immarr, len(imm), C.byref(vid)),
+            _check(lib.dvm_prog_op(self._h, _opcode(op.name, op.attrs), args, len(op.args), immarr, len(imm), C.byref(vid)),
                    f"dvm_prog_op({op.name})")
             ids[op.out] = vid.value
         for name, dt in desc.outputs:
@@ -197,9 +211,6 @@ class Program:
         _check(lib.dvm_prog_finish(self._h), "dvm_prog_finish")
         self.n_in = lib.dvm_prog_num_inputs(self._h)
         self.n_out = lib.dvm_prog_num_outputs(self._h)
-
-    def set_limits(self, max_elems_per_lane: int = 0, max_tile_regs: int = 0) -> None:
-        _check(load().dvm_ctx_set_limits(self._h, max_elems_per_lane, max_tile_regs), "dvm_ctx_set_limits")
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:
@@ -282,6 +293,53 @@ def dvm_run(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: in
     n = len(tensor_ptrs)
     arr = (C.c_void_p * max(n, 1))(*tensor_ptrs)
     _check(load().dvm_run(ctx._h, code.ptr, len(code), arr, n, C.c_void_p(stream)), "dvm_run")
+
+
+class Fuser:
+    """dvm_fuser: lazy operator buffer that fuses on arrival (argument marshalling only)."""
+
+    _DT = {"f32": 0, "bf16": 1}
+
+    def __init__(self, ctx: Context, stream: int = 0):
+        self._h = C.c_void_p()
+        self._ctx = ctx
+        _check(load().dvm_fuser_create(ctx._h, C.c_void_p(stream), C.byref(self._h)), "dvm_fuser_create")
+
+    def tensor(self, ptr: int, dtype: str, shape: dvm_shape) -> int:
+        v = C.c_int()
+        _check(load().dvm_fuser_tensor(self._h, C.c_void_p(ptr), self._DT[dtype], C.byref(shape), C.byref(v)), "dvm_fuser_tensor")
+        return v.value
+
+    def op(self, name: str, args: Sequence[int], out_dtype: str, out_ptr: int, **attrs) -> int:
+        imm = _immediates(name, attrs)
+        arr = (C.c_int * len(args))(*args)
+        immarr = (C.c_double * max(len(imm), 1))(*imm)
+        v = C.c_int()
+        _check(load().dvm_fuser_op(self._h, _opcode(name, attrs), arr, len(args), immarr, len(imm), self._DT[out_dtype],
+                                   C.c_void_p(out_ptr), C.byref(v)), "dvm_fuser_op")
+        return v.value
+
+    def release(self, value: int) -> None:
+        _check(load().dvm_fuser_release(self._h, value), "dvm_fuser_release")
+
+    def flush(self) -> None:
+        _check(load().dvm_fuser_flush(self._h), "dvm_fuser_flush")
+
+    def stats(self) -> Dict[str, int]:
+        a, b, c, d = C.c_int64(), C.c_int64(), C.c_int64(), C.c_int64()
+        _check(load().dvm_fuser_stats(self._h, C.byref(a), C.byref(b), C.byref(c), C.byref(d)), "dvm_fuser_stats")
+        return {"ops": a.value, "launches": b.value, "flushes": c.value, "elided": d.value}
+
+    def last_code(self) -> "Bytecode":
+        buf = C.create_string_buffer(_ENC_CAP)
+        ln = C.c_size_t()
+        _check(load().dvm_fuser_last_code(self._h, buf, _ENC_CAP, C.byref(ln)), "dvm_fuser_last_code")
+        return Bytecode(buf.raw[: ln.value], [])
+
+    def __del__(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.dvm_fuser_destroy(self._h)
+            self._h = None
 
 
 def dvm_plan(total: int, n_cores: int, t_max: int, align: int, overhead: int = 2) -> Tuple[int, int, int]:

@@ -27,7 +27,7 @@ DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-pa
 def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
-    for src, extra in (("dvm_encode.cpp", []), ("dvm_vm.hip", DEVICE)):
+    for src, extra in (("dvm_encode.cpp", []), ("dvm_fuser.cpp", []), ("dvm_vm.hip", DEVICE)):
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
         cmd = [hipcc, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:

@@ -425,7 +425,6 @@ template <int K> DI void request_dispatch(Raw<K> &raw, uint32_t dt, uint32_t V, 
 }
 
 template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw, gcptr rowp, const Geo &g) {
-    constexpr int ES = DT == 0 ? 4 : 2;
     if constexpr (K < V) tile_zero<K>(t);
     if constexpr (K >= V) {
         constexpr int NJ = K / V;

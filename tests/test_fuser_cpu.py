@@ -1,0 +1,82 @@
+"""Streaming fuser, host side (no GPU): on an encode-only context a flush encodes the buffered
+operators without launching, which shows what was fused, what was elided and when the buffer ran."""
+import re
+
+import pytest
+
+from paper_2603_24239_amd import binding as B
+
+
+def _ctx():
+    return B.Context(-1)
+
+
+def test_chain_fuses_into_one_launch_and_released_values_never_reach_memory():
+    f = B.Fuser(_ctx())
+    x = f.tensor(0x1000, "f32", B.make_shape((64, 1000)))
+    y = f.tensor(0x2000, "f32", B.make_shape((64, 1000)))
+    t = f.op("muls", [x], "f32", 0x3000, imm=2.0)
+    u = f.op("add", [t, y], "f32", 0x4000)
+    f.release(t)                         # the framework dropped the temporary before anything ran
+    assert f.stats() == {"ops": 2, "launches": 0, "flushes": 0, "elided": 0}
+    f.flush()
+    assert f.stats() == {"ops": 2, "launches": 1, "flushes": 1, "elided": 1}
+    txt = f.last_code().disasm()
+    assert len(re.findall(r"\bstore\b", txt)) == 1 and "mul" in txt and "add" in txt
+    f.flush()                            # nothing buffered: no launch
+    assert f.stats()["launches"] == 1
+    # the result is now a plain tensor and feeds the next buffer
+    v = f.op("tanh", [u], "f32", 0x5000)
+    f.flush()
+    assert f.stats()["launches"] == 2 and v != u
+
+
+def test_unfusable_operator_runs_the_buffer_first():
+    f = B.Fuser(_ctx())
+    a = f.tensor(0x1000, "f32", B.make_shape((8, 128)))
+    b = f.tensor(0x2000, "f32", B.make_shape((5, 77)))
+    f.op("exp", [a], "f32", 0x3000)
+    assert f.stats()["launches"] == 0
+    f.op("neg", [b], "f32", 0x4000)      # another iteration space: the first operator runs now
+    assert f.stats()["launches"] == 1 and f.stats()["flushes"] == 1
+    f.flush()
+    assert f.stats()["launches"] == 2
+
+
+def test_reduction_and_its_consumers_share_a_launch():
+    f = B.Fuser(_ctx())
+    x = f.tensor(0x1000, "bf16", B.make_shape((300, 4096)))
+    w = f.tensor(0x2000, "bf16", B.make_shape((4096,)))
+    ms = f.op("meansq", [x], "f32", 0x3000)
+    v = f.op("adds", [ms], "f32", 0x3100, imm=1e-6)
+    r = f.op("rsqrt", [v], "f32", 0x3200)
+    n = f.op("mul", [x, r], "bf16", 0x4000)
+    y = f.op("mul", [n, w], "bf16", 0x5000)
+    for t in (ms, v, r, n):
+        f.release(t)
+    f.flush()
+    st = f.stats()
+    assert st["launches"] == 1 and st["elided"] == 4
+    txt = f.last_code().disasm()
+    assert "red.sumsq" in txt and len(re.findall(r"\bstores?\b", txt)) == 1
+    assert y >= 0
+
+
+def test_errors_and_limits():
+    f = B.Fuser(_ctx())
+    a = f.tensor(0x1000, "f32", B.make_shape((8, 128)))
+    b = f.tensor(0x2000, "f32", B.make_shape((8, 100)))
+    with pytest.raises(B.DvmError):
+        f.op("add", [a, b], "f32", 0x3000)           # shapes do not broadcast
+    with pytest.raises(B.DvmError):
+        f.op("neg", [12345], "f32", 0x3000)          # unknown value
+    # a long chain: the buffer runs by itself when it is full
+    cur = a
+    for k in range(100):
+        nxt = f.op("adds", [cur], "f32", 0x10000 + 0x1000 * k, imm=1.0)
+        if cur != a:
+            f.release(cur)
+        cur = nxt
+    f.flush()
+    st = f.stats()
+    assert st["ops"] == 100 and 2 <= st["launches"] <= 5 and st["elided"] >= 95

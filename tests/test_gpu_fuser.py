@@ -1,0 +1,101 @@
+"""Streaming fuser on the GPU: operators issued one by one (the host decides the graph as it goes),
+results compared with the oracle evaluating the same operator sequence."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_24239_amd import binding as B
+from workloads import gen
+from workloads import programs as W
+from workloads.programs import _p
+
+from . import harness as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def _fuser():
+    return B.Fuser(H.gpu_ctx(), torch.cuda.current_stream().cuda_stream)
+
+
+def test_if_else_add_stream_with_host_side_branches():
+    """(a > b ? 2x : 4x) + y with the branch taken on the host (the paper's dynamic control-flow
+    workload, Table 2): which multiply is issued differs from instance to instance."""
+    f = _fuser()
+    shapes = [sh for sh in gen.if_else_add_shapes(40) if sh[0] * sh[1] * sh[2] <= 2e7][:12]     # the oracle's share of the time
+    for k, (b, s, ff, flag) in enumerate(shapes):
+        say(f"if-else-add {k}: [{b},{s},{ff}] branch={flag}")
+        x = gen.randn((b, s, ff), 800 + k, DEV)
+        y = gen.randn((b, s, ff), 900 + k, DEV)
+        tmp = torch.empty_like(x)
+        out = torch.full_like(x, float("nan"))
+        vx = f.tensor(x.data_ptr(), "f32", B.shape_of_tensor(x))
+        vy = f.tensor(y.data_ptr(), "f32", B.shape_of_tensor(y))
+        t = f.op("muls", [vx], "f32", tmp.data_ptr(), imm=2.0 if flag else 4.0)
+        o = f.op("add", [t, vy], "f32", out.data_ptr())
+        f.release(t)
+        f.flush()
+        torch.cuda.synchronize()
+        desc = W.get_program("if_else_add_true" if flag else "if_else_add_false")
+        rounded, exact = H.run_oracle(desc, {"x": x, "y": y})
+        name = desc.outputs[0][0]
+        H.compare(out, rounded[name], exact[name], "f32", False, f"if-else-add {k}")
+        for v in (vx, vy, o):
+            f.release(v)
+    st = f.stats()
+    assert st["launches"] == len(shapes) and st["elided"] == len(shapes)
+
+
+def test_rmsnorm_issued_op_by_op_equals_the_fused_program():
+    f = _fuser()
+    d = gen.c2_inputs(3, 333, 77, DEV)
+    x, w = d["x"], d["w"]
+    rows = torch.empty((3, 333, 1), dtype=torch.float32, device=DEV)
+    rows2, rows3 = torch.empty_like(rows), torch.empty_like(rows)
+    n = torch.empty_like(x)
+    y = torch.full_like(x, float("nan"))
+    vx = f.tensor(x.data_ptr(), "bf16", B.shape_of_tensor(x))
+    vw = f.tensor(w.data_ptr(), "bf16", B.shape_of_tensor(w))
+    ms = f.op("meansq", [vx], "f32", rows.data_ptr())
+    v = f.op("adds", [ms], "f32", rows2.data_ptr(), imm=1e-6)
+    r = f.op("rsqrt", [v], "f32", rows3.data_ptr())
+    nn_ = f.op("mul", [vx, r], "bf16", n.data_ptr())
+    f.op("mul", [nn_, vw], "bf16", y.data_ptr())
+    for t in (ms, v, nn_):
+        f.release(t)                    # r stays referenced: it must be written as a second output
+    f.flush()
+    torch.cuda.synchronize()
+    assert f.stats()["launches"] == 1
+    desc = W.get_program("c2_rmsnorm_basic")
+    rounded, exact = H.run_oracle(desc, {"x": x, "w": w})
+    H.compare(y, rounded["y"], exact["y"], "bf16", True, "fuser rmsnorm")
+    # the kept row value against the oracle's intermediate
+    keep = _p("keep_r", [("x", "bf16")], [("ms", "meansq", ["x"], {}), ("v", "adds", ["ms"], {"imm": 1e-6}),
+                                          ("r", "rsqrt", ["v"], {})], [("r", "f32")])
+    rr, re_ = H.run_oracle(keep, {"x": x})
+    H.compare(rows3, rr["r"], re_["r"], "f32", True, "fuser kept row value")
+
+
+def test_buffers_of_different_shapes_run_in_order():
+    f = _fuser()
+    a = gen.randn((40, 257), 61, DEV)
+    b = gen.randn((7, 1000), 62, DEV)
+    ea, eb, sa = torch.empty_like(a), torch.empty_like(b), torch.empty_like(a)
+    va = f.tensor(a.data_ptr(), "f32", B.shape_of_tensor(a))
+    vb = f.tensor(b.data_ptr(), "f32", B.shape_of_tensor(b))
+    t = f.op("tanh", [va], "f32", ea.data_ptr())
+    f.op("sigmoid", [vb], "f32", eb.data_ptr())          # does not fuse with the first: it runs now
+    f.op("mul", [t, va], "f32", sa.data_ptr())           # uses the first result as a plain tensor
+    f.flush()
+    torch.cuda.synchronize()
+    assert f.stats()["launches"] == 3
+    assert torch.allclose(ea, torch.tanh(a), atol=1e-6)
+    assert torch.allclose(eb, torch.sigmoid(b), atol=1e-6)
+    assert torch.allclose(sa, torch.tanh(a) * a, atol=1e-6)
