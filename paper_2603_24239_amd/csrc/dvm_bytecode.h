@@ -149,7 +149,7 @@ inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
 struct Variant { int K, NR, max_threads, waves_per_simd; };
 constexpr Variant VARIANTS[] = {
     { 4, 2, 1024, 8}, { 4, 6, 1024, 7},
-    { 8, 2, 1024, 5}, { 8, 6,  512, 4},
+    { 8, 2, 1024, 6}, { 8, 6,  512, 4},
     {16, 2, 1024, 4}, {16, 4,  512, 3}, {16, 6,  512, 2},
     {32, 2,  256, 2},
 };

@@ -1078,7 +1078,9 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                     if (E.reg_of[b] >= 0) {
                         E.emit(I_BIN, (uint8_t)E.reg_of[b], (uint8_t)op);
                     } else if (E.is_input(b)) {
-                        if (E.uses[b] == 1 || E.reload_inputs) {
+                        // (a load combines into the accumulator with add, sub, reversed sub and mul only)
+                        const bool combines = op == B_ADD || op == B_SUB || op == B_RSUB || op == B_MUL;
+                        if ((E.uses[b] == 1 || E.reload_inputs) && combines) {
                             E.emit(I_LOAD, (uint8_t)SRC_ACC, (uint8_t)op, E.tensor_of_input(b));
                         } else {
                             const int r = E.to_reg(b);
@@ -1530,7 +1532,10 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     want = (op == I_LOAD || op == I_STORE) ? LEN_LOAD : LEN_VLOAD;
                     if (l != want) return bad("memory instruction length");
                     if (a != SRC_ACC && !reg_ok(a, vr)) return bad("tile register index");
-                    if ((op == I_LOAD || op == I_VLOAD) ? (bb >= B_COUNT || (a != SRC_ACC && bb != B_NONE)) : bb != 0) return bad("combine op");
+                    if ((op == I_LOAD || op == I_VLOAD)
+                            ? (!(bb == B_NONE || bb == B_ADD || bb == B_SUB || bb == B_RSUB || bb == B_MUL) || (a != SRC_ACC && bb != B_NONE))
+                            : bb != 0)
+                        return bad("combine op");
                     const uint32_t w1 = w[pc + 1];
                     if ((w1 & 0xFF) >= nt) return bad("tensor index");
                     const uint32_t info = w[PH_WORDS_N + (tbase + (w1 & 0xFF)) * TT_WORDS + TT_INFO];

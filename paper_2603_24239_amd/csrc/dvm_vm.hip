@@ -424,26 +424,43 @@ template <int K> DI void request_dispatch(Raw<K> &raw, uint32_t dt, uint32_t V, 
     }
 }
 
-template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw, gcptr rowp, const Geo &g) {
-    if constexpr (K < V) tile_zero<K>(t);
+// B == B_NONE: t = loaded tile.  Otherwise t = B(t, loaded tile), element by element as the pieces
+// are widened (no second tile register is needed); elements outside the row keep their old value.
+template <int K, int DT, int V, uint32_t B> DI void widen_tile(Tile<K> &t, const Raw<K> &raw, const Geo &g) {
+    if constexpr (K < V && B == B_NONE) tile_zero<K>(t);
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        if (g.ncols < (uint32_t)V) tile_zero<K>(t);     // narrower than one chunk: only the ragged part below
+        if constexpr (B == B_NONE) {
+            if (g.ncols < (uint32_t)V) tile_zero<K>(t);     // narrower than one chunk: only the ragged part below
+        }
         if (g.ncols >= (uint32_t)V) {
-            if constexpr (DT == 0) {
-                sfor<NJ *(V / 4)>([&]<int Q>() LI {
-                    const f32x4 r = raw.q[Q];
-                    t.v[4 * Q + 0] = r.x; t.v[4 * Q + 1] = r.y; t.v[4 * Q + 2] = r.z; t.v[4 * Q + 3] = r.w;
-                });
-            } else {
-                sfor<NJ>([&]<int J>() LI {
+            const bool masked = B != B_NONE && g.ragged != 0;       // wave-uniform
+            auto chunk = [&]<int J>(bool whole) LI {
+                float x[V];
+                if constexpr (DT == 0) {
+                    sfor<V / 4>([&]<int H>() LI {
+                        const f32x4 r = raw.q[J * (V / 4) + H];
+                        x[4 * H + 0] = r.x; x[4 * H + 1] = r.y; x[4 * H + 2] = r.z; x[4 * H + 3] = r.w;
+                    });
+                } else {
                     const u32x4 r = __builtin_bit_cast(u32x4, raw.q[J]);
                     const uint32_t w0 = r.x, w1 = r.y, w2 = r.z, w3 = r.w;
-                    t.v[J * V + 0] = bf16_lo(w0); t.v[J * V + 1] = bf16_hi(w0);
-                    t.v[J * V + 2] = bf16_lo(w1); t.v[J * V + 3] = bf16_hi(w1);
-                    t.v[J * V + 4] = bf16_lo(w2); t.v[J * V + 5] = bf16_hi(w2);
-                    t.v[J * V + 6] = bf16_lo(w3); t.v[J * V + 7] = bf16_hi(w3);
+                    x[0] = bf16_lo(w0); x[1] = bf16_hi(w0); x[2] = bf16_lo(w1); x[3] = bf16_hi(w1);
+                    x[4] = bf16_lo(w2); x[5] = bf16_hi(w2); x[6] = bf16_lo(w3); x[7] = bf16_hi(w3);
+                }
+                sfor<V>([&]<int E>() LI {
+                    if constexpr (B == B_NONE) {
+                        t.v[J * V + E] = x[E];
+                    } else {
+                        const float y = bin_op<B>(t.v[J * V + E], x[E]);
+                        t.v[J * V + E] = whole ? y : t.v[J * V + E];
+                    }
                 });
+            };
+            if (!masked) {
+                sfor<NJ>([&]<int J>() LI { chunk.template operator()<J>(true); });
+            } else {
+                sfor<NJ>([&]<int J>() LI { chunk.template operator()<J>(g.lanecol + (uint32_t)J * g.GV + V <= g.ncols); });
             }
         }
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
@@ -463,6 +480,7 @@ template <int K, int DT, int V> DI void widen_tile(Tile<K> &t, const Raw<K> &raw
                         // which forces both arrays into memory)
                         float x = pv[E];
                         asm volatile("" : "+v"(x));
+                        if constexpr (B != B_NONE) x = bin_op<B>(t.v[J * V + E], x);
                         t.v[J * V + E] = ok ? x : t.v[J * V + E];
                     });
                 }
@@ -513,12 +531,12 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
     }
 }
 
-template <int K> DI void widen_dispatch(Tile<K> &t, const Raw<K> &raw, uint32_t dt, uint32_t V, gcptr rowp, const Geo &g) {
+template <int K, uint32_t B> DI void widen_dispatch(Tile<K> &t, const Raw<K> &raw, uint32_t dt, uint32_t V, const Geo &g) {
     if (dt == 0) {
-        if (V == 4) widen_tile<K, 0, 4>(t, raw, rowp, g);
-        else widen_tile<K, 0, 8>(t, raw, rowp, g);
+        if (V == 4) widen_tile<K, 0, 4, B>(t, raw, g);
+        else widen_tile<K, 0, 8, B>(t, raw, g);
     } else {
-        widen_tile<K, 1, 8>(t, raw, rowp, g);
+        widen_tile<K, 1, 8, B>(t, raw, g);
     }
 }
 template <int K> DI void store_dispatch(const Tile<K> &t, uint32_t dt, uint32_t V, gptr rowp, const Geo &g) {
@@ -685,6 +703,16 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
         case 5: if constexpr (NR > 5) { Tile<K> &RR = r5; STMT; } break;   \
         default: break;                                                  \
     }
+#define DVM_WITH_R2(IDX, RR, STMT)                                       \
+    switch (IDX) {                                                       \
+        case 0: { Tile<K> &RR = r0; STMT; } break;                         \
+        case 1: if constexpr (NR > 1) { Tile<K> &RR = r1; STMT; } break;   \
+        case 2: if constexpr (NR > 2) { Tile<K> &RR = r2; STMT; } break;   \
+        case 3: if constexpr (NR > 3) { Tile<K> &RR = r3; STMT; } break;   \
+        case 4: if constexpr (NR > 4) { Tile<K> &RR = r4; STMT; } break;   \
+        case 5: if constexpr (NR > 5) { Tile<K> &RR = r5; STMT; } break;   \
+        default: break;                                                  \
+    }
 #define DVM_GET_S(I) pick_s(s0, s1, s2, s3, (I))
 #define DVM_SET_S(I, VAL)                   \
     do {                                    \
@@ -835,17 +863,18 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         gcptr rowp = base + off * es;
                         Raw<K> raw;
                         request_dispatch<K>(raw, dt, V, ((w1 >> 16) & MF_STREAM) != 0, rowp, g);
-                        // widen straight into the destination register
+                        // widen straight into the destination register; a load into the accumulator may
+                        // combine with what it holds (acc = acc op tile) while it widens
                         if (a == SRC_ACC) {
-                            if (b == B_NONE) {
-                                widen_dispatch<K>(acc, raw, dt, V, rowp, g);
-                            } else {
-                                Tile<K> t;
-                                widen_dispatch<K>(t, raw, dt, V, rowp, g);
-                                tile_bin_dispatch<K>(acc, t, b);
+                            switch (b) {
+                                case B_ADD: widen_dispatch<K, B_ADD>(acc, raw, dt, V, g); break;
+                                case B_SUB: widen_dispatch<K, B_SUB>(acc, raw, dt, V, g); break;
+                                case B_RSUB: widen_dispatch<K, B_RSUB>(acc, raw, dt, V, g); break;
+                                case B_MUL: widen_dispatch<K, B_MUL>(acc, raw, dt, V, g); break;
+                                default: widen_dispatch<K, B_NONE>(acc, raw, dt, V, g); break;
                             }
                         } else {
-                            DVM_WITH_R(a, rr, widen_dispatch<K>(rr, raw, dt, V, rowp, g))
+                            DVM_WITH_R(a, rr, (widen_dispatch<K, B_NONE>(rr, raw, dt, V, g)))
                         }
                         break;
                     }
@@ -918,13 +947,9 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             tile_bins_dispatch<K>(acc, s, b);
                         }
                         break;
-                    case I_SEL: {
-                        Tile<K> xa = acc, xb = acc;
-                        DVM_WITH_R(a, rr, xa = rr)
-                        DVM_WITH_R(b, rr, xb = rr)
-                        sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; });
+                    case I_SEL:         // every pair of registers gets its own copy of the loop: no tile is copied
+                        DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; })))
                         break;
-                    }
                     case I_RED: {
                         DVM_GEO()
                         float v = reduce_dispatch<K>(acc, g, V, b, width);
