@@ -151,7 +151,7 @@ constexpr Variant VARIANTS[] = {
     { 4, 2, 1024, 8}, { 4, 6, 1024, 7},
     { 8, 2, 1024, 6}, { 8, 6,  512, 4},
     {16, 2, 1024, 4}, {16, 4,  512, 3}, {16, 6,  512, 2},
-    {32, 2,  256, 2},
+    {32, 2,  256, 2}, {32, 4,  256, 2},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 

@@ -1141,8 +1141,6 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     };
     // first without hoisting, to learn how many tile registers the body needs; then, in row mode,
     // again with as many pinned operands as keep the program within four tile registers
-    // (rows long enough for 32 elements per lane keep to the two tile registers of that variant:
-    // fewer interpreted records per element outweigh reloading a row vector from cache)
     E.nr_limit = ctx->max_nr < NR_MAX ? ctx->max_nr : NR_MAX;
     E.reload_inputs = false;
     linearize(0);
@@ -1152,8 +1150,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         linearize(0);
     }
     {
-        const int64_t lanes32 = cdiv(cdiv(E.D0 > 0 ? E.D0 : 1, any_bf16_full ? 8 : 4), any_bf16_full ? 4 : 8);
-        int reg_cap = (lanes32 >= 32 && E.nr_used <= 2 && ctx->dbg_k != 16 && ctx->max_k >= 32) ? 2 : 4;
+        int reg_cap = 4;
         if (reg_cap > ctx->max_nr) reg_cap = ctx->max_nr;
         if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap) {
             const int body_regs = E.nr_used;

@@ -1006,7 +1006,7 @@ const VariantEntry g_variants[] = {
     { 4, 2, dvm_vm_kernel< 4, 2, 1024, 4>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024, 4>},
     { 8, 2, dvm_vm_kernel< 8, 2, 1024, 4>}, { 8, 6, dvm_vm_kernel< 8, 6,  512, 4>},
     {16, 2, dvm_vm_kernel<16, 2, 1024, 4>}, {16, 4, dvm_vm_kernel<16, 4,  512, 3>}, {16, 6, dvm_vm_kernel<16, 6,  512, 2>},
-    {32, 2, dvm_vm_kernel<32, 2,  256, 2>},
+    {32, 2, dvm_vm_kernel<32, 2,  256, 2>}, {32, 4, dvm_vm_kernel<32, 4,  256, 2>},
 };
 
 thread_local int t_last_hip_error = 0;
