@@ -102,6 +102,7 @@ enum : uint32_t {
                  // reduction folded into its record.  When a row spans several waves the handler
                  // synchronises the workgroup between the per-wave part and the combination.
     I_SOP,       // S[a] = op(S[b], S[c] | imm)
+    I_FMA,       // ACC = ACC * R[a] + R[b]: a multiply by a tile register directly followed by an add of one
     I_COUNT
 };
 

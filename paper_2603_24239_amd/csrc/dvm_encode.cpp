@@ -536,6 +536,13 @@ struct Enc {
     void emit(uint8_t op, uint8_t a = 0, uint8_t b = 0, int tensor = -1, float imm = 0.0f, uint8_t kind = 0,
               uint8_t srck = 0, uint8_t c = 0) {
         if (n_ai >= MAX_AI) { fail(DVM_E_LIMIT, "too many instructions"); return; }
+        // acc * R + R in two adjacent records becomes one fused multiply-add record
+        if (op == I_BIN && b == B_ADD && a < SRC_S0 && n_ai > 0 && ai[n_ai - 1].op == I_BIN && ai[n_ai - 1].b == B_MUL &&
+            ai[n_ai - 1].a < SRC_S0) {
+            ai[n_ai - 1].op = I_FMA;
+            ai[n_ai - 1].b = a;
+            return;
+        }
         AI &x = ai[n_ai++];
         x.op = op; x.a = a; x.b = b; x.c = c; x.kind = kind; x.srck = srck; x.tensor = (int16_t)tensor; x.imm = imm;
         x.imm2 = 0.0f;
@@ -1568,6 +1575,9 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                 case I_SEL:
                     if (l != LEN_REC || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("select");
                     break;
+                case I_FMA:
+                    if (l != LEN_REC || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("fused multiply-add");
+                    break;
                 case I_RED:
                     if (l != LEN_REC || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
                     if (w[pc + 1] >= U_COUNT) return bad("reduction post op");
@@ -1894,6 +1904,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
                     break;
                 case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
+                case I_FMA: o.put("  %04zu fma     acc = acc * r%u + r%u\n", pc - at - SH_WORDS, a, b); break;
                 case I_RED:
                     o.put("  %04zu red.%-5s s%u = %s(acc * %.9g + %.9g)%s\n", pc - at - SH_WORDS, RED_NAMES[b], a,
                           w[pc + 1] ? UN_NAMES[w[pc + 1]] : "", (double)f32_bits(w[pc + 2]), (double)f32_bits(w[pc + 3]),

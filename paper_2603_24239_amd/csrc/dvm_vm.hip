@@ -950,6 +950,9 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                     case I_SEL:         // every pair of registers gets its own copy of the loop: no tile is copied
                         DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; })))
                         break;
+                    case I_FMA:
+                        DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I], xa.v[I], xb.v[I]); })))
+                        break;
                     case I_RED: {
                         DVM_GEO()
                         float v = reduce_dispatch<K>(acc, g, V, b, width);
