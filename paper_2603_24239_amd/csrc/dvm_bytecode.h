@@ -102,7 +102,8 @@ enum : uint32_t {
                  // reduction folded into its record.  When a row spans several waves the handler
                  // synchronises the workgroup between the per-wave part and the combination.
     I_SOP,       // S[a] = op(S[b], S[c] | imm)
-    I_FMA,       // ACC = ACC * R[a] + R[b]: a multiply by a tile register directly followed by an add of one
+    I_FMA,       // ACC = ACC * s * R[a] + R[b]: adjacent multiplies and an add fused into one record.  word1 = 0: s = 1,
+                 // else s = S[word1 - 1]; b = FMA_NO_ADDEND: nothing is added
     I_COUNT
 };
 
@@ -119,6 +120,7 @@ constexpr uint32_t SRC_S0  = 16;        // 16 .. 16+NS-1
 constexpr uint32_t SRC_ACC = 32;
 constexpr uint32_t SRC_IMM = 33;
 constexpr int NS = 4;                   // row-scalar registers
+constexpr uint32_t FMA_NO_ADDEND = 0xFF;
 
 // binary ops B_*
 enum : uint32_t {

@@ -536,12 +536,20 @@ struct Enc {
     void emit(uint8_t op, uint8_t a = 0, uint8_t b = 0, int tensor = -1, float imm = 0.0f, uint8_t kind = 0,
               uint8_t srck = 0, uint8_t c = 0) {
         if (n_ai >= MAX_AI) { fail(DVM_E_LIMIT, "too many instructions"); return; }
-        // acc * R + R in two adjacent records becomes one fused multiply-add record
-        if (op == I_BIN && b == B_ADD && a < SRC_S0 && n_ai > 0 && ai[n_ai - 1].op == I_BIN && ai[n_ai - 1].b == B_MUL &&
-            ai[n_ai - 1].a < SRC_S0) {
-            ai[n_ai - 1].op = I_FMA;
-            ai[n_ai - 1].b = a;
-            return;
+        // adjacent multiplies by a row scalar and by a tile register, and an add of a tile register after
+        // them, become one fused record: acc = acc * S * R + R (kind: S index + 1, 0 = no scalar)
+        if (op == I_BIN && n_ai > 0) {
+            AI &p = ai[n_ai - 1];
+            const bool is_r = a < SRC_S0, is_s = a >= SRC_S0 && a < SRC_S0 + NS;
+            if (b == B_ADD && is_r) {
+                if (p.op == I_BIN && p.b == B_MUL && p.a < SRC_S0) { p.op = I_FMA; p.b = a; p.kind = 0; return; }
+                if (p.op == I_FMA && p.b == FMA_NO_ADDEND) { p.b = a; return; }
+            }
+            if (b == B_MUL && p.op == I_BIN && p.b == B_MUL) {
+                const bool p_r = p.a < SRC_S0, p_s = p.a >= SRC_S0 && p.a < SRC_S0 + NS;
+                if (p_s && is_r) { const uint8_t s = (uint8_t)(p.a - SRC_S0 + 1); p.op = I_FMA; p.a = a; p.b = FMA_NO_ADDEND; p.kind = s; return; }
+                if (p_r && is_s) { p.op = I_FMA; p.b = FMA_NO_ADDEND; p.kind = (uint8_t)(a - SRC_S0 + 1); return; }
+            }
         }
         AI &x = ai[n_ai++];
         x.op = op; x.a = a; x.b = b; x.c = c; x.kind = kind; x.srck = srck; x.tensor = (int16_t)tensor; x.imm = imm;
@@ -1394,6 +1402,12 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 b[2] = x.srck == 1 ? bits_f32(x.imm) : 0u;
                 b += LEN_SOP;
                 break;
+            case I_FMA:
+                imask |= 1u << I_FMA;
+                b[0] = w0(I_FMA, LEN_REC, x.a, x.b);
+                b[1] = x.kind;
+                b += LEN_REC;
+                break;
             case I_RED:
                 imask |= 1u << I_RED;
                 b[0] = w0(I_RED, LEN_REC, x.a, x.b);
@@ -1576,7 +1590,8 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (l != LEN_REC || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("select");
                     break;
                 case I_FMA:
-                    if (l != LEN_REC || !reg_ok(a, vr) || !reg_ok(bb, vr)) return bad("fused multiply-add");
+                    if (l != LEN_REC || !reg_ok(a, vr) || !(reg_ok(bb, vr) || bb == FMA_NO_ADDEND)) return bad("fused multiply-add");
+                    if (w[pc + 1] > (uint32_t)NS || (w[pc + 1] == 0 && bb == FMA_NO_ADDEND)) return bad("fused multiply-add scalar");
                     break;
                 case I_RED:
                     if (l != LEN_REC || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
@@ -1904,7 +1919,13 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
                     break;
                 case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
-                case I_FMA: o.put("  %04zu fma     acc = acc * r%u + r%u\n", pc - at - SH_WORDS, a, b); break;
+                case I_FMA: {
+                    char sc[8] = "", ad[8] = "";
+                    if (w[pc + 1]) snprintf(sc, sizeof sc, " * s%u", w[pc + 1] - 1);
+                    if (b != FMA_NO_ADDEND) snprintf(ad, sizeof ad, " + r%u", b);
+                    o.put("  %04zu fma     acc = acc%s * r%u%s\n", pc - at - SH_WORDS, sc, a, ad);
+                    break;
+                }
                 case I_RED:
                     o.put("  %04zu red.%-5s s%u = %s(acc * %.9g + %.9g)%s\n", pc - at - SH_WORDS, RED_NAMES[b], a,
                           w[pc + 1] ? UN_NAMES[w[pc + 1]] : "", (double)f32_bits(w[pc + 2]), (double)f32_bits(w[pc + 3]),

@@ -951,7 +951,16 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; })))
                         break;
                     case I_FMA:
-                        DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I], xa.v[I], xb.v[I]); })))
+                        if (cw1 == 0) {
+                            DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I], xa.v[I], xb.v[I]); })))
+                        } else {
+                            const float s = DVM_GET_S(cw1 - 1);
+                            if (b == FMA_NO_ADDEND) {
+                                DVM_WITH_R(a, xa, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] * s * xa.v[I]; }))
+                            } else {
+                                DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I] * s, xa.v[I], xb.v[I]); })))
+                            }
+                        }
                         break;
                     case I_RED: {
                         DVM_GEO()

@@ -295,3 +295,19 @@ def test_spatial_stack_gives_every_part_its_share_of_workgroups(ctx):
     # a stacked program cannot be a part of a spatial stack; a temporal stack of it is fine
     with pytest.raises(B.DvmError):
         B.dvm_stack([st, codes[0]], spatial=True)
+
+
+def test_adjacent_multiplies_and_add_fuse_into_one_record(ctx):
+    # rmsnorm: x * rsqrt(...) * w -> acc * s * r in one record, four records per tile in all
+    txt = _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)]).disasm()
+    body = txt.split("; body (once per tile)")[1]
+    assert re.search(r"fma\s+acc = acc \* s0 \* r0\n", body) and len(re.findall(r"^\s+\d{4} ", body, flags=re.M)) == 4
+    # layernorm: ... * rs * gamma + beta
+    txt = _encode(ctx, "layernorm_bf16", [(64, 8192, 2048), (2048,), (2048,)]).disasm()
+    assert re.search(r"fma\s+acc = acc \* s0 \* r0 \+ r1", txt)
+    # a multiply whose result is also an output must stay a record of its own
+    from workloads.programs import _p
+    keep = _p("keep_product", [("x", "f32"), ("g", "f32"), ("b", "f32")],
+              [("m", "mul", ["x", "g"], {}), ("y", "add", ["m", "b"], {})], [("m", "f32"), ("y", "f32")])
+    txt = B.dvm_encode(ctx, B.Program(keep), [B.make_shape((64, 512)), B.make_shape((512,)), B.make_shape((512,))]).disasm()
+    assert "fma" not in txt and len(re.findall(r"\bstore\b", txt)) == 2
