@@ -10,7 +10,9 @@ as plain scalar jumps and lets every instruction update its destination register
 """
 from __future__ import annotations
 
+import concurrent.futures
 import os
+import re
 import subprocess
 import sys
 
@@ -24,21 +26,44 @@ DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-pa
           "-mllvm", "-simplifycfg-sink-common=false"]
 
 
+def variants():
+    """(K, NR, largest workgroup, waves per SIMD) of every interpreter variant, read from the device source."""
+    src = open(os.path.join(CSRC, "dvm_vm.hip")).read()
+    body = src[src.index("#define DVM_VARIANT_LIST(X)"):]
+    body = body[: body.index("\n\n")]
+    out = [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+),\s*(\d+)\)", body)]
+    if not out:
+        raise RuntimeError("no interpreter variants found in dvm_vm.hip")
+    return out
+
+
 def build(verbose: bool = True) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
-    for src, extra in (("dvm_encode.cpp", []), ("dvm_fuser.cpp", []), ("dvm_vm.hip", DEVICE)):
-        obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
-        cmd = [hipcc, *COMMON, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    vm = os.path.join(CSRC, "dvm_vm.hip")
+    jobs = [([hipcc, *COMMON, "-c", os.path.join(CSRC, "dvm_encode.cpp")], os.path.join(CSRC, "dvm_encode.o")),
+            ([hipcc, *COMMON, "-c", os.path.join(CSRC, "dvm_fuser.cpp")], os.path.join(CSRC, "dvm_fuser.o")),
+            ([hipcc, *COMMON, *DEVICE, "-c", vm], os.path.join(CSRC, "dvm_vm_host.o"))]
+    # every interpreter variant is a translation unit of its own, compiled side by side
+    for k, nr, maxt, waves in variants():
+        defs = [f"-DDVM_VARIANT_K={k}", f"-DDVM_VARIANT_NR={nr}", f"-DDVM_VARIANT_MAXT={maxt}", f"-DDVM_VARIANT_WAVES={waves}"]
+        jobs.append(([hipcc, *COMMON, *DEVICE, *defs, "-c", vm], os.path.join(CSRC, f"dvm_vm_k{k}_r{nr}.o")))
+
+    def run(job):
+        cmd, obj = job
+        cmd = cmd + ["-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+            raise RuntimeError(f"hipcc failed on {obj}:\n{err}")
         if verbose and err.strip():
             print(err)
-        objs.append(obj)
+        return obj
+
+    workers = max(1, min(len(jobs), os.cpu_count() or 1, int(os.environ.get("MAX_JOBS", "16"))))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+        objs = list(pool.map(run, jobs))
     cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", *objs, "-o", LIB]
     if verbose:
         print(" ".join(cmd), flush=True)

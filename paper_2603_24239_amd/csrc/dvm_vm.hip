@@ -950,18 +950,25 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                     case I_SEL:         // every pair of registers gets its own copy of the loop: no tile is copied
                         DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; })))
                         break;
-                    case I_FMA:
-                        if (cw1 == 0) {
-                            DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I], xa.v[I], xb.v[I]); })))
-                        } else {
-                            const float s = DVM_GET_S(cw1 - 1);
-                            if (b == FMA_NO_ADDEND) {
+                    case I_FMA: {
+                        const float s = cw1 != 0 ? DVM_GET_S(cw1 - 1) : 1.0f;
+                        if constexpr (NR <= 4) {        // one loop per (multiplier, addend) pair of registers
+                            if (cw1 == 0) {
+                                DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I], xa.v[I], xb.v[I]); })))
+                            } else if (b == FMA_NO_ADDEND) {
                                 DVM_WITH_R(a, xa, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] * s * xa.v[I]; }))
                             } else {
                                 DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I] * s, xa.v[I], xb.v[I]); })))
                             }
+                        } else {                        // many registers: the pairs would multiply the code size
+                            if (cw1 != 0) tile_bins<K, B_MUL>(acc, s);
+                            DVM_WITH_R(a, xa, (tile_bin<K, B_MUL>(acc, xa)))
+                            if (b != FMA_NO_ADDEND) {
+                                DVM_WITH_R(b, xb, (tile_bin<K, B_ADD>(acc, xb)))
+                            }
                         }
                         break;
+                    }
                     case I_RED: {
                         DVM_GEO()
                         float v = reduce_dispatch<K>(acc, g, V, b, width);
@@ -1007,19 +1014,40 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 }
 
 // ------------------------------------------------------------------------------------------
-// host side: dvm_run
+// interpreter variants and host side
 // ------------------------------------------------------------------------------------------
-typedef void (*vm_kernel_t)(const KArgs);
+// X(K, NR, largest workgroup, resident waves per SIMD the register allocation aims for).  Every
+// variant is compiled in a translation unit of its own (this file with -DDVM_VARIANT_K=.. etc.),
+// which defines the kernel and a launcher; the translation unit without those macros holds the
+// host side.  The build script reads this list.
+#define DVM_VARIANT_LIST(X) \
+    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 4) X(8, 6, 512, 4) \
+    X(16, 2, 1024, 4) X(16, 4, 512, 3) X(16, 6, 512, 2) X(32, 2, 256, 2) X(32, 4, 256, 2)
 
-struct VariantEntry { int K, NR; vm_kernel_t fn; };
+#define DVM_LAUNCHER_NAME_(K, NR) dvm_vm_launch_##K##_##NR
+#define DVM_LAUNCHER_NAME(K, NR) DVM_LAUNCHER_NAME_(K, NR)
 
-// (the last template argument is the number of resident waves per SIMD the register allocation aims for)
-const VariantEntry g_variants[] = {
-    { 4, 2, dvm_vm_kernel< 4, 2, 1024, 4>}, { 4, 6, dvm_vm_kernel< 4, 6, 1024, 4>},
-    { 8, 2, dvm_vm_kernel< 8, 2, 1024, 4>}, { 8, 6, dvm_vm_kernel< 8, 6,  512, 4>},
-    {16, 2, dvm_vm_kernel<16, 2, 1024, 4>}, {16, 4, dvm_vm_kernel<16, 4,  512, 3>}, {16, 6, dvm_vm_kernel<16, 6,  512, 2>},
-    {32, 2, dvm_vm_kernel<32, 2,  256, 2>}, {32, 4, dvm_vm_kernel<32, 4,  256, 2>},
-};
+}  // namespace
+
+#ifdef DVM_VARIANT_K
+// ---- one interpreter variant: kernel instantiation + launcher ---------------------------------
+extern "C" void DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, void *stream, const void *kargs) {
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES>), dim3(grid), dim3(block), 0,
+                       (hipStream_t)stream, *(const KArgs *)kargs);
+}
+#else
+// ---- host side: dvm_run ---------------------------------------------------------------------
+#define X(K, NR, MAXT, W) extern "C" void DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, void *, const void *);
+DVM_VARIANT_LIST(X)
+#undef X
+
+namespace {
+
+typedef void (*vm_launch_t)(unsigned, unsigned, void *, const void *);
+struct VariantEntry { int K, NR; vm_launch_t launch; };
+#define X(K, NR, MAXT, W) {K, NR, DVM_LAUNCHER_NAME(K, NR)},
+const VariantEntry g_variants[] = {DVM_VARIANT_LIST(X)};
+#undef X
 
 thread_local int t_last_hip_error = 0;
 
@@ -1067,12 +1095,12 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     ka.pad = 0;
 
     const int K = (int)(w[PH_VARIANT] & 0xFF), NR = (int)((w[PH_VARIANT] >> 8) & 0xFF);
-    vm_kernel_t fn = nullptr;
+    vm_launch_t launch = nullptr;
     for (const VariantEntry &v : g_variants)
-        if (v.K == K && v.NR == NR) fn = v.fn;
-    if (!fn) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
+        if (v.K == K && v.NR == NR) launch = v.launch;
+    if (!launch) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
-    hipLaunchKernelGGL(fn, dim3(grid), dim3(block), 0, (hipStream_t)hip_stream, ka);
+    launch(grid, block, hip_stream, &ka);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;
@@ -1080,3 +1108,4 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     }
     return DVM_OK;
 }
+#endif  // host side
