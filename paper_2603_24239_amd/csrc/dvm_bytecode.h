@@ -89,7 +89,7 @@ enum : uint32_t {
     I_LOAD,      // contiguous rows, one row stride     a = dst, b = combine op (B_NONE: plain move)
     I_VLOAD,     // view load: three outer strides      (Table 1: ViewLoad)
     I_LOADS,     // one value per row -> S[a]
-    I_STORE,     // a = src register                    (Table 1: Store)
+    I_STORE,     // a = src register; b != 0: multiply ACC by S[b-1] first   (Table 1: Store)
     I_VSTORE,    //                                     (Table 1: ViewStore)
     I_STORES,    // S[a] -> one value per row
     I_MOVRA,     // R[a] = ACC                          (Table 1: Copy)

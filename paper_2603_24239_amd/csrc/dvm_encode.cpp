@@ -972,7 +972,16 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (E.rows_class[n]) {
                 E.emit(I_STORES, (uint8_t)E.sreg(n), 0, t);
             } else if (E.in_acc == n) {
-                E.emit(I_STORE, (uint8_t)SRC_ACC, 0, t);
+                // a multiply by a row scalar whose only use is this store rides along with the store record
+                uint8_t scale = 0;
+                if (E.uses[n] == 1 && E.n_ai > E.n_prolog) {
+                    const AI &p = E.ai[E.n_ai - 1];
+                    if (p.op == I_BIN && p.b == B_MUL && p.a >= SRC_S0 && p.a < SRC_S0 + NS) {
+                        scale = (uint8_t)(p.a - SRC_S0 + 1);
+                        --E.n_ai;
+                    }
+                }
+                E.emit(I_STORE, (uint8_t)SRC_ACC, scale, t);
             } else if (E.reg_of[n] >= 0) {
                 E.emit(I_STORE, (uint8_t)E.reg_of[n], 0, t);
             } else {
@@ -1552,7 +1561,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (a != SRC_ACC && !reg_ok(a, vr)) return bad("tile register index");
                     if ((op == I_LOAD || op == I_VLOAD)
                             ? (!(bb == B_NONE || bb == B_ADD || bb == B_SUB || bb == B_RSUB || bb == B_MUL) || (a != SRC_ACC && bb != B_NONE))
-                            : bb != 0)
+                            : (bb > (uint32_t)NS || (bb != 0 && a != SRC_ACC)))
                         return bad("combine op");
                     const uint32_t w1 = w[pc + 1];
                     if ((w1 & 0xFF) >= nt) return bad("tensor index");
@@ -1897,11 +1906,12 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                           w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6), ((w[pc + 1] >> 16) & MF_STREAM) ? "  [read once]" : "");
                     break;
                 case I_STORE:
-                    o.put("  %04zu store   t%u = %s stride=%lld\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2));
+                    if (b) o.put("  %04zu store   t%u = %s * s%u stride=%lld\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, b - 1, i64(pc + 2));
+                    else o.put("  %04zu store   t%u = %s stride=%lld\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2));
                     break;
                 case I_VSTORE:
-                    o.put("  %04zu viewstore t%u = %s strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra, i64(pc + 2),
-                          i64(pc + 4), i64(pc + 6));
+                    o.put("  %04zu viewstore t%u = %s%s strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, w[pc + 1] & 0xFF, ra,
+                          b ? " * s" : "", i64(pc + 2), i64(pc + 4), i64(pc + 6));
                     break;
                 case I_LOADS:
                     o.put("  %04zu loads   s%u = t%u strides=[%lld,%lld,%lld]\n", pc - at - SH_WORDS, a, w[pc + 1] & 0xFF, i64(pc + 2),

@@ -893,6 +893,8 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         gptr base = (gptr)args.tensors[tbase + ti];
                         gptr rowp = base + off * es;
                         if (a == SRC_ACC) {
+                            // (b: a row scalar to multiply by first; the accumulator's value is dead afterwards)
+                            if (b != 0) tile_bins<K, B_MUL>(acc, DVM_GET_S(b - 1));
                             store_dispatch<K>(acc, dt, V, rowp, g);
                         } else {
                             DVM_WITH_R(a, rr, store_dispatch<K>(rr, dt, V, rowp, g))

@@ -311,3 +311,14 @@ def test_adjacent_multiplies_and_add_fuse_into_one_record(ctx):
               [("m", "mul", ["x", "g"], {}), ("y", "add", ["m", "b"], {})], [("m", "f32"), ("y", "f32")])
     txt = B.dvm_encode(ctx, B.Program(keep), [B.make_shape((64, 512)), B.make_shape((512,)), B.make_shape((512,))]).disasm()
     assert "fma" not in txt and len(re.findall(r"\bstore\b", txt)) == 2
+
+
+def test_trailing_row_scalar_multiply_rides_with_the_store(ctx):
+    txt = _encode(ctx, "softmax_bf16", [(100, 4096)]).disasm()
+    assert re.search(r"store\s+t1 = acc \* s0", txt) and "mul " not in txt
+    # not when the product is needed again
+    from workloads.programs import _p
+    again = _p("scaled_twice", [("x", "f32")], [("m", "rmax", ["x"], {}), ("y", "mul", ["x", "m"], {}), ("z", "tanh", ["y"], {})],
+               [("y", "f32"), ("z", "f32")])
+    txt = B.dvm_encode(ctx, B.Program(again), [B.make_shape((64, 512))]).disasm()
+    assert "mul " in txt and not re.search(r"store\s+t\d = acc \*", txt)
