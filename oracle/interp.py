@@ -151,6 +151,14 @@ def _eval(name: str, a: Tuple[np.ndarray, ...], attrs: Mapping[str, object]) -> 
             return np.max(a[0], axis=-1, keepdims=True)
         if name == "rmin":
             return np.min(a[0], axis=-1, keepdims=True)
+        # Table 1's reductions in their general form: [M, size, N] reduced along `size` to [M, 1, N]
+        # (the penultimate axis; the row reductions above are the N = 1 case)
+        if name == "csum":
+            return np.sum(a[0], axis=-2, keepdims=True)
+        if name == "cmax":
+            return np.max(a[0], axis=-2, keepdims=True)
+        if name == "cmin":
+            return np.min(a[0], axis=-2, keepdims=True)
         if name == "select":
             cond, xm, xn = a
             return np.where(_f32(cond) != 0.0, xm, xn)

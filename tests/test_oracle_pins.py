@@ -433,3 +433,43 @@ def test_add_sqrt_example_and_if_else_add():
     _, et = run(W.get_program("if_else_add_true"), x=x, y=y)
     _, ef = run(W.get_program("if_else_add_false"), x=x, y=y)
     assert et["o"].tolist() == [21.0, 41.0, 61.0] and ef["o"].tolist() == [41.0, 81.0, 121.0]
+
+
+# ------------------------------------------------------------------ reductions along the penultimate axis (Table 1)
+
+def test_penultimate_axis_reductions_closed_form_and_bruteforce():
+    # closed form: x[m, r, n] = r * (n + 1) + m  =>  sum_r = (n + 1) * size * (size - 1) / 2 + m * size,
+    # max_r = (size - 1) * (n + 1) + m, min_r = m; a transposed or wrong-axis reduction fails the shape
+    # or the values (M, size and N all differ)
+    M, size, N = 3, 7, 5
+    m, r, n = np.meshgrid(np.arange(M), np.arange(size), np.arange(N), indexing="ij")
+    x = (r * (n + 1) + m).astype(np.float64)
+    nn = np.arange(N, dtype=np.float64)
+    mm = np.arange(M, dtype=np.float64)[:, None, None]
+    for op, want in (("csum", (nn + 1) * size * (size - 1) / 2 + mm * size),
+                     ("cmax", (size - 1) * (nn + 1) + mm + 0 * nn),
+                     ("cmin", mm + 0 * nn)):
+        _, ex = run(single_op_program(op, 1), a0=x)
+        assert ex["y"].shape == (M, 1, N)
+        assert np.array_equal(ex["y"], np.broadcast_to(want, (M, 1, N))), op
+    # brute force with plain loops on random values
+    rng = np.random.default_rng(41)
+    x = rng.standard_normal((2, 6, 4)).astype(np.float32).astype(np.float64)
+    _, s = run(single_op_program("csum", 1), a0=x)
+    _, hi = run(single_op_program("cmax", 1), a0=x)
+    _, lo = run(single_op_program("cmin", 1), a0=x)
+    for i in range(2):
+        for k in range(4):
+            col = [x[i, j, k] for j in range(6)]
+            assert s["y"][i, 0, k] == pytest.approx(math.fsum(col), rel=1e-15, abs=1e-15)
+            assert hi["y"][i, 0, k] == max(col)
+            assert lo["y"][i, 0, k] == min(col)
+    # N = 1 is the row reduction: the same numbers as `sum` over the last axis of the transposed input
+    x1 = rng.standard_normal((3, 9, 1))
+    _, a = run(single_op_program("csum", 1), a0=x1)
+    _, b = run(single_op_program("sum", 1), a0=np.swapaxes(x1, -1, -2).copy())
+    assert np.allclose(a["y"], b["y"], rtol=1e-15)
+    # rank 2: [size, N] -> [1, N], checked against torch's fp64 reduction
+    x2 = rng.standard_normal((11, 3))
+    _, c = run(single_op_program("csum", 1), a0=x2)
+    assert np.allclose(c["y"], torch.from_numpy(x2).sum(dim=0, keepdim=True).numpy(), rtol=1e-14)
