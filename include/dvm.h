@@ -78,6 +78,11 @@ typedef enum dvm_opcode {
     DVM_OP_SELECT = 60,
     /* reductions over the last axis (kept, extent 1) */
     DVM_OP_SUM = 64, DVM_OP_RMAX, DVM_OP_RMIN, DVM_OP_MEAN, DVM_OP_MEANSQ,
+    /* Table 1's Sum / Max / Min in their general form: [M, size, N] reduced along `size`, the penultimate
+     * axis (kept, extent 1).  A program holds reductions along one axis only; a value reduced this way may
+     * feed further ops of its own shape ([M, 1, N] and tensors that broadcast into it), not full-size ones.
+     * The `size` rows are accumulated in order by one workgroup per (M index, column tile), in fp32. */
+    DVM_OP_CSUM = 72, DVM_OP_CMAX, DVM_OP_CMIN,
     /* compound ops, decomposed by dvm_prog_finish */
     DVM_OP_SOFTMAX = 80,    /* args = (z)                                    */
     DVM_OP_RMSNORM,         /* args = (x, w),           imm[0] = eps         */

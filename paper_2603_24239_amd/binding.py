@@ -29,6 +29,8 @@ for _i, _n in enumerate(["add", "sub", "mul", "div", "min", "max", "pow", "cmp_e
 OPCODES["select"] = 60
 for _i, _n in enumerate(["sum", "rmax", "rmin", "mean", "meansq"], start=64):
     OPCODES[_n] = _i
+for _i, _n in enumerate(["csum", "cmax", "cmin"], start=72):      # reductions along the penultimate axis
+    OPCODES[_n] = _i
 for _i, _n in enumerate(["softmax", "rmsnorm", "layernorm"], start=80):
     OPCODES[_n] = _i
 

@@ -75,7 +75,11 @@ enum : int {
     S_PROLOGA,      // the first S_PROLOGA words of the prologue run once per workgroup only; the rest of it runs
                     // again whenever the index of the second outer dim (row / S_D1) differs from the previous tile's
     S_WG0, S_NWG,   // spatial stacking: this segment runs on workgroups [S_WG0, S_WG0 + S_NWG) only (S_NWG 0: on all)
-    S_PAD2, S_PAD3, // keep the body 16-byte aligned
+    S_INNER,        // reduction along the penultimate axis: its extent `size` (0: the segment has none).  Then
+                    // S_NTILES counts units of work (outer index, column tile); a workgroup visits the `size`
+                    // rows of a unit one after the other, so a tile register can accumulate over them
+    S_EPILOG,       // body words that run for every row of a unit; the records after them (the epilogue) run
+                    // after the last row of the unit only (= S_CODESIZE when there is no epilogue)
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");
@@ -104,6 +108,8 @@ enum : uint32_t {
     I_SOP,       // S[a] = op(S[b], S[c] | imm)
     I_FMA,       // ACC = ACC * s * R[a] + R[b]: adjacent multiplies and an add fused into one record.  word1 = 0: s = 1,
                  // else s = S[word1 - 1]; b = FMA_NO_ADDEND: nothing is added
+    I_CACC,      // R[a] = first row of the unit ? ACC : R_b(R[a], ACC): accumulates a reduction along the
+                 // penultimate axis (Table 1: Sum / Max / Min over [M, size, N] with N > 1)
     I_COUNT
 };
 

@@ -150,7 +150,7 @@ extern "C" int dvm_ctx_set_planner(dvm_ctx *c, int n_cu, int overhead) {
 // ------------------------------------------------------------------------------------------------
 namespace {
 
-enum NodeKind : uint8_t { N_IN = 0, N_UN, N_BIN, N_BINI, N_SEL, N_RED, N_DEAD };
+enum NodeKind : uint8_t { N_IN = 0, N_UN, N_BIN, N_BINI, N_SEL, N_RED, N_DEAD, N_CRED };
 enum ImmKind : uint8_t { IMM_LIT = 0, IMM_INV_H = 1 };   // literal, or 1 / (row length of operand a)
 
 constexpr int MAX_NODES = 160;
@@ -214,6 +214,7 @@ static int op_arity(int opcode, int *n_imm) {
     if (opcode >= DVM_OP_ADD && opcode <= DVM_OP_CMP_GE) return 2;
     if (opcode == DVM_OP_SELECT) return 3;
     if (opcode >= DVM_OP_SUM && opcode <= DVM_OP_MEANSQ) return 1;
+    if (opcode >= DVM_OP_CSUM && opcode <= DVM_OP_CMIN) return 1;
     if (opcode == DVM_OP_SOFTMAX) return 1;
     if (opcode == DVM_OP_RMSNORM) { *n_imm = 1; return 2; }
     if (opcode == DVM_OP_LAYERNORM) { *n_imm = 1; return 3; }
@@ -342,6 +343,9 @@ extern "C" int dvm_prog_finish(dvm_prog *p) {
             case DVM_OP_SUM: r = L.red(R_SUM, a); break;
             case DVM_OP_RMAX: r = L.red(R_MAX, a); break;
             case DVM_OP_RMIN: r = L.red(R_MIN, a); break;
+            case DVM_OP_CSUM: r = L.add(N_CRED, (uint8_t)R_SUM, a); break;
+            case DVM_OP_CMAX: r = L.add(N_CRED, (uint8_t)R_MAX, a); break;
+            case DVM_OP_CMIN: r = L.add(N_CRED, (uint8_t)R_MIN, a); break;
             case DVM_OP_MEAN: r = L.inv_h(L.red(R_SUM, a)); p->nodes[r].b = (int16_t)a; break;
             case DVM_OP_MEANSQ: r = L.inv_h(L.red(R_SUMSQ, a)); p->nodes[r].b = (int16_t)a; break;
             case DVM_OP_SOFTMAX: {       // exp(z - max z) / sum exp(z - max z)
@@ -518,6 +522,11 @@ struct Enc {
     int64_t D0, nrows, Dg[4];
     int n_groups;
     bool has_red;
+    bool has_cred;                      // some value is reduced along the penultimate axis
+    bool cred_real[MAX_NODES];          // N_CRED over an axis of extent > 1 (otherwise the identity)
+    bool post[MAX_NODES];               // computed from such a reduction: once per unit, in the epilogue
+    int n_epilog;                       // first abstract instruction of the epilogue
+    int n_fence;                        // peepholes do not reach back across this instruction index
     // linearisation
     AI ai[MAX_AI];
     int n_ai, n_prolog, n_prolog_a;
@@ -538,7 +547,7 @@ struct Enc {
         if (n_ai >= MAX_AI) { fail(DVM_E_LIMIT, "too many instructions"); return; }
         // adjacent multiplies by a row scalar and by a tile register, and an add of a tile register after
         // them, become one fused record: acc = acc * S * R + R (kind: S index + 1, 0 = no scalar)
-        if (op == I_BIN && n_ai > 0) {
+        if (op == I_BIN && n_ai > n_fence) {
             AI &p = ai[n_ai - 1];
             const bool is_r = a < SRC_S0, is_s = a >= SRC_S0 && a < SRC_S0 + NS;
             if (b == B_ADD && is_r) {
@@ -731,6 +740,10 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             }
         }
         if (nd.kind == N_RED) sh[R - 1] = 1;
+        if (nd.kind == N_CRED) {
+            if (R < 2) return dvm_set_error(DVM_E_RANK, "a reduction along the penultimate axis needs rank >= 2");
+            sh[R - 2] = 1;
+        }
     }
     for (int k = 0; k < R; ++k) E.dom[k] = 1;
     for (int n = 0; n < NN; ++n) {
@@ -758,6 +771,41 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         if (nd.kind == N_DEAD) continue;
         E.rows_class[n] = E.row_axis && E.shape[n][R - 1] == 1;
         if (nd.kind == N_RED && !E.rows_class[nd.a] && E.row_axis) E.has_red = true;
+    }
+    // Reductions along the penultimate axis.  The values computed from one (`post`) exist once per unit
+    // (outer index, column tile) and are evaluated by an epilogue after the unit's last row; everything
+    // else is evaluated row by row as usual.
+    E.has_cred = false;
+    for (int n = 0; n < NN; ++n) {
+        const Node &nd = prog->nodes[n];
+        E.cred_real[n] = nd.kind == N_CRED && E.shape[nd.a][R - 2] > 1;
+        if (nd.kind == N_CRED && E.shape[nd.a][R - 2] == 0) return dvm_set_error(DVM_E_UNSUPPORTED, "reduction along an empty axis");
+        E.post[n] = false;
+        E.has_cred |= E.cred_real[n];
+    }
+    if (E.has_cred) {
+        if (!E.row_axis) return dvm_set_error(DVM_E_UNSUPPORTED, "reduction along the penultimate axis of a tensor whose last axis has extent 1: reduce the last axis of [M, size] instead");
+        for (int n = 0; n < NN; ++n) {
+            const Node &nd = prog->nodes[n];
+            if (nd.kind == N_DEAD || nd.kind == N_IN) continue;
+            if (nd.kind == N_RED) return dvm_set_error(DVM_E_UNSUPPORTED, "a program reduces along one axis only");
+            const int args[3] = {nd.a, (nd.kind == N_BIN || nd.kind == N_SEL) ? nd.b : -1, nd.kind == N_SEL ? nd.c : -1};
+            bool any_post = false;
+            for (int j = 0; j < 3; ++j) any_post |= args[j] >= 0 && E.post[args[j]];
+            if (E.cred_real[n]) {
+                if (E.rows_class[nd.a]) return dvm_set_error(DVM_E_UNSUPPORTED, "reduction along the penultimate axis of a row value");
+                if (any_post) return dvm_set_error(DVM_E_UNSUPPORTED, "internal: reduced value reduced again");
+                E.post[n] = true;
+                continue;
+            }
+            if (!any_post) continue;
+            if (E.shape[n][R - 2] != 1)
+                return dvm_set_error(DVM_E_UNSUPPORTED, "a value reduced along the penultimate axis feeds a full-size op: that needs a second pass over the data");
+            for (int j = 0; j < 3; ++j)
+                if (args[j] >= 0 && !E.post[args[j]] && prog->nodes[args[j]].kind != N_IN)
+                    return dvm_set_error(DVM_E_UNSUPPORTED, "an op after the reduction takes a value computed before it");
+            E.post[n] = true;
+        }
     }
 
     // ---- 3. tensor accesses, collapse -------------------------------------------------------------
@@ -792,7 +840,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             // an output must cover the whole iteration space (except the row axis for row values)
             for (int k = 0; k < R; ++k) {
                 const bool row_value = (k == R - 1) && E.rows_class[node];
-                if (E.shape[node][k] != E.dom[k] && !row_value)
+                const bool reduced = (k == R - 2) && E.post[node];
+                if (E.shape[node][k] != E.dom[k] && !row_value && !reduced)
                     return dvm_set_error(DVM_E_UNSUPPORTED, "an output is smaller than the fused iteration space");
             }
         }
@@ -836,6 +885,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         const int ax = ax_list[i];
         bool merge = ng > 0;
         if (merge && ng == 1 && E.row_axis && E.has_red) merge = false;     // rows stay whole under a reduction
+        if (merge && E.has_cred && ng <= 2) merge = false;      // the reduced axis is outer group 1, by itself
         if (merge) {
             const int inner = grp_last[ng - 1];
             for (int t = 0; t < E.n_acc && merge; ++t) {
@@ -859,7 +909,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     // runs back to back, then read the same part of that input again and find it in cache, instead of
     // every workgroup streaming the whole broadcast tensor once per repetition (a causal mask [S,S]
     // under scores [B,H,S,S] would otherwise be fetched from memory B*H times).
-    if (ng > 2) {
+    if (ng > 2 && !E.has_cred) {
         auto carries_broadcast = [&](int g) {
             for (int t = 0; t < prog->n_in; ++t) {
                 const Access &A = E.acc[t];
@@ -924,6 +974,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     E.n_ai = 0;
     E.nr_used = 0;
     E.ns_used = 0;
+    E.n_epilog = -1;
+    E.n_fence = 0;
     // input tensors that are row values by layout (see above) make their nodes row values too
     for (int n = 0; n < NN; ++n)
         if (prog->nodes[n].kind == N_IN && E.acc[prog->nodes[n].input].rows) E.rows_class[n] = true;
@@ -950,7 +1002,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     E.n_prolog_a = E.n_ai;
     // Operands that are invariant along the fastest outer dim only (a mask [S,S] under [B*H,S,S] once that
     // dim is the fastest) are pinned too; their loads run again when the slower index changes.
-    for (int n = 0, left = hoist_budget - hoisted; n < NN && left > 0 && ng >= 3 && E.Dg[1] >= 16; ++n) {
+    for (int n = 0, left = hoist_budget - hoisted; n < NN && left > 0 && ng >= 3 && E.Dg[1] >= 16 && !E.has_cred; ++n) {
         const Node &nd = prog->nodes[n];
         if (nd.kind != N_IN || E.rows_class[n] || E.uses[n] == 0) continue;
         const Access &A = E.acc[nd.input];
@@ -974,7 +1026,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             } else if (E.in_acc == n) {
                 // a multiply by a row scalar whose only use is this store rides along with the store record
                 uint8_t scale = 0;
-                if (E.uses[n] == 1 && E.n_ai > E.n_prolog) {
+                if (E.uses[n] == 1 && E.n_ai > E.n_prolog && E.n_ai > E.n_fence) {
                     const AI &p = E.ai[E.n_ai - 1];
                     if (p.op == I_BIN && p.b == B_MUL && p.a >= SRC_S0 && p.a < SRC_S0 + NS) {
                         scale = (uint8_t)(p.a - SRC_S0 + 1);
@@ -992,9 +1044,36 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         }
     };
 
+    // The accumulators of reductions along the penultimate axis live across the rows of a unit: each
+    // gets a tile register of its own before anything else, so that no temporary of the per-row code
+    // is ever placed in it.
+    for (int n = 0; n < NN && !E.err; ++n)
+        if (E.cred_real[n] && E.uses[n] > 0) E.alloc_reg(n);
+    for (int pass = 0; pass < (E.has_cred ? 2 : 1) && !E.err; ++pass) {
+    if (pass == 1) {            // the epilogue: values computed from the reductions, once per unit
+        E.n_epilog = E.n_ai;
+        E.n_fence = E.n_ai;
+        E.in_acc = -1;
+    }
     for (int n = 0; n < NN && !E.err; ++n) {
-        const Node &nd = prog->nodes[n];
+        Node nd = prog->nodes[n];
         if (nd.kind == N_DEAD) continue;
+        if (E.cred_real[n]) {
+            if (pass == 0) {
+                if (E.uses[n] > 0) {
+                    E.to_acc(nd.a);
+                    E.emit(I_CACC, (uint8_t)E.reg_of[n], nd.op);
+                }
+                E.use(nd.a);
+            } else {
+                store_outputs(n);
+            }
+            continue;
+        }
+        if (E.post[n] != (pass == 1)) continue;
+        if (nd.kind == N_CRED) {        // over an axis of extent 1: the identity (x * 1 keeps every value, NaNs and signed zeros included)
+            nd.kind = N_BINI; nd.op = (uint8_t)B_MUL; nd.imm = 1.0f; nd.immkind = IMM_LIT;
+        }
         if (nd.kind == N_IN) {
             store_outputs(n);       // an input that is also an output: a plain copy
             continue;
@@ -1162,6 +1241,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         }
         if (!E.err) store_outputs(n);
     }
+    }
+    if (E.n_epilog < 0) E.n_epilog = E.n_ai;
     };
     // first without hoisting, to learn how many tile registers the body needs; then, in row mode,
     // again with as many pinned operands as keep the program within four tile registers
@@ -1176,7 +1257,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     {
         int reg_cap = 4;
         if (reg_cap > ctx->max_nr) reg_cap = ctx->max_nr;
-        if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap) {
+        if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap && !E.has_cred) {
             const int body_regs = E.nr_used;
             linearize(reg_cap - body_regs);
             if (E.err || E.nr_used > reg_cap) { E.err = nullptr; linearize(0); }
@@ -1207,7 +1288,35 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     bool has_rows_output = false;
     for (int t = prog->n_in; t < E.n_acc; ++t) has_rows_output |= E.acc[t].rows;
     if (has_rows_output) column_mode = false;
-    if (!column_mode) {
+    const int64_t cred_outer = E.has_cred && E.Dg[1] > 0 ? E.nrows / E.Dg[1] : 0;
+    if (E.has_cred) {
+        // Reduction along the penultimate axis: a unit of work is (outer index, column tile); one wave
+        // walks the `size` rows of a unit and accumulates in a tile register.  The tile is as wide as
+        // still leaves enough units to fill the machine.
+        if (has_rows_output) return dvm_set_error(DVM_E_UNSUPPORTED, "a row-value output beside a reduction along the penultimate axis");
+        column_mode = false;
+        const int ks[4] = {4, 8, 16, 32};
+        int pick = -1;
+        for (int i = 0; i < 4; ++i) {
+            const int K = ks[i];
+            if ((uint32_t)K < V) continue;
+            const int v = find_variant(K);
+            if (v < 0) continue;
+            const int64_t units = cred_outer * cdiv(E.D0 > 0 ? E.D0 : 1, 64 * K);
+            if (pick < 0 || units >= (int64_t)ctx->n_cu * slots_per_cu(VARIANTS[v], 64)) pick = v;
+        }
+        if (pick < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
+        vi = pick;
+        G = 64;
+        RP = 1;
+        nvec = (uint32_t)(VARIANTS[vi].K / V);
+        TC = G * nvec * V;
+        nct = (uint32_t)cdiv(E.D0 > 0 ? E.D0 : 1, TC);
+        if (nct == 1) {                 // a short row: only as many chunks per lane as it needs
+            nvec = (uint32_t)cdiv(Cr, G);
+            TC = G * nvec * V;
+        }
+    } else if (!column_mode) {
         const int ks[4] = {4, 8, 16, 32};
         int pick = -1;
         // the largest K that still spreads a row over >= 16 lanes (K = 32: over >= 32 lanes, since that
@@ -1298,7 +1407,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     }
     const Variant &vr = VARIANTS[vi];
     const uint32_t threads = G * RP;
-    const int64_t M64 = total == 0 ? 0 : cdiv(E.nrows, RP) * nct;
+    const int64_t M64 = total == 0 ? 0 : (E.has_cred ? cred_outer * nct : cdiv(E.nrows, RP) * nct);
     if (M64 >= (1ll << 31)) return dvm_set_error(DVM_E_LIMIT, "more than 2^31 tiles");
     const int64_t Nslots = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
     const int64_t Ngrid = Nslots * ctx->dbg_grid_x;
@@ -1307,12 +1416,13 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
 
     // ---- 6. emit ---------------------------------------------------------------------------
     // size first
-    size_t body_words = 0, prolog_words = 0, prolog_a_words = 0;
+    size_t body_words = 0, prolog_words = 0, prolog_a_words = 0, epilog_words = 0;
     const bool view = ng > 2;       // more than one outer group: rows need the multi-stride form
     for (int i = 0; i < E.n_ai; ++i) {
         const AI &x = E.ai[i];
         if (i == E.n_prolog) prolog_words = body_words;
         if (i == E.n_prolog_a) prolog_a_words = body_words;
+        if (i == E.n_epilog) epilog_words = body_words;
         switch (x.op) {
             case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
             case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
@@ -1368,6 +1478,10 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
+    if (E.has_cred) {
+        sh[S_INNER] = (uint32_t)E.Dg[1];
+        sh[S_EPILOG] = (uint32_t)(E.n_epilog >= E.n_ai ? body_words : epilog_words);
+    }
     uint32_t imask = 0;
     uint32_t *b = sh + SH_WORDS;
     auto put_i64 = [&](int64_t v) { *b++ = (uint32_t)((uint64_t)v & 0xFFFFFFFFu); *b++ = (uint32_t)((uint64_t)v >> 32); };
@@ -1505,7 +1619,16 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         if (M != 0) {
             if ((uint64_t)nct * TC < D0) return bad("column tiles do not cover the row");
             if (nct > 1 && (uint64_t)(nct - 1) * TC >= D0) return bad("an empty column tile");
-            if (M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
+            if (sh[S_INNER] == 0 && M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
+        }
+        if (sh[S_INNER] != 0) {        // units of (outer index, column tile), `size` rows each
+            if (RP != 1 || G != 64) return bad("geometry of a reduction along the penultimate axis");
+            if (nrows % sh[S_INNER] != 0 || M != (nrows / sh[S_INNER]) * nct) return bad("unit count");
+            if (M != 0 && (sh[S_D1] != 0 ? sh[S_D1] != sh[S_INNER] : nrows != sh[S_INNER])) return bad("reduced axis is not the fastest outer dim");
+            if (sh[S_PROLOG] != 0) return bad("prologue in a segment that reduces along the penultimate axis");
+            if (sh[S_EPILOG] > cs || (sh[S_EPILOG] & 3)) return bad("epilogue offset");
+        } else if (sh[S_EPILOG] != 0) {
+            return bad("epilogue without a reduced axis");
         }
         if (sh[S_D1] == 0 && sh[S_D2] != 0) return bad("outer dims");
         if (sh[S_D1] != 0) {
@@ -1524,7 +1647,6 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if (m != sh[S_NCTM] || sft != sh[S_NCTSH]) return bad("division constants of the column tiles");
         }
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
-        if (sh[S_PAD2] != 0 || sh[S_PAD3] != 0) return bad("padding words");
         if (kt == KT_STACK_SPATIAL) {
             if (sh[S_NWG] == 0 || sh[S_WG0] != wg_next) return bad("workgroup share of a spatially stacked segment");
             if (sh[S_NTILES] != 0) {
@@ -1540,6 +1662,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         if (sh[S_PROLOGA] != sh[S_PROLOG] && sh[S_D1] == 0) return bad("reloading prologue without a second outer dim");
         bool prolog_ends_on_record = sh[S_PROLOG] == 0;
         bool prolog_a_ends_on_record = sh[S_PROLOGA] == 0;
+        bool epilog_on_record = sh[S_INNER] == 0 || sh[S_EPILOG] == 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
         if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
         tiles_total += M;
@@ -1552,6 +1675,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if ((l != LEN_REC && l != LEN_VLOAD) || pc + l > end) return bad("instruction length");
             if (pc + l == at + SH_WORDS + sh[S_PROLOG]) prolog_ends_on_record = true;
             if (pc + l == at + SH_WORDS + sh[S_PROLOGA]) prolog_a_ends_on_record = true;
+            if (pc + l == at + SH_WORDS + sh[S_EPILOG]) epilog_on_record = true;
             if (pc < at + SH_WORDS + sh[S_PROLOG] && op != I_LOAD && op != I_VLOAD) return bad("prologue holds loads only");
             uint32_t want = LEN_REC;
             switch (op) {
@@ -1614,6 +1738,10 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (srck > 1 || (srck == 0 && !sreg_ok(c))) return bad("row-scalar source");
                     break;
                 }
+                case I_CACC:
+                    if (l != LEN_REC || !reg_ok(a, vr) || bb > R_MIN) return bad("accumulate");
+                    if (sh[S_INNER] == 0 || pc >= at + SH_WORDS + sh[S_EPILOG]) return bad("accumulate outside the per-row part of a reducing segment");
+                    break;
                 case I_NOP:
                     if (l != LEN_REC) return bad("nop");
                     break;
@@ -1622,6 +1750,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             pc += l;
         }
         if (!prolog_ends_on_record || !prolog_a_ends_on_record) return bad("prologue does not end on a record boundary");
+        if (!epilog_on_record) return bad("epilogue does not start on a record boundary");
         at += sw;
     }
     if (at != words) return bad("trailing words after the last segment");
@@ -1737,7 +1866,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
             uint32_t *sh = sg + at;
             sh[S_TBASE] += tbase;
             const uint32_t G = sh[S_GEOM] & 0xFFFF, RP = sh[S_RP] & 0xFFFF;
-            if (sh[S_NCT] == 1 && G <= block && sh[S_NROWS] > 0) {
+            if (sh[S_NCT] == 1 && G <= block && sh[S_NROWS] > 0 && sh[S_INNER] == 0) {
                 const uint32_t rp_new = block / G;
                 if (rp_new > RP && rp_new <= 0xFFFF) {
                     sh[S_RP] = rp_new | ((rp_new * G) << 16);
@@ -1890,6 +2019,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
             if (sh[S_PROLOG] && pc == at + SH_WORDS + sh[S_PROLOG]) o.put("  ; body (once per tile)\n");
             else if (sh[S_PROLOGA] != sh[S_PROLOG] && pc == at + SH_WORDS + sh[S_PROLOGA])
                 o.put("  ; prologue (again whenever the second outer index changes)\n");
+            if (sh[S_INNER] && pc == at + SH_WORDS + sh[S_EPILOG]) o.put("  ; epilogue (after the last of the %u rows of a unit)\n", sh[S_INNER]);
             const uint32_t x = w[pc];
             const uint32_t op = x & 0xFF, l = (x >> 8) & 0xFF, a = (x >> 16) & 0xFF, b = x >> 24;
             char ra[8], rb[8];
@@ -1929,6 +2059,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
                     break;
                 case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
+                case I_CACC: o.put("  %04zu acc.%-4s r%u = first row ? acc : %s(r%u, acc)\n", pc - at - SH_WORDS, RED_NAMES[b], a, RED_NAMES[b], a); break;
                 case I_FMA: {
                     char sc[8] = "", ad[8] = "";
                     if (w[pc + 1]) snprintf(sc, sizeof sc, " * s%u", w[pc + 1] - 1);

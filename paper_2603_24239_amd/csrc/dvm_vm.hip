@@ -808,21 +808,27 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 
         const uint32_t nct = sh[S_NCT];
         if (nct <= 1) tile_cols(gt, sh, 0, G, V);
+        // A segment that reduces along the penultimate axis counts units (outer index, column tile) in M;
+        // the workgroup walks the `inner` rows of a unit one after the other (rin), accumulating in tile
+        // registers, and runs the epilogue records after the last of them.  Other segments: inner = 1.
+        const uint32_t inner = sh[S_INNER] != 0 ? sh[S_INNER] : 1;
+        const uint32_t per_row_end = sh[S_INNER] != 0 ? body + sh[S_EPILOG] : body_end;
         for (uint32_t tile = t_lo; tile < t_hi; ++tile) {
-            {   // tile prologue: where this tile sits, which of its lanes and chunks are valid
-                uint32_t tile_r = tile;
-                if (nct > 1) {          // (a single column tile was placed once, before the loop)
-                    tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
-                    tile_cols(gt, sh, tile - tile_r * nct, G, V);
-                }
-                tile_rows(gt, sh, tile_r, rp, tid, RP, seg_threads);
-            }
+          uint32_t tile_r0 = tile;
+          if (nct > 1) {          // (a single column tile was placed once, before the loop)
+              tile_r0 = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
+              tile_cols(gt, sh, tile - tile_r0 * nct, G, V);
+          }
+          for (uint32_t rin = 0; rin < inner; ++rin) {
+            // where this tile sits, which of its lanes and chunks are valid
+            tile_rows(gt, sh, tile_r0 * inner + rin, rp, tid, RP, seg_threads);
+            const uint32_t this_end = rin + 1 == inner ? body_end : per_row_end;
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
             // (its second part runs again when the second outer index of the tile's first or last row
             // differs from that of the previous tile: an operand pinned there varies with that index only)
             uint32_t first = body;
-            if (tile != t_lo) {
+            if (tile != t_lo || rin != 0) {
                 first = body + sh[S_PROLOG];
                 if (sh[S_PROLOGA] != sh[S_PROLOG]) {
                     const uint32_t m1 = sh[S_M1], sh1 = sh[S_SH1];
@@ -834,7 +840,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             }
             // (the program counter is a byte offset into the code)
             u32x4s nw = fetch4b(code, first * 4);
-            for (uint32_t pcb = first * 4; pcb < body_end * 4;) {
+            for (uint32_t pcb = first * 4; pcb < this_end * 4;) {
                 const u32x4s cw = nw;
                 // (elements are copied to scalars first: bit-casting a vector element directly is miscompiled)
                 const uint32_t w = cw.x, cw1 = cw.y, cw2 = cw.z, cw3 = cw.w;
@@ -949,6 +955,17 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             tile_bins_dispatch<K>(acc, s, b);
                         }
                         break;
+                    case I_CACC:        // the first row of a unit starts the accumulator, the others combine into it
+                        if (rin == 0) {
+                            DVM_WITH_R(a, rr, rr = acc)
+                        } else if (b == R_SUM) {
+                            DVM_WITH_R(a, rr, (tile_bin<K, B_ADD>(rr, acc)))
+                        } else if (b == R_MAX) {
+                            DVM_WITH_R(a, rr, (tile_bin<K, B_MAX>(rr, acc)))
+                        } else {
+                            DVM_WITH_R(a, rr, (tile_bin<K, B_MIN>(rr, acc)))
+                        }
+                        break;
                     case I_SEL:         // every pair of registers gets its own copy of the loop: no tile is copied
                         DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; })))
                         break;
@@ -1010,6 +1027,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         break;
                 }
             }
+          }
         }
         seg += seg_words;
     }

@@ -322,3 +322,46 @@ def test_trailing_row_scalar_multiply_rides_with_the_store(ctx):
                [("y", "f32"), ("z", "f32")])
     txt = B.dvm_encode(ctx, B.Program(again), [B.make_shape((64, 512))]).disasm()
     assert "mul " in txt and not re.search(r"store\s+t\d = acc \*", txt)
+
+
+def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ctx):
+    # [M, size, N]: units of (M index, column tile); the per-row part accumulates, the epilogue stores
+    code = _encode(ctx, "colsum", [(4, 100, 300)])
+    txt = code.disasm()
+    assert re.search(r"acc\.sum\s+r0 = first row \? acc : sum\(r0, acc\)", txt)
+    per_row, epilogue = txt.split("; epilogue (after the last of the 100 rows of a unit)")
+    assert "load" in per_row and "store" not in per_row and "store" in epilogue
+    assert code.out_shapes[0] == (4, 1, 300)
+    info = code.info()
+    assert info.n_tiles == 4 * 2 and info.block == 64       # 4 outer indices x 2 column tiles of 256
+    # wide rows split into column tiles when the outer extent alone cannot fill the machine
+    wide = _encode(ctx, "colsum", [(2000, 8200)])
+    assert wide.out_shapes[0] == (1, 8200) and wide.info().n_tiles > 1
+    # ops on the reduced values run in the epilogue; both accumulators keep a register of their own
+    txt = _encode(ctx, "col_stats", [(3, 50, 256), (256,)]).disasm()
+    per_row, epilogue = txt.split("; epilogue")
+    assert len(re.findall(r"acc\.(sum|max|min)", per_row)) == 3 and "sqrt" in epilogue and "sqrt" not in per_row
+    regs = set(re.findall(r"acc\.\w+\s+r(\d)", per_row))
+    assert len(regs) == 3
+    for m in re.finditer(r"(load|copy)\s+r(\d)", per_row):
+        assert m.group(2) not in regs            # no per-row temporary lands in an accumulator
+    # a full-size output beside the reduction is stored row by row
+    txt = _encode(ctx, "colsum_exp", [(64, 512)]).disasm()
+    per_row, epilogue = txt.split("; epilogue")
+    assert "store" in per_row and "store" in epilogue
+    # an axis of extent 1 reduces to itself: no unit loop
+    txt = _encode(ctx, "colsum", [(7, 1, 128)]).disasm()
+    assert "epilogue" not in txt and "acc.sum" not in txt
+    # what one pass cannot compute is refused with a code
+    from workloads.programs import _p
+    centred = _p("centred", [("x", "f32")], [("s", "csum", ["x"], {}), ("d", "sub", ["x", "s"], {})], [("d", "f32")])
+    both = _p("both_axes", [("x", "f32")], [("s", "csum", ["x"], {}), ("t", "sum", ["s"], {})], [("t", "f32")])
+    for bad, shape in ((centred, (8, 64)), (both, (8, 64)), (W.get_program("colsum"), (8, 64, 1)), (W.get_program("colsum"), (64,))):
+        with pytest.raises(B.DvmError) as e:
+            B.dvm_encode(ctx, B.Program(bad), [B.make_shape(shape)])
+        assert e.value.status in (-5, -3), e.value
+    # stacking keeps the unit geometry of such a part
+    a = _encode(ctx, "colsum", [(4, 100, 300)])
+    b = _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])
+    st = B.dvm_stack([a, b])
+    assert "acc.sum" in st.disasm() and st.info().n_segments == 2

@@ -1,0 +1,95 @@
+"""Parity of reductions along the penultimate axis (Table 1's Sum / Max / Min over [M, size, N] with N > 1)
+against the oracle: element by element, fp32 rtol 1e-4 (the tolerance of programs with a reduction)."""
+from __future__ import annotations
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2603_24239_amd import binding as B
+from workloads import gen
+from workloads import programs as W
+
+from . import harness as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def say(msg):
+    print(f"[case] {msg}", flush=True)
+
+
+def randn(shape, seed, dtype=torch.float32, scale=1.0):
+    g = torch.Generator(device="cpu").manual_seed(gen.BASE_SEED + seed)
+    return (torch.randn(shape, generator=g, dtype=torch.float32) * scale).to(dtype).to(DEV)
+
+
+def check(desc, ins, what):
+    outs, code = H.run_vm(desc, ins)
+    rounded, exact = H.run_oracle(desc, ins)
+    for n, dt in desc.outputs:
+        H.compare(outs[n], rounded[n], exact[n], dt, True, f"{what}:{n}")
+    return outs, code
+
+
+# several units per workgroup, ragged row tails, one and several column tiles, rank 2 to 4, a short reduced axis
+SHAPES = [(3, 37, 300), (5, 7, 33), (1, 1000, 4096), (2, 64, 8200), (513, 1024), (2, 3, 17, 129), (600, 2, 8),
+          (1, 4097, 5), (700, 3, 64)]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_colsum_matches_oracle(shape):
+    say(f"colsum {shape}")
+    x = randn(shape, 7000 + len(shape) + shape[-1])
+    outs, code = check(W.get_program("colsum"), {"x": x}, f"colsum{shape}")
+    assert tuple(outs["s"].shape) == tuple(shape[:-2]) + (1, shape[-1])
+
+
+@pytest.mark.parametrize("shape", [(3, 50, 256), (1, 333, 1030), (64, 9, 40)], ids=lambda s: "x".join(map(str, s)))
+def test_col_stats_epilogue_matches_oracle(shape):
+    say(f"col_stats {shape}")
+    x = randn(shape, 7100 + shape[-1])
+    b = randn((shape[-1],), 7101)
+    check(W.get_program("col_stats"), {"x": x, "b": b}, f"col_stats{shape}")
+
+
+def test_full_size_output_beside_the_reduction():
+    say("colsum_exp (1500, 700)")
+    x = randn((1500, 700), 7200, scale=0.5)
+    check(W.get_program("colsum_exp"), {"x": x}, "colsum_exp")
+
+
+def test_bias_gradient_bf16_at_layer_size():
+    # [tokens, hidden] bf16 -> [1, hidden] fp32, the oracle evaluates it whole
+    say("bias_grad_bf16 (8192, 4096)")
+    dy = randn((8192, 4096), 7300, dtype=torch.bfloat16)
+    check(W.get_program("bias_grad_bf16"), {"dy": dy}, "bias_grad")
+
+
+def test_strided_rows_and_extent_one_axis():
+    say("colsum on every second row of [4, 40, 96]; colsum over an axis of extent 1")
+    base = randn((4, 40, 96), 7400)
+    check(W.get_program("colsum"), {"x": base[:, ::2, :]}, "colsum strided")
+    one = randn((9, 1, 130), 7401)
+    outs, _ = check(W.get_program("colsum"), {"x": one}, "colsum extent 1")
+    assert torch.equal(outs["s"], one)
+
+
+def test_stacked_with_a_row_program():
+    # temporal stacking: the column reduction shares a launch (and a larger workgroup) with an RMSNorm
+    say("stack colsum + c2_rmsnorm")
+    ctx = H.gpu_ctx()
+    x = randn((6, 90, 200), 7500)
+    d = gen.c2_inputs(1, 64, gen.BASE_SEED + 7501, DEV)
+    pa, pb = H.program(W.get_program("colsum")), H.program(W.get_program("c2_rmsnorm"))
+    ca = B.encode_for(ctx, pa, [x])
+    cb = B.encode_for(ctx, pb, [d["x"], d["w"]])
+    s = torch.empty(ca.out_shapes[0], dtype=torch.float32, device=DEV)
+    y = torch.empty(cb.out_shapes[0], dtype=torch.bfloat16, device=DEV)
+    st = B.dvm_stack([ca, cb])
+    B.run_on(ctx, st, [x, s, d["x"], d["w"], y])
+    torch.cuda.synchronize()
+    for desc, ins, out, name in ((W.get_program("colsum"), {"x": x}, s, "s"), (W.get_program("c2_rmsnorm"), d, y, "y")):
+        rounded, exact = H.run_oracle(desc, ins)
+        H.compare(out, rounded[name], exact[name], desc.outputs[0][1], True, f"stacked {desc.name}")

@@ -131,6 +131,20 @@ def _build() -> Dict[str, Program]:
                                     [("t", "muls", ["x"], {"imm": k}), ("o", "add", ["t", "y"], {})],
                                     [("o", "f32")])
 
+    # reductions along the penultimate axis (Table 1's Sum / Max / Min over [M, size, N]): a plain column sum,
+    # a bias gradient (bf16 in, fp32 out), a full-size output beside the reduction, and an epilogue of ops on
+    # the reduced values
+    P["colsum"] = _p("colsum", [("x", "f32")], [("s", "csum", ["x"], {})], [("s", "f32")])
+    P["bias_grad_bf16"] = _p("bias_grad_bf16", [("dy", "bf16")], [("db", "csum", ["dy"], {})], [("db", "f32")])
+    P["colsum_exp"] = _p("colsum_exp", [("x", "f32")],
+                         [("e", "exp", ["x"], {}), ("s", "csum", ["e"], {})], [("e", "f32"), ("s", "f32")])
+    P["col_stats"] = _p(
+        "col_stats", [("x", "f32"), ("b", "f32")],
+        [("q", "square", ["x"], {}), ("s", "csum", ["q"], {}), ("m", "muls", ["s"], {"imm": 0.125}),
+         ("r", "sqrt", ["m"], {}), ("o", "add", ["r", "b"], {}),
+         ("hi", "cmax", ["x"], {}), ("lo", "cmin", ["x"], {}), ("w", "sub", ["hi", "lo"], {})],
+        [("o", "f32"), ("w", "f32")])
+
     # small programs used by pins and unit tests
     P["identity_affine"] = _p("identity_affine", [("x", "f32")],
                               [("t", "muls", ["x"], {"imm": 1.0}), ("y", "adds", ["t"], {"imm": 0.0})],
