@@ -77,7 +77,8 @@ enum : int {
     S_WG0, S_NWG,   // spatial stacking: this segment runs on workgroups [S_WG0, S_WG0 + S_NWG) only (S_NWG 0: on all)
     S_INNER,        // reduction along the penultimate axis: its extent `size` (0: the segment has none).  Then
                     // S_NTILES counts units of work (outer index, column tile); a workgroup visits the `size`
-                    // rows of a unit one after the other, so a tile register can accumulate over them
+                    // rows of a unit S_RP at a time (one row per wave), so a tile register can accumulate over
+                    // them; I_CCOMB combines the waves' registers
     S_EPILOG,       // body words that run for every row of a unit; the records after them (the epilogue) run
                     // after the last row of the unit only (= S_CODESIZE when there is no epilogue)
     SH_WORDS
@@ -110,6 +111,8 @@ enum : uint32_t {
                  // else s = S[word1 - 1]; b = FMA_NO_ADDEND: nothing is added
     I_CACC,      // R[a] = first row of the unit ? ACC : R_b(R[a], ACC): accumulates a reduction along the
                  // penultimate axis (Table 1: Sum / Max / Min over [M, size, N] with N > 1)
+    I_CCOMB,     // epilogue only: combine R[a] over the waves of the workgroup with R_b (each wave accumulated its
+                 // own share of the unit's rows), through LDS; afterwards only the first wave stores
     I_COUNT
 };
 

@@ -1052,8 +1052,11 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     for (int pass = 0; pass < (E.has_cred ? 2 : 1) && !E.err; ++pass) {
     if (pass == 1) {            // the epilogue: values computed from the reductions, once per unit
         E.n_epilog = E.n_ai;
-        E.n_fence = E.n_ai;
         E.in_acc = -1;
+        // each wave of the workgroup accumulated its own share of the rows: combine them first
+        for (int n = 0; n < NN; ++n)
+            if (E.cred_real[n] && E.uses[n] > 0) E.emit(I_CCOMB, (uint8_t)E.reg_of[n], prog->nodes[n].op);
+        E.n_fence = E.n_ai;
     }
     for (int n = 0; n < NN && !E.err; ++n) {
         Node nd = prog->nodes[n];
@@ -1302,13 +1305,24 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if ((uint32_t)K < V) continue;
             const int v = find_variant(K);
             if (v < 0) continue;
-            const int64_t units = cred_outer * cdiv(E.D0 > 0 ? E.D0 : 1, 64 * K);
-            if (pick < 0 || units >= (int64_t)ctx->n_cu * slots_per_cu(VARIANTS[v], 64)) pick = v;
+            // (a workgroup holds up to 16 waves, each taking every RP-th row of the unit)
+            int64_t rp_max = VARIANTS[v].max_threads / 64 < 16 ? VARIANTS[v].max_threads / 64 : 16;
+            if (rp_max > E.Dg[1]) rp_max = E.Dg[1];
+            const int64_t waves = cred_outer * cdiv(E.D0 > 0 ? E.D0 : 1, 64 * K) * rp_max;
+            if (pick < 0 || waves >= (int64_t)ctx->n_cu * slots_per_cu(VARIANTS[v], 64)) pick = v;
         }
         if (pick < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
         vi = pick;
         G = 64;
-        RP = 1;
+        {
+            const Variant &vr = VARIANTS[vi];
+            int64_t rp_max = vr.max_threads / 64 < 16 ? vr.max_threads / 64 : 16;
+            if (rp_max > E.Dg[1]) rp_max = E.Dg[1];
+            const int64_t units = cred_outer * cdiv(E.D0 > 0 ? E.D0 : 1, 64 * vr.K);
+            const int64_t want = cdiv((int64_t)ctx->n_cu * slots_per_cu(vr, 64), units > 0 ? units : 1);
+            RP = (uint32_t)(want < 1 ? 1 : (want > rp_max ? rp_max : want));
+            if (ctx->dbg_rp > 0 && ctx->dbg_rp <= rp_max) RP = (uint32_t)ctx->dbg_rp;
+        }
         nvec = (uint32_t)(VARIANTS[vi].K / V);
         TC = G * nvec * V;
         nct = (uint32_t)cdiv(E.D0 > 0 ? E.D0 : 1, TC);
@@ -1622,7 +1636,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if (sh[S_INNER] == 0 && M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
         }
         if (sh[S_INNER] != 0) {        // units of (outer index, column tile), `size` rows each
-            if (RP != 1 || G != 64) return bad("geometry of a reduction along the penultimate axis");
+            if (RP > 16 || G != 64) return bad("geometry of a reduction along the penultimate axis");
             if (nrows % sh[S_INNER] != 0 || M != (nrows / sh[S_INNER]) * nct) return bad("unit count");
             if (M != 0 && (sh[S_D1] != 0 ? sh[S_D1] != sh[S_INNER] : nrows != sh[S_INNER])) return bad("reduced axis is not the fastest outer dim");
             if (sh[S_PROLOG] != 0) return bad("prologue in a segment that reduces along the penultimate axis");
@@ -1741,6 +1755,10 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                 case I_CACC:
                     if (l != LEN_REC || !reg_ok(a, vr) || bb > R_MIN) return bad("accumulate");
                     if (sh[S_INNER] == 0 || pc >= at + SH_WORDS + sh[S_EPILOG]) return bad("accumulate outside the per-row part of a reducing segment");
+                    break;
+                case I_CCOMB:
+                    if (l != LEN_REC || !reg_ok(a, vr) || bb > R_MIN) return bad("combine");
+                    if (sh[S_INNER] == 0 || pc < at + SH_WORDS + sh[S_EPILOG]) return bad("combine outside the epilogue of a reducing segment");
                     break;
                 case I_NOP:
                     if (l != LEN_REC) return bad("nop");
@@ -2059,6 +2077,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
                     break;
                 case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
+                case I_CCOMB: o.put("  %04zu comb.%-3s r%u = %s of r%u over the workgroup's waves\n", pc - at - SH_WORDS, RED_NAMES[b], a, RED_NAMES[b], a); break;
                 case I_CACC: o.put("  %04zu acc.%-4s r%u = first row ? acc : %s(r%u, acc)\n", pc - at - SH_WORDS, RED_NAMES[b], a, RED_NAMES[b], a); break;
                 case I_FMA: {
                     char sc[8] = "", ad[8] = "";

@@ -668,10 +668,8 @@ DI void tile_cols(Geo &gt, const uint32_t *sh, uint32_t tile_c, uint32_t G, uint
     // rows never mix in a reduction, so only invalid columns inside live chunks need a mask
     gt.ragged = gt.ncols != gt.nact * G;
 }
-DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uint32_t tid, uint32_t RP, uint32_t seg_threads) {
-    const uint32_t nrows = sh[S_NROWS];
-    const uint32_t row = tile_r * RP + rp;
-    gt.rowok = (row < nrows) && (rp < RP) && (tid < seg_threads);
+DI void tile_rows_at(Geo &gt, const uint32_t *sh, uint32_t row, bool ok) {
+    gt.rowok = ok;
     const uint32_t rowc = gt.rowok ? row : 0;
     gt.i1 = rowc; gt.i2 = 0; gt.i3 = 0;
     const uint32_t D1 = sh[S_D1];
@@ -686,6 +684,10 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
             gt.i3 = q2;
         }
     }
+}
+DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uint32_t tid, uint32_t RP, uint32_t seg_threads) {
+    const uint32_t row = tile_r * RP + rp;
+    tile_rows_at(gt, sh, row, (row < sh[S_NROWS]) && (rp < RP) && (tid < seg_threads));
 }
 
 // ------------------------------------------------------------------------------------------
@@ -752,6 +754,8 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
 template <int K, int NR, int MAXT, int WAVES>
 __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES))) dvm_vm_kernel(const KArgs args) {
     __shared__ float red_lds[2][16];
+    // (sized by the launch: 1 KiB per wave of the widest segment that reduces along the penultimate axis, else nothing)
+    extern __shared__ __align__(16) float comb_lds[];
 
     // the register file of one lane: accumulator, tile registers, row-scalar registers
     Tile<K> acc, r0, r1, r2, r3, r4, r5;
@@ -809,20 +813,27 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         const uint32_t nct = sh[S_NCT];
         if (nct <= 1) tile_cols(gt, sh, 0, G, V);
         // A segment that reduces along the penultimate axis counts units (outer index, column tile) in M;
-        // the workgroup walks the `inner` rows of a unit one after the other (rin), accumulating in tile
-        // registers, and runs the epilogue records after the last of them.  Other segments: inner = 1.
-        const uint32_t inner = sh[S_INNER] != 0 ? sh[S_INNER] : 1;
-        const uint32_t per_row_end = sh[S_INNER] != 0 ? body + sh[S_EPILOG] : body_end;
+        // the workgroup walks the `inner` rows of a unit step by step (rin), accumulating in tile registers,
+        // and runs the epilogue records after the last step.  Other segments: one step per tile.
+        // the workgroup walks the rows of a unit RP at a time, one row per wave: n_it steps
+        const uint32_t inner = sh[S_INNER];
+        const uint32_t n_it = inner != 0 ? (inner + RP - 1) / RP : 1;
+        const uint32_t per_row_end = inner != 0 ? body + sh[S_EPILOG] : body_end;
         for (uint32_t tile = t_lo; tile < t_hi; ++tile) {
           uint32_t tile_r0 = tile;
           if (nct > 1) {          // (a single column tile was placed once, before the loop)
               tile_r0 = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
               tile_cols(gt, sh, tile - tile_r0 * nct, G, V);
           }
-          for (uint32_t rin = 0; rin < inner; ++rin) {
+          for (uint32_t rin = 0; rin < n_it; ++rin) {
             // where this tile sits, which of its lanes and chunks are valid
-            tile_rows(gt, sh, tile_r0 * inner + rin, rp, tid, RP, seg_threads);
-            const uint32_t this_end = rin + 1 == inner ? body_end : per_row_end;
+            if (inner != 0) {
+                const uint32_t r = rin * RP + rp;
+                tile_rows_at(gt, sh, tile_r0 * inner + r, (r < inner) && (rp < RP) && (tid < seg_threads));
+            } else {
+                tile_rows(gt, sh, tile_r0, rp, tid, RP, seg_threads);
+            }
+            const uint32_t this_end = rin + 1 == n_it ? body_end : per_row_end;
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
             // (its second part runs again when the second outer index of the tile's first or last row
@@ -955,15 +966,42 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             tile_bins_dispatch<K>(acc, s, b);
                         }
                         break;
-                    case I_CACC:        // the first row of a unit starts the accumulator, the others combine into it
+                    case I_CACC: {      // the first step of a unit starts the accumulator, the others combine into it
+                        // (a wave whose row lies past the end of the unit contributes nothing)
+                        const bool ok = gt.rowok;
                         if (rin == 0) {
-                            DVM_WITH_R(a, rr, rr = acc)
+                            const float ident = b == R_SUM ? 0.0f : (b == R_MAX ? -__builtin_inff() : __builtin_inff());
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? acc.v[I] : ident; }))
                         } else if (b == R_SUM) {
-                            DVM_WITH_R(a, rr, (tile_bin<K, B_ADD>(rr, acc)))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? rr.v[I] + acc.v[I] : rr.v[I]; }))
                         } else if (b == R_MAX) {
-                            DVM_WITH_R(a, rr, (tile_bin<K, B_MAX>(rr, acc)))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? f_max(rr.v[I], acc.v[I]) : rr.v[I]; }))
                         } else {
-                            DVM_WITH_R(a, rr, (tile_bin<K, B_MIN>(rr, acc)))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? f_min(rr.v[I], acc.v[I]) : rr.v[I]; }))
+                        }
+                        break;
+                    }
+                    case I_CCOMB:       // every wave ends up with the combination, taken in wave order; the first wave stores
+                        if (inner != 0 && RP > 1) {
+                            uint32_t lane = tid & 63u;
+                            asm volatile("" : "+v"(lane));      // (keeps the LDS addresses out of the registers that live across the loop)
+                            DVM_WITH_R(a, rr, sfor<K / 4>([&]<int Q>() LI {
+                                if (wave < RP) {
+                                    float *mine = &comb_lds[(wave * 64u + lane) * 4u];
+                                    mine[0] = rr.v[4 * Q]; mine[1] = rr.v[4 * Q + 1]; mine[2] = rr.v[4 * Q + 2]; mine[3] = rr.v[4 * Q + 3];
+                                }
+                                __syncthreads();
+                                float c0 = comb_lds[lane * 4u], c1 = comb_lds[lane * 4u + 1], c2 = comb_lds[lane * 4u + 2], c3 = comb_lds[lane * 4u + 3];
+                                for (uint32_t o = 1; o < RP; ++o) {
+                                    const float *p = &comb_lds[(o * 64u + lane) * 4u];
+                                    if (b == R_SUM) { c0 += p[0]; c1 += p[1]; c2 += p[2]; c3 += p[3]; }
+                                    else if (b == R_MAX) { c0 = f_max(c0, p[0]); c1 = f_max(c1, p[1]); c2 = f_max(c2, p[2]); c3 = f_max(c3, p[3]); }
+                                    else { c0 = f_min(c0, p[0]); c1 = f_min(c1, p[1]); c2 = f_min(c2, p[2]); c3 = f_min(c3, p[3]); }
+                                }
+                                __syncthreads();
+                                rr.v[4 * Q] = c0; rr.v[4 * Q + 1] = c1; rr.v[4 * Q + 2] = c2; rr.v[4 * Q + 3] = c3;
+                            }))
+                            gt.rowok = (rp == 0) && (tid < seg_threads);
                         }
                         break;
                     case I_SEL:         // every pair of registers gets its own copy of the loop: no tile is copied
@@ -1041,7 +1079,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 // which defines the kernel and a launcher; the translation unit without those macros holds the
 // host side.  The build script reads this list.
 #define DVM_VARIANT_LIST(X) \
-    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 4) X(8, 6, 512, 4) \
+    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 6) X(8, 6, 512, 4) \
     X(16, 2, 1024, 4) X(16, 4, 512, 3) X(16, 6, 512, 2) X(32, 2, 256, 2) X(32, 4, 256, 2)
 
 #define DVM_LAUNCHER_NAME_(K, NR) dvm_vm_launch_##K##_##NR
@@ -1051,19 +1089,19 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 
 #ifdef DVM_VARIANT_K
 // ---- one interpreter variant: kernel instantiation + launcher ---------------------------------
-extern "C" void DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES>), dim3(grid), dim3(block), 0,
+extern "C" void DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES>), dim3(grid), dim3(block), lds_bytes,
                        (hipStream_t)stream, *(const KArgs *)kargs);
 }
 #else
 // ---- host side: dvm_run ---------------------------------------------------------------------
-#define X(K, NR, MAXT, W) extern "C" void DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, void *, const void *);
+#define X(K, NR, MAXT, W) extern "C" void DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
 DVM_VARIANT_LIST(X)
 #undef X
 
 namespace {
 
-typedef void (*vm_launch_t)(unsigned, unsigned, void *, const void *);
+typedef void (*vm_launch_t)(unsigned, unsigned, unsigned, void *, const void *);
 struct VariantEntry { int K, NR; vm_launch_t launch; };
 #define X(K, NR, MAXT, W) {K, NR, DVM_LAUNCHER_NAME(K, NR)},
 const VariantEntry g_variants[] = {DVM_VARIANT_LIST(X)};
@@ -1120,7 +1158,16 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
         if (v.K == K && v.NR == NR) launch = v.launch;
     if (!launch) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
-    launch(grid, block, hip_stream, &ka);
+    // LDS for the combination across waves of segments that reduce along the penultimate axis:
+    // four floats per lane of every participating wave
+    uint32_t lds_bytes = 0;
+    for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
+        const uint32_t *sh = w + at;
+        const uint32_t rp = sh[S_RP] & 0xFFFF;
+        if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
+        at += sh[S_WORDS];
+    }
+    launch(grid, block, lds_bytes, hip_stream, &ka);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;

@@ -333,7 +333,7 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
     assert "load" in per_row and "store" not in per_row and "store" in epilogue
     assert code.out_shapes[0] == (4, 1, 300)
     info = code.info()
-    assert info.n_tiles == 4 * 2 and info.block == 64       # 4 outer indices x 2 column tiles of 256
+    assert info.n_tiles == 4 * 2 and info.block == 64 * 16  # 4 outer indices x 2 column tiles of 256; 16 waves share a unit
     # wide rows split into column tiles when the outer extent alone cannot fill the machine
     wide = _encode(ctx, "colsum", [(2000, 8200)])
     assert wide.out_shapes[0] == (1, 8200) and wide.info().n_tiles > 1
@@ -361,7 +361,12 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
             B.dvm_encode(ctx, B.Program(bad), [B.make_shape(shape)])
         assert e.value.status in (-5, -3), e.value
     # stacking keeps the unit geometry of such a part
-    a = _encode(ctx, "colsum", [(4, 100, 300)])
-    b = _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])
+    # (its 16-wave workgroup needs a variant that allows 1024 threads: none with 32 elements per lane does)
+    small = B.Context(-1)
+    small.set_limits(16, 6)
+    a = _encode(small, "colsum", [(4, 100, 300)])
+    b = _encode(small, "c2_rmsnorm", [(100, 4096), (4096,)])
     st = B.dvm_stack([a, b])
-    assert "acc.sum" in st.disasm() and st.info().n_segments == 2
+    assert "acc.sum" in st.disasm() and st.info().n_segments == 2 and st.info().block == 1024
+    with pytest.raises(B.DvmError):
+        B.dvm_stack([a, _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])])

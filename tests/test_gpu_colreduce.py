@@ -79,7 +79,10 @@ def test_strided_rows_and_extent_one_axis():
 def test_stacked_with_a_row_program():
     # temporal stacking: the column reduction shares a launch (and a larger workgroup) with an RMSNorm
     say("stack colsum + c2_rmsnorm")
-    ctx = H.gpu_ctx()
+    # (a context limited to 16 elements per lane: the 16-wave workgroup of the reduction needs a variant
+    # that allows 1024 threads)
+    ctx = B.Context(torch.cuda.current_device())
+    ctx.set_limits(16, 6)
     x = randn((6, 90, 200), 7500)
     d = gen.c2_inputs(1, 64, gen.BASE_SEED + 7501, DEV)
     pa, pb = H.program(W.get_program("colsum")), H.program(W.get_program("c2_rmsnorm"))
@@ -93,3 +96,19 @@ def test_stacked_with_a_row_program():
     for desc, ins, out, name in ((W.get_program("colsum"), {"x": x}, s, "s"), (W.get_program("c2_rmsnorm"), d, y, "y")):
         rounded, exact = H.run_oracle(desc, ins)
         H.compare(out, rounded[name], exact[name], desc.outputs[0][1], True, f"stacked {desc.name}")
+
+
+@pytest.mark.parametrize("waves", [1, 3, 16])
+def test_any_number_of_waves_per_unit(waves, monkeypatch):
+    # the planner picks the waves that share a unit; the debug override walks the other settings,
+    # among them one wave (no combination step) and a count that does not divide the reduced extent
+    say(f"col_stats with {waves} wave(s) per unit")
+    monkeypatch.setenv("DVM_DEBUG_RP", str(waves))
+    ctx = B.Context(torch.cuda.current_device())
+    desc = W.get_program("col_stats")
+    ins = {"x": randn((5, 37, 300), 7600 + waves), "b": randn((300,), 7601)}
+    outs, code = H.run_vm(desc, ins, ctx=ctx)
+    assert code.info().block == 64 * waves
+    rounded, exact = H.run_oracle(desc, ins)
+    for n, dt in desc.outputs:
+        H.compare(outs[n], rounded[n], exact[n], dt, True, f"col_stats waves={waves}:{n}")
