@@ -61,8 +61,9 @@ typedef enum dvm_status {
 
 typedef enum dvm_dtype { DVM_F32 = 0, DVM_BF16 = 1 } dvm_dtype;
 
-/* Operator vocabulary of the program builder.  Names follow Table 1 of the paper; reductions act
- * on the last axis and keep it with extent 1 (Table 1's Sum/Max/Min with N = 1). */
+/* Operator vocabulary of the program builder.  Names follow Table 1 of the paper; DVM_OP_SUM/RMAX/RMIN
+ * (and MEAN, MEANSQ) act on the last axis and keep it with extent 1 (Table 1's Sum/Max/Min with N = 1),
+ * DVM_OP_CSUM/CMAX/CMIN on the penultimate axis (Table 1's general form, N > 1). */
 typedef enum dvm_opcode {
     /* unary */
     DVM_OP_COPY = 1, DVM_OP_SQRT, DVM_OP_ABS, DVM_OP_LOG, DVM_OP_EXP, DVM_OP_ROUND, DVM_OP_FLOOR,

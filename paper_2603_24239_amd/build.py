@@ -26,10 +26,11 @@ DEVICE = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-pa
           "-mllvm", "-simplifycfg-sink-common=false"]
 
 
-def variants():
-    """(K, NR, largest workgroup, waves per SIMD) of every interpreter variant, read from the device source."""
+def variants(which: str = "DVM_VARIANT_LIST"):
+    """(K, NR, largest workgroup, waves per SIMD) of every interpreter variant, read from the device source
+    (`DVM_CRED_VARIANT_LIST`: those also built as the instantiation that runs reductions along the penultimate axis)."""
     src = open(os.path.join(CSRC, "dvm_vm.hip")).read()
-    body = src[src.index("#define DVM_VARIANT_LIST(X)"):]
+    body = src[src.index(f"#define {which}(X)"):]
     body = body[: body.index("\n\n")]
     out = [tuple(int(v) for v in m) for m in re.findall(r"X\((\d+),\s*(\d+),\s*(\d+),\s*(\d+)\)", body)]
     if not out:
@@ -47,6 +48,10 @@ def build(verbose: bool = True) -> str:
     for k, nr, maxt, waves in variants():
         defs = [f"-DDVM_VARIANT_K={k}", f"-DDVM_VARIANT_NR={nr}", f"-DDVM_VARIANT_MAXT={maxt}", f"-DDVM_VARIANT_WAVES={waves}"]
         jobs.append(([hipcc, *COMMON, *DEVICE, *defs, "-c", vm], os.path.join(CSRC, f"dvm_vm_k{k}_r{nr}.o")))
+    for k, nr, maxt, waves in variants("DVM_CRED_VARIANT_LIST"):
+        defs = [f"-DDVM_VARIANT_K={k}", f"-DDVM_VARIANT_NR={nr}", f"-DDVM_VARIANT_MAXT={maxt}", f"-DDVM_VARIANT_WAVES={waves}",
+                "-DDVM_VARIANT_CRED=1"]
+        jobs.append(([hipcc, *COMMON, *DEVICE, *defs, "-c", vm], os.path.join(CSRC, f"dvm_vm_c_k{k}_r{nr}.o")))
 
     def run(job):
         cmd, obj = job

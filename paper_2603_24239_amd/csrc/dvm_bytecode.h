@@ -158,12 +158,13 @@ inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
 // interpreter variants compiled into the library: elements per lane per tile register (K),
 // number of tile registers (NR), largest workgroup, and resident waves per SIMD (from the
 // compiled kernels' register use; 4 SIMDs per compute unit).
-struct Variant { int K, NR, max_threads, waves_per_simd; };
+// `cred`: also built as the instantiation that runs reductions along the penultimate axis.
+struct Variant { int K, NR, max_threads, waves_per_simd; bool cred; };
 constexpr Variant VARIANTS[] = {
-    { 4, 2, 1024, 8}, { 4, 6, 1024, 7},
-    { 8, 2, 1024, 6}, { 8, 6,  512, 4},
-    {16, 2, 1024, 4}, {16, 4,  512, 3}, {16, 6,  512, 2},
-    {32, 2,  256, 2}, {32, 4,  256, 2},
+    { 4, 2, 1024, 8, true}, { 4, 6, 1024, 7, true},
+    { 8, 2, 1024, 6, true}, { 8, 6,  512, 4, true},
+    {16, 2, 1024, 4, false}, {16, 4,  512, 3, false}, {16, 6,  512, 2, true},
+    {32, 2,  256, 2, true}, {32, 4,  256, 2, true},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 

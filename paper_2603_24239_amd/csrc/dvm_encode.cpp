@@ -1278,7 +1278,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     auto find_variant = [&](int K) {
         int best = -1;
         for (int i = 0; i < N_VARIANTS; ++i)
-            if (VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && VARIANTS[i].NR <= ctx->max_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
+            if ((VARIANTS[i].cred || !E.has_cred) && VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && VARIANTS[i].NR <= ctx->max_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
         return best;
     };
     auto slots_per_cu = [&](const Variant &v, uint32_t threads) {
@@ -1636,6 +1636,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if (sh[S_INNER] == 0 && M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
         }
         if (sh[S_INNER] != 0) {        // units of (outer index, column tile), `size` rows each
+            if (!vr->cred) return bad("interpreter variant does not run reductions along the penultimate axis");
             if (RP > 16 || G != 64) return bad("geometry of a reduction along the penultimate axis");
             if (nrows % sh[S_INNER] != 0 || M != (nrows / sh[S_INNER]) * nct) return bad("unit count");
             if (M != 0 && (sh[S_D1] != 0 ? sh[S_D1] != sh[S_INNER] : nrows != sh[S_INNER])) return bad("reduced axis is not the fastest outer dim");
@@ -1821,6 +1822,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
     if (!codes || !lens || !len || n < 1) return dvm_set_error(DVM_E_ARGS, "dvm_stack: bad argument");
     size_t seg_words = 0;
     uint32_t ntens = 0, nseg = 0, block = 0, K = 0, NR = 0;
+    bool need_cred = false;
     uint64_t grid = 0;
     for (int i = 0; i < n; ++i) {
         int st = dvm_validate(codes[i], lens[i]);
@@ -1833,6 +1835,10 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
         if (w[PH_BLOCK] > block) block = w[PH_BLOCK];
         if ((w[PH_VARIANT] & 0xFF) > K) K = w[PH_VARIANT] & 0xFF;
         if (((w[PH_VARIANT] >> 8) & 0xFF) > NR) NR = (w[PH_VARIANT] >> 8) & 0xFF;
+        for (uint32_t s = 0, at = off; s < w[PH_NSEG]; ++s) {      // (a part that reduces along the penultimate axis)
+            need_cred |= w[at + S_INNER] != 0;
+            at += w[at + S_WORDS];
+        }
         // every part was planned to fill the machine with workgroups of its own size: what carries
         // over to the common workgroup size is the number of resident waves, not of workgroups
         const uint64_t part_waves = (uint64_t)w[PH_GRID] * ((w[PH_BLOCK] + 63) / 64);
@@ -1847,7 +1853,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
     const Variant *vr = nullptr;
     for (int i = 0; i < N_VARIANTS; ++i) {
         const Variant &v = VARIANTS[i];
-        if ((uint32_t)v.K >= K && (uint32_t)v.NR >= NR && (uint32_t)v.max_threads >= block) {
+        if ((uint32_t)v.K >= K && (uint32_t)v.NR >= NR && (uint32_t)v.max_threads >= block && (v.cred || !need_cred)) {
             if (!vr || v.K < vr->K || (v.K == vr->K && v.NR < vr->NR)) vr = &v;
         }
     }

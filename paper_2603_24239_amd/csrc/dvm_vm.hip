@@ -751,7 +751,11 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
         g.colbase = (uint64_t)cb_lo | ((uint64_t)cb_hi << 32);                                                \
     }
 
-template <int K, int NR, int MAXT, int WAVES>
+// CRED: the instantiation that also runs segments which reduce along the penultimate axis (unit loop,
+// accumulate and combine records).  Programs without such a segment run the plain instantiation, whose
+// tile loop carries none of that bookkeeping (it costs scalar registers the interpreter loop has none
+// to spare of: 5-10 % on short tiles).
+template <int K, int NR, int MAXT, int WAVES, bool CRED>
 __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES))) dvm_vm_kernel(const KArgs args) {
     __shared__ float red_lds[2][16];
     // (sized by the launch: 1 KiB per wave of the widest segment that reduces along the penultimate axis, else nothing)
@@ -813,40 +817,49 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         const uint32_t nct = sh[S_NCT];
         if (nct <= 1) tile_cols(gt, sh, 0, G, V);
         // A segment that reduces along the penultimate axis counts units (outer index, column tile) in M;
-        // the workgroup walks the `inner` rows of a unit step by step (rin), accumulating in tile registers,
-        // and runs the epilogue records after the last step.  Other segments: one step per tile.
-        // the workgroup walks the rows of a unit RP at a time, one row per wave: n_it steps
-        const uint32_t inner = sh[S_INNER];
-        const uint32_t n_it = inner != 0 ? (inner + RP - 1) / RP : 1;
-        const uint32_t per_row_end = inner != 0 ? body + sh[S_EPILOG] : body_end;
-        for (uint32_t tile = t_lo; tile < t_hi; ++tile) {
-          uint32_t tile_r0 = tile;
-          if (nct > 1) {          // (a single column tile was placed once, before the loop)
-              tile_r0 = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
-              tile_cols(gt, sh, tile - tile_r0 * nct, G, V);
-          }
-          for (uint32_t rin = 0; rin < n_it; ++rin) {
-            // where this tile sits, which of its lanes and chunks are valid
-            if (inner != 0) {
-                const uint32_t r = rin * RP + rp;
-                tile_rows_at(gt, sh, tile_r0 * inner + r, (r < inner) && (rp < RP) && (tid < seg_threads));
+        // the workgroup walks the `inner` rows of a unit RP at a time, one row per wave and step (rin),
+        // accumulating in tile registers, and runs the epilogue records after the last step.  Other
+        // segments: one step per tile.
+        uint32_t rin = 0;
+        for (uint32_t tile = t_lo; tile < t_hi;) {
+            const uint32_t *shl = sh;
+            uint32_t this_end = body_end;
+            if constexpr (CRED) {
+                const uint32_t inner = shl[S_INNER];
+                uint32_t tile_r0 = tile;
+                if (nct > 1) {          // (a single column tile was placed once, before the loop)
+                    tile_r0 = sdiv_u(tile, shl[S_NCTM], shl[S_NCTSH]);
+                    if (rin == 0) tile_cols(gt, shl, tile - tile_r0 * nct, G, V);      // the steps of a unit share its columns
+                }
+                if (inner != 0) {
+                    const uint32_t r = rin * RP + rp;
+                    tile_rows_at(gt, shl, tile_r0 * inner + r, (r < inner) && (rp < RP) && (tid < seg_threads));
+                    if ((rin + 1) * RP < inner) this_end = body + shl[S_EPILOG];
+                } else {
+                    tile_rows(gt, shl, tile_r0, rp, tid, RP, seg_threads);
+                }
             } else {
-                tile_rows(gt, sh, tile_r0, rp, tid, RP, seg_threads);
+                // tile prologue: where this tile sits, which of its lanes and chunks are valid
+                uint32_t tile_r = tile;
+                if (nct > 1) {          // (a single column tile was placed once, before the loop)
+                    tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
+                    tile_cols(gt, sh, tile - tile_r * nct, G, V);
+                }
+                tile_rows(gt, sh, tile_r, rp, tid, RP, seg_threads);
             }
-            const uint32_t this_end = rin + 1 == n_it ? body_end : per_row_end;
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
             // (its second part runs again when the second outer index of the tile's first or last row
             // differs from that of the previous tile: an operand pinned there varies with that index only)
             uint32_t first = body;
             if (tile != t_lo || rin != 0) {
-                first = body + sh[S_PROLOG];
-                if (sh[S_PROLOGA] != sh[S_PROLOG]) {
-                    const uint32_t m1 = sh[S_M1], sh1 = sh[S_SH1];
+                first = body + shl[S_PROLOG];
+                if (shl[S_PROLOGA] != shl[S_PROLOG]) {
+                    const uint32_t m1 = shl[S_M1], sh1 = shl[S_SH1];
                     const uint32_t ra = tile * RP;          // prologues exist in row mode only: tile = row tile
                     const bool crossed = sdiv_u(ra, m1, sh1) != sdiv_u(ra - RP, m1, sh1) ||
                                          sdiv_u(ra + RP - 1, m1, sh1) != sdiv_u(ra - 1, m1, sh1);
-                    if (crossed) first = body + sh[S_PROLOGA];
+                    if (crossed) first = body + shl[S_PROLOGA];
                 }
             }
             // (the program counter is a byte offset into the code)
@@ -966,7 +979,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             tile_bins_dispatch<K>(acc, s, b);
                         }
                         break;
-                    case I_CACC: {      // the first step of a unit starts the accumulator, the others combine into it
+                    case I_CACC: if constexpr (CRED) {      // the first step of a unit starts the accumulator, the others combine into it
                         // (a wave whose row lies past the end of the unit contributes nothing)
                         const bool ok = gt.rowok;
                         if (rin == 0) {
@@ -979,10 +992,10 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         } else {
                             DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? f_min(rr.v[I], acc.v[I]) : rr.v[I]; }))
                         }
-                        break;
                     }
+                        break;
                     case I_CCOMB:       // every wave ends up with the combination, taken in wave order; the first wave stores
-                        if (inner != 0 && RP > 1) {
+                        if constexpr (CRED) if (sh[S_INNER] != 0 && RP > 1) {
                             uint32_t lane = tid & 63u;
                             asm volatile("" : "+v"(lane));      // (keeps the LDS addresses out of the registers that live across the loop)
                             DVM_WITH_R(a, rr, sfor<K / 4>([&]<int Q>() LI {
@@ -1065,7 +1078,12 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         break;
                 }
             }
-          }
+            if constexpr (CRED) {   // next step of this unit, or the next tile
+                const uint32_t inner = sh[S_INNER];
+                if (inner == 0 || (rin + 1) * RP >= inner) { rin = 0; ++tile; } else { ++rin; }
+            } else {
+                ++tile;
+            }
         }
         seg += seg_words;
     }
@@ -1082,21 +1100,35 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
     X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 6) X(8, 6, 512, 4) \
     X(16, 2, 1024, 4) X(16, 4, 512, 3) X(16, 6, 512, 2) X(32, 2, 256, 2) X(32, 4, 256, 2)
 
+// (the variants also built as the instantiation that runs reductions along the penultimate axis)
+#define DVM_CRED_VARIANT_LIST(X) \
+    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 6) X(8, 6, 512, 4) X(16, 6, 512, 2) X(32, 2, 256, 2) X(32, 4, 256, 2)
+
 #define DVM_LAUNCHER_NAME_(K, NR) dvm_vm_launch_##K##_##NR
 #define DVM_LAUNCHER_NAME(K, NR) DVM_LAUNCHER_NAME_(K, NR)
+#define DVM_CRED_LAUNCHER_NAME_(K, NR) dvm_vm_launch_c_##K##_##NR
+#define DVM_CRED_LAUNCHER_NAME(K, NR) DVM_CRED_LAUNCHER_NAME_(K, NR)
 
 }  // namespace
 
 #ifdef DVM_VARIANT_K
 // ---- one interpreter variant: kernel instantiation + launcher ---------------------------------
+#ifdef DVM_VARIANT_CRED
+extern "C" void DVM_CRED_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, true>), dim3(grid), dim3(block), lds_bytes,
+#else
 extern "C" void DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES>), dim3(grid), dim3(block), lds_bytes,
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false>), dim3(grid), dim3(block), lds_bytes,
+#endif
                        (hipStream_t)stream, *(const KArgs *)kargs);
 }
 #else
 // ---- host side: dvm_run ---------------------------------------------------------------------
 #define X(K, NR, MAXT, W) extern "C" void DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
 DVM_VARIANT_LIST(X)
+#undef X
+#define X(K, NR, MAXT, W) extern "C" void DVM_CRED_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
+DVM_CRED_VARIANT_LIST(X)
 #undef X
 
 namespace {
@@ -1105,6 +1137,9 @@ typedef void (*vm_launch_t)(unsigned, unsigned, unsigned, void *, const void *);
 struct VariantEntry { int K, NR; vm_launch_t launch; };
 #define X(K, NR, MAXT, W) {K, NR, DVM_LAUNCHER_NAME(K, NR)},
 const VariantEntry g_variants[] = {DVM_VARIANT_LIST(X)};
+#undef X
+#define X(K, NR, MAXT, W) {K, NR, DVM_CRED_LAUNCHER_NAME(K, NR)},
+const VariantEntry g_cred_variants[] = {DVM_CRED_VARIANT_LIST(X)};
 #undef X
 
 thread_local int t_last_hip_error = 0;
@@ -1153,20 +1188,27 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     ka.pad = 0;
 
     const int K = (int)(w[PH_VARIANT] & 0xFF), NR = (int)((w[PH_VARIANT] >> 8) & 0xFF);
-    vm_launch_t launch = nullptr;
-    for (const VariantEntry &v : g_variants)
-        if (v.K == K && v.NR == NR) launch = v.launch;
-    if (!launch) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
-    // LDS for the combination across waves of segments that reduce along the penultimate axis:
-    // four floats per lane of every participating wave
+    // A segment that reduces along the penultimate axis needs the instantiation that runs such segments,
+    // and LDS for the combination across waves: four floats per lane of every participating wave
     uint32_t lds_bytes = 0;
+    bool cred = false;
     for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
         const uint32_t *sh = w + at;
         const uint32_t rp = sh[S_RP] & 0xFFFF;
+        cred |= sh[S_INNER] != 0;
         if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
         at += sh[S_WORDS];
     }
+    vm_launch_t launch = nullptr;
+    if (cred) {
+        for (const VariantEntry &v : g_cred_variants)
+            if (v.K == K && v.NR == NR) launch = v.launch;
+    } else {
+        for (const VariantEntry &v : g_variants)
+            if (v.K == K && v.NR == NR) launch = v.launch;
+    }
+    if (!launch) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
     launch(grid, block, lds_bytes, hip_stream, &ka);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {

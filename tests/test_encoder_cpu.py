@@ -360,13 +360,14 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
         with pytest.raises(B.DvmError) as e:
             B.dvm_encode(ctx, B.Program(bad), [B.make_shape(shape)])
         assert e.value.status in (-5, -3), e.value
-    # stacking keeps the unit geometry of such a part
-    # (its 16-wave workgroup needs a variant that allows 1024 threads: none with 32 elements per lane does)
+    # stacking keeps the unit geometry of such a part; the launch then runs the interpreter instantiation
+    # that knows such segments, which exists for the variants with the most tile registers
     small = B.Context(-1)
     small.set_limits(16, 6)
-    a = _encode(small, "colsum", [(4, 100, 300)])
+    a = _encode(small, "colsum", [(8000, 5, 200)])        # enough units: one wave each
     b = _encode(small, "c2_rmsnorm", [(100, 4096), (4096,)])
     st = B.dvm_stack([a, b])
-    assert "acc.sum" in st.disasm() and st.info().n_segments == 2 and st.info().block == 1024
+    assert "acc.sum" in st.disasm() and st.info().n_segments == 2 and st.info().variant_nr == 6
+    # a 16-wave workgroup fits no variant that also holds a 32-element-per-lane part
     with pytest.raises(B.DvmError):
-        B.dvm_stack([a, _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])])
+        B.dvm_stack([_encode(ctx, "colsum", [(4, 100, 300)]), _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])])
