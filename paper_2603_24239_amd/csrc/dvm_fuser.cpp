@@ -216,11 +216,15 @@ extern "C" int dvm_fuser_op(dvm_fuser *f, int opcode, const int *args, int n_arg
     if (out_dtype != DVM_F32 && out_dtype != DVM_BF16) return dvm_set_error(DVM_E_DTYPE, "dvm_fuser_op: dtype");
     for (int a = 0; a < n_args; ++a)
         if (!valid_value(f, args[a])) return dvm_set_error(DVM_E_ARGS, "dvm_fuser_op: unknown value");
-    // shape of the result: broadcast of the arguments; a reduction keeps the last axis with extent 1
+    // shape of the result: broadcast of the arguments; a reduction keeps its axis with extent 1
     dvm_shape s = f->vals[args[0]].shape;
     for (int a = 1; a < n_args; ++a)
         if (!broadcast_into(s, f->vals[args[a]].shape)) return dvm_set_error(DVM_E_SHAPE, "dvm_fuser_op: operands do not broadcast together");
     if (is_reduction(opcode) && s.rank > 0) s.dim[s.rank - 1] = 1;
+    if (opcode >= DVM_OP_CSUM && opcode <= DVM_OP_CMIN) {       // along the penultimate axis
+        if (s.rank < 2) return dvm_set_error(DVM_E_RANK, "dvm_fuser_op: a reduction along the penultimate axis needs rank >= 2");
+        s.dim[s.rank - 2] = 1;
+    }
     {
         int64_t dims[DVM_MAX_RANK];
         for (int k = 0; k < s.rank; ++k) dims[k] = s.dim[k];

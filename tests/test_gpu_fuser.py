@@ -99,3 +99,32 @@ def test_buffers_of_different_shapes_run_in_order():
     assert torch.allclose(ea, torch.tanh(a), atol=1e-6)
     assert torch.allclose(eb, torch.sigmoid(b), atol=1e-6)
     assert torch.allclose(sa, torch.tanh(a) * a, atol=1e-6)
+
+
+def test_reduction_along_the_penultimate_axis_joins_the_buffer():
+    # exp, column sum and the log of the sums arrive one by one and run as one launch; a full-size op on
+    # the reduced value cannot join that launch's program and runs after it
+    say("fuser: exp -> csum -> log, then x - logsumexp")
+    f = _fuser()
+    x = gen.randn((6, 50, 300), 2100, DEV)
+    e = torch.empty_like(x)
+    s_ = torch.empty((6, 1, 300), dtype=torch.float32, device=DEV)
+    l = torch.full((6, 1, 300), float("nan"), dtype=torch.float32, device=DEV)
+    d = torch.full_like(x, float("nan"))
+    vx = f.tensor(x.data_ptr(), "f32", B.shape_of_tensor(x))
+    ve = f.op("exp", [vx], "f32", e.data_ptr())
+    vs = f.op("csum", [ve], "f32", s_.data_ptr())
+    vl = f.op("log", [vs], "f32", l.data_ptr())
+    f.release(ve)
+    f.release(vs)
+    vd = f.op("sub", [vx, vl], "f32", d.data_ptr())
+    f.flush()
+    torch.cuda.synchronize()
+    st = f.stats()
+    assert st["ops"] == 4 and st["launches"] >= 2, st
+    want_l = np.log(np.exp(H.to_np64(x)).sum(axis=-2, keepdims=True))
+    H.compare(l, want_l.astype(np.float32).astype(np.float64), want_l, "f32", True, "fuser logsumexp over columns")
+    want_d = H.to_np64(x) - want_l
+    H.compare(d, want_d.astype(np.float32).astype(np.float64), want_d, "f32", True, "fuser x - logsumexp")
+    for v in (vx, vl, vd):
+        f.release(v)
