@@ -112,3 +112,39 @@ def test_any_number_of_waves_per_unit(waves, monkeypatch):
     rounded, exact = H.run_oracle(desc, ins)
     for n, dt in desc.outputs:
         H.compare(outs[n], rounded[n], exact[n], dt, True, f"col_stats waves={waves}:{n}")
+
+
+def _prog(name, inputs, ops, outputs):
+    from workloads.programs import _p
+    return _p(name, inputs, ops, outputs)
+
+
+def test_broadcast_operands_before_and_after_the_reduction():
+    # a weight per reduced row ([size, 1]: a row value in the per-row part), a bias per column added before the
+    # reduction, and a scale per outer index ([M, 1, 1]: a row value in the epilogue)
+    say("weighted column sum with bias and per-index scale, fp32 [5, 41, 700]")
+    desc = _prog("weighted_colsum", [("x", "f32"), ("w", "f32"), ("b", "f32"), ("g", "f32")],
+                 [("t", "add", ["x", "b"], {}), ("u", "mul", ["t", "w"], {}), ("s", "csum", ["u"], {}),
+                  ("y", "mul", ["s", "g"], {})], [("y", "f32")])
+    ins = {"x": randn((5, 41, 700), 7700), "w": randn((41, 1), 7701), "b": randn((700,), 7702), "g": randn((5, 1, 1), 7703)}
+    check(desc, ins, "weighted_colsum")
+
+
+@pytest.mark.parametrize("shape", [(3, 29, 520), (1, 257, 72), (40, 6, 4096)], ids=lambda s: "x".join(map(str, s)))
+def test_bf16_storage(shape):
+    # bf16 in and out (chunks of eight elements): max and min are exact, the sum is rounded once at the output
+    say(f"bf16 column max / min / sum {shape}")
+    desc = _prog("col_bf16", [("x", "bf16")],
+                 [("hi", "cmax", ["x"], {}), ("lo", "cmin", ["x"], {}), ("s", "csum", ["x"], {})],
+                 [("hi", "bf16"), ("lo", "bf16"), ("s", "bf16")])
+    x = randn(shape, 7800 + shape[-1], dtype=torch.bfloat16)
+    outs, _ = check(desc, {"x": x}, f"col_bf16{shape}")
+    assert torch.equal(outs["hi"], x.max(dim=-2, keepdim=True).values)
+    assert torch.equal(outs["lo"], x.min(dim=-2, keepdim=True).values)
+
+
+def test_empty_outer_extent_launches_nothing():
+    say("colsum [0, 5, 7]")
+    x = torch.empty((0, 5, 7), dtype=torch.float32, device=DEV)
+    outs, code = H.run_vm(W.get_program("colsum"), {"x": x})
+    assert tuple(outs["s"].shape) == (0, 1, 7) and code.info().n_tiles == 0
