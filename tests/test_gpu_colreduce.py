@@ -148,3 +148,30 @@ def test_empty_outer_extent_launches_nothing():
     x = torch.empty((0, 5, 7), dtype=torch.float32, device=DEV)
     outs, code = H.run_vm(W.get_program("colsum"), {"x": x})
     assert tuple(outs["s"].shape) == (0, 1, 7) and code.info().n_tiles == 0
+
+
+def test_stacked_under_a_larger_workgroup(monkeypatch):
+    # four waves share a unit; the stacked launch runs sixteen waves per workgroup (a softmax over rows of 8192
+    # elements at eight elements per lane): the twelve waves outside the reduction's workgroup hold no rows but
+    # take part in its combination step's synchronisation
+    say("stack colsum (4 waves per unit) + softmax_f32 rows of 8192 (1024 threads)")
+    monkeypatch.setenv("DVM_DEBUG_RP", "4")
+    ctx = B.Context(torch.cuda.current_device())
+    ctx.set_limits(8, 6)
+    x = randn((12, 70, 520), 7900)
+    z = randn((24, 8192), 7901)
+    pa, pb = H.program(W.get_program("colsum")), H.program(W.get_program("softmax_f32"))
+    ca = B.encode_for(ctx, pa, [x])
+    cb = B.encode_for(ctx, pb, [z])
+    assert ca.info().block == 256 and cb.info().block == 1024
+    s = torch.empty(ca.out_shapes[0], dtype=torch.float32, device=DEV)
+    p = torch.empty(cb.out_shapes[0], dtype=torch.float32, device=DEV)
+    for order in ((ca, cb), (cb, ca)):
+        st = B.dvm_stack(list(order))
+        assert st.info().block == 1024
+        s.fill_(float("nan")); p.fill_(float("nan"))
+        B.run_on(ctx, st, [x, s, z, p] if order[0] is ca else [z, p, x, s])
+        torch.cuda.synchronize()
+        for desc, ins, out, name in ((W.get_program("colsum"), {"x": x}, s, "s"), (W.get_program("softmax_f32"), {"z": z}, p, "p")):
+            rounded, exact = H.run_oracle(desc, ins)
+            H.compare(out, rounded[name], exact[name], "f32", True, f"stacked {desc.name}")
