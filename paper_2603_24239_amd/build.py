@@ -53,6 +53,12 @@ def build(verbose: bool = True) -> str:
                 "-DDVM_VARIANT_CRED=1"]
         jobs.append(([hipcc, *COMMON, *DEVICE, *defs, "-c", vm], os.path.join(CSRC, f"dvm_vm_c_k{k}_r{nr}.o")))
 
+    # the variants with the most registers take the longest to compile: start them first
+    def weight(job):
+        m = re.search(r"dvm_vm(?:_c)?_k(\d+)_r(\d+)\.o$", job[1])
+        return -(int(m.group(1)) * int(m.group(2))) if m else 0
+    jobs.sort(key=weight)
+
     def run(job):
         cmd, obj = job
         cmd = cmd + ["-o", obj]
