@@ -80,3 +80,29 @@ def test_errors_and_limits():
     f.flush()
     st = f.stats()
     assert st["ops"] == 100 and 2 <= st["launches"] <= 5 and st["elided"] >= 95
+
+
+def test_reduction_along_the_penultimate_axis_and_its_epilogue_share_a_launch():
+    f = B.Fuser(_ctx())
+    x = f.tensor(0x1000, "f32", B.make_shape((6, 50, 300)))
+    e = f.op("exp", [x], "f32", 0x2000)
+    s = f.op("csum", [e], "f32", 0x3000)
+    l = f.op("log", [s], "f32", 0x4000)          # on [6, 1, 300]: joins as the epilogue
+    f.release(e)
+    f.release(s)
+    f.flush()
+    assert f.stats() == {"ops": 3, "launches": 1, "flushes": 1, "elided": 2}
+    txt = f.last_code().disasm()
+    per_row, epilogue = txt.split("; epilogue")
+    assert "exp" in per_row and "acc.sum" in per_row and "log" in epilogue and len(re.findall(r"store\b", txt)) == 1
+    # a full-size operator on the reduced value cannot be part of that program: the group falls back to
+    # one launch per operator
+    e = f.op("exp", [x], "f32", 0x2000)
+    s = f.op("csum", [e], "f32", 0x3000)
+    d = f.op("sub", [x, s], "f32", 0x5000)
+    f.flush()
+    assert f.stats()["launches"] == 1 + 3
+    # rank 1 has no penultimate axis
+    v = f.tensor(0x6000, "f32", B.make_shape((64,)))
+    with pytest.raises(B.DvmError):
+        f.op("csum", [v], "f32", 0x7000)
