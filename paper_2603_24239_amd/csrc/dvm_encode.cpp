@@ -1922,7 +1922,9 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
             // the per-record work of the interpreter, long ones by memory
             uint32_t n_rec = 0;
             for (uint32_t pc = SH_WORDS + sh[S_PROLOG]; pc < sh[S_WORDS]; pc += (sh[pc] >> 8) & 0xFF) ++n_rec;
-            c = (double)sh[S_NTILES] * n_rec + c / 2048.0;
+            // (a unit of a segment that reduces along the penultimate axis runs its per-row records once per step)
+            const double steps = sh[S_INNER] != 0 ? (double)((sh[S_INNER] + (sh[S_RP] & 0xFFFF) - 1) / (sh[S_RP] & 0xFFFF)) : 1.0;
+            c = (double)sh[S_NTILES] * steps * n_rec + c / 2048.0;
             if (sh[S_NTILES] == 0) c = 0;
             cost[ns] = c;
             total += c;

@@ -90,12 +90,14 @@ def test_stacked_with_a_row_program():
     cb = B.encode_for(ctx, pb, [d["x"], d["w"]])
     s = torch.empty(ca.out_shapes[0], dtype=torch.float32, device=DEV)
     y = torch.empty(cb.out_shapes[0], dtype=torch.bfloat16, device=DEV)
-    st = B.dvm_stack([ca, cb])
-    B.run_on(ctx, st, [x, s, d["x"], d["w"], y])
-    torch.cuda.synchronize()
-    for desc, ins, out, name in ((W.get_program("colsum"), {"x": x}, s, "s"), (W.get_program("c2_rmsnorm"), d, y, "y")):
-        rounded, exact = H.run_oracle(desc, ins)
-        H.compare(out, rounded[name], exact[name], desc.outputs[0][1], True, f"stacked {desc.name}")
+    for spatial in (False, True):       # one after the other in every workgroup, then side by side on shares of them
+        st = B.dvm_stack([ca, cb], spatial=spatial)
+        s.fill_(float("nan")); y.fill_(float("nan"))
+        B.run_on(ctx, st, [x, s, d["x"], d["w"], y])
+        torch.cuda.synchronize()
+        for desc, ins, out, name in ((W.get_program("colsum"), {"x": x}, s, "s"), (W.get_program("c2_rmsnorm"), d, y, "y")):
+            rounded, exact = H.run_oracle(desc, ins)
+            H.compare(out, rounded[name], exact[name], desc.outputs[0][1], True, f"stacked {desc.name} spatial={spatial}")
 
 
 @pytest.mark.parametrize("waves", [1, 3, 16])
