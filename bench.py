@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 
 # rocprofv3 summaries of this command (kernel trace and the two HBM byte counters) per workload
 PROFILE_SUMMARY = {w: f"profiles/dvm_vm_kernel_{w}.md"
-                   for w in ("c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16")}
+                   for w in ("c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16", "column_sum")}
 
 
 def measured_traffic(workload: str):
@@ -155,7 +155,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="c2_rmsnorm",
-                    choices=["c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16", "if_else_add"])
+                    choices=["c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16", "if_else_add",
+                             "column_sum"])
     ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = the workload's default)")
     ap.add_argument("--stack", type=int, default=0,
                     help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
@@ -235,6 +236,15 @@ def main() -> int:
                      gen.layernorm_bytes(b, s_, h), (b, s_, h))
         wl = {"workload": "LayerNorm bf16 over [b, 8192, h], b 1..60, h in {1024, 2048, 3072, 4096} (the paper's Table 2 range), eps 1e-5",
               "instances": len(parts)}
+    elif args.workload == "column_sum":
+        # Table 1's Sum in its general form: [M, size, N] reduced along `size` to [M, 1, N], fp32
+        shapes = gen.column_sum_shapes()[: args.instances or None]
+        for i, (m, size, n) in enumerate(shapes):
+            x = gen.randn((m, size, n), gen.BASE_SEED + 8000 + i, dev)
+            add_part("colsum", {"x": x}, gen.column_sum_bytes(m, size, n), (m, size, n),
+                     {"s": torch.empty((m, 1, n), dtype=torch.float32, device=dev)})
+        wl = {"workload": "sum along the penultimate axis fp32, [M,size,N] -> [M,1,N], 48 dynamic instances "
+                          "(M 1..256, size 16..4096, N 512..4096)", "instances": len(parts)}
     elif args.workload == "c4_chain":
         shapes = gen.c4_shapes()[: args.instances or None]
         for i, t in enumerate(shapes):
@@ -290,7 +300,8 @@ def main() -> int:
         max_group = max(1, min(32 // n_t_part, 10))
         # default: eight per launch; config 3's instances are gigabytes each and differ in row length (a stacked
         # launch runs all its parts with the largest tile register size among them), so they stay apart
-        default_stack = 1 if args.workload == "c3_masked_softmax" else 8
+        # (and a column sum's workgroup and tile register size depend on its shape: one launch each as well)
+        default_stack = 1 if args.workload in ("c3_masked_softmax", "column_sum") else 8
         group = max(1, min(args.stack if args.stack > 0 else default_stack, max_group))
         groups_idx = [list(range(lo, min(lo + group, len(parts)))) for lo in range(0, len(parts), group)]
         singles_idx = [[i] for i in range(len(parts))]

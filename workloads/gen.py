@@ -84,6 +84,26 @@ def layernorm_paper_shapes(n: int = 60, seed: int = BASE_SEED + 6) -> List[Tuple
     return [(int(rng.integers(1, 61)), 8192, hs[int(rng.integers(0, 4))]) for _ in range(n)]
 
 
+def column_sum_shapes(n: int = 48, seed: int = BASE_SEED + 8) -> List[Tuple[int, int, int]]:
+    """A dynamic stream for Table 1's Sum in its general form, [M, size, N] reduced along `size`:
+    M log-uniform in 1..256, size log-uniform in 16..4096, N in {512, 1024, 2048, 4096}; instances above
+    2^27 elements are drawn again (the oracle evaluates whole instances)."""
+    rng = np.random.default_rng(seed)
+    ns = (512, 1024, 2048, 4096)
+    out: List[Tuple[int, int, int]] = []
+    while len(out) < n:
+        m = int(round(2.0 ** rng.uniform(0.0, 8.0)))
+        size = int(round(2.0 ** rng.uniform(4.0, 12.0)))
+        nn = ns[int(rng.integers(0, 4))]
+        if m * size * nn <= 2 ** 27:
+            out.append((m, size, nn))
+    return out
+
+
+def column_sum_bytes(m: int, size: int, n: int) -> int:
+    return m * size * n * 4 + m * n * 4
+
+
 def if_else_add_shapes(n: int = 60, seed: int = BASE_SEED + 7) -> List[Tuple[int, int, int, bool]]:
     """The paper's if-else-add range (Table 2): [b, s, f] plus a random branch flag."""
     rng = np.random.default_rng(seed)
