@@ -87,6 +87,7 @@ static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte align
 constexpr int LEN_REC = 4;              // length of every record except the view forms
 constexpr uint32_t SF_WGSYNC  = 1u;     // rows span several waves: reductions use the barrier
 constexpr uint32_t SF_RAGGED  = 2u;     // some tile has invalid rows or columns: mask reductions
+constexpr uint32_t SF_CSTREAM = 4u;     // reducing segment whose per-row part is I_CSTREAM records only: one step per unit
 
 // ---- instruction ids --------------------------------------------------------------------------
 enum : uint32_t {
@@ -113,6 +114,9 @@ enum : uint32_t {
                  // penultimate axis (Table 1: Sum / Max / Min over [M, size, N] with N > 1)
     I_CCOMB,     // epilogue only: combine R[a] over the waves of the workgroup with R_b (each wave accumulated its
                  // own share of the unit's rows), through LDS; afterwards only the first wave stores
+    I_CSTREAM,   // R[a] = R_b over the rows of the unit that fall to this wave, of a tensor (memory record with three
+                 // strides): the whole per-row part of a segment that only reduces input tensors along the
+                 // penultimate axis (SF_CSTREAM), with several rows in flight per wave instead of one per step
     I_COUNT
 };
 

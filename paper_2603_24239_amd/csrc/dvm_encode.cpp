@@ -526,6 +526,7 @@ struct Enc {
     bool cred_real[MAX_NODES];          // N_CRED over an axis of extent > 1 (otherwise the identity)
     bool post[MAX_NODES];               // computed from such a reduction: once per unit, in the epilogue
     int n_epilog;                       // first abstract instruction of the epilogue
+    bool cstream;                       // the per-row part only reduces input tensors: one streaming record each
     int n_fence;                        // peepholes do not reach back across this instruction index
     // linearisation
     AI ai[MAX_AI];
@@ -808,6 +809,20 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         }
     }
 
+    // A program whose per-row part does nothing but reduce input tensors gets one streaming record per
+    // reduction (several rows in flight per wave) instead of a load and an accumulate per row.
+    E.cstream = E.has_cred;
+    for (int n = 0; n < NN && E.cstream; ++n) {
+        const Node &nd = prog->nodes[n];
+        if (nd.kind == N_DEAD || nd.kind == N_IN || E.post[n]) {
+            if (E.cred_real[n] && (prog->nodes[nd.a].kind != N_IN || E.rows_class[nd.a])) E.cstream = false;
+            continue;
+        }
+        E.cstream = false;              // some other per-row computation
+    }
+    for (int o = 0; o < prog->n_out && E.cstream; ++o)
+        if (prog->nodes[prog->out_node[o]].kind == N_IN) E.cstream = false;     // an input copied to an output, row by row
+
     // ---- 3. tensor accesses, collapse -------------------------------------------------------------
     E.n_acc = prog->n_in + prog->n_out;
     for (int t = 0; t < E.n_acc; ++t) {
@@ -1064,8 +1079,12 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         if (E.cred_real[n]) {
             if (pass == 0) {
                 if (E.uses[n] > 0) {
-                    E.to_acc(nd.a);
-                    E.emit(I_CACC, (uint8_t)E.reg_of[n], nd.op);
+                    if (E.cstream) {
+                        E.emit(I_CSTREAM, (uint8_t)E.reg_of[n], nd.op, E.tensor_of_input(nd.a));
+                    } else {
+                        E.to_acc(nd.a);
+                        E.emit(I_CACC, (uint8_t)E.reg_of[n], nd.op);
+                    }
                 }
                 E.use(nd.a);
             } else {
@@ -1330,6 +1349,15 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             nvec = (uint32_t)cdiv(Cr, G);
             TC = G * nvec * V;
         }
+        // The streaming record keeps several rows' loads in registers at once: only the variants with few
+        // elements per lane have room for that (they are the ones picked when units are scarce, which is
+        // where it matters); wider tiles go row by row.
+        if (E.cstream && VARIANTS[vi].K > 8) {
+            E.cstream = false;
+            linearize(0);
+            if (E.err) return dvm_set_error(E.err_code, E.err);
+            if (E.nr_used > VARIANTS[vi].NR) return dvm_set_error(DVM_E_UNSUPPORTED, "internal: register count changed between linearisations");
+        }
     } else if (!column_mode) {
         const int ks[4] = {4, 8, 16, 32};
         int pick = -1;
@@ -1439,7 +1467,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         if (i == E.n_epilog) epilog_words = body_words;
         switch (x.op) {
             case I_LOAD: case I_STORE: body_words += view ? LEN_VLOAD : LEN_LOAD; break;
-            case I_LOADS: case I_STORES: body_words += LEN_VLOAD; break;
+            case I_LOADS: case I_STORES: case I_CSTREAM: body_words += LEN_VLOAD; break;
             default: body_words += LEN_REC; break;
         }
     }
@@ -1489,7 +1517,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (nct > 1) magic_u32(nct, &sh[S_NCTM], &sh[S_NCTSH]);
     sh[S_TBASE] = 0;
     sh[S_NTENS] = (uint32_t)E.n_acc;
-    sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0);
+    sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0) | (E.has_cred && E.cstream ? SF_CSTREAM : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
     if (E.has_cred) {
@@ -1516,6 +1544,16 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8) | (mflags << 16);
                 put_i64(A.s[1]);
                 if (view) { put_i64(A.s[2]); put_i64(A.s[3]); }
+                break;
+            }
+            case I_CSTREAM: {
+                const Access &A = E.acc[x.tensor];
+                imask |= 1u << I_CSTREAM;
+                *b++ = w0(I_CSTREAM, LEN_VLOAD, x.a, x.b);
+                bool once = true;       // read exactly once: no outer dim is broadcast
+                for (int g = 1; g < ng; ++g) once &= !(E.Dg[g] > 1 && A.s[g] == 0);
+                *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8) | ((once ? MF_STREAM : 0u) << 16);
+                put_i64(A.s[1]); put_i64(A.s[2]); put_i64(A.s[3]);
                 break;
             }
             case I_LOADS: case I_STORES: {
@@ -1756,7 +1794,21 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                 case I_CACC:
                     if (l != LEN_REC || !reg_ok(a, vr) || bb > R_MIN) return bad("accumulate");
                     if (sh[S_INNER] == 0 || pc >= at + SH_WORDS + sh[S_EPILOG]) return bad("accumulate outside the per-row part of a reducing segment");
+                    if (sh[S_FLAGS] & SF_CSTREAM) return bad("per-row accumulate in a segment marked as streaming reductions only");
                     break;
+                case I_CSTREAM: {
+                    if (l != LEN_VLOAD || !reg_ok(a, vr) || bb > R_MIN) return bad("streaming reduction");
+                    if (vr->K > 8) return bad("streaming reduction in a variant that does not run it");
+                    if (sh[S_INNER] == 0 || !(sh[S_FLAGS] & SF_CSTREAM) || pc >= at + SH_WORDS + sh[S_EPILOG])
+                        return bad("streaming reduction outside the per-row part of a segment marked for it");
+                    const uint32_t w1 = w[pc + 1];
+                    if ((w1 & 0xFF) >= nt) return bad("tensor index");
+                    const uint32_t info = w[PH_WORDS_N + (tbase + (w1 & 0xFF)) * TT_WORDS + TT_INFO];
+                    if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
+                    if (((w1 >> 8) & 0xFF) == DVM_BF16 && V != 8) return bad("bf16 tile with 4-element chunks");
+                    if ((w1 >> 16) & ~MF_STREAM) return bad("memory flags");
+                    break;
+                }
                 case I_CCOMB:
                     if (l != LEN_REC || !reg_ok(a, vr) || bb > R_MIN) return bad("combine");
                     if (sh[S_INNER] == 0 || pc < at + SH_WORDS + sh[S_EPILOG]) return bad("combine outside the epilogue of a reducing segment");
@@ -1822,7 +1874,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
     if (!codes || !lens || !len || n < 1) return dvm_set_error(DVM_E_ARGS, "dvm_stack: bad argument");
     size_t seg_words = 0;
     uint32_t ntens = 0, nseg = 0, block = 0, K = 0, NR = 0;
-    bool need_cred = false;
+    bool need_cred = false, need_cstream = false;   // (streaming reductions run in the variants with at most 8 elements per lane)
     uint64_t grid = 0;
     for (int i = 0; i < n; ++i) {
         int st = dvm_validate(codes[i], lens[i]);
@@ -1837,6 +1889,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
         if (((w[PH_VARIANT] >> 8) & 0xFF) > NR) NR = (w[PH_VARIANT] >> 8) & 0xFF;
         for (uint32_t s = 0, at = off; s < w[PH_NSEG]; ++s) {      // (a part that reduces along the penultimate axis)
             need_cred |= w[at + S_INNER] != 0;
+            need_cstream |= (w[at + S_FLAGS] & SF_CSTREAM) != 0;
             at += w[at + S_WORDS];
         }
         // every part was planned to fill the machine with workgroups of its own size: what carries
@@ -1853,7 +1906,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
     const Variant *vr = nullptr;
     for (int i = 0; i < N_VARIANTS; ++i) {
         const Variant &v = VARIANTS[i];
-        if ((uint32_t)v.K >= K && (uint32_t)v.NR >= NR && (uint32_t)v.max_threads >= block && (v.cred || !need_cred)) {
+        if ((uint32_t)v.K >= K && (uint32_t)v.NR >= NR && (uint32_t)v.max_threads >= block && (v.cred || !need_cred) && (v.K <= 8 || !need_cstream)) {
             if (!vr || v.K < vr->K || (v.K == vr->K && v.NR < vr->NR)) vr = &v;
         }
     }
@@ -2085,6 +2138,10 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     else o.put("  %04zu %-7s acc, %s\n", pc - at - SH_WORDS, BIN_NAMES[b], ra);
                     break;
                 case I_SEL: o.put("  %04zu select  acc = acc ? r%u : r%u\n", pc - at - SH_WORDS, a, b); break;
+                case I_CSTREAM:
+                    o.put("  %04zu stream.%-3s r%u = %s over this wave's rows of t%u strides=[%lld,%lld,%lld]%s\n", pc - at - SH_WORDS, RED_NAMES[b], a,
+                          RED_NAMES[b], w[pc + 1] & 0xFF, i64(pc + 2), i64(pc + 4), i64(pc + 6), ((w[pc + 1] >> 16) & MF_STREAM) ? "  [read once]" : "");
+                    break;
                 case I_CCOMB: o.put("  %04zu comb.%-3s r%u = %s of r%u over the workgroup's waves\n", pc - at - SH_WORDS, RED_NAMES[b], a, RED_NAMES[b], a); break;
                 case I_CACC: o.put("  %04zu acc.%-4s r%u = first row ? acc : %s(r%u, acc)\n", pc - at - SH_WORDS, RED_NAMES[b], a, RED_NAMES[b], a); break;
                 case I_FMA: {

@@ -834,7 +834,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                 if (inner != 0) {
                     const uint32_t r = rin * RP + rp;
                     tile_rows_at(gt, shl, tile_r0 * inner + r, (r < inner) && (rp < RP) && (tid < seg_threads));
-                    if ((rin + 1) * RP < inner) this_end = body + shl[S_EPILOG];
+                    if ((rin + 1) * RP < inner && !(shl[S_FLAGS] & SF_CSTREAM)) this_end = body + shl[S_EPILOG];
                 } else {
                     tile_rows(gt, shl, tile_r0, rp, tid, RP, seg_threads);
                 }
@@ -994,6 +994,45 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         }
                     }
                         break;
+                    case I_CSTREAM: if constexpr (CRED && K <= 8) {      // (the encoder emits it for these variants only)
+                        // this wave's share of the unit's rows (every RP-th, starting at its own), U rows in flight:
+                        // all their loads are issued before the first is combined into the accumulator
+                        DVM_GEO()
+                        const uint32_t w1 = cw1;
+                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                        const bool nt = ((w1 >> 16) & MF_STREAM) != 0;
+                        const int64_t st1 = DVM_I64(cw2, cw3);
+                        const u32x4s hw = fetch4(code, cur + 4);
+                        const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                        const uint32_t es = dt == 0 ? 4 : 2;
+                        // (a wave without a valid first row decomposed row 0: in bounds, and it combines nothing)
+                        const int64_t off0 = (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3) + (int64_t)g.colbase;
+                        gcptr base = (gcptr)args.tensors[tbase + ti];
+                        const uint32_t inner_n = sh[S_INNER];
+                        const float ident = b == R_SUM ? 0.0f : (b == R_MAX ? -__builtin_inff() : __builtin_inff());
+                        constexpr int U = K <= 4 ? 8 : 4;       // (as many as the registers hold)
+                        DVM_WITH_R(a, rr, {
+                            sfor<K>([&]<int I>() LI { rr.v[I] = ident; });
+                            if (wave < RP) {
+                                for (uint32_t r = wave; r < inner_n; r += RP * U) {
+                                    Raw<K> raw[U];
+                                    sfor<U>([&]<int J>() LI {
+                                        const uint32_t ru = r + (uint32_t)J * RP;
+                                        const uint32_t rc = ru < inner_n ? ru : r;      // past the end: read row r again, unused
+                                        request_dispatch<K>(raw[J], dt, V, nt, base + (off0 + (int64_t)rc * st1) * es, g);
+                                    });
+                                    sfor<U>([&]<int J>() LI {
+                                        if (r + (uint32_t)J * RP < inner_n) {
+                                            if (b == R_SUM) widen_dispatch<K, B_ADD>(rr, raw[J], dt, V, g);
+                                            else if (b == R_MAX) widen_dispatch<K, B_MAX>(rr, raw[J], dt, V, g);
+                                            else widen_dispatch<K, B_MIN>(rr, raw[J], dt, V, g);
+                                        }
+                                    });
+                                }
+                            }
+                        })
+                    }
+                        break;
                     case I_CCOMB:       // every wave ends up with the combination, taken in wave order; the first wave stores
                         if constexpr (CRED) if (sh[S_INNER] != 0 && RP > 1) {
                             uint32_t lane = tid & 63u;
@@ -1080,7 +1119,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             }
             if constexpr (CRED) {   // next step of this unit, or the next tile
                 const uint32_t inner = sh[S_INNER];
-                if (inner == 0 || (rin + 1) * RP >= inner) { rin = 0; ++tile; } else { ++rin; }
+                if (inner == 0 || (rin + 1) * RP >= inner || (sh[S_FLAGS] & SF_CSTREAM)) { rin = 0; ++tile; } else { ++rin; }
             } else {
                 ++tile;
             }

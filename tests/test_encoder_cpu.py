@@ -328,9 +328,10 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
     # [M, size, N]: units of (M index, column tile); the per-row part accumulates, the epilogue stores
     code = _encode(ctx, "colsum", [(4, 100, 300)])
     txt = code.disasm()
-    assert re.search(r"acc\.sum\s+r0 = first row \? acc : sum\(r0, acc\)", txt)
+    # (nothing but the reduction of an input: one streaming record, several rows in flight per wave)
+    assert re.search(r"stream\.sum r0 = sum over this wave's rows of t0", txt) and "acc.sum" not in txt
     per_row, epilogue = txt.split("; epilogue (after the last of the 100 rows of a unit)")
-    assert "load" in per_row and "store" not in per_row and "store" in epilogue
+    assert "store" not in per_row and "comb.sum" in epilogue and "store" in epilogue
     assert code.out_shapes[0] == (4, 1, 300)
     info = code.info()
     assert info.n_tiles == 4 * 2 and info.block == 64 * 16  # 4 outer indices x 2 column tiles of 256; 16 waves share a unit
@@ -351,7 +352,7 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
     assert "store" in per_row and "store" in epilogue
     # an axis of extent 1 reduces to itself: no unit loop
     txt = _encode(ctx, "colsum", [(7, 1, 128)]).disasm()
-    assert "epilogue" not in txt and "acc.sum" not in txt
+    assert "epilogue" not in txt and "acc.sum" not in txt and "stream.sum" not in txt
     # what one pass cannot compute is refused with a code
     from workloads.programs import _p
     centred = _p("centred", [("x", "f32")], [("s", "csum", ["x"], {}), ("d", "sub", ["x", "s"], {})], [("d", "f32")])
@@ -368,6 +369,9 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
     b = _encode(small, "c2_rmsnorm", [(100, 4096), (4096,)])
     st = B.dvm_stack([a, b])
     assert "acc.sum" in st.disasm() and st.info().n_segments == 2 and st.info().variant_nr == 6
+    # a streaming reduction runs in the variants with at most 8 elements per lane only
+    with pytest.raises(B.DvmError):
+        B.dvm_stack([_encode(small, "colsum", [(4, 100, 300)]), b])
     # a 16-wave workgroup fits no variant that also holds a 32-element-per-lane part
     with pytest.raises(B.DvmError):
         B.dvm_stack([_encode(ctx, "colsum", [(4, 100, 300)]), _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])])
