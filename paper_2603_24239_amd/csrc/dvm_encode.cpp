@@ -822,6 +822,10 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     }
     for (int o = 0; o < prog->n_out && E.cstream; ++o)
         if (prog->nodes[prog->out_node[o]].kind == N_IN) E.cstream = false;     // an input copied to an output, row by row
+    // (several reductions of one input share its load when they go row by row; streaming records would each read it)
+    for (int n = 0; n < NN && E.cstream; ++n)
+        for (int m = n + 1; m < NN && E.cstream; ++m)
+            if (E.cred_real[n] && E.cred_real[m] && prog->nodes[n].a == prog->nodes[m].a) E.cstream = false;
 
     // ---- 3. tensor accesses, collapse -------------------------------------------------------------
     E.n_acc = prog->n_in + prog->n_out;

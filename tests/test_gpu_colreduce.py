@@ -177,3 +177,21 @@ def test_stacked_under_a_larger_workgroup(monkeypatch):
         for desc, ins, out, name in ((W.get_program("colsum"), {"x": x}, s, "s"), (W.get_program("softmax_f32"), {"z": z}, p, "p")):
             rounded, exact = H.run_oracle(desc, ins)
             H.compare(out, rounded[name], exact[name], "f32", True, f"stacked {desc.name}")
+
+
+@pytest.mark.parametrize("op", ["cmax", "cmin", "csum"])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_single_reduction_of_an_input_streams(op, dtype):
+    # nothing but the reduction of an input: the streaming record (several rows in flight per wave); max and min
+    # are exact in both storage types
+    from workloads.programs import single_op_program
+    shape = (3, 77, 1100)
+    say(f"{op} {dtype} {shape}")
+    desc = single_op_program(op, 1, dtype)
+    x = randn(shape, 8100 + len(op), dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
+    outs, code = check(desc, {"a0": x}, f"{op} {dtype}")
+    assert "stream." in code.disasm()
+    if op == "cmax":
+        assert torch.equal(outs["y"], x.max(dim=-2, keepdim=True).values)
+    if op == "cmin":
+        assert torch.equal(outs["y"], x.min(dim=-2, keepdim=True).values)
