@@ -3,6 +3,7 @@ inputs and independent library routines.  None of these tests touches the HIP pa
 import itertools
 import math
 import os
+import zlib
 
 import numpy as np
 import pytest
@@ -139,7 +140,7 @@ def test_elementwise_ops_bruteforce_with_broadcast(op):
         nargs = 1
     if op in ("min", "max"):
         nargs = 2
-    rng = np.random.default_rng(hash(op) % 1000)
+    rng = np.random.default_rng(zlib.crc32(op.encode()) % 1000)      # (the same inputs in every process: str hashes are salted)
     shape_sets = [[(1,)], [(1, 1)], [(2, 3)], [(3, 1, 5), (1, 4, 1)]]
     for shapes in shape_sets:
         shapes = (shapes * 2)[:nargs] if len(shapes) >= nargs else (shapes * nargs)[:nargs]
