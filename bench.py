@@ -1,21 +1,24 @@
 #!/usr/bin/env python3
 """Benchmark of the DVM hot path on one MI355X.
 
-A step is one pass of the whole hot path over the configured workload: every instance of the
-dynamic-shape stream is encoded by dvm_encode (host: shape inference, fusion, register allocation,
-tile plan, bytecode), consecutive instances are merged eight at a time into one launch by dvm_stack
-(temporal stacking), and dvm_run executes each launch (device: the bytecode interpreter), all on one
-stream.  Inputs and outputs of all instances are resident in HBM before the timed region.  The same
-stream is also run with every instance as its own launch; that figure is reported beside the main one.
+A step is one pass of the whole hot path over the configured workloads: every instance of a
+dynamic-shape stream is encoded by dvm_encode (host: shape inference, fusion, register allocation, tile
+plan, bytecode), consecutive instances are merged into one launch by dvm_stack (temporal stacking), and
+dvm_run executes each launch (device: the bytecode interpreter), all on one stream.  Inputs and outputs
+of a stream are resident in HBM before its timed region starts.
 
-Workload (default): fused RMSNorm with learned scale, bf16 in/out with fp32 accumulation,
-x = [B, S, 4096] ~ N(0,1), weight ~ N(1, 0.1), eps 1e-6, 200 instances with B uniform in 1..32 and
-S uniform in 1..2048, all shapes distinct, drawn from a seed (synthetic data).
+Default (`--workload suite`): the four dynamic streams of the benchmark configuration, one after the
+other (they do not fit the device together): config 2 (RMSNorm bf16, 200 instances), config 3 (causal
+masked softmax fp32, all 50 instances), config 4 (12-op chain bf16, 100 instances) and config 5 (64 steps
+of a 32-layer stack), plus the latency of config 1.  The headline `value` and the `roofline` record are
+the aggregate over the large memory-bound configs 2-4; `per_config` holds every stream's own figures.
+`--workload <name>` runs one stream alone (the committed rocprofv3 summaries are made that way).
 
-Prints ONE JSON line: whole-job throughput in GB/s of algorithmic bytes (one read of every input
-element + one write of every output element), the roofline record of the interpreter kernel
-(per-launch HIP-event durations on the launch stream), the encode latency per instance, and the
-CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line: throughput in GB/s of algorithmic bytes (one read of every input element + one
+write of every output element), the roofline record of the interpreter kernel (per-launch HIP-event
+durations on the launch stream), the copy-kernel ceiling measured in the same job, the encode latency per
+instance measured inside the library (dvm_encode_timed), and the CPU oracle timed on a bounded sample of
+the same workloads on all host cores and on one.
 """
 from __future__ import annotations
 
@@ -30,25 +33,141 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+SUITE = ["c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers"]
+LARGE_CLASS = ["c2_rmsnorm", "c3_masked_softmax", "c4_chain"]
+ALL_WORKLOADS = ["c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16", "if_else_add", "column_sum"]
 
-# rocprofv3 summaries of this command (kernel trace and the two HBM byte counters) per workload
-PROFILE_SUMMARY = {w: f"profiles/dvm_vm_kernel_{w}.md"
-                   for w in ("c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16", "column_sum")}
+# rocprofv3 summaries (kernel trace and the two HBM byte counters) of `bench.py --workload <name>`
+PROFILE_SUMMARY = {w: f"profiles/dvm_vm_kernel_{w}.md" for w in ALL_WORKLOADS}
 
 
-def measured_traffic(workload: str):
-    """HBM bytes per interpreter launch from the committed counter summary (FETCH_SIZE + WRITE_SIZE, each scaled
-    by what the same counter reads for a plain copy of known size), or None if there is no such summary."""
+def measured_traffic_ratio(workload: str):
+    """HBM bytes / algorithmic bytes of the interpreter launches of a workload, from the committed counter summary
+    (two rocprofv3 --pmc runs of this command, FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter
+    reads for a plain copy of known size), or None if there is no such summary."""
     path = os.path.join(ROOT, PROFILE_SUMMARY.get(workload, ""))
     try:
         with open(path) as f:
             for line in f:
-                if line.startswith("traffic_bytes_per_launch:"):
-                    return int(line.split(":", 1)[1])
+                if line.startswith("traffic_ratio:"):
+                    return float(line.split(":", 1)[1])
     except (OSError, ValueError):
         pass
     return None
 
+
+# ------------------------------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands, one row block per worker process.  The pool is forked before the
+# process touches the GPU; workers use NumPy only.
+# ------------------------------------------------------------------------------------------------------
+
+def _np_from_raw(path, dtype, shape):
+    """A storage-dtype array written by the parent into shared memory, widened to float64 (bf16 travels as uint16)."""
+    import numpy as np
+    if dtype == "bf16":
+        u = np.fromfile(path, dtype=np.uint16).reshape(shape)
+        return (u.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return np.fromfile(path, dtype=np.float32).reshape(shape).astype(np.float64)
+
+
+def _oracle_worker(task):
+    import numpy as np
+    from oracle import interp
+    from workloads import programs as W
+    name, ins_spec, got_spec, rtol, start_at = task
+    desc = W.get_program(name)
+    ins = {k: _np_from_raw(p, dt, sh) for k, (p, dt, sh) in ins_spec.items()}
+    while time.monotonic() < start_at:      # all workers of a leg start together
+        time.sleep(0.0005)
+    t0 = time.monotonic()
+    rounded, exact = interp.run(desc, ins)
+    t1 = time.monotonic()
+    worst = 0.0
+    for nm, (p, dt, sh) in got_spec.items():
+        got = _np_from_raw(p, dt, sh)
+        ref = rounded[nm]
+        scale = np.broadcast_to(interp.row_scale(exact[nm]), ref.shape)
+        tol = rtol * np.abs(ref) + rtol * scale
+        fin = np.isfinite(ref)
+        if not np.array_equal(np.isnan(got), np.isnan(ref)):
+            worst = float("inf")
+        worst = max(worst, float(np.max(np.where(fin, np.abs(got - ref) / np.maximum(tol, 1e-300), 0.0))))
+    return t0, t1, worst
+
+
+class CpuBaseline:
+    def __init__(self, enabled: bool):
+        self.enabled = enabled
+        self.cores = 0
+        self.pool = None
+        self.legs = []
+        if not enabled:
+            return
+        import multiprocessing as mp
+        self.cores = max(1, min(len(os.sched_getaffinity(0)), 16))
+        self.pool = mp.get_context("fork").Pool(self.cores)
+        self.dir = f"/dev/shm/dvm_bench_{os.getpid()}"
+        os.makedirs(self.dir, exist_ok=True)
+        self.n_files = 0
+
+    def _put(self, t):
+        """Write a CPU tensor's storage bits to shared memory; returns (path, storage dtype, shape)."""
+        import torch
+        p = os.path.join(self.dir, f"t{self.n_files}.bin")
+        self.n_files += 1
+        t = t.contiguous()
+        if t.dtype == torch.bfloat16:
+            t.view(torch.int16).numpy().tofile(p)
+            return p, "bf16", tuple(t.shape)
+        t.numpy().tofile(p)
+        return p, "f32", tuple(t.shape)
+
+    def leg(self, name: str, desc_name: str, blocks, bytes_per_block: float, rtol: float):
+        """blocks: list of (inputs dict name -> CPU tensor, GPU outputs dict name -> CPU tensor), one per worker."""
+        if not self.enabled or not blocks:
+            return
+        tasks = [(desc_name, {k: self._put(v) for k, v in ins.items()}, {k: self._put(v) for k, v in got.items()}, rtol)
+                 for ins, got in blocks]
+        # one block on one core, the others idle
+        t0, t1, w1 = self.pool.apply(_oracle_worker, (tasks[0] + (0.0,),))
+        one = bytes_per_block / max(t1 - t0, 1e-9)
+        start_at = time.monotonic() + 0.5
+        res = self.pool.map(_oracle_worker, [t + (start_at,) for t in tasks], chunksize=1)
+        wall = max(r[1] for r in res) - min(r[0] for r in res)
+        self.legs.append({"config": name, "blocks": len(blocks), "bytes": bytes_per_block * len(blocks), "wall_s": wall,
+                          "cpu_s_1core": t1 - t0, "GBps_1core": one / 1e9, "worst": max([w1] + [r[2] for r in res])})
+        for f in os.listdir(self.dir):
+            os.unlink(os.path.join(self.dir, f))
+
+    def result(self):
+        if not self.enabled or not self.legs:
+            return None
+        tot_b = sum(l["bytes"] for l in self.legs)
+        tot_t = sum(l["wall_s"] for l in self.legs)
+        one_b = sum(l["bytes"] / l["blocks"] for l in self.legs)
+        one_t = sum(l["cpu_s_1core"] for l in self.legs)
+        return {"value": round(tot_b / tot_t / 1e9, 4), "unit": "GB/s", "cores": self.cores, "kind": "oracle",
+                "one_core_GBps": round(one_b / one_t / 1e9, 4),
+                "sample": "leading row blocks of one instance per config (" + ", ".join(
+                    f"{l['config']}: {l['blocks']} blocks, {l['bytes'] / 1e6:.0f} MB, {l['wall_s']:.1f} s" for l in self.legs) +
+                    f"), one block per worker process on {self.cores} cores (count from sched_getaffinity, capped at 16), "
+                    "NumPy float64 per-op evaluation; one_core_GBps: one block alone on one core",
+                "per_config_GBps": {l["config"]: round(l["bytes"] / l["wall_s"] / 1e9, 4) for l in self.legs},
+                "max_err_over_tol_vs_gpu": round(max(l["worst"] for l in self.legs), 4)}
+
+    def close(self):
+        if self.pool is not None:
+            self.pool.close()
+            self.pool.join()
+            try:
+                os.rmdir(self.dir)
+            except OSError:
+                pass
+
+
+# ------------------------------------------------------------------------------------------------------
+# the streaming fuser workload
+# ------------------------------------------------------------------------------------------------------
 
 def bench_fuser(args, B, gen, W, ctx, dev) -> int:
     """The paper's dynamic control-flow workload (Table 2): (a > b ? 2x : 4x) + y over [b, s, f] with the branch
@@ -149,14 +268,328 @@ def bench_fuser(args, B, gen, W, ctx, dev) -> int:
     return 0
 
 
+# ------------------------------------------------------------------------------------------------------
+# one dynamic stream: inputs, launches, timing
+# ------------------------------------------------------------------------------------------------------
+
+class Stream:
+    """The parts (one program applied to one set of tensors) of a workload and how they group into launches."""
+
+    def __init__(self, name, args, B, gen, W, ctx, dev):
+        import numpy as np
+        import torch
+        self.name, self.args, self.B, self.ctx, self.dev = name, args, B, ctx, dev
+        self.parts = []
+        self.fixed_groups = None
+        self.dtype = "bf16 storage, f32 arithmetic"
+        progs = {}
+
+        def program(pname):
+            if pname not in progs:
+                progs[pname] = (W.get_program(pname), B.Program(W.get_program(pname)))
+            return progs[pname]
+
+        def add_part(pname, ins_d, nbytes, shape, outs=None):
+            desc, prog = program(pname)
+            ins = [ins_d[n] for n, _ in desc.inputs]
+            if outs is None:
+                shapes = [tuple(t.shape) for t in ins]
+                full = max(shapes, key=lambda sh: (len(sh), int(np.prod(sh))))
+                out_shape = tuple(np.broadcast_shapes(*shapes)) if len(shapes) > 1 else full
+                outs_l = [torch.empty(out_shape, dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device=dev)
+                          for _, dt in desc.outputs]
+                layout = None
+            else:
+                outs_l = [outs[n] for n, _ in desc.outputs]
+                layout = (B.dvm_shape * len(outs_l))(*[B.shape_of_tensor(t) for t in outs_l])
+            self.parts.append({"name": pname, "desc": desc, "prog": prog, "ins": ins, "outs": outs_l, "bytes": nbytes, "shape": shape,
+                               "shapes": (B.dvm_shape * len(ins))(*[B.shape_of_tensor(t) for t in ins]), "layout": layout})
+
+        n_inst = args.instances or None
+        self.default_stack = 8
+        if name == "c2_rmsnorm":
+            for i, (b, s) in enumerate(gen.c2_shapes()[:n_inst]):
+                add_part("c2_rmsnorm", gen.c2_inputs(b, s, gen.BASE_SEED + 2000 + i, dev), gen.c2_bytes(b, s), (b, s))
+            self.wl = {"workload": "config 2: fused RMSNorm bf16, x[B,S,4096], 200 dynamic instances (B 1..32, S 1..2048), eps 1e-6"}
+        elif name == "layernorm_bf16":
+            # the LayerNorm subgraph range of the paper's Table 2 ([b, 8192, h]); the first 24 of the seeded stream
+            for i, (b, s_, h) in enumerate(gen.layernorm_paper_shapes()[: args.instances or 24]):
+                add_part("layernorm_bf16", gen.layernorm_inputs(b, s_, h, gen.BASE_SEED + 6000 + 3 * i, dev),
+                         gen.layernorm_bytes(b, s_, h), (b, s_, h))
+            self.wl = {"workload": "LayerNorm bf16 over [b, 8192, h], b 1..60, h in {1024, 2048, 3072, 4096} (the paper's Table 2 range), eps 1e-5"}
+        elif name == "column_sum":
+            # Table 1's Sum in its general form: [M, size, N] reduced along `size` to [M, 1, N], fp32
+            for i, (m, size, n) in enumerate(gen.column_sum_shapes()[:n_inst]):
+                x = gen.randn((m, size, n), gen.BASE_SEED + 8000 + i, dev)
+                add_part("colsum", {"x": x}, gen.column_sum_bytes(m, size, n), (m, size, n),
+                         {"s": torch.empty((m, 1, n), dtype=torch.float32, device=dev)})
+            self.wl = {"workload": "sum along the penultimate axis fp32, [M,size,N] -> [M,1,N], 48 dynamic instances "
+                                   "(M 1..256, size 16..4096, N 512..4096)"}
+            self.default_stack = 1      # (workgroup and tile register size depend on the shape: one launch each)
+            self.dtype = "f32"
+        elif name == "c4_chain":
+            for i, t in enumerate(gen.c4_shapes()[:n_inst]):
+                add_part("c4_chain", gen.c4_inputs(t, gen.BASE_SEED + 4000 + i, dev), gen.c4_bytes(t), (t,))
+            self.wl = {"workload": "config 4: 12-op transformer non-GEMM chain bf16 over [T,8192], 100 dynamic instances (T 1..16384)"}
+        elif name == "c1_gelu":
+            add_part("c1_gelu_erf", gen.c1_inputs(gen.BASE_SEED + 1, dev), 4 * 1000 * 4 * 2 + 2 * 1000 * 4, (4, 1000))
+            self.wl = {"workload": "config 1: gelu(x*a+b) fp32 on [4,1000] (latency-bound)"}
+            self.dtype = "f32"
+        elif name == "c3_masked_softmax":
+            # all 50 instances of the seeded stream (92 GB of scores, as much again of outputs); the causal mask of a
+            # given S is one tensor shared by the instances of that S
+            masks = {}
+            for i, (b, s) in enumerate(gen.c3_shapes()[:n_inst]):
+                d = gen.c3_inputs(b, s, gen.BASE_SEED + 3000 + i, dev)
+                d["mask"] = masks.setdefault(s, d["mask"])
+                add_part("c3_masked_softmax", d, gen.c3_bytes(b, s), (b, s))
+            self.wl = {"workload": "config 3: causal-masked softmax fp32 over [B,32,S,S] (B 1..4, S 128..4096), mask [S,S] broadcast, "
+                                   "50 dynamic instances"}
+            self.default_stack = 1      # (instances are gigabytes each and differ in row length)
+            self.dtype = "f32"
+        elif name == "c5_layers":
+            # config 5: 64 steps of a 32-layer stack, six programs per layer, T log-normal; one buffer set per
+            # step shared by its 32 layers; every layer is one launch (its six programs stacked)
+            if not args.limits:
+                ctx.set_limits(16, 6)   # parts that share a launch must fit one interpreter variant
+            steps_T = gen.c5_steps()[:n_inst]
+            self.fixed_groups = []
+            for si, T in enumerate(steps_T):
+                d = gen.c5_inputs(T, gen.BASE_SEED + 5000 + 100 * si, dev)
+                rope_out = torch.empty((T, 32, 128), dtype=torch.bfloat16, device=dev)
+                L = T // 8 + 1
+                first = len(self.parts)
+                add_part("c5_rmsnorm", d["c5_rmsnorm"], (2 * T * 4096 + 4096) * 2, (T,))
+                add_part("c5_rope", d["c5_rope"], 2 * T * 32 * 128 * 2 + 2 * T * 64 * 4, (T,),
+                         {"y1": rope_out[..., :64], "y2": rope_out[..., 64:]})
+                add_part("c5_softmax", d["c5_softmax"], 2 * 32 * T * L * 2, (T,))
+                add_part("c5_residual", d["c5_residual_a"], 3 * T * 4096 * 2, (T,))
+                add_part("c5_silu_gate", d["c5_silu_gate"], 3 * T * 14336 * 2, (T,))
+                add_part("c5_residual", d["c5_residual_b"], 3 * T * 4096 * 2, (T,))
+                self.fixed_groups += [list(range(first, first + 6))] * 32
+            self.wl = {"workload": "config 5: 64 steps x 32 layers x {rmsnorm, rope, softmax, residual, silu-gate, residual} bf16, "
+                                   "T log-normal (median 512, 1..8192); one launch per layer, every step's wall time includes its encodes",
+                       "steps_of_the_stream": len(steps_T)}
+            self.steps_T = steps_T
+        else:
+            raise ValueError(name)
+        torch.cuda.synchronize()
+
+        # launches: lists of part indices
+        if self.fixed_groups is not None:
+            self.groups_idx = self.fixed_groups
+            self.group = 6
+            self.singles_idx = [[i] for g in self.fixed_groups for i in g]
+        else:
+            n_t_part = len(self.parts[0]["ins"]) + len(self.parts[0]["outs"])
+            max_group = max(1, min(32 // n_t_part, 10))
+            self.group = max(1, min(args.stack if args.stack > 0 else self.default_stack, max_group))
+            n = len(self.parts)
+            self.groups_idx = [list(range(lo, min(lo + self.group, n))) for lo in range(0, n, self.group)]
+            self.singles_idx = [[i] for i in range(n)]
+        self.total_bytes = sum(self.parts[i]["bytes"] for g in self.groups_idx for i in g)
+        self.wl["instances"] = len(self.groups_idx) if self.fixed_groups is not None else len(self.parts)
+        self.wl["instances_per_launch"] = self.group
+        self.stacking = args.stacking or "temporal"
+        self.wl["stacking"] = self.stacking if self.group > 1 else "none"
+
+    def ctx_restore(self):
+        if self.name == "c5_layers" and not self.args.limits:
+            self.ctx.set_limits(32, 6)
+
+    def run(self, lib, steps, warmup, unstacked=True):
+        """Time `steps` passes over the stream (after `warmup` untimed ones); returns the stream's figures."""
+        import numpy as np
+        import torch
+        B, ctx, parts = self.B, self.ctx, self.parts
+        enc_cap = 8192
+        max_parts = max(len(g) for g in self.groups_idx)
+        part_bufs = [C.create_string_buffer(enc_cap) for _ in range(max_parts)]
+        part_ptrs = (C.c_void_p * max_parts)(*[C.cast(b, C.c_void_p) for b in part_bufs])
+        part_lens = (C.c_size_t * max_parts)()
+        stacked = C.create_string_buffer(enc_cap)
+        ln = C.c_size_t()
+        ns = (C.c_int64 * 1)()
+        stream = torch.cuda.current_stream()
+        stream_h = C.c_void_p(stream.cuda_stream)
+        perf = time.perf_counter
+        stack_fn = lib.dvm_stack_spatial if self.stacking == "spatial" else lib.dvm_stack
+
+        def marshal(groups):
+            out = []
+            for idx in groups:
+                tens = [t for i in idx for t in parts[i]["ins"] + parts[i]["outs"]]
+                out.append((idx, (C.c_void_p * len(tens))(*[t.data_ptr() for t in tens]), len(tens)))
+            return out
+
+        def one_step(groups, events=None, enc_ns=None):
+            """Encode every part, stack the parts of each launch (a single part is launched as it is), run."""
+            for k, (idx, ptrs, n_t) in enumerate(groups):
+                for j, i in enumerate(idx):
+                    pt = parts[i]
+                    st = lib.dvm_encode_timed(ctx._h, pt["prog"]._h, pt["shapes"], len(pt["ins"]), pt["layout"], part_bufs[j], enc_cap,
+                                              C.byref(ln), 1, ns)
+                    if st != 0:
+                        raise B.DvmError(st, "dvm_encode")
+                    part_lens[j] = ln.value
+                    if enc_ns is not None:
+                        enc_ns.append(ns[0])
+                if len(idx) == 1:
+                    code, code_len = part_bufs[0], part_lens[0]
+                else:
+                    st = stack_fn(part_ptrs, part_lens, len(idx), stacked, enc_cap, C.byref(ln))
+                    if st != 0:
+                        raise B.DvmError(st, "dvm_stack")
+                    code, code_len = stacked, ln.value
+                if events is not None:
+                    events[k][0].record(stream)
+                st = lib.dvm_run(ctx._h, code, code_len, ptrs, n_t, stream_h)
+                if st != 0:
+                    raise B.DvmError(st, "dvm_run")
+                if events is not None:
+                    events[k][1].record(stream)
+
+        def timed(groups, n_steps, n_warm, enc_ns=None):
+            for _ in range(n_warm):
+                one_step(groups)
+            evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in groups]
+                   for _ in range(n_steps)]
+            torch.cuda.synchronize()
+            t0 = perf()
+            for s in range(n_steps):
+                one_step(groups, evs[s], enc_ns)
+            torch.cuda.synchronize()
+            return perf() - t0, evs
+
+        groups = marshal(self.groups_idx)
+        enc_ns = []
+        elapsed, all_events = timed(groups, steps, warmup, enc_ns)
+        kern_ms = [a.elapsed_time(b) for evs in all_events for (a, b) in evs]
+        group_bytes = [sum(parts[i]["bytes"] for i in g) for g in self.groups_idx]
+        big_groups = [k for k, b in enumerate(group_bytes) if b >= 256e6]
+        group_ms = [float(np.mean([all_events[s][k][0].elapsed_time(all_events[s][k][1]) for s in range(steps)])) for k in range(len(groups))]
+        r = {"config": dict(self.wl), "dtype": self.dtype, "total_bytes": self.total_bytes, "elapsed_s": elapsed, "steps": steps,
+             "kernel_ms_sum_per_step": sum(kern_ms) / steps, "launches_per_step": len(groups),
+             "whole_job_GBps": self.total_bytes * steps / elapsed / 1e9,
+             "kernel_GBps": self.total_bytes / (sum(kern_ms) / steps) / 1e6,
+             "large_launches": None, "unstacked": None}
+        if big_groups:
+            r["large_launches"] = {"launches": len(big_groups),
+                                   "GBps": sum(group_bytes[k] for k in big_groups) / sum(group_ms[k] for k in big_groups) / 1e6,
+                                   "bytes": sum(group_bytes[k] for k in big_groups), "ms": sum(group_ms[k] for k in big_groups)}
+        # first-call encode of every distinct part (cold) and the steady state inside the timed steps
+        enc = np.array(enc_ns, dtype=np.float64) / 1e3
+        r["encode_us"] = {"median": round(float(np.median(enc)), 2), "p99": round(float(np.percentile(enc, 99)), 2),
+                          "max": round(float(enc.max()), 2), "calls": int(enc.size),
+                          "note": "every dvm_encode call of the timed steps, CLOCK_MONOTONIC inside the library (dvm_encode_timed)"}
+        # the same stream with every program as its own launch (no stacking): per-program launch times
+        if unstacked:
+            if self.group > 1:
+                singles = marshal(self.singles_idx)
+                elapsed1, events1 = timed(singles, steps, 1)
+            else:
+                elapsed1, events1 = elapsed, all_events
+            one_ms = [float(np.mean([events1[s][k][0].elapsed_time(events1[s][k][1]) for s in range(steps)]))
+                      for k in range(len(self.singles_idx))]
+            one_bytes = [parts[g[0]]["bytes"] for g in self.singles_idx]
+            if self.args.dump_launches:
+                with open(self.args.dump_launches, "a") as f:
+                    f.write("launch,program,shape,bytes,mean_launch_us,GBps\n")
+                    for k, g in enumerate(self.singles_idx):
+                        pt = parts[g[0]]
+                        f.write(f"{k},{pt['name']},{'x'.join(map(str, pt['shape']))},{pt['bytes']},{one_ms[k] * 1e3:.2f},"
+                                f"{pt['bytes'] / one_ms[k] / 1e6:.1f}\n")
+            rates = np.array([b / m / 1e6 for b, m in zip(one_bytes, one_ms)])
+            big = [k for k, b in enumerate(one_bytes) if b >= 256e6]
+            r["unstacked"] = {"whole_job_GBps": round(self.total_bytes * steps / elapsed1 / 1e9, 1),
+                              "kernel_GBps": round(sum(one_bytes) / sum(one_ms) / 1e6, 1),
+                              "per_instance_GBps_median": round(float(np.median(rates)), 1),
+                              "per_instance_GBps_p10": round(float(np.percentile(rates, 10)), 1),
+                              "large_only_GBps": round(sum(one_bytes[k] for k in big) / sum(one_ms[k] for k in big) / 1e6, 1) if big else None,
+                              "large_instances": len(big), "avg_launch_ms": round(float(np.mean(one_ms)), 5),
+                              "note": "same stream, every program its own launch; large = at least 256 MB of algorithmic bytes"}
+        if self.name == "c5_layers":
+            n_steps_stream = len(self.steps_T)
+            r["ms_per_32_layer_step"] = round(elapsed / steps / n_steps_stream * 1e3, 4)
+        return r
+
+
+def copy_ceiling(lib, ctx, dev, B):
+    """The library's own copy kernel on 512 MiB (beyond the last-level cache), both tile assignments; GB/s read + written."""
+    import torch
+    n = 512 * 2**20
+    src = torch.empty(n, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    stream = torch.cuda.current_stream()
+    out = {}
+    for mode, label in ((1, "interleaved"), (0, "blocked")):
+        for _ in range(2):
+            st = lib.dvm_copy_kernel(ctx._h, dst.data_ptr(), src.data_ptr(), n, mode, C.c_void_p(stream.cuda_stream))
+            if st != 0:
+                raise B.DvmError(st, "dvm_copy_kernel")
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        torch.cuda.synchronize()
+        for a, b in evs:
+            a.record(stream)
+            lib.dvm_copy_kernel(ctx._h, dst.data_ptr(), src.data_ptr(), n, mode, C.c_void_p(stream.cuda_stream))
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs)
+        out[label] = round(2.0 * n / (ms[len(ms) // 2] * 1e-3) / 1e9, 1)
+    ok = bool(torch.equal(src, dst))
+    del src, dst
+    return {"GBps": max(out.values()), "by_tile_assignment": out, "bytes_copied": n, "verified": ok,
+            "kernel": "dvm_copy_tiles (csrc/dvm_bench.hip): 16 B per lane and access, streaming hints; median of 10 launches"}
+
+
+def baseline_blocks(stream, name, cores, gen):
+    """Row blocks (one per worker) of one instance of a stream for the CPU oracle, with the GPU's outputs for the same rows."""
+    import torch
+    parts = stream.parts
+    blocks = []
+    if name == "c2_rmsnorm":
+        rows_per = 3072
+        i = max(range(len(parts)), key=lambda k: parts[k]["ins"][0].shape[0] * parts[k]["ins"][0].shape[1])
+        x, w = parts[i]["ins"]
+        y = parts[i]["outs"][0]
+        x2, y2 = x.reshape(-1, x.shape[-1]), y.reshape(-1, y.shape[-1])
+        nb = min(cores, x2.shape[0] // rows_per)
+        for b in range(nb):
+            sl = slice(b * rows_per, (b + 1) * rows_per)
+            blocks.append(({"x": x2[sl].cpu(), "w": w.cpu()}, {"y": y2[sl].cpu()}))
+        return "c2_rmsnorm", blocks, rows_per * 4096 * 2 * 2 + 4096 * 2, 2e-2
+    if name == "c4_chain":
+        rows_per = 512
+        i = max(range(len(parts)), key=lambda k: parts[k]["ins"][0].shape[0])
+        x, r, gamma, beta, bias, mask = parts[i]["ins"]
+        y = parts[i]["outs"][0]
+        nb = min(cores, x.shape[0] // rows_per)
+        for b in range(nb):
+            sl = slice(b * rows_per, (b + 1) * rows_per)
+            blocks.append(({"x": x[sl].cpu(), "r": r[sl].cpu(), "gamma": gamma.cpu(), "beta": beta.cpu(), "bias": bias.cpu(),
+                            "mask": mask[sl].cpu()}, {"y": y[sl].cpu()}))
+        return "c4_chain", blocks, rows_per * 8192 * 2 * 4 + 3 * 8192 * 2, 2e-2
+    if name == "c3_masked_softmax":
+        # one [S, S] plane (one batch index and head) per worker, of the instance whose S is nearest 2048
+        i = min(range(len(parts)), key=lambda k: abs(parts[k]["ins"][0].shape[-1] - 2048))
+        z, mask = parts[i]["ins"]
+        p = parts[i]["outs"][0]
+        S = z.shape[-1]
+        z3, p3 = z.reshape(-1, S, S), p.reshape(-1, S, S)
+        nb = min(cores, z3.shape[0])
+        mh = mask.cpu()
+        for b in range(nb):
+            blocks.append(({"z": z3[b].cpu(), "mask": mh}, {"p": p3[b].cpu()}))
+        return "c3_masked_softmax", blocks, S * S * 4 * 2 + S * S * 4, 1e-4
+    return name, [], 0, 0.0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="c2_rmsnorm",
-                    choices=["c1_gelu", "c2_rmsnorm", "c3_masked_softmax", "c4_chain", "c5_layers", "layernorm_bf16", "if_else_add",
-                             "column_sum"])
+    ap.add_argument("--workload", default="suite", choices=["suite"] + ALL_WORKLOADS)
     ap.add_argument("--instances", type=int, default=0, help="use only the first N instances (0 = the workload's default)")
     ap.add_argument("--stack", type=int, default=0,
                     help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
@@ -164,11 +597,14 @@ def main() -> int:
     ap.add_argument("--stacking", default="", choices=["", "temporal", "spatial"],
                     help="how the parts of a launch share it: one after the other on all workgroups (temporal) or side by "
                          "side on shares of the workgroups (spatial); default temporal (it measured faster on every workload here)")
+    ap.add_argument("--assignment", default="", choices=["", "blocked", "interleaved"],
+                    help="how tiles are dealt out to workgroups: Algorithm 2's blocked ranges or round-robin (the library's default)")
+    ap.add_argument("--limits", default="", help="K,NR: bound the interpreter variant the planner may choose (dvm_ctx_set_limits), for tuning")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-unstacked", action="store_true",
                     help="leave out the second pass that launches every program on its own (profiler runs use this so "
                          "that the kernel statistics cover the stacked launches only)")
-    ap.add_argument("--dump-launches", default="", help="write per-program bytes and mean launch time to this CSV file")
+    ap.add_argument("--dump-launches", default="", help="append per-program bytes and mean launch time to this CSV file")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region run a plain 256 MiB device copy (a known-size kernel that scales "
                          "the HBM byte counters of a profiler run)")
@@ -178,6 +614,17 @@ def main() -> int:
               "run with --gpus 1", file=sys.stderr)
         return 2
 
+    # worker processes of the CPU baseline are forked before anything touches the GPU
+    names = SUITE if args.workload == "suite" else [args.workload]
+    want_cpu = not args.no_cpu_baseline and args.workload != "if_else_add" and any(n in LARGE_CLASS for n in names)
+    cpu = CpuBaseline(want_cpu)
+    try:
+        return run(args, names, cpu)
+    finally:
+        cpu.close()
+
+
+def run(args, names, cpu) -> int:
     import numpy as np
     import torch
     from paper_2603_24239_amd import binding as B
@@ -191,193 +638,37 @@ def main() -> int:
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     ctx = B.Context(0)
+    if args.assignment:
+        ctx.set_assignment(args.assignment)
+    if args.limits:
+        k_, nr_ = (int(v) for v in args.limits.split(","))
+        ctx.set_limits(k_, nr_)
     if args.workload == "if_else_add":
         return bench_fuser(args, B, gen, W, ctx, dev)
-    progs = {}
 
-    def program(name):
-        if name not in progs:
-            progs[name] = (W.get_program(name), B.Program(W.get_program(name)))
-        return progs[name]
+    per = {}
+    for name in names:
+        print(f"bench.py: {name}: generating inputs", file=sys.stderr, flush=True)
+        s = Stream(name, args, B, gen, W, ctx, dev)
+        print(f"bench.py: {name}: timing {args.steps} step(s)", file=sys.stderr, flush=True)
+        r = s.run(lib, args.steps, args.warmup, unstacked=not args.skip_unstacked)
+        if cpu.enabled and name in LARGE_CLASS:
+            dn, blocks, bpb, rtol = baseline_blocks(s, name, cpu.cores, gen)
+            print(f"bench.py: {name}: CPU oracle on {len(blocks)} row blocks", file=sys.stderr, flush=True)
+            cpu.leg(name, dn, blocks, bpb, rtol)
+        s.ctx_restore()
+        per[name] = r
+        del s
+        torch.cuda.empty_cache()
 
-    # ---- synthetic inputs, resident in HBM -----------------------------------------------------
-    # a part is one program applied to one set of tensors; `groups` lists the parts of each launch
-    parts = []
+    if args.workload == "suite":
+        # config 1 is latency-bound: time per launch and per encode + launch + synchronise
+        s = Stream("c1_gelu", args, B, gen, W, ctx, dev)
+        r1 = s.run(lib, 200, 20, unstacked=False)
+        per["c1_gelu"] = r1
+        del s
 
-    def add_part(name, ins_d, nbytes, shape, outs=None):
-        desc, prog = program(name)
-        ins = [ins_d[n] for n, _ in desc.inputs]
-        if outs is None:
-            shapes = [tuple(t.shape) for t in ins]
-            full = max(shapes, key=lambda sh: (len(sh), int(np.prod(sh))))
-            out_shape = tuple(np.broadcast_shapes(*shapes)) if len(shapes) > 1 else full
-            outs_l = [torch.empty(out_shape, dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device=dev)
-                      for _, dt in desc.outputs]
-            layout = None
-        else:
-            outs_l = [outs[n] for n, _ in desc.outputs]
-            layout = (B.dvm_shape * len(outs_l))(*[B.shape_of_tensor(t) for t in outs_l])
-        parts.append({"name": name, "desc": desc, "prog": prog, "ins": ins, "outs": outs_l, "bytes": nbytes, "shape": shape,
-                      "shapes": (B.dvm_shape * len(ins))(*[B.shape_of_tensor(t) for t in ins]), "layout": layout})
-
-    fixed_groups = None
-    default_budget = 4e8        # elements of the first input the CPU oracle is given (about 10-30 s)
-    if args.workload == "c2_rmsnorm":
-        shapes = gen.c2_shapes()[: args.instances or None]
-        for i, (b, s) in enumerate(shapes):
-            add_part("c2_rmsnorm", gen.c2_inputs(b, s, gen.BASE_SEED + 2000 + i, dev), gen.c2_bytes(b, s), (b, s))
-        wl = {"workload": "config 2: fused RMSNorm bf16, x[B,S,4096], 200 dynamic instances (B 1..32, S 1..2048)",
-              "instances": len(parts), "hidden": 4096, "eps": 1e-6}
-    elif args.workload == "layernorm_bf16":
-        # the LayerNorm subgraph range of the paper's Table 2 ([b, 8192, h]); the first 24 of the seeded stream
-        shapes = gen.layernorm_paper_shapes()[: args.instances or 24]
-        for i, (b, s_, h) in enumerate(shapes):
-            add_part("layernorm_bf16", gen.layernorm_inputs(b, s_, h, gen.BASE_SEED + 6000 + 3 * i, dev),
-                     gen.layernorm_bytes(b, s_, h), (b, s_, h))
-        wl = {"workload": "LayerNorm bf16 over [b, 8192, h], b 1..60, h in {1024, 2048, 3072, 4096} (the paper's Table 2 range), eps 1e-5",
-              "instances": len(parts)}
-    elif args.workload == "column_sum":
-        # Table 1's Sum in its general form: [M, size, N] reduced along `size` to [M, 1, N], fp32
-        shapes = gen.column_sum_shapes()[: args.instances or None]
-        for i, (m, size, n) in enumerate(shapes):
-            x = gen.randn((m, size, n), gen.BASE_SEED + 8000 + i, dev)
-            add_part("colsum", {"x": x}, gen.column_sum_bytes(m, size, n), (m, size, n),
-                     {"s": torch.empty((m, 1, n), dtype=torch.float32, device=dev)})
-        wl = {"workload": "sum along the penultimate axis fp32, [M,size,N] -> [M,1,N], 48 dynamic instances "
-                          "(M 1..256, size 16..4096, N 512..4096)", "instances": len(parts)}
-    elif args.workload == "c4_chain":
-        shapes = gen.c4_shapes()[: args.instances or None]
-        for i, t in enumerate(shapes):
-            add_part("c4_chain", gen.c4_inputs(t, gen.BASE_SEED + 4000 + i, dev), gen.c4_bytes(t), (t,))
-        wl = {"workload": "config 4: 12-op transformer non-GEMM chain bf16 over [T,8192], 100 dynamic instances",
-              "instances": len(parts), "hidden": 8192}
-        default_budget = 2e8
-    elif args.workload == "c1_gelu":
-        add_part("c1_gelu_erf", gen.c1_inputs(gen.BASE_SEED + 1, dev), 4 * 1000 * 4 * 2 + 2 * 1000 * 4, (4, 1000))
-        wl = {"workload": "config 1: gelu(x*a+b) fp32 on [4,1000] (latency-bound)", "instances": 1}
-    elif args.workload == "c3_masked_softmax":
-        # the first 16 instances of the seeded stream (the whole stream is 185 GB of traffic)
-        shapes = gen.c3_shapes()[: args.instances or 16]
-        for i, (b, s) in enumerate(shapes):
-            add_part("c3_masked_softmax", gen.c3_inputs(b, s, gen.BASE_SEED + 3000 + i, dev), gen.c3_bytes(b, s), (b, s))
-        wl = {"workload": "config 3: causal-masked softmax fp32 over [B,32,S,S] (B 1..4, S 128..4096), mask [S,S] broadcast",
-              "instances": len(parts)}
-        default_budget = 1.5e8
-    else:
-        # config 5: 64 steps of a 32-layer stack, six programs per layer, T log-normal; one buffer set per
-        # step shared by its 32 layers; every layer is one launch (its six programs stacked)
-        ctx.set_limits(16, 6)       # parts that share a launch must fit one interpreter variant
-        steps_T = gen.c5_steps()[: args.instances or None]
-        fixed_groups = []
-        for si, T in enumerate(steps_T):
-            d = gen.c5_inputs(T, gen.BASE_SEED + 5000 + 100 * si, dev)
-            rope_out = torch.empty((T, 32, 128), dtype=torch.bfloat16, device=dev)
-            L = T // 8 + 1
-            first = len(parts)
-            add_part("c5_rmsnorm", d["c5_rmsnorm"], (2 * T * 4096 + 4096) * 2, (T,))
-            add_part("c5_rope", d["c5_rope"], 2 * T * 32 * 128 * 2 + 2 * T * 64 * 4, (T,),
-                     {"y1": rope_out[..., :64], "y2": rope_out[..., 64:]})
-            add_part("c5_softmax", d["c5_softmax"], 2 * 32 * T * L * 2, (T,))
-            add_part("c5_residual", d["c5_residual_a"], 3 * T * 4096 * 2, (T,))
-            add_part("c5_silu_gate", d["c5_silu_gate"], 3 * T * 14336 * 2, (T,))
-            add_part("c5_residual", d["c5_residual_b"], 3 * T * 4096 * 2, (T,))
-            layer = list(range(first, first + 6))
-            fixed_groups += [layer] * 32
-        wl = {"workload": "config 5: 64 steps x 32 layers x {rmsnorm, rope, softmax, residual, silu-gate, residual} bf16, "
-                          "T log-normal (median 512, 1..8192); one launch per layer",
-              "instances": len(fixed_groups), "steps_of_the_stream": len(steps_T)}
-        default_budget = 1.5e8
-    torch.cuda.synchronize()
-
-    # ---- launches: lists of part indices -------------------------------------------------------
-    enc_cap = 8192
-    if fixed_groups is not None:
-        groups_idx = fixed_groups
-        group = 6
-        singles_idx = [[i] for g in fixed_groups for i in g]
-    else:
-        n_t_part = len(parts[0]["ins"]) + len(parts[0]["outs"])
-        max_group = max(1, min(32 // n_t_part, 10))
-        # default: eight per launch; config 3's instances are gigabytes each and differ in row length (a stacked
-        # launch runs all its parts with the largest tile register size among them), so they stay apart
-        # (and a column sum's workgroup and tile register size depend on its shape: one launch each as well)
-        default_stack = 1 if args.workload in ("c3_masked_softmax", "column_sum") else 8
-        group = max(1, min(args.stack if args.stack > 0 else default_stack, max_group))
-        groups_idx = [list(range(lo, min(lo + group, len(parts)))) for lo in range(0, len(parts), group)]
-        singles_idx = [[i] for i in range(len(parts))]
-    total_bytes = sum(parts[i]["bytes"] for g in groups_idx for i in g)
-
-    def marshal(groups):
-        out = []
-        for idx in groups:
-            tens = [t for i in idx for t in parts[i]["ins"] + parts[i]["outs"]]
-            out.append((idx, (C.c_void_p * len(tens))(*[t.data_ptr() for t in tens]), len(tens)))
-        return out
-
-    max_parts = max(len(g) for g in groups_idx)
-    part_bufs = [C.create_string_buffer(enc_cap) for _ in range(max_parts)]
-    part_ptrs = (C.c_void_p * max_parts)(*[C.cast(b, C.c_void_p) for b in part_bufs])
-    part_lens = (C.c_size_t * max_parts)()
-    stacked = C.create_string_buffer(enc_cap)
-    ln = C.c_size_t()
-    stream = torch.cuda.current_stream()
-    stream_h = C.c_void_p(stream.cuda_stream)
-    perf = time.perf_counter
-
-    stacking = args.stacking or "temporal"
-    stack_fn = lib.dvm_stack_spatial if stacking == "spatial" else lib.dvm_stack
-
-    def one_step(groups, events=None, enc_us=None):
-        """Encode every part, stack the parts of each launch (temporal stacking; a single part is launched
-        as it is), run."""
-        for k, (idx, ptrs, n_t) in enumerate(groups):
-            for j, i in enumerate(idx):
-                pt = parts[i]
-                t0 = perf()
-                st = lib.dvm_encode(ctx._h, pt["prog"]._h, pt["shapes"], len(pt["ins"]), pt["layout"], part_bufs[j], enc_cap,
-                                    C.byref(ln), None)
-                t1 = perf()
-                if st != 0:
-                    raise B.DvmError(st, "dvm_encode")
-                part_lens[j] = ln.value
-                if enc_us is not None:
-                    enc_us.append((t1 - t0) * 1e6)
-            if len(idx) == 1:
-                code, code_len = part_bufs[0], part_lens[0]
-            else:
-                st = stack_fn(part_ptrs, part_lens, len(idx), stacked, enc_cap, C.byref(ln))
-                if st != 0:
-                    raise B.DvmError(st, "dvm_stack")
-                code, code_len = stacked, ln.value
-            if events is not None:
-                events[k][0].record(stream)
-            st = lib.dvm_run(ctx._h, code, code_len, ptrs, n_t, stream_h)
-            if st != 0:
-                raise B.DvmError(st, "dvm_run")
-            if events is not None:
-                events[k][1].record(stream)
-
-    def timed(groups, steps, warmup, enc_us=None):
-        for _ in range(warmup):
-            one_step(groups)
-        evs = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in groups]
-               for _ in range(steps)]
-        torch.cuda.synchronize()
-        t0 = perf()
-        for s in range(steps):
-            one_step(groups, evs[s], enc_us)
-        torch.cuda.synchronize()
-        return perf() - t0, evs
-
-    groups = marshal(groups_idx)
-    enc_us = []
-    elapsed, all_events = timed(groups, args.steps, args.warmup, enc_us)
-
-    # the same stream with every program as its own launch (no stacking): per-program launch times
-    unstacked = not args.skip_unstacked
-    if unstacked:
-        singles = marshal(singles_idx)
-        elapsed1, events1 = timed(singles, args.steps, 1) if group > 1 else (elapsed, all_events)
+    ceiling = copy_ceiling(lib, ctx, dev, B)
 
     if args.calibrate_copy:
         src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -386,118 +677,74 @@ def main() -> int:
             dst.copy_(src)
         torch.cuda.synchronize()
 
-    ms_per_step = elapsed / args.steps * 1e3
-    value = total_bytes * args.steps / elapsed / 1e9
-    kern_ms = [a.elapsed_time(b) for evs in all_events for (a, b) in evs]
-    avg_launch_ms = float(np.mean(kern_ms))
-    bytes_per_launch = total_bytes / len(groups)
-    achieved = bytes_per_launch / (avg_launch_ms * 1e-3) / 1e9
-    large = single = None
-    if unstacked:
-        one_ms = [float(np.mean([events1[s][k][0].elapsed_time(events1[s][k][1]) for s in range(args.steps)]))
-                  for k in range(len(singles_idx))]
-        one_bytes = [parts[g[0]]["bytes"] for g in singles_idx]
-        if args.dump_launches:
-            with open(args.dump_launches, "w") as f:
-                f.write("launch,program,shape,bytes,mean_launch_us,GBps\n")
-                for k, g in enumerate(singles_idx):
-                    pt = parts[g[0]]
-                    f.write(f"{k},{pt['name']},{'x'.join(map(str, pt['shape']))},{pt['bytes']},{one_ms[k] * 1e3:.2f},"
-                            f"{pt['bytes'] / one_ms[k] / 1e6:.1f}\n")
-        # the large launches (beyond the 256 MB Infinity Cache), each program on its own
-        big = [k for k, b in enumerate(one_bytes) if b >= 256e6]
-        if big:
-            large = {"launches": len(big),
-                     "GBps": round(sum(one_bytes[k] for k in big) / sum(one_ms[k] for k in big) / 1e6, 1)}
-        single = {"value": round(total_bytes * args.steps / elapsed1 / 1e9, 2), "unit": "GB/s",
-                  "ms_per_step": round(elapsed1 / args.steps * 1e3, 4),
-                  "avg_launch_ms": round(float(np.mean(one_ms)), 5),
-                  "achieved": round(sum(one_bytes) / sum(one_ms) / 1e6, 2),
-                  "note": "same stream, every program its own launch, HIP events around every launch"}
-    enc = np.array(enc_us)
+    # ---- aggregate: the large memory-bound configs ----------------------------------------------------
+    head = [n for n in names if n in LARGE_CLASS] or names
+    tot_bytes_step = sum(per[n]["total_bytes"] for n in head)
+    wall_step = sum(per[n]["elapsed_s"] / per[n]["steps"] for n in head)
+    kern_step_ms = sum(per[n]["kernel_ms_sum_per_step"] for n in head)
+    launches_step = sum(per[n]["launches_per_step"] for n in head)
+    value = tot_bytes_step / wall_step / 1e9
+    achieved = tot_bytes_step / kern_step_ms / 1e6
+    ratios = {n: measured_traffic_ratio(n) for n in head}
+    traffic = None
+    if all(v is not None for v in ratios.values()) and not args.instances and not args.stack and not args.stacking and not args.assignment and not args.limits:
+        traffic = int(sum(per[n]["total_bytes"] * ratios[n] for n in head) / launches_step)
+    ms_per_step = sum(per[n]["elapsed_s"] / per[n]["steps"] for n in names if n in per) * 1e3
 
-    wl["instances_per_launch"] = group
-    wl["stacking"] = stacking if group > 1 else "none"
+    per_config = {}
+    for n, r in per.items():
+        frac = r["kernel_GBps"] / HBM_PEAK_GBS
+        pc = {"workload": r["config"]["workload"], "instances": r["config"]["instances"],
+              "instances_per_launch": r["config"]["instances_per_launch"], "dtype": r["dtype"],
+              "whole_job_GBps": round(r["whole_job_GBps"], 1), "kernel_GBps": round(r["kernel_GBps"], 1), "frac": round(frac, 4),
+              "pct_of_copy_ceiling": round(100.0 * r["kernel_GBps"] / ceiling["GBps"], 1),
+              "ms_per_pass": round(r["elapsed_s"] / r["steps"] * 1e3, 4), "launches_per_pass": r["launches_per_step"],
+              "large_launches_GBps": round(r["large_launches"]["GBps"], 1) if r["large_launches"] else None,
+              "traffic_ratio": measured_traffic_ratio(n), "encode_us": r["encode_us"], "unstacked": r["unstacked"]}
+        if "ms_per_32_layer_step" in r:
+            pc["ms_per_32_layer_step"] = r["ms_per_32_layer_step"]
+        if n == "c1_gelu":
+            pc["us_per_encode_and_launch"] = round(r["elapsed_s"] / r["steps"] * 1e6, 2)
+        per_config[n] = pc
+    big_b = sum(per[n]["large_launches"]["bytes"] for n in head if per[n]["large_launches"])
+    big_ms = sum(per[n]["large_launches"]["ms"] for n in head if per[n]["large_launches"])
+
+    dtypes = sorted({per[n]["dtype"] for n in head})
+    if args.workload == "suite":
+        wl = {"workload": "configs 2, 3 and 4 (the large memory-bound dynamic streams: RMSNorm bf16 x 200, causal-masked softmax fp32 x 50, "
+                          "12-op chain bf16 x 100), run one after the other; config 5 (32-layer model stream) and config 1 (latency) "
+                          "are timed in the same job and reported under per_config",
+              "instances": sum(per[n]["config"]["instances"] for n in head)}
+    else:
+        wl = per[names[0]]["config"]
     result = {
         "metric": "achieved HBM GB/s of VM-run fused ops (algorithmic bytes / wall time, encode included)",
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic", "config": wl,
+        "dtype": "; ".join(dtypes), "data": "synthetic", "config": wl,
         "pct_of_hbm_peak": round(100.0 * value / HBM_PEAK_GBS, 2),
-        "encode_us_per_instance": {"median": round(float(np.median(enc)), 2), "p99": round(float(np.percentile(enc, 99)), 2),
-                                   "max": round(float(enc.max()), 2), "note": "dvm_encode timed through ctypes"},
-        "large_instances": large, "one_launch_per_instance": single,
         "roofline": {"bound": "hbm", "kernel": "dvm_vm_kernel (bytecode interpreter)", "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "bytes_per_launch": int(bytes_per_launch), "avg_launch_ms": round(avg_launch_ms, 5),
-                     "launches": len(kern_ms), "instances_per_launch": group,
-                     "traffic": measured_traffic(args.workload) if not args.instances and not args.stack and not args.stacking else None},
+                     "bytes_per_launch": int(tot_bytes_step / launches_step), "avg_launch_ms": round(kern_step_ms / launches_step, 5),
+                     "launches": launches_step * args.steps,
+                     "large_launches_GBps": round(big_b / big_ms / 1e6, 1) if big_ms else None,
+                     "pct_of_copy_ceiling": round(100.0 * achieved / ceiling["GBps"], 1),
+                     "traffic": traffic,
+                     "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --workload <config>`, summaries under profiles/"
+                                       if traffic is not None else None},
+        "copy_ceiling": ceiling,
+        "per_config": per_config,
     }
-
-    # ---- the CPU oracle on a bounded sample of the same workload (a baseline, not the target) -----
-    if not args.no_cpu_baseline:
-        from oracle import interp
-        budget = default_budget
-        # distinct parts in stream order while they fit the budget (elements of the first input); if none
-        # fits, the leading rows of the first part (its rows are independent and its other inputs are vectors)
-        used, sample, seen = 0.0, [], set()
-        for g in groups_idx:
-            for i in g:
-                n_el = parts[i]["ins"][0].numel()
-                if i in seen or n_el > budget - used:
-                    continue
-                seen.add(i)
-                sample.append((i, None))
-                used += n_el
-            if len(sample) >= 40 or used >= 0.9 * budget:
-                break
-        if not sample:
-            x = parts[0]["ins"][0]
-            sample.append((0, max(1, int(budget // x.shape[-1]))))
-            used = sample[0][1] * x.shape[-1]
-
-        def head_rows(t, lead, n):
-            """The first n rows of a tensor with the full leading shape; broadcast vectors stay whole."""
-            if n is None or t.dim() < 2 or tuple(t.shape[:-1]) != lead:
-                return t
-            return t.reshape(-1, t.shape[-1])[:n]
-        host_inputs = []
-        for i, n in sample:
-            pt = parts[i]
-            lead = tuple(pt["ins"][0].shape[:-1])
-            host_inputs.append({nm: head_rows(t, lead, n).detach().cpu().to(torch.float64).numpy()
-                                for (nm, _), t in zip(pt["desc"].inputs, pt["ins"])})
-        t0 = perf()
-        refs = [interp.run(parts[i]["desc"], hi) for (i, _), hi in zip(sample, host_inputs)]
-        cpu_s = perf() - t0
-        cpu_bytes = sum(parts[i]["bytes"] * (1.0 if n is None else n / (parts[i]["ins"][0].numel() // parts[i]["ins"][0].shape[-1]))
-                        for i, n in sample)
-        # the same sample doubles as an end-to-end check of the benchmarked path
-        worst = 0.0
-        for (i, n), (rounded, exact) in zip(sample, refs):
-            pt = parts[i]
-            for (nm, dt), out_t in zip(pt["desc"].outputs, pt["outs"]):
-                got = out_t.detach().cpu().to(torch.float64).numpy()
-                ref = rounded[nm]
-                if n is not None:
-                    got = got.reshape(-1, got.shape[-1])[:n]
-                    ref = ref.reshape(-1, ref.shape[-1])
-                rtol = 2e-2 if dt == "bf16" else 1e-4
-                scale = np.broadcast_to(interp.row_scale(exact[nm]).reshape(ref.shape[:-1] + (1,)), ref.shape)
-                tol = rtol * np.abs(ref) + rtol * scale
-                fin = np.isfinite(ref)
-                worst = max(worst, float(np.max(np.where(fin, np.abs(got - ref) / np.maximum(tol, 1e-300), 0.0))))
-        result["cpu_baseline"] = {"value": round(cpu_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": 1, "kind": "oracle",
-                                  "sample": f"{len(sample)} programs (or their leading rows) of the same stream, "
-                                            f"{int(used)} elements of their first inputs, "
-                                            f"{cpu_s:.1f} s of NumPy float64 per-op evaluation",
-                                  "max_err_over_tol_vs_gpu": round(worst, 4)}
-        if worst > 1.0:
-            print(f"bench.py: GPU output differs from the oracle on the sample (x{worst:.3g} of tolerance)", file=sys.stderr)
-            print(json.dumps(result))
-            return 1
+    base = cpu.result()
+    rc = 0
+    if base is not None:
+        result["cpu_baseline"] = base
+        if base["max_err_over_tol_vs_gpu"] > 1.0:
+            print(f"bench.py: GPU output differs from the oracle on the sample (x{base['max_err_over_tol_vs_gpu']:.3g} of tolerance)",
+                  file=sys.stderr)
+            rc = 1
     print(json.dumps(result))
-    return 0
+    return rc
 
 
 if __name__ == "__main__":

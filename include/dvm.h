@@ -120,6 +120,22 @@ int  dvm_ctx_set_planner(dvm_ctx *ctx, int n_compute_units, int tile_overhead_el
  * a program that needs more tile registers than allowed makes dvm_encode return DVM_E_UNSUPPORTED. */
 int  dvm_ctx_set_limits(dvm_ctx *ctx, int max_elems_per_lane, int max_tile_regs);
 
+/* Force parts of the tile plan instead of letting the cost model choose (tests and tuning walk plans the
+ * model would not pick): `elems_per_lane` (4, 8, 16 or 32) selects the interpreter variant's tile register
+ * size where the row length allows it, `rows_per_tile` the rows of a tile (for a reduction along the
+ * penultimate axis: the waves that share one unit of work), `grid_multiplier` launches that many workgroups
+ * per resident slot.  0 leaves a choice to the planner.  The bytecode depends on these settings and on the
+ * other context settings, the program and the shapes only; the library reads no environment variable. */
+int  dvm_ctx_set_plan_override(dvm_ctx *ctx, int elems_per_lane, int rows_per_tile, int grid_multiplier);
+/* How the M tiles of a meta-kernel are dealt out to the N workgroups of the launch (Section 4.3, Algorithm 2).
+ * DVM_ASSIGN_BLOCKED is the range the algorithm prints: workgroup id runs tiles [m*id, min(M, m*(id+1))) with
+ * m = ceil(M/N).  DVM_ASSIGN_INTERLEAVED (the default on this hardware) deals them out round-robin: workgroup
+ * id runs tiles id, id+N, id+2N, ... -- the same tiles per workgroup to within one, still static and free of
+ * atomics, but the resident workgroups sweep the tensors as one front, which HBM serves faster than N streams
+ * that lie far apart.  Results do not depend on the choice. */
+typedef enum dvm_assignment { DVM_ASSIGN_BLOCKED = 0, DVM_ASSIGN_INTERLEAVED = 1 } dvm_assignment;
+int  dvm_ctx_set_assignment(dvm_ctx *ctx, int assignment);
+
 /* ---- program builder (shape free) --------------------------------------------------------------- */
 typedef struct dvm_prog dvm_prog;
 
@@ -243,6 +259,18 @@ int  dvm_plan(int64_t total, int n_cores, int64_t t_max, int align, int overhead
  */
 int  dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len,
              void *const *tensors, int n_tensors, void *hip_stream);
+
+/* ---- measurement support (Section 6.1: run time and compile time are measured apart) ----------------- */
+/* dvm_encode called `reps` times on the same arguments, each call timed with CLOCK_MONOTONIC inside the library
+ * (no language binding between the clock and the encoder); ns[r] receives the duration of call r in nanoseconds,
+ * ns[0] being the first call for these shapes.  Everything else as dvm_encode (out_shapes is not filled). */
+int  dvm_encode_timed(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_shape *in_shapes, int n_in,
+                      const dvm_shape *out_layout, void *bytecode, size_t cap, size_t *len, int reps, int64_t *ns);
+/* A plain copy kernel of this library's own: `bytes` (a positive multiple of 16 KiB) from `src` to `dst` (DEVICE
+ * pointers, 16-byte aligned, not overlapping) on `hip_stream`, asynchronously; 16 bytes per lane and access,
+ * streaming cache hints, tiles dealt out to the workgroups as `assignment` says (dvm_assignment).  It is the
+ * bandwidth ceiling of a load-store loop on the device, measured beside the interpreter. */
+int  dvm_copy_kernel(const dvm_ctx *ctx, void *dst, const void *src, size_t bytes, int assignment, void *hip_stream);
 
 const char *dvm_strerror(int status);
 /* Detail text of the last error raised on the calling thread ("" if none). */

@@ -64,6 +64,13 @@ def vm_tile_range(n_tiles: int, n_cores: int, core_id: int) -> Tuple[int, int]:
     return lo, max(lo, hi)
 
 
+def interleaved_tiles(n_tiles: int, n_cores: int, core_id: int) -> List[int]:
+    """The round-robin alternative to Algorithm 2's blocked range that the library uses by default on the
+    GPU: core ``id`` runs tiles id, id + N, id + 2N, ...  Like the blocked range it is static, needs no
+    atomics and gives every core ceil(M/N) tiles or one fewer."""
+    return list(range(core_id, n_tiles, n_cores))
+
+
 def shape_tiling(dominant_shape: Sequence[int], t_max: int, n_cores: int, align: int,
                  extra: int = 2) -> List[int]:
     """Algorithm 1 for one dominant shape: walk the dimensions from the outermost inwards; a

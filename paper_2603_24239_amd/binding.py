@@ -75,6 +75,8 @@ def load() -> C.CDLL:
         "dvm_ctx_destroy": (None, [vp]),
         "dvm_ctx_set_planner": (i, [vp, i, i]),
         "dvm_ctx_set_limits": (i, [vp, i, i]),
+        "dvm_ctx_set_plan_override": (i, [vp, i, i, i]),
+        "dvm_ctx_set_assignment": (i, [vp, i]),
         "dvm_prog_create": (i, [P(vp)]),
         "dvm_prog_input": (i, [vp, i, P(i)]),
         "dvm_prog_op": (i, [vp, i, P(i), i, P(C.c_double), i, P(i)]),
@@ -92,6 +94,8 @@ def load() -> C.CDLL:
         "dvm_code_tensor": (i, [vp, sz, i, P(C.c_int64), P(i), P(i), P(i)]),
         "dvm_plan": (i, [C.c_int64, i, C.c_int64, i, i, P(C.c_int64), P(C.c_int64), P(C.c_int64)]),
         "dvm_run": (i, [vp, vp, sz, P(vp), i, vp]),
+        "dvm_encode_timed": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), i, P(C.c_int64)]),
+        "dvm_copy_kernel": (i, [vp, vp, vp, sz, i, vp]),
         "dvm_strerror": (C.c_char_p, [i]),
         "dvm_last_error_detail": (C.c_char_p, []),
         "dvm_last_hip_error": (i, []),
@@ -112,10 +116,11 @@ def load() -> C.CDLL:
     return lib
 
 
-EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_ctx_set_limits", "dvm_prog_create",
+EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_ctx_set_limits",
+            "dvm_ctx_set_plan_override", "dvm_ctx_set_assignment", "dvm_prog_create",
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
             "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_validate", "dvm_disasm",
-            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_strerror", "dvm_last_error_detail",
+            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_encode_timed", "dvm_copy_kernel", "dvm_strerror", "dvm_last_error_detail",
             "dvm_last_hip_error", "dvm_fuser_create", "dvm_fuser_destroy", "dvm_fuser_tensor", "dvm_fuser_op",
             "dvm_fuser_release", "dvm_fuser_flush", "dvm_fuser_stats", "dvm_fuser_last_code"]
 
@@ -167,6 +172,13 @@ class Context:
 
     def set_limits(self, max_elems_per_lane: int = 0, max_tile_regs: int = 0) -> None:
         _check(load().dvm_ctx_set_limits(self._h, max_elems_per_lane, max_tile_regs), "dvm_ctx_set_limits")
+
+    def set_plan_override(self, elems_per_lane: int = 0, rows_per_tile: int = 0, grid_multiplier: int = 0) -> None:
+        _check(load().dvm_ctx_set_plan_override(self._h, elems_per_lane, rows_per_tile, grid_multiplier),
+               "dvm_ctx_set_plan_override")
+
+    def set_assignment(self, assignment: str) -> None:
+        _check(load().dvm_ctx_set_assignment(self._h, {"blocked": 0, "interleaved": 1}[assignment]), "dvm_ctx_set_assignment")
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

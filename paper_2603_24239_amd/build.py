@@ -43,11 +43,16 @@ def build(verbose: bool = True) -> str:
     vm = os.path.join(CSRC, "dvm_vm.hip")
     jobs = [([hipcc, *COMMON, "-c", os.path.join(CSRC, "dvm_encode.cpp")], os.path.join(CSRC, "dvm_encode.o")),
             ([hipcc, *COMMON, "-c", os.path.join(CSRC, "dvm_fuser.cpp")], os.path.join(CSRC, "dvm_fuser.o")),
-            ([hipcc, *COMMON, *DEVICE, "-c", vm], os.path.join(CSRC, "dvm_vm_host.o"))]
+            ([hipcc, *COMMON, *DEVICE, "-c", vm], os.path.join(CSRC, "dvm_vm_host.o")),
+            ([hipcc, *COMMON, *DEVICE, "-c", os.path.join(CSRC, "dvm_bench.hip")], os.path.join(CSRC, "dvm_bench.o"))]
     # every interpreter variant is a translation unit of its own, compiled side by side
     for k, nr, maxt, waves in variants():
         defs = [f"-DDVM_VARIANT_K={k}", f"-DDVM_VARIANT_NR={nr}", f"-DDVM_VARIANT_MAXT={maxt}", f"-DDVM_VARIANT_WAVES={waves}"]
         jobs.append(([hipcc, *COMMON, *DEVICE, *defs, "-c", vm], os.path.join(CSRC, f"dvm_vm_k{k}_r{nr}.o")))
+    for k, nr, maxt, waves in variants():       # (the instantiation for launches whose rows all span whole waves)
+        defs = [f"-DDVM_VARIANT_K={k}", f"-DDVM_VARIANT_NR={nr}", f"-DDVM_VARIANT_MAXT={maxt}", f"-DDVM_VARIANT_WAVES={waves}",
+                "-DDVM_VARIANT_WIDE=1"]
+        jobs.append(([hipcc, *COMMON, *DEVICE, *defs, "-c", vm], os.path.join(CSRC, f"dvm_vm_w_k{k}_r{nr}.o")))
     for k, nr, maxt, waves in variants("DVM_CRED_VARIANT_LIST"):
         defs = [f"-DDVM_VARIANT_K={k}", f"-DDVM_VARIANT_NR={nr}", f"-DDVM_VARIANT_MAXT={maxt}", f"-DDVM_VARIANT_WAVES={waves}",
                 "-DDVM_VARIANT_CRED=1"]
@@ -55,7 +60,7 @@ def build(verbose: bool = True) -> str:
 
     # the variants with the most registers take the longest to compile: start them first
     def weight(job):
-        m = re.search(r"dvm_vm(?:_c)?_k(\d+)_r(\d+)\.o$", job[1])
+        m = re.search(r"dvm_vm(?:_c|_w)?_k(\d+)_r(\d+)\.o$", job[1])
         return -(int(m.group(1)) * int(m.group(2))) if m else 0
     jobs.sort(key=weight)
 

@@ -88,11 +88,13 @@ constexpr int LEN_REC = 4;              // length of every record except the vie
 constexpr uint32_t SF_WGSYNC  = 1u;     // rows span several waves: reductions use the barrier
 constexpr uint32_t SF_RAGGED  = 2u;     // some tile has invalid rows or columns: mask reductions
 constexpr uint32_t SF_CSTREAM = 4u;     // reducing segment whose per-row part is I_CSTREAM records only: one step per unit
+constexpr uint32_t SF_INTERLEAVED = 8u; // workgroup id runs tiles id, id + N, id + 2N, ... instead of Algorithm 2's blocked range
 
 // ---- instruction ids --------------------------------------------------------------------------
 enum : uint32_t {
     I_NOP = 0,
-    I_LOAD,      // contiguous rows, one row stride     a = dst, b = combine op (B_NONE: plain move)
+    I_LOAD,      // contiguous rows, one row stride     a = dst (b = 0).  Consecutive load records form a group: the
+                 // interpreter issues the requests of all of them before it waits for the first
     I_VLOAD,     // view load: three outer strides      (Table 1: ViewLoad)
     I_LOADS,     // one value per row -> S[a]
     I_STORE,     // a = src register; b != 0: multiply ACC by S[b-1] first   (Table 1: Store)
@@ -165,10 +167,10 @@ inline uint32_t w0(uint32_t op, uint32_t len, uint32_t a, uint32_t b) {
 // `cred`: also built as the instantiation that runs reductions along the penultimate axis.
 struct Variant { int K, NR, max_threads, waves_per_simd; bool cred; };
 constexpr Variant VARIANTS[] = {
-    { 4, 2, 1024, 8, true}, { 4, 6, 1024, 7, true},
-    { 8, 2, 1024, 6, true}, { 8, 6,  512, 4, true},
-    {16, 2, 1024, 4, false}, {16, 4,  512, 3, false}, {16, 6,  512, 2, true},
-    {32, 2,  256, 2, true}, {32, 4,  256, 2, true},
+    { 4, 2, 1024, 8, true}, { 4, 6, 1024, 8, true},
+    { 8, 2, 1024, 7, true}, { 8, 6,  512, 4, true},
+    {16, 2, 1024, 6, false}, {16, 4,  512, 4, false}, {16, 6,  512, 3, true},
+    {32, 2,  256, 4, true}, {32, 4,  256, 2, true},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 

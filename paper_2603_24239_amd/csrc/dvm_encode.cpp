@@ -88,10 +88,11 @@ struct dvm_ctx {
     int overhead;   // per-tile overhead of the cost model, in elements
     int max_k;      // largest elements-per-lane the planner may choose
     int max_nr;     // most tile registers a program may use
-    // tuning aids, settable through environment variables read once at dvm_ctx_create
-    int dbg_k;      // DVM_DEBUG_K: preferred elements per lane (0 = planner's choice)
-    int dbg_grid_x; // DVM_DEBUG_GRIDX: workgroups launched per resident slot (default 1)
-    int dbg_rp;     // DVM_DEBUG_RP: rows per tile (0 = cost model)
+    // plan overrides (dvm_ctx_set_plan_override): tests and tuning walk plans the cost model would not pick
+    int dbg_k;      // preferred elements per lane (0 = planner's choice)
+    int dbg_grid_x; // workgroups launched per resident slot (default 1)
+    int dbg_rp;     // rows per tile, or waves per unit of a reduction along the penultimate axis (0 = cost model)
+    int assignment; // DVM_ASSIGN_*: how the tiles of a meta-kernel are dealt out to the workgroups
 };
 
 extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
@@ -103,11 +104,10 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->overhead = 512;
     c->max_k = 32;
     c->max_nr = NR_LIMIT;
-    const char *e;
-    c->dbg_k = (e = getenv("DVM_DEBUG_K")) ? atoi(e) : 0;
-    c->dbg_grid_x = (e = getenv("DVM_DEBUG_GRIDX")) ? atoi(e) : 1;
-    c->dbg_rp = (e = getenv("DVM_DEBUG_RP")) ? atoi(e) : 0;
-    if (c->dbg_grid_x < 1) c->dbg_grid_x = 1;
+    c->dbg_k = 0;
+    c->dbg_grid_x = 1;
+    c->dbg_rp = 0;
+    c->assignment = DVM_ASSIGN_INTERLEAVED;
     if (hip_device >= 0) {
         int n = 0;
         int st = dvm_ctx_query_device(hip_device, &n);
@@ -125,6 +125,11 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
 }
 extern "C" void dvm_ctx_destroy(dvm_ctx *c) { delete c; }
 extern "C" int dvm_ctx_device(const dvm_ctx *c) { return c ? c->device : -1; }
+extern "C" void dvm_ctx_planner_get(const dvm_ctx *c, int *n_cu, int *overhead) {
+    if (!c) return;
+    if (n_cu) *n_cu = c->n_cu;
+    if (overhead) *overhead = c->overhead;
+}
 extern "C" int dvm_ctx_set_limits(dvm_ctx *c, int max_k, int max_nr) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
     if (max_k > 0) {
@@ -135,6 +140,25 @@ extern "C" int dvm_ctx_set_limits(dvm_ctx *c, int max_k, int max_nr) {
         if (max_nr != 2 && max_nr != 4 && max_nr != 6) return dvm_set_error(DVM_E_ARGS, "tile registers must be 2, 4 or 6");
         c->max_nr = max_nr;
     }
+    return DVM_OK;
+}
+
+extern "C" int dvm_ctx_set_plan_override(dvm_ctx *c, int elems_per_lane, int rows_per_tile, int grid_multiplier) {
+    if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
+    if (elems_per_lane != 0 && elems_per_lane != 4 && elems_per_lane != 8 && elems_per_lane != 16 && elems_per_lane != 32)
+        return dvm_set_error(DVM_E_ARGS, "elements per lane must be 0, 4, 8, 16 or 32");
+    if (rows_per_tile < 0 || rows_per_tile > 1024) return dvm_set_error(DVM_E_ARGS, "rows per tile must be 0 .. 1024");
+    if (grid_multiplier < 0 || grid_multiplier > 64) return dvm_set_error(DVM_E_ARGS, "grid multiplier must be 0 .. 64");
+    c->dbg_k = elems_per_lane;
+    c->dbg_rp = rows_per_tile;
+    c->dbg_grid_x = grid_multiplier > 0 ? grid_multiplier : 1;
+    return DVM_OK;
+}
+
+extern "C" int dvm_ctx_set_assignment(dvm_ctx *c, int assignment) {
+    if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
+    if (assignment != DVM_ASSIGN_BLOCKED && assignment != DVM_ASSIGN_INTERLEAVED) return dvm_set_error(DVM_E_ARGS, "unknown tile assignment");
+    c->assignment = assignment;
     return DVM_OK;
 }
 
@@ -1207,14 +1231,11 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                     if (E.reg_of[b] >= 0) {
                         E.emit(I_BIN, (uint8_t)E.reg_of[b], (uint8_t)op);
                     } else if (E.is_input(b)) {
-                        // (a load combines into the accumulator with add, sub, reversed sub and mul only)
-                        const bool combines = op == B_ADD || op == B_SUB || op == B_RSUB || op == B_MUL;
-                        if ((E.uses[b] == 1 || E.reload_inputs) && combines) {
-                            E.emit(I_LOAD, (uint8_t)SRC_ACC, (uint8_t)op, E.tensor_of_input(b));
-                        } else {
-                            const int r = E.to_reg(b);
-                            E.emit(I_BIN, (uint8_t)r, (uint8_t)op);
-                        }
+                        // the operand is loaded into a tile register of its own (its load then shares a group with
+                        // the loads before it); when inputs are not kept, the register is free again after the op
+                        const int r = E.to_reg(b);
+                        E.emit(I_BIN, (uint8_t)r, (uint8_t)op);
+                        if (E.reload_inputs && E.uses[b] > 1) { E.regs[r] = -1; E.reg_of[b] = -1; }
                     } else {
                         E.fail(DVM_E_UNSUPPORTED, "internal: operand lost during linearisation");
                     }
@@ -1521,7 +1542,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (nct > 1) magic_u32(nct, &sh[S_NCTM], &sh[S_NCTSH]);
     sh[S_TBASE] = 0;
     sh[S_NTENS] = (uint32_t)E.n_acc;
-    sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0) | (E.has_cred && E.cstream ? SF_CSTREAM : 0);
+    sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0) | (E.has_cred && E.cstream ? SF_CSTREAM : 0) |
+                  (ctx->assignment == DVM_ASSIGN_INTERLEAVED ? SF_INTERLEAVED : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
     if (E.has_cred) {
@@ -1740,9 +1762,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     want = (op == I_LOAD || op == I_STORE) ? LEN_LOAD : LEN_VLOAD;
                     if (l != want) return bad("memory instruction length");
                     if (a != SRC_ACC && !reg_ok(a, vr)) return bad("tile register index");
-                    if ((op == I_LOAD || op == I_VLOAD)
-                            ? (!(bb == B_NONE || bb == B_ADD || bb == B_SUB || bb == B_RSUB || bb == B_MUL) || (a != SRC_ACC && bb != B_NONE))
-                            : (bb > (uint32_t)NS || (bb != 0 && a != SRC_ACC)))
+                    if ((op == I_LOAD || op == I_VLOAD) ? bb != B_NONE : (bb > (uint32_t)NS || (bb != 0 && a != SRC_ACC)))
                         return bad("combine op");
                     const uint32_t w1 = w[pc + 1];
                     if ((w1 & 0xFF) >= nt) return bad("tensor index");
@@ -2091,10 +2111,11 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
         const uint32_t M = sh[S_NTILES], N = w[PH_GRID];
         const uint32_t body_tile = N ? (M + N - 1) / N : 0;
         o.put("segment %u: tiles=%u body_tile=%u code_size=%u rows=%u row_len=%llu lanes_per_row=%u chunk=%u chunks_per_lane=%u "
-              "rows_per_tile=%u col_tiles=%u tile_cols=%u outer=[%u,%u] tensor_base=%u\n",
+              "rows_per_tile=%u col_tiles=%u tile_cols=%u outer=[%u,%u] tensor_base=%u tiles_to_workgroups=%s\n",
               s, M, body_tile, sh[S_CODESIZE] * 4, sh[S_NROWS],
               (unsigned long long)((uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32)), sh[S_GEOM] & 0xFFFF,
-              (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE]);
+              (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE],
+              (sh[S_FLAGS] & SF_INTERLEAVED) ? "interleaved" : "blocked");
         size_t pc = at + SH_WORDS;
         const size_t end = pc + sh[S_CODESIZE];
         if (sh[S_PROLOGA]) o.put("  ; prologue (once per workgroup)\n");

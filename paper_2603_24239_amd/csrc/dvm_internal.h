@@ -12,6 +12,8 @@ extern "C" {
 int dvm_set_error(int status, const char *detail);
 // HIP device the context was created for, or -1.
 int dvm_ctx_device(const dvm_ctx *ctx);
+// Planner inputs of the context (either pointer may be null).
+void dvm_ctx_planner_get(const dvm_ctx *ctx, int *n_cu, int *overhead);
 // Implemented in the device file so that the encoder object stays free of HIP calls.
 int dvm_ctx_query_device(int hip_device, int *n_cu);
 

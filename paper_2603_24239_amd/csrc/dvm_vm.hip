@@ -60,10 +60,12 @@ DI float f_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 DI float f_rsq(float x) { return __builtin_amdgcn_rsqf(x); }
 DI float f_sqrt(float x) { return __builtin_amdgcn_sqrtf(x); }
 DI float f_fma(float a, float b, float c) { return __builtin_fmaf(a, b, c); }
-// IEEE maxNum / minNum (a NaN operand yields the other one) as the single hardware instruction; the
-// compiler's own lowering of fmaxf first canonicalises both operands, three instructions per use
-DI float f_max(float a, float b) { float r; asm("v_max_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
-DI float f_min(float a, float b) { float r; asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b)); return r; }
+// Table 1's Max / Min are read as propagating a NaN operand (what NumPy's maximum / minimum and the frameworks
+// this VM serves do).  gfx950 has that operation as one instruction (v_maximum3_f32 / v_minimum3_f32), which the
+// compiler selects for the IEEE-754-2019 maximum / minimum builtins: element-wise ops and every stage of a
+// reduction use it, so a NaN anywhere in a row or column reaches the result.
+DI float f_maxp(float a, float b) { return __builtin_elementwise_maximum(a, b); }
+DI float f_minp(float a, float b) { return __builtin_elementwise_minimum(a, b); }
 
 constexpr float LOG2E    = 1.44269504088896340736f;
 constexpr float LOG2E_LO = 1.92596303e-8f;      // log2(e) - (float)log2(e)
@@ -127,7 +129,24 @@ DI float f_erf(float x) {
     return __builtin_copysignf(r, x);
 }
 DI float f_gelu_erf(float u) { return 0.5f * u * (1.0f + f_erf(u * 0.70710678118654752f)); }
-DI float f_pow(float a, float b) { return f_exp2(b * f_log2(a)); }
+// pow(a, b) = 2^(b log2 |a|) with the sign and the special cases of the C library's pow: a finite negative base
+// is defined for integer exponents only (odd ones keep the sign), pow(x, 0) = pow(1, y) = 1 for every x and y,
+// pow(-1, +-inf) = 1; zeros and infinities fall out of log2 and exp2.
+DI float f_pow(float a, float b) {
+    // (conditions are combined with integer and / or: a logical && would become a branch that differs between lanes)
+    const float aa = __builtin_fabsf(a), ab = __builtin_fabsf(b);
+    float r = f_exp2(b * f_log2(aa));
+    const int b_int = __builtin_truncf(b) == b;
+    const float half = 0.5f * b;
+    const int b_odd = b_int & (int)(__builtin_truncf(half) != half) & (int)(ab < 16777216.0f);
+    const int neg_base = (__builtin_bit_cast(uint32_t, a) >> 31) != 0;
+    const int no_real_power = (int)(a < 0.0f) & (int)(aa < __builtin_inff()) & (b_int ^ 1);
+    r = no_real_power ? __builtin_nanf("") : r;
+    r = (neg_base & b_odd) ? -r : r;
+    r = ((int)(aa == 1.0f) & (int)(ab == __builtin_inff())) ? 1.0f : r;
+    r = ((int)(b == 0.0f) | (int)(a == 1.0f)) ? 1.0f : r;
+    return r;
+}
 DI float f_bf16_round(float x) {
     __bf16 h = (__bf16)x;
     return (float)h;
@@ -163,8 +182,8 @@ template <uint32_t B> DI float bin_op(float a, float b) {
     else if constexpr (B == B_MUL) return a * b;
     else if constexpr (B == B_DIV) return a * f_rcp(b);
     else if constexpr (B == B_RDIV) return b * f_rcp(a);
-    else if constexpr (B == B_MIN) return f_min(a, b);
-    else if constexpr (B == B_MAX) return f_max(a, b);
+    else if constexpr (B == B_MIN) return f_minp(a, b);
+    else if constexpr (B == B_MAX) return f_maxp(a, b);
     else if constexpr (B == B_POW) return f_pow(a, b);
     else if constexpr (B == B_RPOW) return f_pow(b, a);
     else if constexpr (B == B_EQ) return a == b ? 1.0f : 0.0f;
@@ -207,17 +226,20 @@ DI float bin_dyn(uint32_t b, float x, float y) {
 // does that, in the kernel body), so every register is split into K independent scalar VGPRs and
 // an instruction updates its destination in place.
 // ------------------------------------------------------------------------------------------
-template <int K> struct Tile { float v[K]; };
-template <int K> DI void tile_zero(Tile<K> &t) { sfor<K>([&]<int I>() LI { t.v[I] = 0.0f; }); }
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// (held as groups of four consecutive registers: a 16-byte load or store moves a whole group without copies)
+template <int K> struct Tile { f32x4 q[K / 4]; };
+#define TV(T, I) ((T).q[(I) >> 2][(I) & 3])
+template <int K> DI void tile_zero(Tile<K> &t) { sfor<K / 4>([&]<int Q>() LI { t.q[Q] = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; }); }
 
 template <int K, uint32_t U> DI void tile_un(Tile<K> &a) {
-    sfor<K>([&]<int I>() LI { a.v[I] = un_op<U>(a.v[I]); });
+    sfor<K>([&]<int I>() LI { TV(a, I) = un_op<U>(TV(a, I)); });
 }
 template <int K, uint32_t B> DI void tile_bin(Tile<K> &a, const Tile<K> &b) {
-    sfor<K>([&]<int I>() LI { a.v[I] = bin_op<B>(a.v[I], b.v[I]); });
+    sfor<K>([&]<int I>() LI { TV(a, I) = bin_op<B>(TV(a, I), TV(b, I)); });
 }
 template <int K, uint32_t B> DI void tile_bins(Tile<K> &a, float s) {
-    sfor<K>([&]<int I>() LI { a.v[I] = bin_op<B>(a.v[I], s); });
+    sfor<K>([&]<int I>() LI { TV(a, I) = bin_op<B>(TV(a, I), s); });
 }
 
 template <int K> DI void tile_un_dispatch(Tile<K> &a, uint32_t u) {
@@ -255,8 +277,8 @@ template <int K> DI void tile_bins_dispatch(Tile<K> &a, float s, uint32_t op) {
 // are bitwise reproducible.
 // ------------------------------------------------------------------------------------------
 template <uint32_t R> DI float red_comb(float a, float b) {
-    if constexpr (R == R_MAX) return f_max(a, b);
-    else if constexpr (R == R_MIN) return f_min(a, b);
+    if constexpr (R == R_MAX) return f_maxp(a, b);
+    else if constexpr (R == R_MIN) return f_minp(a, b);
     else return a + b;
 }
 template <uint32_t R> DI float red_ident() {
@@ -314,7 +336,6 @@ struct Geo {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
 typedef u32x4 u32x4_a2 __attribute__((aligned(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef f32x4 f32x4_a4 __attribute__((aligned(4)));
 #define GLOBAL_AS __attribute__((address_space(1)))
 typedef const GLOBAL_AS char *gcptr;   // global memory, read
@@ -343,41 +364,46 @@ DI int64_t row_offset(const Geo &g, int64_t s1, int64_t s2, int64_t s3) {
 // lanes of a wave: with only wave-uniform branches the compiler keeps the dispatch as plain scalar
 // jumps and updates registers in place.  Loads therefore clamp the address of an invalid lane to
 // a valid one (its data is never used), and stores switch the invalid lanes off in EXEC inside
-// one assembly statement.
+// one assembly statement.  (The compiler does not look inside the statement, so the wait state that this
+// chip wants between a store of more than 8 bytes and an instruction that overwrites the stored registers is
+// written out: the s_nop after the restored EXEC mask.)
 DI void st_b128(gptr p, f32x4 v, bool ok) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
     uint64_t sv;
-    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dwordx4 %2, %3, off nt\n\ts_mov_b64 exec, %0"
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dwordx4 %2, %3, off nt\n\ts_mov_b64 exec, %0\n\ts_nop 0"
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 DI void st_b32(gptr p, float v, bool ok) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
     uint64_t sv;
-    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dword %2, %3, off nt\n\ts_mov_b64 exec, %0"
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_dword %2, %3, off nt\n\ts_mov_b64 exec, %0\n\ts_nop 0"
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 DI void st_b16(gptr p, uint32_t v, bool ok) {
     const uint64_t m = __builtin_amdgcn_ballot_w64(ok);
     uint64_t sv;
-    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_short %2, %3, off nt\n\ts_mov_b64 exec, %0"
+    asm volatile("s_and_saveexec_b64 %0, %1\n\tglobal_store_short %2, %3, off nt\n\ts_mov_b64 exec, %0\n\ts_nop 0"
                  : "=&s"(sv) : "s"(m), "v"(p), "v"(v) : "memory", "scc");
 }
 
-// Loading the lane's part of a tile has two halves: request_tile puts every whole chunk in flight
-// (raw bits, 16 bytes per chunk half), and widen_tile turns the raw bits into fp32 once they are
-// needed (all chunk requests of a tile are in flight together).
-// DT: 0 = fp32, 1 = bf16.  V = chunk width.  `rowp` points at column `colbase` of the lane's row in
-// this tensor (row 0 for a lane whose row is outside the tensor).  A chunk that lies beyond the
-// tile's columns reads the tile's chunk 0 instead: the value is never stored and reductions mask it.
-template <int K> struct Raw {
-    f32x4 q[K / 4];     // the whole chunks, 16 bytes per piece
-    uint32_t pv[8];     // the elements of the chunk the row ends in (raw bits), requested alongside
-};
+// Loading the lane's part of a tile has two halves, so that the loads of several tensors are in flight
+// together: request_inplace issues every whole chunk straight into the destination tile register (no staging
+// registers: fp32 chunks land where their elements live, a bf16 chunk of 8 elements = 16 bytes lands in the
+// upper half of the register), and finish_tile, called once all loads of a group of load records have been
+// issued, widens the bf16 bits in place and fetches the chunk a ragged row ends in.
+// DT: 0 = fp32, 1 = bf16.  V = chunk width.  `rowp` points at column `colbase` of the lane's row in this tensor
+// (row 0 for a lane whose row is outside the tensor).  A chunk that lies beyond the tile's columns reads the
+// tile's chunk 0 instead: the value is never stored and reductions mask it.  Dtype, chunk width and cache hint
+// are fixed at compile time, so the request needs no per-piece scalar arithmetic.  NT: the data is read once,
+// hint the caches accordingly.
 typedef f32x4 f32x4_a2 __attribute__((aligned(2)));
+template <bool NT> DI f32x4 ld_b128(gcptr q) {
+    const GLOBAL_AS f32x4_a2 *src = (const GLOBAL_AS f32x4_a2 *)q;
+    if constexpr (NT) return __builtin_nontemporal_load(src);
+    else return *src;
+}
 
-// Dtype, chunk width and cache hint are fixed at compile time, so the request needs no per-piece
-// scalar arithmetic.  NT: the data is read once, hint the caches accordingly.
-template <int K, int DT, int V, bool NT> DI void request_tile_static(Raw<K> &raw, gcptr rowp, const Geo &g) {
+template <int K, int DT, int V, bool NT> DI void request_inplace(Tile<K> &t, gcptr rowp, const Geo &g) {
     constexpr int ES = DT == 0 ? 4 : 2;
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
@@ -386,19 +412,110 @@ template <int K, int DT, int V, bool NT> DI void request_tile_static(Raw<K> &raw
                 const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
                 const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
                 gcptr q = rowp + (uint64_t)cc * ES;
-                constexpr int PIECES = DT == 0 ? V / 4 : 1;
-                sfor<PIECES>([&]<int H>() LI {
-                    const GLOBAL_AS f32x4_a2 *src = (const GLOBAL_AS f32x4_a2 *)(q + 16 * H);
-                    if constexpr (NT) raw.q[J * PIECES + H] = __builtin_nontemporal_load(src);
-                    else raw.q[J * PIECES + H] = *src;
-                });
+                if constexpr (DT == 0) {
+                    sfor<V / 4>([&]<int H>() LI { t.q[J * (V / 4) + H] = ld_b128<NT>(q + 16 * H); });
+                } else {
+                    t.q[K / 8 + J] = ld_b128<NT>(q);        // raw bits, widened by finish_tile
+                }
+            });
+        }
+    }
+}
+template <int K> DI void request_dispatch(Tile<K> &t, uint32_t dt, uint32_t V, bool nt, gcptr rowp, const Geo &g) {
+    if (nt) {
+        if (dt == 0) {
+            if (V == 4) request_inplace<K, 0, 4, true>(t, rowp, g);
+            else request_inplace<K, 0, 8, true>(t, rowp, g);
+        } else {
+            request_inplace<K, 1, 8, true>(t, rowp, g);
+        }
+    } else {
+        if (dt == 0) {
+            if (V == 4) request_inplace<K, 0, 4, false>(t, rowp, g);
+            else request_inplace<K, 0, 8, false>(t, rowp, g);
+        } else {
+            request_inplace<K, 1, 8, false>(t, rowp, g);
+        }
+    }
+}
+
+// The second half.  bf16: chunk J sits as raw bits in group K/8 + J and becomes the eight values of groups
+// 2J and 2J + 1; going through the chunks in ascending order never overwrites bits that are still to be read
+// (2J + 1 <= K/8 + J for every J < K/8, and the last chunk is read before its own group is written).
+template <int K, int DT, int V> DI void finish_tile(Tile<K> &t, gcptr rowp, const Geo &g) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    if constexpr (K < V) tile_zero<K>(t);
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        if (g.ncols < (uint32_t)V) {        // narrower than one chunk: only the ragged part below
+            tile_zero<K>(t);
+        } else if constexpr (DT == 1) {
+            sfor<NJ>([&]<int J>() LI {
+                const u32x4 r = __builtin_bit_cast(u32x4, t.q[K / 8 + J]);
+                const uint32_t w0 = r.x, w1 = r.y, w2 = r.z, w3 = r.w;
+                t.q[2 * J] = f32x4{bf16_lo(w0), bf16_hi(w0), bf16_lo(w1), bf16_hi(w1)};
+                t.q[2 * J + 1] = f32x4{bf16_lo(w2), bf16_hi(w2), bf16_lo(w3), bf16_hi(w3)};
             });
         }
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
-            // its elements are read one by one by every lane of the row (one of them keeps them), in
-            // flight together with the whole chunks; an element beyond the row reads element 0 again
+            // its elements are read one by one by every lane of the row (one of them keeps them); an element
+            // beyond the row reads element 0 again
+            const bool own = g.lr == g.part_lane;
+            float pv[V];
             sfor<V>([&]<int E>() LI {
                 const uint32_t e = (uint32_t)E < g.part_n ? (uint32_t)E : 0u;       // wave-uniform
+                gcptr q = rowp + (uint64_t)(g.part_col + e) * ES;
+                if constexpr (DT == 0) pv[E] = *(const GLOBAL_AS float *)q;
+                else pv[E] = bf16_lo(*(const GLOBAL_AS uint16_t *)q);
+            });
+            sfor<NJ>([&]<int J>() LI {
+                if ((uint32_t)J == g.part_slot) {       // wave-uniform
+                    sfor<V>([&]<int E>() LI {
+                        const bool ok = own && (uint32_t)E < g.part_n;
+                        // (the empty statement keeps this a select between two values: a select between
+                        // two register-array elements would be turned into a select of their addresses,
+                        // which forces both arrays into memory)
+                        float x = pv[E];
+                        asm volatile("" : "+v"(x));
+                        TV(t, J * V + E) = ok ? x : TV(t, J * V + E);
+                    });
+                }
+            });
+        }
+    }
+}
+template <int K> DI void finish_dispatch(Tile<K> &t, uint32_t dt, uint32_t V, gcptr rowp, const Geo &g) {
+    if (dt == 0) {
+        if (V == 4) finish_tile<K, 0, 4>(t, rowp, g);
+        else finish_tile<K, 0, 8>(t, rowp, g);
+    } else {
+        finish_tile<K, 1, 8>(t, rowp, g);
+    }
+}
+
+// The streaming reduction along the penultimate axis keeps several rows of one tensor in flight per wave and
+// combines them into an accumulating register: it stages a row's raw bits in registers of its own (only the
+// variants with at most 8 elements per lane run it).
+template <int K> struct Raw {
+    f32x4 q[K / 4];     // the whole chunks, 16 bytes per piece
+    uint32_t pv[8];     // the elements of the chunk the row ends in (raw bits), requested alongside
+};
+template <int K, int DT, int V, bool NT> DI void request_staged(Raw<K> &raw, gcptr rowp, const Geo &g) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        if (g.ncols >= (uint32_t)V) {
+            sfor<NJ>([&]<int J>() LI {
+                const uint32_t c0 = g.lanecol + (uint32_t)J * g.GV;
+                const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
+                gcptr q = rowp + (uint64_t)cc * ES;
+                constexpr int PIECES = DT == 0 ? V / 4 : 1;
+                sfor<PIECES>([&]<int H>() LI { raw.q[J * PIECES + H] = ld_b128<NT>(q + 16 * H); });
+            });
+        }
+        if (g.part_slot != ~0u) {
+            sfor<V>([&]<int E>() LI {
+                const uint32_t e = (uint32_t)E < g.part_n ? (uint32_t)E : 0u;
                 gcptr q = rowp + (uint64_t)(g.part_col + e) * ES;
                 if constexpr (DT == 0) raw.pv[E] = *(const GLOBAL_AS uint32_t *)q;
                 else raw.pv[E] = *(const GLOBAL_AS uint16_t *)q;
@@ -406,35 +523,29 @@ template <int K, int DT, int V, bool NT> DI void request_tile_static(Raw<K> &raw
         }
     }
 }
-template <int K> DI void request_dispatch(Raw<K> &raw, uint32_t dt, uint32_t V, bool nt, gcptr rowp, const Geo &g) {
+template <int K> DI void request_staged_dispatch(Raw<K> &raw, uint32_t dt, uint32_t V, bool nt, gcptr rowp, const Geo &g) {
     if (nt) {
         if (dt == 0) {
-            if (V == 4) request_tile_static<K, 0, 4, true>(raw, rowp, g);
-            else request_tile_static<K, 0, 8, true>(raw, rowp, g);
+            if (V == 4) request_staged<K, 0, 4, true>(raw, rowp, g);
+            else request_staged<K, 0, 8, true>(raw, rowp, g);
         } else {
-            request_tile_static<K, 1, 8, true>(raw, rowp, g);
+            request_staged<K, 1, 8, true>(raw, rowp, g);
         }
     } else {
         if (dt == 0) {
-            if (V == 4) request_tile_static<K, 0, 4, false>(raw, rowp, g);
-            else request_tile_static<K, 0, 8, false>(raw, rowp, g);
+            if (V == 4) request_staged<K, 0, 4, false>(raw, rowp, g);
+            else request_staged<K, 0, 8, false>(raw, rowp, g);
         } else {
-            request_tile_static<K, 1, 8, false>(raw, rowp, g);
+            request_staged<K, 1, 8, false>(raw, rowp, g);
         }
     }
 }
-
-// B == B_NONE: t = loaded tile.  Otherwise t = B(t, loaded tile), element by element as the pieces
-// are widened (no second tile register is needed); elements outside the row keep their old value.
-template <int K, int DT, int V, uint32_t B> DI void widen_tile(Tile<K> &t, const Raw<K> &raw, const Geo &g) {
-    if constexpr (K < V && B == B_NONE) tile_zero<K>(t);
+// t = B(t, staged row), element by element as the pieces are widened; elements outside the row keep their value
+template <int K, int DT, int V, uint32_t B> DI void combine_staged(Tile<K> &t, const Raw<K> &raw, const Geo &g) {
     if constexpr (K >= V) {
         constexpr int NJ = K / V;
-        if constexpr (B == B_NONE) {
-            if (g.ncols < (uint32_t)V) tile_zero<K>(t);     // narrower than one chunk: only the ragged part below
-        }
         if (g.ncols >= (uint32_t)V) {
-            const bool masked = B != B_NONE && g.ragged != 0;       // wave-uniform
+            const bool masked = g.ragged != 0;       // wave-uniform
             auto chunk = [&]<int J>(bool whole) LI {
                 float x[V];
                 if constexpr (DT == 0) {
@@ -449,12 +560,8 @@ template <int K, int DT, int V, uint32_t B> DI void widen_tile(Tile<K> &t, const
                     x[4] = bf16_lo(w2); x[5] = bf16_hi(w2); x[6] = bf16_lo(w3); x[7] = bf16_hi(w3);
                 }
                 sfor<V>([&]<int E>() LI {
-                    if constexpr (B == B_NONE) {
-                        t.v[J * V + E] = x[E];
-                    } else {
-                        const float y = bin_op<B>(t.v[J * V + E], x[E]);
-                        t.v[J * V + E] = whole ? y : t.v[J * V + E];
-                    }
+                    const float y = bin_op<B>(TV(t, J * V + E), x[E]);
+                    TV(t, J * V + E) = whole ? y : TV(t, J * V + E);
                 });
             };
             if (!masked) {
@@ -463,7 +570,7 @@ template <int K, int DT, int V, uint32_t B> DI void widen_tile(Tile<K> &t, const
                 sfor<NJ>([&]<int J>() LI { chunk.template operator()<J>(g.lanecol + (uint32_t)J * g.GV + V <= g.ncols); });
             }
         }
-        if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
+        if (g.part_slot != ~0u) {
             const bool own = g.lr == g.part_lane;
             float pv[V];
             sfor<V>([&]<int E>() LI {
@@ -472,20 +579,25 @@ template <int K, int DT, int V, uint32_t B> DI void widen_tile(Tile<K> &t, const
                 else pv[E] = bf16_lo(bits);
             });
             sfor<NJ>([&]<int J>() LI {
-                if ((uint32_t)J == g.part_slot) {       // wave-uniform
+                if ((uint32_t)J == g.part_slot) {
                     sfor<V>([&]<int E>() LI {
                         const bool ok = own && (uint32_t)E < g.part_n;
-                        // (the empty statement keeps this a select between two values: a select between
-                        // two register-array elements would be turned into a select of their addresses,
-                        // which forces both arrays into memory)
                         float x = pv[E];
                         asm volatile("" : "+v"(x));
-                        if constexpr (B != B_NONE) x = bin_op<B>(t.v[J * V + E], x);
-                        t.v[J * V + E] = ok ? x : t.v[J * V + E];
+                        x = bin_op<B>(TV(t, J * V + E), x);
+                        TV(t, J * V + E) = ok ? x : TV(t, J * V + E);
                     });
                 }
             });
         }
+    }
+}
+template <int K, uint32_t B> DI void combine_staged_dispatch(Tile<K> &t, const Raw<K> &raw, uint32_t dt, uint32_t V, const Geo &g) {
+    if (dt == 0) {
+        if (V == 4) combine_staged<K, 0, 4, B>(t, raw, g);
+        else combine_staged<K, 0, 8, B>(t, raw, g);
+    } else {
+        combine_staged<K, 1, 8, B>(t, raw, g);
     }
 }
 
@@ -496,21 +608,15 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
         const uint32_t lanecol = g.lanecol;
         if (g.ncols >= (uint32_t)V) {
             sfor<NJ>([&]<int J>() LI {
-                {
-                    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
-                    const bool ok = g.rowok && c0 + V <= g.ncols;
-                    gptr q = rowp + (uint64_t)c0 * ES;
-                    if constexpr (DT == 0) {
-                        sfor<V / 4>([&]<int H>() LI {
-                            const f32x4 r = {t.v[J * V + 4 * H + 0], t.v[J * V + 4 * H + 1], t.v[J * V + 4 * H + 2],
-                                             t.v[J * V + 4 * H + 3]};
-                            st_b128(q + 16 * H, r, ok);
-                        });
-                    } else {
-                        const u32x4 r = {pack_bf16x2(t.v[J * V + 0], t.v[J * V + 1]), pack_bf16x2(t.v[J * V + 2], t.v[J * V + 3]),
-                                         pack_bf16x2(t.v[J * V + 4], t.v[J * V + 5]), pack_bf16x2(t.v[J * V + 6], t.v[J * V + 7])};
-                        st_b128(q, __builtin_bit_cast(f32x4, r), ok);
-                    }
+                const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
+                const bool ok = g.rowok && c0 + V <= g.ncols;
+                gptr q = rowp + (uint64_t)c0 * ES;
+                if constexpr (DT == 0) {
+                    sfor<V / 4>([&]<int H>() LI { st_b128(q + 16 * H, t.q[J * (V / 4) + H], ok); });
+                } else {
+                    const f32x4 lo = t.q[2 * J], hi = t.q[2 * J + 1];
+                    const u32x4 r = {pack_bf16x2(lo.x, lo.y), pack_bf16x2(lo.z, lo.w), pack_bf16x2(hi.x, hi.y), pack_bf16x2(hi.z, hi.w)};
+                    st_b128(q, __builtin_bit_cast(f32x4, r), ok);
                 }
             });
         }
@@ -521,22 +627,13 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
                     sfor<V>([&]<int E>() LI {
                         if ((uint32_t)E < g.part_n) {       // wave-uniform
                             gptr q = rowp + (uint64_t)(g.part_col + E) * ES;
-                            if constexpr (DT == 0) st_b32(q, t.v[J * V + E], own);
-                            else st_b16(q, (uint32_t)pack_bf16(t.v[J * V + E]), own);
+                            if constexpr (DT == 0) st_b32(q, TV(t, J * V + E), own);
+                            else st_b16(q, (uint32_t)pack_bf16(TV(t, J * V + E)), own);
                         }
                     });
                 }
             });
         }
-    }
-}
-
-template <int K, uint32_t B> DI void widen_dispatch(Tile<K> &t, const Raw<K> &raw, uint32_t dt, uint32_t V, const Geo &g) {
-    if (dt == 0) {
-        if (V == 4) widen_tile<K, 0, 4, B>(t, raw, g);
-        else widen_tile<K, 0, 8, B>(t, raw, g);
-    } else {
-        widen_tile<K, 1, 8, B>(t, raw, g);
     }
 }
 template <int K> DI void store_dispatch(const Tile<K> &t, uint32_t dt, uint32_t V, gptr rowp, const Geo &g) {
@@ -545,6 +642,77 @@ template <int K> DI void store_dispatch(const Tile<K> &t, uint32_t dt, uint32_t 
         else store_tile<K, 0, 8>(t, rowp, g);
     } else {
         store_tile<K, 1, 8>(t, rowp, g);
+    }
+}
+
+// ---- wide rows ------------------------------------------------------------------------------------
+// When a row is held by at least one whole wave (G >= 64), everything about the row is the same for all lanes
+// of a wave: its index, its offsets in every tensor, whether it exists.  The wide instantiation of the kernel
+// does that arithmetic once per wave on the scalar unit and addresses memory as a scalar row base plus a 32-bit
+// lane offset (the form of the load / store instruction that takes a scalar base), so that a memory record
+// costs a handful of scalar instructions and one vector instruction per chunk for the offset.
+typedef const GLOBAL_AS char *gcptr_u;      // (a wave-uniform pointer)
+struct Wide {
+    uint32_t i1, i2, i3;    // the wave's row, decomposed over the outer dims (wave-uniform)
+    uint32_t rowok;         // the wave's row lies inside the tensor
+};
+
+// byte offset of chunk J of this lane from the row base; a chunk beyond the tile's columns reads chunk 0 instead
+template <int V, int ES> DI uint32_t chunk_off(const Geo &g, uint32_t lanecol, int J) {
+    const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
+    const uint32_t cc = c0 + V <= g.ncols ? c0 : 0u;
+    return cc * ES;
+}
+template <int K, int DT, int V, bool NT> DI void issue_wide(Tile<K> &t, const char *rowbase, const uint32_t (&vo)[K / V]) {
+    constexpr int NJ = K / V;
+    sfor<NJ>([&]<int J>() LI {
+        gcptr q = (gcptr)(rowbase + (uint64_t)vo[J]);
+        if constexpr (DT == 0) {
+            sfor<V / 4>([&]<int H>() LI { t.q[J * (V / 4) + H] = ld_b128<NT>(q + 16 * H); });
+        } else {
+            t.q[K / 8 + J] = ld_b128<NT>(q);
+        }
+    });
+}
+// The offsets are computed before the destination register is selected: inside the selected case nothing but
+// the load instructions may write a register, or the compiler would compute addresses in the registers the
+// load is about to overwrite, which costs a wait for every load still in flight into them.
+#define DVM_ISSUE_WIDE(DT, V, NT)                                                                   \
+    {                                                                                               \
+        uint32_t vo[K / V];                                                                         \
+        sfor<K / V>([&]<int J>() LI { vo[J] = chunk_off<V, (DT == 0 ? 4 : 2)>(g, g.lanecol, J); }); \
+        _Pragma("unroll") for (int j_ = 0; j_ < K / V; ++j_) asm volatile("" : "+v"(vo[j_]));       \
+        if (ra == SRC_ACC) {                                                                        \
+            issue_wide<K, DT, V, NT>(acc, rowbase, vo);                                             \
+        } else {                                                                                    \
+            DVM_WITH_R(ra, rr, (issue_wide<K, DT, V, NT>(rr, rowbase, vo)))                         \
+        }                                                                                           \
+    }
+
+// full tile (no ragged chunk, every chunk inside the row), row inside the tensor: plain 16-byte stores
+template <int K, int DT, int V> DI void store_wide_full(const Tile<K> &t, char *rowbase, const Geo &g) {
+    constexpr int ES = DT == 0 ? 4 : 2;
+    constexpr int NJ = K / V;
+    sfor<NJ>([&]<int J>() LI {
+        if (J == 0 || (uint32_t)(J * V) < g.nact) {        // wave-uniform: chunk slots the tile uses
+            const uint32_t vo = (g.lanecol + (uint32_t)J * g.GV) * ES;
+            GLOBAL_AS char *q = (GLOBAL_AS char *)(rowbase + (uint64_t)vo);
+            if constexpr (DT == 0) {
+                sfor<V / 4>([&]<int H>() LI { __builtin_nontemporal_store(t.q[J * (V / 4) + H], (GLOBAL_AS f32x4 *)(q + 16 * H)); });
+            } else {
+                const f32x4 lo = t.q[2 * J], hi = t.q[2 * J + 1];
+                const u32x4 r = {pack_bf16x2(lo.x, lo.y), pack_bf16x2(lo.z, lo.w), pack_bf16x2(hi.x, hi.y), pack_bf16x2(hi.z, hi.w)};
+                __builtin_nontemporal_store(__builtin_bit_cast(f32x4, r), (GLOBAL_AS f32x4 *)q);
+            }
+        }
+    });
+}
+template <int K> DI void store_wide_full_dispatch(const Tile<K> &t, uint32_t dt, uint32_t V, char *rowbase, const Geo &g) {
+    if (dt == 0) {
+        if (V == 4) store_wide_full<K, 0, 4>(t, rowbase, g);
+        else if constexpr (K >= 8) store_wide_full<K, 0, 8>(t, rowbase, g);
+    } else {
+        if constexpr (K >= 8) store_wide_full<K, 1, 8>(t, rowbase, g);
     }
 }
 
@@ -560,8 +728,8 @@ template <int K, uint32_t R, int V> DI float lane_reduce_ragged(const Tile<K> &a
             if (J == 0 || (uint32_t)(J * V) < g.nact) {        // wave-uniform
                 float c = red_ident<R>();
                 sfor<V>([&]<int E>() LI {
-                    if constexpr (R == R_SUMSQ) c = f_fma(a.v[J * V + E], a.v[J * V + E], c);
-                    else c = red_comb<R>(c, a.v[J * V + E]);
+                    if constexpr (R == R_SUMSQ) c = f_fma(TV(a, J * V + E), TV(a, J * V + E), c);
+                    else c = red_comb<R>(c, TV(a, J * V + E));
                 });
                 const bool whole = g.lanecol + (uint32_t)J * g.GV + V <= g.ncols;
                 v = red_comb<RC>(v, whole ? c : red_ident<R>());
@@ -574,10 +742,10 @@ template <int K, uint32_t R, int V> DI float lane_reduce_ragged(const Tile<K> &a
                     sfor<V>([&]<int E>() LI {
                         const bool ok = own && (uint32_t)E < g.part_n;
                         if constexpr (R == R_SUMSQ) {
-                            const float x = ok ? a.v[J * V + E] : 0.0f;
+                            const float x = ok ? TV(a, J * V + E) : 0.0f;
                             v = f_fma(x, x, v);
                         } else {
-                            v = red_comb<R>(v, ok ? a.v[J * V + E] : red_ident<R>());
+                            v = red_comb<R>(v, ok ? TV(a, J * V + E) : red_ident<R>());
                         }
                     });
                 }
@@ -592,8 +760,8 @@ template <int K, uint32_t R> DI float lane_reduce(const Tile<K> &a, const Geo &g
         sfor<K / 4>([&]<int Q>() LI {
             if (Q == 0 || (uint32_t)(Q * 4) < g.nact) {
                 sfor<4>([&]<int E>() LI {
-                    if constexpr (R == R_SUMSQ) v = f_fma(a.v[Q * 4 + E], a.v[Q * 4 + E], v);
-                    else v = red_comb<R>(v, a.v[Q * 4 + E]);
+                    if constexpr (R == R_SUMSQ) v = f_fma(TV(a, Q * 4 + E), TV(a, Q * 4 + E), v);
+                    else v = red_comb<R>(v, TV(a, Q * 4 + E));
                 });
             }
         });
@@ -755,8 +923,11 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
 // accumulate and combine records).  Programs without such a segment run the plain instantiation, whose
 // tile loop carries none of that bookkeeping (it costs scalar registers the interpreter loop has none
 // to spare of: 5-10 % on short tiles).
-template <int K, int NR, int MAXT, int WAVES, bool CRED>
+// WIDE: the instantiation for launches in which every segment spreads a row over at least one whole wave (see
+// "wide rows" above); the other instantiations take any geometry.
+template <int K, int NR, int MAXT, int WAVES, bool CRED, bool WIDE>
 __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES))) dvm_vm_kernel(const KArgs args) {
+    static_assert(!(CRED && WIDE), "the instantiation for reductions along the penultimate axis is the general one");
     __shared__ float red_lds[2][16];
     // (sized by the launch: 1 KiB per wave of the widest segment that reduces along the penultimate axis, else nothing)
     extern __shared__ __align__(16) float comb_lds[];
@@ -773,6 +944,17 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
     const uint32_t ngrid = gridDim.x;
     uint32_t red_par = 0;
     const uint32_t *code = args.code;
+    // the launch's tensor addresses, one per lane: a memory record reads the one it needs with a single lane read
+    // (the index is wave-uniform) instead of a scalar load whose latency it would have to wait for
+    uint32_t tp_lo, tp_hi;
+    {
+        const uint64_t mine = args.tensors[tid & (DVM_MAX_TENSORS - 1)];
+        tp_lo = (uint32_t)mine;
+        tp_hi = (uint32_t)(mine >> 32);
+    }
+#define DVM_TENSOR(IDX)                                                                                  \
+    ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)tp_lo, (int)(IDX)) |                             \
+     ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)tp_hi, (int)(IDX)) << 32))
 
     uint32_t seg = 0;                       // word offset of the current segment
     for (uint32_t si = 0; si < args.nseg; ++si) {
@@ -811,8 +993,17 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         }
         const uint32_t m = (M + sgrid - 1) / sgrid;
         const uint64_t t_lo64 = (uint64_t)m * sbid;
-        const uint32_t t_lo = t_lo64 < M ? (uint32_t)t_lo64 : M;
-        const uint32_t t_hi = (M - t_lo) < m ? M : t_lo + m;
+        uint32_t t_lo = t_lo64 < M ? (uint32_t)t_lo64 : M;
+        uint32_t t_hi = (M - t_lo) < m ? M : t_lo + m;
+        uint32_t t_step = 1;
+        // Interleaved assignment: workgroup id runs tiles id, id + N, id + 2N, ...  At any moment the resident
+        // workgroups then work on one contiguous stretch of the tensors, which the memory system of this
+        // machine serves measurably faster than N streams that are far apart (the blocked ranges).
+        if (sh[S_FLAGS] & SF_INTERLEAVED) {
+            t_lo = sbid < M ? sbid : M;
+            t_hi = M;
+            t_step = sgrid;
+        }
 
         const uint32_t nct = sh[S_NCT];
         if (nct <= 1) tile_cols(gt, sh, 0, G, V);
@@ -847,6 +1038,13 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                 }
                 tile_rows(gt, sh, tile_r, rp, tid, RP, seg_threads);
             }
+            Wide wd;
+            if constexpr (WIDE) {       // all lanes of a wave hold the same row: its place as wave-uniform values
+                wd.i1 = __builtin_amdgcn_readfirstlane(gt.i1);
+                wd.i2 = __builtin_amdgcn_readfirstlane(gt.i2);
+                wd.i3 = __builtin_amdgcn_readfirstlane(gt.i3);
+                wd.rowok = __builtin_amdgcn_readfirstlane(gt.rowok);
+            }
 
             // the first tile of this workgroup also runs the prologue records (pinned operands)
             // (its second part runs again when the second outer index of the tile's first or last row
@@ -857,8 +1055,9 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                 if (shl[S_PROLOGA] != shl[S_PROLOG]) {
                     const uint32_t m1 = shl[S_M1], sh1 = shl[S_SH1];
                     const uint32_t ra = tile * RP;          // prologues exist in row mode only: tile = row tile
-                    const bool crossed = sdiv_u(ra, m1, sh1) != sdiv_u(ra - RP, m1, sh1) ||
-                                         sdiv_u(ra + RP - 1, m1, sh1) != sdiv_u(ra - 1, m1, sh1);
+                    const uint32_t rb = ra - t_step * RP;   // first row of the tile this workgroup ran before
+                    const bool crossed = sdiv_u(ra, m1, sh1) != sdiv_u(rb, m1, sh1) ||
+                                         sdiv_u(ra + RP - 1, m1, sh1) != sdiv_u(rb + RP - 1, m1, sh1);
                     if (crossed) first = body + shl[S_PROLOGA];
                 }
             }
@@ -875,41 +1074,169 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                 switch (op) {
                     case I_LOAD:
                     case I_VLOAD: {
-                        DVM_GEO()
-                        const uint32_t w1 = cw1;
-                        const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
-                        const int64_t st1 = DVM_I64(cw2, cw3);
-                        int64_t st2 = 0, st3 = 0;
-                        if (op == I_VLOAD) {
-                            const u32x4s hw = fetch4(code, cur + 4);
-                            const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
-                            st2 = DVM_I64(h0, h1);
-                            st3 = DVM_I64(h2, h3);
-                        }
-                        int64_t off = (int64_t)g.i1 * st1 + (int64_t)g.colbase;
-                        if (op == I_VLOAD) off += (int64_t)g.i2 * st2 + (int64_t)g.i3 * st3;
-                        const uint32_t es = dt == 0 ? 4 : 2;
-                        gcptr base = (gcptr)args.tensors[tbase + ti];
-                        gcptr rowp = base + off * es;
-                        Raw<K> raw;
-                        request_dispatch<K>(raw, dt, V, ((w1 >> 16) & MF_STREAM) != 0, rowp, g);
-                        // widen straight into the destination register; a load into the accumulator may
-                        // combine with what it holds (acc = acc op tile) while it widens
-                        if (a == SRC_ACC) {
-                            switch (b) {
-                                case B_ADD: widen_dispatch<K, B_ADD>(acc, raw, dt, V, g); break;
-                                case B_SUB: widen_dispatch<K, B_SUB>(acc, raw, dt, V, g); break;
-                                case B_RSUB: widen_dispatch<K, B_RSUB>(acc, raw, dt, V, g); break;
-                                case B_MUL: widen_dispatch<K, B_MUL>(acc, raw, dt, V, g); break;
-                                default: widen_dispatch<K, B_NONE>(acc, raw, dt, V, g); break;
+                        // A run of consecutive load records is one group: first every record of the run issues its
+                        // requests (all of them are then in flight together, each into its own destination
+                        // register), then a second walk over the same records finishes them (bf16 widening in
+                        // place, the chunk a ragged row ends in).
+                        if constexpr (WIDE) {
+                            Geo g = gt;
+                            uint32_t gp = cur;
+                            u32x4s rw = cw;
+                            const bool slow_finish = g.part_slot != ~0u || g.ncols < V;
+                            uint32_t widen = 0;             // bit r + 1: register r (bit 0: ACC) holds raw bf16 bits
+                            for (;;) {
+                                asm volatile("" : "+v"(g.lanecol));
+                                const uint32_t r0w = rw.x, w1 = rw.y, r2w = rw.z, r3w = rw.w;
+                                const uint32_t rop = r0w & 0xFF, ra = (r0w >> 16) & 0xFF;
+                                const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                                int64_t off = (int64_t)wd.i1 * DVM_I64(r2w, r3w) + (int64_t)g.colbase;
+                                if (rop == I_VLOAD) {
+                                    const u32x4s hw = fetch4(code, gp + 4);
+                                    const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                                    off += (int64_t)wd.i2 * DVM_I64(h0, h1) + (int64_t)wd.i3 * DVM_I64(h2, h3);
+                                }
+                                const char *rowbase = (const char *)DVM_TENSOR(tbase + ti) + off * (dt == 0 ? 4 : 2);
+                                if (g.ncols >= V) {
+                                    if ((w1 >> 16) & MF_STREAM) {
+                                        if (dt != 0) { if constexpr (K >= 8) DVM_ISSUE_WIDE(1, 8, true) }
+                                        else if (V == 4) DVM_ISSUE_WIDE(0, 4, true)
+                                        else { if constexpr (K >= 8) DVM_ISSUE_WIDE(0, 8, true) }
+                                    } else {
+                                        if (dt != 0) { if constexpr (K >= 8) DVM_ISSUE_WIDE(1, 8, false) }
+                                        else if (V == 4) DVM_ISSUE_WIDE(0, 4, false)
+                                        else { if constexpr (K >= 8) DVM_ISSUE_WIDE(0, 8, false) }
+                                    }
+                                }
+                                if (dt != 0) widen |= ra == SRC_ACC ? 1u : 2u << ra;
+                                gp += (r0w >> 8) & 0xFF;
+                                if (gp >= this_end) break;
+                                rw = fetch4(code, gp);
+                                const uint32_t nop = rw.x & 0xFF;
+                                if (nop != I_LOAD && nop != I_VLOAD) break;
                             }
-                        } else {
-                            DVM_WITH_R(a, rr, (widen_dispatch<K, B_NONE>(rr, raw, dt, V, g)))
+                            if (slow_finish) {          // ragged rows: walk the records again (row address for the last chunk)
+                                for (uint32_t fp = cur; fp < gp;) {
+                                    asm volatile("" : "+v"(g.lanecol));
+                                    const u32x4s fw = fetch4(code, fp);
+                                    const uint32_t r0w = fw.x, w1 = fw.y, r2w = fw.z, r3w = fw.w;
+                                    const uint32_t rop = r0w & 0xFF, ra = (r0w >> 16) & 0xFF;
+                                    const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                                    int64_t off = (int64_t)wd.i1 * DVM_I64(r2w, r3w) + (int64_t)g.colbase;
+                                    if (rop == I_VLOAD) {
+                                        const u32x4s hw = fetch4(code, fp + 4);
+                                        const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                                        off += (int64_t)wd.i2 * DVM_I64(h0, h1) + (int64_t)wd.i3 * DVM_I64(h2, h3);
+                                    }
+                                    gcptr rowp = (gcptr)((const char *)DVM_TENSOR(tbase + ti) + off * (dt == 0 ? 4 : 2));
+                                    if (ra == SRC_ACC) {
+                                        finish_dispatch<K>(acc, dt, V, rowp, g);
+                                    } else {
+                                        DVM_WITH_R(ra, rr, (finish_dispatch<K>(rr, dt, V, rowp, g)))
+                                    }
+                                    fp += (r0w >> 8) & 0xFF;
+                                }
+                            } else if (widen != 0) {    // full rows: only the bf16 registers need their second half
+                                if constexpr (K >= 8) {
+                                    if (widen & 1u) finish_tile<K, 1, 8>(acc, nullptr, g);
+                                    if (widen & 2u) finish_tile<K, 1, 8>(r0, nullptr, g);
+                                    if constexpr (NR > 1) if (widen & 4u) finish_tile<K, 1, 8>(r1, nullptr, g);
+                                    if constexpr (NR > 2) if (widen & 8u) finish_tile<K, 1, 8>(r2, nullptr, g);
+                                    if constexpr (NR > 3) if (widen & 16u) finish_tile<K, 1, 8>(r3, nullptr, g);
+                                    if constexpr (NR > 4) if (widen & 32u) finish_tile<K, 1, 8>(r4, nullptr, g);
+                                    if constexpr (NR > 5) if (widen & 64u) finish_tile<K, 1, 8>(r5, nullptr, g);
+                                }
+                            }
+                            pcb = gp * 4;
+                            nw = fetch4b(code, pcb);
+                            break;
                         }
+                        DVM_GEO()
+                        uint32_t gp = cur;              // word offset of the record being issued
+                        u32x4s rw = cw;
+                        bool finish = g.part_slot != ~0u || g.ncols < V;
+                        for (;;) {
+                            // (the lane's column is made opaque once per record: otherwise the chunk addresses of every
+                            // dtype and chunk width are computed ahead of the loop and held in registers throughout)
+                            asm volatile("" : "+v"(g.lanecol));
+                            const uint32_t r0w = rw.x, w1 = rw.y, r2w = rw.z, r3w = rw.w;
+                            const uint32_t rop = r0w & 0xFF, ra = (r0w >> 16) & 0xFF;
+                            const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                            int64_t off = (int64_t)g.i1 * DVM_I64(r2w, r3w) + (int64_t)g.colbase;
+                            if (rop == I_VLOAD) {
+                                const u32x4s hw = fetch4(code, gp + 4);
+                                const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                                off += (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3);
+                            }
+                            const uint32_t es = dt == 0 ? 4 : 2;
+                            gcptr rowp = (gcptr)DVM_TENSOR(tbase + ti) + off * es;
+                            const bool nt = ((w1 >> 16) & MF_STREAM) != 0;
+                            if (ra == SRC_ACC) {
+                                request_dispatch<K>(acc, dt, V, nt, rowp, g);
+                            } else {
+                                DVM_WITH_R(ra, rr, (request_dispatch<K>(rr, dt, V, nt, rowp, g)))
+                            }
+                            finish |= dt != 0;
+                            gp += (r0w >> 8) & 0xFF;
+                            if (gp >= this_end) break;
+                            rw = fetch4(code, gp);
+                            const uint32_t nop = rw.x & 0xFF;
+                            if (nop != I_LOAD && nop != I_VLOAD) break;
+                        }
+                        if (finish) {
+                            for (uint32_t fp = cur; fp < gp;) {
+                                asm volatile("" : "+v"(g.lanecol));
+                                const u32x4s fw = fetch4(code, fp);
+                                const uint32_t r0w = fw.x, w1 = fw.y, r2w = fw.z, r3w = fw.w;
+                                const uint32_t rop = r0w & 0xFF, ra = (r0w >> 16) & 0xFF;
+                                const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                                gcptr rowp = nullptr;
+                                if (g.part_slot != ~0u) {       // (only the ragged chunk needs the address again)
+                                    int64_t off = (int64_t)g.i1 * DVM_I64(r2w, r3w) + (int64_t)g.colbase;
+                                    if (rop == I_VLOAD) {
+                                        const u32x4s hw = fetch4(code, fp + 4);
+                                        const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                                        off += (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3);
+                                    }
+                                    rowp = (gcptr)DVM_TENSOR(tbase + ti) + off * (dt == 0 ? 4 : 2);
+                                }
+                                if (ra == SRC_ACC) {
+                                    finish_dispatch<K>(acc, dt, V, rowp, g);
+                                } else {
+                                    DVM_WITH_R(ra, rr, (finish_dispatch<K>(rr, dt, V, rowp, g)))
+                                }
+                                fp += (r0w >> 8) & 0xFF;
+                            }
+                        }
+                        pcb = gp * 4;                   // resume behind the group
+                        nw = fetch4b(code, pcb);
                         break;
                     }
                     case I_STORE:
                     case I_VSTORE: {
+                        if constexpr (WIDE) {
+                            if (gt.part_slot == ~0u && gt.ragged == 0 && gt.ncols >= V) {   // a full tile: plain stores
+                                if (wd.rowok) {
+                                    Geo g = gt;
+                                    asm volatile("" : "+v"(g.lanecol));
+                                    const uint32_t w1 = cw1;
+                                    const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
+                                    int64_t off = (int64_t)wd.i1 * DVM_I64(cw2, cw3) + (int64_t)g.colbase;
+                                    if (op == I_VSTORE) {
+                                        const u32x4s hw = fetch4(code, cur + 4);
+                                        const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
+                                        off += (int64_t)wd.i2 * DVM_I64(h0, h1) + (int64_t)wd.i3 * DVM_I64(h2, h3);
+                                    }
+                                    char *rowbase = (char *)DVM_TENSOR(tbase + ti) + off * (dt == 0 ? 4 : 2);
+                                    if (a == SRC_ACC) {
+                                        if (b != 0) tile_bins<K, B_MUL>(acc, DVM_GET_S(b - 1));
+                                        store_wide_full_dispatch<K>(acc, dt, V, rowbase, g);
+                                    } else {
+                                        DVM_WITH_R(a, rr, store_wide_full_dispatch<K>(rr, dt, V, rowbase, g))
+                                    }
+                                }
+                                break;
+                            }
+                        }
                         DVM_GEO()
                         const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
@@ -920,7 +1247,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             off += (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3);
                         }
                         const uint32_t es = dt == 0 ? 4 : 2;
-                        gptr base = (gptr)args.tensors[tbase + ti];
+                        gptr base = (gptr)DVM_TENSOR(tbase + ti);
                         gptr rowp = base + off * es;
                         if (a == SRC_ACC) {
                             // (b: a row scalar to multiply by first; the accumulator's value is dead afterwards)
@@ -938,7 +1265,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         const u32x4s hw = fetch4(code, cur + 4);
                         const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
                         const int64_t off = row_offset(g, DVM_I64(cw2, cw3), DVM_I64(h0, h1), DVM_I64(h2, h3));
-                        gcptr base = (gcptr)args.tensors[tbase + ti];
+                        gcptr base = (gcptr)DVM_TENSOR(tbase + ti);
                         float v;       // a lane outside the tensor reads row 0: valid memory, value unused
                         if (dt == 0) v = *(const GLOBAL_AS float *)(base + off * 4);
                         else v = bf16_lo(*(const GLOBAL_AS uint16_t *)(base + off * 2));
@@ -952,7 +1279,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         const u32x4s hw = fetch4(code, cur + 4);
                         const uint32_t h0 = hw.x, h1 = hw.y, h2 = hw.z, h3 = hw.w;
                         const int64_t off = row_offset(g, DVM_I64(cw2, cw3), DVM_I64(h0, h1), DVM_I64(h2, h3));
-                        gptr base = (gptr)args.tensors[tbase + ti];
+                        gptr base = (gptr)DVM_TENSOR(tbase + ti);
                         const float v = DVM_GET_S(a);
                         const bool ok = g.rowok && g.lr == 0 && g.colbase == 0;
                         if (dt == 0) st_b32(base + off * 4, v, ok);
@@ -984,13 +1311,13 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         const bool ok = gt.rowok;
                         if (rin == 0) {
                             const float ident = b == R_SUM ? 0.0f : (b == R_MAX ? -__builtin_inff() : __builtin_inff());
-                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? acc.v[I] : ident; }))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { TV(rr, I) = ok ? TV(acc, I) : ident; }))
                         } else if (b == R_SUM) {
-                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? rr.v[I] + acc.v[I] : rr.v[I]; }))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { TV(rr, I) = ok ? TV(rr, I) + TV(acc, I) : TV(rr, I); }))
                         } else if (b == R_MAX) {
-                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? f_max(rr.v[I], acc.v[I]) : rr.v[I]; }))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { TV(rr, I) = ok ? f_maxp(TV(rr, I), TV(acc, I)) : TV(rr, I); }))
                         } else {
-                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { rr.v[I] = ok ? f_min(rr.v[I], acc.v[I]) : rr.v[I]; }))
+                            DVM_WITH_R(a, rr, sfor<K>([&]<int I>() LI { TV(rr, I) = ok ? f_minp(TV(rr, I), TV(acc, I)) : TV(rr, I); }))
                         }
                     }
                         break;
@@ -1007,25 +1334,25 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         const uint32_t es = dt == 0 ? 4 : 2;
                         // (a wave without a valid first row decomposed row 0: in bounds, and it combines nothing)
                         const int64_t off0 = (int64_t)g.i2 * DVM_I64(h0, h1) + (int64_t)g.i3 * DVM_I64(h2, h3) + (int64_t)g.colbase;
-                        gcptr base = (gcptr)args.tensors[tbase + ti];
+                        gcptr base = (gcptr)DVM_TENSOR(tbase + ti);
                         const uint32_t inner_n = sh[S_INNER];
                         const float ident = b == R_SUM ? 0.0f : (b == R_MAX ? -__builtin_inff() : __builtin_inff());
-                        constexpr int U = K <= 4 ? 8 : 4;       // (as many as the registers hold)
+                        constexpr int U = K <= 4 ? 6 : 4;       // (as many as the registers hold)
                         DVM_WITH_R(a, rr, {
-                            sfor<K>([&]<int I>() LI { rr.v[I] = ident; });
+                            sfor<K>([&]<int I>() LI { TV(rr, I) = ident; });
                             if (wave < RP) {
                                 for (uint32_t r = wave; r < inner_n; r += RP * U) {
                                     Raw<K> raw[U];
                                     sfor<U>([&]<int J>() LI {
                                         const uint32_t ru = r + (uint32_t)J * RP;
                                         const uint32_t rc = ru < inner_n ? ru : r;      // past the end: read row r again, unused
-                                        request_dispatch<K>(raw[J], dt, V, nt, base + (off0 + (int64_t)rc * st1) * es, g);
+                                        request_staged_dispatch<K>(raw[J], dt, V, nt, base + (off0 + (int64_t)rc * st1) * es, g);
                                     });
                                     sfor<U>([&]<int J>() LI {
                                         if (r + (uint32_t)J * RP < inner_n) {
-                                            if (b == R_SUM) widen_dispatch<K, B_ADD>(rr, raw[J], dt, V, g);
-                                            else if (b == R_MAX) widen_dispatch<K, B_MAX>(rr, raw[J], dt, V, g);
-                                            else widen_dispatch<K, B_MIN>(rr, raw[J], dt, V, g);
+                                            if (b == R_SUM) combine_staged_dispatch<K, B_ADD>(rr, raw[J], dt, V, g);
+                                            else if (b == R_MAX) combine_staged_dispatch<K, B_MAX>(rr, raw[J], dt, V, g);
+                                            else combine_staged_dispatch<K, B_MIN>(rr, raw[J], dt, V, g);
                                         }
                                     });
                                 }
@@ -1040,34 +1367,34 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             DVM_WITH_R(a, rr, sfor<K / 4>([&]<int Q>() LI {
                                 if (wave < RP) {
                                     float *mine = &comb_lds[(wave * 64u + lane) * 4u];
-                                    mine[0] = rr.v[4 * Q]; mine[1] = rr.v[4 * Q + 1]; mine[2] = rr.v[4 * Q + 2]; mine[3] = rr.v[4 * Q + 3];
+                                    mine[0] = TV(rr, 4 * Q); mine[1] = TV(rr, 4 * Q + 1); mine[2] = TV(rr, 4 * Q + 2); mine[3] = TV(rr, 4 * Q + 3);
                                 }
                                 __syncthreads();
                                 float c0 = comb_lds[lane * 4u], c1 = comb_lds[lane * 4u + 1], c2 = comb_lds[lane * 4u + 2], c3 = comb_lds[lane * 4u + 3];
                                 for (uint32_t o = 1; o < RP; ++o) {
                                     const float *p = &comb_lds[(o * 64u + lane) * 4u];
                                     if (b == R_SUM) { c0 += p[0]; c1 += p[1]; c2 += p[2]; c3 += p[3]; }
-                                    else if (b == R_MAX) { c0 = f_max(c0, p[0]); c1 = f_max(c1, p[1]); c2 = f_max(c2, p[2]); c3 = f_max(c3, p[3]); }
-                                    else { c0 = f_min(c0, p[0]); c1 = f_min(c1, p[1]); c2 = f_min(c2, p[2]); c3 = f_min(c3, p[3]); }
+                                    else if (b == R_MAX) { c0 = f_maxp(c0, p[0]); c1 = f_maxp(c1, p[1]); c2 = f_maxp(c2, p[2]); c3 = f_maxp(c3, p[3]); }
+                                    else { c0 = f_minp(c0, p[0]); c1 = f_minp(c1, p[1]); c2 = f_minp(c2, p[2]); c3 = f_minp(c3, p[3]); }
                                 }
                                 __syncthreads();
-                                rr.v[4 * Q] = c0; rr.v[4 * Q + 1] = c1; rr.v[4 * Q + 2] = c2; rr.v[4 * Q + 3] = c3;
+                                TV(rr, 4 * Q) = c0; TV(rr, 4 * Q + 1) = c1; TV(rr, 4 * Q + 2) = c2; TV(rr, 4 * Q + 3) = c3;
                             }))
                             gt.rowok = (rp == 0) && (tid < seg_threads);
                         }
                         break;
                     case I_SEL:         // every pair of registers gets its own copy of the loop: no tile is copied
-                        DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] != 0.0f ? xa.v[I] : xb.v[I]; })))
+                        DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { TV(acc, I) = TV(acc, I) != 0.0f ? TV(xa, I) : TV(xb, I); })))
                         break;
                     case I_FMA: {
                         const float s = cw1 != 0 ? DVM_GET_S(cw1 - 1) : 1.0f;
                         if constexpr (NR <= 4) {        // one loop per (multiplier, addend) pair of registers
                             if (cw1 == 0) {
-                                DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I], xa.v[I], xb.v[I]); })))
+                                DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { TV(acc, I) = f_fma(TV(acc, I), TV(xa, I), TV(xb, I)); })))
                             } else if (b == FMA_NO_ADDEND) {
-                                DVM_WITH_R(a, xa, sfor<K>([&]<int I>() LI { acc.v[I] = acc.v[I] * s * xa.v[I]; }))
+                                DVM_WITH_R(a, xa, sfor<K>([&]<int I>() LI { TV(acc, I) = TV(acc, I) * s * TV(xa, I); }))
                             } else {
-                                DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { acc.v[I] = f_fma(acc.v[I] * s, xa.v[I], xb.v[I]); })))
+                                DVM_WITH_R(a, xa, DVM_WITH_R2(b, xb, sfor<K>([&]<int I>() LI { TV(acc, I) = f_fma(TV(acc, I) * s, TV(xa, I), TV(xb, I)); })))
                             }
                         } else {                        // many registers: the pairs would multiply the code size
                             if (cw1 != 0) tile_bins<K, B_MUL>(acc, s);
@@ -1089,7 +1416,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             v = red_lds[red_par][w0i & 15];
                             for (uint32_t i = 1; i < gw; ++i) {
                                 const float o = red_lds[red_par][(w0i + i) & 15];
-                                v = b == R_MAX ? f_max(v, o) : (b == R_MIN ? f_min(v, o) : v + o);
+                                v = b == R_MAX ? f_maxp(v, o) : (b == R_MIN ? f_minp(v, o) : v + o);
                             }
                             red_par ^= 1;
                         }
@@ -1119,9 +1446,9 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             }
             if constexpr (CRED) {   // next step of this unit, or the next tile
                 const uint32_t inner = sh[S_INNER];
-                if (inner == 0 || (rin + 1) * RP >= inner || (sh[S_FLAGS] & SF_CSTREAM)) { rin = 0; ++tile; } else { ++rin; }
+                if (inner == 0 || (rin + 1) * RP >= inner || (sh[S_FLAGS] & SF_CSTREAM)) { rin = 0; tile += t_step; } else { ++rin; }
             } else {
-                ++tile;
+                tile += t_step;
             }
         }
         seg += seg_words;
@@ -1136,34 +1463,42 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 // which defines the kernel and a launcher; the translation unit without those macros holds the
 // host side.  The build script reads this list.
 #define DVM_VARIANT_LIST(X) \
-    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 6) X(8, 6, 512, 4) \
-    X(16, 2, 1024, 4) X(16, 4, 512, 3) X(16, 6, 512, 2) X(32, 2, 256, 2) X(32, 4, 256, 2)
+    X(4, 2, 1024, 8) X(4, 6, 1024, 8) X(8, 2, 1024, 7) X(8, 6, 512, 4) \
+    X(16, 2, 1024, 6) X(16, 4, 512, 4) X(16, 6, 512, 3) X(32, 2, 256, 4) X(32, 4, 256, 2)
 
 // (the variants also built as the instantiation that runs reductions along the penultimate axis)
 #define DVM_CRED_VARIANT_LIST(X) \
-    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 6) X(8, 6, 512, 4) X(16, 6, 512, 2) X(32, 2, 256, 2) X(32, 4, 256, 2)
+    X(4, 2, 1024, 4) X(4, 6, 1024, 4) X(8, 2, 1024, 4) X(8, 6, 512, 4) X(16, 6, 512, 3) X(32, 2, 256, 3) X(32, 4, 256, 2)
 
 #define DVM_LAUNCHER_NAME_(K, NR) dvm_vm_launch_##K##_##NR
 #define DVM_LAUNCHER_NAME(K, NR) DVM_LAUNCHER_NAME_(K, NR)
 #define DVM_CRED_LAUNCHER_NAME_(K, NR) dvm_vm_launch_c_##K##_##NR
 #define DVM_CRED_LAUNCHER_NAME(K, NR) DVM_CRED_LAUNCHER_NAME_(K, NR)
+#define DVM_WIDE_LAUNCHER_NAME_(K, NR) dvm_vm_launch_w_##K##_##NR
+#define DVM_WIDE_LAUNCHER_NAME(K, NR) DVM_WIDE_LAUNCHER_NAME_(K, NR)
 
 }  // namespace
 
 #ifdef DVM_VARIANT_K
 // ---- one interpreter variant: kernel instantiation + launcher ---------------------------------
-#ifdef DVM_VARIANT_CRED
+#if defined(DVM_VARIANT_CRED)
 extern "C" void DVM_CRED_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, true>), dim3(grid), dim3(block), lds_bytes,
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, true, false>), dim3(grid), dim3(block), lds_bytes,
+#elif defined(DVM_VARIANT_WIDE)
+extern "C" void DVM_WIDE_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false, true>), dim3(grid), dim3(block), lds_bytes,
 #else
 extern "C" void DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false>), dim3(grid), dim3(block), lds_bytes,
+    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false, false>), dim3(grid), dim3(block), lds_bytes,
 #endif
                        (hipStream_t)stream, *(const KArgs *)kargs);
 }
 #else
 // ---- host side: dvm_run ---------------------------------------------------------------------
 #define X(K, NR, MAXT, W) extern "C" void DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
+DVM_VARIANT_LIST(X)
+#undef X
+#define X(K, NR, MAXT, W) extern "C" void DVM_WIDE_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
 DVM_VARIANT_LIST(X)
 #undef X
 #define X(K, NR, MAXT, W) extern "C" void DVM_CRED_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
@@ -1176,6 +1511,9 @@ typedef void (*vm_launch_t)(unsigned, unsigned, unsigned, void *, const void *);
 struct VariantEntry { int K, NR; vm_launch_t launch; };
 #define X(K, NR, MAXT, W) {K, NR, DVM_LAUNCHER_NAME(K, NR)},
 const VariantEntry g_variants[] = {DVM_VARIANT_LIST(X)};
+#undef X
+#define X(K, NR, MAXT, W) {K, NR, DVM_WIDE_LAUNCHER_NAME(K, NR)},
+const VariantEntry g_wide_variants[] = {DVM_VARIANT_LIST(X)};
 #undef X
 #define X(K, NR, MAXT, W) {K, NR, DVM_CRED_LAUNCHER_NAME(K, NR)},
 const VariantEntry g_cred_variants[] = {DVM_CRED_VARIANT_LIST(X)};
@@ -1231,17 +1569,21 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     // A segment that reduces along the penultimate axis needs the instantiation that runs such segments,
     // and LDS for the combination across waves: four floats per lane of every participating wave
     uint32_t lds_bytes = 0;
-    bool cred = false;
+    bool cred = false, wide = true;     // wide: every segment spreads a row over whole waves
     for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
         const uint32_t *sh = w + at;
         const uint32_t rp = sh[S_RP] & 0xFFFF;
         cred |= sh[S_INNER] != 0;
+        wide &= (sh[S_GEOM] & 0xFFFF) >= 64;
         if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
         at += sh[S_WORDS];
     }
     vm_launch_t launch = nullptr;
     if (cred) {
         for (const VariantEntry &v : g_cred_variants)
+            if (v.K == K && v.NR == NR) launch = v.launch;
+    } else if (wide) {
+        for (const VariantEntry &v : g_wide_variants)
             if (v.K == K && v.NR == NR) launch = v.launch;
     } else {
         for (const VariantEntry &v : g_variants)

@@ -101,12 +101,12 @@ def test_stacked_with_a_row_program():
 
 
 @pytest.mark.parametrize("waves", [1, 3, 16])
-def test_any_number_of_waves_per_unit(waves, monkeypatch):
+def test_any_number_of_waves_per_unit(waves):
     # the planner picks the waves that share a unit; the debug override walks the other settings,
     # among them one wave (no combination step) and a count that does not divide the reduced extent
     say(f"col_stats with {waves} wave(s) per unit")
-    monkeypatch.setenv("DVM_DEBUG_RP", str(waves))
     ctx = B.Context(torch.cuda.current_device())
+    ctx.set_plan_override(rows_per_tile=waves)
     desc = W.get_program("col_stats")
     ins = {"x": randn((5, 37, 300), 7600 + waves), "b": randn((300,), 7601)}
     outs, code = H.run_vm(desc, ins, ctx=ctx)
@@ -152,13 +152,13 @@ def test_empty_outer_extent_launches_nothing():
     assert tuple(outs["s"].shape) == (0, 1, 7) and code.info().n_tiles == 0
 
 
-def test_stacked_under_a_larger_workgroup(monkeypatch):
+def test_stacked_under_a_larger_workgroup():
     # four waves share a unit; the stacked launch runs sixteen waves per workgroup (a softmax over rows of 8192
     # elements at eight elements per lane): the twelve waves outside the reduction's workgroup hold no rows but
     # take part in its combination step's synchronisation
     say("stack colsum (4 waves per unit) + softmax_f32 rows of 8192 (1024 threads)")
-    monkeypatch.setenv("DVM_DEBUG_RP", "4")
     ctx = B.Context(torch.cuda.current_device())
+    ctx.set_plan_override(rows_per_tile=4)
     ctx.set_limits(8, 6)
     x = randn((12, 70, 520), 7900)
     z = randn((24, 8192), 7901)

@@ -96,9 +96,14 @@ def test_buffers_of_different_shapes_run_in_order():
     f.flush()
     torch.cuda.synchronize()
     assert f.stats()["launches"] == 3
-    assert torch.allclose(ea, torch.tanh(a), atol=1e-6)
-    assert torch.allclose(eb, torch.sigmoid(b), atol=1e-6)
-    assert torch.allclose(sa, torch.tanh(a) * a, atol=1e-6)
+    # the oracle evaluates the same three operators
+    pa = _p("tanh_then_mul", [("a", "f32")], [("t", "tanh", ["a"], {}), ("m", "mul", ["t", "a"], {})], [("t", "f32"), ("m", "f32")])
+    pb = _p("sigmoid_b", [("b", "f32")], [("s", "sigmoid", ["b"], {})], [("s", "f32")])
+    ra, xa = H.run_oracle(pa, {"a": a})
+    rb, xb = H.run_oracle(pb, {"b": b})
+    H.compare(ea, ra["t"], xa["t"], "f32", False, "fuser tanh")
+    H.compare(sa, ra["m"], xa["m"], "f32", False, "fuser tanh * a")
+    H.compare(eb, rb["s"], xb["s"], "f32", False, "fuser sigmoid")
 
 
 def test_reduction_along_the_penultimate_axis_joins_the_buffer():
@@ -122,9 +127,12 @@ def test_reduction_along_the_penultimate_axis_joins_the_buffer():
     torch.cuda.synchronize()
     st = f.stats()
     assert st["ops"] == 4 and st["launches"] >= 2, st
-    want_l = np.log(np.exp(H.to_np64(x)).sum(axis=-2, keepdims=True))
-    H.compare(l, want_l.astype(np.float32).astype(np.float64), want_l, "f32", True, "fuser logsumexp over columns")
-    want_d = H.to_np64(x) - want_l
-    H.compare(d, want_d.astype(np.float32).astype(np.float64), want_d, "f32", True, "fuser x - logsumexp")
+    # the oracle evaluates the same four operators
+    prog = _p("col_logsumexp", [("x", "f32")],
+              [("e", "exp", ["x"], {}), ("s", "csum", ["e"], {}), ("l", "log", ["s"], {}), ("d", "sub", ["x", "l"], {})],
+              [("l", "f32"), ("d", "f32")])
+    rounded, exact = H.run_oracle(prog, {"x": x})
+    H.compare(l, rounded["l"], exact["l"], "f32", True, "fuser logsumexp over columns")
+    H.compare(d, rounded["d"], exact["d"], "f32", True, "fuser x - logsumexp")
     for v in (vx, vl, vd):
         f.release(v)

@@ -98,6 +98,23 @@ def test_alg2_assignment_partitions_tiles():
     assert tiling.vm_tile_range(10, 4, 3) == (9, 10)
 
 
+def test_interleaved_assignment_partitions_tiles_like_the_blocked_one():
+    for M in list(range(0, 80)) + [199, 200]:
+        for N in (1, 2, 3, 7, 40, 64):
+            seen = []
+            for cid in range(N):
+                mine = tiling.interleaved_tiles(M, N, cid)
+                lo, hi = tiling.vm_tile_range(M, N, cid)
+                # as many tiles as Algorithm 2's m = ceil(M/N), or fewer; never more than one apart between cores
+                assert len(mine) <= tiling.ceil_div(M, N) if M else not mine
+                assert all(b - a == N for a, b in zip(mine, mine[1:]))
+                seen += mine
+                assert hi - lo <= tiling.ceil_div(M, N) if M else hi == lo
+            assert sorted(seen) == list(range(M))
+            counts = [len(tiling.interleaved_tiles(M, N, c)) for c in range(N)]
+            assert max(counts) - min(counts) <= 1
+
+
 # ------------------------------------------------------------------ storage rounding
 
 def test_bf16_rounding_matches_library_and_ties_to_even():
@@ -159,6 +176,71 @@ def test_elementwise_ops_bruteforce_with_broadcast(op):
         for idx in itertools.product(*[range(n) for n in bshape]):
             want = fn(*[float(b[idx]) for b in barrs])
             assert got[idx] == pytest.approx(want, rel=1e-14, abs=1e-300), (op, idx)
+
+
+def _c_pow(a, b):
+    try:
+        return math.pow(a, b)
+    except ValueError:          # the C library's domain error: a finite negative base with a non-integer exponent
+        return float("nan")
+    except OverflowError:       # (math.pow raises where the C library returns an infinity)
+        return float("inf") if not (a < 0 and float(b).is_integer() and int(b) % 2 == 1) else float("-inf")
+
+
+def test_pow_min_max_special_values():
+    # Pow on negative bases, zeros, infinities and NaN against the C library's pow (through math.pow)
+    bases = [-8.0, -2.5, -1.0, -0.5, 0.0, 0.5, 1.0, 2.0, 9.0, math.inf, -math.inf, math.nan]
+    exps = [-3.0, -2.0, -1.0, -0.5, 0.0, 0.5, 1.0, 2.0, 3.0, 4.0, 2.5, 17.0, math.inf, -math.inf, math.nan]
+    a = np.array(bases)[:, None] * np.ones((1, len(exps)))
+    b = np.ones((len(bases), 1)) * np.array(exps)[None, :]
+    _, ex = run(single_op_program("pow", 2), a0=a, a1=b)
+    for i, x in enumerate(bases):
+        for j, y in enumerate(exps):
+            if x == 0.0 and y < 0:
+                want = math.inf          # (math.pow raises for a zero base with a negative exponent; C returns +inf for +0)
+            else:
+                want = _c_pow(x, y)
+            got = ex["y"][i, j]
+            assert (math.isnan(got) and math.isnan(want)) or got == pytest.approx(want, rel=1e-15), (x, y, got, want)
+    # (-2)^3 = -8, (-2)^2 = 4, (-8)^(1/3) is not a real power: NaN
+    _, ex = run(single_op_program("pow", 2), a0=np.array([-2.0, -2.0, -8.0]), a1=np.array([3.0, 2.0, 1.0 / 3.0]))
+    assert ex["y"][0] == -8.0 and ex["y"][1] == 4.0 and math.isnan(ex["y"][2])
+    # Min / Max propagate a NaN operand, element-wise and as reductions along either axis
+    x = np.array([[1.0, math.nan, -math.inf, 0.0], [2.0, 3.0, math.inf, -0.0]])
+    y = np.array([[math.nan, 5.0, 7.0, 1.0], [1.0, 4.0, 2.0, 0.0]])
+    for op, pick in (("max", max), ("min", min)):
+        _, ex = run(single_op_program(op, 2), a0=x, a1=y)
+        for idx in itertools.product(range(2), range(4)):
+            u, v = x[idx], y[idx]
+            want = math.nan if (math.isnan(u) or math.isnan(v)) else pick(u, v)
+            got = ex["y"][idx]
+            assert (math.isnan(got) and math.isnan(want)) or got == want, (op, idx)
+    for op, axis, pick in (("rmax", -1, max), ("rmin", -1, min), ("cmax", -2, max), ("cmin", -2, min)):
+        _, ex = run(single_op_program(op, 1), a0=x)
+        lines = x if axis == -1 else x.T
+        want = [math.nan if any(math.isnan(t) for t in line) else pick(line) for line in lines]
+        got = ex["y"].reshape(-1)
+        assert len(got) == len(want)
+        for g_, w_ in zip(got, want):
+            assert (math.isnan(g_) and math.isnan(w_)) or g_ == w_, (op, got, want)
+
+
+def test_row_scale_hand_computed():
+    # RMS over the finite entries of each row (last axis), kept with extent 1: rows (3, 4, inf) and (nan, 0, -6)
+    x = np.array([[3.0, 4.0, math.inf], [math.nan, 0.0, -6.0]])
+    s = interp.row_scale(x)
+    assert s.shape == (2, 1)
+    assert s[0, 0] == pytest.approx(math.sqrt((9 + 16) / 2), rel=1e-15)
+    assert s[1, 0] == pytest.approx(math.sqrt(36 / 2), rel=1e-15)
+    # a wrong axis would give per-column values: shape (1, 3)
+    x3 = np.arange(24, dtype=np.float64).reshape(2, 3, 4)
+    s3 = interp.row_scale(x3)
+    assert s3.shape == (2, 3, 1)
+    for i in range(2):
+        for j in range(3):
+            assert s3[i, j, 0] == pytest.approx(math.sqrt(sum(v * v for v in x3[i, j]) / 4), rel=1e-15)
+    # a row without any finite entry has scale 0
+    assert interp.row_scale(np.array([[math.nan, math.inf]]))[0, 0] == 0.0
 
 
 def test_ops_against_torch_cpu_float64():
