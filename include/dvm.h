@@ -172,9 +172,38 @@ int  dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog,
 
 /* Temporal stacking (Section 5.1): concatenate n encoded programs into one launch.  The stacked
  * program's tensor list is the concatenation of the parts' tensor lists, in order.  The parts
- * must be independent of each other (no part reads what another writes). */
+ * must be independent of each other (no part reads what another writes): dvm_run refuses a launch
+ * in which a buffer one part writes overlaps a buffer of another part (DVM_E_ARGS).  For parts that
+ * depend on each other use dvm_stack_dependent. */
 int  dvm_stack(const void *const *codes, const size_t *lens, int n,
                void *out, size_t cap, size_t *len);
+
+/* Temporal stacking of parts that depend on each other (Section 5.1: stacking does not require independent
+ * operators; Section 5.2: the pieces a fuser cuts an unmergeable operator sequence into run as one stacked
+ * kernel).  As dvm_stack, plus `same_as[n_same_as]`: one entry per tensor of the launch (part 0's tensors, then
+ * part 1's, ...), -1 or the index of an EARLIER entry that is the same buffer (the caller passes the same device
+ * pointer for both to dvm_run, which checks it).  A part that touches a buffer an earlier part wrote, or writes
+ * one an earlier part read, starts behind a synchronisation point:
+ *   - if producer and consumer deal the same rows of that buffer to the same workgroups (same number of rows
+ *     and rows per tile, whole rows per tile, the buffer addressed by plain row index in both), a workgroup only
+ *     waits for its own earlier stores;
+ *   - otherwise every workgroup of the launch waits until all have finished the earlier parts.  That needs
+ *     DVM_WORKSPACE_BYTES of device memory the caller lends to the launch: the stacked program then lists one
+ *     more tensor, the workspace (dvm_code_tensor reports it with is_output = 2), and the caller passes its
+ *     device pointer (256-byte aligned) as the LAST entry of tensors[].  dvm_run clears it before the launch.
+ *     Launches that share a workspace must not overlap in time.  The wait is bounded (dvm_ctx_set_sync_limit):
+ *     a workgroup whose wait runs out sets the workspace's status word and leaves the kernel, and so do all the
+ *     others at their next wait; dvm_workspace_status reads the word back.
+ * Parts must be encoded programs or independent stacks, not dependent stacks themselves. */
+#define DVM_WORKSPACE_BYTES 256
+int  dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as,
+                         void *out, size_t cap, size_t *len);
+/* Upper bound on the polls (about a microsecond each) a workgroup spends at a grid-wide synchronisation point
+ * before it gives up; the default is about one million.  polls < 1 is an error. */
+int  dvm_ctx_set_sync_limit(dvm_ctx *ctx, int64_t polls);
+/* Wait for `hip_stream` and read the status word of a workspace: *gave_up = 1 if a launch that used it since it
+ * was last cleared abandoned a synchronisation point (its outputs are then incomplete), else 0. */
+int  dvm_workspace_status(const void *workspace, void *hip_stream, int *gave_up);
 
 /* Spatial stacking (Section 5.1): like dvm_stack, but the parts run side by side in the one launch,
  * each on its own share of the workgroups (in proportion to an estimate of the part's run time: tiles
@@ -187,10 +216,14 @@ int  dvm_stack_spatial(const void *const *codes, const size_t *lens, int n,
 
 /* ---- streaming fuser for dynamic graphs (Section 5.2, dynamic graph fuser) -----------------------
  * Operators arrive one at a time, as an eager framework issues them.  They are buffered lazily and
- * fused on arrival while their iteration spaces merge; the buffer runs as ONE launch when an
- * operator arrives that does not fuse, when the buffer is full, or on dvm_fuser_flush (a host read,
- * a stream synchronisation).  A result the caller released before the buffer ran is a pure
- * intermediate and is never written to memory.
+ * fused on arrival while their iteration spaces merge.  An operator that does not merge cuts the buffer
+ * and opens its next piece; when the buffer runs -- it is full, or dvm_fuser_flush is called (a host
+ * read, a stream synchronisation) -- the pieces are stacked into ONE launch (dvm_stack_dependent: a later
+ * piece waits for the earlier ones whose results it reads).  A result the caller released before the
+ * buffer ran, and that no later piece reads, is a pure intermediate and is never written to memory.
+ * Pieces that wait for each other grid-wide need the workspace of dvm_fuser_set_workspace; without one,
+ * or when the pieces do not fit one launch (tensor table, bytecode size, interpreter variant), every
+ * piece is launched on its own, in order.
  *
  * All calls are host calls.  The fuser owns no device memory: every tensor and every result buffer
  * is the caller's (device pointers), and must stay valid until the buffer that uses it has run.
@@ -200,6 +233,10 @@ typedef struct dvm_fuser dvm_fuser;
 
 int  dvm_fuser_create(dvm_ctx *ctx, void *hip_stream, dvm_fuser **out);
 void dvm_fuser_destroy(dvm_fuser *f);
+/* Lend the fuser DVM_WORKSPACE_BYTES (or more) of 256-byte aligned device memory for the waits of its stacked
+ * launches (see dvm_stack_dependent); it must stay valid while the fuser uses it and belongs to this fuser's
+ * stream alone.  NULL takes it back. */
+int  dvm_fuser_set_workspace(dvm_fuser *f, void *workspace, size_t bytes);
 /* Register a tensor that already holds data; *value receives its id. */
 int  dvm_fuser_tensor(dvm_fuser *f, void *device_ptr, int dtype, const dvm_shape *shape, int *value);
 /* Issue an operator on earlier values (same opcodes and immediates as dvm_prog_op).  `out_ptr` is the
@@ -238,7 +275,8 @@ typedef struct dvm_code_info {
     int64_t  code_bytes;       /* over all segments (CodeSize, summed)                            */
 } dvm_code_info;
 int  dvm_code_info_get(const void *bytecode, size_t len, dvm_code_info *info);
-/* Minimum size in bytes of the buffer behind tensors[index], and whether it is written. */
+/* Minimum size in bytes of the buffer behind tensors[index], and whether it is written (*is_output: 0 an
+ * input, 1 an output, 2 the launch's workspace, see dvm_stack_dependent). */
 int  dvm_code_tensor(const void *bytecode, size_t len, int index,
                      int64_t *min_bytes, int *is_output, int *dtype, int *align_bytes);
 

@@ -88,6 +88,9 @@ def load() -> C.CDLL:
         "dvm_encode": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), P(dvm_shape)]),
         "dvm_stack": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
         "dvm_stack_spatial": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
+        "dvm_stack_dependent": (i, [P(vp), P(sz), i, P(i), i, vp, sz, P(sz)]),
+        "dvm_ctx_set_sync_limit": (i, [vp, C.c_int64]),
+        "dvm_workspace_status": (i, [vp, vp, P(i)]),
         "dvm_validate": (i, [vp, sz]),
         "dvm_disasm": (i, [vp, sz, C.c_char_p, sz]),
         "dvm_code_info_get": (i, [vp, sz, P(dvm_code_info)]),
@@ -101,6 +104,7 @@ def load() -> C.CDLL:
         "dvm_last_hip_error": (i, []),
         "dvm_fuser_create": (i, [vp, vp, P(vp)]),
         "dvm_fuser_destroy": (None, [vp]),
+        "dvm_fuser_set_workspace": (i, [vp, vp, sz]),
         "dvm_fuser_tensor": (i, [vp, vp, i, P(dvm_shape), P(i)]),
         "dvm_fuser_op": (i, [vp, i, P(i), i, P(C.c_double), i, i, vp, P(i)]),
         "dvm_fuser_release": (i, [vp, i]),
@@ -119,9 +123,10 @@ def load() -> C.CDLL:
 EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_ctx_set_limits",
             "dvm_ctx_set_plan_override", "dvm_ctx_set_assignment", "dvm_prog_create",
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
-            "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_validate", "dvm_disasm",
+            "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_stack_dependent",
+            "dvm_ctx_set_sync_limit", "dvm_workspace_status", "dvm_validate", "dvm_disasm",
             "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_encode_timed", "dvm_copy_kernel", "dvm_strerror", "dvm_last_error_detail",
-            "dvm_last_hip_error", "dvm_fuser_create", "dvm_fuser_destroy", "dvm_fuser_tensor", "dvm_fuser_op",
+            "dvm_last_hip_error", "dvm_fuser_create", "dvm_fuser_destroy", "dvm_fuser_set_workspace", "dvm_fuser_tensor", "dvm_fuser_op",
             "dvm_fuser_release", "dvm_fuser_flush", "dvm_fuser_stats", "dvm_fuser_last_code"]
 
 
@@ -176,6 +181,9 @@ class Context:
     def set_plan_override(self, elems_per_lane: int = 0, rows_per_tile: int = 0, grid_multiplier: int = 0) -> None:
         _check(load().dvm_ctx_set_plan_override(self._h, elems_per_lane, rows_per_tile, grid_multiplier),
                "dvm_ctx_set_plan_override")
+
+    def set_sync_limit(self, polls: int) -> None:
+        _check(load().dvm_ctx_set_sync_limit(self._h, polls), "dvm_ctx_set_sync_limit")
 
     def set_assignment(self, assignment: str) -> None:
         _check(load().dvm_ctx_set_assignment(self._h, {"blocked": 0, "interleaved": 1}[assignment]), "dvm_ctx_set_assignment")
@@ -256,6 +264,15 @@ class Bytecode:
                                       C.byref(al)), "dvm_code_tensor")
         return mb.value, bool(io.value), dt.value, al.value
 
+    def needs_workspace(self) -> bool:
+        """True if the launch's last tensor is its workspace (a dependent stack with a grid-wide synchronisation point)."""
+        n = self.info().n_tensors
+        if n == 0:
+            return False
+        io = C.c_int()
+        _check(load().dvm_code_tensor(self.ptr, len(self.raw), n - 1, None, C.byref(io), None, None), "dvm_code_tensor")
+        return io.value == 2
+
     def disasm(self) -> str:
         buf = C.create_string_buffer(1 << 16)
         _check(load().dvm_disasm(self.ptr, len(self.raw), buf, len(buf)), "dvm_disasm")
@@ -303,6 +320,33 @@ def dvm_stack_spatial(codes: Sequence[Bytecode]) -> Bytecode:
     return dvm_stack(codes, spatial=True)
 
 
+def dvm_stack_dependent(codes: Sequence[Bytecode], same_as: Sequence[int]) -> Bytecode:
+    """same_as: one entry per tensor of the launch (part after part), -1 or the index of an earlier entry that is
+    the same buffer.  If the result lists a workspace (its last tensor), pass WORKSPACE_BYTES of device memory for it."""
+    lib = load()
+    n = len(codes)
+    ptrs = (C.c_void_p * n)(*[c.ptr for c in codes])
+    lens = (C.c_size_t * n)(*[len(c) for c in codes])
+    sa = (C.c_int * max(len(same_as), 1))(*same_as)
+    buf = C.create_string_buffer(_ENC_CAP)
+    ln = C.c_size_t()
+    _check(lib.dvm_stack_dependent(ptrs, lens, n, sa, len(same_as), buf, _ENC_CAP, C.byref(ln)), "dvm_stack_dependent")
+    shapes: List[Tuple[int, ...]] = []
+    for c in codes:
+        shapes.extend(c.out_shapes)
+    return Bytecode(buf.raw[: ln.value], shapes)
+
+
+WORKSPACE_BYTES = 256
+
+
+def workspace_gave_up(workspace_ptr: int, stream: int = 0) -> bool:
+    """Waits for the stream; True if a launch abandoned a synchronisation point since the workspace was cleared."""
+    g = C.c_int()
+    _check(load().dvm_workspace_status(C.c_void_p(workspace_ptr), C.c_void_p(stream), C.byref(g)), "dvm_workspace_status")
+    return bool(g.value)
+
+
 def dvm_run(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: int = 0) -> None:
     n = len(tensor_ptrs)
     arr = (C.c_void_p * max(n, 1))(*tensor_ptrs)
@@ -318,6 +362,9 @@ class Fuser:
         self._h = C.c_void_p()
         self._ctx = ctx
         _check(load().dvm_fuser_create(ctx._h, C.c_void_p(stream), C.byref(self._h)), "dvm_fuser_create")
+
+    def set_workspace(self, ptr: int, nbytes: int) -> None:
+        _check(load().dvm_fuser_set_workspace(self._h, C.c_void_p(ptr), nbytes), "dvm_fuser_set_workspace")
 
     def tensor(self, ptr: int, dtype: str, shape: dvm_shape) -> int:
         v = C.c_int()

@@ -47,7 +47,7 @@ constexpr int PH_WORDS_N = PH_WORDS_COUNT;
 
 // tensor table entry
 enum : int {
-    TT_INFO = 0,    // dtype | is_output << 8 | log2(assumed pointer alignment in bytes) << 16
+    TT_INFO = 0,    // dtype | is_output << 8 | is_workspace << 9 | log2(assumed pointer alignment in bytes) << 16
     TT_BYTES_LO,    // minimum size of the buffer in bytes
     TT_BYTES_HI,
     TT_WORDS
@@ -84,11 +84,23 @@ enum : int {
     SH_WORDS
 };
 static_assert(SH_WORDS % 4 == 0, "segment header must keep records 16-byte aligned");
+// The workspace of a launch (a tensor of its own, the last of the launch, flagged in the tensor table): device memory
+// the caller lends to the launch.  Its first words are the synchronisation area; dvm_run clears it before the launch.
+constexpr uint32_t TI_OUTPUT = 1u << 8, TI_WORKSPACE = 1u << 9;
+enum : int { WS_ARRIVED = 0, WS_STATUS = 1, WS_SYNC_WORDS = 16 };      // (64 bytes)
+constexpr uint32_t WS_STATUS_GAVE_UP = 1;   // a workgroup's bounded wait ran out: the launch's results are incomplete
 constexpr int LEN_REC = 4;              // length of every record except the view forms
 constexpr uint32_t SF_WGSYNC  = 1u;     // rows span several waves: reductions use the barrier
 constexpr uint32_t SF_RAGGED  = 2u;     // some tile has invalid rows or columns: mask reductions
 constexpr uint32_t SF_CSTREAM = 4u;     // reducing segment whose per-row part is I_CSTREAM records only: one step per unit
 constexpr uint32_t SF_INTERLEAVED = 8u; // workgroup id runs tiles id, id + N, id + 2N, ... instead of Algorithm 2's blocked range
+// A stacked meta-kernel that reads what an earlier meta-kernel of the same launch wrote (Section 5.1: temporal
+// stacking does not require independent operators) starts behind a synchronisation point:
+constexpr uint32_t SF_SYNC_WG   = 16u;  // its producer ran with the same tile-to-workgroup assignment over the same rows: a
+                                        // workgroup reads only rows it wrote itself, so it waits for its own stores only
+constexpr uint32_t SF_SYNC_GRID = 32u;  // any other dependence: every workgroup of the launch has finished the segments before
+                                        // (an arrival counter in the launch's workspace; the wait is bounded and gives up
+                                        // through the workspace's status word)
 
 // ---- instruction ids --------------------------------------------------------------------------
 enum : uint32_t {

@@ -93,6 +93,7 @@ struct dvm_ctx {
     int dbg_grid_x; // workgroups launched per resident slot (default 1)
     int dbg_rp;     // rows per tile, or waves per unit of a reduction along the penultimate axis (0 = cost model)
     int assignment; // DVM_ASSIGN_*: how the tiles of a meta-kernel are dealt out to the workgroups
+    int64_t sync_limit;     // polls a workgroup spends at a grid-wide synchronisation point before it gives up
 };
 
 extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
@@ -108,6 +109,7 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->dbg_grid_x = 1;
     c->dbg_rp = 0;
     c->assignment = DVM_ASSIGN_INTERLEAVED;
+    c->sync_limit = 1 << 20;
     if (hip_device >= 0) {
         int n = 0;
         int st = dvm_ctx_query_device(hip_device, &n);
@@ -154,6 +156,13 @@ extern "C" int dvm_ctx_set_plan_override(dvm_ctx *c, int elems_per_lane, int row
     c->dbg_grid_x = grid_multiplier > 0 ? grid_multiplier : 1;
     return DVM_OK;
 }
+
+extern "C" int dvm_ctx_set_sync_limit(dvm_ctx *c, int64_t polls) {
+    if (!c || polls < 1) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_sync_limit: null context or limit below 1");
+    c->sync_limit = polls > 0x7FFFFFFF ? 0x7FFFFFFF : polls;
+    return DVM_OK;
+}
+extern "C" int64_t dvm_ctx_sync_limit(const dvm_ctx *c) { return c ? c->sync_limit : 0; }
 
 extern "C" int dvm_ctx_set_assignment(dvm_ctx *c, int assignment) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
@@ -1425,9 +1434,13 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             // whole number of waves and at most 256 threads (or one row if a row needs more)
             const uint32_t step = G < 64 ? 64 / G : 1;
             const uint32_t rp_max = G >= 256 ? 1 : 256 / G;
+            // (with plenty of rows a workgroup of four waves is the smallest candidate: tiles of 8 KiB and more per
+            // tensor measured 3-4 % faster than the same rows dealt out two waves at a time)
+            uint32_t rp_first = step;
+            if (rp_max > step && E.nrows >= (int64_t)8 * ctx->n_cu * rp_max) rp_first = rp_max;
             int64_t best_cost = -1;
-            RP = step;
-            for (uint32_t rp = step; rp <= (rp_max > step ? rp_max : step); rp += step) {
+            RP = rp_first;
+            for (uint32_t rp = rp_first; rp <= (rp_max > step ? rp_max : step); rp += step) {
                 const uint32_t threads = rp * G;
                 if (threads > (uint32_t)vr.max_threads) break;
                 const int64_t N = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
@@ -1671,7 +1684,14 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         const uint32_t info = w[PH_WORDS_N + t * TT_WORDS + TT_INFO];
         if ((info & 0xFF) > 1) return bad("tensor dtype");
         if (((info >> 16) & 0xFF) > 8) return bad("tensor alignment");
+        if ((info >> 24) > t) return bad("a tensor names a later one as the same buffer");
+        if (info & TI_WORKSPACE) {
+            if (t + 1 != ntens || kt != KT_STACK) return bad("the workspace is the last tensor of a temporally stacked program");
+            const uint64_t bytes = (uint64_t)w[PH_WORDS_N + t * TT_WORDS + TT_BYTES_LO] | ((uint64_t)w[PH_WORDS_N + t * TT_WORDS + TT_BYTES_HI] << 32);
+            if (bytes < WS_SYNC_WORDS * 4 || (info >> 24) != 0 || ((info >> 16) & 0xFF) < 6) return bad("workspace entry");
+        }
     }
+    const bool has_ws = ntens > 0 && (w[PH_WORDS_N + (ntens - 1) * TT_WORDS + TT_INFO] & TI_WORKSPACE);
     if ((words - at) * 4 > DVM_CODE_MAX_BYTES) return bad("segments exceed the per-launch limit");
     uint64_t tiles_total = 0;
     uint32_t wg_next = 0;       // spatial stacking: first workgroup of the next segment's share
@@ -1743,7 +1763,11 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         bool prolog_a_ends_on_record = sh[S_PROLOGA] == 0;
         bool epilog_on_record = sh[S_INNER] == 0 || sh[S_EPILOG] == 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
-        if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
+        if ((uint64_t)tbase + nt > ntens - (has_ws ? 1u : 0u)) return bad("segment tensor range");
+        if (sh[S_FLAGS] & (SF_SYNC_WG | SF_SYNC_GRID)) {
+            if (kt != KT_STACK) return bad("synchronisation point outside a temporally stacked program");
+            if ((sh[S_FLAGS] & SF_SYNC_GRID) && !has_ws) return bad("grid-wide synchronisation without a workspace");
+        }
         tiles_total += M;
         // body
         size_t pc = at + SH_WORDS;
@@ -1888,13 +1912,50 @@ extern "C" int dvm_code_tensor(const void *bytecode, size_t len, int index, int6
     if (index < 0 || (uint32_t)index >= w[PH_NTENS]) return dvm_set_error(DVM_E_ARGS, "dvm_code_tensor: index");
     const uint32_t *tt = w + PH_WORDS_N + index * TT_WORDS;
     if (min_bytes) *min_bytes = (int64_t)((uint64_t)tt[TT_BYTES_LO] | ((uint64_t)tt[TT_BYTES_HI] << 32));
-    if (is_output) *is_output = (int)((tt[TT_INFO] >> 8) & 1);
+    if (is_output) *is_output = (tt[TT_INFO] & TI_WORKSPACE) ? 2 : (int)((tt[TT_INFO] >> 8) & 1);
     if (dtype) *dtype = (int)(tt[TT_INFO] & 0xFF);
     if (align_bytes) *align_bytes = 1 << ((tt[TT_INFO] >> 16) & 0xFF);
     return DVM_OK;
 }
 
-static int stack_impl(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len, bool spatial) {
+namespace {
+
+// Does every record of segment `sh` that names its tensor `t` address it row by row with the flat row index
+// (the short memory record, or a row-scalar record with one stride) and row stride `*s1`?  (*s1 < 0: take it
+// from the first such record.)  False if a record uses another form.
+bool rows_addressed_flat(const uint32_t *sh, uint32_t t, int64_t *s1) {
+    for (uint32_t pc = SH_WORDS; pc < sh[S_WORDS]; pc += (sh[pc] >> 8) & 0xFF) {
+        const uint32_t op = sh[pc] & 0xFF;
+        const bool mem = op == I_LOAD || op == I_STORE, view = op == I_VLOAD || op == I_VSTORE || op == I_CSTREAM;
+        const bool rowv = op == I_LOADS || op == I_STORES;
+        if (!(mem || view || rowv) || (sh[pc + 1] & 0xFF) != t) continue;
+        if (view) return false;
+        const int64_t st = (int64_t)((uint64_t)sh[pc + 2] | ((uint64_t)sh[pc + 3] << 32));
+        if (rowv && (sh[pc + 4] | sh[pc + 5] | sh[pc + 6] | sh[pc + 7]) != 0) return false;
+        if (*s1 < 0) *s1 = st;
+        if (st != *s1) return false;
+    }
+    return true;
+}
+
+// Producer segment A (its tensor ta) and consumer segment B (its tensor tb, the same buffer): does every
+// workgroup of the launch touch in B only rows of the buffer that it touched itself in A?  True when both
+// segments deal the same rows and columns to the same tiles (equal row count, rows per tile, column tiles and
+// tile width, the same assignment of tiles to workgroups, no outer dims) and both address the buffer by the
+// flat row index.
+bool same_rows_per_workgroup(const uint32_t *A, uint32_t ta, const uint32_t *B, uint32_t tb) {
+    if (A[S_INNER] != 0 || B[S_INNER] != 0 || A[S_NCT] != B[S_NCT] || (A[S_NCT] != 1 && A[S_TC] != B[S_TC])) return false;
+    if (A[S_NROWS] != B[S_NROWS] || (A[S_RP] & 0xFFFF) != (B[S_RP] & 0xFFFF) || A[S_NTILES] != B[S_NTILES]) return false;
+    if (A[S_D1] != 0 || B[S_D1] != 0) return false;
+    if ((A[S_FLAGS] & SF_INTERLEAVED) != (B[S_FLAGS] & SF_INTERLEAVED)) return false;
+    int64_t s1 = -1;
+    return rows_addressed_flat(A, ta, &s1) && rows_addressed_flat(B, tb, &s1);
+}
+
+}  // namespace
+
+static int stack_impl(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as, void *out, size_t cap,
+                      size_t *len, bool spatial) {
     if (!codes || !lens || !len || n < 1) return dvm_set_error(DVM_E_ARGS, "dvm_stack: bad argument");
     size_t seg_words = 0;
     uint32_t ntens = 0, nseg = 0, block = 0, K = 0, NR = 0;
@@ -1923,6 +1984,9 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
     }
     grid = grid / ((block + 63) / 64);
     if (grid == 0 && nseg > 0) grid = 1;
+    if (same_as && (uint32_t)n_same_as != ntens) return dvm_set_error(DVM_E_ARGS, "dvm_stack_dependent: one same_as entry per tensor of the launch");
+    for (uint32_t t = 0; same_as && t < ntens; ++t)
+        if (same_as[t] < -1 || same_as[t] >= (int)t) return dvm_set_error(DVM_E_ARGS, "dvm_stack_dependent: same_as names an earlier entry, or -1");
     if (ntens > DVM_MAX_TENSORS) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: too many tensors for one launch");
     if (nseg > 64) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: too many segments");
     if (seg_words * 4 > DVM_CODE_MAX_BYTES) return dvm_set_error(DVM_E_LIMIT, "dvm_stack: bytecode exceeds the per-launch limit");
@@ -1935,7 +1999,17 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
         }
     }
     if (!vr) return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_stack: no interpreter variant fits all parts");
-    const size_t words = PH_WORDS_N + (size_t)ntens * TT_WORDS + seg_words;
+    // (a dependent stack may need the workspace entry: reserve its place, drop it again if no segment waits grid-wide)
+    const uint32_t ntens_parts = ntens;
+    if (same_as) {
+        if (ntens + 1 > DVM_MAX_TENSORS) return dvm_set_error(DVM_E_LIMIT, "dvm_stack_dependent: too many tensors for one launch");
+        for (int i = 0; i < n; ++i)
+            if (((const uint32_t *)codes[i])[PH_NTENS] > 0 &&
+                (((const uint32_t *)codes[i])[PH_WORDS_N + (((const uint32_t *)codes[i])[PH_NTENS] - 1) * TT_WORDS + TT_INFO] & TI_WORKSPACE))
+                return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_stack_dependent: a part is itself a dependent stack");
+        ++ntens;
+    }
+    size_t words = PH_WORDS_N + (size_t)ntens * TT_WORDS + seg_words;
     *len = words * 4;
     if (!out || cap < words * 4) return dvm_set_error(DVM_E_BUFSZ, "dvm_stack: buffer too small");
     uint32_t *w = (uint32_t *)out;
@@ -1978,6 +2052,65 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
         }
         sg += sw;
         tbase += nt;
+    }
+    if (same_as) {
+        // Dependences between the parts follow from the buffers they share: a part that touches a buffer an
+        // earlier part wrote (or writes one an earlier part read) starts behind a synchronisation point.
+        uint32_t *tt0 = w + PH_WORDS_N;
+        uint32_t *seg_of_part[64];          // first segment of every part
+        uint32_t part_of[DVM_MAX_TENSORS], local_of[DVM_MAX_TENSORS], root[DVM_MAX_TENSORS];
+        uint32_t nsegs_of_part[64];
+        {
+            uint32_t t = 0, at = PH_WORDS_N + ntens * TT_WORDS;
+            for (int i = 0; i < n; ++i) {
+                const uint32_t *c = (const uint32_t *)codes[i];
+                seg_of_part[i] = w + at;
+                nsegs_of_part[i] = c[PH_NSEG];
+                for (uint32_t k = 0; k < c[PH_NTENS]; ++k, ++t) { part_of[t] = (uint32_t)i; local_of[t] = k; }
+                for (uint32_t sgi = 0; sgi < c[PH_NSEG]; ++sgi) at += w[at + S_WORDS];
+            }
+        }
+        for (uint32_t t = 0; t < ntens_parts; ++t) {
+            root[t] = same_as[t] < 0 ? t : root[same_as[t]];
+            if (same_as[t] >= 0) {
+                if ((tt0[t * TT_WORDS + TT_INFO] & 0xFF) != (tt0[root[t] * TT_WORDS + TT_INFO] & 0xFF))
+                    return dvm_set_error(DVM_E_DTYPE, "dvm_stack_dependent: entries named as the same buffer differ in dtype");
+                tt0[t * TT_WORDS + TT_INFO] |= (uint32_t)(same_as[t] + 1) << 24;
+            }
+        }
+        bool any_grid = false;
+        for (uint32_t t = 0; t < ntens_parts; ++t) {
+            if (same_as[t] < 0) continue;
+            const uint32_t pi = part_of[t];
+            for (uint32_t u = 0; u < t; ++u) {
+                if (root[u] != root[t] || part_of[u] >= pi) continue;
+                const bool wu = (tt0[u * TT_WORDS + TT_INFO] & TI_OUTPUT) != 0, wt = (tt0[t * TT_WORDS + TT_INFO] & TI_OUTPUT) != 0;
+                if (!wu && !wt) continue;           // both parts only read it
+                uint32_t *cons = seg_of_part[pi];
+                const uint32_t *prod = seg_of_part[part_of[u]];
+                const bool aligned = nsegs_of_part[pi] == 1 && nsegs_of_part[part_of[u]] == 1 &&
+                                     same_rows_per_workgroup(prod, local_of[u], cons, local_of[t]);
+                cons[S_FLAGS] |= aligned ? SF_SYNC_WG : SF_SYNC_GRID;
+            }
+        }
+        for (int i = 0; i < n; ++i) {
+            uint32_t *sh = seg_of_part[i];
+            if (sh[S_FLAGS] & SF_SYNC_GRID) { sh[S_FLAGS] &= ~SF_SYNC_WG; any_grid = true; }
+        }
+        if (any_grid) {
+            uint32_t *te = tt0 + ntens_parts * TT_WORDS;
+            te[TT_INFO] = (uint32_t)DVM_F32 | TI_WORKSPACE | (8u << 16);
+            te[TT_BYTES_LO] = DVM_WORKSPACE_BYTES;
+            te[TT_BYTES_HI] = 0;
+        } else {
+            // no workspace after all: close the gap its table entry left
+            memmove(tt0 + ntens_parts * TT_WORDS, tt0 + ntens * TT_WORDS, seg_words * 4);
+            --ntens;
+            words -= TT_WORDS;
+            w[PH_WORDS] = (uint32_t)words;
+            w[PH_NTENS] = ntens;
+            *len = words * 4;
+        }
     }
     if (spatial) {
         // Spatial stacking (Section 5.1): the segments run side by side, each on a share of the workgroups
@@ -2046,7 +2179,13 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, void 
 }
 
 extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {
-    return stack_impl(codes, lens, n, out, cap, len, false);
+    return stack_impl(codes, lens, n, nullptr, 0, out, cap, len, false);
+}
+
+extern "C" int dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as,
+                                   void *out, size_t cap, size_t *len) {
+    if (!same_as) return dvm_set_error(DVM_E_ARGS, "dvm_stack_dependent: null same_as");
+    return stack_impl(codes, lens, n, same_as, n_same_as, out, cap, len, false);
 }
 
 extern "C" int dvm_stack_spatial(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {
@@ -2054,7 +2193,7 @@ extern "C" int dvm_stack_spatial(const void *const *codes, const size_t *lens, i
         if (dvm_validate(codes[i], lens[i]) == DVM_OK && (((const uint32_t *)codes[i])[PH_TYPE] & 0xFFFF) != KT_META)
             return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_stack_spatial: parts must be single meta-kernels");
     }
-    return stack_impl(codes, lens, n, out, cap, len, true);
+    return stack_impl(codes, lens, n, nullptr, 0, out, cap, len, true);
 }
 
 namespace {
@@ -2102,8 +2241,11 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
           w[PH_NSEG], w[PH_NTENS], w[PH_WORDS]);
     for (uint32_t t = 0; t < w[PH_NTENS]; ++t) {
         const uint32_t *tt = w + PH_WORDS_N + t * TT_WORDS;
-        o.put("  tensor %u: %s %s min_bytes=%llu\n", t, (tt[TT_INFO] & 0xFF) ? "bf16" : "f32", ((tt[TT_INFO] >> 8) & 1) ? "out" : "in",
+        o.put("  tensor %u: %s %s min_bytes=%llu", t, (tt[TT_INFO] & 0xFF) ? "bf16" : "f32",
+              (tt[TT_INFO] & TI_WORKSPACE) ? "workspace" : ((tt[TT_INFO] & TI_OUTPUT) ? "out" : "in"),
               (unsigned long long)((uint64_t)tt[TT_BYTES_LO] | ((uint64_t)tt[TT_BYTES_HI] << 32)));
+        if (tt[TT_INFO] >> 24) o.put(" same_buffer_as=%u", (tt[TT_INFO] >> 24) - 1);
+        o.put("\n");
     }
     size_t at = PH_WORDS_N + (size_t)w[PH_NTENS] * TT_WORDS;
     for (uint32_t s = 0; s < w[PH_NSEG]; ++s) {
@@ -2116,6 +2258,8 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
               (unsigned long long)((uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32)), sh[S_GEOM] & 0xFFFF,
               (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE],
               (sh[S_FLAGS] & SF_INTERLEAVED) ? "interleaved" : "blocked");
+        if (sh[S_FLAGS] & SF_SYNC_GRID) o.put("  ; waits until every workgroup has finished the segments before\n");
+        else if (sh[S_FLAGS] & SF_SYNC_WG) o.put("  ; waits for this workgroup's own stores of the segments before\n");
         size_t pc = at + SH_WORDS;
         const size_t end = pc + sh[S_CODESIZE];
         if (sh[S_PROLOGA]) o.put("  ; prologue (once per workgroup)\n");

@@ -1,11 +1,14 @@
 // Streaming fuser for dynamic graphs (Section 5.2 of the paper, "dynamic graph fuser"): operators
-// arrive one at a time, as an eager framework issues them; they are buffered lazily, fused as they
-// arrive while their iteration spaces merge, and executed as one VM launch when an operator arrives
-// that does not fuse, when the buffer is full, or when the caller asks for a result (flush).
-// Values that the caller released before the flush are pure intermediates and never reach memory.
+// arrive one at a time, as an eager framework issues them; they are buffered lazily and fused as they
+// arrive while their iteration spaces merge.  An operator that does not merge with the buffered ones
+// cuts the buffer: it opens the next piece, and at the flush the pieces are encoded one by one and
+// stacked into ONE launch, later pieces waiting for the earlier ones they read (cut-and-stack: a
+// sequence that is no single meta-kernel still runs as one kernel).  The buffer runs when it is
+// full or when the caller asks for a result (flush).  Values that the caller released before the flush
+// and that no later piece reads are pure intermediates and never reach memory.
 //
-// Built on the public C ABI only (program builder, dvm_encode, dvm_run): host code, no HIP call of
-// its own.
+// Built on the public C ABI only (program builder, dvm_encode, dvm_stack_dependent, dvm_run): host
+// code, no HIP call of its own.
 #include <stdint.h>
 #include <string.h>
 
@@ -19,6 +22,8 @@ namespace {
 constexpr int MAX_VALUES = 4096;        // values alive in one fuser (tensors + pending results)
 constexpr int MAX_PENDING = 48;         // operators buffered before a forced flush
 constexpr int MAX_GROUP_TENSORS = 24;   // distinct tensors (inputs + results) of one launch
+constexpr int MAX_PIECES = 8;           // pieces of one launch
+constexpr size_t PIECE_CODE_CAP = 4096;
 
 struct Val {
     uint8_t used, pending, released, dtype;
@@ -42,10 +47,14 @@ struct dvm_fuser {
     int n_vals_hint;                    // search start for a free slot
     PendingOp ops[MAX_PENDING];
     int n_ops;
-    dvm_shape dom;                      // broadcast of the shapes of the buffered results
+    int piece_lo[MAX_PIECES + 1];       // piece k holds ops [piece_lo[k], piece_lo[k + 1]); the last one is open
+    int n_pieces;
+    dvm_shape dom;                      // broadcast of the shapes of the results of the open piece
+    void *workspace;                    // device memory lent for grid-wide waits (dvm_fuser_set_workspace), or null
     int64_t stat_ops, stat_launches, stat_flushes, stat_elided;
     unsigned char code[8192];
     size_t code_len;
+    unsigned char piece_code[MAX_PIECES][PIECE_CODE_CAP];
 };
 
 namespace {
@@ -83,9 +92,24 @@ int alloc_value(dvm_fuser *f) {
 
 bool valid_value(const dvm_fuser *f, int v) { return v >= 0 && v < MAX_VALUES && f->vals[v].used; }
 
-// Execute ops [lo, hi) of the buffer as one program.  Results that are still referenced are written
-// to their buffers and become plain tensors; released ones are dropped.
-int run_range(dvm_fuser *f, int lo, int hi) {
+// Is the result of a buffered operator read by an operator at or after index `from`?
+bool read_later(const dvm_fuser *f, int value, int from) {
+    for (int i = from; i < f->n_ops; ++i)
+        for (int a = 0; a < f->ops[i].n_args; ++a)
+            if (f->ops[i].args[a] == value) return true;
+    return false;
+}
+
+struct Piece {          // ops [lo, hi) as one encoded program and its tensors (inputs, then outputs)
+    size_t code_len;
+    int n_in, n_out;
+    void *tensors[DVM_MAX_TENSORS];
+    int values[DVM_MAX_TENSORS];        // the fuser value behind every tensor
+};
+
+// Encode ops [lo, hi) of the buffer as one program into `code`.  Its outputs are the results that the caller still
+// references or that a later buffered operator reads; the others stay in tile registers.
+int encode_range(dvm_fuser *f, int lo, int hi, unsigned char *code, size_t cap, Piece *pc) {
     dvm_prog *p = nullptr;
     int st = dvm_prog_create(&p);
     if (st != DVM_OK) return st;
@@ -93,23 +117,26 @@ int run_range(dvm_fuser *f, int lo, int hi) {
     int map_val[MAX_PENDING * 4 + MAX_GROUP_TENSORS], map_ssa[MAX_PENDING * 4 + MAX_GROUP_TENSORS], n_map = 0;
     auto find = [&](int v) { for (int i = 0; i < n_map; ++i) if (map_val[i] == v) return map_ssa[i]; return -1; };
     dvm_shape in_shapes[DVM_MAX_TENSORS];
-    void *tensors[DVM_MAX_TENSORS];
-    int n_in = 0;
-    // inputs: every argument that is not produced inside the range, in first-use order
+    pc->n_in = pc->n_out = 0;
+    pc->code_len = 0;
+    // inputs: every argument that is not produced inside the range, in first-use order (a tensor, or the result
+    // of an earlier piece, which is in its buffer by the time this piece runs)
     for (int i = lo; i < hi && st == DVM_OK; ++i) {
         const PendingOp &o = f->ops[i];
         for (int a = 0; a < o.n_args && st == DVM_OK; ++a) {
             const int v = o.args[a];
-            bool inside = false;
+            bool inside = false, earlier = false;
             for (int j = lo; j < i; ++j) inside |= f->ops[j].value == v;
+            for (int j = 0; j < lo; ++j) earlier |= f->ops[j].value == v;
             if (inside || find(v) >= 0) continue;
-            if (f->vals[v].pending) { st = dvm_set_error(DVM_E_STATE, "dvm_fuser: argument is neither a tensor nor buffered"); break; }
-            if (n_in >= DVM_MAX_TENSORS) { st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: too many tensors in one launch"); break; }
+            if (f->vals[v].pending && !earlier) { st = dvm_set_error(DVM_E_STATE, "dvm_fuser: argument is neither a tensor nor buffered"); break; }
+            if (pc->n_in >= DVM_MAX_TENSORS) { st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: too many tensors in one launch"); break; }
             int id = -1;
             st = dvm_prog_input(p, f->vals[v].dtype, &id);
             map_val[n_map] = v; map_ssa[n_map++] = id;
-            in_shapes[n_in] = f->vals[v].shape;
-            tensors[n_in++] = f->vals[v].ptr;
+            in_shapes[pc->n_in] = f->vals[v].shape;
+            pc->values[pc->n_in] = v;
+            pc->tensors[pc->n_in++] = f->vals[v].ptr;
         }
     }
     for (int i = lo; i < hi && st == DVM_OK; ++i) {
@@ -120,49 +147,59 @@ int run_range(dvm_fuser *f, int lo, int hi) {
         st = dvm_prog_op(p, o.opcode, ids, o.n_args, o.imm, o.n_imm, &id);
         map_val[n_map] = o.value; map_ssa[n_map++] = id;
     }
-    int n_out = 0;
-    int out_vals[MAX_PENDING];
     for (int i = lo; i < hi && st == DVM_OK; ++i) {
         const int v = f->ops[i].value;
-        if (f->vals[v].released) continue;
-        if (n_in + n_out >= DVM_MAX_TENSORS) { st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: too many tensors in one launch"); break; }
+        if (f->vals[v].released && !read_later(f, v, hi)) continue;
+        if (pc->n_in + pc->n_out >= DVM_MAX_TENSORS) { st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: too many tensors in one launch"); break; }
         st = dvm_prog_output(p, find(v), f->vals[v].dtype);
-        tensors[n_in + n_out] = f->vals[v].ptr;
-        out_vals[n_out++] = v;
+        pc->values[pc->n_in + pc->n_out] = v;
+        pc->tensors[pc->n_in + pc->n_out++] = f->vals[v].ptr;
     }
-    if (st == DVM_OK && n_out > 0) {
+    if (st == DVM_OK && pc->n_out > 0) {
         st = dvm_prog_finish(p);
         dvm_shape out_shapes[DVM_MAX_TENSORS];
-        if (st == DVM_OK) st = dvm_encode(f->ctx, p, in_shapes, n_in, nullptr, f->code, sizeof(f->code), &f->code_len, out_shapes);
-        if (st == DVM_OK && dvm_ctx_device(f->ctx) >= 0)
-            st = dvm_run(f->ctx, f->code, f->code_len, tensors, n_in + n_out, f->stream);
-        if (st == DVM_OK) {
-            ++f->stat_launches;
-            for (int k = 0; k < n_out; ++k) {
-                Val &v = f->vals[out_vals[k]];
-                if (v.shape.rank != out_shapes[k].rank || memcmp(v.shape.dim, out_shapes[k].dim, sizeof(int64_t) * v.shape.rank) != 0)
-                    st = dvm_set_error(DVM_E_SHAPE, "dvm_fuser: inferred shape differs from the encoder's");
-            }
+        if (st == DVM_OK) st = dvm_encode(f->ctx, p, in_shapes, pc->n_in, nullptr, code, cap, &pc->code_len, out_shapes);
+        for (int k = 0; k < pc->n_out && st == DVM_OK; ++k) {
+            const Val &v = f->vals[pc->values[pc->n_in + k]];
+            if (v.shape.rank != out_shapes[k].rank || memcmp(v.shape.dim, out_shapes[k].dim, sizeof(int64_t) * v.shape.rank) != 0)
+                st = dvm_set_error(DVM_E_SHAPE, "dvm_fuser: inferred shape differs from the encoder's");
         }
     }
     dvm_prog_destroy(p);
-    if (st != DVM_OK) return st;
+    return st;
+}
+
+// The results of ops [lo, hi) have run as one program: they are plain tensors now.  (Released ones are freed at the
+// end of the flush: a later piece may still read them.)
+void settle(dvm_fuser *f, int lo, int hi) {
     for (int i = lo; i < hi; ++i) {
         Val &v = f->vals[f->ops[i].value];
-        if (v.released) { v.used = 0; ++f->stat_elided; }
-        else v.pending = 0;
+        v.pending = 0;
+        if (v.released && !read_later(f, f->ops[i].value, hi)) ++f->stat_elided;    // it never reached memory
     }
+}
+
+// Execute ops [lo, hi) of the buffer as one launch.
+int run_range(dvm_fuser *f, int lo, int hi) {
+    Piece pc;
+    int st = encode_range(f, lo, hi, f->code, sizeof(f->code), &pc);
+    if (st != DVM_OK) return st;
+    if (pc.n_out > 0) {
+        f->code_len = pc.code_len;
+        if (dvm_ctx_device(f->ctx) >= 0) st = dvm_run(f->ctx, f->code, f->code_len, pc.tensors, pc.n_in + pc.n_out, f->stream);
+        if (st != DVM_OK) return st;
+        ++f->stat_launches;
+    }
+    settle(f, lo, hi);
     return DVM_OK;
 }
 
-int flush_all(dvm_fuser *f) {
-    if (f->n_ops == 0) return DVM_OK;
-    ++f->stat_flushes;
-    int st = run_range(f, 0, f->n_ops);
+// One piece as a launch of its own; if it is no single meta-kernel after all (registers, tensor table, iteration
+// space), operator by operator: every result then reaches its buffer, released or not.
+int run_piece_alone(dvm_fuser *f, int lo, int hi) {
+    int st = run_range(f, lo, hi);
     if (st == DVM_E_UNSUPPORTED || st == DVM_E_LIMIT || st == DVM_E_RANK) {
-        // the chain does not fit one meta-kernel after all (registers, tensor table, iteration space):
-        // run it operator by operator; every result then reaches its buffer, released or not
-        for (int i = 0; i < f->n_ops; ++i) {
+        for (int i = lo; i < hi; ++i) {
             Val &v = f->vals[f->ops[i].value];
             const uint8_t was_released = v.released;
             v.released = 0;
@@ -170,13 +207,86 @@ int flush_all(dvm_fuser *f) {
             v.released = was_released;
             if (st != DVM_OK) break;
         }
-        if (st == DVM_OK)
-            for (int i = 0; i < f->n_ops; ++i) {
-                Val &v = f->vals[f->ops[i].value];
-                if (v.released) v.used = 0;
+    }
+    return st;
+}
+
+// All pieces as one launch: encode each, stack them with the dependences that follow from the values they share.
+// DVM_E_UNSUPPORTED / DVM_E_LIMIT / DVM_E_RANK: the caller falls back to one launch per piece.
+int run_stacked(dvm_fuser *f) {
+    Piece pcs[MAX_PIECES];
+    const void *codes[MAX_PIECES];
+    size_t lens[MAX_PIECES];
+    void *tensors[DVM_MAX_TENSORS];
+    int values[DVM_MAX_TENSORS], same_as[DVM_MAX_TENSORS];
+    int n_parts = 0, n_t = 0;
+    for (int k = 0; k < f->n_pieces; ++k) {
+        Piece &pc = pcs[n_parts];
+        int st = encode_range(f, f->piece_lo[k], f->piece_lo[k + 1], f->piece_code[n_parts], PIECE_CODE_CAP, &pc);
+        if (st == DVM_E_BUFSZ) st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: a piece's bytecode exceeds the fuser's buffer");
+        if (st != DVM_OK) return st;
+        if (pc.n_out == 0) continue;        // every result released and unread: nothing to run
+        if (n_t + pc.n_in + pc.n_out + 1 > DVM_MAX_TENSORS) return dvm_set_error(DVM_E_LIMIT, "dvm_fuser: too many tensors in one launch");
+        for (int t = 0; t < pc.n_in + pc.n_out; ++t) {
+            same_as[n_t] = -1;
+            for (int u = 0; u < n_t; ++u)
+                if (values[u] == pc.values[t]) { same_as[n_t] = u; break; }
+            values[n_t] = pc.values[t];
+            tensors[n_t++] = pc.tensors[t];
+        }
+        codes[n_parts] = f->piece_code[n_parts];
+        lens[n_parts] = pc.code_len;
+        ++n_parts;
+    }
+    if (n_parts > 0) {
+        int st;
+        if (n_parts == 1) {
+            memcpy(f->code, codes[0], lens[0]);
+            f->code_len = lens[0];
+        } else {
+            st = dvm_stack_dependent(codes, lens, n_parts, same_as, n_t, f->code, sizeof(f->code), &f->code_len);
+            if (st == DVM_E_BUFSZ) st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: the stacked bytecode exceeds the fuser's buffer");
+            if (st != DVM_OK) return st;
+            int is_ws = 0;
+            dvm_code_info info;
+            st = dvm_code_info_get(f->code, f->code_len, &info);
+            if (st == DVM_OK) st = dvm_code_tensor(f->code, f->code_len, info.n_tensors - 1, nullptr, &is_ws, nullptr, nullptr);
+            if (st != DVM_OK) return st;
+            if (is_ws == 2) {
+                if (!f->workspace) return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_fuser: the pieces need a grid-wide wait and the fuser has no workspace");
+                tensors[n_t++] = f->workspace;
             }
+        }
+        if (dvm_ctx_device(f->ctx) >= 0) {
+            st = dvm_run(f->ctx, f->code, f->code_len, tensors, n_t, f->stream);
+            if (st != DVM_OK) return st;
+        }
+        ++f->stat_launches;
+    }
+    for (int k = 0; k < f->n_pieces; ++k) settle(f, f->piece_lo[k], f->piece_lo[k + 1]);
+    return DVM_OK;
+}
+
+int flush_all(dvm_fuser *f) {
+    if (f->n_ops == 0) return DVM_OK;
+    ++f->stat_flushes;
+    f->piece_lo[f->n_pieces] = f->n_ops;
+    int st = f->n_pieces > 1 ? run_stacked(f) : DVM_E_UNSUPPORTED;
+    if (st == DVM_E_UNSUPPORTED || st == DVM_E_LIMIT || st == DVM_E_RANK) {
+        for (int k = 0; k < f->n_pieces; ++k) {
+            st = run_piece_alone(f, f->piece_lo[k], f->piece_lo[k + 1]);
+            if (st != DVM_OK) break;
+        }
+    }
+    if (st == DVM_OK) {
+        for (int i = 0; i < f->n_ops; ++i) {
+            Val &v = f->vals[f->ops[i].value];
+            if (v.released) v.used = 0;
+        }
     }
     f->n_ops = 0;
+    f->n_pieces = 1;
+    f->piece_lo[0] = 0;
     f->dom.rank = 0;
     return st;
 }
@@ -190,6 +300,7 @@ extern "C" int dvm_fuser_create(dvm_ctx *ctx, void *hip_stream, dvm_fuser **out)
     memset(f, 0, sizeof(*f));
     f->ctx = ctx;
     f->stream = hip_stream;
+    f->n_pieces = 1;
     *out = f;
     return DVM_OK;
 }
@@ -230,11 +341,17 @@ extern "C" int dvm_fuser_op(dvm_fuser *f, int opcode, const int *args, int n_arg
         for (int k = 0; k < s.rank; ++k) dims[k] = s.dim[k];
         dvm_shape_contiguous(&s, s.rank, dims);
     }
-    // fuse on arrival: the operator joins the buffer if its iteration space merges with the buffered
-    // ones (its result broadcasts with their dominant shape, or is that shape reduced along the row)
-    // and the launch stays within its limits; otherwise the buffer runs first
-    bool fits = f->n_ops < MAX_PENDING;
-    if (fits && f->n_ops > 0) {
+    // fuse on arrival: the operator joins the open piece if its iteration space merges with that piece's
+    // (its result broadcasts with the piece's dominant shape, or is that shape reduced along the row) and the
+    // piece stays within a launch's limits; otherwise it cuts the buffer and opens the next piece; a full
+    // buffer runs first
+    if (f->n_ops >= MAX_PENDING) {
+        int st = flush_all(f);
+        if (st != DVM_OK) return st;
+    }
+    const int lo = f->piece_lo[f->n_pieces - 1];
+    bool fits = true;
+    if (f->n_ops > lo) {
         dvm_shape d = f->dom;
         fits = broadcast_into(d, s);
         if (fits) {
@@ -245,13 +362,18 @@ extern "C" int dvm_fuser_op(dvm_fuser *f, int opcode, const int *args, int n_arg
             fits = same_as_old || same_as_new;
         }
         int distinct = 0;
-        for (int i = 0; i < f->n_ops; ++i) distinct += 1 + f->ops[i].n_args;
+        for (int i = lo; i < f->n_ops; ++i) distinct += 1 + f->ops[i].n_args;
         if (distinct + 1 + n_args > MAX_GROUP_TENSORS * 2) fits = false;
     }
     if (!fits) {
-        int st = flush_all(f);
-        if (st != DVM_OK) return st;
+        if (f->n_pieces < MAX_PIECES) {
+            f->piece_lo[f->n_pieces++] = f->n_ops;      // cut
+        } else {
+            int st = flush_all(f);
+            if (st != DVM_OK) return st;
+        }
     }
+    const bool piece_empty = f->n_ops == f->piece_lo[f->n_pieces - 1];
     const int v = alloc_value(f);
     if (v < 0) return dvm_set_error(DVM_E_LIMIT, "dvm_fuser: too many live values");
     Val &val = f->vals[v];
@@ -266,7 +388,7 @@ extern "C" int dvm_fuser_op(dvm_fuser *f, int opcode, const int *args, int n_arg
     for (int a = 0; a < n_args; ++a) o.args[a] = args[a];
     for (int k = 0; k < n_imm; ++k) o.imm[k] = imm[k];
     o.value = v;
-    if (f->n_ops == 1) f->dom = s;
+    if (piece_empty) f->dom = s;
     else broadcast_into(f->dom, s);
     ++f->stat_ops;
     *value = v;
@@ -284,6 +406,14 @@ extern "C" int dvm_fuser_release(dvm_fuser *f, int value) {
 extern "C" int dvm_fuser_flush(dvm_fuser *f) {
     if (!f) return dvm_set_error(DVM_E_ARGS, "dvm_fuser_flush: null fuser");
     return flush_all(f);
+}
+
+extern "C" int dvm_fuser_set_workspace(dvm_fuser *f, void *workspace, size_t bytes) {
+    if (!f) return dvm_set_error(DVM_E_ARGS, "dvm_fuser_set_workspace: null fuser");
+    if (workspace && (bytes < DVM_WORKSPACE_BYTES || ((uintptr_t)workspace & 255)))
+        return dvm_set_error(DVM_E_ARGS, "dvm_fuser_set_workspace: DVM_WORKSPACE_BYTES of 256-byte aligned device memory, or null");
+    f->workspace = workspace;
+    return DVM_OK;
 }
 
 extern "C" int dvm_fuser_stats(const dvm_fuser *f, int64_t *n_ops, int64_t *n_launches, int64_t *n_flushes, int64_t *n_elided) {

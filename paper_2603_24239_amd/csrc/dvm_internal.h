@@ -14,6 +14,8 @@ int dvm_set_error(int status, const char *detail);
 int dvm_ctx_device(const dvm_ctx *ctx);
 // Planner inputs of the context (either pointer may be null).
 void dvm_ctx_planner_get(const dvm_ctx *ctx, int *n_cu, int *overhead);
+// Bound on the polls of a grid-wide synchronisation point (dvm_ctx_set_sync_limit).
+int64_t dvm_ctx_sync_limit(const dvm_ctx *ctx);
 // Implemented in the device file so that the encoder object stays free of HIP calls.
 int dvm_ctx_query_device(int hip_device, int *n_cu);
 

@@ -36,8 +36,9 @@ constexpr int CODE_WORDS = DVM_CODE_MAX_BYTES / 4;
 struct KArgs {
     uint32_t code[CODE_WORDS];          // the segments of the program (headers + bodies)
     uint64_t tensors[DVM_MAX_TENSORS];  // device addresses
+    uint64_t ws;                        // the launch's workspace (0: none)
     uint32_t nseg;
-    uint32_t pad;
+    uint32_t spin_limit;                // polls a workgroup spends at a grid-wide synchronisation point before it gives up
 };
 
 #define DI __device__ __forceinline__
@@ -943,6 +944,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
     const uint32_t bid = blockIdx.x;
     const uint32_t ngrid = gridDim.x;
     uint32_t red_par = 0;
+    uint32_t n_sync = 0;                    // grid-wide synchronisation points passed so far
     const uint32_t *code = args.code;
     // the launch's tensor addresses, one per lane: a memory record reads the one it needs with a single lane read
     // (the index is wave-uniform) instead of a scalar load whose latency it would have to wait for
@@ -979,6 +981,39 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         const uint32_t gw = G >> 6;             // waves per row when a row spans waves
         const uint32_t width = G < 64 ? G : 64;
         const uint32_t w0i = gw > 1 ? (wave / gw) * gw : wave;   // first wave of this lane's row
+
+        // A segment that depends on earlier ones of this launch waits here (Section 5.1, temporal stacking of
+        // dependent operators).  Release: this workgroup's stores are complete and visible to the device.
+        if (sh[S_FLAGS] & (SF_SYNC_WG | SF_SYNC_GRID)) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            __syncthreads();
+            if (sh[S_FLAGS] & SF_SYNC_GRID) {
+                // every workgroup of the launch arrives once per such point; the grid was sized to be resident as a
+                // whole, so all arrive; should the machine be shared and some never start, the bounded wait ends
+                // with the status word set and this workgroup leaves the kernel
+                ++n_sync;
+                if (tid == 0) {
+                    GLOBAL_AS uint32_t *wsp = (GLOBAL_AS uint32_t *)args.ws;
+                    __hip_atomic_fetch_add(&wsp[WS_ARRIVED], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                    const uint32_t target = n_sync * ngrid;
+                    uint32_t ok = 1;
+                    for (uint32_t spins = 0; __hip_atomic_load(&wsp[WS_ARRIVED], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target; ++spins) {
+                        if (spins >= args.spin_limit || __hip_atomic_load(&wsp[WS_STATUS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            __hip_atomic_store(&wsp[WS_STATUS], WS_STATUS_GAVE_UP, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            ok = 0;
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(16);
+                    }
+                    red_lds[0][0] = __builtin_bit_cast(float, ok);
+                }
+                __syncthreads();
+                const uint32_t go = __builtin_bit_cast(uint32_t, red_lds[0][0]);
+                __syncthreads();
+                if (go == 0) return;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        }
 
         // Algorithm 2: m = ceil(M / N); this workgroup runs tiles [m*id, min(M, m*(id+1))).  In a
         // spatially stacked launch N and id count the workgroups of this segment's share only.
@@ -1481,33 +1516,38 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 
 #ifdef DVM_VARIANT_K
 // ---- one interpreter variant: kernel instantiation + launcher ---------------------------------
+// launcher(grid, block, lds_bytes, stream, kargs, blocks_per_cu): blocks_per_cu null: launch; else only report how
+// many workgroups of this size one compute unit holds at a time.  Returns the hipError_t of the calls it made.
 #if defined(DVM_VARIANT_CRED)
-extern "C" void DVM_CRED_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, true, false>), dim3(grid), dim3(block), lds_bytes,
+#define DVM_THIS_LAUNCHER DVM_CRED_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)
+#define DVM_THIS_KERNEL dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, true, false>
 #elif defined(DVM_VARIANT_WIDE)
-extern "C" void DVM_WIDE_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false, true>), dim3(grid), dim3(block), lds_bytes,
+#define DVM_THIS_LAUNCHER DVM_WIDE_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)
+#define DVM_THIS_KERNEL dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false, true>
 #else
-extern "C" void DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs) {
-    hipLaunchKernelGGL((dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false, false>), dim3(grid), dim3(block), lds_bytes,
+#define DVM_THIS_LAUNCHER DVM_LAUNCHER_NAME(DVM_VARIANT_K, DVM_VARIANT_NR)
+#define DVM_THIS_KERNEL dvm_vm_kernel<DVM_VARIANT_K, DVM_VARIANT_NR, DVM_VARIANT_MAXT, DVM_VARIANT_WAVES, false, false>
 #endif
-                       (hipStream_t)stream, *(const KArgs *)kargs);
+extern "C" int DVM_THIS_LAUNCHER(unsigned grid, unsigned block, unsigned lds_bytes, void *stream, const void *kargs, int *blocks_per_cu) {
+    if (blocks_per_cu) return (int)hipOccupancyMaxActiveBlocksPerMultiprocessor(blocks_per_cu, DVM_THIS_KERNEL, (int)block, lds_bytes);
+    hipLaunchKernelGGL((DVM_THIS_KERNEL), dim3(grid), dim3(block), lds_bytes, (hipStream_t)stream, *(const KArgs *)kargs);
+    return (int)hipGetLastError();
 }
 #else
 // ---- host side: dvm_run ---------------------------------------------------------------------
-#define X(K, NR, MAXT, W) extern "C" void DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
+#define X(K, NR, MAXT, W) extern "C" int DVM_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *, int *);
 DVM_VARIANT_LIST(X)
 #undef X
-#define X(K, NR, MAXT, W) extern "C" void DVM_WIDE_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
+#define X(K, NR, MAXT, W) extern "C" int DVM_WIDE_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *, int *);
 DVM_VARIANT_LIST(X)
 #undef X
-#define X(K, NR, MAXT, W) extern "C" void DVM_CRED_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *);
+#define X(K, NR, MAXT, W) extern "C" int DVM_CRED_LAUNCHER_NAME(K, NR)(unsigned, unsigned, unsigned, void *, const void *, int *);
 DVM_CRED_VARIANT_LIST(X)
 #undef X
 
 namespace {
 
-typedef void (*vm_launch_t)(unsigned, unsigned, unsigned, void *, const void *);
+typedef int (*vm_launch_t)(unsigned, unsigned, unsigned, void *, const void *, int *);
 struct VariantEntry { int K, NR; vm_launch_t launch; };
 #define X(K, NR, MAXT, W) {K, NR, DVM_LAUNCHER_NAME(K, NR)},
 const VariantEntry g_variants[] = {DVM_VARIANT_LIST(X)};
@@ -1520,6 +1560,12 @@ const VariantEntry g_cred_variants[] = {DVM_CRED_VARIANT_LIST(X)};
 #undef X
 
 thread_local int t_last_hip_error = 0;
+
+// clears the synchronisation area of a launch's workspace (a kernel rather than a memset node, so that the
+// clearing may be captured into a HIP graph with the launch it precedes)
+__global__ void dvm_ws_clear(uint32_t *ws) {
+    if (threadIdx.x < WS_SYNC_WORDS) ws[threadIdx.x] = 0;
+}
 
 }  // namespace
 
@@ -1553,30 +1599,64 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
 
     KArgs ka;
     memcpy(ka.code, w + segs_off, (size_t)seg_words * 4);
+    uint64_t size_of[DVM_MAX_TENSORS];
+    ka.ws = 0;
     for (uint32_t i = 0; i < ntens; ++i) {
-        const uint32_t info = w[PH_WORDS_N + i * TT_WORDS + TT_INFO];
+        const uint32_t *te = w + PH_WORDS_N + i * TT_WORDS;
+        const uint32_t info = te[TT_INFO];
         const uint64_t align = 1ull << ((info >> 16) & 0xFF);
         const uint64_t addr = (uint64_t)(uintptr_t)tensors[i];
         if (addr == 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: null tensor pointer");
         if (addr & (align - 1)) return dvm_set_error(DVM_E_ALIGN, "dvm_run: tensor pointer below the alignment the bytecode was encoded for");
+        if ((info >> 24) != 0 && addr != (uint64_t)(uintptr_t)tensors[(info >> 24) - 1])
+            return dvm_set_error(DVM_E_ARGS, "dvm_run: two entries the bytecode names as the same buffer got different pointers");
         ka.tensors[i] = addr;
+        size_of[i] = (uint64_t)te[TT_BYTES_LO] | ((uint64_t)te[TT_BYTES_HI] << 32);
+        if (info & TI_WORKSPACE) ka.ws = addr;
     }
     ka.nseg = w[PH_NSEG];
-    ka.pad = 0;
+    ka.spin_limit = (uint32_t)dvm_ctx_sync_limit(ctx);
 
     const int K = (int)(w[PH_VARIANT] & 0xFF), NR = (int)((w[PH_VARIANT] >> 8) & 0xFF);
-    const uint32_t grid = w[PH_GRID], block = w[PH_BLOCK];
+    uint32_t grid = w[PH_GRID];
+    const uint32_t block = w[PH_BLOCK];
     // A segment that reduces along the penultimate axis needs the instantiation that runs such segments,
     // and LDS for the combination across waves: four floats per lane of every participating wave
     uint32_t lds_bytes = 0;
     bool cred = false, wide = true;     // wide: every segment spreads a row over whole waves
+    bool grid_sync = false;
+    uint8_t seg_of[DVM_MAX_TENSORS];    // the segment a tensor belongs to
+    memset(seg_of, 0xFF, sizeof(seg_of));
     for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
         const uint32_t *sh = w + at;
         const uint32_t rp = sh[S_RP] & 0xFFFF;
         cred |= sh[S_INNER] != 0;
         wide &= (sh[S_GEOM] & 0xFFFF) >= 64;
+        grid_sync |= (sh[S_FLAGS] & SF_SYNC_GRID) != 0;
         if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
+        for (uint32_t t = 0; t < sh[S_NTENS]; ++t) seg_of[sh[S_TBASE] + t] = (uint8_t)s;
         at += sh[S_WORDS];
+    }
+    // Segments of one launch run without order between them unless the bytecode says otherwise: a buffer that
+    // one segment writes must not overlap a buffer of another segment, except where both entries were
+    // declared as the same buffer (dvm_stack_dependent put a synchronisation point between them).
+    if (w[PH_NSEG] > 1) {
+        for (uint32_t i = 0; i < ntens; ++i) {
+            const uint32_t ii = w[PH_WORDS_N + i * TT_WORDS + TT_INFO];
+            if (ii & TI_WORKSPACE) continue;
+            uint32_t root_i = i;
+            while (w[PH_WORDS_N + root_i * TT_WORDS + TT_INFO] >> 24) root_i = (w[PH_WORDS_N + root_i * TT_WORDS + TT_INFO] >> 24) - 1;
+            for (uint32_t j = 0; j < i; ++j) {
+                const uint32_t ij = w[PH_WORDS_N + j * TT_WORDS + TT_INFO];
+                if (seg_of[i] == seg_of[j] || !((ii | ij) & TI_OUTPUT)) continue;
+                if (ka.tensors[i] >= ka.tensors[j] + size_of[j] || ka.tensors[j] >= ka.tensors[i] + size_of[i]) continue;
+                uint32_t root_j = j;
+                while (w[PH_WORDS_N + root_j * TT_WORDS + TT_INFO] >> 24) root_j = (w[PH_WORDS_N + root_j * TT_WORDS + TT_INFO] >> 24) - 1;
+                if (root_i != root_j)
+                    return dvm_set_error(DVM_E_ARGS, "dvm_run: a buffer one stacked part writes overlaps a buffer of another part "
+                                                     "and the bytecode does not order them (dvm_stack_dependent)");
+            }
+        }
     }
     vm_launch_t launch = nullptr;
     if (cred) {
@@ -1590,12 +1670,41 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
             if (v.K == K && v.NR == NR) launch = v.launch;
     }
     if (!launch) return dvm_set_error(DVM_E_BADCODE, "dvm_run: no interpreter variant for this bytecode");
-    launch(grid, block, lds_bytes, hip_stream, &ka);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (grid_sync) {
+        // every workgroup waits for all the others: the whole grid has to be resident at once
+        int per_cu = 0, n_cu = 0;
+        e = (hipError_t)launch(grid, block, lds_bytes, hip_stream, &ka, &per_cu);
+        if (e != hipSuccess) {
+            t_last_hip_error = (int)e;
+            return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
+        }
+        dvm_ctx_planner_get(ctx, &n_cu, nullptr);
+        // (the parts were planned one by one, some for interpreter variants that hold more waves than the
+        // launch's common one: the interpreter deals the tiles out over whatever grid it finds itself in)
+        if (per_cu < 1 || n_cu < 1)
+            return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_run: the device holds no workgroup of this launch's size");
+        if ((uint64_t)grid > (uint64_t)per_cu * (uint64_t)n_cu) grid = (uint32_t)per_cu * (uint32_t)n_cu;
+        hipLaunchKernelGGL(dvm_ws_clear, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (uint32_t *)(uintptr_t)ka.ws);
+    }
+    e = (hipError_t)launch(grid, block, lds_bytes, hip_stream, &ka, nullptr);
     if (e != hipSuccess) {
         t_last_hip_error = (int)e;
         return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
     }
+    return DVM_OK;
+}
+
+extern "C" int dvm_workspace_status(const void *workspace, void *hip_stream, int *gave_up) {
+    if (!workspace || !gave_up) return dvm_set_error(DVM_E_ARGS, "dvm_workspace_status: null argument");
+    uint32_t word = 0;
+    hipError_t e = hipMemcpyAsync(&word, (const uint32_t *)workspace + WS_STATUS, 4, hipMemcpyDeviceToHost, (hipStream_t)hip_stream);
+    if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)hip_stream);
+    if (e != hipSuccess) {
+        t_last_hip_error = (int)e;
+        return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
+    }
+    *gave_up = word != 0;
     return DVM_OK;
 }
 #endif  // host side

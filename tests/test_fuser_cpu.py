@@ -31,16 +31,60 @@ def test_chain_fuses_into_one_launch_and_released_values_never_reach_memory():
     assert f.stats()["launches"] == 2 and v != u
 
 
-def test_unfusable_operator_runs_the_buffer_first():
+def test_unfusable_operator_cuts_the_buffer_and_the_pieces_share_a_launch():
     f = B.Fuser(_ctx())
     a = f.tensor(0x1000, "f32", B.make_shape((8, 128)))
     b = f.tensor(0x2000, "f32", B.make_shape((5, 77)))
     f.op("exp", [a], "f32", 0x3000)
-    assert f.stats()["launches"] == 0
-    f.op("neg", [b], "f32", 0x4000)      # another iteration space: the first operator runs now
-    assert f.stats()["launches"] == 1 and f.stats()["flushes"] == 1
+    f.op("neg", [b], "f32", 0x4000)      # another iteration space: a second piece, nothing runs yet
+    assert f.stats()["launches"] == 0 and f.stats()["flushes"] == 0
     f.flush()
-    assert f.stats()["launches"] == 2
+    assert f.stats()["launches"] == 1
+    txt = f.last_code().disasm()
+    assert "vstack.t" in txt and txt.count("segment ") == 2 and "waits" not in txt
+
+
+def test_a_piece_that_reads_an_earlier_piece_waits_for_it():
+    f = B.Fuser(_ctx())
+    a = f.tensor(0x1000, "f32", B.make_shape((40, 257)))
+    b = f.tensor(0x2000, "f32", B.make_shape((7, 1000)))
+    t = f.op("tanh", [a], "f32", 0x3000)
+    f.op("sigmoid", [b], "f32", 0x4000)         # cut
+    f.op("mul", [t, a], "f32", 0x5000)          # cut again; reads the first piece's result from its buffer
+    f.release(t)                                # released, but a later piece reads it: it is written all the same
+    f.flush()
+    st = f.stats()
+    assert st["launches"] == 1 and st["elided"] == 0
+    txt = f.last_code().disasm()
+    assert txt.count("segment ") == 3
+    # same rows, same tiles: the third piece waits for its own workgroup's stores only, no workspace needed
+    assert txt.count("waits for this workgroup's own stores") == 1 and "workspace" not in txt
+    assert "same_buffer_as=1" in txt            # t: output of piece 0 (tensor 1), input of piece 2
+
+
+def test_pieces_that_need_the_grid_wide_wait_take_the_workspace_or_run_one_by_one():
+    def issue(f):
+        x = f.tensor(0x10000, "f32", B.make_shape((64, 1024)))
+        w = f.tensor(0x20000, "f32", B.make_shape((5, 77)))
+        t = f.op("exp", [x], "f32", 0x30000)
+        f.op("sum", [t], "f32", 0x38000)        # a reduction: this piece is tiled by rows
+        f.op("neg", [w], "f32", 0x40000)        # cut
+        f.op("tanh", [t], "f32", 0x50000)       # cut; element-wise over the flattened tensor: other tiles than the producer's
+        f.flush()
+
+    f = B.Fuser(_ctx())
+    issue(f)
+    assert f.stats()["launches"] == 3           # no workspace: every piece its own launch, in order
+    f = B.Fuser(_ctx())
+    f.set_workspace(0x7000000, B.WORKSPACE_BYTES)
+    issue(f)
+    assert f.stats()["launches"] == 1
+    txt = f.last_code().disasm()
+    assert "waits until every workgroup has finished" in txt and "workspace" in txt
+    with pytest.raises(B.DvmError):
+        f.set_workspace(0x7000010, B.WORKSPACE_BYTES)       # not 256-byte aligned
+    with pytest.raises(B.DvmError):
+        f.set_workspace(0x7000000, 8)
 
 
 def test_reduction_and_its_consumers_share_a_launch():
@@ -106,3 +150,15 @@ def test_reduction_along_the_penultimate_axis_and_its_epilogue_share_a_launch():
     v = f.tensor(0x6000, "f32", B.make_shape((64,)))
     with pytest.raises(B.DvmError):
         f.op("csum", [v], "f32", 0x7000)
+
+
+def test_pieces_that_fit_no_common_interpreter_variant_run_one_by_one():
+    f = B.Fuser(_ctx())
+    f.set_workspace(0x7000000, B.WORKSPACE_BYTES)
+    x = f.tensor(0x10000, "f32", B.make_shape((64, 1024)))
+    w = f.tensor(0x20000, "f32", B.make_shape((5, 77)))
+    t = f.op("exp", [x], "f32", 0x30000)
+    f.op("neg", [w], "f32", 0x40000)
+    f.op("csum", [t], "f32", 0x50000)   # its streaming form runs in the small-tile variants only, exp was planned for a larger one
+    f.flush()
+    assert f.stats()["launches"] == 3

@@ -83,7 +83,7 @@ def test_rmsnorm_issued_op_by_op_equals_the_fused_program():
     H.compare(rows3, rr["r"], re_["r"], "f32", True, "fuser kept row value")
 
 
-def test_buffers_of_different_shapes_run_in_order():
+def test_pieces_of_different_shapes_run_in_order_in_one_launch():
     f = _fuser()
     a = gen.randn((40, 257), 61, DEV)
     b = gen.randn((7, 1000), 62, DEV)
@@ -91,11 +91,12 @@ def test_buffers_of_different_shapes_run_in_order():
     va = f.tensor(a.data_ptr(), "f32", B.shape_of_tensor(a))
     vb = f.tensor(b.data_ptr(), "f32", B.shape_of_tensor(b))
     t = f.op("tanh", [va], "f32", ea.data_ptr())
-    f.op("sigmoid", [vb], "f32", eb.data_ptr())          # does not fuse with the first: it runs now
-    f.op("mul", [t, va], "f32", sa.data_ptr())           # uses the first result as a plain tensor
+    f.op("sigmoid", [vb], "f32", eb.data_ptr())          # does not fuse with the first: a second piece
+    f.op("mul", [t, va], "f32", sa.data_ptr())           # a third piece; reads the first one's result from its buffer
     f.flush()
     torch.cuda.synchronize()
-    assert f.stats()["launches"] == 3
+    assert f.stats()["launches"] == 1                    # cut-and-stack: the three pieces are one launch
+    assert f.last_code().disasm().count("segment ") == 3
     # the oracle evaluates the same three operators
     pa = _p("tanh_then_mul", [("a", "f32")], [("t", "tanh", ["a"], {}), ("m", "mul", ["t", "a"], {})], [("t", "f32"), ("m", "f32")])
     pb = _p("sigmoid_b", [("b", "f32")], [("s", "sigmoid", ["b"], {})], [("s", "f32")])
@@ -136,3 +137,59 @@ def test_reduction_along_the_penultimate_axis_joins_the_buffer():
     H.compare(d, rounded["d"], exact["d"], "f32", True, "fuser x - logsumexp")
     for v in (vx, vl, vd):
         f.release(v)
+
+
+def test_pieces_with_a_grid_wide_dependence_use_the_workspace():
+    say("fuser: exp + row sum | neg (other shape) | tanh of the first piece's result over other tiles, one launch with workspace")
+    f = _fuser()
+    ws = torch.empty(B.WORKSPACE_BYTES // 4, dtype=torch.int32, device=DEV)
+    f.set_workspace(ws.data_ptr(), B.WORKSPACE_BYTES)
+    x = gen.randn((700, 1540), 2200, DEV)
+    w = gen.randn((5, 77), 2201, DEV)
+    e = torch.full_like(x, float("nan"))
+    th = torch.full_like(x, float("nan"))
+    n = torch.full_like(w, float("nan"))
+    s_ = torch.full((700, 1), float("nan"), dtype=torch.float32, device=DEV)
+    vx = f.tensor(x.data_ptr(), "f32", B.shape_of_tensor(x))
+    vw = f.tensor(w.data_ptr(), "f32", B.shape_of_tensor(w))
+    ve = f.op("exp", [vx], "f32", e.data_ptr())
+    f.op("sum", [ve], "f32", s_.data_ptr())
+    f.op("neg", [vw], "f32", n.data_ptr())
+    f.op("tanh", [ve], "f32", th.data_ptr())
+    f.release(ve)
+    f.flush()
+    assert not B.workspace_gave_up(ws.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert f.stats()["launches"] == 1 and "waits until every workgroup" in f.last_code().disasm()
+    pe = _p("exp_sum_tanh", [("x", "f32")], [("e", "exp", ["x"], {}), ("s", "sum", ["e"], {}), ("t", "tanh", ["e"], {})],
+            [("e", "f32"), ("s", "f32"), ("t", "f32")])
+    r, xct = H.run_oracle(pe, {"x": x})
+    H.compare(e, r["e"], xct["e"], "f32", False, "fuser exp")
+    H.compare(s_, r["s"], xct["s"], "f32", True, "fuser row sum of exp")
+    H.compare(th, r["t"], xct["t"], "f32", False, "fuser tanh of exp")
+    pn = _p("neg_w", [("w", "f32")], [("n", "neg", ["w"], {})], [("n", "f32")])
+    r, xct = H.run_oracle(pn, {"w": w})
+    H.compare(n, r["n"], xct["n"], "f32", False, "fuser neg")
+
+
+def test_pieces_without_a_common_variant_fall_back_to_launches_in_order():
+    say("fuser: exp | neg | column sum of exp: no interpreter variant holds all three, launched one by one")
+    f = _fuser()
+    x = gen.randn((3, 700, 520), 2300, DEV)
+    w = gen.randn((5, 77), 2301, DEV)
+    e = torch.full_like(x, float("nan"))
+    n = torch.full_like(w, float("nan"))
+    s_ = torch.full((3, 1, 520), float("nan"), dtype=torch.float32, device=DEV)
+    vx = f.tensor(x.data_ptr(), "f32", B.shape_of_tensor(x))
+    vw = f.tensor(w.data_ptr(), "f32", B.shape_of_tensor(w))
+    ve = f.op("exp", [vx], "f32", e.data_ptr())
+    f.op("neg", [vw], "f32", n.data_ptr())
+    f.op("csum", [ve], "f32", s_.data_ptr())
+    f.release(ve)
+    f.flush()
+    torch.cuda.synchronize()
+    pe = _p("exp_then_csum", [("x", "f32")], [("e", "exp", ["x"], {}), ("s", "csum", ["e"], {})], [("e", "f32"), ("s", "f32")])
+    r, xct = H.run_oracle(pe, {"x": x})
+    H.compare(e, r["e"], xct["e"], "f32", False, "fuser exp")
+    H.compare(s_, r["s"], xct["s"], "f32", True, "fuser column sum of exp")
+    assert torch.equal(n, -w)
