@@ -298,6 +298,20 @@ int  dvm_plan(int64_t total, int n_cores, int64_t t_max, int align, int overhead
 int  dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len,
              void *const *tensors, int n_tensors, void *hip_stream);
 
+/* dvm_run for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same launch, but where the bytecode lists a workspace (dvm_stack_dependent)
+ * the library's own array in device memory takes its place -- DVM_STATIC_WORKSPACE_BYTES per device, part of the
+ * library's image, held until the process ends -- and tensors[] holds the bytecode's tensors WITHOUT the workspace
+ * entry (n_tensors one less than the bytecode lists).  Bytecode without a workspace runs exactly as with dvm_run.
+ * The call allocates nothing and frees nothing; it clears the part of the array it uses with a small kernel on
+ * `hip_stream` before the launch.  A launch that needs more workspace than the array holds is refused with
+ * DVM_E_LIMIT (use dvm_run with a workspace of the caller's).  All calls on one device share that device's array,
+ * which keeps the last call's contents: calls that may overlap in time on one device (different streams, or
+ * different threads) race on it and must be serialised by the caller. */
+#define DVM_STATIC_WORKSPACE_BYTES (4u << 20)
+int  dvm_run_static(const dvm_ctx *ctx, const void *bytecode, size_t len,
+                    void *const *tensors, int n_tensors, void *hip_stream);
+
 /* ---- measurement support (Section 6.1: run time and compile time are measured apart) ----------------- */
 /* dvm_encode called `reps` times on the same arguments, each call timed with CLOCK_MONOTONIC inside the library
  * (no language binding between the clock and the encoder); ns[r] receives the duration of call r in nanoseconds,

@@ -97,6 +97,7 @@ def load() -> C.CDLL:
         "dvm_code_tensor": (i, [vp, sz, i, P(C.c_int64), P(i), P(i), P(i)]),
         "dvm_plan": (i, [C.c_int64, i, C.c_int64, i, i, P(C.c_int64), P(C.c_int64), P(C.c_int64)]),
         "dvm_run": (i, [vp, vp, sz, P(vp), i, vp]),
+        "dvm_run_static": (i, [vp, vp, sz, P(vp), i, vp]),
         "dvm_encode_timed": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), i, P(C.c_int64)]),
         "dvm_copy_kernel": (i, [vp, vp, vp, sz, i, vp]),
         "dvm_strerror": (C.c_char_p, [i]),
@@ -125,7 +126,7 @@ EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ct
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
             "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_stack_dependent",
             "dvm_ctx_set_sync_limit", "dvm_workspace_status", "dvm_validate", "dvm_disasm",
-            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_encode_timed", "dvm_copy_kernel", "dvm_strerror", "dvm_last_error_detail",
+            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_run_static", "dvm_encode_timed", "dvm_copy_kernel", "dvm_strerror", "dvm_last_error_detail",
             "dvm_last_hip_error", "dvm_fuser_create", "dvm_fuser_destroy", "dvm_fuser_set_workspace", "dvm_fuser_tensor", "dvm_fuser_op",
             "dvm_fuser_release", "dvm_fuser_flush", "dvm_fuser_stats", "dvm_fuser_last_code"]
 
@@ -351,6 +352,13 @@ def dvm_run(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: in
     n = len(tensor_ptrs)
     arr = (C.c_void_p * max(n, 1))(*tensor_ptrs)
     _check(load().dvm_run(ctx._h, code.ptr, len(code), arr, n, C.c_void_p(stream)), "dvm_run")
+
+
+def dvm_run_static(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: int = 0) -> None:
+    """dvm_run without the workspace entry: the library's own device array takes its place (no allocation)."""
+    n = len(tensor_ptrs)
+    arr = (C.c_void_p * max(n, 1))(*tensor_ptrs)
+    _check(load().dvm_run_static(ctx._h, code.ptr, len(code), arr, n, C.c_void_p(stream)), "dvm_run_static")
 
 
 class Fuser:

@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string.h>
+#include <atomic>
+#include <mutex>
 #include <utility>
 
 #include "../../include/dvm.h"
@@ -1545,6 +1547,11 @@ DVM_VARIANT_LIST(X)
 DVM_CRED_VARIANT_LIST(X)
 #undef X
 
+// The workspace of dvm_run_static: one array per device, in the library's own image, so that the entry point
+// needs no allocation.  In host code the array's name is only a handle for hipGetSymbolAddress; the device
+// address it yields (per device) is what kernels and fills get.
+static __device__ __align__(256) unsigned char scratch[DVM_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 typedef int (*vm_launch_t)(unsigned, unsigned, unsigned, void *, const void *, int *);
@@ -1560,6 +1567,30 @@ const VariantEntry g_cred_variants[] = {DVM_CRED_VARIANT_LIST(X)};
 #undef X
 
 thread_local int t_last_hip_error = 0;
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<void *> g_scratch_ptr[MAX_DEVICES];
+
+// Look up this device's copy of `scratch` (once per device; the device must be current for the lookup).
+int scratch_setup(int device) {
+    if (device < 0 || device >= MAX_DEVICES) return dvm_set_error(DVM_E_ARGS, "device index out of range");
+    if (g_scratch_ptr[device].load(std::memory_order_acquire)) return DVM_OK;
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e == hipSuccess && cur != device) e = hipSetDevice(device);
+    void *ptr = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (cur >= 0 && cur != device) {
+        const hipError_t e2 = hipSetDevice(cur);
+        if (e == hipSuccess) e = e2;
+    }
+    if (e != hipSuccess || !ptr) {
+        t_last_hip_error = (int)e;
+        return dvm_set_error(DVM_E_HIP, e != hipSuccess ? hipGetErrorString(e) : "hipGetSymbolAddress returned no address");
+    }
+    g_scratch_ptr[device].store(ptr, std::memory_order_release);
+    return DVM_OK;
+}
 
 // clears the synchronisation area of a launch's workspace (a kernel rather than a memset node, so that the
 // clearing may be captured into a HIP graph with the launch it precedes)
@@ -1579,17 +1610,74 @@ extern "C" int dvm_ctx_query_device(int hip_device, int *n_cu) {
         return DVM_E_HIP;
     }
     *n_cu = prop.multiProcessorCount;
-    return DVM_OK;
+    return scratch_setup(hip_device);
 }
+
+namespace {
+
+// Workgroups of `block` threads and `lds_bytes` that one compute unit holds at a time, per launcher; asked of the
+// runtime once and remembered (a handful of combinations occur).
+struct OccEntry { vm_launch_t launch; uint32_t block, lds_bytes; int per_cu; };
+constexpr int OCC_SLOTS = 64;
+OccEntry g_occ[OCC_SLOTS];
+std::atomic<int> g_occ_n{0};
+std::mutex g_occ_mu;
+
+int resident_per_cu(vm_launch_t launch, uint32_t block, uint32_t lds_bytes, int *per_cu) {
+    const int n = g_occ_n.load(std::memory_order_acquire);
+    for (int i = 0; i < n; ++i)
+        if (g_occ[i].launch == launch && g_occ[i].block == block && g_occ[i].lds_bytes == lds_bytes) { *per_cu = g_occ[i].per_cu; return 0; }
+    int v = 0;
+    const int e = launch(0, block, lds_bytes, nullptr, nullptr, &v);
+    if (e != 0) return e;
+    std::lock_guard<std::mutex> lock(g_occ_mu);
+    const int m = g_occ_n.load(std::memory_order_relaxed);
+    if (m < OCC_SLOTS) {
+        g_occ[m] = OccEntry{launch, block, lds_bytes, v};
+        g_occ_n.store(m + 1, std::memory_order_release);
+    }
+    *per_cu = v;
+    return 0;
+}
+
+int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors_in, int n_tensors, void *hip_stream, bool static_ws);
+
+}  // namespace
 
 extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors, int n_tensors,
                        void *hip_stream) {
-    if (!ctx || !bytecode || (!tensors && n_tensors > 0)) return dvm_set_error(DVM_E_ARGS, "dvm_run: null argument");
+    return run_impl(ctx, bytecode, len, tensors, n_tensors, hip_stream, false);
+}
+
+extern "C" int dvm_run_static(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors, int n_tensors,
+                              void *hip_stream) {
+    return run_impl(ctx, bytecode, len, tensors, n_tensors, hip_stream, true);
+}
+
+namespace {
+
+int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors_in, int n_tensors, void *hip_stream, bool static_ws) {
+    if (!ctx || !bytecode || (!tensors_in && n_tensors > 0)) return dvm_set_error(DVM_E_ARGS, "dvm_run: null argument");
     if (dvm_ctx_device(ctx) < 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: context was created without a device");
     int st = dvm_validate(bytecode, len);
     if (st != DVM_OK) return st;
     const uint32_t *w = (const uint32_t *)bytecode;
     const uint32_t ntens = w[PH_NTENS];
+    // dvm_run_static: the library's own array stands in for the workspace entry, which the caller leaves out
+    void *tensors_full[DVM_MAX_TENSORS];
+    void *const *tensors = tensors_in;
+    if (static_ws && ntens > 0 && (w[PH_WORDS_N + (ntens - 1) * TT_WORDS + TT_INFO] & TI_WORKSPACE)) {
+        if ((uint32_t)n_tensors + 1 != ntens) return dvm_set_error(DVM_E_ARGS, "dvm_run_static: pass the bytecode's tensors without its workspace");
+        const uint32_t *te = w + PH_WORDS_N + (ntens - 1) * TT_WORDS;
+        if (te[TT_BYTES_HI] != 0 || te[TT_BYTES_LO] > DVM_STATIC_WORKSPACE_BYTES)
+            return dvm_set_error(DVM_E_LIMIT, "dvm_run_static: the launch needs a workspace beyond DVM_STATIC_WORKSPACE_BYTES; use dvm_run with a workspace of the caller's");
+        st = scratch_setup(dvm_ctx_device(ctx));
+        if (st != DVM_OK) return st;
+        for (int i = 0; i < n_tensors; ++i) tensors_full[i] = tensors_in[i];
+        tensors_full[n_tensors] = g_scratch_ptr[dvm_ctx_device(ctx)].load(std::memory_order_acquire);
+        tensors = tensors_full;
+        ++n_tensors;
+    }
     if ((uint32_t)n_tensors != ntens) return dvm_set_error(DVM_E_ARGS, "dvm_run: tensor count does not match the bytecode");
     const uint32_t segs_off = PH_WORDS_N + ntens * TT_WORDS;
     const uint32_t seg_words = w[PH_WORDS] - segs_off;
@@ -1674,7 +1762,7 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     if (grid_sync) {
         // every workgroup waits for all the others: the whole grid has to be resident at once
         int per_cu = 0, n_cu = 0;
-        e = (hipError_t)launch(grid, block, lds_bytes, hip_stream, &ka, &per_cu);
+        e = (hipError_t)resident_per_cu(launch, block, lds_bytes, &per_cu);
         if (e != hipSuccess) {
             t_last_hip_error = (int)e;
             return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
@@ -1694,6 +1782,8 @@ extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, voi
     }
     return DVM_OK;
 }
+
+}  // namespace
 
 extern "C" int dvm_workspace_status(const void *workspace, void *hip_stream, int *gave_up) {
     if (!workspace || !gave_up) return dvm_set_error(DVM_E_ARGS, "dvm_workspace_status: null argument");
