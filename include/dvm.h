@@ -127,6 +127,10 @@ int  dvm_ctx_set_limits(dvm_ctx *ctx, int max_elems_per_lane, int max_tile_regs)
  * per resident slot.  0 leaves a choice to the planner.  The bytecode depends on these settings and on the
  * other context settings, the program and the shapes only; the library reads no environment variable. */
 int  dvm_ctx_set_plan_override(dvm_ctx *ctx, int elems_per_lane, int rows_per_tile, int grid_multiplier);
+/* Row-invariant operands that a program only multiplies by or adds (a weight vector, a bias) may be kept in
+ * the workgroup's LDS instead of pinned tile registers when that lets the program run in an interpreter variant
+ * with fewer tile registers, i.e. more resident waves (default: enabled).  0 disables it (tests, comparison). */
+int  dvm_ctx_set_lds_operands(dvm_ctx *ctx, int enabled);
 /* How the M tiles of a meta-kernel are dealt out to the N workgroups of the launch (Section 4.3, Algorithm 2).
  * DVM_ASSIGN_BLOCKED is the range the algorithm prints: workgroup id runs tiles [m*id, min(M, m*(id+1))) with
  * m = ceil(M/N).  DVM_ASSIGN_INTERLEAVED (the default on this hardware) deals them out round-robin: workgroup

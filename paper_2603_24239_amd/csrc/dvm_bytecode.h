@@ -96,6 +96,7 @@ constexpr uint32_t SF_CSTREAM = 4u;     // reducing segment whose per-row part i
 constexpr uint32_t SF_INTERLEAVED = 8u; // workgroup id runs tiles id, id + N, id + 2N, ... instead of Algorithm 2's blocked range
 // A stacked meta-kernel that reads what an earlier meta-kernel of the same launch wrote (Section 5.1: temporal
 // stacking does not require independent operators) starts behind a synchronisation point:
+constexpr uint32_t SF_LDS = 64u;        // the prologue copies row-invariant tensors into LDS: the workgroup synchronises around it
 constexpr uint32_t SF_SYNC_WG   = 16u;  // its producer ran with the same tile-to-workgroup assignment over the same rows: a
                                         // workgroup reads only rows it wrote itself, so it waits for its own stores only
 constexpr uint32_t SF_SYNC_GRID = 32u;  // any other dependence: every workgroup of the launch has finished the segments before
@@ -131,8 +132,18 @@ enum : uint32_t {
     I_CSTREAM,   // R[a] = R_b over the rows of the unit that fall to this wave, of a tensor (memory record with three
                  // strides): the whole per-row part of a segment that only reduces input tensors along the
                  // penultimate axis (SF_CSTREAM), with several rows in flight per wave instead of one per step
+    I_LDSCOPY,   // prologue only: copy a row-invariant tensor (every outer stride 0) into the workgroup's LDS, as it
+                 // lies in memory, zero-filled up to the tile width.  word1 = tensor | dtype << 8, word2 = byte offset
+                 // of the image in LDS, word3 = its size in bytes (a multiple of 16); b != 0: the workgroup
+                 // synchronises afterwards (set on the last copy of a prologue)
+    I_LFMA,      // ACC = ACC [* S] [* La] [+ Lb] with La, Lb LDS images (the multiply-add is fused when both are there).
+                 // a = La | Lb << 4 as image numbers (LFMA_NONE: absent), b = bit 0: La is bf16, bit 1: Lb is bf16;
+                 // word1 = 0 or S index + 1, word2 / word3 = byte offsets of La / Lb in LDS
     I_COUNT
 };
+constexpr uint32_t LFMA_NONE = 0xF;
+constexpr int LDS_SLOTS = 4;                    // LDS images per segment
+constexpr uint32_t LDS_IMAGE_MAX_BYTES = 65536; // all images of a segment together
 
 // memory record: word1 = tensor | dtype << 8 | flags << 16 ; then strides as int64 (lo, hi)
 constexpr int LEN_LOAD  = 4;            // word0, word1, s1

@@ -93,6 +93,7 @@ struct dvm_ctx {
     int dbg_grid_x; // workgroups launched per resident slot (default 1)
     int dbg_rp;     // rows per tile, or waves per unit of a reduction along the penultimate axis (0 = cost model)
     int assignment; // DVM_ASSIGN_*: how the tiles of a meta-kernel are dealt out to the workgroups
+    int lds_operands;   // row-invariant operands may live in LDS instead of pinned tile registers
     int64_t sync_limit;     // polls a workgroup spends at a grid-wide synchronisation point before it gives up
 };
 
@@ -109,6 +110,7 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->dbg_grid_x = 1;
     c->dbg_rp = 0;
     c->assignment = DVM_ASSIGN_INTERLEAVED;
+    c->lds_operands = 1;
     c->sync_limit = 1 << 20;
     if (hip_device >= 0) {
         int n = 0;
@@ -163,6 +165,12 @@ extern "C" int dvm_ctx_set_sync_limit(dvm_ctx *c, int64_t polls) {
     return DVM_OK;
 }
 extern "C" int64_t dvm_ctx_sync_limit(const dvm_ctx *c) { return c ? c->sync_limit : 0; }
+
+extern "C" int dvm_ctx_set_lds_operands(dvm_ctx *c, int enabled) {
+    if (!c) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_lds_operands: null context");
+    c->lds_operands = enabled != 0;
+    return DVM_OK;
+}
 
 extern "C" int dvm_ctx_set_assignment(dvm_ctx *c, int assignment) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
@@ -569,6 +577,9 @@ struct Enc {
     int regs[NR_MAX], sregs[NS];
     int nr_limit;           // tile registers the program may use
     bool reload_inputs;     // never keep an input tile in a register: load it again at every use
+    int lds_of[MAX_NODES];  // LDS image (slot) of a row-invariant input that only multiplies or is added, or -1
+    int n_lds;
+    int lds_node[LDS_SLOTS];
     int in_acc;
     int nr_used, ns_used;
     const char *err;
@@ -597,6 +608,20 @@ struct Enc {
         AI &x = ai[n_ai++];
         x.op = op; x.a = a; x.b = b; x.c = c; x.kind = kind; x.srck = srck; x.tensor = (int16_t)tensor; x.imm = imm;
         x.imm2 = 0.0f;
+    }
+    // acc = acc * L or acc + L with L the LDS image in `slot`: joins the record before it where that keeps the
+    // order of the operations (acc * S, then * L, then + L), else a record of its own.
+    // I_LFMA: a = multiplier slot or LFMA_NONE, b = addend slot or LFMA_NONE, kind = S index + 1 or 0.
+    void emit_lds(bool mul, int slot) {
+        if (n_ai > n_fence && n_ai > 0) {
+            AI &p = ai[n_ai - 1];
+            if (mul && p.op == I_BIN && p.b == B_MUL && p.a >= SRC_S0 && p.a < SRC_S0 + NS) {      // acc * S, then * L
+                p.op = I_LFMA; p.kind = (uint8_t)(p.a - SRC_S0 + 1); p.a = (uint8_t)slot; p.b = LFMA_NONE;
+                return;
+            }
+            if (!mul && p.op == I_LFMA && p.b == LFMA_NONE) { p.b = (uint8_t)slot; return; }        // ... * L, then + L
+        }
+        emit(I_LFMA, mul ? (uint8_t)slot : (uint8_t)LFMA_NONE, mul ? (uint8_t)LFMA_NONE : (uint8_t)slot);
     }
     // Row-scalar op on the value a reduction has just produced, that value being used nowhere
     // else: fold it into the reduction's record as post(x) = U(x * scale + shift).
@@ -919,6 +944,25 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             }
         }
         A.min_bytes = empty ? 0 : (maxoff + 1) * es;
+        if (is_out && !empty) {
+            // an output element must have a memory location of its own: no broadcast stride, no two index
+            // tuples at one address (sufficient test: strides sorted ascending, each at least the span below it)
+            int64_t ds[DVM_MAX_RANK], ss[DVM_MAX_RANK];
+            int m = 0;
+            for (int k = 0; k < s->rank; ++k)
+                if (s->dim[k] > 1) {
+                    if (s->stride[k] == 0) return dvm_set_error(DVM_E_SHAPE, "an output layout repeats elements (stride 0 on an axis of extent > 1)");
+                    int at = m++;
+                    while (at > 0 && ss[at - 1] > s->stride[k]) { ss[at] = ss[at - 1]; ds[at] = ds[at - 1]; --at; }
+                    ss[at] = s->stride[k];
+                    ds[at] = s->dim[k];
+                }
+            int64_t span = 1;       // elements covered by the axes below
+            for (int k = 0; k < m; ++k) {
+                if (ss[k] < span) return dvm_set_error(DVM_E_SHAPE, "an output layout maps two elements to one address");
+                span = ss[k] * (ds[k] - 1) + span;
+            }
+        }
         A.rows = E.row_axis && (node >= 0 ? E.rows_class[node] : false);
         if (E.row_axis && !A.rows && A.ostride[R - 1] == 0 && E.dom[R - 1] > 1) {
             // the tensor has the full row extent in its shape; a zero stride there is an expanded view
@@ -1009,7 +1053,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     (void)g0_is_row;
 
     // ---- 4. linearise ---------------------------------------------------------------------------
-    auto linearize = [&](int hoist_budget) {
+    const uint32_t V = any_bf16_full ? 8 : 4;      // elements per 16-byte chunk of a tile
+    auto linearize = [&](int hoist_budget, bool use_lds = false) {
     memset(E.uses, 0, sizeof(E.uses));
     for (int n = 0; n < NN; ++n) {
         const Node &nd = prog->nodes[n];
@@ -1032,14 +1077,48 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     for (int n = 0; n < NN; ++n)
         if (prog->nodes[n].kind == N_IN && E.acc[prog->nodes[n].input].rows) E.rows_class[n] = true;
 
-    // Tile-invariant operands (every outer stride zero: a weight vector broadcast over the rows) are
-    // loaded once per workgroup into a pinned tile register by a prologue that runs before the
-    // first tile, instead of once per tile.
+    // Tile-invariant operands (every outer stride zero: a weight vector broadcast over the rows) that the
+    // program only multiplies by or adds can stay in LDS instead of a tile register: the prologue copies
+    // them there once per workgroup, and the multiply / add reads them from there.
+    E.n_lds = 0;
+    for (int n = 0; n < NN; ++n) E.lds_of[n] = -1;
+    if (use_lds) {
+        int64_t lds_bytes = 0;
+        auto invariant_input = [&](int n) {
+            if (prog->nodes[n].kind != N_IN || E.rows_class[n]) return false;
+            const Access &A = E.acc[prog->nodes[n].input];
+            return A.s[1] == 0 && A.s[2] == 0 && A.s[3] == 0;
+        };
+        for (int n = 0; n < NN && E.n_lds < LDS_SLOTS; ++n) {
+            if (!invariant_input(n) || E.uses[n] == 0) continue;
+            bool ok = true;
+            for (int o = 0; o < prog->n_out; ++o) ok &= prog->out_node[o] != n;
+            for (int m = 0; m < NN && ok; ++m) {
+                const Node &u = prog->nodes[m];
+                if (u.kind == N_IN || u.kind == N_DEAD) continue;
+                const bool is_a = u.a == n, is_b = (u.kind == N_BIN || u.kind == N_SEL) && u.b == n, is_c = u.kind == N_SEL && u.c == n;
+                if (!is_a && !is_b && !is_c) continue;
+                const int other = is_a ? u.b : u.a;
+                ok = u.kind == N_BIN && (u.op == B_ADD || u.op == B_MUL) && !(is_a && is_b) && other >= 0 &&
+                     !E.rows_class[other] && !invariant_input(other) && !E.cred_real[m] && !E.post[m];
+            }
+            const int64_t bytes = cdiv(E.D0 > 0 ? E.D0 : 1, V) * V * (E.acc[prog->nodes[n].input].dtype == DVM_F32 ? 4 : 2);
+            if (!ok || lds_bytes + bytes > (int64_t)LDS_IMAGE_MAX_BYTES) continue;
+            lds_bytes += bytes;
+            E.lds_of[n] = E.n_lds;
+            E.lds_node[E.n_lds++] = n;
+            E.uses[n] += 1 << 20;       // never released
+        }
+    }
+    // The other tile-invariant operands are loaded once per workgroup into a pinned tile register by a
+    // prologue that runs before the first tile, instead of once per tile.
     E.n_prolog = 0;
+    for (int k = 0; k < E.n_lds; ++k)
+        E.emit(I_LDSCOPY, (uint8_t)k, (uint8_t)(k + 1 == E.n_lds), prog->nodes[E.lds_node[k]].input);
     int hoisted = 0;
     for (int n = 0, left = hoist_budget; n < NN && left > 0; ++n) {
         const Node &nd = prog->nodes[n];
-        if (nd.kind != N_IN || E.rows_class[n] || E.uses[n] == 0) continue;
+        if (nd.kind != N_IN || E.rows_class[n] || E.uses[n] == 0 || E.lds_of[n] >= 0) continue;
         const Access &A = E.acc[nd.input];
         if (A.s[1] != 0 || A.s[2] != 0 || A.s[3] != 0) continue;
         bool is_out = false;
@@ -1209,6 +1288,16 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                     op = reversed(op);
                 }
                 // now `a` is a tile and goes through the accumulator
+                if (E.lds_of[a] >= 0 || E.lds_of[b] >= 0) {     // (add or multiply: commutative)
+                    if (E.lds_of[a] >= 0) { int t = a; a = b; b = t; }
+                    E.to_acc(a);
+                    E.preserve(a, 1);
+                    E.use(a);
+                    E.emit_lds(op == B_MUL, E.lds_of[b]);
+                    E.use(b);
+                    E.in_acc = n;
+                    break;
+                }
                 if (E.rows_class[b]) {
                     int sb = E.sreg(b);
                     E.to_acc(a);
@@ -1319,11 +1408,72 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (E.err || E.nr_used > reg_cap) { E.err = nullptr; linearize(0); }
         }
     }
+    // LDS images instead of pinned registers when that lets the program run in an interpreter variant with fewer
+    // tile registers (more resident waves), or when it did not fit the registers at all
+    {
+        auto cls = [](int n) { return n <= 2 ? 2 : (n <= 4 ? 4 : (n <= 6 ? 6 : 8)); };
+        const bool row_mode_ok = E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && !E.has_cred && E.D0 > 0;
+        const int before = E.err ? 99 : E.nr_used;
+        if (row_mode_ok && ctx->lds_operands && (before > 2 || E.reload_inputs)) {
+            const bool was_reload = E.reload_inputs;
+            E.err = nullptr;
+            E.reload_inputs = false;
+            linearize(0, true);
+            if (!E.err && E.n_lds > 0 && (cls(E.nr_used) < cls(before) || was_reload)) {
+                const int body_regs = E.nr_used;
+                const int cap = cls(body_regs) < ctx->max_nr ? cls(body_regs) : ctx->max_nr;
+                if (body_regs < cap) {          // pin what is left over in the registers of the same variant class
+                    linearize(cap - body_regs, true);
+                    if (E.err || E.nr_used > cap) { E.err = nullptr; linearize(0, true); }
+                }
+            } else {                            // no gain: back to the plan without LDS images
+                E.err = nullptr;
+                E.reload_inputs = false;
+                linearize(0);
+                if (E.err) { E.err = nullptr; E.reload_inputs = true; linearize(0); }
+                int reg_cap = 4;
+                if (reg_cap > ctx->max_nr) reg_cap = ctx->max_nr;
+                if (!E.err && E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && E.nr_used < reg_cap && !E.has_cred) {
+                    const int body_regs = E.nr_used;
+                    linearize(reg_cap - body_regs);
+                    if (E.err || E.nr_used > reg_cap) { E.err = nullptr; linearize(0); }
+                }
+            }
+        }
+    }
     if (E.err) return dvm_set_error(E.err_code, E.err);
     if (E.nr_used > ctx->max_nr) return dvm_set_error(DVM_E_UNSUPPORTED, "program needs more tile registers than the context allows");
 
+    // Loads are issued as early as the registers allow: a load record further down the body whose destination
+    // register nothing touches before it moves up into the group of loads the body starts with, so that all of
+    // them are in flight together and the tile waits for memory once.
+    if (!E.has_cred) {
+        auto touches = [&](const AI &x, int r) {
+            switch (x.op) {
+                case I_LOAD: case I_STORE: case I_MOVRA: case I_MOVAR: return x.a == r;
+                case I_BIN: return x.a == r;
+                case I_SEL: return x.a == r || x.b == r;
+                case I_FMA: return x.a == r || x.b == r;
+                default: return false;
+            }
+        };
+        int top = E.n_prolog;
+        while (top < E.n_ai && (E.ai[top].op == I_LOAD || E.ai[top].op == I_LOADS)) ++top;
+        if (top > E.n_prolog) {
+            for (int i = top + 1; i < E.n_ai; ++i) {
+                if (E.ai[i].op != I_LOAD || E.ai[i].a >= SRC_S0) continue;
+                bool free_reg = true;
+                for (int j = top; j < i && free_reg; ++j) free_reg = !touches(E.ai[j], E.ai[i].a);
+                // (the registers of the prologue's pinned operands are never a body load's destination)
+                if (!free_reg) continue;
+                const AI moved = E.ai[i];
+                for (int j = i; j > top; --j) E.ai[j] = E.ai[j - 1];
+                E.ai[top++] = moved;
+            }
+        }
+    }
+
     // ---- 5. tile plan ---------------------------------------------------------------------------
-    const uint32_t V = any_bf16_full ? 8 : 4;
     const int need_nr = E.nr_used;
     const int64_t Cr = cdiv(E.D0 > 0 ? E.D0 : 1, V);
     int vi = -1;                    // chosen variant
@@ -1334,9 +1484,20 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if ((VARIANTS[i].cred || !E.has_cred) && VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && VARIANTS[i].NR <= ctx->max_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
         return best;
     };
+    // LDS images of this program: offsets and sizes (each a whole number of chunks, zero-filled behind the row's end)
+    uint32_t lds_off[LDS_SLOTS] = {0, 0, 0, 0}, lds_size[LDS_SLOTS] = {0, 0, 0, 0}, lds_total = 0;
+    for (int k = 0; k < E.n_lds; ++k) {
+        lds_off[k] = lds_total;
+        lds_size[k] = (uint32_t)(cdiv(E.D0 > 0 ? E.D0 : 1, V) * V * (E.acc[prog->nodes[E.lds_node[k]].input].dtype == DVM_F32 ? 4 : 2));
+        lds_total += lds_size[k];
+    }
     auto slots_per_cu = [&](const Variant &v, uint32_t threads) {
         const int waves_wg = (int)((threads + 63) / 64);
         int s = v.waves_per_simd * 4 / waves_wg;
+        if (lds_total > 0) {            // 160 KiB of LDS per compute unit, allocated in steps of 512 bytes
+            const int by_lds = (int)(163840u / ((lds_total + 128u + 511u) / 512u * 512u));
+            if (by_lds < s) s = by_lds;
+        }
         return s < 1 ? 1 : s;
     };
     const int64_t ovh = ctx->overhead;
@@ -1556,7 +1717,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     sh[S_TBASE] = 0;
     sh[S_NTENS] = (uint32_t)E.n_acc;
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0) | (E.has_cred && E.cstream ? SF_CSTREAM : 0) |
-                  (ctx->assignment == DVM_ASSIGN_INTERLEAVED ? SF_INTERLEAVED : 0);
+                  (ctx->assignment == DVM_ASSIGN_INTERLEAVED ? SF_INTERLEAVED : 0) | (E.n_lds > 0 ? SF_LDS : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
     if (E.has_cred) {
@@ -1601,6 +1762,26 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 *b++ = w0(x.op, LEN_VLOAD, x.a, 0);
                 *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8);
                 put_i64(A.s[1]); put_i64(A.s[2]); put_i64(A.s[3]);
+                break;
+            }
+            case I_LDSCOPY:
+                imask |= 1u << I_LDSCOPY;
+                b[0] = w0(I_LDSCOPY, LEN_REC, x.a, x.b);
+                b[1] = (uint32_t)x.tensor | ((uint32_t)E.acc[x.tensor].dtype << 8);
+                b[2] = lds_off[x.a];
+                b[3] = lds_size[x.a];
+                b += LEN_REC;
+                break;
+            case I_LFMA: {
+                imask |= 1u << I_LFMA;
+                uint32_t dts = 0;
+                if (x.a != LFMA_NONE && E.acc[prog->nodes[E.lds_node[x.a]].input].dtype == DVM_BF16) dts |= 1u;
+                if (x.b != LFMA_NONE && E.acc[prog->nodes[E.lds_node[x.b]].input].dtype == DVM_BF16) dts |= 2u;
+                b[0] = w0(I_LFMA, LEN_REC, (uint32_t)x.a | ((uint32_t)x.b << 4), dts);
+                b[1] = x.kind;
+                b[2] = x.a != LFMA_NONE ? lds_off[x.a] : 0u;
+                b[3] = x.b != LFMA_NONE ? lds_off[x.b] : 0u;
+                b += LEN_REC;
                 break;
             }
             case I_BIN:
@@ -1770,6 +1951,8 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         }
         tiles_total += M;
         // body
+        uint32_t lds_seen = 0, lds_at[LDS_SLOTS] = {0, 0, 0, 0};
+        bool lds_bf16[LDS_SLOTS] = {false, false, false, false}, lds_last_sync = false;
         size_t pc = at + SH_WORDS;
         const size_t end = pc + cs;
         while (pc < end) {
@@ -1779,7 +1962,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             if (pc + l == at + SH_WORDS + sh[S_PROLOG]) prolog_ends_on_record = true;
             if (pc + l == at + SH_WORDS + sh[S_PROLOGA]) prolog_a_ends_on_record = true;
             if (pc + l == at + SH_WORDS + sh[S_EPILOG]) epilog_on_record = true;
-            if (pc < at + SH_WORDS + sh[S_PROLOG] && op != I_LOAD && op != I_VLOAD) return bad("prologue holds loads only");
+            if (pc < at + SH_WORDS + sh[S_PROLOG] && op != I_LOAD && op != I_VLOAD && op != I_LDSCOPY) return bad("prologue holds loads only");
             uint32_t want = LEN_REC;
             switch (op) {
                 case I_LOAD: case I_VLOAD: case I_STORE: case I_VSTORE: {
@@ -1861,6 +2044,34 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (l != LEN_REC || !reg_ok(a, vr) || bb > R_MIN) return bad("combine");
                     if (sh[S_INNER] == 0 || pc < at + SH_WORDS + sh[S_EPILOG]) return bad("combine outside the epilogue of a reducing segment");
                     break;
+                case I_LDSCOPY: {
+                    if (l != LEN_REC || a >= (uint32_t)LDS_SLOTS || bb > 1) return bad("LDS copy");
+                    if (pc >= at + SH_WORDS + sh[S_PROLOGA] || !(sh[S_FLAGS] & SF_LDS) || sh[S_INNER] != 0) return bad("LDS copy outside the once-per-workgroup prologue");
+                    const uint32_t w1 = w[pc + 1];
+                    if ((w1 & 0xFF) >= nt || (w1 >> 16) != 0) return bad("tensor index");
+                    const uint32_t info = w[PH_WORDS_N + (tbase + (w1 & 0xFF)) * TT_WORDS + TT_INFO];
+                    if (((w1 >> 8) & 0xFF) != (info & 0xFF)) return bad("dtype differs from the tensor table");
+                    const uint32_t es = (info & 0xFF) == DVM_F32 ? 4 : 2;
+                    const uint64_t need = (D0 + V - 1) / V * V * es;
+                    if ((w[pc + 3] & 15) || w[pc + 3] < need || (w[pc + 2] & 15) || (uint64_t)w[pc + 2] + w[pc + 3] > LDS_IMAGE_MAX_BYTES)
+                        return bad("LDS image extent");
+                    if (lds_seen & (1u << a)) return bad("LDS image copied twice");
+                    lds_seen |= 1u << a;
+                    lds_at[a] = w[pc + 2];
+                    lds_bf16[a] = (info & 0xFF) == DVM_BF16;
+                    lds_last_sync = bb != 0;
+                    break;
+                }
+                case I_LFMA: {
+                    const uint32_t la = a & 0xF, lb = a >> 4;
+                    if (l != LEN_REC || (la == LFMA_NONE && lb == LFMA_NONE) || bb > 3) return bad("LDS multiply-add");
+                    if (pc < at + SH_WORDS + sh[S_PROLOG]) return bad("LDS multiply-add in the prologue");
+                    if (la != LFMA_NONE && (la >= (uint32_t)LDS_SLOTS || !(lds_seen & (1u << la)) || w[pc + 2] != lds_at[la] || ((bb & 1u) != 0) != lds_bf16[la])) return bad("LDS multiplier");
+                    if (lb != LFMA_NONE && (lb >= (uint32_t)LDS_SLOTS || !(lds_seen & (1u << lb)) || w[pc + 3] != lds_at[lb] || ((bb & 2u) != 0) != lds_bf16[lb])) return bad("LDS addend");
+                    if (w[pc + 1] > (uint32_t)NS) return bad("LDS multiply-add scalar");
+                    if (!lds_last_sync) return bad("LDS images used without a synchronisation after the last copy");
+                    break;
+                }
                 case I_NOP:
                     if (l != LEN_REC) return bad("nop");
                     break;
@@ -1868,6 +2079,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             }
             pc += l;
         }
+        if (((sh[S_FLAGS] & SF_LDS) != 0) != (lds_seen != 0)) return bad("LDS flag does not match the prologue");
         if (!prolog_ends_on_record || !prolog_a_ends_on_record) return bad("prologue does not end on a record boundary");
         if (!epilog_on_record) return bad("epilogue does not start on a record boundary");
         at += sw;
@@ -2318,6 +2530,18 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
                     if (w[pc + 1]) snprintf(sc, sizeof sc, " * s%u", w[pc + 1] - 1);
                     if (b != FMA_NO_ADDEND) snprintf(ad, sizeof ad, " + r%u", b);
                     o.put("  %04zu fma     acc = acc%s * r%u%s\n", pc - at - SH_WORDS, sc, a, ad);
+                    break;
+                }
+                case I_LDSCOPY:
+                    o.put("  %04zu ldscopy L%u = t%u  [%u bytes of LDS at %u%s]\n", pc - at - SH_WORDS, a, w[pc + 1] & 0xFF, w[pc + 3], w[pc + 2],
+                          b ? ", then workgroup sync" : "");
+                    break;
+                case I_LFMA: {
+                    char sc[8] = "", mu[8] = "", ad[8] = "";
+                    if (w[pc + 1]) snprintf(sc, sizeof sc, " * s%u", w[pc + 1] - 1);
+                    if ((a & 0xF) != LFMA_NONE) snprintf(mu, sizeof mu, " * L%u", a & 0xF);
+                    if ((a >> 4) != LFMA_NONE) snprintf(ad, sizeof ad, " + L%u", a >> 4);
+                    o.put("  %04zu lfma    acc = acc%s%s%s\n", pc - at - SH_WORDS, sc, mu, ad);
                     break;
                 }
                 case I_RED:

@@ -331,8 +331,7 @@ struct Geo {
     uint32_t ragged;      // some lane has invalid columns inside live chunks: reductions must mask
     // per lane
     uint32_t i1, i2, i3;  // decomposition of the lane's row index over the outer dims
-    uint32_t lanecol;     // first column of the lane's chunk 0, relative to colbase
-    uint32_t lr;          // lane index within the row group
+    uint32_t lanecol;     // first column of the lane's chunk 0, relative to colbase: V times the lane's index within the row group
     uint32_t rowok;       // 1 when the lane's row lies inside the tensor
 };
 
@@ -463,7 +462,7 @@ template <int K, int DT, int V> DI void finish_tile(Tile<K> &t, gcptr rowp, cons
         if (g.part_slot != ~0u) {   // wave-uniform: this tile ends inside a chunk
             // its elements are read one by one by every lane of the row (one of them keeps them); an element
             // beyond the row reads element 0 again
-            const bool own = g.lr == g.part_lane;
+            const bool own = g.lanecol == g.part_lane * (uint32_t)V;
             float pv[V];
             sfor<V>([&]<int E>() LI {
                 const uint32_t e = (uint32_t)E < g.part_n ? (uint32_t)E : 0u;       // wave-uniform
@@ -574,7 +573,7 @@ template <int K, int DT, int V, uint32_t B> DI void combine_staged(Tile<K> &t, c
             }
         }
         if (g.part_slot != ~0u) {
-            const bool own = g.lr == g.part_lane;
+            const bool own = g.lanecol == g.part_lane * (uint32_t)V;
             float pv[V];
             sfor<V>([&]<int E>() LI {
                 const uint32_t bits = raw.pv[E];
@@ -624,7 +623,7 @@ template <int K, int DT, int V> DI void store_tile(const Tile<K> &t, gptr rowp, 
             });
         }
         if (g.part_slot != ~0u) {
-            const bool own = g.rowok && g.lr == g.part_lane;
+            const bool own = g.rowok && g.lanecol == g.part_lane * (uint32_t)V;
             sfor<NJ>([&]<int J>() LI {
                 if ((uint32_t)J == g.part_slot) {
                     sfor<V>([&]<int E>() LI {
@@ -739,7 +738,7 @@ template <int K, uint32_t R, int V> DI float lane_reduce_ragged(const Tile<K> &a
             }
         });
         if (g.part_slot != ~0u) {
-            const bool own = g.lr == g.part_lane;
+            const bool own = g.lanecol == g.part_lane * (uint32_t)V;
             sfor<NJ>([&]<int J>() LI {
                 if ((uint32_t)J == g.part_slot) {              // wave-uniform
                     sfor<V>([&]<int E>() LI {
@@ -862,6 +861,86 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
 }
 
 // ------------------------------------------------------------------------------------------
+// row-invariant operands kept in LDS
+// ------------------------------------------------------------------------------------------
+#define LDS_AS __attribute__((address_space(3)))
+// Copy the first `d0` elements of the tensor at `src` (dtype dt) into an LDS image of n16 16-byte pieces, zero behind
+// the row's end.  All `nthreads` threads of the workgroup take part; every branch is wave-uniform (a thread
+// past the last piece copies the last piece once more).
+DI void lds_copy_row(LDS_AS char *dst, uint32_t n16, gcptr src, uint64_t d0, uint32_t dt, uint32_t tid, uint32_t nthreads) {
+    const uint32_t es = dt == 0 ? 4u : 2u;
+    const uint32_t epp = 16u / es;                        // elements per piece
+    const bool aligned = (((uint64_t)(uintptr_t)src) & 15u) == 0;
+    for (uint32_t base = 0; base < n16; base += nthreads) {
+        const uint32_t want = base + tid;
+        const uint32_t i = want < n16 ? want : n16 - 1;
+        const uint64_t e0 = (uint64_t)i * epp;
+        const bool whole = aligned && e0 + epp <= d0;
+        u32x4 v;
+        if (__builtin_amdgcn_ballot_w64(!whole) == 0) {     // the usual case: this wave's pieces all lie inside the row
+            v = *(const GLOBAL_AS u32x4 *)(src + (uint64_t)i * 16u);
+        } else {
+            uint32_t wds[4] = {0u, 0u, 0u, 0u};
+            if (dt == 0) {
+                sfor<4>([&]<int E>() LI {
+                    const uint64_t e = e0 + E;
+                    const uint32_t x = *(const GLOBAL_AS uint32_t *)(src + (e < d0 ? e : 0) * 4u);
+                    wds[E] = e < d0 ? x : 0u;
+                });
+            } else {
+                sfor<8>([&]<int E>() LI {
+                    const uint64_t e = e0 + E;
+                    const uint32_t x = *(const GLOBAL_AS uint16_t *)(src + (e < d0 ? e : 0) * 2u);
+                    wds[E / 2] |= (e < d0 ? x : 0u) << (16 * (E & 1));
+                });
+            }
+            v = u32x4{wds[0], wds[1], wds[2], wds[3]};
+        }
+        *(LDS_AS u32x4 *)(dst + (size_t)i * 16u) = v;
+    }
+}
+// Element E (0..V-1) of a chunk of an LDS image held as raw 16-byte pieces: r0 (and r1 for fp32 chunks of eight).
+template <int E> DI float lds_elem(const u32x4 &r0, const u32x4 &r1, bool bf16) {
+    if (bf16) {
+        const uint32_t w = r0[E / 2];
+        return (E & 1) ? bf16_hi(w) : bf16_lo(w);
+    }
+    return __builtin_bit_cast(float, E < 4 ? r0[E & 3] : r1[E & 3]);
+}
+// acc = acc * s [* A] [+ B] chunk by chunk, A and B read from their LDS images (V = 4: fp32 images; V = 8: bf16 or
+// fp32, per image).  A chunk of this lane that lies beyond the image (the lane holds fewer live chunks than
+// others) reads the image's first chunk: its result is never stored and reductions mask it.
+template <int K, int V, bool HASA, bool HASB>
+DI void lds_fma(Tile<K> &acc, float s, const LDS_AS char *pa, const LDS_AS char *pb, bool a_bf16, bool b_bf16, uint32_t lanecol, const Geo &g) {
+    if constexpr (K >= V) {
+        constexpr int NJ = K / V;
+        const uint32_t ncols_pad = (g.ncols + (uint32_t)V - 1u) / (uint32_t)V * (uint32_t)V;
+        const uint32_t esa = (V == 8 && a_bf16) ? 2u : 4u, esb = (V == 8 && b_bf16) ? 2u : 4u;
+        sfor<NJ>([&]<int J>() LI {
+            if ((uint32_t)J < g.nvec) {         // wave-uniform
+                const uint32_t c0 = lanecol + (uint32_t)J * g.GV;
+                const uint32_t cc = c0 + V <= ncols_pad ? c0 : 0u;
+                u32x4 a0 = {0u, 0u, 0u, 0u}, a1 = a0, b0 = a0, b1 = a0;
+                if constexpr (HASA) {
+                    a0 = *(const LDS_AS u32x4 *)(pa + cc * esa);
+                    if (V == 8 && !a_bf16) a1 = *(const LDS_AS u32x4 *)(pa + cc * esa + 16u);
+                }
+                if constexpr (HASB) {
+                    b0 = *(const LDS_AS u32x4 *)(pb + cc * esb);
+                    if (V == 8 && !b_bf16) b1 = *(const LDS_AS u32x4 *)(pb + cc * esb + 16u);
+                }
+                sfor<V>([&]<int E>() LI {
+                    const float t = TV(acc, J * V + E) * s;
+                    if constexpr (HASA && HASB) TV(acc, J * V + E) = f_fma(t, lds_elem<E>(a0, a1, V == 8 && a_bf16), lds_elem<E>(b0, b1, V == 8 && b_bf16));
+                    else if constexpr (HASA) TV(acc, J * V + E) = t * lds_elem<E>(a0, a1, V == 8 && a_bf16);
+                    else TV(acc, J * V + E) = t + lds_elem<E>(b0, b1, V == 8 && b_bf16);
+                });
+            }
+        });
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // the interpreter
 // ------------------------------------------------------------------------------------------
 // Run STMT with `RR` naming tile register number IDX (a wave-uniform value): one switch case per
@@ -903,7 +982,7 @@ DI void tile_rows(Geo &gt, const uint32_t *sh, uint32_t tile_r, uint32_t rp, uin
 // tile prologue and executes them for every tile, used or not.  The empty assembly statements pin
 // each value to its register at no cost.  Handlers that work on registers only skip all of this.
 #define DVM_GEO()                                                                                             \
-    asm volatile("" : "+v"(gt.i1), "+v"(gt.i2), "+v"(gt.i3), "+v"(gt.lanecol), "+v"(gt.lr), "+v"(gt.rowok));   \
+    asm volatile("" : "+v"(gt.i1), "+v"(gt.i2), "+v"(gt.i3), "+v"(gt.lanecol), "+v"(gt.rowok));   \
     Geo g = gt;                                                                                               \
     {                                                                                                         \
         uint32_t cb_lo = __builtin_amdgcn_readfirstlane((uint32_t)gt.colbase);                                \
@@ -978,11 +1057,13 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         gt.nvec = nvec;
         gt.nact = nvec * V;
         const uint32_t rp = tid / G;            // row of the tile held by this lane
-        gt.lr = tid - rp * G;
-        gt.lanecol = gt.lr * V;
+        gt.lanecol = (tid - rp * G) * V;
         const uint32_t gw = G >> 6;             // waves per row when a row spans waves
         const uint32_t width = G < 64 ? G : 64;
         const uint32_t w0i = gw > 1 ? (wave / gw) * gw : wave;   // first wave of this lane's row
+
+        // The prologue of this segment overwrites the LDS images the previous one may still be reading
+        if (sh[S_FLAGS] & SF_LDS) __syncthreads();
 
         // A segment that depends on earlier ones of this launch waits here (Section 5.1, temporal stacking of
         // dependent operators).  Release: this workgroup's stores are complete and visible to the device.
@@ -1318,7 +1399,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         const int64_t off = row_offset(g, DVM_I64(cw2, cw3), DVM_I64(h0, h1), DVM_I64(h2, h3));
                         gptr base = (gptr)DVM_TENSOR(tbase + ti);
                         const float v = DVM_GET_S(a);
-                        const bool ok = g.rowok && g.lr == 0 && g.colbase == 0;
+                        const bool ok = g.rowok && g.lanecol == 0 && g.colbase == 0;
                         if (dt == 0) st_b32(base + off * 4, v, ok);
                         else st_b16(base + off * 2, (uint32_t)pack_bf16(v), ok);
                         break;
@@ -1438,6 +1519,35 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                             DVM_WITH_R(a, xa, (tile_bin<K, B_MUL>(acc, xa)))
                             if (b != FMA_NO_ADDEND) {
                                 DVM_WITH_R(b, xb, (tile_bin<K, B_ADD>(acc, xb)))
+                            }
+                        }
+                        break;
+                    }
+                    case I_LDSCOPY: {
+                        // every thread of the workgroup copies 16-byte pieces of the tensor's only row into the image;
+                        // pieces that reach beyond the row's end are put together element by element, zero-filled
+                        const uint32_t ti = cw1 & 0xFF, dt = (cw1 >> 8) & 0xFF;
+                        gcptr src = (gcptr)DVM_TENSOR(tbase + ti);
+                        const uint64_t D0 = (uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32);
+                        lds_copy_row((LDS_AS char *)comb_lds + cw2, cw3 >> 4, src, D0, dt, tid, blockDim.x);
+                        if (b != 0) __syncthreads();
+                        break;
+                    }
+                    case I_LFMA: {
+                        const float s = cw1 != 0 ? DVM_GET_S(cw1 - 1) : 1.0f;
+                        const uint32_t la = a & 0xF, lb = a >> 4;
+                        const LDS_AS char *pa = (const LDS_AS char *)comb_lds + cw2;
+                        const LDS_AS char *pb = (const LDS_AS char *)comb_lds + cw3;
+                        const uint32_t lc = gt.lanecol;
+                        if (V == 4) {
+                            if (la != LFMA_NONE && lb != LFMA_NONE) lds_fma<K, 4, true, true>(acc, s, pa, pb, false, false, lc, gt);
+                            else if (la != LFMA_NONE) lds_fma<K, 4, true, false>(acc, s, pa, pb, false, false, lc, gt);
+                            else lds_fma<K, 4, false, true>(acc, s, pa, pb, false, false, lc, gt);
+                        } else {
+                            if constexpr (K >= 8) {
+                                if (la != LFMA_NONE && lb != LFMA_NONE) lds_fma<K, 8, true, true>(acc, s, pa, pb, (b & 1u) != 0, (b & 2u) != 0, lc, gt);
+                                else if (la != LFMA_NONE) lds_fma<K, 8, true, false>(acc, s, pa, pb, (b & 1u) != 0, false, lc, gt);
+                                else lds_fma<K, 8, false, true>(acc, s, pa, pb, false, (b & 2u) != 0, lc, gt);
                             }
                         }
                         break;
@@ -1722,6 +1832,9 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
         wide &= (sh[S_GEOM] & 0xFFFF) >= 64;
         grid_sync |= (sh[S_FLAGS] & SF_SYNC_GRID) != 0;
         if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
+        if (sh[S_FLAGS] & SF_LDS)           // the images the prologue copies into LDS
+            for (uint32_t pc = SH_WORDS; pc < SH_WORDS + sh[S_PROLOGA]; pc += (sh[pc] >> 8) & 0xFF)
+                if ((sh[pc] & 0xFF) == I_LDSCOPY && sh[pc + 2] + sh[pc + 3] > lds_bytes) lds_bytes = sh[pc + 2] + sh[pc + 3];
         for (uint32_t t = 0; t < sh[S_NTENS]; ++t) seg_of[sh[S_TBASE] + t] = (uint8_t)s;
         at += sh[S_WORDS];
     }

@@ -104,8 +104,16 @@ def test_fusion_keeps_intermediates_out_of_memory(ctx):
     prog = B.Program(W.get_program("c4_chain"))
     shapes = [(100, 8192), (100, 8192), (8192,), (8192,), (8192,), (100, 8192)]
     txt = B.dvm_encode(ctx, prog, [B.make_shape(s) for s in shapes]).disasm()
-    assert len(re.findall(r"\bload\b", txt)) == 6
+    # the three full-size inputs are loaded per tile (in one group, at the top of the body); the three weight
+    # vectors are copied to LDS once per workgroup and read from there
+    assert len(re.findall(r"\bload\b", txt)) == 3 and len(re.findall(r"\bldscopy\b", txt)) == 3
+    body = txt.split("; body")[1].split("\n")[1:4]
+    assert all(" load " in l for l in body)
     assert len(re.findall(r"\bstore\b", txt)) == 1
+    plain = B.Context(-1)
+    plain.set_lds_operands(False)
+    txt2 = B.dvm_encode(plain, prog, [B.make_shape(s) for s in shapes]).disasm()
+    assert len(re.findall(r"\bload\b", txt2)) == 6 and "ldscopy" not in txt2 and len(re.findall(r"\bstore\b", txt2)) == 1
     assert "workgroup sync" in txt              # rows of 8192 span several waves: the reduction synchronises
 
 
