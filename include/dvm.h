@@ -133,11 +133,12 @@ int  dvm_ctx_set_plan_override(dvm_ctx *ctx, int elems_per_lane, int rows_per_ti
 int  dvm_ctx_set_lds_operands(dvm_ctx *ctx, int enabled);
 /* How the M tiles of a meta-kernel are dealt out to the N workgroups of the launch (Section 4.3, Algorithm 2).
  * DVM_ASSIGN_BLOCKED is the range the algorithm prints: workgroup id runs tiles [m*id, min(M, m*(id+1))) with
- * m = ceil(M/N).  DVM_ASSIGN_INTERLEAVED (the default on this hardware) deals them out round-robin: workgroup
- * id runs tiles id, id+N, id+2N, ... -- the same tiles per workgroup to within one, still static and free of
- * atomics, but the resident workgroups sweep the tensors as one front, which HBM serves faster than N streams
- * that lie far apart.  Results do not depend on the choice. */
-typedef enum dvm_assignment { DVM_ASSIGN_BLOCKED = 0, DVM_ASSIGN_INTERLEAVED = 1 } dvm_assignment;
+ * m = ceil(M/N).  DVM_ASSIGN_INTERLEAVED deals them out round-robin: workgroup id runs tiles id, id+N, id+2N, ...
+ * -- the same tiles per workgroup to within one, still static and free of atomics, but the resident workgroups
+ * sweep the tensors as one front, which HBM serves faster than N streams that lie far apart.  DVM_ASSIGN_AUTO (the
+ * default) is the round-robin order except for programs that keep an operand pinned while consecutive rows share
+ * it and whose rows are not whole 128-byte lines, which run blocked.  Results do not depend on the choice. */
+typedef enum dvm_assignment { DVM_ASSIGN_BLOCKED = 0, DVM_ASSIGN_INTERLEAVED = 1, DVM_ASSIGN_AUTO = 2 } dvm_assignment;
 int  dvm_ctx_set_assignment(dvm_ctx *ctx, int assignment);
 
 /* ---- program builder (shape free) --------------------------------------------------------------- */

@@ -187,11 +187,11 @@ class Context:
     def set_sync_limit(self, polls: int) -> None:
         _check(load().dvm_ctx_set_sync_limit(self._h, polls), "dvm_ctx_set_sync_limit")
 
-    def set_lds_operands(self, enabled: bool) -> None:
+    def set_lds_operands(self, enabled) -> None:
         _check(load().dvm_ctx_set_lds_operands(self._h, int(enabled)), "dvm_ctx_set_lds_operands")
 
     def set_assignment(self, assignment: str) -> None:
-        _check(load().dvm_ctx_set_assignment(self._h, {"blocked": 0, "interleaved": 1}[assignment]), "dvm_ctx_set_assignment")
+        _check(load().dvm_ctx_set_assignment(self._h, {"blocked": 0, "interleaved": 1, "auto": 2}[assignment]), "dvm_ctx_set_assignment")
 
     def __del__(self):
         if getattr(self, "_h", None) and _lib is not None:

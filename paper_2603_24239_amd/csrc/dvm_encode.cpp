@@ -94,6 +94,7 @@ struct dvm_ctx {
     int dbg_rp;     // rows per tile, or waves per unit of a reduction along the penultimate axis (0 = cost model)
     int assignment; // DVM_ASSIGN_*: how the tiles of a meta-kernel are dealt out to the workgroups
     int lds_operands;   // row-invariant operands may live in LDS instead of pinned tile registers
+    int lds_budget;     // bytes of LDS images per workgroup
     int64_t sync_limit;     // polls a workgroup spends at a grid-wide synchronisation point before it gives up
 };
 
@@ -109,8 +110,9 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->dbg_k = 0;
     c->dbg_grid_x = 1;
     c->dbg_rp = 0;
-    c->assignment = DVM_ASSIGN_INTERLEAVED;
+    c->assignment = DVM_ASSIGN_AUTO;
     c->lds_operands = 1;
+    c->lds_budget = 40 * 1024 - 640;    // four workgroups per compute unit keep their images in its 160 KiB
     c->sync_limit = 1 << 20;
     if (hip_device >= 0) {
         int n = 0;
@@ -169,12 +171,13 @@ extern "C" int64_t dvm_ctx_sync_limit(const dvm_ctx *c) { return c ? c->sync_lim
 extern "C" int dvm_ctx_set_lds_operands(dvm_ctx *c, int enabled) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_lds_operands: null context");
     c->lds_operands = enabled != 0;
+    if (enabled > 1) c->lds_budget = enabled < (int)LDS_IMAGE_MAX_BYTES ? enabled : (int)LDS_IMAGE_MAX_BYTES;
     return DVM_OK;
 }
 
 extern "C" int dvm_ctx_set_assignment(dvm_ctx *c, int assignment) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
-    if (assignment != DVM_ASSIGN_BLOCKED && assignment != DVM_ASSIGN_INTERLEAVED) return dvm_set_error(DVM_E_ARGS, "unknown tile assignment");
+    if (assignment != DVM_ASSIGN_BLOCKED && assignment != DVM_ASSIGN_INTERLEAVED && assignment != DVM_ASSIGN_AUTO) return dvm_set_error(DVM_E_ARGS, "unknown tile assignment");
     c->assignment = assignment;
     return DVM_OK;
 }
@@ -1103,7 +1106,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                      !E.rows_class[other] && !invariant_input(other) && !E.cred_real[m] && !E.post[m];
             }
             const int64_t bytes = cdiv(E.D0 > 0 ? E.D0 : 1, V) * V * (E.acc[prog->nodes[n].input].dtype == DVM_F32 ? 4 : 2);
-            if (!ok || lds_bytes + bytes > (int64_t)LDS_IMAGE_MAX_BYTES) continue;
+            if (!ok || lds_bytes + bytes > (int64_t)ctx->lds_budget) continue;
             lds_bytes += bytes;
             E.lds_of[n] = E.n_lds;
             E.lds_node[E.n_lds++] = n;
@@ -1614,7 +1617,10 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         }
     }
     if (column_mode) {
-        int v = find_variant(16);
+        // (the widest tile register first: 128 bytes per lane and tensor in flight measured 2-9 % above 64)
+        int v = ctx->dbg_k >= (int)V ? find_variant(ctx->dbg_k) : -1;
+        if (v < 0) v = find_variant(32);
+        if (v < 0) v = find_variant(16);
         if (v < 0) v = find_variant(8);
         if (v < 0) v = find_variant(4);
         if (v < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
@@ -1716,8 +1722,15 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (nct > 1) magic_u32(nct, &sh[S_NCTM], &sh[S_NCTSH]);
     sh[S_TBASE] = 0;
     sh[S_NTENS] = (uint32_t)E.n_acc;
+    // DVM_ASSIGN_AUTO: round-robin, except for a program that keeps an operand pinned while consecutive rows share it
+    // (the reloading part of the prologue) and whose rows are not whole 128-byte lines: there a workgroup that walks
+    // consecutive rows keeps the operand and meets the lines its rows share with their neighbours again at once
+    // (measured 2-8 % faster; with rows of whole lines the round-robin order is 4 % faster).
+    bool interleaved = ctx->assignment == DVM_ASSIGN_INTERLEAVED;
+    if (ctx->assignment == DVM_ASSIGN_AUTO)
+        interleaved = !(E.n_prolog > E.n_prolog_a && (E.D0 * (int64_t)(any_bf16_full ? 2 : 4)) % 128 != 0);
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0) | (E.has_cred && E.cstream ? SF_CSTREAM : 0) |
-                  (ctx->assignment == DVM_ASSIGN_INTERLEAVED ? SF_INTERLEAVED : 0) | (E.n_lds > 0 ? SF_LDS : 0);
+                  (interleaved ? SF_INTERLEAVED : 0) | (E.n_lds > 0 ? SF_LDS : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
     if (E.has_cred) {

@@ -109,8 +109,8 @@ def compare(got: torch.Tensor, rounded: np.ndarray, exact: np.ndarray, dtype: st
 
 
 def check_program(desc, inputs: Dict[str, torch.Tensor], outputs: Optional[Dict[str, torch.Tensor]] = None,
-                  what: str = ""):
-    outs, code = run_vm(desc, inputs, outputs)
+                  what: str = "", ctx: Optional[B.Context] = None):
+    outs, code = run_vm(desc, inputs, outputs, ctx=ctx)
     rounded, exact = run_oracle(desc, inputs)
     red = has_reduction(desc)
     worst = 0.0

@@ -104,9 +104,10 @@ def test_fusion_keeps_intermediates_out_of_memory(ctx):
     prog = B.Program(W.get_program("c4_chain"))
     shapes = [(100, 8192), (100, 8192), (8192,), (8192,), (8192,), (100, 8192)]
     txt = B.dvm_encode(ctx, prog, [B.make_shape(s) for s in shapes]).disasm()
-    # the three full-size inputs are loaded per tile (in one group, at the top of the body); the three weight
-    # vectors are copied to LDS once per workgroup and read from there
-    assert len(re.findall(r"\bload\b", txt)) == 3 and len(re.findall(r"\bldscopy\b", txt)) == 3
+    # the three full-size inputs are loaded per tile; two of the weight vectors are copied to LDS once per workgroup
+    # (as many as leave room for four workgroups per compute unit) and read from there, the third comes from cache
+    # with the first group of loads
+    assert len(re.findall(r"\bload\b", txt)) == 4 and len(re.findall(r"\bldscopy\b", txt)) == 2
     body = txt.split("; body")[1].split("\n")[1:4]
     assert all(" load " in l for l in body)
     assert len(re.findall(r"\bstore\b", txt)) == 1
@@ -274,6 +275,13 @@ def test_broadcast_dim_is_visited_fastest_and_its_operand_pinned(ctx):
     assert "again whenever the second outer index changes" in txt   # the mask row is reloaded per query index only
     body = txt.split("; body (once per tile)")[1]
     assert len(re.findall(r"load", body)) == 1                      # only the scores are loaded per tile
+    assert "tiles_to_workgroups=interleaved" in txt                 # rows of whole 128-byte lines: round-robin tiles
+    # rows that are not whole lines: such a program runs blocked (a workgroup walks consecutive rows)
+    odd = _encode(ctx, "c3_masked_softmax", [(2, 32, 250, 250), (250, 250)]).disasm()
+    assert "again whenever" in odd and "tiles_to_workgroups=blocked" in odd
+    forced = B.Context(-1)
+    forced.set_assignment("interleaved")
+    assert "tiles_to_workgroups=interleaved" in _encode(forced, "c3_masked_softmax", [(2, 32, 250, 250), (250, 250)]).disasm()
     # too few repetitions to be worth a register: the mask is loaded per tile
     small = _encode(ctx, "c3_masked_softmax", [(1, 8, 256, 256), (256, 256)]).disasm()
     assert "again whenever" not in small

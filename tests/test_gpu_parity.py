@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2603_24239_amd import binding as B
 from tests import harness as H
 from workloads import gen
 from workloads import programs as W
@@ -235,11 +236,18 @@ def test_operand_pinned_along_the_fastest_outer_dim():
     """A mask [S, L] under scores [N, S, L]: the N dim is visited fastest and the mask row stays in a tile
     register until the S index changes; N not a multiple of the rows per tile makes tiles straddle."""
     desc = W.get_program("c3_masked_softmax")
+    blocked = B.Context(torch.cuda.current_device())
+    blocked.set_assignment("blocked")
+    inter = B.Context(torch.cuda.current_device())
+    inter.set_assignment("interleaved")     # (the pinned mask row is reloaded for nearly every tile)
     for (n, s_, l) in [(17, 40, 100), (19, 33, 257), (64, 7, 1000), (16, 300, 64), (130, 5, 33)]:
         say(f"pinned mask rows: scores [{n},{s_},{l}]")
         z = gen.randn((n, s_, l), 500 + n, DEV, "f32", std=3.0)
         mask = torch.zeros((s_, l), dtype=torch.float32, device=DEV)
         mask.masked_fill_(torch.rand((s_, l), generator=torch.Generator(DEV).manual_seed(n), device=DEV) < 0.3, float("-inf"))
         mask[:, 0] = 0.0            # no fully masked row
-        _, code, _ = H.check_program(desc, {"z": z, "mask": mask})
+        _, code, _ = H.check_program(desc, {"z": z, "mask": mask}, ctx=blocked)
         assert "again whenever the second outer index changes" in code.disasm()
+        _, code, _ = H.check_program(desc, {"z": z, "mask": mask}, ctx=inter)
+        assert "again whenever the second outer index changes" in code.disasm()
+        H.check_program(desc, {"z": z, "mask": mask})
