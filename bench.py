@@ -281,6 +281,7 @@ class Stream:
         self.name, self.args, self.B, self.ctx, self.dev = name, args, B, ctx, dev
         self.parts = []
         self.fixed_groups = None
+        self.set_counts = None        # per launch: how many sets of tensors it runs over (dvm_run_batched), None: one each
         self.dtype = "bf16 storage, f32 arithmetic"
         progs = {}
 
@@ -354,6 +355,7 @@ class Stream:
                 ctx.set_limits(16, 6)   # parts that share a launch must fit one interpreter variant
             steps_T = gen.c5_steps()[:n_inst]
             self.fixed_groups = []
+            self.set_counts = []
             for si, T in enumerate(steps_T):
                 d = gen.c5_inputs(T, gen.BASE_SEED + 5000 + 100 * si, dev)
                 rope_out = torch.empty((T, 32, 128), dtype=torch.bfloat16, device=dev)
@@ -366,9 +368,18 @@ class Stream:
                 add_part("c5_residual", d["c5_residual_a"], 3 * T * 4096 * 2, (T,))
                 add_part("c5_silu_gate", d["c5_silu_gate"], 3 * T * 14336 * 2, (T,))
                 add_part("c5_residual", d["c5_residual_b"], 3 * T * 4096 * 2, (T,))
-                self.fixed_groups += [list(range(first, first + 6))] * 32
+                # (layers_per_launch of the 32 layers share a launch: dvm_run_batched runs the layer's bytecode once
+                # per layer, the encode of the six programs serves all of them -- the layers have the same shapes)
+                lpl = max(1, min(32, args.layers_per_launch))
+                self.fixed_groups += [list(range(first, first + 6))] * (32 // lpl)
+                self.set_counts += [lpl] * (32 // lpl)
+                if 32 % lpl:
+                    self.fixed_groups += [list(range(first, first + 6))]
+                    self.set_counts += [32 % lpl]
             self.wl = {"workload": "config 5: 64 steps x 32 layers x {rmsnorm, rope, softmax, residual, silu-gate, residual} bf16, "
-                                   "T log-normal (median 512, 1..8192); one launch per layer, every step's wall time includes its encodes",
+                                   "T log-normal (median 512, 1..8192); the six programs of a layer stacked, %d layer(s) per launch, "
+                                   "every step's wall time includes its encodes" % max(1, min(32, args.layers_per_launch)),
+                       "launches_per_32_layer_step": len(self.fixed_groups) // max(1, len(steps_T)),
                        "steps_of_the_stream": len(steps_T)}
             self.steps_T = steps_T
         else:
@@ -379,7 +390,7 @@ class Stream:
         if self.fixed_groups is not None:
             self.groups_idx = self.fixed_groups
             self.group = 6
-            self.singles_idx = [[i] for g in self.fixed_groups for i in g]
+            self.singles_idx = [[i] for g, c in zip(self.fixed_groups, self.set_counts or [1] * len(self.fixed_groups)) for _ in range(c) for i in g]
         else:
             n_t_part = len(self.parts[0]["ins"]) + len(self.parts[0]["outs"])
             max_group = max(1, min(32 // n_t_part, 10))
@@ -387,7 +398,9 @@ class Stream:
             n = len(self.parts)
             self.groups_idx = [list(range(lo, min(lo + self.group, n))) for lo in range(0, n, self.group)]
             self.singles_idx = [[i] for i in range(n)]
-        self.total_bytes = sum(self.parts[i]["bytes"] for g in self.groups_idx for i in g)
+        counts = self.set_counts if (self.set_counts is not None and self.fixed_groups is not None) else [1] * len(self.groups_idx)
+        self.group_sets = counts
+        self.total_bytes = sum(self.parts[i]["bytes"] * c for g, c in zip(self.groups_idx, counts) for i in g)
         self.wl["instances"] = len(self.groups_idx) if self.fixed_groups is not None else len(self.parts)
         self.wl["instances_per_launch"] = self.group
         self.stacking = args.stacking or "temporal"
@@ -415,16 +428,22 @@ class Stream:
         perf = time.perf_counter
         stack_fn = lib.dvm_stack_spatial if self.stacking == "spatial" else lib.dvm_stack
 
-        def marshal(groups):
+        def marshal(groups, counts=None):
             out = []
-            for idx in groups:
+            for k, idx in enumerate(groups):
                 tens = [t for i in idx for t in parts[i]["ins"] + parts[i]["outs"]]
-                out.append((idx, (C.c_void_p * len(tens))(*[t.data_ptr() for t in tens]), len(tens)))
+                n_sets = counts[k] if counts else 1
+                ptrs = [t.data_ptr() for t in tens] * n_sets
+                out.append((idx, (C.c_void_p * len(ptrs))(*ptrs), len(tens), n_sets))
             return out
+
+        max_table = max(len([t for i in idx for t in parts[i]["ins"] + parts[i]["outs"]]) * c
+                        for idx, c in zip(self.groups_idx, self.group_sets))
+        table = torch.empty(max_table, dtype=torch.int64, device=self.dev)      # dvm_run_batched's address table
 
         def one_step(groups, events=None, enc_ns=None):
             """Encode every part, stack the parts of each launch (a single part is launched as it is), run."""
-            for k, (idx, ptrs, n_t) in enumerate(groups):
+            for k, (idx, ptrs, n_t, n_sets) in enumerate(groups):
                 for j, i in enumerate(idx):
                     pt = parts[i]
                     st = lib.dvm_encode_timed(ctx._h, pt["prog"]._h, pt["shapes"], len(pt["ins"]), pt["layout"], part_bufs[j], enc_cap,
@@ -443,7 +462,10 @@ class Stream:
                     code, code_len = stacked, ln.value
                 if events is not None:
                     events[k][0].record(stream)
-                st = lib.dvm_run(ctx._h, code, code_len, ptrs, n_t, stream_h)
+                if n_sets > 1:
+                    st = lib.dvm_run_batched(ctx._h, code, code_len, ptrs, n_t, n_sets, C.c_void_p(table.data_ptr()), table.numel() * 8, stream_h)
+                else:
+                    st = lib.dvm_run(ctx._h, code, code_len, ptrs, n_t, stream_h)
                 if st != 0:
                     raise B.DvmError(st, "dvm_run")
                 if events is not None:
@@ -461,11 +483,11 @@ class Stream:
             torch.cuda.synchronize()
             return perf() - t0, evs
 
-        groups = marshal(self.groups_idx)
+        groups = marshal(self.groups_idx, self.group_sets)
         enc_ns = []
         elapsed, all_events = timed(groups, steps, warmup, enc_ns)
         kern_ms = [a.elapsed_time(b) for evs in all_events for (a, b) in evs]
-        group_bytes = [sum(parts[i]["bytes"] for i in g) for g in self.groups_idx]
+        group_bytes = [sum(parts[i]["bytes"] for i in g) * c for g, c in zip(self.groups_idx, self.group_sets)]
         big_groups = [k for k, b in enumerate(group_bytes) if b >= 256e6]
         group_ms = [float(np.mean([all_events[s][k][0].elapsed_time(all_events[s][k][1]) for s in range(steps)])) for k in range(len(groups))]
         r = {"config": dict(self.wl), "dtype": self.dtype, "total_bytes": self.total_bytes, "elapsed_s": elapsed, "steps": steps,
@@ -594,6 +616,8 @@ def main() -> int:
     ap.add_argument("--stack", type=int, default=0,
                     help="consecutive instances merged into one launch by temporal stacking (default 8, capped by the "
                          "launch's tensor table; 1 = every instance its own launch; config 5 always stacks a layer)")
+    ap.add_argument("--layers-per-launch", type=int, default=32,
+                    help="config 5: how many of a step's 32 layers share one launch (dvm_run_batched over the layers' tensor sets)")
     ap.add_argument("--stacking", default="", choices=["", "temporal", "spatial"],
                     help="how the parts of a launch share it: one after the other on all workgroups (temporal) or side by "
                          "side on shares of the workgroups (spatial); default temporal (it measured faster on every workload here)")

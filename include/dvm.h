@@ -303,6 +303,20 @@ int  dvm_plan(int64_t total, int n_cores, int64_t t_max, int align, int overhead
 int  dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len,
              void *const *tensors, int n_tensors, void *hip_stream);
 
+/* One launch that runs `bytecode` n_sets times, each time on the next set of tensors: `tensor_sets` is a HOST array of
+ * n_sets * n_tensors DEVICE pointers, set after set, each set in the order dvm_run takes it (n_tensors as the
+ * bytecode lists them).  Every set is checked as dvm_run checks its tensors.  The sets must be independent: no set
+ * reads what another writes (the workgroups pass from one set to the next without waiting for each other); sets that
+ * write the same buffer leave the result of one of them.  `table` is DEVICE memory the caller lends to the launch
+ * (8-byte aligned, table_bytes >= 8 * n_sets * n_tensors): the addresses are copied there on `hip_stream` and read
+ * from there by the launch, so it must stay untouched until the launch has finished.  Bytecode that lists a
+ * workspace (dvm_stack_dependent with a grid-wide wait) is refused with DVM_E_UNSUPPORTED.
+ * Use: the layers of a model step that apply one program (or one stack of programs) to different tensors of the
+ * same shapes -- one encode, one launch. */
+int  dvm_run_batched(const dvm_ctx *ctx, const void *bytecode, size_t len,
+                     void *const *tensor_sets, int n_tensors, int n_sets,
+                     void *table, size_t table_bytes, void *hip_stream);
+
 /* dvm_run for callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
  * harnesses that forbid hipMalloc): the same launch, but where the bytecode lists a workspace (dvm_stack_dependent)
  * the library's own array in device memory takes its place -- DVM_STATIC_WORKSPACE_BYTES per device, part of the

@@ -99,6 +99,7 @@ def load() -> C.CDLL:
         "dvm_plan": (i, [C.c_int64, i, C.c_int64, i, i, P(C.c_int64), P(C.c_int64), P(C.c_int64)]),
         "dvm_run": (i, [vp, vp, sz, P(vp), i, vp]),
         "dvm_run_static": (i, [vp, vp, sz, P(vp), i, vp]),
+        "dvm_run_batched": (i, [vp, vp, sz, P(vp), i, i, vp, sz, vp]),
         "dvm_encode_timed": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), i, P(C.c_int64)]),
         "dvm_copy_kernel": (i, [vp, vp, vp, sz, i, vp]),
         "dvm_strerror": (C.c_char_p, [i]),
@@ -127,7 +128,7 @@ EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ct
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
             "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_stack_dependent",
             "dvm_ctx_set_sync_limit", "dvm_workspace_status", "dvm_validate", "dvm_disasm",
-            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_run_static", "dvm_encode_timed", "dvm_copy_kernel", "dvm_strerror", "dvm_last_error_detail",
+            "dvm_code_info_get", "dvm_code_tensor", "dvm_plan", "dvm_run", "dvm_run_static", "dvm_run_batched", "dvm_encode_timed", "dvm_copy_kernel", "dvm_strerror", "dvm_last_error_detail",
             "dvm_last_hip_error", "dvm_fuser_create", "dvm_fuser_destroy", "dvm_fuser_set_workspace", "dvm_fuser_tensor", "dvm_fuser_op",
             "dvm_fuser_release", "dvm_fuser_flush", "dvm_fuser_stats", "dvm_fuser_last_code"]
 
@@ -356,6 +357,18 @@ def dvm_run(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: in
     n = len(tensor_ptrs)
     arr = (C.c_void_p * max(n, 1))(*tensor_ptrs)
     _check(load().dvm_run(ctx._h, code.ptr, len(code), arr, n, C.c_void_p(stream)), "dvm_run")
+
+
+def dvm_run_batched(ctx: Context, code: Bytecode, tensor_ptr_sets: Sequence[Sequence[int]], table_ptr: int, table_bytes: int,
+                    stream: int = 0) -> None:
+    """One launch over several sets of tensors (device pointers); `table_ptr`: device memory for the address table."""
+    n_sets = len(tensor_ptr_sets)
+    n = len(tensor_ptr_sets[0])
+    flat = [p for s_ in tensor_ptr_sets for p in s_]
+    assert len(flat) == n * n_sets
+    arr = (C.c_void_p * len(flat))(*flat)
+    _check(load().dvm_run_batched(ctx._h, code.ptr, len(code), arr, n, n_sets, C.c_void_p(table_ptr), table_bytes, C.c_void_p(stream)),
+           "dvm_run_batched")
 
 
 def dvm_run_static(ctx: Context, code: Bytecode, tensor_ptrs: Sequence[int], stream: int = 0) -> None:

@@ -41,6 +41,12 @@ struct KArgs {
     uint64_t ws;                        // the launch's workspace (0: none)
     uint32_t nseg;
     uint32_t spin_limit;                // polls a workgroup spends at a grid-wide synchronisation point before it gives up
+    uint64_t sets;                      // batched launch: device array of n_sets * n_tensors addresses (0: `tensors` above)
+    uint32_t n_sets;                    // times the program runs, each time on the next set of tensors (at least 1)
+    uint32_t n_tensors;
+    uint32_t rotate;                    // 1: every segment deals its tiles out starting at the workgroup after the one the
+                                        // segment before stopped at (short segments then do not all land on the first workgroups)
+    uint32_t pad;
 };
 
 #define DI __device__ __forceinline__
@@ -1026,12 +1032,23 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
     const uint32_t ngrid = gridDim.x;
     uint32_t red_par = 0;
     uint32_t n_sync = 0;                    // grid-wide synchronisation points passed so far
+    uint32_t rot = 0;                       // first workgroup of the next segment's tiles (rotating assignment)
     const uint32_t *code = args.code;
     // the launch's tensor addresses, one per lane: a memory record reads the one it needs with a single lane read
     // (the index is wave-uniform) instead of a scalar load whose latency it would have to wait for
     uint32_t tp_lo, tp_hi;
     {
         const uint64_t mine = args.tensors[tid & (DVM_MAX_TENSORS - 1)];
+        tp_lo = (uint32_t)mine;
+        tp_hi = (uint32_t)(mine >> 32);
+    }
+    // A batched launch runs the whole program once per set of tensors, the sets one after the other; the workgroups
+    // pass from one set to the next without waiting for each other (the sets are independent).
+    for (uint32_t set = 0; set < args.n_sets; ++set) {
+    if (args.sets != 0) {
+        const uint32_t slot = tid & (DVM_MAX_TENSORS - 1);
+        const uint32_t idx = set * args.n_tensors + (slot < args.n_tensors ? slot : 0u);
+        const uint64_t mine = ((const GLOBAL_AS uint64_t *)args.sets)[idx];
         tp_lo = (uint32_t)mine;
         tp_hi = (uint32_t)(mine >> 32);
     }
@@ -1101,6 +1118,11 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         // Algorithm 2: m = ceil(M / N); this workgroup runs tiles [m*id, min(M, m*(id+1))).  In a
         // spatially stacked launch N and id count the workgroups of this segment's share only.
         uint32_t sbid = bid, sgrid = ngrid;
+        if (args.rotate != 0) {
+            sbid = bid >= rot ? bid - rot : bid + ngrid - rot;
+            rot += M % ngrid;
+            if (rot >= ngrid) rot -= ngrid;
+        }
         if (sh[S_NWG] != 0) {
             sbid = bid - sh[S_WG0];
             sgrid = sh[S_NWG];
@@ -1600,6 +1622,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         }
         seg += seg_words;
     }
+    }   // (sets)
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1750,23 +1773,74 @@ int resident_per_cu(vm_launch_t launch, uint32_t block, uint32_t lds_bytes, int 
     return 0;
 }
 
-int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors_in, int n_tensors, void *hip_stream, bool static_ws);
+struct Batch { int n_sets; void *table; size_t table_bytes; };     // device memory for the sets' address table
+int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors_in, int n_tensors, void *hip_stream, bool static_ws,
+             const Batch *batch);
 
 }  // namespace
 
 extern "C" int dvm_run(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors, int n_tensors,
                        void *hip_stream) {
-    return run_impl(ctx, bytecode, len, tensors, n_tensors, hip_stream, false);
+    return run_impl(ctx, bytecode, len, tensors, n_tensors, hip_stream, false, nullptr);
 }
 
 extern "C" int dvm_run_static(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors, int n_tensors,
                               void *hip_stream) {
-    return run_impl(ctx, bytecode, len, tensors, n_tensors, hip_stream, true);
+    return run_impl(ctx, bytecode, len, tensors, n_tensors, hip_stream, true, nullptr);
+}
+
+extern "C" int dvm_run_batched(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensor_sets, int n_tensors, int n_sets,
+                               void *table, size_t table_bytes, void *hip_stream) {
+    if (n_sets < 1 || n_tensors < 1 || !table) return dvm_set_error(DVM_E_ARGS, "dvm_run_batched: at least one set of at least one tensor, and a table buffer");
+    if (((uintptr_t)table & 7) || table_bytes < (size_t)n_sets * (size_t)n_tensors * 8)
+        return dvm_set_error(DVM_E_ARGS, "dvm_run_batched: the table buffer holds n_sets * n_tensors addresses of 8 bytes, 8-byte aligned");
+    const Batch b{n_sets, table, table_bytes};
+    return run_impl(ctx, bytecode, len, tensor_sets, n_tensors, hip_stream, false, &b);
 }
 
 namespace {
 
-int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors_in, int n_tensors, void *hip_stream, bool static_ws) {
+// One set of tensors against the bytecode's tensor table: no null pointer, the alignment the bytecode was encoded
+// for, equal pointers where it names two entries as the same buffer, and no overlap between a buffer one segment
+// writes and a buffer of another segment unless the bytecode orders them.
+int check_tensor_set(const uint32_t *w, const uint8_t *seg_of, void *const *tensors) {
+    const uint32_t ntens = w[PH_NTENS];
+    uint64_t addr_of[DVM_MAX_TENSORS], size_of[DVM_MAX_TENSORS];
+    for (uint32_t i = 0; i < ntens; ++i) {
+        const uint32_t *te = w + PH_WORDS_N + i * TT_WORDS;
+        const uint32_t info = te[TT_INFO];
+        const uint64_t align = 1ull << ((info >> 16) & 0xFF);
+        const uint64_t addr = (uint64_t)(uintptr_t)tensors[i];
+        if (addr == 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: null tensor pointer");
+        if (addr & (align - 1)) return dvm_set_error(DVM_E_ALIGN, "dvm_run: tensor pointer below the alignment the bytecode was encoded for");
+        if ((info >> 24) != 0 && addr != (uint64_t)(uintptr_t)tensors[(info >> 24) - 1])
+            return dvm_set_error(DVM_E_ARGS, "dvm_run: two entries the bytecode names as the same buffer got different pointers");
+        addr_of[i] = addr;
+        size_of[i] = (uint64_t)te[TT_BYTES_LO] | ((uint64_t)te[TT_BYTES_HI] << 32);
+    }
+    if (w[PH_NSEG] > 1) {
+        for (uint32_t i = 0; i < ntens; ++i) {
+            const uint32_t ii = w[PH_WORDS_N + i * TT_WORDS + TT_INFO];
+            if (ii & TI_WORKSPACE) continue;
+            uint32_t root_i = i;
+            while (w[PH_WORDS_N + root_i * TT_WORDS + TT_INFO] >> 24) root_i = (w[PH_WORDS_N + root_i * TT_WORDS + TT_INFO] >> 24) - 1;
+            for (uint32_t j = 0; j < i; ++j) {
+                const uint32_t ij = w[PH_WORDS_N + j * TT_WORDS + TT_INFO];
+                if (seg_of[i] == seg_of[j] || !((ii | ij) & TI_OUTPUT)) continue;
+                if (addr_of[i] >= addr_of[j] + size_of[j] || addr_of[j] >= addr_of[i] + size_of[i]) continue;
+                uint32_t root_j = j;
+                while (w[PH_WORDS_N + root_j * TT_WORDS + TT_INFO] >> 24) root_j = (w[PH_WORDS_N + root_j * TT_WORDS + TT_INFO] >> 24) - 1;
+                if (root_i != root_j)
+                    return dvm_set_error(DVM_E_ARGS, "dvm_run: a buffer one stacked part writes overlaps a buffer of another part "
+                                                     "and the bytecode does not order them (dvm_stack_dependent)");
+            }
+        }
+    }
+    return DVM_OK;
+}
+
+int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *tensors_in, int n_tensors, void *hip_stream, bool static_ws,
+             const Batch *batch) {
     if (!ctx || !bytecode || (!tensors_in && n_tensors > 0)) return dvm_set_error(DVM_E_ARGS, "dvm_run: null argument");
     if (dvm_ctx_device(ctx) < 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: context was created without a device");
     int st = dvm_validate(bytecode, len);
@@ -1797,21 +1871,16 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
 
     KArgs ka;
     memcpy(ka.code, w + segs_off, (size_t)seg_words * 4);
-    uint64_t size_of[DVM_MAX_TENSORS];
     ka.ws = 0;
     for (uint32_t i = 0; i < ntens; ++i) {
-        const uint32_t *te = w + PH_WORDS_N + i * TT_WORDS;
-        const uint32_t info = te[TT_INFO];
-        const uint64_t align = 1ull << ((info >> 16) & 0xFF);
-        const uint64_t addr = (uint64_t)(uintptr_t)tensors[i];
-        if (addr == 0) return dvm_set_error(DVM_E_ARGS, "dvm_run: null tensor pointer");
-        if (addr & (align - 1)) return dvm_set_error(DVM_E_ALIGN, "dvm_run: tensor pointer below the alignment the bytecode was encoded for");
-        if ((info >> 24) != 0 && addr != (uint64_t)(uintptr_t)tensors[(info >> 24) - 1])
-            return dvm_set_error(DVM_E_ARGS, "dvm_run: two entries the bytecode names as the same buffer got different pointers");
-        ka.tensors[i] = addr;
-        size_of[i] = (uint64_t)te[TT_BYTES_LO] | ((uint64_t)te[TT_BYTES_HI] << 32);
-        if (info & TI_WORKSPACE) ka.ws = addr;
+        ka.tensors[i] = (uint64_t)(uintptr_t)tensors[i];
+        if (w[PH_WORDS_N + i * TT_WORDS + TT_INFO] & TI_WORKSPACE) ka.ws = ka.tensors[i];
     }
+    ka.sets = 0;
+    ka.n_sets = 1;
+    ka.n_tensors = ntens;
+    ka.rotate = 0;
+    ka.pad = 0;
     ka.nseg = w[PH_NSEG];
     ka.spin_limit = (uint32_t)dvm_ctx_sync_limit(ctx);
 
@@ -1822,7 +1891,7 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
     // and LDS for the combination across waves: four floats per lane of every participating wave
     uint32_t lds_bytes = 0;
     bool cred = false, wide = true;     // wide: every segment spreads a row over whole waves
-    bool grid_sync = false;
+    bool grid_sync = false, wg_sync = false;
     uint8_t seg_of[DVM_MAX_TENSORS];    // the segment a tensor belongs to
     memset(seg_of, 0xFF, sizeof(seg_of));
     for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
@@ -1831,6 +1900,7 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
         cred |= sh[S_INNER] != 0;
         wide &= (sh[S_GEOM] & 0xFFFF) >= 64;
         grid_sync |= (sh[S_FLAGS] & SF_SYNC_GRID) != 0;
+        wg_sync |= (sh[S_FLAGS] & SF_SYNC_WG) != 0;
         if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
         if (sh[S_FLAGS] & SF_LDS)           // the images the prologue copies into LDS
             for (uint32_t pc = SH_WORDS; pc < SH_WORDS + sh[S_PROLOGA]; pc += (sh[pc] >> 8) & 0xFF)
@@ -1838,27 +1908,27 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
         for (uint32_t t = 0; t < sh[S_NTENS]; ++t) seg_of[sh[S_TBASE] + t] = (uint8_t)s;
         at += sh[S_WORDS];
     }
-    // Segments of one launch run without order between them unless the bytecode says otherwise: a buffer that
-    // one segment writes must not overlap a buffer of another segment, except where both entries were
-    // declared as the same buffer (dvm_stack_dependent put a synchronisation point between them).
-    if (w[PH_NSEG] > 1) {
-        for (uint32_t i = 0; i < ntens; ++i) {
-            const uint32_t ii = w[PH_WORDS_N + i * TT_WORDS + TT_INFO];
-            if (ii & TI_WORKSPACE) continue;
-            uint32_t root_i = i;
-            while (w[PH_WORDS_N + root_i * TT_WORDS + TT_INFO] >> 24) root_i = (w[PH_WORDS_N + root_i * TT_WORDS + TT_INFO] >> 24) - 1;
-            for (uint32_t j = 0; j < i; ++j) {
-                const uint32_t ij = w[PH_WORDS_N + j * TT_WORDS + TT_INFO];
-                if (seg_of[i] == seg_of[j] || !((ii | ij) & TI_OUTPUT)) continue;
-                if (ka.tensors[i] >= ka.tensors[j] + size_of[j] || ka.tensors[j] >= ka.tensors[i] + size_of[i]) continue;
-                uint32_t root_j = j;
-                while (w[PH_WORDS_N + root_j * TT_WORDS + TT_INFO] >> 24) root_j = (w[PH_WORDS_N + root_j * TT_WORDS + TT_INFO] >> 24) - 1;
-                if (root_i != root_j)
-                    return dvm_set_error(DVM_E_ARGS, "dvm_run: a buffer one stacked part writes overlaps a buffer of another part "
-                                                     "and the bytecode does not order them (dvm_stack_dependent)");
-            }
-        }
+    // Segments of one launch run without order between them unless the bytecode says otherwise: see check_tensor_set
+    const int n_sets = batch ? batch->n_sets : 1;
+    for (int k = 0; k < n_sets; ++k) {
+        st = check_tensor_set(w, seg_of, tensors + (size_t)k * ntens);
+        if (st != DVM_OK) return st;
     }
+    if (batch) {
+        if (grid_sync || ka.ws != 0) return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_run_batched: bytecode with a workspace runs one set at a time");
+        // the sets' addresses travel through the caller's table buffer (copied on the launch's stream)
+        const hipError_t ce = hipMemcpyAsync(batch->table, tensors, (size_t)n_sets * ntens * 8, hipMemcpyHostToDevice, (hipStream_t)hip_stream);
+        if (ce != hipSuccess) {
+            t_last_hip_error = (int)ce;
+            return dvm_set_error(DVM_E_HIP, hipGetErrorString(ce));
+        }
+        ka.sets = (uint64_t)(uintptr_t)batch->table;
+        ka.n_sets = (uint32_t)n_sets;
+    }
+    // Several segments, or several sets: the tiles of each are dealt out from where the one before stopped.  (Not
+    // when a segment relies on its producer's assignment of tiles to workgroups, nor when the segments own shares
+    // of the workgroups.)
+    ka.rotate = (w[PH_NSEG] > 1 || n_sets > 1) && !wg_sync && (w[PH_TYPE] & 0xFFFF) != KT_STACK_SPATIAL ? 1u : 0u;
     vm_launch_t launch = nullptr;
     if (cred) {
         for (const VariantEntry &v : g_cred_variants)
