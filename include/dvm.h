@@ -127,6 +127,17 @@ int  dvm_ctx_set_limits(dvm_ctx *ctx, int max_elems_per_lane, int max_tile_regs)
  * per resident slot.  0 leaves a choice to the planner.  The bytecode depends on these settings and on the
  * other context settings, the program and the shapes only; the library reads no environment variable. */
 int  dvm_ctx_set_plan_override(dvm_ctx *ctx, int elems_per_lane, int rows_per_tile, int grid_multiplier);
+/* Let dvm_encode plan for a workspace of up to `bytes` bytes (default 0: no program ever needs one).  With a limit
+ * above 0, a program that reduces along the penultimate axis (DVM_OP_CSUM / CMAX / CMIN) over few (outer index, column
+ * tile) units and a long axis is split: the bytecode is then a temporally stacked program of two meta-kernels -- partial
+ * results of S row ranges into the workspace, then their combination in the fixed order of the ranges and the ops
+ * after the reduction; dvm_run issues the second as a kernel launch of its own behind the first, which on this
+ * hardware is the cheapest way to make the partial results visible -- and lists the workspace as its LAST tensor
+ * (dvm_code_tensor: is_output = 2, min_bytes = what this program needs); the caller passes that much 256-byte
+ * aligned device memory as the last entry of tensors[] (or calls dvm_run_static, whose array then serves, up to
+ * DVM_STATIC_WORKSPACE_BYTES).  The result does not depend on the number of compute units running: S and the order
+ * are fixed by the shapes.  Such bytecode cannot be a part of dvm_stack / dvm_stack_dependent or run batched. */
+int  dvm_ctx_set_workspace_limit(dvm_ctx *ctx, int64_t bytes);
 /* Row-invariant operands that a program only multiplies by or adds (a weight vector, a bias) may be kept in
  * the workgroup's LDS instead of pinned tile registers when that lets the program run in an interpreter variant
  * with fewer tile registers, i.e. more resident waves (default: enabled).  0 disables it (tests, comparison). */
@@ -206,7 +217,8 @@ int  dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, co
 /* Upper bound on the polls (about a microsecond each) a workgroup spends at a grid-wide synchronisation point
  * before it gives up; the default is about one million.  polls < 1 is an error. */
 int  dvm_ctx_set_sync_limit(dvm_ctx *ctx, int64_t polls);
-/* Wait for `hip_stream` and read the status word of a workspace: *gave_up = 1 if a launch that used it since it
+/* (Only launches with a grid-wide synchronisation point use and clear the status word.)
+ * Wait for `hip_stream` and read the status word of a workspace: *gave_up = 1 if a launch that used it since it
  * was last cleared abandoned a synchronisation point (its outputs are then incomplete), else 0. */
 int  dvm_workspace_status(const void *workspace, void *hip_stream, int *gave_up);
 

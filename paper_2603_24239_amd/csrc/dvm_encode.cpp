@@ -95,6 +95,7 @@ struct dvm_ctx {
     int assignment; // DVM_ASSIGN_*: how the tiles of a meta-kernel are dealt out to the workgroups
     int lds_operands;   // row-invariant operands may live in LDS instead of pinned tile registers
     int lds_budget;     // bytes of LDS images per workgroup
+    int64_t workspace_limit;    // bytes of workspace dvm_encode may plan for (0: programs never need one)
     int64_t sync_limit;     // polls a workgroup spends at a grid-wide synchronisation point before it gives up
 };
 
@@ -112,6 +113,7 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->dbg_rp = 0;
     c->assignment = DVM_ASSIGN_AUTO;
     c->lds_operands = 1;
+    c->workspace_limit = 0;
     c->lds_budget = 40 * 1024 - 640;    // four workgroups per compute unit keep their images in its 160 KiB
     c->sync_limit = 1 << 20;
     if (hip_device >= 0) {
@@ -167,6 +169,12 @@ extern "C" int dvm_ctx_set_sync_limit(dvm_ctx *c, int64_t polls) {
     return DVM_OK;
 }
 extern "C" int64_t dvm_ctx_sync_limit(const dvm_ctx *c) { return c ? c->sync_limit : 0; }
+
+extern "C" int dvm_ctx_set_workspace_limit(dvm_ctx *c, int64_t bytes) {
+    if (!c || bytes < 0) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_workspace_limit: null context or negative size");
+    c->workspace_limit = bytes;
+    return DVM_OK;
+}
 
 extern "C" int dvm_ctx_set_lds_operands(dvm_ctx *c, int enabled) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_lds_operands: null context");
@@ -759,6 +767,176 @@ uint32_t bits_f32(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 
 }  // namespace
 
+static int stack_impl(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as, void *out, size_t cap,
+                      size_t *len, bool spatial);
+
+// dvm_encode of a program whose single reduction along the penultimate axis (node c, over `size` rows) is split S ways.
+// Part 1: the ops before the reduction and the reduction itself over tensors seen as [.., S, size/S, N]: its output,
+// [.., S, 1, N] fp32, is the data area of the launch's workspace.  Part 2: the same reduction over that area seen as
+// [.., S, N], then the ops after it.  The two are encoded on their own and joined into one temporally stacked program
+// whose tensor table is the program's inputs, its outputs and the workspace; part 2 is a kernel launch of its own.
+static int encode_split_reduction(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_shape *in_shapes, const dvm_shape *out_layout,
+                                  void *bytecode, size_t cap, size_t *len, dvm_shape *out_shapes, const bool *post, int c, int R, int S,
+                                  int64_t size, const int64_t *dom) {
+    const int NN = prog->n_nodes, n_in = prog->n_in, n_out = prog->n_out;
+    dvm_ctx sub = *ctx;
+    sub.workspace_limit = 0;
+    if (sub.max_k > 8) sub.max_k = 8;       // (the streaming form of the reduction runs in the variants up to 8 elements per lane)
+    if (sub.dbg_rp == 0) sub.dbg_rp = 4;    // four waves per unit: workgroups of 256 threads, four of them per compute unit
+    // ---- part 1
+    dvm_prog p1;
+    memset(&p1, 0, sizeof(p1));
+    p1.finished = true;
+    p1.n_in = n_in;
+    for (int i = 0; i < n_in; ++i) p1.in_dtype[i] = prog->in_dtype[i];
+    p1.n_nodes = NN;
+    for (int n = 0; n < NN; ++n) {
+        p1.nodes[n] = prog->nodes[n];
+        if (post[n] && n != c) p1.nodes[n].kind = N_DEAD;
+    }
+    p1.n_out = 1;
+    p1.out_node[0] = c;
+    p1.out_dtype[0] = DVM_F32;
+    dvm_shape sh1[DVM_MAX_TENSORS];
+    for (int i = 0; i < n_in; ++i) {
+        const dvm_shape &a = in_shapes[i];
+        dvm_shape &b = sh1[i];
+        b = a;
+        if (a.rank >= 2) {              // [.., d, last] -> [.., S, d / S, last] (a broadcast extent of 1 -> 1, 1)
+            const int ax = a.rank - 2;
+            b.rank = a.rank + 1;
+            for (int k = 0; k < ax; ++k) { b.dim[k] = a.dim[k]; b.stride[k] = a.stride[k]; }
+            if (a.dim[ax] == 1) {
+                b.dim[ax] = 1; b.stride[ax] = 0;
+                b.dim[ax + 1] = 1; b.stride[ax + 1] = 0;
+            } else {
+                if (a.dim[ax] != size) return dvm_set_error(DVM_E_SHAPE, "internal: extent of the reduced axis");
+                b.dim[ax] = S; b.stride[ax] = a.stride[ax] * (size / S);
+                b.dim[ax + 1] = size / S; b.stride[ax + 1] = a.stride[ax];
+            }
+            b.dim[ax + 2] = a.dim[ax + 1];
+            b.stride[ax + 2] = a.stride[ax + 1];
+        }
+    }
+    unsigned char code1[DVM_CODE_MAX_BYTES + 512], code2[DVM_CODE_MAX_BYTES + 512];
+    size_t len1 = 0, len2 = 0;
+    dvm_shape part_shape;
+    int st = dvm_encode(&sub, &p1, sh1, n_in, nullptr, code1, sizeof(code1), &len1, &part_shape);
+    if (st != DVM_OK) return st;
+    int64_t part_elems = 1;
+    for (int k = 0; k < part_shape.rank; ++k) part_elems *= part_shape.dim[k];
+    // ---- part 2: [partial results, the inputs the later ops take] -> the program's outputs
+    dvm_prog p2;
+    memset(&p2, 0, sizeof(p2));
+    p2.finished = true;
+    int map[MAX_NODES], in_of[DVM_MAX_TENSORS];
+    for (int n = 0; n < NN; ++n) map[n] = -1;
+    int nn = 0;
+    p2.in_dtype[0] = DVM_F32;
+    p2.nodes[nn] = Node{N_IN, 0, 0, 0, -1, -1, -1, 0, 0.0f};
+    const int part_node = nn++;
+    p2.n_in = 1;
+    dvm_shape sh2[DVM_MAX_TENSORS];
+    {
+        int64_t dims[DVM_MAX_RANK];
+        for (int k = 0; k < R; ++k) dims[k] = dom[k];
+        dims[R - 2] = S;
+        dvm_shape_contiguous(&sh2[0], R, dims);
+        sh2[0].align_bytes = 16;
+    }
+    for (int n = 0; n < NN; ++n) {          // inputs of the ops after the reduction
+        if (!post[n] || n == c) continue;
+        const Node &nd = prog->nodes[n];
+        const int args[3] = {nd.a, (nd.kind == N_BIN || nd.kind == N_SEL) ? nd.b : -1, nd.kind == N_SEL ? nd.c : -1};
+        for (int j = 0; j < 3; ++j) {
+            const int a = args[j];
+            if (a < 0 || map[a] >= 0 || prog->nodes[a].kind != N_IN) continue;
+            const int t = prog->nodes[a].input;
+            in_of[p2.n_in] = t;
+            p2.in_dtype[p2.n_in] = prog->in_dtype[t];
+            sh2[p2.n_in] = in_shapes[t];
+            p2.nodes[nn] = Node{N_IN, 0, 0, 0, -1, -1, -1, (int16_t)p2.n_in, 0.0f};
+            map[a] = nn++;
+            ++p2.n_in;
+        }
+    }
+    p2.nodes[nn] = Node{N_CRED, prog->nodes[c].op, 0, 0, (int16_t)part_node, -1, -1, 0, 0.0f};
+    map[c] = nn++;
+    for (int n = 0; n < NN; ++n) {
+        if (!post[n] || n == c) continue;
+        Node nd = prog->nodes[n];
+        if (nd.kind == N_DEAD) continue;
+        if (nd.a >= 0) nd.a = (int16_t)map[nd.a];
+        if ((nd.kind == N_BIN || nd.kind == N_SEL) && nd.b >= 0) nd.b = (int16_t)map[nd.b];
+        if (nd.kind == N_SEL && nd.c >= 0) nd.c = (int16_t)map[nd.c];
+        p2.nodes[nn] = nd;
+        map[n] = nn++;
+    }
+    p2.n_nodes = nn;
+    p2.n_out = n_out;
+    for (int o = 0; o < n_out; ++o) {
+        if (map[prog->out_node[o]] < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "internal: output of a split reduction not computed after it");
+        p2.out_node[o] = map[prog->out_node[o]];
+        p2.out_dtype[o] = prog->out_dtype[o];
+    }
+    st = dvm_encode(&sub, &p2, sh2, p2.n_in, out_layout, code2, sizeof(code2), &len2, out_shapes);
+    if (st != DVM_OK) return st;
+    // ---- join: stack the two, then fold their tensor tables into [inputs, outputs, workspace]
+    unsigned char both[2 * DVM_CODE_MAX_BYTES + 1024];
+    const void *codes[2] = {code1, code2};
+    const size_t lens[2] = {len1, len2};
+    size_t lenb = 0;
+    st = stack_impl(codes, lens, 2, nullptr, 0, both, sizeof(both), &lenb, false);
+    if (st != DVM_OK) return st;
+    const uint32_t *sw = (const uint32_t *)both;
+    const uint32_t nt1 = (uint32_t)n_in + 1, nt2 = (uint32_t)p2.n_in + (uint32_t)n_out, ntf = (uint32_t)(n_in + n_out + 1);
+    const uint32_t ws_index = (uint32_t)(n_in + n_out);
+    uint32_t final_of[2 * DVM_MAX_TENSORS];     // index in the stacked table -> index in the final table
+    for (uint32_t t = 0; t < nt1; ++t) final_of[t] = t < (uint32_t)n_in ? t : ws_index;
+    for (uint32_t t = 0; t < nt2; ++t)
+        final_of[nt1 + t] = t == 0 ? ws_index : (t < (uint32_t)p2.n_in ? (uint32_t)in_of[t] : (uint32_t)n_in + (t - (uint32_t)p2.n_in));
+    const uint32_t segs_off_s = PH_WORDS_N + (nt1 + nt2) * TT_WORDS;
+    const uint32_t seg_words = sw[PH_WORDS] - segs_off_s;
+    const size_t words = PH_WORDS_N + (size_t)ntf * TT_WORDS + seg_words;
+    *len = words * 4;
+    if (seg_words * 4 > DVM_CODE_MAX_BYTES) return dvm_set_error(DVM_E_LIMIT, "bytecode exceeds the per-launch limit");
+    if (!bytecode || cap < words * 4) return dvm_set_error(DVM_E_BUFSZ, "bytecode buffer too small");
+    uint32_t *w = (uint32_t *)bytecode;
+    memset(w, 0, words * 4);
+    memcpy(w, sw, PH_WORDS_N * 4);
+    w[PH_WORDS] = (uint32_t)words;
+    w[PH_NTENS] = ntf;
+    uint32_t *tt = w + PH_WORDS_N;
+    for (uint32_t t = 0; t < (uint32_t)n_in; ++t) memcpy(tt + t * TT_WORDS, sw + PH_WORDS_N + t * TT_WORDS, TT_WORDS * 4);
+    for (uint32_t o = 0; o < (uint32_t)n_out; ++o)
+        memcpy(tt + ((uint32_t)n_in + o) * TT_WORDS, sw + PH_WORDS_N + (nt1 + (uint32_t)p2.n_in + o) * TT_WORDS, TT_WORDS * 4);
+    {
+        uint32_t *te = tt + ws_index * TT_WORDS;
+        const uint64_t bytes = (uint64_t)DVM_WORKSPACE_BYTES + (uint64_t)part_elems * 4;
+        te[TT_INFO] = (uint32_t)DVM_F32 | TI_OUTPUT | TI_WORKSPACE | (8u << 16);
+        te[TT_BYTES_LO] = (uint32_t)(bytes & 0xFFFFFFFFu);
+        te[TT_BYTES_HI] = (uint32_t)(bytes >> 32);
+    }
+    uint32_t *sg = w + PH_WORDS_N + ntf * TT_WORDS;
+    memcpy(sg, sw + segs_off_s, (size_t)seg_words * 4);
+    uint32_t at = 0;
+    for (uint32_t k = 0; k < sw[PH_NSEG]; ++k) {
+        uint32_t *sh = sg + at;
+        const uint32_t tb = sh[S_TBASE];
+        for (uint32_t pc = SH_WORDS; pc < sh[S_WORDS]; pc += (sh[pc] >> 8) & 0xFF) {
+            const uint32_t op = sh[pc] & 0xFF;
+            if (op == I_LOAD || op == I_VLOAD || op == I_STORE || op == I_VSTORE || op == I_LOADS || op == I_STORES || op == I_CSTREAM ||
+                op == I_LDSCOPY)
+                sh[pc + 1] = (sh[pc + 1] & ~0xFFu) | final_of[tb + (sh[pc + 1] & 0xFF)];
+        }
+        sh[S_TBASE] = 0;
+        sh[S_NTENS] = ntf;
+        if (k > 0) sh[S_FLAGS] |= SF_NEW_LAUNCH;
+        at += sh[S_WORDS];
+    }
+    return dvm_validate(bytecode, words * 4);
+}
+
 extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_shape *in_shapes, int n_in,
                           const dvm_shape *out_layout, void *bytecode, size_t cap, size_t *len, dvm_shape *out_shapes) {
     if (!ctx || !prog || !len || (n_in > 0 && !in_shapes)) return dvm_set_error(DVM_E_ARGS, "dvm_encode: null argument");
@@ -887,6 +1065,39 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     for (int n = 0; n < NN && E.cstream; ++n)
         for (int m = n + 1; m < NN && E.cstream; ++m)
             if (E.cred_real[n] && E.cred_real[m] && prog->nodes[n].a == prog->nodes[m].a) E.cstream = false;
+
+    // A reduction along the penultimate axis with few units of work (outer index, column tile) and a long reduced
+    // axis is split when the context allows a workspace: the rows of every unit are dealt out to S units that each
+    // leave a partial result in the workspace, and a second meta-kernel, behind a grid-wide synchronisation
+    // point, combines the S partial results in their fixed order and runs the ops that follow the reduction.
+    if (E.has_cred && ctx->workspace_limit > 0 && total > 0) {
+        int c = -1, n_cred = 0;
+        for (int n = 0; n < NN; ++n)
+            if (E.cred_real[n]) { c = n; ++n_cred; }
+        bool all_post = true;
+        for (int o = 0; o < prog->n_out; ++o) all_post &= E.post[prog->out_node[o]];
+        const int64_t size = E.dom[R - 2], N = E.dom[R - 1];
+        int64_t outer = 1;
+        for (int k = 0; k < R - 2; ++k) outer *= E.dom[k];
+        const int64_t units = outer * cdiv(N, 512);     // (at tiles of 64 lanes by 8 elements)
+        const int64_t want_units = (int64_t)ctx->n_cu * 4;
+        int64_t S = 0;
+        if (n_cred == 1 && all_post && R < DVM_MAX_RANK && units * 4 <= want_units && size >= 64) {
+            // the smallest divisor of the reduced extent that fills the machine and leaves every unit 16 rows or more
+            for (int64_t d = 2; d <= size / 16 && S == 0; ++d)
+                if (size % d == 0 && units * d >= want_units) S = d;
+            if (S == 0)
+                for (int64_t d = size / 16; d >= 2 && S == 0; --d)
+                    if (size % d == 0) S = d;
+        }
+        if (S >= 2 && (int64_t)DVM_WORKSPACE_BYTES + outer * S * N * 4 <= ctx->workspace_limit) {
+            const int st_split = encode_split_reduction(ctx, prog, in_shapes, out_layout, bytecode, cap, len, out_shapes, E.post, c, R, (int)S,
+                                                        size, E.dom);
+            // (the two parts may fit no common interpreter variant: the program then runs unsplit)
+            if (st_split != DVM_E_UNSUPPORTED && st_split != DVM_E_LIMIT) return st_split;
+            t_detail[0] = 0;
+        }
+    }
 
     // ---- 3. tensor accesses, collapse -------------------------------------------------------------
     E.n_acc = prog->n_in + prog->n_out;
@@ -1957,9 +2168,9 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         bool prolog_a_ends_on_record = sh[S_PROLOGA] == 0;
         bool epilog_on_record = sh[S_INNER] == 0 || sh[S_EPILOG] == 0;
         const uint32_t tbase = sh[S_TBASE], nt = sh[S_NTENS];
-        if ((uint64_t)tbase + nt > ntens - (has_ws ? 1u : 0u)) return bad("segment tensor range");
-        if (sh[S_FLAGS] & (SF_SYNC_WG | SF_SYNC_GRID)) {
-            if (kt != KT_STACK) return bad("synchronisation point outside a temporally stacked program");
+        if ((uint64_t)tbase + nt > ntens) return bad("segment tensor range");
+        if (sh[S_FLAGS] & (SF_SYNC_WG | SF_SYNC_GRID | SF_NEW_LAUNCH)) {
+            if (kt != KT_STACK || s == 0) return bad("synchronisation point outside a temporally stacked program, or on its first segment");
             if ((sh[S_FLAGS] & SF_SYNC_GRID) && !has_ws) return bad("grid-wide synchronisation without a workspace");
         }
         tiles_total += M;
@@ -2483,6 +2694,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
               (unsigned long long)((uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32)), sh[S_GEOM] & 0xFFFF,
               (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE],
               (sh[S_FLAGS] & SF_INTERLEAVED) ? "interleaved" : "blocked");
+        if (sh[S_FLAGS] & SF_NEW_LAUNCH) o.put("  ; a kernel launch of its own: starts when the segments before are complete\n");
         if (sh[S_FLAGS] & SF_SYNC_GRID) o.put("  ; waits until every workgroup has finished the segments before\n");
         else if (sh[S_FLAGS] & SF_SYNC_WG) o.put("  ; waits for this workgroup's own stores of the segments before\n");
         size_t pc = at + SH_WORDS;

@@ -46,7 +46,7 @@ struct KArgs {
     uint32_t n_tensors;
     uint32_t rotate;                    // 1: every segment deals its tiles out starting at the workgroup after the one the
                                         // segment before stopped at (short segments then do not all land on the first workgroups)
-    uint32_t pad;
+    uint32_t seg_first;                 // this launch runs segments seg_first .. nseg - 1
 };
 
 #define DI __device__ __forceinline__
@@ -1060,6 +1060,10 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
     for (uint32_t si = 0; si < args.nseg; ++si) {
         const uint32_t *sh = &code[seg];
         const uint32_t seg_words = sh[S_WORDS];
+        if (si < args.seg_first) {          // (a segment of an earlier launch of this program)
+            seg += seg_words;
+            continue;
+        }
         const uint32_t code_size = sh[S_CODESIZE];
         const uint32_t M = sh[S_NTILES];
         const uint32_t geom = sh[S_GEOM];
@@ -1085,34 +1089,44 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         // A segment that depends on earlier ones of this launch waits here (Section 5.1, temporal stacking of
         // dependent operators).  Release: this workgroup's stores are complete and visible to the device.
         if (sh[S_FLAGS] & (SF_SYNC_WG | SF_SYNC_GRID)) {
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+            // every wave: its own stores have left the wave (they sit in this compute unit's caches or beyond)
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __syncthreads();
             if (sh[S_FLAGS] & SF_SYNC_GRID) {
                 // every workgroup of the launch arrives once per such point; the grid was sized to be resident as a
                 // whole, so all arrive; should the machine be shared and some never start, the bounded wait ends
-                // with the status word set and this workgroup leaves the kernel
+                // with the status word set and this workgroup leaves the kernel.  One wave per workgroup makes
+                // the workgroup's stores visible to the device (the caches it has to write back and, afterwards,
+                // invalidate are shared by all its waves) and waits.
                 ++n_sync;
-                if (tid == 0) {
-                    GLOBAL_AS uint32_t *wsp = (GLOBAL_AS uint32_t *)args.ws;
-                    __hip_atomic_fetch_add(&wsp[WS_ARRIVED], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
-                    const uint32_t target = n_sync * ngrid;
+                if (wave == 0) {
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
                     uint32_t ok = 1;
-                    for (uint32_t spins = 0; __hip_atomic_load(&wsp[WS_ARRIVED], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target; ++spins) {
-                        if (spins >= args.spin_limit || __hip_atomic_load(&wsp[WS_STATUS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                            __hip_atomic_store(&wsp[WS_STATUS], WS_STATUS_GAVE_UP, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            ok = 0;
-                            break;
+                    if (tid == 0) {
+                        GLOBAL_AS uint32_t *wsp = (GLOBAL_AS uint32_t *)args.ws;
+                        __hip_atomic_fetch_add(&wsp[WS_ARRIVED], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+                        const uint32_t target = n_sync * ngrid;
+                        for (uint32_t spins = 0; __hip_atomic_load(&wsp[WS_ARRIVED], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) < target; ++spins) {
+                            if (spins >= args.spin_limit || __hip_atomic_load(&wsp[WS_STATUS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                                __hip_atomic_store(&wsp[WS_STATUS], WS_STATUS_GAVE_UP, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                                ok = 0;
+                                break;
+                            }
+                            __builtin_amdgcn_s_sleep(8);
                         }
-                        __builtin_amdgcn_s_sleep(16);
+                        red_lds[0][0] = __builtin_bit_cast(float, ok);
                     }
-                    red_lds[0][0] = __builtin_bit_cast(float, ok);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
                 }
                 __syncthreads();
                 const uint32_t go = __builtin_bit_cast(uint32_t, red_lds[0][0]);
                 __syncthreads();
                 if (go == 0) return;
+            } else {
+                // (lines of the buffer that this compute unit cached before the producer wrote them must go)
+                if (wave == 0) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                __syncthreads();
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
         }
 
         // Algorithm 2: m = ceil(M / N); this workgroup runs tiles [m*id, min(M, m*(id+1))).  In a
@@ -1874,13 +1888,16 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
     ka.ws = 0;
     for (uint32_t i = 0; i < ntens; ++i) {
         ka.tensors[i] = (uint64_t)(uintptr_t)tensors[i];
-        if (w[PH_WORDS_N + i * TT_WORDS + TT_INFO] & TI_WORKSPACE) ka.ws = ka.tensors[i];
+        if (w[PH_WORDS_N + i * TT_WORDS + TT_INFO] & TI_WORKSPACE) {
+            ka.ws = ka.tensors[i];                      // the synchronisation area
+            ka.tensors[i] += DVM_WORKSPACE_BYTES;       // segments that name the workspace as a tensor see its data area
+        }
     }
     ka.sets = 0;
     ka.n_sets = 1;
     ka.n_tensors = ntens;
     ka.rotate = 0;
-    ka.pad = 0;
+    ka.seg_first = 0;
     ka.nseg = w[PH_NSEG];
     ka.spin_limit = (uint32_t)dvm_ctx_sync_limit(ctx);
 
@@ -1958,10 +1975,21 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
         if ((uint64_t)grid > (uint64_t)per_cu * (uint64_t)n_cu) grid = (uint32_t)per_cu * (uint32_t)n_cu;
         hipLaunchKernelGGL(dvm_ws_clear, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (uint32_t *)(uintptr_t)ka.ws);
     }
-    e = (hipError_t)launch(grid, block, lds_bytes, hip_stream, &ka, nullptr);
-    if (e != hipSuccess) {
-        t_last_hip_error = (int)e;
-        return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
+    // one kernel launch per run of segments up to the next one that asks for a launch of its own
+    for (uint32_t first = 0; first < w[PH_NSEG];) {
+        uint32_t end = first + 1;
+        for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
+            if (s > first && s == end && !(w[at + S_FLAGS] & SF_NEW_LAUNCH)) ++end;
+            at += w[at + S_WORDS];
+        }
+        ka.seg_first = first;
+        ka.nseg = end;
+        e = (hipError_t)launch(grid, block, lds_bytes, hip_stream, &ka, nullptr);
+        if (e != hipSuccess) {
+            t_last_hip_error = (int)e;
+            return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
+        }
+        first = end;
     }
     return DVM_OK;
 }

@@ -391,3 +391,32 @@ def test_reduction_along_the_penultimate_axis_is_a_unit_loop_with_an_epilogue(ct
     # a 16-wave workgroup fits no variant that also holds a 32-element-per-lane part
     with pytest.raises(B.DvmError):
         B.dvm_stack([_encode(ctx, "colsum", [(4, 100, 300)]), _encode(ctx, "c2_rmsnorm", [(100, 4096), (4096,)])])
+
+
+def test_split_reduction_along_the_penultimate_axis_needs_a_context_that_allows_a_workspace(ctx):
+    from workloads.programs import _p
+    desc = _p("biasgrad", [("g", "f32")], [("s", "csum", ["g"], {})], [("s", "f32")])
+    shape = [B.make_shape((8192, 4096))]
+    plain = B.dvm_encode(ctx, B.Program(desc), shape)
+    assert plain.info().n_segments == 1 and not plain.needs_workspace()
+    ws = B.Context(-1)
+    ws.set_workspace_limit(4 << 20)
+    code = B.dvm_encode(ws, B.Program(desc), shape)
+    code.validate()
+    inf = code.info()
+    assert inf.n_segments == 2 and inf.n_tensors == 3 and code.needs_workspace()
+    txt = code.disasm()
+    assert "vstack.t" in txt and txt.count("a kernel launch of its own") == 1
+    m = re.search(r"segment 0: .* rows=(\d+) .* outer=\[(\d+),", txt)
+    rows_per_unit = int(m.group(2))
+    S = 8192 // rows_per_unit                           # (the first segment reduces S ranges of rows)
+    need, is_out, dt, al = code.tensor(2)
+    assert need == B.WORKSPACE_BYTES + S * 4096 * 4 and al == 256
+    assert f"rows={S} " in txt.split("segment 1:")[1].splitlines()[0]      # the second one combines the S partial results
+    assert code.raw == B.dvm_encode(ws, B.Program(desc), shape).raw
+    # a limit below what the split needs: the program runs unsplit
+    small = B.Context(-1)
+    small.set_workspace_limit(4096)
+    assert B.dvm_encode(small, B.Program(desc), shape).raw == plain.raw
+    # plenty of units already: no split either
+    assert not B.dvm_encode(ws, B.Program(desc), [B.make_shape((1024, 64, 1024))]).needs_workspace()
