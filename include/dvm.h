@@ -203,7 +203,12 @@ int  dvm_stack(const void *const *codes, const size_t *lens, int n,
  *   - if producer and consumer deal the same rows of that buffer to the same workgroups (same number of rows
  *     and rows per tile, whole rows per tile, the buffer addressed by plain row index in both), a workgroup only
  *     waits for its own earlier stores;
- *   - otherwise every workgroup of the launch waits until all have finished the earlier parts.  That needs
+ *   - otherwise, with order_by = DVM_ORDER_BY_LAUNCH, dvm_run starts a kernel launch of its own at that part (everything
+ *     before it is then complete and visible; no workspace, no wait on the device; on this hardware the cheaper of
+ *     the two: a few microseconds per boundary);
+ *   - or, with order_by = DVM_ORDER_IN_KERNEL, the whole program stays ONE kernel launch and every workgroup waits
+ *     until all have finished the earlier parts (its cost grows with the number of workgroups: each makes its
+ *     stores visible beyond its own second-level cache).  That needs
  *     DVM_WORKSPACE_BYTES of device memory the caller lends to the launch: the stacked program then lists one
  *     more tensor, the workspace (dvm_code_tensor reports it with is_output = 2), and the caller passes its
  *     device pointer (256-byte aligned) as the LAST entry of tensors[].  dvm_run clears it before the launch.
@@ -212,7 +217,8 @@ int  dvm_stack(const void *const *codes, const size_t *lens, int n,
  *     others at their next wait; dvm_workspace_status reads the word back.
  * Parts must be encoded programs or independent stacks, not dependent stacks themselves. */
 #define DVM_WORKSPACE_BYTES 256
-int  dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as,
+typedef enum dvm_order_by { DVM_ORDER_IN_KERNEL = 0, DVM_ORDER_BY_LAUNCH = 1 } dvm_order_by;
+int  dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as, int order_by,
                          void *out, size_t cap, size_t *len);
 /* Upper bound on the polls (about a microsecond each) a workgroup spends at a grid-wide synchronisation point
  * before it gives up; the default is about one million.  polls < 1 is an error. */
@@ -238,9 +244,11 @@ int  dvm_stack_spatial(const void *const *codes, const size_t *lens, int n,
  * read, a stream synchronisation) -- the pieces are stacked into ONE launch (dvm_stack_dependent: a later
  * piece waits for the earlier ones whose results it reads).  A result the caller released before the
  * buffer ran, and that no later piece reads, is a pure intermediate and is never written to memory.
- * Pieces that wait for each other grid-wide need the workspace of dvm_fuser_set_workspace; without one,
- * or when the pieces do not fit one launch (tensor table, bytecode size, interpreter variant), every
- * piece is launched on its own, in order.
+ * A piece that needs all of an earlier piece (not only what its own workgroup wrote) starts a kernel launch of
+ * its own inside that one dvm_run call (DVM_ORDER_BY_LAUNCH), or, when dvm_fuser_set_workspace has lent a workspace,
+ * waits inside the single kernel launch (DVM_ORDER_IN_KERNEL).  When the pieces do not fit one program (tensor
+ * table, bytecode size, interpreter variant), every piece is run on its own, in order.  dvm_fuser_stats counts
+ * kernel launches.
  *
  * All calls are host calls.  The fuser owns no device memory: every tensor and every result buffer
  * is the caller's (device pointers), and must stay valid until the buffer that uses it has run.
@@ -290,6 +298,8 @@ typedef struct dvm_code_info {
     int32_t  n_instructions;   /* over all segments                                               */
     int64_t  n_tiles;          /* over all segments (the M of Algorithm 2, summed)                */
     int64_t  code_bytes;       /* over all segments (CodeSize, summed)                            */
+    int32_t  n_launches;       /* kernel launches dvm_run issues for this bytecode (1 unless parts ask for their own) */
+    int32_t  reserved;
 } dvm_code_info;
 int  dvm_code_info_get(const void *bytecode, size_t len, dvm_code_info *info);
 /* Minimum size in bytes of the buffer behind tensors[index], and whether it is written (*is_output: 0 an

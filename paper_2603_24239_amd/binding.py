@@ -43,7 +43,8 @@ class dvm_shape(C.Structure):
 class dvm_code_info(C.Structure):
     _fields_ = [("kernel_type", C.c_int32), ("n_segments", C.c_int32), ("n_tensors", C.c_int32),
                 ("grid", C.c_int32), ("block", C.c_int32), ("variant_k", C.c_int32), ("variant_nr", C.c_int32),
-                ("n_instructions", C.c_int32), ("n_tiles", C.c_int64), ("code_bytes", C.c_int64)]
+                ("n_instructions", C.c_int32), ("n_tiles", C.c_int64), ("code_bytes", C.c_int64),
+                ("n_launches", C.c_int32), ("reserved", C.c_int32)]
 
 
 class DvmError(RuntimeError):
@@ -90,7 +91,7 @@ def load() -> C.CDLL:
         "dvm_encode": (i, [vp, vp, P(dvm_shape), i, P(dvm_shape), vp, sz, P(sz), P(dvm_shape)]),
         "dvm_stack": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
         "dvm_stack_spatial": (i, [P(vp), P(sz), i, vp, sz, P(sz)]),
-        "dvm_stack_dependent": (i, [P(vp), P(sz), i, P(i), i, vp, sz, P(sz)]),
+        "dvm_stack_dependent": (i, [P(vp), P(sz), i, P(i), i, i, vp, sz, P(sz)]),
         "dvm_ctx_set_sync_limit": (i, [vp, C.c_int64]),
         "dvm_workspace_status": (i, [vp, vp, P(i)]),
         "dvm_validate": (i, [vp, sz]),
@@ -330,7 +331,7 @@ def dvm_stack_spatial(codes: Sequence[Bytecode]) -> Bytecode:
     return dvm_stack(codes, spatial=True)
 
 
-def dvm_stack_dependent(codes: Sequence[Bytecode], same_as: Sequence[int]) -> Bytecode:
+def dvm_stack_dependent(codes: Sequence[Bytecode], same_as: Sequence[int], order_by: str = "kernel") -> Bytecode:
     """same_as: one entry per tensor of the launch (part after part), -1 or the index of an earlier entry that is
     the same buffer.  If the result lists a workspace (its last tensor), pass WORKSPACE_BYTES of device memory for it."""
     lib = load()
@@ -340,7 +341,8 @@ def dvm_stack_dependent(codes: Sequence[Bytecode], same_as: Sequence[int]) -> By
     sa = (C.c_int * max(len(same_as), 1))(*same_as)
     buf = C.create_string_buffer(_ENC_CAP)
     ln = C.c_size_t()
-    _check(lib.dvm_stack_dependent(ptrs, lens, n, sa, len(same_as), buf, _ENC_CAP, C.byref(ln)), "dvm_stack_dependent")
+    _check(lib.dvm_stack_dependent(ptrs, lens, n, sa, len(same_as), {"kernel": 0, "launch": 1}[order_by], buf, _ENC_CAP, C.byref(ln)),
+           "dvm_stack_dependent")
     shapes: List[Tuple[int, ...]] = []
     for c in codes:
         shapes.extend(c.out_shapes)

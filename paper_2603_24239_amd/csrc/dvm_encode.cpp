@@ -768,7 +768,7 @@ uint32_t bits_f32(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
 }  // namespace
 
 static int stack_impl(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as, void *out, size_t cap,
-                      size_t *len, bool spatial);
+                      size_t *len, bool spatial, bool by_launch = false);
 
 // dvm_encode of a program whose single reduction along the penultimate axis (node c, over `size` rows) is split S ways.
 // Part 1: the ops before the reduction and the reduction itself over tensors seen as [.., S, size/S, N]: its output,
@@ -2328,8 +2328,10 @@ extern "C" int dvm_code_info_get(const void *bytecode, size_t len, dvm_code_info
     info->variant_k = (int32_t)(w[PH_VARIANT] & 0xFF);
     info->variant_nr = (int32_t)((w[PH_VARIANT] >> 8) & 0xFF);
     size_t at = PH_WORDS_N + (size_t)w[PH_NTENS] * TT_WORDS;
+    info->n_launches = 1;
     for (uint32_t s = 0; s < w[PH_NSEG]; ++s) {
         const uint32_t *sh = w + at;
+        if (sh[S_FLAGS] & SF_NEW_LAUNCH) info->n_launches++;
         info->n_tiles += sh[S_NTILES];
         info->code_bytes += (int64_t)sh[S_CODESIZE] * 4;
         size_t pc = at + SH_WORDS;
@@ -2391,7 +2393,7 @@ bool same_rows_per_workgroup(const uint32_t *A, uint32_t ta, const uint32_t *B, 
 }  // namespace
 
 static int stack_impl(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as, void *out, size_t cap,
-                      size_t *len, bool spatial) {
+                      size_t *len, bool spatial, bool by_launch) {
     if (!codes || !lens || !len || n < 1) return dvm_set_error(DVM_E_ARGS, "dvm_stack: bad argument");
     size_t seg_words = 0;
     uint32_t ntens = 0, nseg = 0, block = 0, K = 0, NR = 0;
@@ -2526,12 +2528,16 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, const
                 const uint32_t *prod = seg_of_part[part_of[u]];
                 const bool aligned = nsegs_of_part[pi] == 1 && nsegs_of_part[part_of[u]] == 1 &&
                                      same_rows_per_workgroup(prod, local_of[u], cons, local_of[t]);
-                cons[S_FLAGS] |= aligned ? SF_SYNC_WG : SF_SYNC_GRID;
+                cons[S_FLAGS] |= aligned ? SF_SYNC_WG : (by_launch ? SF_NEW_LAUNCH : SF_SYNC_GRID);
             }
         }
         for (int i = 0; i < n; ++i) {
             uint32_t *sh = seg_of_part[i];
             if (sh[S_FLAGS] & SF_SYNC_GRID) { sh[S_FLAGS] &= ~SF_SYNC_WG; any_grid = true; }
+            if (sh[S_FLAGS] & SF_NEW_LAUNCH) sh[S_FLAGS] &= ~SF_SYNC_WG;
+            // (a segment that only waits for its own workgroup relies on the producer having run in the same launch
+            // with the same tiles per workgroup: true across a launch boundary too -- the tiles are dealt out alike --
+            // and everything before a boundary is complete anyway)
         }
         if (any_grid) {
             uint32_t *te = tt0 + ntens_parts * TT_WORDS;
@@ -2618,10 +2624,11 @@ extern "C" int dvm_stack(const void *const *codes, const size_t *lens, int n, vo
     return stack_impl(codes, lens, n, nullptr, 0, out, cap, len, false);
 }
 
-extern "C" int dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as,
+extern "C" int dvm_stack_dependent(const void *const *codes, const size_t *lens, int n, const int *same_as, int n_same_as, int order_by,
                                    void *out, size_t cap, size_t *len) {
     if (!same_as) return dvm_set_error(DVM_E_ARGS, "dvm_stack_dependent: null same_as");
-    return stack_impl(codes, lens, n, same_as, n_same_as, out, cap, len, false);
+    if (order_by != DVM_ORDER_IN_KERNEL && order_by != DVM_ORDER_BY_LAUNCH) return dvm_set_error(DVM_E_ARGS, "dvm_stack_dependent: order_by");
+    return stack_impl(codes, lens, n, same_as, n_same_as, out, cap, len, false, order_by == DVM_ORDER_BY_LAUNCH);
 }
 
 extern "C" int dvm_stack_spatial(const void *const *codes, const size_t *lens, int n, void *out, size_t cap, size_t *len) {

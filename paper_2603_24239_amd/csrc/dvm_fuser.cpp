@@ -219,7 +219,7 @@ int run_stacked(dvm_fuser *f) {
     size_t lens[MAX_PIECES];
     void *tensors[DVM_MAX_TENSORS];
     int values[DVM_MAX_TENSORS], same_as[DVM_MAX_TENSORS];
-    int n_parts = 0, n_t = 0;
+    int n_parts = 0, n_t = 0, n_launches = 1;
     for (int k = 0; k < f->n_pieces; ++k) {
         Piece &pc = pcs[n_parts];
         int st = encode_range(f, f->piece_lo[k], f->piece_lo[k + 1], f->piece_code[n_parts], PIECE_CODE_CAP, &pc);
@@ -244,7 +244,8 @@ int run_stacked(dvm_fuser *f) {
             memcpy(f->code, codes[0], lens[0]);
             f->code_len = lens[0];
         } else {
-            st = dvm_stack_dependent(codes, lens, n_parts, same_as, n_t, f->code, sizeof(f->code), &f->code_len);
+            st = dvm_stack_dependent(codes, lens, n_parts, same_as, n_t, f->workspace ? DVM_ORDER_IN_KERNEL : DVM_ORDER_BY_LAUNCH, f->code,
+                                     sizeof(f->code), &f->code_len);
             if (st == DVM_E_BUFSZ) st = dvm_set_error(DVM_E_LIMIT, "dvm_fuser: the stacked bytecode exceeds the fuser's buffer");
             if (st != DVM_OK) return st;
             int is_ws = 0;
@@ -252,16 +253,14 @@ int run_stacked(dvm_fuser *f) {
             st = dvm_code_info_get(f->code, f->code_len, &info);
             if (st == DVM_OK) st = dvm_code_tensor(f->code, f->code_len, info.n_tensors - 1, nullptr, &is_ws, nullptr, nullptr);
             if (st != DVM_OK) return st;
-            if (is_ws == 2) {
-                if (!f->workspace) return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_fuser: the pieces need a grid-wide wait and the fuser has no workspace");
-                tensors[n_t++] = f->workspace;
-            }
+            if (is_ws == 2) tensors[n_t++] = f->workspace;
+            n_launches = info.n_launches;
         }
         if (dvm_ctx_device(f->ctx) >= 0) {
             st = dvm_run(f->ctx, f->code, f->code_len, tensors, n_t, f->stream);
             if (st != DVM_OK) return st;
         }
-        ++f->stat_launches;
+        f->stat_launches += n_launches;
     }
     for (int k = 0; k < f->n_pieces; ++k) settle(f, f->piece_lo[k], f->piece_lo[k + 1]);
     return DVM_OK;

@@ -62,7 +62,7 @@ def test_a_piece_that_reads_an_earlier_piece_waits_for_it():
     assert "same_buffer_as=1" in txt            # t: output of piece 0 (tensor 1), input of piece 2
 
 
-def test_pieces_that_need_the_grid_wide_wait_take_the_workspace_or_run_one_by_one():
+def test_pieces_that_need_all_of_an_earlier_piece_wait_in_the_kernel_or_start_a_launch():
     def issue(f):
         x = f.tensor(0x10000, "f32", B.make_shape((64, 1024)))
         w = f.tensor(0x20000, "f32", B.make_shape((5, 77)))
@@ -74,7 +74,10 @@ def test_pieces_that_need_the_grid_wide_wait_take_the_workspace_or_run_one_by_on
 
     f = B.Fuser(_ctx())
     issue(f)
-    assert f.stats()["launches"] == 3           # no workspace: every piece its own launch, in order
+    # no workspace: still one program, whose third piece starts a kernel launch of its own behind the first two
+    assert f.stats()["launches"] == 2 and f.stats()["flushes"] == 1
+    txt = f.last_code().disasm()
+    assert txt.count("segment ") == 3 and txt.count("a kernel launch of its own") == 1 and "workspace" not in txt
     f = B.Fuser(_ctx())
     f.set_workspace(0x7000000, B.WORKSPACE_BYTES)
     issue(f)

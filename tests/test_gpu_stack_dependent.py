@@ -39,7 +39,7 @@ def dep_ctx():
     return _ctx
 
 
-def run_chain(parts, one_launch=True, ctx=None):
+def run_chain(parts, one_launch=True, ctx=None, order_by="kernel"):
     """parts: list of (desc, {input name: tensor}, {output name: tensor} or None for fresh zeroed outputs).  An input
     at the address of an earlier part's output is that buffer.  Returns (outputs per part, the stacked bytecode)."""
     ctx = ctx or dep_ctx()
@@ -64,7 +64,7 @@ def run_chain(parts, one_launch=True, ctx=None):
     flat = [t for ts in tensors for t in ts]
     # entries with the same address are the same buffer (the parts here never share part of a buffer only)
     same_as = [next((j for j in range(i) if flat[j].data_ptr() == t.data_ptr()), -1) for i, t in enumerate(flat)]
-    st = B.dvm_stack_dependent(codes, same_as)
+    st = B.dvm_stack_dependent(codes, same_as, order_by)
     st.validate()
     ptrs = [t.data_ptr() for t in flat]
     if st.needs_workspace():
@@ -87,6 +87,13 @@ def check_chain(build, what, expect):
         assert txt.count(needle) == count, (what, needle, txt)
     parts2 = build()
     alone, _ = run_chain(parts2, one_launch=False)
+    # the same program with launch boundaries instead of waits on the device
+    parts3 = build()
+    by_launch, st3 = run_chain(parts3, order_by="launch")
+    assert not st3.needs_workspace() and st3.info().n_launches == 1 + txt.count(GRID)
+    for (desc, _, _), g, b3 in zip(parts, got, by_launch):
+        for n, _dt in desc.outputs:
+            assert torch.equal(_bits(g[n]), _bits(b3[n])), f"{what}: {desc.name}:{n} differs between the two ways of ordering the parts"
     for (desc, ins, _), g, a in zip(parts, got, alone):
         rounded, exact = H.run_oracle(desc, ins)       # (ins hold what the stacked launch left in memory)
         for n, dt in desc.outputs:

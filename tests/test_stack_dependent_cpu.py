@@ -129,3 +129,20 @@ def test_validator_rejects_tampered_synchronisation(ctx):
     words_a[flags_at] |= 16
     with pytest.raises(B.DvmError):
         B.Bytecode(struct.pack("<%dI" % len(words_a), *words_a), []).validate()
+
+
+def test_order_by_launch_needs_no_workspace(ctx):
+    T = 3000
+    a = _rmsnorm(ctx, T)
+    add = single_op_program("add", 2, "bf16")
+    b = B.dvm_encode(ctx, B.Program(add), [B.make_shape((T * 4, 1024)), B.make_shape((T * 4, 1024))])
+    st = B.dvm_stack_dependent([a, b], [-1, -1, -1, 2, -1, -1], order_by="launch")
+    st.validate()
+    txt = st.disasm()
+    assert txt.count("a kernel launch of its own") == 1 and "waits until" not in txt
+    assert not st.needs_workspace() and st.info().n_tensors == 6 and st.info().n_launches == 2
+    # a consumer over the same rows still only waits for its own workgroup, inside the launch
+    soft = _p("soft_bf16", [("z", "bf16")], [("y", "softmax", ["z"], {})], [("y", "bf16")])
+    c = B.dvm_encode(ctx, B.Program(soft), [B.make_shape((T, 4096))])
+    st = B.dvm_stack_dependent([a, c], [-1, -1, -1, 2, -1], order_by="launch")
+    assert "waits for this workgroup's own stores" in st.disasm() and st.info().n_launches == 1
