@@ -96,6 +96,9 @@ constexpr uint32_t SF_CSTREAM = 4u;     // reducing segment whose per-row part i
 constexpr uint32_t SF_INTERLEAVED = 8u; // workgroup id runs tiles id, id + N, id + 2N, ... instead of Algorithm 2's blocked range
 // A stacked meta-kernel that reads what an earlier meta-kernel of the same launch wrote (Section 5.1: temporal
 // stacking does not require independent operators) starts behind a synchronisation point:
+constexpr uint32_t SF_LONGROW = 256u;    // rows longer than a tile with reductions along them: S_NTILES counts rows, S_NCT the column tiles
+                                         // of a row, S_NCTSH the reductions in the body; the workgroup passes over the row once
+                                         // per reduction (accumulating it tile after tile) and once more for the stores
 constexpr uint32_t SF_NEW_LAUNCH = 128u; // dvm_run starts a kernel launch of its own at this segment: everything before it is complete and
                                          // visible (the cheapest device-wide order on a chip whose second-level caches are
                                          // not coherent with each other; used where the data handed over is small)

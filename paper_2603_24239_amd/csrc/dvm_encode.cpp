@@ -588,6 +588,7 @@ struct Enc {
     int regs[NR_MAX], sregs[NS];
     int nr_limit;           // tile registers the program may use
     bool reload_inputs;     // never keep an input tile in a register: load it again at every use
+    bool keep_sregs;        // never give a row-scalar register a second value (rows longer than a tile: the body runs once per pass)
     int lds_of[MAX_NODES];  // LDS image (slot) of a row-invariant input that only multiplies or is added, or -1
     int n_lds;
     int lds_node[LDS_SLOTS];
@@ -679,7 +680,7 @@ struct Enc {
     }
     void release(int node) {            // called when the last use of `node` is gone
         if (reg_of[node] >= 0) { regs[reg_of[node]] = -1; reg_of[node] = -1; }
-        if (sreg_of[node] >= 0) { sregs[sreg_of[node]] = -1; sreg_of[node] = -1; }
+        if (sreg_of[node] >= 0 && !keep_sregs) { sregs[sreg_of[node]] = -1; sreg_of[node] = -1; }
         if (in_acc == node) in_acc = -1;
     }
     void use(int node) {
@@ -1524,7 +1525,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                             const int st = E.alloc_sreg(-1);
                             E.emit(I_SOP, (uint8_t)st, (uint8_t)sb, -1, 0.0f, (uint8_t)(SOP_UNARY + U_RCP), 0, 0);
                             E.emit(I_BIN, (uint8_t)(SRC_S0 + st), (uint8_t)B_MUL);
-                            E.sregs[st] = -1;
+                            if (!E.keep_sregs) E.sregs[st] = -1;
                         }
                     } else {
                         E.emit(I_BIN, (uint8_t)(SRC_S0 + sb), (uint8_t)op);
@@ -1607,6 +1608,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     // again with as many pinned operands as keep the program within four tile registers
     E.nr_limit = ctx->max_nr < NR_MAX ? ctx->max_nr : NR_MAX;
     E.reload_inputs = false;
+    E.keep_sregs = false;
     linearize(0);
     if (E.err) {                // too many live tiles: trade registers for repeated (cached) loads
         E.err = nullptr;
@@ -1691,6 +1693,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     const int need_nr = E.nr_used;
     const int64_t Cr = cdiv(E.D0 > 0 ? E.D0 : 1, V);
     int vi = -1;                    // chosen variant
+    bool long_row = false;          // rows longer than a tile, with reductions along them
     uint32_t G = 1, RP = 1, nvec = 1, nct = 1, TC = 0;
     auto find_variant = [&](int K) {
         int best = -1;
@@ -1794,8 +1797,33 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 if (v >= 0 && cdiv(Cr, K / V) <= VARIANTS[v].max_threads) pick = v;
             }
         }
-        if (pick < 0) {
-            if (E.has_red || has_rows_output) return dvm_set_error(DVM_E_UNSUPPORTED, "row too long for a register-resident reduction");
+        if (pick < 0 && (E.has_red || has_rows_output)) {
+            // Rows longer than the widest tile: the row is cut into column tiles and the workgroup passes over it
+            // once per reduction, then once more for the rest (SF_LONGROW).  The body must be a pure function of the
+            // loads and of the reductions before: no pinned operands, no row-scalar register used twice.
+            if (has_rows_output && !E.has_red) return dvm_set_error(DVM_E_UNSUPPORTED, "row too long for a row-value output without a reduction");
+            E.err = nullptr;
+            E.reload_inputs = false;
+            E.keep_sregs = true;
+            linearize(0);
+            if (E.err) { E.err = nullptr; E.reload_inputs = true; linearize(0); }
+            if (E.err) return dvm_set_error(E.err_code, E.err);
+            int v = -1;
+            for (int i = 3; i >= 0 && v < 0; --i) {             // the widest tile register first
+                if ((uint32_t)ks[i] < V || ks[i] > ctx->max_k) continue;
+                for (int j = 0; j < N_VARIANTS; ++j)
+                    if (VARIANTS[j].K == ks[i] && VARIANTS[j].NR >= E.nr_used && VARIANTS[j].NR <= ctx->max_nr && (v < 0 || VARIANTS[j].NR < VARIANTS[v].NR)) v = j;
+            }
+            if (v < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
+            vi = v;
+            long_row = true;
+            const Variant &vr = VARIANTS[vi];
+            G = (uint32_t)(vr.max_threads < 512 ? vr.max_threads : 512);
+            nvec = (uint32_t)(vr.K / V);
+            TC = G * nvec * V;
+            nct = (uint32_t)cdiv(E.D0, TC);
+            RP = 1;
+        } else if (pick < 0) {
             column_mode = true;
         } else {
             vi = pick;
@@ -1865,7 +1893,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     }
     const Variant &vr = VARIANTS[vi];
     const uint32_t threads = G * RP;
-    const int64_t M64 = total == 0 ? 0 : (E.has_cred ? cred_outer * nct : cdiv(E.nrows, RP) * nct);
+    const int64_t M64 = total == 0 ? 0 : (E.has_cred ? cred_outer * nct : (long_row ? E.nrows : cdiv(E.nrows, RP) * nct));
     if (M64 >= (1ll << 31)) return dvm_set_error(DVM_E_LIMIT, "more than 2^31 tiles");
     const int64_t Nslots = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
     const int64_t Ngrid = Nslots * ctx->dbg_grid_x;
@@ -1930,7 +1958,13 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             magic_u32((uint32_t)E.Dg[2], &sh[S_M2], &sh[S_SH2]);
         }
     }
-    if (nct > 1) magic_u32(nct, &sh[S_NCTM], &sh[S_NCTSH]);
+    if (long_row) {
+        uint32_t n_red = 0;
+        for (int i = 0; i < E.n_ai; ++i) n_red += E.ai[i].op == I_RED;
+        sh[S_NCTSH] = n_red;
+    } else if (nct > 1) {
+        magic_u32(nct, &sh[S_NCTM], &sh[S_NCTSH]);
+    }
     sh[S_TBASE] = 0;
     sh[S_NTENS] = (uint32_t)E.n_acc;
     // DVM_ASSIGN_AUTO: round-robin, except for a program that keeps an operand pinned while consecutive rows share it
@@ -1941,7 +1975,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (ctx->assignment == DVM_ASSIGN_AUTO)
         interleaved = !(E.n_prolog > E.n_prolog_a && (E.D0 * (int64_t)(any_bf16_full ? 2 : 4)) % 128 != 0);
     sh[S_FLAGS] = (wgsync ? SF_WGSYNC : 0) | (E.has_cred && E.cstream ? SF_CSTREAM : 0) |
-                  (interleaved ? SF_INTERLEAVED : 0) | (E.n_lds > 0 ? SF_LDS : 0);
+                  (interleaved ? SF_INTERLEAVED : 0) | (E.n_lds > 0 ? SF_LDS : 0) | (long_row ? SF_LONGROW : 0);
     sh[S_PROLOG] = (uint32_t)(E.n_prolog == E.n_ai ? body_words : prolog_words);
     sh[S_PROLOGA] = (uint32_t)(E.n_prolog_a == E.n_ai ? body_words : prolog_a_words);
     if (E.has_cred) {
@@ -1963,7 +1997,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 if (x.op == I_LOAD) {
                     bool once = !A.rows;        // read exactly once: no outer dim is broadcast
                     for (int g = 1; g < ng; ++g) once &= !(E.Dg[g] > 1 && A.s[g] == 0);
-                    if (once) mflags |= MF_STREAM;
+                    if (once && !long_row) mflags |= MF_STREAM;     // (a long row is read once per pass: keep it cached)
                 }
                 *b++ = (uint32_t)x.tensor | ((uint32_t)A.dtype << 8) | (mflags << 16);
                 put_i64(A.s[1]);
@@ -2122,7 +2156,9 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
         if (M != 0) {
             if ((uint64_t)nct * TC < D0) return bad("column tiles do not cover the row");
             if (nct > 1 && (uint64_t)(nct - 1) * TC >= D0) return bad("an empty column tile");
-            if (sh[S_INNER] == 0 && M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
+            if (sh[S_INNER] == 0 && !(sh[S_FLAGS] & SF_LONGROW) && M != ((nrows + RP - 1) / RP) * nct) return bad("tile count");
+            if ((sh[S_FLAGS] & SF_LONGROW) && (M != nrows || RP != 1 || sh[S_INNER] != 0 || sh[S_PROLOG] != 0 || nct < 2 || G < 64))
+                return bad("geometry of a segment over rows longer than a tile");
         }
         if (sh[S_INNER] != 0) {        // units of (outer index, column tile), `size` rows each
             if (!vr->cred) return bad("interpreter variant does not run reductions along the penultimate axis");
@@ -2145,11 +2181,12 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             magic_u32(sh[S_D2], &m, &sft);
             if (m != sh[S_M2] || sft != sh[S_SH2]) return bad("division constants of outer dim 2");
         }
-        if (nct > 1) {
+        if (nct > 1 && !(sh[S_FLAGS] & SF_LONGROW)) {
             uint32_t m, sft;
             magic_u32(nct, &m, &sft);
             if (m != sh[S_NCTM] || sft != sh[S_NCTSH]) return bad("division constants of the column tiles");
         }
+        uint32_t n_red_seen = 0;
         if (sh[S_PROLOG] > cs || (sh[S_PROLOG] & 3) || (sh[S_PROLOG] != 0 && nct != 1)) return bad("prologue length");
         if (kt == KT_STACK_SPATIAL) {
             if (sh[S_NWG] == 0 || sh[S_WG0] != wg_next) return bad("workgroup share of a spatially stacked segment");
@@ -2235,6 +2272,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
                     if (w[pc + 1] > (uint32_t)NS || (w[pc + 1] == 0 && bb == FMA_NO_ADDEND)) return bad("fused multiply-add scalar");
                     break;
                 case I_RED:
+                    ++n_red_seen;
                     if (l != LEN_REC || !sreg_ok(a) || bb >= R_COUNT) return bad("reduction");
                     if (w[pc + 1] >= U_COUNT) return bad("reduction post op");
                     break;
@@ -2304,6 +2342,7 @@ extern "C" int dvm_validate(const void *bytecode, size_t len) {
             pc += l;
         }
         if (((sh[S_FLAGS] & SF_LDS) != 0) != (lds_seen != 0)) return bad("LDS flag does not match the prologue");
+        if ((sh[S_FLAGS] & SF_LONGROW) && (sh[S_NCTSH] != n_red_seen || n_red_seen == 0)) return bad("reduction count of a segment over rows longer than a tile");
         if (!prolog_ends_on_record || !prolog_a_ends_on_record) return bad("prologue does not end on a record boundary");
         if (!epilog_on_record) return bad("epilogue does not start on a record boundary");
         at += sw;
@@ -2701,6 +2740,7 @@ extern "C" int dvm_disasm(const void *bytecode, size_t len, char *txt, size_t ca
               (unsigned long long)((uint64_t)sh[S_D0LO] | ((uint64_t)sh[S_D0HI] << 32)), sh[S_GEOM] & 0xFFFF,
               (sh[S_GEOM] >> 16) & 0xFF, sh[S_GEOM] >> 24, sh[S_RP] & 0xFFFF, sh[S_NCT], sh[S_TC], sh[S_D1], sh[S_D2], sh[S_TBASE],
               (sh[S_FLAGS] & SF_INTERLEAVED) ? "interleaved" : "blocked");
+        if (sh[S_FLAGS] & SF_LONGROW) o.put("  ; rows longer than a tile: %u passes over a row, %u column tiles each\n", sh[S_NCTSH] + 1, sh[S_NCT]);
         if (sh[S_FLAGS] & SF_NEW_LAUNCH) o.put("  ; a kernel launch of its own: starts when the segments before are complete\n");
         if (sh[S_FLAGS] & SF_SYNC_GRID) o.put("  ; waits until every workgroup has finished the segments before\n");
         else if (sh[S_FLAGS] & SF_SYNC_WG) o.put("  ; waits for this workgroup's own stores of the segments before\n");

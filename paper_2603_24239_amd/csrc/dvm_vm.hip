@@ -781,6 +781,22 @@ template <int K, uint32_t R> DI float lane_reduce(const Tile<K> &a, const Geo &g
     return v;
 }
 
+// the two halves apart (a row longer than a tile is reduced tile after tile within the lane, then once across the lanes)
+template <int K> DI float lane_reduce_dispatch(const Tile<K> &a, const Geo &g, uint32_t V, uint32_t kind) {
+    switch (kind) {
+        case R_MAX: return lane_reduce<K, R_MAX>(a, g, V);
+        case R_MIN: return lane_reduce<K, R_MIN>(a, g, V);
+        case R_SUMSQ: return lane_reduce<K, R_SUMSQ>(a, g, V);
+        default: return lane_reduce<K, R_SUM>(a, g, V);
+    }
+}
+DI float wave_allreduce_dispatch(float v, uint32_t kind, uint32_t width) {
+    switch (kind) {
+        case R_MAX: return wave_allreduce<R_MAX>(v, width);
+        case R_MIN: return wave_allreduce<R_MIN>(v, width);
+        default: return wave_allreduce<R_SUM>(v, width);
+    }
+}
 template <int K> DI float reduce_dispatch(const Tile<K> &a, const Geo &g, uint32_t V, uint32_t kind, uint32_t width) {
     switch (kind) {
         case R_MAX: return wave_allreduce<R_MAX>(lane_reduce<K, R_MAX>(a, g, V), width);
@@ -1165,6 +1181,14 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
         // the workgroup walks the `inner` rows of a unit RP at a time, one row per wave and step (rin),
         // accumulating in tile registers, and runs the epilogue records after the last step.  Other
         // segments: one step per tile.
+        // A segment over rows longer than a tile (SF_LONGROW) counts rows in M; the workgroup passes over a row once per
+        // reduction and once more for the rest (lr_phase), each pass column tile after column tile (lr_c): a pass runs
+        // the records from the start of the body up to its reduction, skipping the reductions whose value is final and
+        // every store; the last pass runs to the end and stores.
+        const bool longrow = (sh[S_FLAGS] & SF_LONGROW) != 0;
+        const uint32_t n_red = longrow ? sh[S_NCTSH] : 0u;
+        uint32_t lr_phase = 0, lr_c = 0;
+        float racc = 0.0f;                  // the lane's part of the reduction of the current pass
         uint32_t rin = 0;
         for (uint32_t tile = t_lo; tile < t_hi;) {
             const uint32_t *shl = sh;
@@ -1186,7 +1210,9 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             } else {
                 // tile prologue: where this tile sits, which of its lanes and chunks are valid
                 uint32_t tile_r = tile;
-                if (nct > 1) {          // (a single column tile was placed once, before the loop)
+                if (longrow) {
+                    tile_cols(gt, sh, lr_c, G, V);
+                } else if (nct > 1) {   // (a single column tile was placed once, before the loop)
                     tile_r = sdiv_u(tile, sh[S_NCTM], sh[S_NCTSH]);
                     tile_cols(gt, sh, tile - tile_r * nct, G, V);
                 }
@@ -1204,6 +1230,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             // (its second part runs again when the second outer index of the tile's first or last row
             // differs from that of the previous tile: an operand pinned there varies with that index only)
             uint32_t first = body;
+            uint32_t red_idx = 0;           // reductions met so far in this pass over the records
             if (tile != t_lo || rin != 0) {
                 first = body + shl[S_PROLOG];
                 if (shl[S_PROLOGA] != shl[S_PROLOG]) {
@@ -1367,6 +1394,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                     }
                     case I_STORE:
                     case I_VSTORE: {
+                        if (longrow && lr_phase != n_red) break;    // (only the last pass over a long row stores)
                         if constexpr (WIDE) {
                             if (gt.part_slot == ~0u && gt.ragged == 0 && gt.ncols >= V) {   // a full tile: plain stores
                                 if (wd.rowok) {
@@ -1427,6 +1455,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         break;
                     }
                     case I_STORES: {
+                        if (longrow && (lr_phase != n_red || lr_c != 0)) break;     // (once per row, in its last pass)
                         DVM_GEO()
                         const uint32_t w1 = cw1;
                         const uint32_t ti = w1 & 0xFF, dt = (w1 >> 8) & 0xFF;
@@ -1589,8 +1618,23 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
                         break;
                     }
                     case I_RED: {
+                        if (longrow) {
+                            const uint32_t mine = red_idx++;
+                            if (mine < lr_phase) break;         // its value is final: S[a] holds it
+                        }
                         DVM_GEO()
-                        float v = reduce_dispatch<K>(acc, g, V, b, width);
+                        float v;
+                        if (longrow) {
+                            // this pass's reduction: the lane's part of this column tile joins those of the tiles before;
+                            // after the row's last tile the lanes (and waves) are combined as for a short row
+                            const float part = lane_reduce_dispatch<K>(acc, g, V, b);
+                            racc = lr_c == 0 ? part : (b == R_MAX ? f_maxp(racc, part) : (b == R_MIN ? f_minp(racc, part) : racc + part));
+                            pcb = this_end * 4;                 // the pass ends here
+                            if (lr_c + 1 < nct) break;
+                            v = wave_allreduce_dispatch(racc, b, width);
+                        } else {
+                            v = reduce_dispatch<K>(acc, g, V, b, width);
+                        }
                         if (gw > 1) {
                             // a row spans gw waves: exchange the per-wave results through LDS.  Two
                             // buffers alternate, so one barrier per reduction is enough.
@@ -1630,6 +1674,11 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
             if constexpr (CRED) {   // next step of this unit, or the next tile
                 const uint32_t inner = sh[S_INNER];
                 if (inner == 0 || (rin + 1) * RP >= inner || (sh[S_FLAGS] & SF_CSTREAM)) { rin = 0; tile += t_step; } else { ++rin; }
+            } else if (longrow) {
+                if (++lr_c == nct) {
+                    lr_c = 0;
+                    if (++lr_phase > n_red) { lr_phase = 0; tile += t_step; }
+                }
             } else {
                 tile += t_step;
             }
@@ -1908,7 +1957,7 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
     // and LDS for the combination across waves: four floats per lane of every participating wave
     uint32_t lds_bytes = 0;
     bool cred = false, wide = true;     // wide: every segment spreads a row over whole waves
-    bool grid_sync = false, wg_sync = false;
+    bool grid_sync = false, wg_sync = false, longrow = false;
     uint8_t seg_of[DVM_MAX_TENSORS];    // the segment a tensor belongs to
     memset(seg_of, 0xFF, sizeof(seg_of));
     for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
@@ -1918,6 +1967,7 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
         wide &= (sh[S_GEOM] & 0xFFFF) >= 64;
         grid_sync |= (sh[S_FLAGS] & SF_SYNC_GRID) != 0;
         wg_sync |= (sh[S_FLAGS] & SF_SYNC_WG) != 0;
+        longrow |= (sh[S_FLAGS] & SF_LONGROW) != 0;
         if (sh[S_INNER] != 0 && rp > 1 && rp * 64u * 16u > lds_bytes) lds_bytes = rp * 64u * 16u;
         if (sh[S_FLAGS] & SF_LDS)           // the images the prologue copies into LDS
             for (uint32_t pc = SH_WORDS; pc < SH_WORDS + sh[S_PROLOGA]; pc += (sh[pc] >> 8) & 0xFF)
@@ -1946,6 +1996,8 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
     // when a segment relies on its producer's assignment of tiles to workgroups, nor when the segments own shares
     // of the workgroups.)
     ka.rotate = (w[PH_NSEG] > 1 || n_sets > 1) && !wg_sync && (w[PH_TYPE] & 0xFFFF) != KT_STACK_SPATIAL ? 1u : 0u;
+    if (cred && longrow)
+        return dvm_set_error(DVM_E_UNSUPPORTED, "dvm_run: a launch holds both a reduction along the penultimate axis and rows longer than a tile");
     vm_launch_t launch = nullptr;
     if (cred) {
         for (const VariantEntry &v : g_cred_variants)
