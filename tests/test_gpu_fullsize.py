@@ -113,3 +113,83 @@ def test_c5_layer_at_max_tokens():
     check_rows(desc, {"z": z.reshape(32 * T, L)[r2]}, {out_name: outs[out_name].reshape(32 * T, L)[r2]}, "c5 full softmax")
     del outs, d
     torch.cuda.empty_cache()
+
+
+# ---- every row of one instance per configuration in which a workgroup runs several tiles -------------------------
+# (the oracle goes over the instance in blocks of rows; the instance is sized so that this takes seconds)
+
+def check_every_row(desc, make_block_inputs, outs2d, n_rows, what, block=2048):
+    red = H.has_reduction(desc)
+    worst = 0.0
+    for lo in range(0, n_rows, block):
+        hi = min(n_rows, lo + block)
+        rounded, exact = H.run_oracle(desc, make_block_inputs(lo, hi))
+        for n, dt in desc.outputs:
+            worst = max(worst, H.compare(outs2d[n][lo:hi], rounded[n], exact[n], dt, red, f"{what} rows {lo}..{hi}:{n}"))
+    return worst
+
+
+def _tiles_per_workgroup(code):
+    inf = code.info()
+    return inf.n_tiles / max(1, inf.grid)
+
+
+def test_c2_every_row_of_a_multi_tile_instance():
+    B, S = 4, 2048
+    say(f"c2 rmsnorm, every row, B={B} S={S}")
+    d = gen.c2_inputs(B, S, gen.BASE_SEED + 2777, DEV)
+    desc = W.get_program("c2_rmsnorm")
+    outs, code = H.run_vm(desc, d)
+    assert _tiles_per_workgroup(code) >= 2
+    x = d["x"].reshape(B * S, 4096)
+    check_every_row(desc, lambda lo, hi: {"x": x[lo:hi], "w": d["w"]}, {"y": outs["y"].reshape(B * S, 4096)}, B * S, "c2 every row")
+
+
+def test_c4_every_row_of_a_multi_tile_instance():
+    T = 3100
+    say(f"c4 chain, every row, T={T}")
+    d = gen.c4_inputs(T, gen.BASE_SEED + 4777, DEV)
+    desc = W.get_program("c4_chain")
+    outs, code = H.run_vm(desc, d)
+    assert _tiles_per_workgroup(code) >= 2
+    check_every_row(desc, lambda lo, hi: {k: (v[lo:hi] if v.dim() == 2 else v) for k, v in d.items()}, {"y": outs["y"]}, T, "c4 every row",
+                    block=1024)
+
+
+def test_c3_every_row_of_a_multi_tile_instance():
+    S = 701                                     # (rows that are not whole lines: the blocked assignment with a pinned mask row)
+    say(f"c3 masked softmax, every row, B=2 S={S}")
+    d = gen.c3_inputs(2, S, gen.BASE_SEED + 3777, DEV)
+    desc = W.get_program("c3_masked_softmax")
+    outs, code = H.run_vm(desc, d)
+    assert _tiles_per_workgroup(code) >= 2
+    out_name = desc.outputs[0][0]
+    n_rows = 2 * 32 * S
+    z = d["z"].reshape(n_rows, S)
+    idx = torch.arange(n_rows, device=DEV) % S
+    check_every_row(desc, lambda lo, hi: {"z": z[lo:hi], "mask": d["mask"][idx[lo:hi]]}, {out_name: outs[out_name].reshape(n_rows, S)},
+                    n_rows, "c3 every row", block=8192)
+
+
+def test_c5_every_row_of_a_layer():
+    T = 1500
+    say(f"c5 programs, every row, T={T}")
+    d = gen.c5_inputs(T, gen.BASE_SEED + 5777, DEV)
+    for name, key in [("c5_rmsnorm", "c5_rmsnorm"), ("c5_residual", "c5_residual_a"), ("c5_silu_gate", "c5_silu_gate")]:
+        desc = W.get_program(name)
+        outs, _ = H.run_vm(desc, d[key])
+        check_every_row(desc, lambda lo, hi: {k: (v[lo:hi] if v.dim() == 2 else v) for k, v in d[key].items()},
+                        {n: outs[n] for n, _ in desc.outputs}, T, f"c5 every row {name}")
+    desc = W.get_program("c5_rope")
+    out = torch.full((T, 32, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    H.run_vm(desc, d["c5_rope"], {"y1": out[..., :64], "y2": out[..., 64:]})
+    check_every_row(desc, lambda lo, hi: {k: v[lo:hi] for k, v in d["c5_rope"].items()}, {"y1": out[..., :64], "y2": out[..., 64:]}, T,
+                    "c5 every row rope", block=512)
+    desc = W.get_program("c5_softmax")
+    z = d["c5_softmax"]["z"]
+    L = T // 8 + 1
+    outs, code = H.run_vm(desc, {"z": z})
+    assert _tiles_per_workgroup(code) >= 2
+    out_name = desc.outputs[0][0]
+    check_every_row(desc, lambda lo, hi: {"z": z.reshape(32 * T, L)[lo:hi]}, {out_name: outs[out_name].reshape(32 * T, L)}, 32 * T,
+                    "c5 every row softmax", block=16384)
