@@ -420,3 +420,16 @@ def test_split_reduction_along_the_penultimate_axis_needs_a_context_that_allows_
     assert B.dvm_encode(small, B.Program(desc), shape).raw == plain.raw
     # plenty of units already: no split either
     assert not B.dvm_encode(ws, B.Program(desc), [B.make_shape((1024, 64, 1024))]).needs_workspace()
+
+
+def test_output_layouts_that_repeat_or_overlap_elements_are_refused(ctx):
+    prog = B.Program(W.get_program("c5_residual"))
+    ins = [B.make_shape((16, 64)), B.make_shape((16, 64))]
+    for strides in [(0, 1), (64, 0), (32, 1), (1, 1)]:          # broadcast rows, broadcast columns, rows that overlap, both axes on one stride
+        with pytest.raises(B.DvmError) as e:
+            B.dvm_encode(ctx, prog, ins, [B.make_shape((16, 64), strides)])
+        assert e.value.status == -2, strides
+    B.dvm_encode(ctx, prog, ins, [B.make_shape((16, 64), (128, 1))]).validate()      # padded rows are fine
+    with pytest.raises(B.DvmError) as e:                                             # a transposed output: an error code of its own
+        B.dvm_encode(ctx, prog, ins, [B.make_shape((16, 64), (1, 16))])
+    assert e.value.status == -5
