@@ -150,7 +150,7 @@ class CpuBaseline:
                 "one_core_GBps": round(one_b / one_t / 1e9, 4),
                 "sample": "leading row blocks of one instance per config (" + ", ".join(
                     f"{l['config']}: {l['blocks']} blocks, {l['bytes'] / 1e6:.0f} MB, {l['wall_s']:.1f} s" for l in self.legs) +
-                    f"), one block per worker process on {self.cores} cores (count from sched_getaffinity, capped at 16), "
+                    f"), the blocks dealt out to {self.cores} worker processes, one per core (count from sched_getaffinity, capped at 16), "
                     "NumPy float64 per-op evaluation; one_core_GBps: one block alone on one core",
                 "per_config_GBps": {l["config"]: round(l["bytes"] / l["wall_s"] / 1e9, 4) for l in self.legs},
                 "max_err_over_tol_vs_gpu": round(max(l["worst"] for l in self.legs), 4)}
@@ -564,8 +564,61 @@ def copy_ceiling(lib, ctx, dev, B):
             "kernel": "dvm_copy_tiles (csrc/dvm_bench.hip): 16 B per lane and access, streaming hints; median of 10 launches"}
 
 
+def single_launch_extras(B, gen, W, dev):
+    """Single launches of the forms beyond the five configurations: a reduction along the penultimate axis split over a
+    workspace (a bias gradient) and rows longer than a tile (softmax and RMSNorm at 32768 and 100000 columns).  GB/s of
+    algorithmic bytes (one read of every input element, one write of every output element) over the median of 10 timed runs
+    (a split reduction is two kernel launches per run)."""
+    import torch
+    from workloads.programs import _p, single_op_program
+    stream = torch.cuda.current_stream()
+
+    def timed(ctx, desc, ins, n_bytes):
+        code = B.encode_for(ctx, B.Program(desc), ins)
+        outs = [torch.empty(s_, dtype=torch.bfloat16 if dt == "bf16" else torch.float32, device=dev) for s_, (_, dt) in zip(code.out_shapes, desc.outputs)]
+        ptrs = [t.data_ptr() for t in ins + outs]
+        if code.needs_workspace():
+            ws = torch.empty(code.tensor(code.info().n_tensors - 1)[0] // 4, dtype=torch.int32, device=dev)
+            ptrs.append(ws.data_ptr())
+        for _ in range(3):
+            B.dvm_run(ctx, code, ptrs, stream.cuda_stream)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(10)]
+        torch.cuda.synchronize()
+        for a, b in evs:
+            a.record(stream)
+            B.dvm_run(ctx, code, ptrs, stream.cuda_stream)
+            b.record(stream)
+        torch.cuda.synchronize()
+        ms = sorted(a.elapsed_time(b) for a, b in evs)[len(evs) // 2]
+        inf = code.info()
+        return {"GBps": round(n_bytes / ms / 1e6, 1), "us": round(ms * 1e3, 1), "kernel_launches": inf.n_launches, "segments": inf.n_segments}
+
+    out = {}
+    ctx = B.Context(0)
+    ctx.set_workspace_limit(4 << 20)
+    g = gen.randn((8192, 4096), gen.BASE_SEED + 9001, dev, "f32")
+    desc = _p("bias_gradient", [("g", "f32")], [("s", "csum", ["g"], {})], [("s", "f32")])
+    r = timed(ctx, desc, [g], g.numel() * 4 + 4096 * 4)
+    plain = timed(B.Context(0), desc, [g], g.numel() * 4 + 4096 * 4)
+    r["unsplit_GBps"] = plain["GBps"]
+    out["bias_gradient_f32_8192x4096"] = r
+    del g
+    ctx = B.Context(0)
+    for cols in (32768, 100000):
+        rows = (1 << 28) // (cols * 4)
+        z = gen.randn((rows, cols), gen.BASE_SEED + 9002, dev, "f32")
+        out[f"softmax_f32_{rows}x{cols}"] = timed(ctx, single_op_program("softmax", 1, "f32"), [z], 2 * z.numel() * 4)
+        del z
+        x = gen.randn((rows, cols), gen.BASE_SEED + 9003, dev, "bf16")
+        w = gen.randn((cols,), gen.BASE_SEED + 9004, dev, "bf16")
+        out[f"rmsnorm_bf16_{rows}x{cols}"] = timed(ctx, W.get_program("c2_rmsnorm"), [x, w], 2 * x.numel() * 2 + cols * 2)
+        del x, w
+    torch.cuda.empty_cache()
+    return out
+
+
 def baseline_blocks(stream, name, cores, gen):
-    """Row blocks (one per worker) of one instance of a stream for the CPU oracle, with the GPU's outputs for the same rows."""
+    """Row blocks (up to four per worker) of one instance of a stream for the CPU oracle, with the GPU's outputs for the same rows."""
     import torch
     parts = stream.parts
     blocks = []
@@ -575,7 +628,7 @@ def baseline_blocks(stream, name, cores, gen):
         x, w = parts[i]["ins"]
         y = parts[i]["outs"][0]
         x2, y2 = x.reshape(-1, x.shape[-1]), y.reshape(-1, y.shape[-1])
-        nb = min(cores, x2.shape[0] // rows_per)
+        nb = min(4 * cores, x2.shape[0] // rows_per)
         for b in range(nb):
             sl = slice(b * rows_per, (b + 1) * rows_per)
             blocks.append(({"x": x2[sl].cpu(), "w": w.cpu()}, {"y": y2[sl].cpu()}))
@@ -585,7 +638,7 @@ def baseline_blocks(stream, name, cores, gen):
         i = max(range(len(parts)), key=lambda k: parts[k]["ins"][0].shape[0])
         x, r, gamma, beta, bias, mask = parts[i]["ins"]
         y = parts[i]["outs"][0]
-        nb = min(cores, x.shape[0] // rows_per)
+        nb = min(4 * cores, x.shape[0] // rows_per)
         for b in range(nb):
             sl = slice(b * rows_per, (b + 1) * rows_per)
             blocks.append(({"x": x[sl].cpu(), "r": r[sl].cpu(), "gamma": gamma.cpu(), "beta": beta.cpu(), "bias": bias.cpu(),
@@ -598,7 +651,7 @@ def baseline_blocks(stream, name, cores, gen):
         p = parts[i]["outs"][0]
         S = z.shape[-1]
         z3, p3 = z.reshape(-1, S, S), p.reshape(-1, S, S)
-        nb = min(cores, z3.shape[0])
+        nb = min(4 * cores, z3.shape[0])
         mh = mask.cpu()
         for b in range(nb):
             blocks.append(({"z": z3[b].cpu(), "mask": mh}, {"p": p3[b].cpu()}))
@@ -671,15 +724,16 @@ def run(args, names, cpu) -> int:
         return bench_fuser(args, B, gen, W, ctx, dev)
 
     per = {}
+    cpu_legs = []
     for name in names:
         print(f"bench.py: {name}: generating inputs", file=sys.stderr, flush=True)
         s = Stream(name, args, B, gen, W, ctx, dev)
         print(f"bench.py: {name}: timing {args.steps} step(s)", file=sys.stderr, flush=True)
         r = s.run(lib, args.steps, args.warmup, unstacked=not args.skip_unstacked)
         if cpu.enabled and name in LARGE_CLASS:
-            dn, blocks, bpb, rtol = baseline_blocks(s, name, cpu.cores, gen)
-            print(f"bench.py: {name}: CPU oracle on {len(blocks)} row blocks", file=sys.stderr, flush=True)
-            cpu.leg(name, dn, blocks, bpb, rtol)
+            # (the sample is taken now; the oracle runs on it after all GPU timing, so that the device never idles
+            # between two timed workloads)
+            cpu_legs.append((name,) + tuple(baseline_blocks(s, name, cpu.cores, gen)))
         s.ctx_restore()
         per[name] = r
         del s
@@ -693,6 +747,10 @@ def run(args, names, cpu) -> int:
         del s
 
     ceiling = copy_ceiling(lib, ctx, dev, B)
+    extras = single_launch_extras(B, gen, W, dev) if args.workload == "suite" else None
+    for name, dn, blocks, bpb, rtol in cpu_legs:
+        print(f"bench.py: {name}: CPU oracle on {len(blocks)} row blocks", file=sys.stderr, flush=True)
+        cpu.leg(name, dn, blocks, bpb, rtol)
 
     if args.calibrate_copy:
         src = torch.empty(256 * 2**20, dtype=torch.uint8, device=dev).random_(0, 255)
@@ -759,6 +817,8 @@ def run(args, names, cpu) -> int:
         "copy_ceiling": ceiling,
         "per_config": per_config,
     }
+    if extras is not None:
+        result["single_launches"] = extras
     base = cpu.result()
     rc = 0
     if base is not None:
