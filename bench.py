@@ -352,7 +352,7 @@ class Stream:
             # config 5: 64 steps of a 32-layer stack, six programs per layer, T log-normal; one buffer set per
             # step shared by its 32 layers; every layer is one launch (its six programs stacked)
             if not args.limits:
-                ctx.set_limits(16, 6)   # parts that share a launch must fit one interpreter variant
+                ctx.set_limits(32, 2)   # parts that share a launch must fit one interpreter variant (this one measured fastest)
             steps_T = gen.c5_steps()[:n_inst]
             self.fixed_groups = []
             self.set_counts = []

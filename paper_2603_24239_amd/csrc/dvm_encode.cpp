@@ -1773,6 +1773,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     } else if (!column_mode) {
         const int ks[4] = {4, 8, 16, 32};
         int pick = -1;
+        uint32_t nv_cap = 0;        // chunks per lane the geometry may use (0: as many as the variant holds)
         // the largest K that still spreads a row over >= 16 lanes (K = 32: over >= 32 lanes, since that
         // variant keeps only two waves per SIMD resident); fewer lanes per row mean fewer interpreted
         // records per element, which measured faster than the higher occupancy of the smaller variants
@@ -1784,6 +1785,40 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             const int64_t gneed = cdiv(Cr, K / V);
             if (gneed > VARIANTS[v].max_threads) continue;
             if (pick < 0 || gneed >= (K == 32 ? 32 : 16)) pick = v;
+        }
+        // Short rows (a variant exists that holds a row in less than a wave).  What a wave spends on a tile is
+        // mostly fixed -- record decode, addresses, the steps of a reduction across lanes: measured at about four
+        // chunk slots' worth of instructions -- so fewer lanes per row and more chunks per lane mean less work per
+        // row, as long as the waves still fill the machine.  Every (variant, chunks per lane) pair is priced in the
+        // form of the cost model of Section 4.2, ceil(wave tiles / SIMDs) * (4 + chunks per lane), a wave tile
+        // being the part of a tile that one wave holds; the cheapest wins, the smaller variant on a tie.
+        if (pick >= 0 && ctx->dbg_k < (int)V) {
+            int kmax = 0;
+            for (int i = 0; i < 4; ++i)
+                if ((uint32_t)ks[i] >= V && find_variant(ks[i]) >= 0) kmax = ks[i];
+            if (kmax > 0 && cdiv(Cr, kmax / V) < 64) {
+                int64_t best = -1;
+                int prev_k = 0;
+                const int64_t n_simd = 4 * (int64_t)ctx->n_cu;
+                const int64_t nr = E.nrows > 0 ? E.nrows : 1;
+                for (int i = 0; i < 4; ++i) {
+                    const int K = ks[i];
+                    if ((uint32_t)K < V) continue;
+                    const int v = find_variant(K);
+                    if (v < 0) continue;
+                    for (int nv = prev_k / (int)V + 1; nv <= K / (int)V; ++nv) {     // (chunk counts a smaller variant holds were priced with it)
+                        const int64_t gneed = cdiv(Cr, nv);
+                        if (gneed > VARIANTS[v].max_threads) continue;
+                        const int64_t g = gneed <= 64 ? pow2ceil((uint32_t)gneed) : cdiv(gneed, 64) * 64;
+                        if (nv > 1 && g < 4) continue;                               // (keep a few lanes side by side on a row)
+                        const int64_t nvec_g = cdiv(Cr, g);
+                        const int64_t wt = g < 64 ? cdiv(nr, 64 / g) : nr * (g / 64);
+                        const int64_t cost = cdiv(wt, n_simd) * (4 + nvec_g + (g > 64 ? 3 : 0));   // (rows over several waves: a barrier per reduction)
+                        if (best < 0 || cost < best) { best = cost; pick = v; nv_cap = (uint32_t)nv; }
+                    }
+                    prev_k = K;
+                }
+            }
         }
         if (ctx->dbg_k >= (int)V) {
             const int v = find_variant(ctx->dbg_k);
@@ -1828,7 +1863,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         } else {
             vi = pick;
             const Variant &vr = VARIANTS[vi];
-            const int64_t gneed = cdiv(Cr, vr.K / V);
+            const int64_t gneed = cdiv(Cr, nv_cap != 0 ? nv_cap : vr.K / V);
             G = gneed <= 64 ? pow2ceil((uint32_t)gneed) : (uint32_t)(cdiv(gneed, 64) * 64);
             nvec = (uint32_t)cdiv(Cr, G);
             TC = G * nvec * V;

@@ -433,3 +433,26 @@ def test_output_layouts_that_repeat_or_overlap_elements_are_refused(ctx):
     with pytest.raises(B.DvmError) as e:                                             # a transposed output: an error code of its own
         B.dvm_encode(ctx, prog, ins, [B.make_shape((16, 64), (1, 16))])
     assert e.value.status == -5
+
+
+def test_short_rows_take_few_lanes_and_many_chunks_while_the_waves_fill_the_machine():
+    """A wave's cost per tile is mostly fixed, so rows shorter than a wave are planned with as few lanes per row (more
+    rows per wave) as the variants allow, priced as ceil(wave tiles / SIMDs) * (fixed + chunks per lane) in the manner
+    of the cost model of Section 4.2; with few rows the plan spreads out instead."""
+    free = B.Context(-1)
+    geo = lambda code: tuple(int(v) for v in re.search(r"lanes_per_row=(\d+) chunk=\d+ chunks_per_lane=(\d+) rows_per_tile=(\d+)", code.disasm()).groups())
+    soft = W.single_op_program("softmax", 1, "bf16")
+    enc = lambda c, rows, cols: B.dvm_encode(c, B.Program(soft), [B.make_shape((rows, cols))])
+    many = enc(free, 65536, 257)                # 33 chunks of 8: 16 lanes x 3 chunks, not 32 lanes x 2 with one lane busy in the second
+    assert many.info().variant_k == 32 and geo(many)[:2] == (16, 3)
+    assert geo(enc(free, 16384, 65))[:2] == (4, 3)
+    few = enc(free, 64, 257)                    # 64 rows: one wave tile per SIMD at most either way; the cheaper wave wins
+    assert few.info().variant_k <= 16 and geo(few)[0] >= 32
+    lim = B.Context(-1)
+    lim.set_limits(16, 2)
+    assert geo(enc(lim, 65536, 257))[:2] == (32, 2)     # what two chunks per lane allow
+    assert geo(enc(lim, 16384, 65))[:2] == (8, 2)
+    # long rows are not touched by this rule
+    assert geo(enc(free, 4096, 4096))[:2] == (128, 4)
+    for c in (many, few):
+        c.validate()
