@@ -1810,7 +1810,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                         const int64_t gneed = cdiv(Cr, nv);
                         if (gneed > VARIANTS[v].max_threads) continue;
                         const int64_t g = gneed <= 64 ? pow2ceil((uint32_t)gneed) : cdiv(gneed, 64) * 64;
-                        if (nv > 1 && g < 4) continue;                               // (keep a few lanes side by side on a row)
+                        if (nv > 1 && g < 2) continue;                               // (keep a few lanes side by side on a row)
                         const int64_t nvec_g = cdiv(Cr, g);
                         const int64_t wt = g < 64 ? cdiv(nr, 64 / g) : nr * (g / 64);
                         const int64_t cost = cdiv(wt, n_simd) * (4 + nvec_g + (g > 64 ? 3 : 0));   // (rows over several waves: a barrier per reduction)
