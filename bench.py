@@ -353,6 +353,7 @@ class Stream:
             # step shared by its 32 layers; every layer is one launch (its six programs stacked)
             if not args.limits:
                 ctx.set_limits(32, 2)   # parts that share a launch must fit one interpreter variant (this one measured fastest)
+            ctx.set_copies_in_flight(max(1, min(32, args.layers_per_launch)))      # (the planner prices a layer's tiles that many times)
             steps_T = gen.c5_steps()[:n_inst]
             self.fixed_groups = []
             self.set_counts = []

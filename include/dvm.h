@@ -138,6 +138,12 @@ int  dvm_ctx_set_plan_override(dvm_ctx *ctx, int elems_per_lane, int rows_per_ti
  * DVM_STATIC_WORKSPACE_BYTES).  The result does not depend on the number of compute units running: S and the order
  * are fixed by the shapes.  Such bytecode cannot be a part of dvm_stack / dvm_stack_dependent or run batched. */
 int  dvm_ctx_set_workspace_limit(dvm_ctx *ctx, int64_t bytes);
+/* Tell the planner that `copies` copies of every program encoded with this context share a launch: the tensor sets
+ * of a dvm_run_batched call, or like parts of a stack (Section 5.1).  In the cost model of Section 4.2,
+ * ceil(#tiles / N) * (tile length + overhead), #tiles then counts `copies` times, so the planner stops cutting a
+ * small program into many small tiles just to give every workgroup one: the other copies fill the machine.
+ * Default 1; 1 .. 4096.  The bytecode runs correctly whatever the launch turns out to hold. */
+int  dvm_ctx_set_copies_in_flight(dvm_ctx *ctx, int copies);
 /* Row-invariant operands that a program only multiplies by or adds (a weight vector, a bias) may be kept in
  * the workgroup's LDS instead of pinned tile registers when that lets the program run in an interpreter variant
  * with fewer tile registers, i.e. more resident waves (default: enabled).  0 disables it (tests, comparison). */

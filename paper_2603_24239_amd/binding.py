@@ -80,6 +80,7 @@ def load() -> C.CDLL:
         "dvm_ctx_set_assignment": (i, [vp, i]),
         "dvm_ctx_set_lds_operands": (i, [vp, i]),
         "dvm_ctx_set_workspace_limit": (i, [vp, C.c_int64]),
+        "dvm_ctx_set_copies_in_flight": (i, [vp, i]),
         "dvm_prog_create": (i, [P(vp)]),
         "dvm_prog_input": (i, [vp, i, P(i)]),
         "dvm_prog_op": (i, [vp, i, P(i), i, P(C.c_double), i, P(i)]),
@@ -126,7 +127,7 @@ def load() -> C.CDLL:
 
 
 EXPORTED = ["dvm_shape_contiguous", "dvm_ctx_create", "dvm_ctx_destroy", "dvm_ctx_set_planner", "dvm_ctx_set_limits",
-            "dvm_ctx_set_plan_override", "dvm_ctx_set_assignment", "dvm_ctx_set_lds_operands", "dvm_ctx_set_workspace_limit", "dvm_prog_create",
+            "dvm_ctx_set_plan_override", "dvm_ctx_set_assignment", "dvm_ctx_set_lds_operands", "dvm_ctx_set_workspace_limit", "dvm_ctx_set_copies_in_flight", "dvm_prog_create",
             "dvm_prog_input", "dvm_prog_op", "dvm_prog_output", "dvm_prog_finish", "dvm_prog_num_inputs",
             "dvm_prog_num_outputs", "dvm_prog_destroy", "dvm_encode", "dvm_stack", "dvm_stack_spatial", "dvm_stack_dependent",
             "dvm_ctx_set_sync_limit", "dvm_workspace_status", "dvm_validate", "dvm_disasm",
@@ -189,6 +190,9 @@ class Context:
 
     def set_sync_limit(self, polls: int) -> None:
         _check(load().dvm_ctx_set_sync_limit(self._h, polls), "dvm_ctx_set_sync_limit")
+
+    def set_copies_in_flight(self, copies: int) -> None:
+        _check(load().dvm_ctx_set_copies_in_flight(self._h, copies), "dvm_ctx_set_copies_in_flight")
 
     def set_workspace_limit(self, nbytes: int) -> None:
         _check(load().dvm_ctx_set_workspace_limit(self._h, nbytes), "dvm_ctx_set_workspace_limit")

@@ -96,6 +96,7 @@ struct dvm_ctx {
     int lds_operands;   // row-invariant operands may live in LDS instead of pinned tile registers
     int lds_budget;     // bytes of LDS images per workgroup
     int64_t workspace_limit;    // bytes of workspace dvm_encode may plan for (0: programs never need one)
+    int copies;                 // copies of every program that share a launch (tensor sets of a batched run): tiles count that many times in the cost model
     int64_t sync_limit;     // polls a workgroup spends at a grid-wide synchronisation point before it gives up
 };
 
@@ -114,6 +115,7 @@ extern "C" int dvm_ctx_create(int hip_device, dvm_ctx **out) {
     c->assignment = DVM_ASSIGN_AUTO;
     c->lds_operands = 1;
     c->workspace_limit = 0;
+    c->copies = 1;
     c->lds_budget = 40 * 1024 - 640;    // four workgroups per compute unit keep their images in its 160 KiB
     c->sync_limit = 1 << 20;
     if (hip_device >= 0) {
@@ -170,6 +172,11 @@ extern "C" int dvm_ctx_set_sync_limit(dvm_ctx *c, int64_t polls) {
 }
 extern "C" int64_t dvm_ctx_sync_limit(const dvm_ctx *c) { return c ? c->sync_limit : 0; }
 
+extern "C" int dvm_ctx_set_copies_in_flight(dvm_ctx *c, int copies) {
+    if (!c || copies < 1 || copies > 4096) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_copies_in_flight: null context, or copies not in 1 .. 4096");
+    c->copies = copies;
+    return DVM_OK;
+}
 extern "C" int dvm_ctx_set_workspace_limit(dvm_ctx *c, int64_t bytes) {
     if (!c || bytes < 0) return dvm_set_error(DVM_E_ARGS, "dvm_ctx_set_workspace_limit: null context or negative size");
     c->workspace_limit = bytes;
@@ -1718,6 +1725,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         return s < 1 ? 1 : s;
     };
     const int64_t ovh = ctx->overhead;
+    const int64_t copies = ctx->copies;
     bool column_mode = !E.has_red && E.D0 > 4096;
     bool has_rows_output = false;
     for (int t = prog->n_in; t < E.n_acc; ++t) has_rows_output |= E.acc[t].rows;
@@ -1740,7 +1748,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             int64_t rp_max = VARIANTS[v].max_threads / 64 < 16 ? VARIANTS[v].max_threads / 64 : 16;
             if (rp_max > E.Dg[1]) rp_max = E.Dg[1];
             const int64_t waves = cred_outer * cdiv(E.D0 > 0 ? E.D0 : 1, 64 * K) * rp_max;
-            if (pick < 0 || waves >= (int64_t)ctx->n_cu * slots_per_cu(VARIANTS[v], 64)) pick = v;
+            if (pick < 0 || waves * copies >= (int64_t)ctx->n_cu * slots_per_cu(VARIANTS[v], 64)) pick = v;
         }
         if (pick < 0) return dvm_set_error(DVM_E_UNSUPPORTED, "no interpreter variant with enough tile registers");
         vi = pick;
@@ -1750,7 +1758,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             int64_t rp_max = vr.max_threads / 64 < 16 ? vr.max_threads / 64 : 16;
             if (rp_max > E.Dg[1]) rp_max = E.Dg[1];
             const int64_t units = cred_outer * cdiv(E.D0 > 0 ? E.D0 : 1, 64 * vr.K);
-            const int64_t want = cdiv((int64_t)ctx->n_cu * slots_per_cu(vr, 64), units > 0 ? units : 1);
+            const int64_t want = cdiv((int64_t)ctx->n_cu * slots_per_cu(vr, 64), (units > 0 ? units : 1) * copies);
             RP = (uint32_t)(want < 1 ? 1 : (want > rp_max ? rp_max : want));
             if (ctx->dbg_rp > 0 && ctx->dbg_rp <= rp_max) RP = (uint32_t)ctx->dbg_rp;
         }
@@ -1813,7 +1821,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                         if (nv > 1 && g < 2) continue;                               // (keep a few lanes side by side on a row)
                         const int64_t nvec_g = cdiv(Cr, g);
                         const int64_t wt = g < 64 ? cdiv(nr, 64 / g) : nr * (g / 64);
-                        const int64_t cost = cdiv(wt, n_simd) * (4 + nvec_g + (g > 64 ? 3 : 0));   // (rows over several waves: a barrier per reduction)
+                        const int64_t cost = cdiv(wt * copies, n_simd) * (4 + nvec_g + (g > 64 ? 3 : 0));   // (rows over several waves: a barrier per reduction)
                         if (best < 0 || cost < best) { best = cost; pick = v; nv_cap = (uint32_t)nv; }
                     }
                     prev_k = K;
@@ -1875,7 +1883,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             // (with plenty of rows a workgroup of four waves is the smallest candidate: tiles of 8 KiB and more per
             // tensor measured 3-4 % faster than the same rows dealt out two waves at a time)
             uint32_t rp_first = step;
-            if (rp_max > step && E.nrows >= (int64_t)8 * ctx->n_cu * rp_max) rp_first = rp_max;
+            if (rp_max > step && E.nrows * copies >= (int64_t)8 * ctx->n_cu * rp_max) rp_first = rp_max;
             int64_t best_cost = -1;
             RP = rp_first;
             for (uint32_t rp = rp_first; rp <= (rp_max > step ? rp_max : step); rp += step) {
@@ -1883,7 +1891,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
                 if (threads > (uint32_t)vr.max_threads) break;
                 const int64_t N = (int64_t)ctx->n_cu * slots_per_cu(vr, threads);
                 const int64_t tiles = cdiv(E.nrows > 0 ? E.nrows : 1, rp);
-                const int64_t cost = cdiv(tiles, N) * ((int64_t)rp * (E.D0 > 0 ? E.D0 : 1) + ovh);
+                const int64_t cost = cdiv(tiles * copies, N) * ((int64_t)rp * (E.D0 > 0 ? E.D0 : 1) + ovh);
                 if (best_cost < 0 || cost <= best_cost) { best_cost = cost; RP = rp; }
             }
             if (ctx->dbg_rp > 0 && (uint32_t)ctx->dbg_rp % step == 0 && (uint32_t)ctx->dbg_rp * G <= (uint32_t)vr.max_threads)
@@ -1914,12 +1922,12 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (tc < tc_min) tc = tc_min;
             if (tc > t_max) return;
             const int64_t kk = cdiv(E.D0, tc);
-            const int64_t cost = cdiv(E.nrows * kk, N) * (tc + ovh);
+            const int64_t cost = cdiv(E.nrows * kk * copies, N) * (tc + ovh);
             if (best_cost < 0 || cost < best_cost || (cost == best_cost && kk < best_nct)) { best_cost = cost; best_nct = kk; }
         };
         consider(nct_min);
-        const int64_t w0 = cdiv(E.nrows * nct_min, N);
-        for (int64_t w = w0; w < w0 + 8; ++w) consider((w * N) / E.nrows);
+        const int64_t w0 = cdiv(E.nrows * nct_min * copies, N);
+        for (int64_t w = w0; w < w0 + 8; ++w) consider((w * N) / (E.nrows * copies));
         int64_t tc = cdiv(cdiv(E.D0, best_nct), V) * V;
         if (tc < (int64_t)G * V) tc = (int64_t)G * V;
         TC = (uint32_t)tc;

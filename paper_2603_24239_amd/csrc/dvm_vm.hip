@@ -2027,6 +2027,29 @@ int run_impl(const dvm_ctx *ctx, const void *bytecode, size_t len, void *const *
         if ((uint64_t)grid > (uint64_t)per_cu * (uint64_t)n_cu) grid = (uint32_t)per_cu * (uint32_t)n_cu;
         hipLaunchKernelGGL(dvm_ws_clear, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (uint32_t *)(uintptr_t)ka.ws);
     }
+    // A launch whose segments (and sets) deal their tiles out in rotation keeps as many workgroups busy as it has
+    // tiles in all: the grid grows from what the largest segment alone asked for to that, up to what the device holds
+    // at once (short segments of many sets then run side by side instead of one after the other on a few workgroups).
+    if (ka.rotate != 0 && !grid_sync) {
+        uint64_t total = 0;
+        for (uint32_t s = 0, at = segs_off; s < w[PH_NSEG]; ++s) {
+            total += w[at + S_NTILES];
+            at += w[at + S_WORDS];
+        }
+        total *= (uint64_t)n_sets;
+        if (total > grid) {
+            int per_cu = 0, n_cu = 0;
+            e = (hipError_t)resident_per_cu(launch, block, lds_bytes, &per_cu);
+            if (e != hipSuccess) {
+                t_last_hip_error = (int)e;
+                return dvm_set_error(DVM_E_HIP, hipGetErrorString(e));
+            }
+            dvm_ctx_planner_get(ctx, &n_cu, nullptr);
+            const uint64_t cap = (uint64_t)(per_cu > 0 ? per_cu : 1) * (uint64_t)(n_cu > 0 ? n_cu : 1);
+            const uint64_t want = total < cap ? total : cap;
+            if (want > grid) grid = (uint32_t)want;
+        }
+    }
     // one kernel launch per run of segments up to the next one that asks for a launch of its own
     for (uint32_t first = 0; first < w[PH_NSEG];) {
         uint32_t end = first + 1;

@@ -456,3 +456,24 @@ def test_short_rows_take_few_lanes_and_many_chunks_while_the_waves_fill_the_mach
     assert geo(enc(free, 4096, 4096))[:2] == (128, 4)
     for c in (many, few):
         c.validate()
+
+
+def test_copies_in_flight_make_the_planner_keep_tiles_large():
+    """With the launch shared by many copies of a program (tensor sets of a batched run), the cost model of Section 4.2
+    counts the program's tiles that many times: a small element-wise program is no longer cut into one small tile per
+    workgroup."""
+    alone = B.Context(-1)
+    shared = B.Context(-1)
+    shared.set_copies_in_flight(32)
+    add = W.single_op_program("add", 2, "bf16")
+    shapes = [B.make_shape((512, 4096)), B.make_shape((512, 4096))]
+    a = B.dvm_encode(alone, B.Program(add), shapes)
+    b = B.dvm_encode(shared, B.Program(add), shapes)
+    assert a.info().n_tiles >= 4 * b.info().n_tiles and b.info().n_tiles * 8192 >= 512 * 4096
+    b.validate()
+    soft = W.single_op_program("softmax", 1, "bf16")
+    few = [B.make_shape((2048, 65))]
+    assert B.dvm_encode(shared, B.Program(soft), few).info().n_tiles < B.dvm_encode(alone, B.Program(soft), few).info().n_tiles
+    for bad in (0, -1, 5000):
+        with pytest.raises(B.DvmError):
+            shared.set_copies_in_flight(bad)

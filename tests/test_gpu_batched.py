@@ -61,11 +61,12 @@ def test_one_program_over_several_sets(name, make):
         H.compare(got, rounded[n], exact[n], dt, H.has_reduction(desc), f"batched {name} set 3: {n}")
 
 
-def test_a_stack_of_programs_over_several_sets():
-    say("batched: the six programs of a layer, stacked, over 4 sets (T=45)")
+@pytest.mark.parametrize("limits,copies,T", [((16, 6), 1, 45), ((32, 2), 32, 45), ((32, 2), 32, 300), ((16, 4), 8, 131)])
+def test_a_stack_of_programs_over_several_sets(limits, copies, T):
+    say(f"batched: the six programs of a layer, stacked, over 4 sets (T={T}, variant limits {limits}, planned for {copies} copies in flight)")
     ctx = B.Context(torch.cuda.current_device())
-    ctx.set_limits(16, 6)
-    T = 45
+    ctx.set_limits(*limits)
+    ctx.set_copies_in_flight(copies)
     stream = torch.cuda.current_stream().cuda_stream
     names = ["c5_rmsnorm", "c5_rope", "c5_softmax", "c5_residual", "c5_silu_gate", "c5_residual"]
     keys = ["c5_rmsnorm", "c5_rope", "c5_softmax", "c5_residual_a", "c5_silu_gate", "c5_residual_b"]
@@ -86,7 +87,7 @@ def test_a_stack_of_programs_over_several_sets():
             codes.append(code)
             tensors += ins + o
             outs.append(o if nm != "c5_rope" else [rope_out])
-        return codes, tensors, outs
+        return codes, tensors, outs, d
 
     layers_b = [layer(7300 + k) for k in range(4)]
     layers_1 = [layer(7300 + k) for k in range(4)]
@@ -102,6 +103,14 @@ def test_a_stack_of_programs_over_several_sets():
             for a, b in zip(ob, o1):
                 assert torch.equal(_bits(a), _bits(b)), f"set {k}: a stacked part differs from the launch of its own"
     assert float(layers_b[2][2][0][0].float().abs().max()) > 0      # (the outputs were written at all)
+    # one set against the oracle, program by program
+    d = layers_b[1][3]
+    for nm, key, o in zip(names, keys, layers_b[1][2]):
+        desc = W.get_program(nm)
+        rounded, exact = H.run_oracle(desc, d[key])
+        got = {"y1": o[0][..., :64], "y2": o[0][..., 64:]} if nm == "c5_rope" else {n: t for (n, _), t in zip(desc.outputs, o)}
+        for n, dt in desc.outputs:
+            H.compare(got[n], rounded[n], exact[n], dt, H.has_reduction(desc), f"batched layer, {nm}: {n}")
 
 
 def test_argument_errors():
