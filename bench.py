@@ -353,7 +353,6 @@ class Stream:
             # step shared by its 32 layers; every layer is one launch (its six programs stacked)
             if not args.limits:
                 ctx.set_limits(32, 2)   # parts that share a launch must fit one interpreter variant (this one measured fastest)
-            ctx.set_copies_in_flight(max(1, min(32, args.layers_per_launch)))      # (the planner prices a layer's tiles that many times)
             steps_T = gen.c5_steps()[:n_inst]
             self.fixed_groups = []
             self.set_counts = []
@@ -406,8 +405,14 @@ class Stream:
         self.wl["instances_per_launch"] = self.group
         self.stacking = args.stacking or "temporal"
         self.wl["stacking"] = self.stacking if self.group > 1 else "none"
+        # the planner is told how many copies of a program share a launch (it prices the tiles that many times)
+        # (sets of a batched launch; stacking 8 large instances of config 2 or 4 measured the same with and without)
+        self.copies = args.copies_hint if args.copies_hint > 0 else (max(self.set_counts) if self.set_counts else 1)
+        ctx.set_copies_in_flight(self.copies)
+        self.wl["planned_for_copies_in_flight"] = self.copies
 
     def ctx_restore(self):
+        self.ctx.set_copies_in_flight(1)
         if self.name == "c5_layers" and not self.args.limits:
             self.ctx.set_limits(32, 6)
 
@@ -508,8 +513,10 @@ class Stream:
         # the same stream with every program as its own launch (no stacking): per-program launch times
         if unstacked:
             if self.group > 1:
+                ctx.set_copies_in_flight(1)
                 singles = marshal(self.singles_idx)
                 elapsed1, events1 = timed(singles, steps, 1)
+                ctx.set_copies_in_flight(self.copies)
             else:
                 elapsed1, events1 = elapsed, all_events
             one_ms = [float(np.mean([events1[s][k][0].elapsed_time(events1[s][k][1]) for s in range(steps)]))
@@ -678,6 +685,8 @@ def main() -> int:
     ap.add_argument("--assignment", default="", choices=["", "blocked", "interleaved"],
                     help="how tiles are dealt out to workgroups: Algorithm 2's blocked ranges or round-robin (the library's default)")
     ap.add_argument("--limits", default="", help="K,NR: bound the interpreter variant the planner may choose (dvm_ctx_set_limits), for tuning")
+    ap.add_argument("--copies-hint", type=int, default=0,
+                    help="dvm_ctx_set_copies_in_flight for the stream's programs (0 = the tensor sets of a batched launch, else 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-unstacked", action="store_true",
                     help="leave out the second pass that launches every program on its own (profiler runs use this so "
