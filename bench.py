@@ -572,6 +572,38 @@ def copy_ceiling(lib, ctx, dev, B):
             "kernel": "dvm_copy_tiles (csrc/dvm_bench.hip): 16 B per lane and access, streaming hints; median of 10 launches"}
 
 
+def condition_memory(torch, dev, gib, chunk_mib):
+    """Bring the device's free memory into the state it has in a process that has been allocating and freeing for a while:
+    allocate `gib` GiB in blocks of `chunk_mib` MiB and hand them back to the driver in a scrambled order, so that the
+    tensors allocated afterwards lie on physical pages scattered over the memory instead of on one pristine contiguous
+    stretch.  On this machine the same launches (the library's copy kernel included) run 4-10 % faster over such pages
+    than in the first process on a freshly booted box, and later processes on a box see them anyway; doing it here
+    makes the figures independent of what ran on the box before.  Nothing of it is timed."""
+    import random
+    import time
+    if gib <= 0:
+        return {"conditioned": False}
+    t0 = time.perf_counter()
+    chunk = int(chunk_mib * 2**20)
+    blocks = []
+    try:
+        for _ in range(int(gib * 2**30 // chunk)):
+            blocks.append(torch.empty(chunk, dtype=torch.uint8, device=dev))
+    except RuntimeError:            # (less free memory than asked for: scramble what there is)
+        pass
+    got = len(blocks)
+    torch.cuda.synchronize()
+    random.Random(1).shuffle(blocks)
+    while blocks:
+        blocks.pop()
+        if len(blocks) % 1024 == 0:
+            torch.cuda.empty_cache()
+    torch.cuda.empty_cache()
+    return {"conditioned": True, "GiB": round(got * chunk / 2**30, 1), "block_MiB": chunk_mib, "seconds": round(time.perf_counter() - t0, 1),
+            "note": "device memory allocated in blocks and freed in a scrambled order before the inputs are allocated (untimed): "
+                    "physical pages as in a long-running process; --shuffle-memory-gib 0 gives the pristine-box figures"}
+
+
 def single_launch_extras(B, gen, W, dev):
     """Single launches of the forms beyond the five configurations: a reduction along the penultimate axis split over a
     workspace (a bias gradient) and rows longer than a tile (softmax and RMSNorm at 32768 and 100000 columns).  GB/s of
@@ -687,6 +719,9 @@ def main() -> int:
     ap.add_argument("--limits", default="", help="K,NR: bound the interpreter variant the planner may choose (dvm_ctx_set_limits), for tuning")
     ap.add_argument("--copies-hint", type=int, default=0,
                     help="dvm_ctx_set_copies_in_flight for the stream's programs (0 = the tensor sets of a batched launch, else 1)")
+    ap.add_argument("--shuffle-memory-gib", type=float, default=240.0,
+                    help="before the inputs are allocated, allocate this much device memory in blocks and free them in a scrambled order (0: off)")
+    ap.add_argument("--shuffle-chunk-mib", type=float, default=2.0, help="block size of that step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--skip-unstacked", action="store_true",
                     help="leave out the second pass that launches every program on its own (profiler runs use this so "
@@ -730,6 +765,7 @@ def run(args, names, cpu) -> int:
     if args.limits:
         k_, nr_ = (int(v) for v in args.limits.split(","))
         ctx.set_limits(k_, nr_)
+    placement = condition_memory(torch, dev, args.shuffle_memory_gib, args.shuffle_chunk_mib)
     if args.workload == "if_else_add":
         return bench_fuser(args, B, gen, W, ctx, dev)
 
@@ -825,6 +861,7 @@ def run(args, names, cpu) -> int:
                      "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of `bench.py --workload <config>`, summaries under profiles/"
                                        if traffic is not None else None},
         "copy_ceiling": ceiling,
+        "memory_placement": placement,
         "per_config": per_config,
     }
     if extras is not None:
