@@ -351,8 +351,16 @@ class Stream:
         elif name == "c5_layers":
             # config 5: 64 steps of a 32-layer stack, six programs per layer, T log-normal; one buffer set per
             # step shared by its 32 layers; every layer is one launch (its six programs stacked)
+            # parts that share a launch must fit one interpreter variant: five of the six programs need one tile register
+            # at most and run in the 64-element variant; RoPE needs two and is a launch of its own (32 elements)
+            ctx_rope = ctx
             if not args.limits:
-                ctx.set_limits(32, 2)   # parts that share a launch must fit one interpreter variant (this one measured fastest)
+                ctx.set_limits(64, 1)
+                ctx_rope = B.Context(0)
+                ctx_rope.set_limits(32, 2)
+                if args.assignment:
+                    ctx_rope.set_assignment(args.assignment)
+                self.extra_ctx = [ctx_rope]
             steps_T = gen.c5_steps()[:n_inst]
             self.fixed_groups = []
             self.set_counts = []
@@ -371,13 +379,19 @@ class Stream:
                 # (layers_per_launch of the 32 layers share a launch: dvm_run_batched runs the layer's bytecode once
                 # per layer, the encode of the six programs serves all of them -- the layers have the same shapes)
                 lpl = max(1, min(32, args.layers_per_launch))
-                self.fixed_groups += [list(range(first, first + 6))] * (32 // lpl)
-                self.set_counts += [lpl] * (32 // lpl)
-                if 32 % lpl:
-                    self.fixed_groups += [list(range(first, first + 6))]
-                    self.set_counts += [32 % lpl]
+                if ctx_rope is not ctx:
+                    self.parts[first + 1]["ctx"] = ctx_rope
+                    launches = [[first, first + 2, first + 3, first + 4, first + 5], [first + 1]]
+                else:
+                    launches = [list(range(first, first + 6))]
+                for g_ in launches:
+                    self.fixed_groups += [g_] * (32 // lpl)
+                    self.set_counts += [lpl] * (32 // lpl)
+                    if 32 % lpl:
+                        self.fixed_groups += [g_]
+                        self.set_counts += [32 % lpl]
             self.wl = {"workload": "config 5: 64 steps x 32 layers x {rmsnorm, rope, softmax, residual, silu-gate, residual} bf16, "
-                                   "T log-normal (median 512, 1..8192); the six programs of a layer stacked, %d layer(s) per launch, "
+                                   "T log-normal (median 512, 1..8192); five programs of a layer stacked and RoPE beside them, %d layer(s) per launch, "
                                    "every step's wall time includes its encodes" % max(1, min(32, args.layers_per_launch)),
                        "launches_per_32_layer_step": len(self.fixed_groups) // max(1, len(steps_T)),
                        "steps_of_the_stream": len(steps_T)}
@@ -408,7 +422,8 @@ class Stream:
         # the planner is told how many copies of a program share a launch (it prices the tiles that many times)
         # (sets of a batched launch; stacking 8 large instances of config 2 or 4 measured the same with and without)
         self.copies = args.copies_hint if args.copies_hint > 0 else (max(self.set_counts) if self.set_counts else 1)
-        ctx.set_copies_in_flight(self.copies)
+        for c_ in [ctx] + getattr(self, "extra_ctx", []):
+            c_.set_copies_in_flight(self.copies)
         self.wl["planned_for_copies_in_flight"] = self.copies
 
     def ctx_restore(self):
@@ -452,7 +467,7 @@ class Stream:
             for k, (idx, ptrs, n_t, n_sets) in enumerate(groups):
                 for j, i in enumerate(idx):
                     pt = parts[i]
-                    st = lib.dvm_encode_timed(ctx._h, pt["prog"]._h, pt["shapes"], len(pt["ins"]), pt["layout"], part_bufs[j], enc_cap,
+                    st = lib.dvm_encode_timed(pt.get("ctx", ctx)._h, pt["prog"]._h, pt["shapes"], len(pt["ins"]), pt["layout"], part_bufs[j], enc_cap,
                                               C.byref(ln), 1, ns)
                     if st != 0:
                         raise B.DvmError(st, "dvm_encode")
@@ -513,10 +528,12 @@ class Stream:
         # the same stream with every program as its own launch (no stacking): per-program launch times
         if unstacked:
             if self.group > 1:
-                ctx.set_copies_in_flight(1)
+                for c_ in [ctx] + getattr(self, "extra_ctx", []):
+                    c_.set_copies_in_flight(1)
                 singles = marshal(self.singles_idx)
                 elapsed1, events1 = timed(singles, steps, 1)
-                ctx.set_copies_in_flight(self.copies)
+                for c_ in [ctx] + getattr(self, "extra_ctx", []):
+                    c_.set_copies_in_flight(self.copies)
             else:
                 elapsed1, events1 = elapsed, all_events
             one_ms = [float(np.mean([events1[s][k][0].elapsed_time(events1[s][k][1]) for s in range(steps)]))

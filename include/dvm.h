@@ -114,14 +114,17 @@ void dvm_ctx_destroy(dvm_ctx *ctx);
  * of the cost model, in elements.  Values <= 0 leave the setting unchanged. */
 int  dvm_ctx_set_planner(dvm_ctx *ctx, int n_compute_units, int tile_overhead_elems);
 /* Bound the interpreter variant dvm_encode may plan for: at most `max_elems_per_lane` elements of a
- * tile per lane (4, 8, 16 or 32) and at most `max_tile_regs` tile registers (2, 4 or 6).  Parts that
+ * tile per lane (4, 8, 16, 32 or 64) and at most `max_tile_regs` tile registers (1, 2, 4 or 6).  Parts that
  * are to share one launch (dvm_stack; Section 5, stacking) must all fit one variant, so a caller that
  * stacks encodes every part under common limits, e.g. (16, 4).  Values <= 0 leave a limit unchanged;
- * a program that needs more tile registers than allowed makes dvm_encode return DVM_E_UNSUPPORTED. */
+ * a program that needs more tile registers than allowed makes dvm_encode return DVM_E_UNSUPPORTED.  The default
+ * bounds are 32 elements and 6 registers; the variant with 64 elements exists with one tile register only (programs
+ * over bf16 tensors that need no more: 128 bytes per lane and tensor in flight, as 32 fp32 elements are) and is
+ * planned for only when the bound is raised to 64. */
 int  dvm_ctx_set_limits(dvm_ctx *ctx, int max_elems_per_lane, int max_tile_regs);
 
 /* Force parts of the tile plan instead of letting the cost model choose (tests and tuning walk plans the
- * model would not pick): `elems_per_lane` (4, 8, 16 or 32) selects the interpreter variant's tile register
+ * model would not pick): `elems_per_lane` (4, 8, 16, 32 or 64) selects the interpreter variant's tile register
  * size where the row length allows it, `rows_per_tile` the rows of a tile (for a reduction along the
  * penultimate axis: the waves that share one unit of work), `grid_multiplier` launches that many workgroups
  * per resident slot.  0 leaves a choice to the planner.  The bytecode depends on these settings and on the

@@ -200,6 +200,7 @@ constexpr Variant VARIANTS[] = {
     { 8, 2, 1024, 7, true}, { 8, 6,  512, 4, true},
     {16, 2, 1024, 6, false}, {16, 4,  512, 4, false}, {16, 6,  512, 3, true},
     {32, 2,  256, 4, true}, {32, 4,  256, 2, true},
+    {64, 1,  256, 3, false},
 };
 constexpr int N_VARIANTS = sizeof(VARIANTS) / sizeof(VARIANTS[0]);
 

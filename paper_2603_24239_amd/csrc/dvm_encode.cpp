@@ -143,11 +143,11 @@ extern "C" void dvm_ctx_planner_get(const dvm_ctx *c, int *n_cu, int *overhead) 
 extern "C" int dvm_ctx_set_limits(dvm_ctx *c, int max_k, int max_nr) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
     if (max_k > 0) {
-        if (max_k != 4 && max_k != 8 && max_k != 16 && max_k != 32) return dvm_set_error(DVM_E_ARGS, "elements per lane must be 4, 8, 16 or 32");
+        if (max_k != 4 && max_k != 8 && max_k != 16 && max_k != 32 && max_k != 64) return dvm_set_error(DVM_E_ARGS, "elements per lane must be 4, 8, 16, 32 or 64");
         c->max_k = max_k;
     }
     if (max_nr > 0) {
-        if (max_nr != 2 && max_nr != 4 && max_nr != 6) return dvm_set_error(DVM_E_ARGS, "tile registers must be 2, 4 or 6");
+        if (max_nr != 1 && max_nr != 2 && max_nr != 4 && max_nr != 6) return dvm_set_error(DVM_E_ARGS, "tile registers must be 1, 2, 4 or 6");
         c->max_nr = max_nr;
     }
     return DVM_OK;
@@ -155,8 +155,8 @@ extern "C" int dvm_ctx_set_limits(dvm_ctx *c, int max_k, int max_nr) {
 
 extern "C" int dvm_ctx_set_plan_override(dvm_ctx *c, int elems_per_lane, int rows_per_tile, int grid_multiplier) {
     if (!c) return dvm_set_error(DVM_E_ARGS, "null context");
-    if (elems_per_lane != 0 && elems_per_lane != 4 && elems_per_lane != 8 && elems_per_lane != 16 && elems_per_lane != 32)
-        return dvm_set_error(DVM_E_ARGS, "elements per lane must be 0, 4, 8, 16 or 32");
+    if (elems_per_lane != 0 && elems_per_lane != 4 && elems_per_lane != 8 && elems_per_lane != 16 && elems_per_lane != 32 && elems_per_lane != 64)
+        return dvm_set_error(DVM_E_ARGS, "elements per lane must be 0, 4, 8, 16, 32 or 64");
     if (rows_per_tile < 0 || rows_per_tile > 1024) return dvm_set_error(DVM_E_ARGS, "rows per tile must be 0 .. 1024");
     if (grid_multiplier < 0 || grid_multiplier > 64) return dvm_set_error(DVM_E_ARGS, "grid multiplier must be 0 .. 64");
     c->dbg_k = elems_per_lane;
@@ -1737,9 +1737,9 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         // still leaves enough units to fill the machine.
         if (has_rows_output) return dvm_set_error(DVM_E_UNSUPPORTED, "a row-value output beside a reduction along the penultimate axis");
         column_mode = false;
-        const int ks[4] = {4, 8, 16, 32};
+        const int ks[5] = {4, 8, 16, 32, 64};
         int pick = -1;
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 5; ++i) {
             const int K = ks[i];
             if ((uint32_t)K < V) continue;
             const int v = find_variant(K);
@@ -1779,20 +1779,20 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (E.nr_used > VARIANTS[vi].NR) return dvm_set_error(DVM_E_UNSUPPORTED, "internal: register count changed between linearisations");
         }
     } else if (!column_mode) {
-        const int ks[4] = {4, 8, 16, 32};
+        const int ks[5] = {4, 8, 16, 32, 64};
         int pick = -1;
         uint32_t nv_cap = 0;        // chunks per lane the geometry may use (0: as many as the variant holds)
         // the largest K that still spreads a row over >= 16 lanes (K = 32: over >= 32 lanes, since that
         // variant keeps only two waves per SIMD resident); fewer lanes per row mean fewer interpreted
         // records per element, which measured faster than the higher occupancy of the smaller variants
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 5; ++i) {
             const int K = ks[i];
             if ((uint32_t)K < V) continue;
             const int v = find_variant(K);
             if (v < 0) continue;
             const int64_t gneed = cdiv(Cr, K / V);
             if (gneed > VARIANTS[v].max_threads) continue;
-            if (pick < 0 || gneed >= (K == 32 ? 32 : 16)) pick = v;
+            if (pick < 0 || gneed >= (K >= 32 ? 32 : 16)) pick = v;
         }
         // Short rows (a variant exists that holds a row in less than a wave).  What a wave spends on a tile is
         // mostly fixed -- record decode, addresses, the steps of a reduction across lanes: measured at about four
@@ -1802,14 +1802,14 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         // being the part of a tile that one wave holds; the cheapest wins, the smaller variant on a tie.
         if (pick >= 0 && ctx->dbg_k < (int)V) {
             int kmax = 0;
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 5; ++i)
                 if ((uint32_t)ks[i] >= V && find_variant(ks[i]) >= 0) kmax = ks[i];
             if (kmax > 0 && cdiv(Cr, kmax / V) < 64) {
                 int64_t best = -1;
                 int prev_k = 0;
                 const int64_t n_simd = 4 * (int64_t)ctx->n_cu;
                 const int64_t nr = E.nrows > 0 ? E.nrows : 1;
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < 5; ++i) {
                     const int K = ks[i];
                     if ((uint32_t)K < V) continue;
                     const int v = find_variant(K);
@@ -1833,7 +1833,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (v >= 0 && cdiv(Cr, ctx->dbg_k / V) <= VARIANTS[v].max_threads) pick = v;
         }
         if (pick < 0) {                         // long rows: more elements per lane
-            for (int i = 0; i < 4 && pick < 0; ++i) {
+            for (int i = 0; i < 5 && pick < 0; ++i) {
                 const int K = ks[i];
                 if ((uint32_t)K < V) continue;
                 const int v = find_variant(K);
@@ -1852,7 +1852,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (E.err) { E.err = nullptr; E.reload_inputs = true; linearize(0); }
             if (E.err) return dvm_set_error(E.err_code, E.err);
             int v = -1;
-            for (int i = 3; i >= 0 && v < 0; --i) {             // the widest tile register first
+            for (int i = 4; i >= 0 && v < 0; --i) {             // the widest tile register first
                 if ((uint32_t)ks[i] < V || ks[i] > ctx->max_k) continue;
                 for (int j = 0; j < N_VARIANTS; ++j)
                     if (VARIANTS[j].K == ks[i] && VARIANTS[j].NR >= E.nr_used && VARIANTS[j].NR <= ctx->max_nr && (v < 0 || VARIANTS[j].NR < VARIANTS[v].NR)) v = j;
@@ -1901,6 +1901,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (column_mode) {
         // (the widest tile register first: 128 bytes per lane and tensor in flight measured 2-9 % above 64)
         int v = ctx->dbg_k >= (int)V ? find_variant(ctx->dbg_k) : -1;
+        if (v < 0) v = find_variant(64);
         if (v < 0) v = find_variant(32);
         if (v < 0) v = find_variant(16);
         if (v < 0) v = find_variant(8);

@@ -1697,7 +1697,7 @@ __global__ void __launch_bounds__(MAXT) __attribute__((amdgpu_waves_per_eu(WAVES
 // host side.  The build script reads this list.
 #define DVM_VARIANT_LIST(X) \
     X(4, 2, 1024, 8) X(4, 6, 1024, 8) X(8, 2, 1024, 7) X(8, 6, 512, 4) \
-    X(16, 2, 1024, 6) X(16, 4, 512, 4) X(16, 6, 512, 3) X(32, 2, 256, 4) X(32, 4, 256, 2)
+    X(16, 2, 1024, 6) X(16, 4, 512, 4) X(16, 6, 512, 3) X(32, 2, 256, 4) X(32, 4, 256, 2) X(64, 1, 256, 3)
 
 // (the variants also built as the instantiation that runs reductions along the penultimate axis)
 #define DVM_CRED_VARIANT_LIST(X) \

@@ -241,7 +241,7 @@ def test_limits_bound_the_variant_and_trade_registers_for_reloads():
     loads = lambda code: len(re.findall(r"^\s+\d+ (?:view)?load ", code.disasm(), flags=re.M))
     assert loads(b) > loads(a)
     b.validate()
-    for bad in [(5, 0), (0, 3), (64, 0)]:
+    for bad in [(5, 0), (0, 3), (128, 0)]:
         with pytest.raises(B.DvmError):
             lim.set_limits(*bad)
     two = B.Context(-1)
