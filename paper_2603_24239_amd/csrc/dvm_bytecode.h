@@ -39,7 +39,7 @@ enum : int {
     PH_NSEG,        // number of segments (meta-kernels)
     PH_BLOCK,       // threads per workgroup of the launch
     PH_GRID,        // workgroups of the launch: the N of Algorithm 2
-    PH_VARIANT,     // interpreter variant: K | NR << 8
+    PH_VARIANT,     // interpreter variant: K | NR << 8; bits 16-23: tile registers the program uses + 1 (0: not noted)
     PH_NTENS,       // tensors of the launch
     PH_WORDS_COUNT
 };

@@ -1704,6 +1704,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     uint32_t G = 1, RP = 1, nvec = 1, nct = 1, TC = 0;
     auto find_variant = [&](int K) {
         int best = -1;
+        if (K > 32 && V != 8) return best;      // (64 elements per lane: 128 bytes of bf16 per lane and tensor, what 32 fp32 elements are)
         for (int i = 0; i < N_VARIANTS; ++i)
             if ((VARIANTS[i].cred || !E.has_cred) && VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && VARIANTS[i].NR <= ctx->max_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
         return best;
@@ -1853,7 +1854,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (E.err) return dvm_set_error(E.err_code, E.err);
             int v = -1;
             for (int i = 4; i >= 0 && v < 0; --i) {             // the widest tile register first
-                if ((uint32_t)ks[i] < V || ks[i] > ctx->max_k) continue;
+                if ((uint32_t)ks[i] < V || ks[i] > ctx->max_k || (ks[i] > 32 && V != 8)) continue;
                 for (int j = 0; j < N_VARIANTS; ++j)
                     if (VARIANTS[j].K == ks[i] && VARIANTS[j].NR >= E.nr_used && VARIANTS[j].NR <= ctx->max_nr && (v < 0 || VARIANTS[j].NR < VARIANTS[v].NR)) v = j;
             }
@@ -1971,7 +1972,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     w[PH_NSEG] = 1;
     w[PH_BLOCK] = threads;
     w[PH_GRID] = grid;
-    w[PH_VARIANT] = (uint32_t)vr.K | ((uint32_t)vr.NR << 8);
+    w[PH_VARIANT] = (uint32_t)vr.K | ((uint32_t)vr.NR << 8) | ((uint32_t)(E.nr_used + 1) << 16);
     w[PH_NTENS] = (uint32_t)E.n_acc;
     for (int t = 0; t < E.n_acc; ++t) {
         uint32_t *tt = w + PH_WORDS_N + t * TT_WORDS;
@@ -2492,7 +2493,11 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, const
         nseg += w[PH_NSEG];
         if (w[PH_BLOCK] > block) block = w[PH_BLOCK];
         if ((w[PH_VARIANT] & 0xFF) > K) K = w[PH_VARIANT] & 0xFF;
-        if (((w[PH_VARIANT] >> 8) & 0xFF) > NR) NR = (w[PH_VARIANT] >> 8) & 0xFF;
+        {   // tile registers the part uses (recorded beside its variant; bytecode without the note: its variant's)
+            const uint32_t noted = (w[PH_VARIANT] >> 16) & 0xFF;
+            const uint32_t need = noted != 0 ? noted - 1 : (w[PH_VARIANT] >> 8) & 0xFF;
+            if (need > NR) NR = need;
+        }
         for (uint32_t s = 0, at = off; s < w[PH_NSEG]; ++s) {      // (a part that reduces along the penultimate axis)
             need_cred |= w[at + S_INNER] != 0;
             need_cstream |= (w[at + S_FLAGS] & SF_CSTREAM) != 0;
@@ -2541,7 +2546,7 @@ static int stack_impl(const void *const *codes, const size_t *lens, int n, const
     w[PH_NSEG] = nseg;
     w[PH_BLOCK] = block;
     w[PH_GRID] = (uint32_t)grid;
-    w[PH_VARIANT] = (uint32_t)vr->K | ((uint32_t)vr->NR << 8);
+    w[PH_VARIANT] = (uint32_t)vr->K | ((uint32_t)vr->NR << 8) | ((NR + 1) << 16);
     w[PH_NTENS] = ntens;
     uint32_t *tt = w + PH_WORDS_N;
     uint32_t *sg = w + PH_WORDS_N + ntens * TT_WORDS;
