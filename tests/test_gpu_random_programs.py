@@ -53,3 +53,13 @@ def test_random_programs_under_stacking_limits():
     ctx.set_limits(16, 4)
     ran = sum(_run(seed, ctx) for seed in range(200, 240))
     assert ran >= 28
+
+
+def test_random_programs_planned_for_wide_tiles_and_a_shared_launch():
+    """The same differential test under the planner settings of a batched run: 64 elements per lane allowed, the cost
+    model told that 32 copies of every program share the launch."""
+    ctx = B.Context(torch.cuda.current_device())
+    ctx.set_limits(64, 6)
+    ctx.set_copies_in_flight(32)
+    ran = sum(_run(seed, ctx) for seed in range(300, 340))
+    assert ran >= 28
