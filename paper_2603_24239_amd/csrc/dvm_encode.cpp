@@ -1704,7 +1704,6 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     uint32_t G = 1, RP = 1, nvec = 1, nct = 1, TC = 0;
     auto find_variant = [&](int K) {
         int best = -1;
-        if (K > 32 && V != 8) return best;      // (64 elements per lane: 128 bytes of bf16 per lane and tensor, what 32 fp32 elements are)
         for (int i = 0; i < N_VARIANTS; ++i)
             if ((VARIANTS[i].cred || !E.has_cred) && VARIANTS[i].K == K && K <= ctx->max_k && VARIANTS[i].NR >= need_nr && VARIANTS[i].NR <= ctx->max_nr && (best < 0 || VARIANTS[i].NR < VARIANTS[best].NR)) best = i;
         return best;
@@ -1854,7 +1853,7 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
             if (E.err) return dvm_set_error(E.err_code, E.err);
             int v = -1;
             for (int i = 4; i >= 0 && v < 0; --i) {             // the widest tile register first
-                if ((uint32_t)ks[i] < V || ks[i] > ctx->max_k || (ks[i] > 32 && V != 8)) continue;
+                if ((uint32_t)ks[i] < V || ks[i] > ctx->max_k) continue;
                 for (int j = 0; j < N_VARIANTS; ++j)
                     if (VARIANTS[j].K == ks[i] && VARIANTS[j].NR >= E.nr_used && VARIANTS[j].NR <= ctx->max_nr && (v < 0 || VARIANTS[j].NR < VARIANTS[v].NR)) v = j;
             }
@@ -1902,8 +1901,8 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
     if (column_mode) {
         // (the widest tile register first: 128 bytes per lane and tensor in flight measured 2-9 % above 64)
         int v = ctx->dbg_k >= (int)V ? find_variant(ctx->dbg_k) : -1;
+        if (v < 0) v = find_variant(32);        // (64 elements at three waves per SIMD measured 18 % slower than 32 at four on a flat bf16 add)
         if (v < 0) v = find_variant(64);
-        if (v < 0) v = find_variant(32);
         if (v < 0) v = find_variant(16);
         if (v < 0) v = find_variant(8);
         if (v < 0) v = find_variant(4);

@@ -1,6 +1,6 @@
 """The interpreter variant with 64 elements per lane and one tile register, on the GPU against the oracle.  A context whose
-limits allow 64 elements plans programs over bf16 tensors that need at most one tile register beside the accumulator
-for it; programs over fp32 tensors and programs that need more registers keep the 32-element variants."""
+limits allow 64 elements plans programs with rows long enough that need at most one tile register beside the accumulator
+for it; programs that need more registers and flat element-wise programs keep the 32-element variants."""
 from __future__ import annotations
 
 import pytest
@@ -34,14 +34,12 @@ def ctx():
 def test_softmax_rows(ctx, dt, rows, cols):
     say(f"64 elements per lane: softmax {dt} [{rows},{cols}]")
     _, code, _ = H.check_program(single_op_program("softmax", 1, dt), {"a0": gen.randn((rows, cols), 11, DEV, dt)}, ctx=ctx)
-    if dt == "f32":
-        assert code.info().variant_k <= 32
-    elif cols >= 4095 and rows >= 33:
+    if cols >= 4095 and rows >= 33:
         assert (code.info().variant_k, code.info().variant_nr) == (64, 1)
 
 
 def test_config_programs(ctx):
-    for name, d, k in [("c2_rmsnorm", gen.c2_inputs(3, 700, 5, DEV), 64), ("c3_masked_softmax", gen.c3_inputs(1, 1000, 6, DEV), 32),
+    for name, d, k in [("c2_rmsnorm", gen.c2_inputs(3, 700, 5, DEV), 64), ("c3_masked_softmax", gen.c3_inputs(1, 2300, 6, DEV), 64),
                        ("c4_chain", gen.c4_inputs(333, 7, DEV), 32)]:
         say(f"64 elements per lane allowed: {name}")
         _, code, _ = H.check_program(W.get_program(name), d, ctx=ctx)
