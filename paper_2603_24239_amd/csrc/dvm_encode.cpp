@@ -1637,7 +1637,13 @@ extern "C" int dvm_encode(const dvm_ctx *ctx, const dvm_prog *prog, const dvm_sh
         auto cls = [](int n) { return n <= 2 ? 2 : (n <= 4 ? 4 : (n <= 6 ? 6 : 8)); };
         const bool row_mode_ok = E.nrows > 1 && !(!E.has_red && E.D0 > 4096) && !E.has_cred && E.D0 > 0;
         const int before = E.err ? 99 : E.nr_used;
-        if (row_mode_ok && ctx->lds_operands && (before > 2 || E.reload_inputs)) {
+        bool any_invariant = false;     // (without a row-invariant input tensor there is nothing to keep in LDS: skip the attempt)
+        for (int n = 0; n < NN && !any_invariant; ++n) {
+            if (prog->nodes[n].kind != N_IN || E.acc[prog->nodes[n].input].rows) continue;
+            const Access &A = E.acc[prog->nodes[n].input];
+            any_invariant = A.s[1] == 0 && A.s[2] == 0 && A.s[3] == 0;
+        }
+        if (row_mode_ok && ctx->lds_operands && any_invariant && (before > 2 || E.reload_inputs)) {
             const bool was_reload = E.reload_inputs;
             E.err = nullptr;
             E.reload_inputs = false;
