@@ -119,8 +119,8 @@ int  dvm_ctx_set_planner(dvm_ctx *ctx, int n_compute_units, int tile_overhead_el
  * stacks encodes every part under common limits, e.g. (16, 4).  Values <= 0 leave a limit unchanged;
  * a program that needs more tile registers than allowed makes dvm_encode return DVM_E_UNSUPPORTED.  The default
  * bounds are 32 elements and 6 registers; the variant with 64 elements exists with one tile register only (programs
- * over bf16 tensors that need no more: 128 bytes per lane and tensor in flight, as 32 fp32 elements are) and is
- * planned for only when the bound is raised to 64. */
+ * with long rows that need no more: a row of up to 4096 elements is then held by one wave; flat element-wise
+ * programs keep 32 elements) and is planned for only when the bound is raised to 64. */
 int  dvm_ctx_set_limits(dvm_ctx *ctx, int max_elems_per_lane, int max_tile_regs);
 
 /* Force parts of the tile plan instead of letting the cost model choose (tests and tuning walk plans the
